@@ -1,0 +1,6 @@
+"""fp64 CPU oracle for Eigen Attention's low-rank inference path.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this
+directory; it is used by tests/, by __graft_entry__.smoke() and by the
+cpu_baseline leg of bench.py.  It shares no code with the HIP path.
+"""

@@ -1,0 +1,301 @@
+"""Pins for the fp64 oracle: each test checks it against something the paper or
+the mathematics fixes, never against itself.  CPU only."""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import eigen_attention as ora
+from paper_2408_05646_amd import synth
+
+GOLDEN = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
+
+
+def make_layer(seed, d, H, Hkv, d_h, r_k, r_v, n):
+    g = synth.rng(900, seed)
+    Wq = synth.gaussian(g, (d, H * d_h), d ** -0.5)
+    Wk = synth.gaussian(g, (d, Hkv * d_h), d ** -0.5)
+    Wv = synth.gaussian(g, (d, Hkv * d_h), d ** -0.5)
+    Wo = synth.gaussian(g, (H * d_h, d), d ** -0.5)
+    Uk = np.stack([synth.orthonormal_basis(g, d_h, r_k) for _ in range(Hkv)])
+    Uv = np.stack([synth.orthonormal_basis(g, d_h, r_v) for _ in range(Hkv)])
+    x = synth.gaussian(g, (n, d))
+    return Wq, Wk, Wv, Wo, Uk, Uv, x
+
+
+def lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, Hkv, d_h):
+    """Feed x[:-1] through prefill-style appends, then one decode step on x[-1]."""
+    folded = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    cache = ora.RankCache.empty(1, Hkv, Uk.shape[2], Uv.shape[2])
+    if x.shape[0] > 1:
+        _, k, v = ora.project_qkv(x[:-1], *folded[:3])
+        cache.append(0, k, v)
+    return ora.decode_step(x[-1:], folded, cache, d_h)
+
+
+# ---- P1: r = d_h reproduces standard attention exactly (Sec. 4.2: U^T U = I, so U U^T = I at full rank)
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (4, 1)])
+def test_full_rank_equals_standard_attention_decode(H, Hkv):
+    d, d_h, n = 32, 8, 13
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(1, d, H, Hkv, d_h, d_h, d_h, n)
+    y_low = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, Hkv, d_h)
+    y_std = ora.standard_attention_block(x, Wq, Wk, Wv, Wo, H, Hkv)
+    assert ora.rel_l2(y_low, y_std) < 1e-12
+
+
+def test_full_rank_equals_standard_attention_prefill():
+    d, H, Hkv, d_h, n = 32, 4, 2, 8, 11
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(2, d, H, Hkv, d_h, d_h, d_h, n)
+    folded = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    cache = ora.RankCache.empty(1, Hkv, d_h, d_h)
+    y_low = ora.prefill_step(x[None], folded, cache, d_h)[0]
+    y_std = ora.standard_attention_block(x, Wq, Wk, Wv, Wo, H, Hkv, causal_all=True)
+    assert ora.rel_l2(y_low, y_std) < 1e-12
+
+
+def test_wrong_scale_would_break_full_rank_pin():
+    """The pin is sensitive to the softmax divisor: sqrt(r) in place of sqrt(d_h) at r < d_h
+    changes the result, while at r = d_h they coincide -- so P1+P2 together fix it."""
+    d, H, d_h, r, n = 32, 4, 8, 4, 9
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(3, d, H, H, d_h, r, r, n)
+    good = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, H, d_h)
+    bad = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, H, r)       # divisor sqrt(r)
+    ref = ora.eigen_attention_block_projected_back(x, Wq, Wk, Wv, Wo, Uk, Uv, H, H)
+    assert ora.rel_l2(good, ref) < 1e-12
+    assert ora.rel_l2(bad, ref) > 1e-3
+
+
+# ---- P2: rank-space form == project-back form (Eq. 6-7 vs Eq. 8), r < d_h, r_k != r_v, GQA
+@pytest.mark.parametrize("H,Hkv,r_k,r_v", [(4, 4, 3, 5), (4, 2, 5, 2), (6, 2, 4, 4)])
+def test_rank_space_equals_projected_back_form(H, Hkv, r_k, r_v):
+    d_h, n = 8, 12
+    d = H * d_h
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(4, d, H, Hkv, d_h, r_k, r_v, n)
+    y_low = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, Hkv, d_h)
+    y_ref = ora.eigen_attention_block_projected_back(x, Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    assert ora.rel_l2(y_low, y_ref) < 1e-12
+    # prefill, every row
+    folded = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    cache = ora.RankCache.empty(1, Hkv, r_k, r_v)
+    y_pre = ora.prefill_step(x[None], folded, cache, d_h)[0]
+    y_ref_all = ora.eigen_attention_block_projected_back(x, Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv, causal_all=True)
+    assert ora.rel_l2(y_pre, y_ref_all) < 1e-12
+    # and the decode result is the last prefill row
+    assert ora.rel_l2(y_low[0], y_pre[-1]) < 1e-12
+
+
+# ---- P3: softmax rows are probabilities
+def test_softmax_rows_sum_to_one():
+    g = synth.rng(901)
+    B, H, r, n = 2, 3, 6, 500
+    cache = ora.RankCache.from_arrays([synth.gaussian(g, (H, n, r), 3.0) for _ in range(B)],
+                                      [synth.gaussian(g, (H, n, r)) for _ in range(B)])
+    _, probs = ora.decode_attention(synth.gaussian(g, (B, H, r), 3.0), cache, 16, return_probs=True)
+    for p in probs:
+        assert np.all(p >= 0)
+        assert abs(p.sum() - 1.0) < 1e-15 * n
+    big = ora.softmax(np.array([1e4, 1e4 - 1.0, -1e4]))       # no overflow at large scores
+    assert np.isfinite(big).all() and abs(big.sum() - 1) < 1e-15
+
+
+# ---- P4: brute force with plain Python floats (no numpy in the arithmetic)
+def brute_decode(q, K, V, d_h):
+    n, r_k, r_v = len(K), len(q), len(V[0])
+    s = [sum(q[c] * K[t][c] for c in range(r_k)) / math.sqrt(d_h) for t in range(n)]
+    e = [math.exp(v) for v in s]                                # naive softmax, scores are small
+    z = sum(e)
+    return [sum(e[t] / z * V[t][c] for t in range(n)) for c in range(r_v)]
+
+
+def test_brute_force_decode_and_prefill_tiny():
+    g = synth.rng(902)
+    B, H, Hkv, r_k, r_v, n, d_h = 2, 4, 2, 3, 5, 7, 8
+    Ks = [synth.gaussian(g, (Hkv, n + b, r_k)) for b in range(B)]
+    Vs = [synth.gaussian(g, (Hkv, n + b, r_v)) for b in range(B)]
+    q = synth.gaussian(g, (B, H, r_k))
+    o = ora.decode_attention(q, ora.RankCache.from_arrays(Ks, Vs), d_h)
+    for b, i in itertools.product(range(B), range(H)):
+        gk = i // (H // Hkv)
+        ref = brute_decode(q[b, i].tolist(), Ks[b][gk].tolist(), Vs[b][gk].tolist(), d_h)
+        assert np.allclose(o[b, i], ref, rtol=1e-12, atol=1e-14)
+    # prefill: query j (of the last m positions) sees tokens 0..(len-m+j)
+    m = 4
+    qp = synth.gaussian(g, (B, m, H, r_k))
+    op = ora.prefill_attention(qp, ora.RankCache.from_arrays(Ks, Vs), d_h)
+    for b, j, i in itertools.product(range(B), range(m), range(H)):
+        gk = i // (H // Hkv)
+        upto = Ks[b].shape[1] - m + j + 1
+        ref = brute_decode(qp[b, j, i].tolist(), Ks[b][gk][:upto].tolist(), Vs[b][gk][:upto].tolist(), d_h)
+        assert np.allclose(op[b, j, i], ref, rtol=1e-12, atol=1e-14)
+
+
+def test_brute_force_projection_and_out_proj():
+    g = synth.rng(903)
+    M, d, H, Hkv, r_k, r_v = 3, 6, 4, 2, 2, 3
+    x = synth.gaussian(g, (M, d))
+    Wq_f, Wk_f, Wv_f = (synth.gaussian(g, s) for s in ((H, d, r_k), (Hkv, d, r_k), (Hkv, d, r_v)))
+    Wo_f = synth.gaussian(g, (H, r_v, d))
+    q, k, v = ora.project_qkv(x, Wq_f, Wk_f, Wv_f)
+    for m, i, c in itertools.product(range(M), range(H), range(r_k)):
+        assert abs(q[m, i, c] - sum(x[m, a] * Wq_f[i, a, c] for a in range(d))) < 1e-13
+    for m, i, c in itertools.product(range(M), range(Hkv), range(r_v)):
+        assert abs(v[m, i, c] - sum(x[m, a] * Wv_f[i, a, c] for a in range(d))) < 1e-13
+    for m, i, c in itertools.product(range(M), range(Hkv), range(r_k)):
+        assert abs(k[m, i, c] - sum(x[m, a] * Wk_f[i, a, c] for a in range(d))) < 1e-13
+    o = synth.gaussian(g, (M, H, r_v))
+    y = ora.out_proj(o, Wo_f)
+    for m, a in itertools.product(range(M), range(d)):
+        ref = sum(o[m, i, c] * Wo_f[i, c, a] for i in range(H) for c in range(r_v))
+        assert abs(y[m, a] - ref) < 1e-13
+
+
+def test_fold_weights_elementwise():
+    """Eq. (8) entry by entry, incl. which KV head's basis a query head uses and
+    that W^O' = U^V^T W^O uses rows i*d_h..(i+1)*d_h of W^O."""
+    d, H, Hkv, d_h, r_k, r_v = 12, 4, 2, 3, 2, 2
+    Wq, Wk, Wv, Wo, Uk, Uv, _ = make_layer(5, d, H, Hkv, d_h, r_k, r_v, 1)
+    Wq_f, Wk_f, Wv_f, Wo_f = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    for i in range(H):
+        gk = i // (H // Hkv)
+        for a, c in itertools.product(range(d), range(r_k)):
+            assert abs(Wq_f[i, a, c] - sum(Wq[a, i * d_h + j] * Uk[gk, j, c] for j in range(d_h))) < 1e-14
+        for c, a in itertools.product(range(r_v), range(d)):
+            assert abs(Wo_f[i, c, a] - sum(Uv[gk, j, c] * Wo[i * d_h + j, a] for j in range(d_h))) < 1e-14
+    for gk in range(Hkv):
+        for a, c in itertools.product(range(d), range(r_k)):
+            assert abs(Wk_f[gk, a, c] - sum(Wk[a, gk * d_h + j] * Uk[gk, j, c] for j in range(d_h))) < 1e-14
+        for a, c in itertools.product(range(d), range(r_v)):
+            assert abs(Wv_f[gk, a, c] - sum(Wv[a, gk * d_h + j] * Uv[gk, j, c] for j in range(d_h))) < 1e-14
+
+
+# ---- P5: special cases with textbook answers
+def test_special_cases():
+    g = synth.rng(904)
+    H, r_k, r_v, d_h = 2, 4, 3, 16
+    # n = 1: output is the single value row
+    K1, V1 = synth.gaussian(g, (H, 1, r_k)), synth.gaussian(g, (H, 1, r_v))
+    q = synth.gaussian(g, (1, H, r_k))
+    o = ora.decode_attention(q, ora.RankCache.from_arrays([K1], [V1]), d_h)
+    assert np.allclose(o[0], V1[:, 0, :], rtol=0, atol=1e-15)
+    # q = 0 -> uniform weights -> mean of the values
+    n = 37
+    K, V = synth.gaussian(g, (H, n, r_k)), synth.gaussian(g, (H, n, r_v))
+    o = ora.decode_attention(np.zeros((1, H, r_k)), ora.RankCache.from_arrays([K], [V]), d_h)
+    assert np.allclose(o[0], V.mean(axis=1), rtol=1e-13)
+    # all keys identical -> mean of the values
+    Ksame = np.repeat(synth.gaussian(g, (H, 1, r_k)), n, axis=1)
+    o = ora.decode_attention(q, ora.RankCache.from_arrays([Ksame], [V]), d_h)
+    assert np.allclose(o[0], V.mean(axis=1), rtol=1e-13)
+    # one key scoring 60 above the rest -> that value row (others weigh < e^-60 each)
+    qd = np.zeros((1, H, r_k)); qd[0, :, 0] = 1.0
+    Kd = np.zeros((H, n, r_k)); Kd[:, 5, 0] = 60.0 * math.sqrt(d_h)
+    o = ora.decode_attention(qd, ora.RankCache.from_arrays([Kd], [V]), d_h)
+    assert np.allclose(o[0], V[:, 5, :], rtol=0, atol=1e-20 + 1e-24 * n)
+    # permuting the cached tokens leaves the output unchanged
+    perm = g.permutation(n)
+    o_a = ora.decode_attention(q, ora.RankCache.from_arrays([K], [V]), d_h)
+    o_b = ora.decode_attention(q, ora.RankCache.from_arrays([K[:, perm]], [V[:, perm]]), d_h)
+    assert np.allclose(o_a, o_b, rtol=1e-13)
+    # shifting every score by a constant (a key direction q is blind to) changes nothing;
+    # first prefill row equals the first value row
+    qp = synth.gaussian(g, (1, n, H, r_k))
+    op = ora.prefill_attention(qp, ora.RankCache.from_arrays([K], [V]), d_h)
+    assert np.allclose(op[0, 0], V[:, 0, :], atol=1e-15)
+    with pytest.raises(ValueError):
+        ora.decode_attention(q, ora.RankCache.empty(1, H, r_k, r_v), d_h)
+
+
+# ---- P6: the block output does not depend on the basis chosen inside the subspace
+def test_basis_rotation_invariance():
+    d, H, Hkv, d_h, r_k, r_v, n = 32, 4, 2, 8, 5, 3, 10
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(6, d, H, Hkv, d_h, r_k, r_v, n)
+    g = synth.rng(905)
+    Ok = np.stack([synth.orthonormal_basis(g, r_k, r_k) for _ in range(Hkv)])
+    Ov = np.stack([synth.orthonormal_basis(g, r_v, r_v) for _ in range(Hkv)])
+    y_a = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk, Uv, x, H, Hkv, d_h)
+    y_b = lowrank_decode_last(Wq, Wk, Wv, Wo, Uk @ Ok, Uv @ Ov, x, H, Hkv, d_h)
+    assert ora.rel_l2(y_a, y_b) < 1e-12
+
+
+# ---- P7: Table 1 closed forms against what the oracle actually holds and multiplies
+@pytest.mark.parametrize("r_head", [4, 8])      # 8 = d_h: the "standard attention" column
+def test_table1_counts(r_head):
+    d, H, d_h, n = 32, 4, 8, 21
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(7, d, H, H, d_h, r_head, r_head, n)
+    folded = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, H)
+    cache = ora.RankCache.empty(1, H, r_head, r_head)
+    _, k, v = ora.project_qkv(x[:-1], *folded[:3])
+    cache.append(0, k, v)
+    ctr = ora.OpCounter()
+    ora.decode_step(x[-1:], folded, cache, d_h, ctr)
+    r = H * r_head                                  # Table 1's r: total compressed width
+    assert cache.elements() == 2 * n * r            # KV cache size 2.n.r   (2.n.d at r_head = d_h)
+    assert sum(w.size for w in folded) == 4 * d * r  # parameters 4.d.r
+    assert ctr.macs == 4 * d * r + 2 * n * r        # generation FLOPs 4.d.r + 2.n.r
+    if r_head == d_h:
+        assert (cache.elements(), ctr.macs) == (2 * n * d, 4 * d * d + 2 * n * d)
+
+
+# ---- P8: the Introduction's worked example
+def test_intro_memory_example():
+    ex = GOLDEN["intro_memory_example"]
+    d_h = 128
+    full = ora.kv_cache_bytes(ex["batch"], ex["context_tokens"], ex["d_model"] // d_h, d_h, d_h,
+                              ex["n_layers"], ex["bytes_per_element"])
+    assert full == 274_877_906_944 == ex["kv_cache_GB"] * 2 ** 30
+    low = ora.kv_cache_bytes(16, 32768, 32, 80, 80, 32, 2)
+    assert low == 171_798_691_840 and low * 128 == full * 80
+    assert abs(7e9 * 2 / 1e9 - ex["weights_GB"]) < 1e-9         # 7 B parameters at 16 bit
+    # and the oracle's cache holds exactly that many scalars per sequence and layer
+    c = ora.RankCache.empty(1, 32, 80, 80)
+    c.append(0, np.zeros((3, 32, 80)), np.zeros((3, 32, 80)))
+    assert c.elements() * 2 == ora.kv_cache_bytes(1, 3, 32, 80, 80, 1, 2)
+
+
+# ---- P9: keys -54 %, values -26 %  =>  cache -40 %
+def test_mixed_rank_bookkeeping():
+    v = GOLDEN["layerwise_rank_visualization"]
+    d_h = 100
+    r_k, r_v = round(d_h * (1 - v["key_compression"])), round(d_h * (1 - v["value_compression"]))
+    ratio = ora.kv_cache_bytes(1, 10, 8, r_k, r_v, 4, 2) / ora.kv_cache_bytes(1, 10, 8, d_h, d_h, 4, 2)
+    assert abs(ratio - (1 - v["total_compression"])) < 1e-12
+
+
+# ---- P10: Appendix table, KV sizes at n = 2048 (un-garbled rows)
+def test_appendix_kv_sizes():
+    t = GOLDEN["table9_kv_sizes_GB_at_n2048"]
+    base = ora.kv_cache_bytes(1, t["sequence_length"], 32, 128, 128, 32, 2)
+    assert base == 2 ** 30
+    for label, printed in t["mpt_7b"].items():
+        assert abs(base * float(label[:-1]) / 2 ** 30 - printed) < 5e-3
+    for label, printed in t["llama2_7b"].items():   # achieved compression lands within 0.03 of nominal
+        assert abs(base * float(label[:-1]) / 2 ** 30 - printed) <= 0.03 + 1e-9
+
+
+# ---- P11: low-rank data are reproduced exactly when the noise vanishes (sanity of "U U^T ~ I")
+def test_lowrank_data_sanity():
+    g = synth.rng(906)
+    d_h, r, n = 16, 6, 64
+    A = synth.orthonormal_basis(g, d_h, r).T
+    errs = []
+    for sigma in (0.0, 0.01, 0.1):
+        S = synth.lowrank_plus_noise(g, 400, A, sigma)
+        U = synth.top_singular_basis(S, r)
+        X = synth.lowrank_plus_noise(g, n, A, sigma)
+        errs.append(ora.rel_l2(ora.project_to_basis(X, U) @ U.T, X))
+    assert errs[0] < 1e-12 and errs[0] < errs[1] < errs[2] < 0.5
+
+
+def test_bf16_rounding_helpers():
+    x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.0, 3.4028e38, np.inf], np.float32)
+    r = synth.round_to_bf16(x)
+    assert r[0] == 1.0 and r[1] == 1.0            # tie -> even
+    assert r[2] == np.float32(1.0 + 2 ** -7)      # just above the tie -> up
+    assert r[3] == np.float32(1.0 + 2 ** -6)      # tie -> even (up)
+    assert np.signbit(r[4]) and np.isinf(r[5]) and np.isinf(r[6])
+    import torch
+    t = torch.randn(4096, dtype=torch.float32)
+    assert np.array_equal(synth.round_to_bf16(t.numpy()), t.to(torch.bfloat16).float().numpy())
