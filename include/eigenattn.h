@@ -1,0 +1,177 @@
+/*
+ * eigenattn.h -- C ABI of the Eigen Attention low-rank inference path for MI355X (gfx950).
+ *
+ * The library computes attention in a rank-r space over a compressed, paged KV
+ * cache (arXiv 2408.05646).  The per-head orthonormal bases U^K, U^V are folded
+ * into the projection weights offline (Eq. 8), so the cache holds only rank-r
+ * keys and values and every call below works on rank-r tensors.
+ *
+ * Conventions
+ *  - Every function returns int: EA_OK (0) or a negative EA_ERR_* code; nothing
+ *    aborts, throws, allocates or frees device memory, or synchronises.
+ *  - Pointers named dev_* are DEVICE pointers owned by the caller.  `stream` is a
+ *    hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *    enqueued on it and the call returns immediately.
+ *  - Shapes are row-major with the last index fastest.  B = sequences in the
+ *    batch, T = new tokens per sequence in this call, H = query heads,
+ *    H_kv = KV heads (H % H_kv == 0; query head i uses KV head i / (H / H_kv)),
+ *    d = d_model, d_h = d_head, r_k / r_v = key / value rank per head.
+ *  - Host-side argument, shape and alignment checks happen before any launch.
+ *    Errors that only the device can see (a page id outside the pool, a position
+ *    beyond the page table) never fault: the affected tokens are skipped on
+ *    write and masked out on read.
+ *  - dtype EA_F32: x, weights, q_r, o, y and the cache are float.  dtype
+ *    EA_BF16: x, weights, y and the cache are bfloat16 with fp32 accumulation;
+ *    q_r and o are float or bfloat16 as the q_dtype / o_dtype arguments say.
+ *    The cache is written with one round-to-nearest-even of the fp32 accumulator.
+ */
+#ifndef EIGENATTN_H
+#define EIGENATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EA_API __attribute__((visibility("default")))
+
+enum {
+  EA_OK = 0,
+  EA_ERR_ARG = -1,         /* null pointer, non-positive size, bad enum          */
+  EA_ERR_SHAPE = -2,       /* shape the kernels do not support (see each call)   */
+  EA_ERR_ALIGN = -3,       /* pointer not 16-byte aligned                         */
+  EA_ERR_WORKSPACE = -4,   /* workspace missing or too small                      */
+  EA_ERR_DEVICE = -5       /* the HIP runtime reported a launch error             */
+};
+
+enum { EA_F32 = 0, EA_BF16 = 1 };
+
+/* One attention layer.  The softmax divisor is sqrt(d_head), never sqrt(r):
+ * Eq. (7) keeps sqrt(d_h) in rank space. */
+typedef struct ea_layer_desc {
+  int32_t d_model;
+  int32_t n_heads;
+  int32_t n_kv_heads;
+  int32_t d_head;
+  int32_t r_k;           /* 1..128 (EA_BF16) / 1..256 (EA_F32)                    */
+  int32_t r_v;
+  int32_t dtype;         /* EA_F32 or EA_BF16                                      */
+  int32_t page_tokens;   /* tokens per cache page: multiple of 64 (EA_BF16), of 16 (EA_F32) */
+} ea_layer_desc;
+
+/* Geometry of the two page pools of a layer (K and V are separate pools, page p
+ * of a pool starts at element p * page_elems).  Inside a page the kv heads
+ * follow each other, slab by slab.  Inside a slab the element order is:
+ *  layout_id 0 (EA_F32): token-major rows, [page_tokens][r_pad].
+ *  layout_id 1 (EA_BF16): matrix-core fragment order.  Tokens are grouped in tiles
+ *    of 64.  K tile: [4 blocks of 16 tokens][r_k_pad/8 chunks][16 tokens][8 channels].
+ *    V tile: [2 groups of 32 tokens][r_v_pad/16 blocks][4 quads][16 channels][8 token slots],
+ *    token slot j of quad q is token 16*(j/4) + 4*q + j%4 of the group.
+ *  Padding channels (r..r_pad-1) are written as zero by ea_project_qkv and
+ *  ea_cache_scatter; r_k_pad is a multiple of 8 (4 for EA_F32), r_v_pad of 16 (4).
+ *  ea_cache_k_index / ea_cache_v_index give the exact element index. */
+typedef struct ea_cache_layout {
+  int32_t layout_id;
+  int32_t elem_bytes;
+  int32_t r_k_pad;
+  int32_t r_v_pad;
+  int64_t k_slab_elems;   /* page_tokens * r_k_pad                                  */
+  int64_t v_slab_elems;
+  int64_t k_page_elems;   /* n_kv_heads * k_slab_elems                              */
+  int64_t v_page_elems;
+} ea_cache_layout;
+
+/* ---- host-only helpers (pure functions, no device access) ---------------- */
+
+EA_API int ea_cache_layout_query(const ea_layer_desc* desc, ea_cache_layout* out);
+
+/* Element index inside the K (V) pool of channel `channel` of the token at
+ * offset `token_in_page` of kv head `kv_head` in physical page `page`;
+ * -1 on an argument out of range.  This is the reference of the layout. */
+EA_API int64_t ea_cache_k_index(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
+EA_API int64_t ea_cache_v_index(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
+
+/* Logical token slot of position `pos` of a sequence whose page-table row is
+ * `page_table_row` (host memory, max_pages entries): page * page_tokens +
+ * pos % page_tokens, or -1 if pos is beyond the table.  Reference of the paging
+ * arithmetic used by every kernel (K <- Concat(K, k) in paged form). */
+EA_API int64_t ea_cache_slot(const ea_layer_desc* desc, const int32_t* page_table_row, int32_t max_pages, int32_t pos);
+
+EA_API const char* ea_strerror(int code);
+EA_API int ea_version(void);
+
+/* ---- cache import / export (device) -------------------------------------- */
+
+/* Copy dense rank-r tensors into / out of the paged pools.
+ * dev_k_dense [B, H_kv, n, r_k], dev_v_dense [B, H_kv, n, r_v] in the cache
+ * dtype; token t of sequence b goes to position pos0 + t.  Either dense
+ * pointer may be NULL to skip that pool.  Scatter zero-fills padding channels. */
+EA_API int ea_cache_scatter(const ea_layer_desc* desc, const void* dev_k_dense, const void* dev_v_dense,
+                     void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
+                     int32_t B, int32_t n, int32_t pos0, int32_t max_pages, int32_t pool_pages, void* stream);
+EA_API int ea_cache_gather(const ea_layer_desc* desc, void* dev_k_dense, void* dev_v_dense,
+                    const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
+                    int32_t B, int32_t n, int32_t pos0, int32_t max_pages, int32_t pool_pages, void* stream);
+
+/* ---- the hot path -------------------------------------------------------- */
+
+/* Fused low-rank QKV projection and cache append: Eq. (1) with the folded
+ * weights of Eq. (8), then K <- Concat(K, k), V <- Concat(V, v) (Sec. 2, LLM
+ * inference).
+ *   dev_x      [B*T, d]  (row b*T + t is token t of sequence b), desc dtype
+ *   dev_wqkv_t [H*r_k + H_kv*r_k + H_kv*r_v, d]: one row of d weights per
+ *              output channel ("out-major"), ordered q heads, k heads, v heads;
+ *              row (i*r_k + c) is column c of W^Q_i U^K_{g(i)}, and so on.
+ *   dev_q_r    [B*T, H, r_k] out, float (q_dtype EA_F32) or bfloat16 (EA_BF16)
+ *   dev_seq_len[B]: length of each sequence BEFORE this call; token t is
+ *              appended at position seq_len[b] + t.  Not modified.
+ *   dev_page_table [B, max_pages] int32 physical page ids (< pool_pages).
+ * Requires d % 32 == 0 for EA_BF16 (d % 4 == 0 for EA_F32). */
+EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t,
+                   void* dev_q_r, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
+
+/* Number of splits of the cached sequence ea_decode_attn would pick for
+ * n_splits = 0, and the workspace it needs for a given split count. */
+EA_API int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len);
+EA_API int64_t ea_decode_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits);
+
+/* Generation-phase attention in rank space, Eq. (3) with Eq. (7)'s rank-r
+ * operands:  s_t = q_r . K_r[t] / sqrt(d_h) for t < seq_len[b],
+ * p = Softmax(s), o = sum_t p_t V_r[t].
+ *   dev_q_r [B, H, r_k] float;  dev_out [B, H, r_v] float
+ *   dev_seq_len [B]: cached tokens per sequence INCLUDING the one just appended;
+ *              a sequence of length 0 yields a zero output row.
+ *   n_splits: the cached sequence is cut in this many parts handled by different
+ *              workgroups and merged afterwards (0 = choose).  dev_ws must hold
+ *              ea_decode_workspace_bytes(desc, B, n_splits) bytes when the
+ *              effective split count is > 1. */
+EA_API int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
+                   int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
+                   void* dev_ws, int64_t ws_bytes, void* stream);
+
+/* Prefill-phase attention in rank space, Eq. (2) with a causal mask: the n
+ * queries of sequence b are its last n cached positions (query j sits at
+ * position seq_len[b] - n + j and sees positions <= its own).
+ *   dev_q_r [B, n, H, r_k], dev_out [B, n, H, r_v]: desc dtype (EA_F32 float,
+ *   EA_BF16 bfloat16).  dev_seq_len [B] includes the n new tokens. */
+EA_API int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out,
+                    int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages, void* stream);
+
+/* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
+ * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
+ *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T
+ *   dev_wo_t [d, H*r_v] out-major: row a holds column a of the stacked W^O'
+ *   dev_y    [M, d] desc dtype.
+ * Requires (H*r_v) % 32 == 0 for EA_BF16 (% 4 for EA_F32). */
+EA_API int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, const void* dev_wo_t,
+                void* dev_y, int32_t M, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EIGENATTN_H */

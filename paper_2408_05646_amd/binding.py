@@ -1,0 +1,266 @@
+"""ctypes binding of libeigenattn.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors living on the GPU (PyTorch is used for device memory
+and streams, nothing else); every step of the path runs in the library's HIP
+kernels.  There is no CPU fallback: if the library is missing, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+__all__ = [
+    "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
+    "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
+    "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
+    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS",
+]
+
+EA_F32, EA_BF16 = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
+    "ea_cache_scatter", "ea_cache_gather", "ea_project_qkv", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
+    "ea_decode_attn", "ea_prefill_attn", "ea_out_proj",
+)
+
+
+class EigenAttnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("d_model", "n_heads", "n_kv_heads", "d_head", "r_k", "r_v", "dtype", "page_tokens")]
+
+    def __repr__(self):
+        return "LayerDesc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"
+
+
+class CacheLayout(ctypes.Structure):
+    _fields_ = [("layout_id", ctypes.c_int32), ("elem_bytes", ctypes.c_int32), ("r_k_pad", ctypes.c_int32),
+                ("r_v_pad", ctypes.c_int32), ("k_slab_elems", ctypes.c_int64), ("v_slab_elems", ctypes.c_int64),
+                ("k_page_elems", ctypes.c_int64), ("v_page_elems", ctypes.c_int64)]
+
+
+_LIB = None
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libeigenattn.so")
+
+
+def load_library():
+    """Loads libeigenattn.so (built by paper_2408_05646_amd/build.py).  Raises if it is not there."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2408_05646_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    P, I32, I64, VP = ctypes.POINTER, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+    D = P(LayerDesc)
+    lib.ea_version.restype = ctypes.c_int
+    lib.ea_strerror.restype = ctypes.c_char_p
+    lib.ea_strerror.argtypes = [ctypes.c_int]
+    lib.ea_cache_layout_query.argtypes = [D, P(CacheLayout)]
+    for f in (lib.ea_cache_k_index, lib.ea_cache_v_index):
+        f.restype = I64
+        f.argtypes = [D, I32, I32, I32, I32]
+    lib.ea_cache_slot.restype = I64
+    lib.ea_cache_slot.argtypes = [D, P(I32), I32, I32]
+    lib.ea_cache_scatter.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    lib.ea_cache_gather.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    lib.ea_project_qkv.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
+    lib.ea_decode_auto_splits.restype = I32
+    lib.ea_decode_auto_splits.argtypes = [D, I32, I32]
+    lib.ea_decode_workspace_bytes.restype = I64
+    lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
+    lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_prefill_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
+    lib.ea_out_proj.argtypes = [D, VP, I32, VP, VP, I32, VP]
+    _LIB = lib
+    return lib
+
+
+def strerror(code: int) -> str:
+    return load_library().ea_strerror(int(code)).decode()
+
+
+def version() -> int:
+    return int(load_library().ea_version())
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise EigenAttnError(rc, where)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _dt(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return EA_F32
+    if t.dtype == torch.bfloat16:
+        return EA_BF16
+    raise ValueError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _expect(t, desc_dtype: int, name: str) -> None:
+    if _dt(t) != desc_dtype:
+        raise ValueError(f"{name}: dtype {t.dtype} does not match the layer dtype")
+
+
+def _i32(t, name: str) -> None:
+    import torch
+    if t.dtype != torch.int32:
+        raise ValueError(f"{name} must be int32")
+
+
+# ---- host helpers ------------------------------------------------------------
+def cache_layout_query(desc: LayerDesc) -> CacheLayout:
+    out = CacheLayout()
+    _check(load_library().ea_cache_layout_query(ctypes.byref(desc), ctypes.byref(out)), "ea_cache_layout_query")
+    return out
+
+
+def cache_k_index(desc: LayerDesc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
+    return int(load_library().ea_cache_k_index(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def cache_v_index(desc: LayerDesc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
+    return int(load_library().ea_cache_v_index(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def cache_slot(desc: LayerDesc, page_table_row, pos: int) -> int:
+    row = np.ascontiguousarray(page_table_row, dtype=np.int32)
+    return int(load_library().ea_cache_slot(ctypes.byref(desc), row.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                            int(row.shape[0]), int(pos)))
+
+
+def alloc_pools(desc: LayerDesc, pool_pages: int, device="cuda", zero: bool = True):
+    """Device memory for the K and V page pools of one layer: [pool_pages, page_elems] each."""
+    import torch
+    lay = cache_layout_query(desc)
+    dt = torch.bfloat16 if desc.dtype == EA_BF16 else torch.float32
+    mk = torch.zeros if zero else torch.empty
+    return (mk((pool_pages, lay.k_page_elems), dtype=dt, device=device),
+            mk((pool_pages, lay.v_page_elems), dtype=dt, device=device))
+
+
+# ---- device calls ------------------------------------------------------------
+def cache_scatter(desc, k_dense, v_dense, k_pool, v_pool, page_table, pos0: int = 0, stream=None) -> None:
+    """k_dense [B, H_kv, n, r_k], v_dense [B, H_kv, n, r_v] -> pools (either dense tensor may be None)."""
+    ref = k_dense if k_dense is not None else v_dense
+    B, n = ref.shape[0], ref.shape[2]
+    _i32(page_table, "page_table")
+    for t, nm in ((k_dense, "k_dense"), (v_dense, "v_dense"), (k_pool, "k_pool"), (v_pool, "v_pool")):
+        if t is not None:
+            _expect(t, desc.dtype, nm)
+    rc = load_library().ea_cache_scatter(ctypes.byref(desc), _ptr(k_dense), _ptr(v_dense), _ptr(k_pool), _ptr(v_pool),
+                                         _ptr(page_table), B, n, pos0, page_table.shape[1],
+                                         (k_pool if k_pool is not None else v_pool).shape[0], _stream(stream))
+    _check(rc, "ea_cache_scatter")
+
+
+def cache_gather(desc, k_dense, v_dense, k_pool, v_pool, page_table, pos0: int = 0, stream=None) -> None:
+    ref = k_dense if k_dense is not None else v_dense
+    B, n = ref.shape[0], ref.shape[2]
+    _i32(page_table, "page_table")
+    for t, nm in ((k_dense, "k_dense"), (v_dense, "v_dense"), (k_pool, "k_pool"), (v_pool, "v_pool")):
+        if t is not None:
+            _expect(t, desc.dtype, nm)
+    rc = load_library().ea_cache_gather(ctypes.byref(desc), _ptr(k_dense), _ptr(v_dense), _ptr(k_pool), _ptr(v_pool),
+                                        _ptr(page_table), B, n, pos0, page_table.shape[1],
+                                        (k_pool if k_pool is not None else v_pool).shape[0], _stream(stream))
+    _check(rc, "ea_cache_gather")
+
+
+def project_qkv(desc, x, wqkv_t, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+    """x [B*T, d]; wqkv_t [N_qkv, d]; q_r [B*T, H, r_k] (float32 or bfloat16) is written, k/v go to the pools."""
+    B = seq_len.shape[0]
+    if x.shape[0] != B * T:
+        raise ValueError("x must have B*T rows")
+    _expect(x, desc.dtype, "x"); _expect(wqkv_t, desc.dtype, "wqkv_t")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    n_out = desc.n_heads * desc.r_k + desc.n_kv_heads * (desc.r_k + desc.r_v)
+    if tuple(wqkv_t.shape) != (n_out, desc.d_model) or x.shape[1] != desc.d_model:
+        raise ValueError("weight / activation shape does not match the layer")
+    if q_r.numel() != B * T * desc.n_heads * desc.r_k:
+        raise ValueError("q_r has the wrong size")
+    rc = load_library().ea_project_qkv(ctypes.byref(desc), _ptr(x), _ptr(wqkv_t), _ptr(q_r), _dt(q_r), _ptr(k_pool),
+                                       _ptr(v_pool), _ptr(page_table), _ptr(seq_len), B, T, page_table.shape[1],
+                                       k_pool.shape[0], _stream(stream))
+    _check(rc, "ea_project_qkv")
+
+
+def decode_auto_splits(desc, B: int, max_seq_len: int) -> int:
+    return int(load_library().ea_decode_auto_splits(ctypes.byref(desc), B, max_seq_len))
+
+
+def decode_workspace_bytes(desc, B: int, n_splits: int) -> int:
+    return int(load_library().ea_decode_workspace_bytes(ctypes.byref(desc), B, n_splits))
+
+
+def decode_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, n_splits: int = 0, ws=None, stream=None) -> None:
+    """q_r [B, H, r_k] float32 -> out [B, H, r_v] float32 over the cached tokens of each sequence."""
+    import torch
+    B = seq_len.shape[0]
+    if q_r.dtype != torch.float32 or out.dtype != torch.float32:
+        raise ValueError("q_r and out must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_decode_attn(ctypes.byref(desc), _ptr(q_r), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+                                       _ptr(seq_len), _ptr(out), B, page_table.shape[1], k_pool.shape[0], n_splits,
+                                       _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_decode_attn")
+
+
+def prefill_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, stream=None) -> None:
+    """q_r [B, n, H, r_k] -> out [B, n, H, r_v] (layer dtype), causal over each sequence's cache."""
+    B, n = q_r.shape[0], q_r.shape[1]
+    _expect(q_r, desc.dtype, "q_r"); _expect(out, desc.dtype, "out")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    if q_r.numel() != B * n * desc.n_heads * desc.r_k or out.numel() != B * n * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    rc = load_library().ea_prefill_attn(ctypes.byref(desc), _ptr(q_r), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+                                        _ptr(seq_len), _ptr(out), B, n, page_table.shape[1], k_pool.shape[0],
+                                        _stream(stream))
+    _check(rc, "ea_prefill_attn")
+
+
+def out_proj(desc, o, wo_t, y, stream=None) -> None:
+    """o [M, H*r_v] (float32 or bfloat16) x wo_t [d, H*r_v] -> y [M, d] (layer dtype)."""
+    M = y.shape[0]
+    _expect(wo_t, desc.dtype, "wo_t"); _expect(y, desc.dtype, "y")
+    if tuple(wo_t.shape) != (desc.d_model, desc.n_heads * desc.r_v) or o.numel() != M * desc.n_heads * desc.r_v:
+        raise ValueError("o / wo_t shape does not match the layer")
+    rc = load_library().ea_out_proj(ctypes.byref(desc), _ptr(o), _dt(o), _ptr(wo_t), _ptr(y), M, _stream(stream))
+    _check(rc, "ea_out_proj")

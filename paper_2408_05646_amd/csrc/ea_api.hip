@@ -1,0 +1,207 @@
+// Host side of the C ABI: argument checks, layout reference functions, dispatch.
+#include "ea_common.h"
+
+using namespace ea;
+
+extern "C" {
+
+int ea_version(void) { return 100; }
+
+const char* ea_strerror(int code) {
+  switch (code) {
+    case EA_OK: return "ok";
+    case EA_ERR_ARG: return "invalid argument (null pointer, non-positive size or bad enum)";
+    case EA_ERR_SHAPE: return "unsupported shape";
+    case EA_ERR_ALIGN: return "pointer is not 16-byte aligned";
+    case EA_ERR_WORKSPACE: return "workspace missing or too small";
+    case EA_ERR_DEVICE: return "HIP launch error";
+    default: return "unknown error code";
+  }
+}
+
+int ea_cache_layout_query(const ea_layer_desc* desc, ea_cache_layout* out) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!out) return EA_ERR_ARG;
+  Geo g = make_geo(desc, 0, 0);
+  out->layout_id = desc->dtype == EA_BF16 ? 1 : 0;
+  out->elem_bytes = desc->dtype == EA_BF16 ? 2 : 4;
+  out->r_k_pad = g.r_k_pad;
+  out->r_v_pad = g.r_v_pad;
+  out->k_slab_elems = g.k_slab;
+  out->v_slab_elems = g.v_slab;
+  out->k_page_elems = g.k_page;
+  out->v_page_elems = g.v_page;
+  return EA_OK;
+}
+
+static int64_t cache_index(const ea_layer_desc* desc, bool is_k, int32_t page, int32_t kv_head, int32_t t, int32_t c) {
+  if (validate_desc(desc) != EA_OK) return -1;
+  Geo g = make_geo(desc, 0, 0);
+  const int32_t r = is_k ? g.r_k : g.r_v;
+  if (page < 0 || kv_head < 0 || kv_head >= g.n_kv_heads || t < 0 || t >= g.page_tokens || c < 0 || c >= r) return -1;
+  const int32_t r_pad = is_k ? g.r_k_pad : g.r_v_pad;
+  const int64_t base = (int64_t)page * (is_k ? g.k_page : g.v_page) + (int64_t)kv_head * (is_k ? g.k_slab : g.v_slab);
+  if (desc->dtype == EA_F32) return base + f32_slab_off(t, c, r_pad);
+  return base + (is_k ? bf16_k_slab_off(t, c, r_pad) : bf16_v_slab_off(t, c, r_pad));
+}
+
+int64_t ea_cache_k_index(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel) {
+  return cache_index(desc, true, page, kv_head, token_in_page, channel);
+}
+int64_t ea_cache_v_index(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel) {
+  return cache_index(desc, false, page, kv_head, token_in_page, channel);
+}
+
+int64_t ea_cache_slot(const ea_layer_desc* desc, const int32_t* page_table_row, int32_t max_pages, int32_t pos) {
+  if (validate_desc(desc) != EA_OK || !page_table_row || pos < 0) return -1;
+  const int32_t lp = pos / desc->page_tokens;
+  if (lp >= max_pages) return -1;
+  const int32_t page = page_table_row[lp];
+  if (page < 0) return -1;
+  return (int64_t)page * desc->page_tokens + pos % desc->page_tokens;
+}
+
+int ea_cache_scatter(const ea_layer_desc* desc, const void* dev_k_dense, const void* dev_v_dense, void* dev_k_pool,
+                     void* dev_v_pool, const int32_t* dev_page_table, int32_t B, int32_t n, int32_t pos0,
+                     int32_t max_pages, int32_t pool_pages, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_page_table || B <= 0 || n < 0 || pos0 < 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if ((dev_k_dense && !dev_k_pool) || (dev_v_dense && !dev_v_pool)) return EA_ERR_ARG;
+  if (n == 0) return EA_OK;
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  return cache_copy(desc, g, true, const_cast<void*>(dev_k_dense), const_cast<void*>(dev_v_dense), dev_k_pool,
+                    dev_v_pool, dev_page_table, B, n, pos0, (hipStream_t)stream);
+}
+
+int ea_cache_gather(const ea_layer_desc* desc, void* dev_k_dense, void* dev_v_dense, const void* dev_k_pool,
+                    const void* dev_v_pool, const int32_t* dev_page_table, int32_t B, int32_t n, int32_t pos0,
+                    int32_t max_pages, int32_t pool_pages, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_page_table || B <= 0 || n < 0 || pos0 < 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if ((dev_k_dense && !dev_k_pool) || (dev_v_dense && !dev_v_pool)) return EA_ERR_ARG;
+  if (n == 0) return EA_OK;
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  return cache_copy(desc, g, false, dev_k_dense, dev_v_dense, const_cast<void*>(dev_k_pool),
+                    const_cast<void*>(dev_v_pool), dev_page_table, B, n, pos0, (hipStream_t)stream);
+}
+
+int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t, void* dev_q_r, int32_t q_dtype,
+                   void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_x || !dev_wqkv_t || !dev_q_r || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len)
+    return EA_ERR_ARG;
+  if (B <= 0 || T <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if (q_dtype != EA_F32 && q_dtype != EA_BF16) return EA_ERR_ARG;
+  if (desc->dtype == EA_F32 && q_dtype != EA_F32) return EA_ERR_ARG;
+  if ((int64_t)B * T > INT32_MAX) return EA_ERR_SHAPE;
+  if (!aligned16(dev_x) || !aligned16(dev_wqkv_t) || !aligned16(dev_q_r) || !aligned16(dev_k_pool) ||
+      !aligned16(dev_v_pool))
+    return EA_ERR_ALIGN;
+  if (desc->d_model % (desc->dtype == EA_BF16 ? 32 : 4) != 0) return EA_ERR_SHAPE;
+  QkvDest dst;
+  dst.q = dev_q_r;
+  dst.q_is_f32 = q_dtype == EA_F32;
+  dst.k_pool = dev_k_pool;
+  dst.v_pool = dev_v_pool;
+  dst.page_table = dev_page_table;
+  dst.seq_len = dev_seq_len;
+  dst.T = T;
+  dst.g = make_geo(desc, max_pages, pool_pages);
+  const int32_t N = desc->n_heads * desc->r_k + desc->n_kv_heads * (desc->r_k + desc->r_v);
+  if (desc->dtype == EA_BF16)
+    return gemm_qkv_bf16(dev_x, dev_wqkv_t, B * T, N, desc->d_model, dst, (hipStream_t)stream);
+  return gemm_qkv_f32((const float*)dev_x, (const float*)dev_wqkv_t, B * T, N, desc->d_model, dst, (hipStream_t)stream);
+}
+
+int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || max_seq_len <= 0) return 1;
+  // Aim at a few workgroups per compute unit (256 CUs, two resident workgroups each)
+  // while leaving every workgroup at least eight 64-token tiles.
+  const int64_t streams = (int64_t)B * (desc->dtype == EA_BF16 ? desc->n_kv_heads : desc->n_heads);
+  const int32_t tiles = (max_seq_len + kTile - 1) / kTile;
+  int64_t want = (2048 + streams - 1) / streams;
+  int64_t cap = tiles / 8;
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  return (int32_t)want;
+}
+
+int64_t ea_decode_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || n_splits < 0) return -1;
+  if (n_splits <= 1) return 0;
+  Geo g = make_geo(desc, 0, 0);
+  return ws_floats(B, g.n_heads, n_splits, g.r_v_pad) * (int64_t)sizeof(float);
+}
+
+int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out, int32_t B,
+                   int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                   void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out) return EA_ERR_ARG;
+  if (B <= 0 || max_pages <= 0 || pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  if (n_splits == 0) {
+    const int64_t cap_tokens = (int64_t)max_pages * desc->page_tokens;
+    n_splits = ea_decode_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
+  }
+  if (n_splits > 1) {
+    if (!dev_ws || !aligned16(dev_ws)) return EA_ERR_WORKSPACE;
+    if (ws_bytes < ea_decode_workspace_bytes(desc, B, n_splits)) return EA_ERR_WORKSPACE;
+  }
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  hipStream_t st = (hipStream_t)stream;
+  if (desc->dtype == EA_BF16)
+    rc = decode_bf16(desc, g, (const float*)dev_q_r, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, dev_out, B,
+                     n_splits, (float*)dev_ws, st);
+  else
+    rc = decode_f32(desc, g, (const float*)dev_q_r, (const float*)dev_k_pool, (const float*)dev_v_pool, dev_page_table,
+                    dev_seq_len, dev_out, B, n_splits, (float*)dev_ws, st);
+  if (rc != EA_OK) return rc;
+  if (n_splits > 1) rc = merge_splits(g, (const float*)dev_ws, dev_out, B, n_splits, st);
+  return rc;
+}
+
+int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out, int32_t B, int32_t n,
+                    int32_t max_pages, int32_t pool_pages, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out) return EA_ERR_ARG;
+  if (B <= 0 || n <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  if (desc->dtype == EA_BF16)
+    return prefill_bf16(desc, g, dev_q_r, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, dev_out, B, n,
+                        (hipStream_t)stream);
+  return prefill_f32(desc, g, (const float*)dev_q_r, (const float*)dev_k_pool, (const float*)dev_v_pool,
+                     dev_page_table, dev_seq_len, (float*)dev_out, B, n, (hipStream_t)stream);
+}
+
+int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, const void* dev_wo_t, void* dev_y,
+                int32_t M, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_o || !dev_wo_t || !dev_y || M <= 0) return EA_ERR_ARG;
+  if (o_dtype != EA_F32 && o_dtype != EA_BF16) return EA_ERR_ARG;
+  if (desc->dtype == EA_F32 && o_dtype != EA_F32) return EA_ERR_ARG;
+  if (!aligned16(dev_o) || !aligned16(dev_wo_t) || !aligned16(dev_y)) return EA_ERR_ALIGN;
+  const int32_t K = desc->n_heads * desc->r_v;
+  if (K % (desc->dtype == EA_BF16 ? 32 : 4) != 0) return EA_ERR_SHAPE;
+  if (desc->dtype == EA_BF16)
+    return gemm_out_bf16(dev_o, o_dtype == EA_F32, dev_wo_t, dev_y, M, desc->d_model, K, (hipStream_t)stream);
+  return gemm_out_f32((const float*)dev_o, (const float*)dev_wo_t, (float*)dev_y, M, desc->d_model, K,
+                      (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,143 @@
+// Internal definitions shared by the HIP translation units of libeigenattn.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "eigenattn.h"
+
+namespace ea {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kTile = 64;          // tokens per cache tile of the bf16 layout
+
+// Cache geometry, precomputed on the host and passed to kernels by value.
+struct Geo {
+  int32_t n_heads, n_kv_heads, group;   // group = n_heads / n_kv_heads
+  int32_t r_k, r_v, r_k_pad, r_v_pad;
+  int32_t page_tokens;
+  int32_t max_pages, pool_pages;
+  int64_t k_slab, v_slab, k_page, v_page;   // elements
+};
+
+__host__ __device__ inline int32_t round_up(int32_t x, int32_t m) { return (x + m - 1) / m * m; }
+
+inline int validate_desc(const ea_layer_desc* d) {
+  if (!d) return EA_ERR_ARG;
+  if (d->dtype != EA_F32 && d->dtype != EA_BF16) return EA_ERR_ARG;
+  if (d->d_model <= 0 || d->n_heads <= 0 || d->n_kv_heads <= 0 || d->d_head <= 0 || d->r_k <= 0 || d->r_v <= 0 ||
+      d->page_tokens <= 0)
+    return EA_ERR_ARG;
+  if (d->n_heads % d->n_kv_heads != 0) return EA_ERR_SHAPE;
+  if (d->dtype == EA_BF16) {
+    if (d->r_k > 128 || d->r_v > 128) return EA_ERR_SHAPE;
+    if (d->page_tokens % kTile != 0) return EA_ERR_SHAPE;
+    if (d->n_heads / d->n_kv_heads > 16) return EA_ERR_SHAPE;
+  } else {
+    if (d->r_k > 256 || d->r_v > 256) return EA_ERR_SHAPE;
+    if (d->page_tokens % 16 != 0) return EA_ERR_SHAPE;
+  }
+  return EA_OK;
+}
+
+inline Geo make_geo(const ea_layer_desc* d, int32_t max_pages, int32_t pool_pages) {
+  Geo g;
+  g.n_heads = d->n_heads;
+  g.n_kv_heads = d->n_kv_heads;
+  g.group = d->n_heads / d->n_kv_heads;
+  g.r_k = d->r_k;
+  g.r_v = d->r_v;
+  if (d->dtype == EA_BF16) {
+    g.r_k_pad = round_up(d->r_k, 8);
+    g.r_v_pad = round_up(d->r_v, 16);
+  } else {
+    g.r_k_pad = round_up(d->r_k, 4);
+    g.r_v_pad = round_up(d->r_v, 4);
+  }
+  g.page_tokens = d->page_tokens;
+  g.max_pages = max_pages;
+  g.pool_pages = pool_pages;
+  g.k_slab = (int64_t)d->page_tokens * g.r_k_pad;
+  g.v_slab = (int64_t)d->page_tokens * g.r_v_pad;
+  g.k_page = g.k_slab * d->n_kv_heads;
+  g.v_page = g.v_slab * d->n_kv_heads;
+  return g;
+}
+
+// ---- element offsets inside one (page, kv head) slab ------------------------
+// fp32 cache: token-major rows.
+__host__ __device__ inline int64_t f32_slab_off(int32_t t, int32_t c, int32_t r_pad) { return (int64_t)t * r_pad + c; }
+
+// bf16 K: tiles of 64 tokens; in a tile [4 blocks of 16 tokens][r_pad/8 chunks][16 tokens][8 channels].
+__host__ __device__ inline int64_t bf16_k_slab_off(int32_t t, int32_t c, int32_t r_pad) {
+  const int32_t tile = t >> 6, tt = t & 63, tb = tt >> 4, row = tt & 15;
+  const int32_t nck = r_pad >> 3;
+  return (int64_t)tile * (kTile * r_pad) + (((tb * nck + (c >> 3)) * 16 + row) << 3) + (c & 7);
+}
+
+// bf16 V: tiles of 64 tokens; in a tile [2 groups of 32 tokens][r_pad/16 blocks][4 quads][16 channels][8 slots],
+// slot j of quad q <-> token 16*(j/4) + 4*q + j%4 of the group.
+__host__ __device__ inline int64_t bf16_v_slab_off(int32_t t, int32_t c, int32_t r_pad) {
+  const int32_t tile = t >> 6, tt = t & 63, grp = tt >> 5, t32 = tt & 31;
+  const int32_t half = t32 >> 4, r16 = t32 & 15, quad = r16 >> 2, j = half * 4 + (r16 & 3);
+  const int32_t ncb = r_pad >> 4;
+  return (int64_t)tile * (kTile * r_pad) + (((((grp * ncb + (c >> 4)) * 4 + quad) * 16 + (c & 15)) << 3) + j);
+}
+
+// D[16x16] += A[16x32] . B[32x16] on the matrix cores.  Lane l holds, of A, row l%16 and
+// k = 8*(l/16) .. +7; of B, column l%16 and the same k; of D, column l%16 and rows 4*(l/16) .. +3.
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 zero_frag() {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  return __builtin_bit_cast(bf16x8, z);
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? EA_OK : EA_ERR_DEVICE; }
+
+// ---- entry points implemented per translation unit --------------------------
+int cache_copy(const ea_layer_desc* d, const Geo& g, bool scatter, void* k_dense, void* v_dense, void* k_pool,
+               void* v_pool, const int32_t* page_table, int32_t B, int32_t n, int32_t pos0, hipStream_t st);
+
+int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
+                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
+                hipStream_t st);
+int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
+               const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
+               hipStream_t st);
+int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st);
+
+int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
+                 const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st);
+int prefill_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
+                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n, hipStream_t st);
+
+// Destination of the fused QKV GEMM: q goes to a dense tensor, k and v to the paged cache.
+struct QkvDest {
+  void* q;
+  int32_t q_is_f32;
+  void* k_pool;
+  void* v_pool;
+  const int32_t* page_table;
+  const int32_t* seq_len;
+  int32_t T;
+  Geo g;
+};
+int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);
+int gemm_qkv_f32(const float* x, const float* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);
+int gemm_out_bf16(const void* a, int32_t a_is_f32, const void* w_t, void* y, int32_t M, int32_t N, int32_t K,
+                  hipStream_t st);
+int gemm_out_f32(const float* a, const float* w_t, float* y, int32_t M, int32_t N, int32_t K, hipStream_t st);
+
+// Workspace layout of the split partials: m [B,H,S], l [B,H,S], acc [B,H,S,r_v_pad].
+__host__ __device__ inline int64_t ws_floats(int32_t B, int32_t H, int32_t S, int32_t r_v_pad) {
+  return (int64_t)B * H * S * (2 + r_v_pad);
+}
+
+}  // namespace ea

@@ -1,0 +1,235 @@
+// fp32 path: straightforward vector-ALU kernels for the reference-precision
+// configuration (float cache, float weights).  Token-major cache rows.
+#include "ea_common.h"
+#include "ea_epilogue.h"
+
+namespace ea {
+
+constexpr int kChunk = 256;   // tokens per step = threads per workgroup
+
+// Online-softmax attention of one query over tokens [tok_begin, tok_end) of sequence b (Eq. 3 / Eq. 2 row).
+// Thread t scores token chunk*256 + t; afterwards thread c accumulates value channel c.
+// Returns through (m, l, acc): running max (log2 domain), denominator and numerator of channel threadIdx.x.
+__device__ __forceinline__ void attend_f32(const float* __restrict__ qrow, const float* __restrict__ k_pool,
+                                           const float* __restrict__ v_pool, const int32_t* __restrict__ pt_row,
+                                           const Geo& g, int kvh, int tok_begin, int tok_end, float scale_log2,
+                                           float& m_out, float& l_out, float& acc_out) {
+  __shared__ float sq[256];
+  __shared__ float sp[kChunk];
+  __shared__ int64_t svoff[kChunk];
+  __shared__ float sred[4];
+  const int tid = threadIdx.x;
+  __syncthreads();
+  if (tid < g.r_k) sq[tid] = qrow[tid];
+  __syncthreads();
+  float m = -INFINITY, l = 0.f, acc = 0.f;
+  for (int base = tok_begin; base < tok_end; base += kChunk) {
+    const int tok = base + tid;
+    float s = -INFINITY;
+    int64_t voff = -1;
+    if (tok < tok_end) {
+      const int lp = tok / g.page_tokens;
+      const int page = lp < g.max_pages ? pt_row[lp] : -1;
+      if (page >= 0 && page < g.pool_pages) {
+        const int tp = tok % g.page_tokens;
+        const float* krow = k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tp * g.r_k_pad;
+        float dot = 0.f;
+        for (int c = 0; c < g.r_k; ++c) dot = fmaf(sq[c], krow[c], dot);
+        s = dot * scale_log2;
+        voff = (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab + (int64_t)tp * g.r_v_pad;
+      }
+    }
+    float mx = s;
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+    if ((tid & 63) == 0) sred[tid >> 6] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(sred[0], sred[1]), fmaxf(sred[2], sred[3]));
+    const float m_new = fmaxf(m, mx);
+    const float m_use = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = exp2f(m - m_use);
+    m = m_new;
+    sp[tid] = exp2f(s - m_use);
+    svoff[tid] = voff;
+    __syncthreads();
+    const int cnt = min(kChunk, tok_end - base);
+    float psum = 0.f, vsum = 0.f;
+    for (int j = 0; j < cnt; ++j) {
+      const float p = sp[j];
+      psum += p;
+      if (tid < g.r_v && svoff[j] >= 0) vsum = fmaf(p, v_pool[svoff[j] + tid], vsum);
+    }
+    l = l * alpha + psum;
+    acc = acc * alpha + vsum;
+    __syncthreads();
+  }
+  m_out = m;
+  l_out = l;
+  acc_out = acc;
+}
+
+struct AttnF32Args {
+  const float* q;
+  const float* k_pool;
+  const float* v_pool;
+  const int32_t* page_table;
+  const int32_t* seq_len;
+  float* out;
+  float* ws;
+  Geo g;
+  int32_t n_splits;
+  int32_t n_q;   // prefill: queries per sequence
+  float scale_log2;
+};
+
+__device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
+  int64_t n = a.seq_len[b];
+  const int64_t cap = (int64_t)a.g.max_pages * a.g.page_tokens;
+  if (n > cap) n = cap;
+  if (n < 0) n = 0;
+  return (int)n;
+}
+
+__global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
+  const Geo& g = a.g;
+  const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int kvh = head / g.group;
+  const int n = clamp_len(a, b);
+  const int chunks = (n + kChunk - 1) / kChunk;
+  const int per = (chunks + a.n_splits - 1) / a.n_splits;
+  const int tok_begin = min(n, split * per * kChunk);
+  const int tok_end = min(n, (split + 1) * per * kChunk);
+  float m, l, acc;
+  attend_f32(a.q + ((int64_t)b * g.n_heads + head) * g.r_k, a.k_pool, a.v_pool,
+             a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m, l, acc);
+  const int c = threadIdx.x;
+  if (a.n_splits == 1) {
+    if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = l > 0.f ? acc / l : 0.f;
+  } else {
+    const int64_t BHS = (int64_t)gridDim.z * g.n_heads * a.n_splits;
+    const int64_t row = ((int64_t)b * g.n_heads + head) * a.n_splits + split;
+    if (c == 0) {
+      a.ws[row] = m;
+      a.ws[BHS + row] = l;
+    }
+    if (c < g.r_v_pad) a.ws[2 * BHS + row * g.r_v_pad + c] = c < g.r_v ? acc : 0.f;
+  }
+}
+
+// Causal prefill: one workgroup per (query, head, sequence); query j sits at position len - n_q + j.
+__global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
+  const Geo& g = a.g;
+  const int j = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int kvh = head / g.group;
+  const int n = clamp_len(a, b);
+  const int pos = n - a.n_q + j;
+  const int64_t row = (((int64_t)b * a.n_q + j) * g.n_heads + head);
+  float m, l, acc;
+  attend_f32(a.q + row * g.r_k, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
+             pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+  const int c = threadIdx.x;
+  if (c < g.r_v) a.out[row * g.r_v + c] = l > 0.f ? acc / l : 0.f;
+}
+
+static AttnF32Args make_args(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool,
+                             const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out,
+                             float* ws, int32_t n_splits, int32_t n_q) {
+  AttnF32Args a;
+  a.q = q;
+  a.k_pool = k_pool;
+  a.v_pool = v_pool;
+  a.page_table = page_table;
+  a.seq_len = seq_len;
+  a.out = out;
+  a.ws = ws;
+  a.g = g;
+  a.n_splits = n_splits;
+  a.n_q = n_q;
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
+  return a;
+}
+
+int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
+               const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
+               hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
+  decode_f32_kernel<<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int prefill_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
+                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
+  prefill_f32_kernel<<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+// ---- C[M,N] = A[M,K] . Bt[N,K]^T, 64x64 tiles, 4x4 outputs per thread --------
+template <typename Epilogue>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ Bt,
+                                                       int32_t M, int32_t N, int32_t K, Epilogue ep) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float As[BK][BM + 4];
+  __shared__ float Bs[BK][BN + 4];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tx = tid & 15, ty = tid >> 4;
+  const int lr = tid >> 2, lk = (tid & 3) * 4;
+  float c[4][4] = {};
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    float4 av = make_float4(0.f, 0.f, 0.f, 0.f), bv = av;
+    if (m0 + lr < M && k0 + lk < K) av = *reinterpret_cast<const float4*>(A + (int64_t)(m0 + lr) * K + k0 + lk);
+    if (n0 + lr < N && k0 + lk < K) bv = *reinterpret_cast<const float4*>(Bt + (int64_t)(n0 + lr) * K + k0 + lk);
+    As[lk + 0][lr] = av.x; As[lk + 1][lr] = av.y; As[lk + 2][lr] = av.z; As[lk + 3][lr] = av.w;
+    Bs[lk + 0][lr] = bv.x; Bs[lk + 1][lr] = bv.y; Bs[lk + 2][lr] = bv.z; Bs[lk + 3][lr] = bv.w;
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float a4[4], b4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a4[i] = As[kk][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b4[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[i][j] = fmaf(a4[i], b4[j], c[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = m0 + ty * 4 + i, cc = n0 + tx * 4 + j;
+      if (r < M && cc < N) ep(r, cc, c[i][j]);
+    }
+}
+
+struct QkvEpF32 {
+  QkvDest d;
+  __device__ void operator()(int r, int c, float v) const { qkv_store<false>(d, r, c, v); }
+};
+struct PlainEpF32 {
+  float* y;
+  int32_t N;
+  __device__ void operator()(int r, int c, float v) const { y[(int64_t)r * N + c] = v; }
+};
+
+int gemm_qkv_f32(const float* x, const float* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst,
+                 hipStream_t st) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  if (grid.y > 65535) return EA_ERR_SHAPE;
+  gemm_f32_kernel<<<grid, dim3(256), 0, st>>>(x, w_t, M, N, K, QkvEpF32{dst});
+  return launch_status();
+}
+
+int gemm_out_f32(const float* a, const float* w_t, float* y, int32_t M, int32_t N, int32_t K, hipStream_t st) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  if (grid.y > 65535) return EA_ERR_SHAPE;
+  gemm_f32_kernel<<<grid, dim3(256), 0, st>>>(a, w_t, M, N, K, PlainEpF32{y, N});
+  return launch_status();
+}
+
+}  // namespace ea

@@ -1,0 +1,139 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol,
+and its host-side layout / paging reference functions behave as documented."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2408_05646_amd as ea
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
+    return ea.LayerDesc(d, H, Hkv, d_h, r_k, r_v, dtype, P)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
+    declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 14
+    lib = ctypes.CDLL(ea.library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert ea.version() >= 100
+    assert ea.strerror(0) == "ok" and "aligned" in ea.strerror(-3)
+
+
+def test_layout_query_and_padding():
+    lay = ea.cache_layout_query(desc(r_k=80, r_v=40))
+    assert (lay.layout_id, lay.elem_bytes, lay.r_k_pad, lay.r_v_pad) == (1, 2, 80, 48)
+    assert lay.k_slab_elems == 128 * 80 and lay.k_page_elems == 2 * 128 * 80
+    assert lay.v_slab_elems == 128 * 48
+    lay = ea.cache_layout_query(desc(ea.EA_F32, r_k=30, r_v=33, P=16))
+    assert (lay.layout_id, lay.elem_bytes, lay.r_k_pad, lay.r_v_pad) == (0, 4, 32, 36)
+
+
+@pytest.mark.parametrize("dtype,P,r_k,r_v", [(ea.EA_BF16, 64, 80, 80), (ea.EA_BF16, 192, 48, 112),
+                                             (ea.EA_BF16, 128, 128, 16), (ea.EA_F32, 16, 32, 64)])
+def test_cache_index_is_a_bijection_per_slab(dtype, P, r_k, r_v):
+    d = desc(dtype, Hkv=2, r_k=r_k, r_v=r_v, P=P)
+    lay = ea.cache_layout_query(d)
+    for fn, r, slab, page_elems in ((ea.cache_k_index, r_k, lay.k_slab_elems, lay.k_page_elems),
+                                    (ea.cache_v_index, r_v, lay.v_slab_elems, lay.v_page_elems)):
+        for page, head in ((0, 0), (3, 1)):
+            idx = np.array([[fn(d, page, head, t, c) for c in range(r)] for t in range(P)])
+            base = page * page_elems + head * slab
+            assert idx.min() == base and idx.max() == base + slab - 1      # ranks here need no padding
+            assert np.unique(idx).size == P * r
+
+
+def k_index_from_description(t, c, r_pad):
+    """Written from the header's words: tiles of 64 tokens; [4 blocks of 16 tokens][r_pad/8 chunks][16 tokens][8 channels]."""
+    tile, tt = divmod(t, 64)
+    tb, row = divmod(tt, 16)
+    chunk, e = divmod(c, 8)
+    return tile * 64 * r_pad + ((tb * (r_pad // 8) + chunk) * 16 + row) * 8 + e
+
+
+def v_index_from_description(t, c, r_pad):
+    """[2 groups of 32 tokens][r_pad/16 blocks][4 quads][16 channels][8 slots]; slot j of quad q is token 16*(j/4)+4*q+j%4."""
+    tile, tt = divmod(t, 64)
+    grp, t32 = divmod(tt, 32)
+    cb, c16 = divmod(c, 16)
+    for quad in range(4):
+        for j in range(8):
+            if 16 * (j // 4) + 4 * quad + j % 4 == t32:
+                return tile * 64 * r_pad + ((((grp * (r_pad // 16) + cb) * 4 + quad) * 16 + c16) * 8 + j)
+    raise AssertionError
+
+
+def test_bf16_fragment_order_matches_its_description():
+    d = desc(ea.EA_BF16, Hkv=2, r_k=72, r_v=40, P=128)
+    lay = ea.cache_layout_query(d)
+    assert (lay.r_k_pad, lay.r_v_pad) == (72, 48)
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        page, head, t = int(rng.integers(0, 5)), int(rng.integers(0, 2)), int(rng.integers(0, 128))
+        ck, cv = int(rng.integers(0, 72)), int(rng.integers(0, 40))
+        assert ea.cache_k_index(d, page, head, t, ck) == page * lay.k_page_elems + head * lay.k_slab_elems + \
+            k_index_from_description(t, ck, 72)
+        assert ea.cache_v_index(d, page, head, t, cv) == page * lay.v_page_elems + head * lay.v_slab_elems + \
+            v_index_from_description(t, cv, 48)
+    # one wave-wide load of a K block is contiguous: 16 tokens x 8 channels of one chunk = 128 consecutive elements
+    base = ea.cache_k_index(d, 0, 0, 16, 8)
+    got = sorted(ea.cache_k_index(d, 0, 0, 16 + row, 8 + e) - base for row in range(16) for e in range(8))
+    assert got == list(range(128))
+    assert ea.cache_k_index(d, 0, 0, 0, 72) == -1 and ea.cache_k_index(d, 0, 2, 0, 0) == -1
+    assert ea.cache_v_index(d, 0, 0, 128, 0) == -1 and ea.cache_v_index(d, -1, 0, 0, 0) == -1
+
+
+def test_f32_rows_are_token_major():
+    d = desc(ea.EA_F32, Hkv=2, r_k=30, r_v=64, P=16)
+    assert ea.cache_k_index(d, 2, 1, 5, 7) == 2 * (2 * 16 * 32) + 1 * 16 * 32 + 5 * 32 + 7
+    assert ea.cache_v_index(d, 1, 0, 15, 63) == 1 * (2 * 16 * 64) + 15 * 64 + 63
+
+
+def test_cache_slot_paging_arithmetic():
+    d = desc(P=128)
+    row = np.array([7, 3, 11, 0], np.int32)
+    for pos in (0, 1, 127, 128, 129, 383, 384, 511):
+        assert ea.cache_slot(d, row, pos) == int(row[pos // 128]) * 128 + pos % 128
+    assert ea.cache_slot(d, row, 512) == -1 and ea.cache_slot(d, row, -1) == -1
+    assert ea.cache_slot(d, np.array([-1], np.int32), 0) == -1
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    lib = ea.load_library()
+    good = desc()
+    bad_group = desc(H=8, Hkv=3)
+    bad_rank = desc(r_k=136)
+    bad_page = desc(P=48)
+    out = ea.CacheLayout()
+    assert lib.ea_cache_layout_query(ctypes.byref(bad_group), ctypes.byref(out)) == -2
+    assert lib.ea_cache_layout_query(ctypes.byref(bad_rank), ctypes.byref(out)) == -2
+    assert lib.ea_cache_layout_query(ctypes.byref(bad_page), ctypes.byref(out)) == -2
+    assert lib.ea_cache_layout_query(None, ctypes.byref(out)) == -1
+    # null pointers / bad sizes: rejected on the host, nothing is launched
+    assert lib.ea_decode_attn(ctypes.byref(good), None, None, None, None, None, None, 1, 1, 1, 0, None, 0, None) == -1
+    assert lib.ea_project_qkv(ctypes.byref(good), None, None, None, 0, None, None, None, None, 1, 1, 1, 1, None) == -1
+    assert lib.ea_out_proj(ctypes.byref(good), None, 0, None, None, 4, None) == -1
+    assert lib.ea_prefill_attn(ctypes.byref(good), None, None, None, None, None, None, 1, 1, 1, 1, None) == -1
+    # misaligned pointer (fake, never dereferenced: the check comes first)
+    p = 0x1000
+    assert lib.ea_decode_attn(ctypes.byref(good), p + 4, p, p, p, p, p, 1, 1, 1, 1, None, 0, None) == -3
+    # splits > 1 without a workspace
+    assert lib.ea_decode_attn(ctypes.byref(good), p, p, p, p, p, p, 1, 1, 1, 4, None, 0, None) == -4
+    assert ea.decode_workspace_bytes(good, 2, 4) == 2 * 8 * 4 * (2 + 48) * 4
+    assert ea.decode_workspace_bytes(good, 2, 1) == 0
+    assert 1 <= ea.decode_auto_splits(good, 16, 32768) <= 64
+
+
+def test_auto_splits_fill_the_chip():
+    d = ea.LayerDesc(4096, 32, 32, 128, 80, 80, ea.EA_BF16, 64)
+    assert ea.decode_auto_splits(d, 16, 32768) == 4          # 512 streams x 4 = 2048 workgroups
+    assert ea.decode_auto_splits(d, 16, 64) == 1
+    g = ea.LayerDesc(4096, 32, 8, 128, 80, 80, ea.EA_BF16, 64)
+    assert ea.decode_auto_splits(g, 8, 16384) == 32           # 64 streams, 256 tiles each
