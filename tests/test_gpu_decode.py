@@ -113,7 +113,10 @@ def test_split_count_does_not_change_the_result():
     outs = [run_decode(desc, K, V, q, synth.rng(5, 1), s) for s in (1, 2, 7, 16)]
     for o in outs:
         assert_close(o, ref, TOL_BF16, "split sweep")
-        assert np.abs(o - outs[0]).max() <= 1e-5 * np.abs(outs[0]).max()
+        # P is rounded to bf16 relative to a running max that depends on the split, so results
+        # agree to bf16-rounding level, not to fp32 bits
+        dev = float(np.abs(o - outs[0]).max() / np.abs(outs[0]).max())
+        assert dev <= 5e-3, dev
 
 
 def test_out_of_range_pages_are_masked_not_read():
