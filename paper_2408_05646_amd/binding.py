@@ -64,6 +64,9 @@ def load_library():
     if not os.path.exists(path):
         raise RuntimeError(f"{path} not found: build it with `python -m paper_2408_05646_amd.build` "
                            "(there is no fallback path)")
+    # PyTorch ships its own copy of the HIP runtime.  It must be in the process first, so that this
+    # library binds to the SAME runtime that owns the tensors and streams handed to it.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     P, I32, I64, VP = ctypes.POINTER, ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
     D = P(LayerDesc)

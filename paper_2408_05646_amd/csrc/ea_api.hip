@@ -71,6 +71,7 @@ int ea_cache_scatter(const ea_layer_desc* desc, const void* dev_k_dense, const v
   if ((dev_k_dense && !dev_k_pool) || (dev_v_dense && !dev_v_pool)) return EA_ERR_ARG;
   if (n == 0) return EA_OK;
   Geo g = make_geo(desc, max_pages, pool_pages);
+  clear_stale_error();
   return cache_copy(desc, g, true, const_cast<void*>(dev_k_dense), const_cast<void*>(dev_v_dense), dev_k_pool,
                     dev_v_pool, dev_page_table, B, n, pos0, (hipStream_t)stream);
 }
@@ -84,6 +85,7 @@ int ea_cache_gather(const ea_layer_desc* desc, void* dev_k_dense, void* dev_v_de
   if ((dev_k_dense && !dev_k_pool) || (dev_v_dense && !dev_v_pool)) return EA_ERR_ARG;
   if (n == 0) return EA_OK;
   Geo g = make_geo(desc, max_pages, pool_pages);
+  clear_stale_error();
   return cache_copy(desc, g, false, dev_k_dense, dev_v_dense, const_cast<void*>(dev_k_pool),
                     const_cast<void*>(dev_v_pool), dev_page_table, B, n, pos0, (hipStream_t)stream);
 }
@@ -103,6 +105,7 @@ int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev
       !aligned16(dev_v_pool))
     return EA_ERR_ALIGN;
   if (desc->d_model % (desc->dtype == EA_BF16 ? 32 : 4) != 0) return EA_ERR_SHAPE;
+  clear_stale_error();
   QkvDest dst;
   dst.q = dev_q_r;
   dst.q_is_f32 = q_dtype == EA_F32;
@@ -160,6 +163,7 @@ int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* d
   }
   Geo g = make_geo(desc, max_pages, pool_pages);
   hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
   if (desc->dtype == EA_BF16)
     rc = decode_bf16(desc, g, (const float*)dev_q_r, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, dev_out, B,
                      n_splits, (float*)dev_ws, st);
@@ -181,6 +185,7 @@ int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* 
   if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
     return EA_ERR_ALIGN;
   Geo g = make_geo(desc, max_pages, pool_pages);
+  clear_stale_error();
   if (desc->dtype == EA_BF16)
     return prefill_bf16(desc, g, dev_q_r, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, dev_out, B, n,
                         (hipStream_t)stream);
@@ -198,6 +203,7 @@ int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, c
   if (!aligned16(dev_o) || !aligned16(dev_wo_t) || !aligned16(dev_y)) return EA_ERR_ALIGN;
   const int32_t K = desc->n_heads * desc->r_v;
   if (K % (desc->dtype == EA_BF16 ? 32 : 4) != 0) return EA_ERR_SHAPE;
+  clear_stale_error();
   if (desc->dtype == EA_BF16)
     return gemm_out_bf16(dev_o, o_dtype == EA_F32, dev_wo_t, dev_y, M, desc->d_model, K, (hipStream_t)stream);
   return gemm_out_f32((const float*)dev_o, (const float*)dev_wo_t, (float*)dev_y, M, desc->d_model, K,

@@ -99,6 +99,10 @@ __device__ __forceinline__ bf16x8 zero_frag() {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// The HIP runtime keeps the last error of ANY earlier call of the process (another library's
+// event query that was not ready, for instance); drop it so launch_status() reports our launches only.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? EA_OK : EA_ERR_DEVICE; }
 
 // ---- entry points implemented per translation unit --------------------------
