@@ -37,6 +37,9 @@ def parse_args():
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
     ap.add_argument("--no-fullrank", action="store_true", help="skip the d_h = 128 full-rank comparison")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 4 GiB device copy, so that a rocprofv3 --pmc run of this command has a "
+                         "kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--cpu-streams", type=int, default=512, help="(sequence, head) streams the oracle is timed on")
     return ap.parse_args()
 
@@ -238,6 +241,14 @@ def main():
             "ratio_predicted_by_rank": round(r_k / s.d_head, 4),
             "note": "same kernel, r_k = r_v = d_h = 128, same B, n and page table, one 8.6 GB layer buffer"}
         del fk, fv
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.float32, device=dev).normal_(generator=gen)     # 4 GiB
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_baseline(args.cpu_streams, n, r_k, s.d_head)

@@ -27,8 +27,13 @@ struct DecodeArgs {
   float scale_log2;   // log2(e) / sqrt(d_head)
 };
 
-template <int KS, int NCB>
+// TBN = 16-token blocks handled per loop iteration: 4 (a whole 64-token tile) or 2 (half a tile, for the
+// large ranks whose fragments would not fit the register file otherwise).
+template <int KS, int NCB, int TBN>
 __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
+  constexpr int UN = TBN / 2;            // 32-token groups per iteration
+  constexpr int SUB = 4 / TBN;           // iterations per 64-token tile
+  constexpr int TOK = TBN * 16;          // tokens per iteration
   const Geo& g = a.g;
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -73,52 +78,56 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
   f32x4 lacc = {0.f, 0.f, 0.f, 0.f};
   float m = -INFINITY;
 
-  bf16x8 kf[4][KS], vf[2][NCB];
+  bf16x8 kf[TBN][KS], vf[UN][NCB];
 
   // Physical page of tile t, or -1.
-  auto tile_page = [&](int t) -> int {
-    const int lp = t / tiles_per_page;
+  auto tile_page = [&](int it) -> int {
+    const int lp = (it / SUB) / tiles_per_page;
     const int page = a.page_table[(int64_t)b * g.max_pages + lp];
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
-  auto load_k = [&](int t, int page) {
+  auto load_k = [&](int it, int page) {
     const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
-                           (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad);
+                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_k_pad) +
+                           (it % SUB) * (TOK * g.r_k_pad);
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
+    for (int tb = 0; tb < TBN; ++tb) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int chunk = ks * 4 + quad;
         if (chunk < nck)
-          kf[tb][ks] = *reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3));
+          kf[tb][ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3)));
         else
           kf[tb][ks] = zero_frag();
       }
     }
   };
-  auto load_v = [&](int t, int page) {
+  auto load_v = [&](int it, int page) {
     const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
-                           (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad);
+                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_v_pad) +
+                           (it % SUB) * (TOK * g.r_v_pad);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < UN; ++u) {
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb)
-        vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
+        vf[u][cb] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3)));
     }
   };
   auto zero_kv = [&]() {
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
+    for (int tb = 0; tb < TBN; ++tb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) kf[tb][ks] = zero_frag();
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < UN; ++u)
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) vf[u][cb] = zero_frag();
   };
 
-  int t = t_begin + wave;
-  bool have = t < t_end;
+  // the four waves interleave the iterations of the split (neighbouring waves read neighbouring memory)
+  const int it_end = t_end * SUB;
+  int t = t_begin * SUB + wave;
+  bool have = t < it_end;
   int page = -1;
   if (have) {
     page = tile_page(t);
@@ -132,9 +141,9 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
 
   while (have) {
     // ---- scores: S[tb] (16 tokens x 16 head columns) = K_block . q^T
-    f32x4 s[4];
+    f32x4 s[TBN];
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
+    for (int tb = 0; tb < TBN; ++tb) {
       s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -142,20 +151,20 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
         s[tb] = mfma16(kf[tb][ks], qlo[ks], s[tb]);
       }
     }
-    const int rem = page >= 0 ? n - t * kTile : 0;   // valid tokens in this tile (>= 64: all)
+    const int rem = page >= 0 ? n - t * TOK : 0;   // valid tokens in this iteration (>= TOK: all)
     const int tn = t + 4;
-    const bool have_n = tn < t_end;
+    const bool have_n = tn < it_end;
     const int page_n = have_n ? tile_page(tn) : -1;
     if (have_n && page_n >= 0) load_k(tn, page_n);   // K registers are free again: prefetch the next tile
 
     // ---- online softmax on s (lane: head column `col`, tokens tb*16 + 4*quad + i)
     float mx = -INFINITY;
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) {
+    for (int tb = 0; tb < TBN; ++tb) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float v = s[tb][i] * a.scale_log2;
-        if (rem < kTile && tb * 16 + quad * 4 + i >= rem) v = -INFINITY;
+        if (rem < TOK && tb * 16 + quad * 4 + i >= rem) v = -INFINITY;
         s[tb][i] = v;
         mx = fmaxf(mx, v);
       }
@@ -166,19 +175,19 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m - m_use);   // m = -inf -> 0
     m = m_new;
-    bf16x8 pf[2];
+    bf16x8 pf[UN];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < UN; ++u) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i] - m_use);
       }
     }
-    if (rem < kTile) {
+    if (rem < TOK) {
       // Partial tile: cache slots past the sequence end hold arbitrary bits; clear them so 0 * x stays 0.
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < UN; ++u) {
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
@@ -191,13 +200,13 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
     }
     // ---- O^T += V^T . P^T, row sums of P through the all-ones operand
     lacc *= alpha;
-    lacc = mfma16(ones, pf[0], lacc);
-    lacc = mfma16(ones, pf[1], lacc);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) lacc = mfma16(ones, pf[u], lacc);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       acc[cb] *= alpha;
-      acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
-      acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
+#pragma unroll
+      for (int u = 0; u < UN; ++u) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
     }
     if (have_n) {
       if (page_n >= 0) load_v(tn, page_n);
@@ -283,7 +292,8 @@ int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n
 template <int KS, int NCB>
 static void launch_decode(const DecodeArgs& a, int32_t B, hipStream_t st) {
   dim3 grid(a.n_splits, a.g.n_kv_heads, B), block(256);
-  decode_bf16_kernel<KS, NCB><<<grid, block, 0, st>>>(a);
+  constexpr int TBN = (KS * 4 + NCB * 2 > 22) ? 2 : 4;   // fragments of a whole tile: 16*KS + 8*NCB registers
+  decode_bf16_kernel<KS, NCB, TBN><<<grid, block, 0, st>>>(a);
 }
 
 template <int KS>
