@@ -9,6 +9,7 @@
 //    HBM (the weights are read exactly once; x stays in L2).
 #include "ea_common.h"
 #include "ea_epilogue.h"
+#include <type_traits>
 
 namespace ea {
 
@@ -25,7 +26,9 @@ __device__ __forceinline__ bf16x8 load_frag(const void* base, int64_t elem_off) 
 }
 
 // ---------------------------------------------------------------------------
-// Tiled kernel
+// Tiled kernel.  A wave owns a 64x64 output tile as 4x4 MFMA blocks.  With SWAP the operands
+// are exchanged (D^T = W_blk . A_blk^T), so a lane holds 4 CONSECUTIVE OUTPUT CHANNELS of one
+// row (an 8-byte bf16 store) instead of one channel of 4 rows; the epilogue picks per wave.
 // ---------------------------------------------------------------------------
 template <typename Epilogue, bool A_F32>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __restrict__ A,
@@ -38,6 +41,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
   const int col = lane & 15, quad = lane >> 4;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int r0 = m0 + wm * 64, c0 = n0 + wn * 64;
+  const bool swap = ep.swap_for(c0);          // wave-uniform
 
   f32x4 acc[4][4];
 #pragma unroll
@@ -46,7 +51,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   bf16x8 ga[4], gb[4];
-  auto gload = [&](int k0) {
+  auto gload = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
@@ -55,40 +60,38 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
       gb[i] = (kin && n0 + row < N) ? load_frag<false>(Wt, (int64_t)(n0 + row) * K + k0 + kc) : zero_frag();
     }
   };
-  gload(0);
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
-      *reinterpret_cast<bf16x8*>(&As[row * LDK + kc]) = ga[i];
-      *reinterpret_cast<bf16x8*>(&Bs[row * LDK + kc]) = gb[i];
-    }
-    __syncthreads();
-    if (k0 + BK < K) gload(k0 + BK);
-#pragma unroll
-    for (int ks = 0; ks < BK / 32; ++ks) {
-      bf16x8 af[4], bfr[4];
+  auto mainloop = [&](auto swap_tag) __attribute__((always_inline)) {
+    constexpr bool SWAP = decltype(swap_tag)::value;
+    gload(0);
+    for (int k0 = 0; k0 < K; k0 += BK) {
+      __syncthreads();
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
-        bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+        const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
+        *reinterpret_cast<bf16x8*>(&As[row * LDK + kc]) = ga[i];
+        *reinterpret_cast<bf16x8*>(&Bs[row * LDK + kc]) = gb[i];
       }
+      __syncthreads();
+      if (k0 + BK < K) gload(k0 + BK);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int ks = 0; ks < BK / 32; ++ks) {
+        bf16x8 af[4], bfr[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(af[i], bfr[j], acc[i][j]);
+        for (int i = 0; i < 4; ++i) {
+          af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            acc[i][j] = SWAP ? mfma16(bfr[j], af[i], acc[i][j]) : mfma16(af[i], bfr[j], acc[i][j]);
+      }
     }
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int r = m0 + wm * 64 + i * 16 + quad * 4 + e, c = n0 + wn * 64 + j * 16 + col;
-        if (r < M && c < N) ep(r, c, acc[i][j][e]);
-      }
+  };
+  if (swap) mainloop(std::true_type{});
+  else mainloop(std::false_type{});
+  ep.store(swap, r0, c0, acc, M, N, col, quad);
 }
 
 // ---------------------------------------------------------------------------
@@ -161,14 +164,151 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __res
   }
 }
 
+__device__ __forceinline__ u32x2 pack4_bf16(f32x4 v) {
+  u32x2 w;
+  w[0] = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+  w[1] = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+  return w;
+}
+
+// Element (row, column) of accumulator register e of block (i, j) of a wave tile at (r0, c0).
+//   not swapped: lane = column, registers = 4 rows;   swapped: lane = row, registers = 4 columns.
+__device__ __forceinline__ void acc_coord(bool swap, int r0, int c0, int i, int j, int e, int col, int quad, int& r,
+                                          int& c) {
+  r = swap ? r0 + i * 16 + col : r0 + i * 16 + quad * 4 + e;
+  c = swap ? c0 + j * 16 + quad * 4 + e : c0 + j * 16 + col;
+}
+
+// Fused QKV destination.  When every section (q | k | v) is a multiple of 64 columns and the ranks are
+// multiples of 16, a wave tile lies in one section and 16-row blocks that start on a 16-token boundary
+// of the cache are stored as whole fragments of the cache layout:
+//   q, k (swapped): a lane holds 4 consecutive channels of one token -> one 8-byte store;
+//   v (not swapped): a lane holds one channel of 4 consecutive tokens = 4 consecutive slots of the V layout.
+// Everything else falls back to element-wise stores.
 struct QkvEpBf16 {
   QkvDest d;
-  __device__ void operator()(int r, int c, float v) const { qkv_store<true>(d, r, c, v); }
+  int32_t fast_cols;
+  __device__ __forceinline__ void operator()(int r, int c, float v) const { qkv_store<true>(d, r, c, v); }
+  __device__ __forceinline__ bool swap_for(int c0) const {
+    const Geo& g = d.g;
+    return fast_cols && c0 < g.n_heads * g.r_k + g.n_kv_heads * g.r_k;
+  }
+  // I is a compile-time index: the accumulators must stay in registers (no dynamic indexing).
+  template <int I>
+  __device__ __forceinline__ void store_slow(bool swap, int r0, int c0, const f32x4 (&acc)[4][4], int M, int N,
+                                             int col, int quad) const {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int r, c;
+        acc_coord(swap, r0, c0, I, j, e, col, quad, r, c);
+        if (r < M && c < N) qkv_store<true>(d, r, c, acc[I][j][e]);
+      }
+  }
+  template <int I>
+  __device__ __forceinline__ void store_block(bool swap, bool is_k, int sec0, int r, int r0, int c0,
+                                              const f32x4 (&acc)[4][4], int M, int N, int col, int quad) const {
+    const Geo& g = d.g;
+    const int row0 = r0 + I * 16;                  // wave-uniform
+    bool fast = row0 + 16 <= M && d.T % 16 == 0;
+    int page = -1, tp0 = 0;
+    if (fast) {
+      const int b = row0 / d.T;
+      const int64_t pos0 = (int64_t)d.seq_len[b] + row0 % d.T;
+      const int64_t lp = pos0 / g.page_tokens;
+      fast = pos0 >= 0 && (pos0 & 15) == 0 && lp < g.max_pages;
+      if (fast) {
+        page = d.page_table[(int64_t)b * g.max_pages + lp];
+        tp0 = (int)(pos0 % g.page_tokens);
+        fast = page >= 0 && page < g.pool_pages;
+      }
+    }
+    if (!fast) {
+      store_slow<I>(swap, r0, c0, acc, M, N, col, quad);
+      return;
+    }
+    const int tile = tp0 >> 6, tb = (tp0 & 63) >> 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int cc0 = sec0 + j * 16;               // first channel of this 16-column block, wave-uniform
+      const int kvh = cc0 / r, ch0 = cc0 % r;      // ch0 is a multiple of 16
+      if (is_k) {
+        const int ch = ch0 + quad * 4;             // this lane: channels ch .. ch+3 of token tp0 + col
+        uint16_t* dst = reinterpret_cast<uint16_t*>(d.k_pool) + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
+                        (int64_t)tile * (kTile * g.r_k_pad) +
+                        ((((tb * (g.r_k_pad >> 3) + (ch >> 3)) * 16 + col) << 3) + (ch & 7));
+        *reinterpret_cast<u32x2*>(dst) = pack4_bf16(acc[I][j]);
+      } else {
+        const int grp = tb >> 1, half = tb & 1;    // this lane: channel ch0 + col, tokens tp0 + 4*quad .. +3
+        uint16_t* dst = reinterpret_cast<uint16_t*>(d.v_pool) + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
+                        (int64_t)tile * (kTile * g.r_v_pad) +
+                        ((((((grp * (g.r_v_pad >> 4) + (ch0 >> 4)) * 4 + quad) * 16 + col) << 3) + half * 4));
+        *reinterpret_cast<u32x2*>(dst) = pack4_bf16(acc[I][j]);
+      }
+    }
+  }
+  __device__ __forceinline__ void store(bool swap, int r0, int c0, const f32x4 (&acc)[4][4], int M, int N, int col,
+                                        int quad) const {
+    const Geo& g = d.g;
+    const int nq = g.n_heads * g.r_k, nk = g.n_kv_heads * g.r_k;
+    if (!fast_cols || c0 + 64 > N) {
+      store_slow<0>(swap, r0, c0, acc, M, N, col, quad);
+      store_slow<1>(swap, r0, c0, acc, M, N, col, quad);
+      store_slow<2>(swap, r0, c0, acc, M, N, col, quad);
+      store_slow<3>(swap, r0, c0, acc, M, N, col, quad);
+      return;
+    }
+    if (c0 < nq) {                                   // ---- q section: dense [M, nq]
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = r0 + i * 16 + col;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t idx = (int64_t)r * nq + c0 + j * 16 + quad * 4;
+          if (r < M) {
+            if (d.q_is_f32) *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(d.q) + idx) = acc[i][j];
+            else *reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(d.q) + idx) = pack4_bf16(acc[i][j]);
+          }
+        }
+      }
+      return;
+    }
+    const bool is_k = c0 < nq + nk;
+    const int sec0 = is_k ? c0 - nq : c0 - nq - nk;  // first column of the wave tile inside its section
+    const int r = is_k ? g.r_k : g.r_v;
+    store_block<0>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
+    store_block<1>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
+    store_block<2>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
+    store_block<3>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
+  }
 };
+
 struct PlainEpBf16 {
   uint16_t* y;
   int32_t N;
   __device__ void operator()(int r, int c, float v) const { y[(int64_t)r * N + c] = f32_to_bf16_rne(v); }
+  __device__ __forceinline__ bool swap_for(int) const { return true; }
+  __device__ __forceinline__ void store(bool, int r0, int c0, const f32x4 (&acc)[4][4], int M, int Ncols, int col,
+                                        int quad) const {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = r0 + i * 16 + col;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int c = c0 + j * 16 + quad * 4;
+        uint16_t* dst = y + (int64_t)r * Ncols + c;
+        if (r >= M) {
+        } else if (c + 3 < Ncols && (Ncols & 3) == 0) {
+          *reinterpret_cast<u32x2*>(dst) = pack4_bf16(acc[i][j]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (c + e < Ncols) dst[e] = f32_to_bf16_rne(acc[i][j][e]);
+        }
+      }
+    }
+  }
 };
 
 template <typename Epilogue, bool A_F32>
@@ -194,7 +334,10 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
 
 int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst,
                   hipStream_t st) {
-  return launch_gemm<QkvEpBf16, false>(x, w_t, M, N, K, QkvEpBf16{dst}, st);
+  const Geo& g = dst.g;
+  const int nq = g.n_heads * g.r_k, nk = g.n_kv_heads * g.r_k, nv = g.n_kv_heads * g.r_v;
+  const int32_t fast_cols = nq % 64 == 0 && nk % 64 == 0 && nv % 64 == 0 && g.r_k % 16 == 0 && g.r_v % 16 == 0;
+  return launch_gemm<QkvEpBf16, false>(x, w_t, M, N, K, QkvEpBf16{dst, fast_cols}, st);
 }
 
 int gemm_out_bf16(const void* a, int32_t a_is_f32, const void* w_t, void* y, int32_t M, int32_t N, int32_t K,
