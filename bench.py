@@ -138,8 +138,8 @@ def main():
         perm = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32)   # pages in seeded random order
         layers.append(dict(
             k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
-            wqkv_t=(torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16),
-            wo_t=(torch.randn((d, H * r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16),
+            wqkv_t=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
+            wo_t=ea.pack_weight((torch.randn((d, H * r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),
             y=torch.empty((B, d), dtype=torch.bfloat16, device=dev)))
     torch.cuda.synchronize()

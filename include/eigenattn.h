@@ -114,21 +114,34 @@ EA_API int ea_cache_gather(const ea_layer_desc* desc, void* dev_k_dense, void* d
                     const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
                     int32_t B, int32_t n, int32_t pos0, int32_t max_pages, int32_t pool_pages, void* stream);
 
+/* ---- weight packing (device, done once, offline like the folding of Eq. 8) - */
+
+/* The projection calls read their folded weights in a packed order.  The source is
+ * "out-major": dev_w_t [N, K], one row of K input weights per output channel.
+ *   EA_F32 : packed = the same [N, K] array (a plain copy).
+ *   EA_BF16: matrix-core fragment order [ceil(N/16)][K/32][4 quads][16 channels][8 k]:
+ *            element (n, k) sits at ((n/16 * K/32 + k/32) * 4 + (k%32)/8) * 128 + (n%16)*8 + k%8;
+ *            rows N..ceil16(N)-1 are zero.  Requires K % 32 == 0.
+ * ea_packed_weight_elems gives the element count of the packed buffer (-1 on bad arguments). */
+EA_API int64_t ea_packed_weight_elems(int32_t N, int32_t K, int32_t dtype);
+EA_API int ea_pack_weight(const void* dev_w_t, void* dev_packed, int32_t N, int32_t K, int32_t dtype, void* stream);
+
 /* ---- the hot path -------------------------------------------------------- */
 
 /* Fused low-rank QKV projection and cache append: Eq. (1) with the folded
  * weights of Eq. (8), then K <- Concat(K, k), V <- Concat(V, v) (Sec. 2, LLM
  * inference).
  *   dev_x      [B*T, d]  (row b*T + t is token t of sequence b), desc dtype
- *   dev_wqkv_t [H*r_k + H_kv*r_k + H_kv*r_v, d]: one row of d weights per
- *              output channel ("out-major"), ordered q heads, k heads, v heads;
- *              row (i*r_k + c) is column c of W^Q_i U^K_{g(i)}, and so on.
+ *   dev_wqkv   packed by ea_pack_weight from [H*r_k + H_kv*r_k + H_kv*r_v, d]:
+ *              one row of d weights per output channel ("out-major"), ordered
+ *              q heads, k heads, v heads; row (i*r_k + c) is column c of
+ *              W^Q_i U^K_{g(i)}, and so on.
  *   dev_q_r    [B*T, H, r_k] out, float (q_dtype EA_F32) or bfloat16 (EA_BF16)
  *   dev_seq_len[B]: length of each sequence BEFORE this call; token t is
  *              appended at position seq_len[b] + t.  Not modified.
  *   dev_page_table [B, max_pages] int32 physical page ids (< pool_pages).
  * Requires d % 32 == 0 for EA_BF16 (d % 4 == 0 for EA_F32). */
-EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t,
+EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
                    void* dev_q_r, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
                    const int32_t* dev_page_table, const int32_t* dev_seq_len,
                    int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
@@ -165,10 +178,11 @@ EA_API int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T
- *   dev_wo_t [d, H*r_v] out-major: row a holds column a of the stacked W^O'
+ *   dev_wo   packed by ea_pack_weight from [d, H*r_v] out-major: row a holds
+ *            column a of the stacked W^O'
  *   dev_y    [M, d] desc dtype.
  * Requires (H*r_v) % 32 == 0 for EA_BF16 (% 4 for EA_F32). */
-EA_API int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, const void* dev_wo_t,
+EA_API int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, const void* dev_wo,
                 void* dev_y, int32_t M, void* stream);
 
 #ifdef __cplusplus

@@ -15,7 +15,7 @@ import numpy as np
 __all__ = [
     "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
-    "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
+    "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS",
 ]
 
@@ -23,7 +23,7 @@ EA_F32, EA_BF16 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
-    "ea_cache_scatter", "ea_cache_gather", "ea_project_qkv", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
+    "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
     "ea_decode_attn", "ea_prefill_attn", "ea_out_proj",
 )
 
@@ -81,6 +81,9 @@ def load_library():
     lib.ea_cache_slot.argtypes = [D, P(I32), I32, I32]
     lib.ea_cache_scatter.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.ea_cache_gather.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    lib.ea_packed_weight_elems.restype = I64
+    lib.ea_packed_weight_elems.argtypes = [I32, I32, I32]
+    lib.ea_pack_weight.argtypes = [VP, VP, I32, I32, I32, VP]
     lib.ea_project_qkv.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_auto_splits.restype = I32
     lib.ea_decode_auto_splits.argtypes = [D, I32, I32]
@@ -201,20 +204,38 @@ def cache_gather(desc, k_dense, v_dense, k_pool, v_pool, page_table, pos0: int =
     _check(rc, "ea_cache_gather")
 
 
-def project_qkv(desc, x, wqkv_t, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
-    """x [B*T, d]; wqkv_t [N_qkv, d]; q_r [B*T, H, r_k] (float32 or bfloat16) is written, k/v go to the pools."""
+def packed_weight_elems(N: int, K: int, dtype: int) -> int:
+    return int(load_library().ea_packed_weight_elems(N, K, dtype))
+
+
+def pack_weight(w_t, stream=None):
+    """Out-major weights w_t [N, K] (float32 or bfloat16, on the GPU) -> the packed order the projection calls read."""
+    import torch
+    N, K = w_t.shape
+    dt = _dt(w_t)
+    n = packed_weight_elems(N, K, dt)
+    if n < 0:
+        raise ValueError("weights cannot be packed (bfloat16 needs K % 32 == 0)")
+    packed = torch.empty((n,), dtype=w_t.dtype, device=w_t.device)
+    _check(load_library().ea_pack_weight(_ptr(w_t), _ptr(packed), N, K, dt, _stream(stream)), "ea_pack_weight")
+    return packed
+
+
+def project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+    """x [B*T, d]; wqkv = pack_weight([N_qkv, d]); q_r [B*T, H, r_k] (float32 or bfloat16) is written,
+    k and v go to the pools."""
     B = seq_len.shape[0]
     if x.shape[0] != B * T:
         raise ValueError("x must have B*T rows")
-    _expect(x, desc.dtype, "x"); _expect(wqkv_t, desc.dtype, "wqkv_t")
+    _expect(x, desc.dtype, "x"); _expect(wqkv, desc.dtype, "wqkv")
     _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
     _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
     n_out = desc.n_heads * desc.r_k + desc.n_kv_heads * (desc.r_k + desc.r_v)
-    if tuple(wqkv_t.shape) != (n_out, desc.d_model) or x.shape[1] != desc.d_model:
-        raise ValueError("weight / activation shape does not match the layer")
+    if wqkv.numel() != packed_weight_elems(n_out, desc.d_model, desc.dtype) or x.shape[1] != desc.d_model:
+        raise ValueError("packed weight / activation size does not match the layer")
     if q_r.numel() != B * T * desc.n_heads * desc.r_k:
         raise ValueError("q_r has the wrong size")
-    rc = load_library().ea_project_qkv(ctypes.byref(desc), _ptr(x), _ptr(wqkv_t), _ptr(q_r), _dt(q_r), _ptr(k_pool),
+    rc = load_library().ea_project_qkv(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(q_r), _dt(q_r), _ptr(k_pool),
                                        _ptr(v_pool), _ptr(page_table), _ptr(seq_len), B, T, page_table.shape[1],
                                        k_pool.shape[0], _stream(stream))
     _check(rc, "ea_project_qkv")
@@ -259,11 +280,12 @@ def prefill_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, stream=Non
     _check(rc, "ea_prefill_attn")
 
 
-def out_proj(desc, o, wo_t, y, stream=None) -> None:
-    """o [M, H*r_v] (float32 or bfloat16) x wo_t [d, H*r_v] -> y [M, d] (layer dtype)."""
+def out_proj(desc, o, wo, y, stream=None) -> None:
+    """o [M, H*r_v] (float32 or bfloat16) x wo = pack_weight([d, H*r_v]) -> y [M, d] (layer dtype)."""
     M = y.shape[0]
-    _expect(wo_t, desc.dtype, "wo_t"); _expect(y, desc.dtype, "y")
-    if tuple(wo_t.shape) != (desc.d_model, desc.n_heads * desc.r_v) or o.numel() != M * desc.n_heads * desc.r_v:
-        raise ValueError("o / wo_t shape does not match the layer")
-    rc = load_library().ea_out_proj(ctypes.byref(desc), _ptr(o), _dt(o), _ptr(wo_t), _ptr(y), M, _stream(stream))
+    _expect(wo, desc.dtype, "wo"); _expect(y, desc.dtype, "y")
+    if (wo.numel() != packed_weight_elems(desc.d_model, desc.n_heads * desc.r_v, desc.dtype)
+            or o.numel() != M * desc.n_heads * desc.r_v):
+        raise ValueError("o / packed wo size does not match the layer")
+    rc = load_library().ea_out_proj(ctypes.byref(desc), _ptr(o), _dt(o), _ptr(wo), _ptr(y), M, _stream(stream))
     _check(rc, "ea_out_proj")

@@ -90,6 +90,20 @@ int ea_cache_gather(const ea_layer_desc* desc, void* dev_k_dense, void* dev_v_de
                     const_cast<void*>(dev_v_pool), dev_page_table, B, n, pos0, (hipStream_t)stream);
 }
 
+int64_t ea_packed_weight_elems(int32_t N, int32_t K, int32_t dtype) {
+  if (N <= 0 || K <= 0 || (dtype != EA_F32 && dtype != EA_BF16)) return -1;
+  if (dtype == EA_F32) return (int64_t)N * K;
+  if (K % 32 != 0) return -1;
+  return (int64_t)round_up(N, 16) * K;
+}
+
+int ea_pack_weight(const void* dev_w_t, void* dev_packed, int32_t N, int32_t K, int32_t dtype, void* stream) {
+  if (!dev_w_t || !dev_packed || ea_packed_weight_elems(N, K, dtype) < 0) return EA_ERR_ARG;
+  if (!aligned16(dev_w_t) || !aligned16(dev_packed)) return EA_ERR_ALIGN;
+  clear_stale_error();
+  return pack_weight(dev_w_t, dev_packed, N, K, dtype == EA_BF16, (hipStream_t)stream);
+}
+
 int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t, void* dev_q_r, int32_t q_dtype,
                    void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
                    int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream) {

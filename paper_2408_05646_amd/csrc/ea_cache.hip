@@ -67,4 +67,41 @@ int cache_copy(const ea_layer_desc* d, const Geo& g, bool scatter, void* k_dense
   return launch_status();
 }
 
+// ---- weights: out-major [N, K] -> matrix-core fragment order [N/16][K/32][4][16][8] (bf16), copy (fp32)
+__global__ void pack_weight_bf16_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int32_t N,
+                                        int32_t K) {
+  const int64_t total = (int64_t)round_up(N, 16) * K / 8;           // 16-byte units
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < total; u += (int64_t)gridDim.x * blockDim.x) {
+    const int row16 = (int)(u & 15), quad = (int)((u >> 4) & 3);
+    const int64_t frag = u >> 6;
+    const int steps = K / 32;
+    const int64_t nblk = frag / steps;
+    const int step = (int)(frag % steps);
+    const int64_t n = nblk * 16 + row16;
+    const int k = step * 32 + quad * 8;
+    reinterpret_cast<u32x4*>(dst)[u] = n < N ? *reinterpret_cast<const u32x4*>(src + n * K + k) : zero;
+  }
+}
+
+__global__ void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+int pack_weight(const void* w_t, void* packed, int32_t N, int32_t K, bool bf16, hipStream_t st) {
+  if (bf16) {
+    const int64_t units = (int64_t)round_up(N, 16) * K / 8;
+    int64_t blocks = (units + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    pack_weight_bf16_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, st>>>((const uint16_t*)w_t, (uint16_t*)packed, N, K);
+  } else {
+    const int64_t n = (int64_t)N * K;
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    copy_f32_kernel<<<dim3((uint32_t)blocks), dim3(256), 0, st>>>((const float*)w_t, (float*)packed, n);
+  }
+  return launch_status();
+}
+
 }  // namespace ea

@@ -133,6 +133,7 @@ struct QkvDest {
   int32_t T;
   Geo g;
 };
+int pack_weight(const void* w_t, void* packed, int32_t N, int32_t K, bool bf16, hipStream_t st);
 int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);
 int gemm_qkv_f32(const float* x, const float* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);
 int gemm_out_bf16(const void* a, int32_t a_is_f32, const void* w_t, void* y, int32_t M, int32_t N, int32_t K,

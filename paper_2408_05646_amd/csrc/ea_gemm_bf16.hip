@@ -1,7 +1,9 @@
 // bf16 matrix-core GEMMs for the low-rank projections (Eq. 1 with the folded
 // weights of Eq. 8, and the output projection of Eq. 2):
-//   C[M,N] = A[M,K] . Wt[N,K]^T,  bf16 operands, fp32 accumulation.
-// Both operands are K-contiguous, so MFMA fragments are plain 16-byte loads.
+//   C[M,N] = A[M,K] . W[N,K]^T,  bf16 operands, fp32 accumulation.
+// A is row-major (K contiguous).  W is packed in MFMA fragment order
+// [N/16][K/32][4 quads][16 channels][8 k]: the B operand of one (channel block, k step) is one
+// contiguous 1 KiB wave load, and a channel block's K range is one contiguous stream.
 //  - tiled kernel (M > 64): 128x128x64 workgroup tiles staged through LDS,
 //    2x2 waves of 64x64, v_mfma_f32_16x16x32_bf16;
 //  - skinny kernel (M <= 64, the generation phase): one workgroup per 16 output
@@ -51,13 +53,20 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   bf16x8 ga[4], gb[4];
+  const int ksteps = K >> 5;
+  const int64_t nblks = (N + 15) >> 4;
   auto gload = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
       const bool kin = k0 + kc < K;
       ga[i] = (kin && m0 + row < M) ? load_frag<A_F32>(A, (int64_t)(m0 + row) * K + k0 + kc) : zero_frag();
-      gb[i] = (kin && n0 + row < N) ? load_frag<false>(Wt, (int64_t)(n0 + row) * K + k0 + kc) : zero_frag();
+      // W: this thread's 16-byte unit of fragment (channel block nb, k step): 64 threads read 1 KiB contiguous
+      const int frag = chunk >> 6, ln = chunk & 63, nb = frag >> 1, kst = frag & 1;
+      const int64_t nblk = (n0 >> 4) + nb;
+      gb[i] = ((k0 >> 5) + kst < ksteps && nblk < nblks)
+                  ? *reinterpret_cast<const bf16x8*>(Wt + ((nblk * ksteps + (k0 >> 5) + kst) << 9) + (ln << 3))
+                  : zero_frag();
     }
   };
   auto mainloop = [&](auto swap_tag) __attribute__((always_inline)) {
@@ -69,7 +78,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
       for (int i = 0; i < 4; ++i) {
         const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
         *reinterpret_cast<bf16x8*>(&As[row * LDK + kc]) = ga[i];
-        *reinterpret_cast<bf16x8*>(&Bs[row * LDK + kc]) = gb[i];
+        *reinterpret_cast<bf16x8*>(&Bs[chunk << 3]) = gb[i];          // fragment order: [8 channel blocks][2 k steps][64 lanes][8]
       }
       __syncthreads();
       if (k0 + BK < K) gload(k0 + BK);
@@ -79,7 +88,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
-          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + i) * 2 + ks) * 64) + lane) << 3]);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -95,40 +104,55 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
 }
 
 // ---------------------------------------------------------------------------
-// Skinny kernel: M <= 16*MT rows, 16 output channels per workgroup, K split over 4 waves.
+// Skinny kernel: M <= 16*MT rows.  One workgroup owns NB blocks of 16 output channels; its four
+// waves interleave the 32-wide K steps, each keeps UN steps of weight fragments in flight
+// (nontemporal: the weights are streamed exactly once), and the partial sums meet in LDS.
 // A float A operand is split in hi + lo bf16 halves so it loses no precision.
 // ---------------------------------------------------------------------------
-template <typename Epilogue, bool A_F32, int MT>
+template <typename Epilogue, bool A_F32, int MT, int NB>
 __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __restrict__ A,
                                                                const uint16_t* __restrict__ Wt, int32_t M, int32_t N,
                                                                int32_t K, Epilogue ep) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, quad = lane >> 4;
-  const int n0 = blockIdx.x * 16;
-  const bool n_ok = n0 + col < N;
-  const uint16_t* wrow = Wt + (int64_t)(n_ok ? n0 + col : 0) * K + quad * 8;
-
-  f32x4 acc[MT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+  const int n0 = blockIdx.x * (16 * NB);
   const int steps = K / 32;
-  constexpr int UN = 4;
-  for (int s0 = wave * UN; s0 < steps; s0 += 4 * UN) {
-    bf16x8 bw[UN];
+  const uint16_t* wfrag[NB];                              // fragment (channel block, step 0) + this lane's unit
+  bool n_ok[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    n_ok[nb] = n0 + nb * 16 < N;                          // packed rows beyond N exist and are zero
+    wfrag[nb] = Wt + ((((int64_t)(n_ok[nb] ? (n0 >> 4) + nb : 0) * steps) << 9) + (lane << 3));
+  }
+
+  f32x4 acc[MT][NB];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  constexpr int UN = 8;
+  for (int s0 = wave; s0 < steps; s0 += 4 * UN) {       // this wave: steps s0, s0 + 4, ..., s0 + 4*(UN-1)
+    bf16x8 bw[UN][NB];
 #pragma unroll
     for (int u = 0; u < UN; ++u)
-      bw[u] = (n_ok && s0 + u < steps) ? *reinterpret_cast<const bf16x8*>(wrow + (int64_t)(s0 + u) * 32) : zero_frag();
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+        bw[u][nb] = (n_ok[nb] && s0 + 4 * u < steps)
+                        ? __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(wfrag[nb] + ((int64_t)(s0 + 4 * u) << 9)))
+                        : zero_frag();
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      if (s0 + u >= steps) break;
-      const int64_t koff = (int64_t)(s0 + u) * 32 + quad * 8;
+      const int st = s0 + 4 * u;
+      if (st >= steps) break;
+      const int64_t koff = (int64_t)st * 32 + quad * 8;
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int row = i * 16 + col;
         if (!A_F32) {
           const bf16x8 af = row < M ? load_frag<false>(A, (int64_t)row * K + koff) : zero_frag();
-          acc[i] = mfma16(af, bw[u], acc[i]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[i][nb] = mfma16(af, bw[u][nb], acc[i][nb]);
         } else {
           bf16x8 hi = zero_frag(), lo = zero_frag();
           if (row < M) {
@@ -142,20 +166,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __res
               lo[j] = (__bf16)(f[j] - (float)h);
             }
           }
-          acc[i] = mfma16(hi, bw[u], acc[i]);
-          acc[i] = mfma16(lo, bw[u], acc[i]);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            acc[i][nb] = mfma16(hi, bw[u][nb], acc[i][nb]);
+            acc[i][nb] = mfma16(lo, bw[u][nb], acc[i][nb]);
+          }
         }
       }
     }
   }
-  __shared__ f32x4 red[4][MT][64];
+  __shared__ f32x4 red[4][MT][NB][64];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) red[wave][i][lane] = acc[i];
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) red[wave][i][nb][lane] = acc[i][nb];
   __syncthreads();
-  for (int idx = tid; idx < MT * 64; idx += 256) {
-    const int i = idx >> 6, ln = idx & 63;
-    const f32x4 v = red[0][i][ln] + red[1][i][ln] + red[2][i][ln] + red[3][i][ln];
-    const int c = n0 + (ln & 15);
+  for (int idx = tid; idx < MT * NB * 64; idx += 256) {
+    const int ln = idx & 63, nb = (idx >> 6) % NB, i = (idx >> 6) / NB;
+    const f32x4 v = red[0][i][nb][ln] + red[1][i][nb][ln] + red[2][i][nb][ln] + red[3][i][nb][ln];
+    const int c = n0 + nb * 16 + (ln & 15);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int r = i * 16 + (ln >> 4) * 4 + e;
@@ -316,14 +345,27 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
                        hipStream_t st) {
   const uint16_t* w = (const uint16_t*)Wt;
   if (M <= 64) {
-    dim3 grid((N + 15) / 16), block(256);
+    // two channel blocks per workgroup when that still leaves about one workgroup per compute unit
+    const int nb = (N / 32 >= 200) ? 2 : 1;
+    dim3 grid((N + 16 * nb - 1) / (16 * nb)), block(256);
     const int mt = (M + 15) / 16;
-    switch (mt) {
-      case 1: gemm_bf16_skinny_kernel<Epilogue, A_F32, 1><<<grid, block, 0, st>>>(A, w, M, N, K, ep); break;
-      case 2: gemm_bf16_skinny_kernel<Epilogue, A_F32, 2><<<grid, block, 0, st>>>(A, w, M, N, K, ep); break;
-      case 3: gemm_bf16_skinny_kernel<Epilogue, A_F32, 3><<<grid, block, 0, st>>>(A, w, M, N, K, ep); break;
-      default: gemm_bf16_skinny_kernel<Epilogue, A_F32, 4><<<grid, block, 0, st>>>(A, w, M, N, K, ep); break;
+#define EA_SKINNY(MT_, NB_) gemm_bf16_skinny_kernel<Epilogue, A_F32, MT_, NB_><<<grid, block, 0, st>>>(A, w, M, N, K, ep)
+    if (nb == 2) {
+      switch (mt) {
+        case 1: EA_SKINNY(1, 2); break;
+        case 2: EA_SKINNY(2, 2); break;
+        case 3: EA_SKINNY(3, 2); break;
+        default: EA_SKINNY(4, 2); break;
+      }
+    } else {
+      switch (mt) {
+        case 1: EA_SKINNY(1, 1); break;
+        case 2: EA_SKINNY(2, 1); break;
+        case 3: EA_SKINNY(3, 1); break;
+        default: EA_SKINNY(4, 1); break;
+      }
     }
+#undef EA_SKINNY
   } else {
     dim3 grid((N + 127) / 128, (M + 127) / 128), block(256);
     if (grid.y > 65535) return EA_ERR_SHAPE;

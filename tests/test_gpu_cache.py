@@ -58,3 +58,20 @@ def test_scatter_gather_roundtrip_and_slot_positions(dtype, P, Hkv, r_k, r_v, n,
     assert written_v == B * Hkv * n * lay.r_v_pad - int((vd == -77).sum())
     assert int((kp == 0).sum()) >= B * Hkv * n * (lay.r_k_pad - r_k)
     assert int((vp == 0).sum()) >= B * Hkv * n * (lay.r_v_pad - r_v)
+
+
+@pytest.mark.parametrize("N,K", [(7680, 4096), (100, 64), (16, 32), (333, 96)])
+def test_pack_weight_fragment_order(N, K):
+    """Element (n, k) of the out-major weights must land where the header says:
+    ((n/16 * K/32 + k/32) * 4 + (k%32)/8) * 128 + (n%16)*8 + k%8; rows beyond N are zero."""
+    g = np.random.default_rng(N + K)
+    w = torch.from_numpy(g.integers(-120, 120, size=(N, K)).astype(np.float32)).to(torch.bfloat16).cuda()
+    packed = ea.pack_weight(w).float().cpu().numpy()
+    assert packed.size == ea.packed_weight_elems(N, K, ea.EA_BF16) == -(-N // 16) * 16 * K
+    n, k = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
+    idx = ((n // 16 * (K // 32) + k // 32) * 4 + (k % 32) // 8) * 128 + (n % 16) * 8 + k % 8
+    assert np.array_equal(packed[idx], w.float().cpu().numpy())
+    mask = np.ones(packed.size, bool); mask[idx.ravel()] = False
+    assert (packed[mask] == 0).all()
+    wf = torch.from_numpy(g.standard_normal((N, K)).astype(np.float32)).cuda()
+    assert torch.equal(ea.pack_weight(wf).view(N, K), wf)

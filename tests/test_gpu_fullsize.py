@@ -131,9 +131,9 @@ def test_cfg4_prefill_chain_sampled():
     o = torch.empty((B, n, H, r), dtype=torch.bfloat16, device="cuda")
     y = torch.empty((B * n, d), dtype=torch.bfloat16, device="cuda")
     print("cfg4 running the HIP path", flush=True)
-    ea.project_qkv(desc, dev(x.reshape(B * n, d)), dev(wqkv_t), q_r, k_pool, v_pool, pt, seq0, n)
+    ea.project_qkv(desc, dev(x.reshape(B * n, d)), ea.pack_weight(dev(wqkv_t)), q_r, k_pool, v_pool, pt, seq0, n)
     ea.prefill_attn(desc, q_r.view(B, n, H, r), k_pool, v_pool, pt, seq0 + n, o)
-    ea.out_proj(desc, o.view(B * n, H * r), dev(wo_t), y)
+    ea.out_proj(desc, o.view(B * n, H * r), ea.pack_weight(dev(wo_t)), y)
     torch.cuda.synchronize()
     y_gpu = y.float().view(B, n, d).cpu().numpy()
     assert np.isfinite(y_gpu).all()

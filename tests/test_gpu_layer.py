@@ -37,7 +37,7 @@ def device_weights(desc, folded):
     Wk_q = np.stack([wqkv_t[q_rows + i * r_k:q_rows + (i + 1) * r_k].T for i in range(Hkv)])
     Wv_q = np.stack([wqkv_t[q_rows + k_rows + i * r_v:q_rows + k_rows + (i + 1) * r_v].T for i in range(Hkv)])
     Wo_q = np.stack([wo_t.T[i * r_v:(i + 1) * r_v] for i in range(H)])
-    return to_dev(desc, wqkv_t), to_dev(desc, wo_t), (Wq_q, Wk_q, Wv_q, Wo_q)
+    return ea.pack_weight(to_dev(desc, wqkv_t)), ea.pack_weight(to_dev(desc, wo_t)), (Wq_q, Wk_q, Wv_q, Wo_q)
 
 
 def assert_one_bf16_rounding(got: np.ndarray, ref: np.ndarray):
@@ -126,7 +126,7 @@ def test_out_proj(dtype, d, H, r_v, M):
     for o_dt in ([torch.float32] if dtype == ea.EA_F32 else [torch.float32, torch.bfloat16]):
         o_in = o if o_dt == torch.float32 else quantize(desc, o)
         y = torch.full((M, d), float("nan"), dtype=tdtype(desc), device="cuda")
-        ea.out_proj(desc, torch.from_numpy(o_in.astype(np.float32)).to(o_dt).cuda(), to_dev(desc, wo_t), y)
+        ea.out_proj(desc, torch.from_numpy(o_in.astype(np.float32)).to(o_dt).cuda(), ea.pack_weight(to_dev(desc, wo_t)), y)
         torch.cuda.synchronize()
         assert_close(y.float().cpu().numpy(), ora.out_proj(o_in, Wo_q), TOL_F32 if dtype == ea.EA_F32 else TOL_BF16, "y")
 

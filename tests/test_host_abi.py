@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 14
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 16
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -129,6 +129,14 @@ def test_argument_errors_are_reported_before_any_launch():
     assert ea.decode_workspace_bytes(good, 2, 4) == 2 * 8 * 4 * (2 + 48) * 4
     assert ea.decode_workspace_bytes(good, 2, 1) == 0
     assert 1 <= ea.decode_auto_splits(good, 16, 32768) <= 64
+
+
+def test_packed_weight_size():
+    assert ea.packed_weight_elems(7680, 4096, ea.EA_BF16) == 7680 * 4096
+    assert ea.packed_weight_elems(100, 64, ea.EA_BF16) == 112 * 64        # channel rows padded to 16
+    assert ea.packed_weight_elems(100, 48, ea.EA_BF16) == -1              # K must be a multiple of 32
+    assert ea.packed_weight_elems(100, 50, ea.EA_F32) == 5000
+    assert ea.packed_weight_elems(0, 64, ea.EA_BF16) == -1
 
 
 def test_auto_splits_fill_the_chip():
