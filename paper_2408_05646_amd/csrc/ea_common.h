@@ -97,6 +97,20 @@ __device__ __forceinline__ bf16x8 zero_frag() {
   return __builtin_bit_cast(bf16x8, z);
 }
 
+// Maximum over the lanes l, l^16, l^32, l^48: the four register quads that hold one column of an MFMA
+// result.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
+// the second, v_permlane32_swap the upper half of the first with the lower half of the second; with both
+// operands equal, the two results hold each lane's own value and its partner's.
+__device__ __forceinline__ float quad_column_max(float x) {
+  typedef __attribute__((ext_vector_type(2))) unsigned u2;
+  unsigned xi = __builtin_bit_cast(unsigned, x);
+  u2 a = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);
+  x = fmaxf(__builtin_bit_cast(float, (unsigned)a[0]), __builtin_bit_cast(float, (unsigned)a[1]));
+  xi = __builtin_bit_cast(unsigned, x);
+  u2 b = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  return fmaxf(__builtin_bit_cast(float, (unsigned)b[0]), __builtin_bit_cast(float, (unsigned)b[1]));
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // The HIP runtime keeps the last error of ANY earlier call of the process (another library's

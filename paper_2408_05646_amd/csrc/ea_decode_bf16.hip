@@ -163,25 +163,28 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
     for (int tb = 0; tb < TBN; ++tb) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float v = s[tb][i] * a.scale_log2;
-        if (rem < TOK && tb * 16 + quad * 4 + i >= rem) v = -INFINITY;
-        s[tb][i] = v;
-        mx = fmaxf(mx, v);
+        if (rem < TOK && tb * 16 + quad * 4 + i >= rem) s[tb][i] = -INFINITY;
+        mx = fmaxf(mx, s[tb][i]);
       }
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = quad_column_max(mx) * a.scale_log2;                  // the scale is positive: max commutes with it
     const float m_new = fmaxf(m, mx);
     const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_use);   // m = -inf -> 0
-    m = m_new;
+    if (__any(m_new > m)) {                                   // rescale only when some column's max moved
+      const float alpha = __builtin_amdgcn_exp2f(m - m_use);  // m = -inf -> 0
+      lacc *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+      m = m_new;
+    }
     bf16x8 pf[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i] - m_use);
+        for (int i = 0; i < 4; ++i)
+          pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], a.scale_log2, -m_use));
       }
     }
     if (rem < TOK) {
@@ -199,12 +202,10 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
       }
     }
     // ---- O^T += V^T . P^T, row sums of P through the all-ones operand
-    lacc *= alpha;
 #pragma unroll
     for (int u = 0; u < UN; ++u) lacc = mfma16(ones, pf[u], lacc);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
-      acc[cb] *= alpha;
 #pragma unroll
       for (int u = 0; u < UN; ++u) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
     }

@@ -3,14 +3,16 @@
 // the paged cache in MFMA fragment order.
 //
 // One workgroup = 4 waves = 4 * QT * 16 consecutive queries of one (sequence, head).
-// A wave keeps QT blocks of 16 queries as MFMA columns and walks the 64-token cache
-// tiles up to its diagonal:
+// The workgroup stages each 64-token K / V tile of its kv head in LDS once (double buffered,
+// the next tile's global loads are in flight while the current one is computed); a wave keeps
+// QT blocks of 16 queries as MFMA columns and walks the tiles up to its diagonal:
 //   S[64 kv x 16 q]   = K_tile . Q^T              (A = K fragments, B = q rows)
 //   online softmax per query column (rows = kv tokens: 16 registers + two cross-quad shuffles)
 //   O^T[r_v x 16 q]  += V_tile^T . P^T            (P rounded to bf16; row sums by an all-ones MFMA)
-// Every K / V fragment is loaded once per wave and reused for the QT query blocks.
+// Every K / V fragment is read from LDS once per wave and tile and reused for the QT query blocks.
 #include "ea_common.h"
 #include "ea_epilogue.h"
+#include <cstdlib>
 
 namespace ea {
 
@@ -23,19 +25,124 @@ struct PrefillArgs {
   uint16_t* out;
   Geo g;
   int32_t n_q;
+  int32_t batch;
+  int32_t n_qtiles;   // query tiles per (sequence, head) = gridDim.x / (H * batch)
   float scale_log2;
 };
 
-template <int KS, int NCB, int QT>
-__global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
+constexpr float kLazy = 8.0f;
+
+// One 64-token tile against one block of 16 queries: scores, online softmax, P.V.
+// MASKED = the tile is cut by the causal diagonal or by the end of the sequence (lane-wise limits);
+// unmasked tiles run the lean path.  `vis` = number of kv positions this lane's query may see.
+template <int KS, int NCB, bool MASKED>
+__device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf16x8 (&vf)[2][NCB],
+                                             const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
+                                             f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad) {
+  f32x4 s[4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) {
+    s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
+      mx = fmaxf(mx, s[tb][i]);
+    }
+  mx = quad_column_max(mx) * scale_log2;                     // the scale is positive: max commutes with it
+  // m is a reference exponent, not the exact running max: it only moves when the max has grown by more
+  // than kLazy (log2 units), so P stays <= 2^kLazy -- harmless in bf16 / fp32 -- and the accumulators are
+  // rescaled a handful of times per query instead of at every tile.  The final o = acc / l is unchanged.
+  if (__any(mx > m + kLazy)) {
+    const float m_new = fmaxf(m, mx);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf -> 0
+    lacc *= alpha;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+    m = m_new;
+  }
+  const float m_use = (MASKED && m == -INFINITY) ? 0.f : m;
+  bf16x8 pf[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], scale_log2, -m_use));
+  lacc = mfma16(ones, pf[0], lacc);
+  lacc = mfma16(ones, pf[1], lacc);
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
+    acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
+  }
+}
+
+// Clears value slots of tokens >= limit (never written, arbitrary bits) so that 0 * x stays 0.
+template <int NCB>
+__device__ __forceinline__ void clear_tail(bf16x8 (&vf)[2][NCB], int tok0, int limit, int quad) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int tok = tok0 + u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
+        if (tok >= limit) vf[u][cb][j] = (__bf16)0.0f;
+      }
+}
+
+template <int NCB, int QT>
+__device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&acc)[QT][NCB], const f32x4 (&lacc)[QT],
+                                          int b, int head, int q0, int col, int quad) {
   const Geo& g = a.g;
-  const int head = blockIdx.y, b = blockIdx.z;
+#pragma unroll
+  for (int qb = 0; qb < QT; ++qb) {
+    const int qi = q0 + qb * 16 + col;
+    const float l = lacc[qb][0];
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    uint16_t* orow = a.out + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_v;
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+      const int c = cb * 16 + quad * 4;
+      if (qi >= a.n_q) {
+      } else if (c + 3 < g.r_v) {
+        u32x2 w;
+        w[0] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][1] * inv) << 16);
+        w[1] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][3] * inv) << 16);
+        *reinterpret_cast<u32x2*>(orow + c) = w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (c + i < g.r_v) orow[c + i] = f32_to_bf16_rne(acc[qb][cb][i] * inv);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Variant D: every wave reads its K / V fragments straight from global memory (L2), next tile
+// prefetched into the registers the current one has just left.
+// ---------------------------------------------------------------------------
+template <int KS, int NCB, int QT, int WPE>
+__global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillArgs a) {
+  const Geo& g = a.g;
+  // 1-D grid ordered by work: the latest (longest) query tiles of every (sequence, head) come first
+  const int hb = g.n_heads * a.batch;
+  const int q_tile = a.n_qtiles - 1 - (int)(blockIdx.x / hb);
+  const int head = (blockIdx.x % hb) % g.n_heads, b = (blockIdx.x % hb) / g.n_heads;
   const int kvh = head / g.group;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, quad = lane >> 4;
   const int nck = g.r_k_pad >> 3;
   constexpr int QW = QT * 16;                                   // queries per wave
-  const int q_tile = gridDim.x - 1 - blockIdx.x;                // longest (latest) query tiles first
   const int q0 = (q_tile * 4 + wave) * QW;                      // first query of this wave
   if (q0 >= a.n_q) return;
 
@@ -47,7 +154,6 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
   const int pos0 = len - a.n_q;                                  // position of query 0 (may be < 0: such queries see nothing)
   const int tiles_per_page = g.page_tokens / kTile;
 
-  // B operands: q rows of this wave's QT query blocks
   bf16x8 qf[QT][KS];
 #pragma unroll
   for (int qb = 0; qb < QT; ++qb) {
@@ -83,7 +189,7 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     const int page = a.page_table[(int64_t)b * g.max_pages + t / tiles_per_page];
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
-  auto load_k = [&](int t, int page) {
+  auto load_k = [&](int t, int page) __attribute__((always_inline)) {
     const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
                            (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad);
 #pragma unroll
@@ -95,7 +201,7 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
                                  : zero_frag();
       }
   };
-  auto load_v = [&](int t, int page) {
+  auto load_v = [&](int t, int page) __attribute__((always_inline)) {
     const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
                            (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad);
 #pragma unroll
@@ -104,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
       for (int cb = 0; cb < NCB; ++cb)
         vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
   };
-  auto zero_kv = [&]() {
+  auto zero_kv = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
@@ -132,103 +238,218 @@ __global__ __launch_bounds__(256, 2) void prefill_bf16_kernel(PrefillArgs a) {
     const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
     const bool have_n = t + 1 < t_end;
     const int page_n = have_n ? tile_page(t + 1) : -1;
+    if (full) {
+#pragma unroll
+      for (int qb = 0; qb < QT; ++qb)
+        attend_block<KS, NCB, false>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad);
+    } else {
+      if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
+#pragma unroll
+      for (int qb = 0; qb < QT; ++qb) {
+        const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
+        attend_block<KS, NCB, true>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis, quad);
+      }
+    }
+    if (have_n) {
+      if (page_n >= 0) {
+        load_k(t + 1, page_n);
+        load_v(t + 1, page_n);
+      } else {
+        zero_kv();
+      }
+    }
+    page = page_n;
+  }
+  write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
+}
 
-    if (tok0 + kTile > limit) {
-      // slots past the end of the sequence hold arbitrary bits: clear them so 0 * x stays 0
+// ---------------------------------------------------------------------------
+// Variant L: the workgroup stages each 64-token K / V tile of its kv head in LDS once (double
+// buffered; the cache layout is the fragment order, so the copy is linear); the next tile's global
+// loads are in flight while the current one is computed.
+// ---------------------------------------------------------------------------
+template <int KS, int NCB, int QT, int WPE>
+__global__ __launch_bounds__(256, WPE) void prefill_bf16_lds_kernel(PrefillArgs a) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];   // 2 buffers x (K tile | V tile)
+  const Geo& g = a.g;
+  const int hb = g.n_heads * a.batch;
+  const int q_tile = a.n_qtiles - 1 - (int)(blockIdx.x / hb);
+  const int head = (blockIdx.x % hb) % g.n_heads, b = (blockIdx.x % hb) / g.n_heads;
+  const int kvh = head / g.group;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 15, quad = lane >> 4;
+  const int nck = g.r_k_pad >> 3;
+  constexpr int QW = QT * 16;
+  const int q0 = (q_tile * 4 + wave) * QW;
+
+  int64_t n64 = a.seq_len[b];
+  const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
+  if (n64 > cap) n64 = cap;
+  if (n64 < 0) n64 = 0;
+  const int len = (int)n64;
+  const int pos0 = len - a.n_q;
+  const int tiles_per_page = g.page_tokens / kTile;
+
+  bf16x8 qf[QT][KS];
+#pragma unroll
+  for (int qb = 0; qb < QT; ++qb) {
+    const int qi = q0 + qb * 16 + col;
+    const uint16_t* qrow = a.q + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_k;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int k = ks * 32 + quad * 8;
+      qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
+    }
+  }
+  bf16x8 ones;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+
+  f32x4 acc[QT][NCB], lacc[QT];
+  float m[QT];
+#pragma unroll
+  for (int qb = 0; qb < QT; ++qb) {
+    m[qb] = -INFINITY;
+    lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto tiles_for = [&](int q_first) -> int {
+    if (q_first >= a.n_q) return 0;
+    const int pos_last = pos0 + min(a.n_q, q_first + QW) - 1;
+    return pos_last >= 0 ? min(pos_last, len - 1) / kTile + 1 : 0;
+  };
+  const int t_end = tiles_for(q0);
+  int t_end_wg = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) t_end_wg = max(t_end_wg, tiles_for((q_tile * 4 + w) * QW));
+  const int pos_first = pos0 + q0;
+
+  constexpr int KU = KS, VU = (NCB + 1) / 2;                    // 16-byte units per thread: 8*r_pad / 256 threads
+  const int k_units = g.r_k_pad * 8, v_units = g.r_v_pad * 8;
+  const int buf_elems = (g.r_k_pad + g.r_v_pad) * kTile;
+  u32x4 kreg[KU], vreg[VU];
+  auto tile_page = [&](int t) -> int {
+    const int page = a.page_table[(int64_t)b * g.max_pages + t / tiles_per_page];
+    return (page >= 0 && page < g.pool_pages) ? page : -1;
+  };
+  auto gload = [&](int t, int page) __attribute__((always_inline)) {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    const u32x4* kb = nullptr;
+    const u32x4* vb = nullptr;
+    if (page >= 0) {
+      kb = reinterpret_cast<const u32x4*>(a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
+                                          (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad));
+      vb = reinterpret_cast<const u32x4*>(a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
+                                          (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad));
+    }
+#pragma unroll
+    for (int i = 0; i < KU; ++i) kreg[i] = (page >= 0 && tid + 256 * i < k_units) ? kb[tid + 256 * i] : zero;
+#pragma unroll
+    for (int i = 0; i < VU; ++i) vreg[i] = (page >= 0 && tid + 256 * i < v_units) ? vb[tid + 256 * i] : zero;
+  };
+  auto lds_store = [&](int buf) __attribute__((always_inline)) {
+    u32x4* kd = reinterpret_cast<u32x4*>(smem + buf * buf_elems);
+    u32x4* vd = reinterpret_cast<u32x4*>(smem + buf * buf_elems + g.r_k_pad * kTile);
+#pragma unroll
+    for (int i = 0; i < KU; ++i)
+      if (tid + 256 * i < k_units) kd[tid + 256 * i] = kreg[i];
+#pragma unroll
+    for (int i = 0; i < VU; ++i)
+      if (tid + 256 * i < v_units) vd[tid + 256 * i] = vreg[i];
+  };
+
+  int page = -1;
+  if (t_end_wg > 0) {
+    page = tile_page(0);
+    gload(0, page);
+    lds_store(0);
+  }
+  __syncthreads();
+
+  for (int t = 0; t < t_end_wg; ++t) {
+    const bool have_n = t + 1 < t_end_wg;
+    const int page_n = have_n ? tile_page(t + 1) : -1;
+    if (have_n) gload(t + 1, page_n);                           // in flight while this tile is computed
+
+    if (t < t_end) {
+      const uint16_t* ks_ = smem + (t & 1) * buf_elems;
+      const uint16_t* vs_ = ks_ + g.r_k_pad * kTile;
+      const int tok0 = t * kTile;
+      const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;
+      const int limit = page >= 0 ? len : 0;
+      bf16x8 kf[4][KS], vf[2][NCB];
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const int chunk = ks * 4 + quad;
+          kf[tb][ks] = chunk < nck ? *reinterpret_cast<const bf16x8*>(ks_ + (((tb * nck + chunk) * 16 + col) << 3))
+                                   : zero_frag();
+        }
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
+          vf[u][cb] = *reinterpret_cast<const bf16x8*>(vs_ + (((u * NCB + cb) * 64 + lane) << 3));
+      if (full) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const int tok = tok0 + u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
-            if (tok >= limit) vf[u][cb][j] = (__bf16)0.0f;
-          }
-    }
-
+        for (int qb = 0; qb < QT; ++qb)
+          attend_block<KS, NCB, false>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad);
+      } else {
+        if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
 #pragma unroll
-    for (int qb = 0; qb < QT; ++qb) {
-      f32x4 s[4];
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb) {
-        s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], qf[qb][ks], s[tb]);
-      }
-      if (qb == QT - 1 && have_n && page_n >= 0) load_k(t + 1, page_n);   // K registers are free: prefetch
-      const int qpos = pos0 + q0 + qb * 16 + col;                // this lane's query position
-      const int vis = min(qpos + 1, limit);                      // kv tokens < vis are visible
-      float mx = -INFINITY;
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float v = s[tb][i] * a.scale_log2;
-          if (!full && tok0 + tb * 16 + quad * 4 + i >= vis) v = -INFINITY;
-          s[tb][i] = v;
-          mx = fmaxf(mx, v);
+        for (int qb = 0; qb < QT; ++qb) {
+          const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
+          attend_block<KS, NCB, true>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis, quad);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m[qb], mx);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m[qb] - m_use);
-      m[qb] = m_new;
-      bf16x8 pf[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i] - m_use);
-      lacc[qb] *= alpha;
-      lacc[qb] = mfma16(ones, pf[0], lacc[qb]);
-      lacc[qb] = mfma16(ones, pf[1], lacc[qb]);
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        acc[qb][cb] *= alpha;
-        acc[qb][cb] = mfma16(vf[0][cb], pf[0], acc[qb][cb]);
-        acc[qb][cb] = mfma16(vf[1][cb], pf[1], acc[qb][cb]);
       }
     }
-    if (have_n) {
-      if (page_n >= 0) load_v(t + 1, page_n);
-      else zero_kv();
-    }
+    if (have_n) lds_store((t + 1) & 1);     // that buffer was last read in iteration t-1, which every wave has left
+    __syncthreads();
     page = page_n;
   }
+  write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
+}
 
-  // ---- write O: lane holds, for query `col` of each block, channels cb*16 + 4*quad .. +3
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    const int qi = q0 + qb * 16 + col;
-    if (qi >= a.n_q) continue;
-    const float l = lacc[qb][0];
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-    uint16_t* orow = a.out + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_v;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      const int c = cb * 16 + quad * 4;
-      if (c + 3 < g.r_v) {
-        u32x2 w;
-        w[0] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][1] * inv) << 16);
-        w[1] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][3] * inv) << 16);
-        *reinterpret_cast<u32x2*>(orow + c) = w;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (c + i < g.r_v) orow[c + i] = f32_to_bf16_rne(acc[qb][cb][i] * inv);
-      }
-    }
+static int prefill_variant() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("EA_PREFILL_VARIANT");
+    v = e ? atoi(e) : 0;
   }
+  return v;
 }
 
 template <int KS, int NCB>
-static void launch_prefill(const PrefillArgs& a, int32_t B, hipStream_t st) {
-  constexpr int QT = (KS <= 2 && NCB <= 4) ? 4 : 2;
-  const int per_block = 4 * QT * 16;
-  dim3 grid((a.n_q + per_block - 1) / per_block, a.g.n_heads, B), block(256);
-  prefill_bf16_kernel<KS, NCB, QT><<<grid, block, 0, st>>>(a);
+static void launch_prefill(const PrefillArgs& a_in, int32_t B, hipStream_t st) {
+  constexpr bool SMALL = (KS <= 2 && NCB <= 4);
+  const size_t lds = (size_t)2 * (a_in.g.r_k_pad + a_in.g.r_v_pad) * kTile * sizeof(uint16_t);   // <= 64 KiB
+  const int v = prefill_variant();
+  PrefillArgs a = a_in;
+  a.batch = B;
+  auto grid_for = [&](int qt) {
+    a.n_qtiles = (a.n_q + 64 * qt - 1) / (64 * qt);
+    return dim3((uint32_t)(a.n_qtiles * a.g.n_heads * B));
+  };
+#define EA_PREFILL(KERNEL, QT_, WPE_, LDS_)                              \
+  do {                                                                 \
+    const dim3 grid = grid_for(QT_);                                   \
+    KERNEL<KS, NCB, QT_, WPE_><<<grid, 256, LDS_, st>>>(a);            \
+  } while (0)
+  if constexpr (SMALL) {
+    switch (v) {
+      case 1: EA_PREFILL(prefill_bf16_lds_kernel, 4, 2, lds); break;
+      case 4: EA_PREFILL(prefill_bf16_direct_kernel, 2, 2, 0); break;
+      case 5: EA_PREFILL(prefill_bf16_lds_kernel, 2, 2, lds); break;
+      default: EA_PREFILL(prefill_bf16_direct_kernel, 4, 2, 0); break;
+    }
+  } else {
+    if (v == 1) EA_PREFILL(prefill_bf16_lds_kernel, 2, 2, lds);
+    else EA_PREFILL(prefill_bf16_direct_kernel, 2, 2, 0);
+  }
+#undef EA_PREFILL
 }
 
 template <int KS>
@@ -249,7 +470,7 @@ static int dispatch_ncb(int ncb, const PrefillArgs& a, int32_t B, hipStream_t st
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
                  const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st) {
-  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  if ((int64_t)((n + 127) / 128) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
   if (g.r_k % 8 != 0 || g.r_v % 4 != 0) return EA_ERR_SHAPE;     // 16-byte q rows, 8-byte output stores
   PrefillArgs a;
   a.q = (const uint16_t*)q;
