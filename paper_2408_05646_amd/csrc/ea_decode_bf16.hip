@@ -14,6 +14,8 @@
 
 namespace ea {
 
+constexpr float kLazy = 8.0f;
+
 struct DecodeArgs {
   const float* q;
   const uint16_t* k_pool;
@@ -29,13 +31,14 @@ struct DecodeArgs {
 
 // TBN = 16-token blocks handled per loop iteration: 4 (a whole 64-token tile) or 2 (half a tile, for the
 // large ranks whose fragments would not fit the register file otherwise).
-template <int KS, int NCB, int TBN>
-__global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
+template <int KS, int NCB, int TBN, int WPE>
+__global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   constexpr int UN = TBN / 2;            // 32-token groups per iteration
   constexpr int SUB = 4 / TBN;           // iterations per 64-token tile
   constexpr int TOK = TBN * 16;          // tokens per iteration
   const Geo& g = a.g;
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // neighbouring workgroups take neighbouring kv heads of the same pages: their slabs are adjacent in memory
+  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 15, quad = lane >> 4;
   const int G = g.group;
@@ -168,15 +171,18 @@ __global__ __launch_bounds__(256, 2) void decode_bf16_kernel(DecodeArgs a) {
       }
     }
     mx = quad_column_max(mx) * a.scale_log2;                  // the scale is positive: max commutes with it
-    const float m_new = fmaxf(m, mx);
-    const float m_use = m_new == -INFINITY ? 0.f : m_new;
-    if (__any(m_new > m)) {                                   // rescale only when some column's max moved
-      const float alpha = __builtin_amdgcn_exp2f(m - m_use);  // m = -inf -> 0
+    // m is a reference exponent: it moves only when the max has grown by more than kLazy (log2 units), so
+    // P stays <= 2^kLazy and the accumulators are rescaled a few times per stream, not at every tile.
+    if (__any(mx > m + kLazy)) {
+      const float m_new = fmaxf(m, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_safe);  // m = -inf -> 0
       lacc *= alpha;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
       m = m_new;
     }
+    const float m_use = m == -INFINITY ? 0.f : m;
     bf16x8 pf[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
@@ -292,9 +298,9 @@ int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n
 
 template <int KS, int NCB>
 static void launch_decode(const DecodeArgs& a, int32_t B, hipStream_t st) {
-  dim3 grid(a.n_splits, a.g.n_kv_heads, B), block(256);
+  dim3 grid(a.g.n_kv_heads, a.n_splits, B), block(256);
   constexpr int TBN = (KS * 4 + NCB * 2 > 22) ? 2 : 4;   // fragments of a whole tile: 16*KS + 8*NCB registers
-  decode_bf16_kernel<KS, NCB, TBN><<<grid, block, 0, st>>>(a);
+  decode_bf16_kernel<KS, NCB, TBN, 2><<<grid, block, 0, st>>>(a);
 }
 
 template <int KS>

@@ -4,14 +4,15 @@
 // A is row-major (K contiguous).  W is packed in MFMA fragment order
 // [N/16][K/32][4 quads][16 channels][8 k]: the B operand of one (channel block, k step) is one
 // contiguous 1 KiB wave load, and a channel block's K range is one contiguous stream.
-//  - tiled kernel (M > 64): 128x128x64 workgroup tiles staged through LDS,
-//    2x2 waves of 64x64, v_mfma_f32_16x16x32_bf16;
+//  - tiled kernel (M > 64): 128x128x64 (256x128x64 for M >= 2048) workgroup tiles staged
+//    through LDS, 2x2 waves, v_mfma_f32_16x16x32_bf16, XCD-aware banded tile order;
 //  - skinny kernel (M <= 64, the generation phase): one workgroup per 16 output
 //    channels, the four waves split K and stream the weight rows straight from
 //    HBM (the weights are read exactly once; x stays in L2).
 #include "ea_common.h"
 #include "ea_epilogue.h"
 #include <type_traits>
+#include <utility>
 
 namespace ea {
 
@@ -32,36 +33,57 @@ __device__ __forceinline__ bf16x8 load_frag(const void* base, int64_t elem_off) 
 // are exchanged (D^T = W_blk . A_blk^T), so a lane holds 4 CONSECUTIVE OUTPUT CHANNELS of one
 // row (an 8-byte bf16 store) instead of one channel of 4 rows; the epilogue picks per wave.
 // ---------------------------------------------------------------------------
-template <typename Epilogue, bool A_F32>
+template <typename Epilogue, bool A_F32, int MI>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __restrict__ A,
                                                                  const uint16_t* __restrict__ Wt, int32_t M, int32_t N,
                                                                  int32_t K, Epilogue ep) {
-  constexpr int BM = 128, BN = 128, BK = 64, LDK = BK + 8;   // +8 elements: rows 144 B apart, conflict-free b128 reads
+  // The W tile sits in LDS in MFMA fragment order [8 blocks of 16 rows][2 k steps][64 lanes][8 elements]
+  // (the order it has in memory); the A tile is row-major with padded rows.
+  constexpr int BM = 32 * MI, BN = 128, BK = 64, LDK = BK + 8;   // A rows 144 B apart: conflict-free 16-byte reads
   __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDK];
-  __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDK];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * BK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, quad = lane >> 4;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int r0 = m0 + wm * 64, c0 = n0 + wn * 64;
+  // Tile order.  Workgroups go round-robin to the 8 XCDs (each with its own L2): give every XCD a contiguous
+  // range of the tile sequence, and walk that sequence in bands of kGroupM row tiles so that the workgroups
+  // running together on an XCD share a few A row tiles and W column tiles.
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    const int remapped = (pid % 8) * per_xcd + pid / 8;
+    if (per_xcd * 8 == total) pid = remapped;          // only when the tiles divide evenly over the XCDs
+  }
+  constexpr int kGroupM = 8;
+  const int band = pid / (kGroupM * tiles_n);
+  const int band_rows = min(kGroupM, tiles_m - band * kGroupM);
+  const int in_band = pid - band * kGroupM * tiles_n;
+  const int tm = band * kGroupM + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int r0 = m0 + wm * (16 * MI), c0 = n0 + wn * 64;
   const bool swap = ep.swap_for(c0);          // wave-uniform
 
-  f32x4 acc[4][4];
+  f32x4 acc[MI][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 ga[4], gb[4];
+  bf16x8 ga[MI], gb[4];
   const int ksteps = K >> 5;
   const int64_t nblks = (N + 15) >> 4;
   auto gload = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;   // A: 8 threads read 128 B of a row
+      ga[i] = (k0 + kc < K && m0 + row < M) ? load_frag<A_F32>(A, (int64_t)(m0 + row) * K + k0 + kc) : zero_frag();
+    }
+#pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
-      const bool kin = k0 + kc < K;
-      ga[i] = (kin && m0 + row < M) ? load_frag<A_F32>(A, (int64_t)(m0 + row) * K + k0 + kc) : zero_frag();
-      // W: this thread's 16-byte unit of fragment (channel block nb, k step): 64 threads read 1 KiB contiguous
+      // W: this thread's 16-byte unit of fragment (channel block nb, k step kst): 64 threads read 1 KiB contiguous
+      const int chunk = tid + 256 * i;
       const int frag = chunk >> 6, ln = chunk & 63, nb = frag >> 1, kst = frag & 1;
       const int64_t nblk = (n0 >> 4) + nb;
       gb[i] = ((k0 >> 5) + kst < ksteps && nblk < nblks)
@@ -75,23 +97,25 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
     for (int k0 = 0; k0 < K; k0 += BK) {
       __syncthreads();
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < MI; ++i) {
         const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;
         *reinterpret_cast<bf16x8*>(&As[row * LDK + kc]) = ga[i];
-        *reinterpret_cast<bf16x8*>(&Bs[chunk << 3]) = gb[i];          // fragment order: [8 channel blocks][2 k steps][64 lanes][8]
       }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8*>(&Bs[(tid + 256 * i) << 3]) = gb[i];
       __syncthreads();
       if (k0 + BK < K) gload(k0 + BK);
 #pragma unroll
       for (int ks = 0; ks < BK / 32; ++ks) {
-        bf16x8 af[4], bfr[4];
+        bf16x8 af[MI], bfr[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * 64 + i * 16 + col) * LDK + ks * 32 + quad * 8]);
-          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + i) * 2 + ks) * 64) + lane) << 3]);
-        }
+        for (int i = 0; i < MI; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * (16 * MI) + i * 16 + col) * LDK + ks * 32 + quad * 8]);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
+          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + i) * 2 + ks) * 64) + lane) << 3]);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
             acc[i][j] = SWAP ? mfma16(bfr[j], af[i], acc[i][j]) : mfma16(af[i], bfr[j], acc[i][j]);
@@ -100,7 +124,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
   };
   if (swap) mainloop(std::true_type{});
   else mainloop(std::false_type{});
-  ep.store(swap, r0, c0, acc, M, N, col, quad);
+  ep.template store<MI>(swap, r0, c0, acc, M, N, col, quad);
 }
 
 // ---------------------------------------------------------------------------
@@ -223,8 +247,8 @@ struct QkvEpBf16 {
     return fast_cols && c0 < g.n_heads * g.r_k + g.n_kv_heads * g.r_k;
   }
   // I is a compile-time index: the accumulators must stay in registers (no dynamic indexing).
-  template <int I>
-  __device__ __forceinline__ void store_slow(bool swap, int r0, int c0, const f32x4 (&acc)[4][4], int M, int N,
+  template <int I, int MI>
+  __device__ __forceinline__ void store_slow(bool swap, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int N,
                                              int col, int quad) const {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -235,9 +259,9 @@ struct QkvEpBf16 {
         if (r < M && c < N) qkv_store<true>(d, r, c, acc[I][j][e]);
       }
   }
-  template <int I>
+  template <int I, int MI>
   __device__ __forceinline__ void store_block(bool swap, bool is_k, int sec0, int r, int r0, int c0,
-                                              const f32x4 (&acc)[4][4], int M, int N, int col, int quad) const {
+                                              const f32x4 (&acc)[MI][4], int M, int N, int col, int quad) const {
     const Geo& g = d.g;
     const int row0 = r0 + I * 16;                  // wave-uniform
     bool fast = row0 + 16 <= M && d.T % 16 == 0;
@@ -254,7 +278,7 @@ struct QkvEpBf16 {
       }
     }
     if (!fast) {
-      store_slow<I>(swap, r0, c0, acc, M, N, col, quad);
+      store_slow<I, MI>(swap, r0, c0, acc, M, N, col, quad);
       return;
     }
     const int tile = tp0 >> 6, tb = (tp0 & 63) >> 4;
@@ -277,20 +301,29 @@ struct QkvEpBf16 {
       }
     }
   }
-  __device__ __forceinline__ void store(bool swap, int r0, int c0, const f32x4 (&acc)[4][4], int M, int N, int col,
+  template <int MI, int... Is>
+  __device__ __forceinline__ void store_slow_all(std::integer_sequence<int, Is...>, bool swap, int r0, int c0,
+                                                 const f32x4 (&acc)[MI][4], int M, int N, int col, int quad) const {
+    (store_slow<Is, MI>(swap, r0, c0, acc, M, N, col, quad), ...);
+  }
+  template <int MI, int... Is>
+  __device__ __forceinline__ void store_block_all(std::integer_sequence<int, Is...>, bool swap, bool is_k, int sec0,
+                                                  int r, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int N,
+                                                  int col, int quad) const {
+    (store_block<Is, MI>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad), ...);
+  }
+  template <int MI>
+  __device__ __forceinline__ void store(bool swap, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int N, int col,
                                         int quad) const {
     const Geo& g = d.g;
     const int nq = g.n_heads * g.r_k, nk = g.n_kv_heads * g.r_k;
     if (!fast_cols || c0 + 64 > N) {
-      store_slow<0>(swap, r0, c0, acc, M, N, col, quad);
-      store_slow<1>(swap, r0, c0, acc, M, N, col, quad);
-      store_slow<2>(swap, r0, c0, acc, M, N, col, quad);
-      store_slow<3>(swap, r0, c0, acc, M, N, col, quad);
+      store_slow_all<MI>(std::make_integer_sequence<int, MI>{}, swap, r0, c0, acc, M, N, col, quad);
       return;
     }
     if (c0 < nq) {                                   // ---- q section: dense [M, nq]
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < MI; ++i) {
         const int r = r0 + i * 16 + col;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -306,10 +339,7 @@ struct QkvEpBf16 {
     const bool is_k = c0 < nq + nk;
     const int sec0 = is_k ? c0 - nq : c0 - nq - nk;  // first column of the wave tile inside its section
     const int r = is_k ? g.r_k : g.r_v;
-    store_block<0>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
-    store_block<1>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
-    store_block<2>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
-    store_block<3>(swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
+    store_block_all<MI>(std::make_integer_sequence<int, MI>{}, swap, is_k, sec0, r, r0, c0, acc, M, N, col, quad);
   }
 };
 
@@ -318,10 +348,11 @@ struct PlainEpBf16 {
   int32_t N;
   __device__ void operator()(int r, int c, float v) const { y[(int64_t)r * N + c] = f32_to_bf16_rne(v); }
   __device__ __forceinline__ bool swap_for(int) const { return true; }
-  __device__ __forceinline__ void store(bool, int r0, int c0, const f32x4 (&acc)[4][4], int M, int Ncols, int col,
+  template <int MI>
+  __device__ __forceinline__ void store(bool, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int Ncols, int col,
                                         int quad) const {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < MI; ++i) {
       const int r = r0 + i * 16 + col;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -367,9 +398,12 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
     }
 #undef EA_SKINNY
   } else {
-    dim3 grid((N + 127) / 128, (M + 127) / 128), block(256);
-    if (grid.y > 65535) return EA_ERR_SHAPE;
-    gemm_bf16_tiled_kernel<Epilogue, A_F32><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
+    const int bm = M >= 2048 ? 256 : 128;      // taller tiles re-read the weights half as often
+    const int64_t tiles = (int64_t)((N + 127) / 128) * ((M + bm - 1) / bm);
+    if (tiles > INT32_MAX) return EA_ERR_SHAPE;
+    dim3 grid((uint32_t)tiles), block(256);
+    if (bm == 256) gemm_bf16_tiled_kernel<Epilogue, A_F32, 8><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
+    else gemm_bf16_tiled_kernel<Epilogue, A_F32, 4><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
   }
   return launch_status();
 }

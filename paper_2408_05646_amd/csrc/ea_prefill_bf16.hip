@@ -3,16 +3,15 @@
 // the paged cache in MFMA fragment order.
 //
 // One workgroup = 4 waves = 4 * QT * 16 consecutive queries of one (sequence, head).
-// The workgroup stages each 64-token K / V tile of its kv head in LDS once (double buffered,
-// the next tile's global loads are in flight while the current one is computed); a wave keeps
-// QT blocks of 16 queries as MFMA columns and walks the tiles up to its diagonal:
+// A wave keeps QT blocks of 16 queries as MFMA columns and walks the 64-token cache
+// tiles up to its diagonal:
 //   S[64 kv x 16 q]   = K_tile . Q^T              (A = K fragments, B = q rows)
 //   online softmax per query column (rows = kv tokens: 16 registers + two cross-quad shuffles)
 //   O^T[r_v x 16 q]  += V_tile^T . P^T            (P rounded to bf16; row sums by an all-ones MFMA)
-// Every K / V fragment is read from LDS once per wave and tile and reused for the QT query blocks.
+// Every K / V fragment is loaded once per wave and tile and reused for the QT query blocks.
+// Tiles below the diagonal take a lean unmasked path; the grid is ordered by work (longest query tiles first).
 #include "ea_common.h"
 #include "ea_epilogue.h"
-#include <cstdlib>
 
 namespace ea {
 
@@ -127,10 +126,9 @@ __device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&ac
   }
 }
 
-// ---------------------------------------------------------------------------
-// Variant D: every wave reads its K / V fragments straight from global memory (L2), next tile
-// prefetched into the registers the current one has just left.
-// ---------------------------------------------------------------------------
+// Every wave reads its K / V fragments straight from global memory (the four waves of a workgroup walk
+// the same tiles, so three of four reads hit in L1/L2); the next tile is requested into the registers the
+// current one has just left.  (Staging the tiles through LDS was measured and is slower here.)
 template <int KS, int NCB, int QT, int WPE>
 __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillArgs a) {
   const Geo& g = a.g;
@@ -263,193 +261,15 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
   write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
 }
 
-// ---------------------------------------------------------------------------
-// Variant L: the workgroup stages each 64-token K / V tile of its kv head in LDS once (double
-// buffered; the cache layout is the fragment order, so the copy is linear); the next tile's global
-// loads are in flight while the current one is computed.
-// ---------------------------------------------------------------------------
-template <int KS, int NCB, int QT, int WPE>
-__global__ __launch_bounds__(256, WPE) void prefill_bf16_lds_kernel(PrefillArgs a) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];   // 2 buffers x (K tile | V tile)
-  const Geo& g = a.g;
-  const int hb = g.n_heads * a.batch;
-  const int q_tile = a.n_qtiles - 1 - (int)(blockIdx.x / hb);
-  const int head = (blockIdx.x % hb) % g.n_heads, b = (blockIdx.x % hb) / g.n_heads;
-  const int kvh = head / g.group;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int col = lane & 15, quad = lane >> 4;
-  const int nck = g.r_k_pad >> 3;
-  constexpr int QW = QT * 16;
-  const int q0 = (q_tile * 4 + wave) * QW;
-
-  int64_t n64 = a.seq_len[b];
-  const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
-  if (n64 > cap) n64 = cap;
-  if (n64 < 0) n64 = 0;
-  const int len = (int)n64;
-  const int pos0 = len - a.n_q;
-  const int tiles_per_page = g.page_tokens / kTile;
-
-  bf16x8 qf[QT][KS];
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    const int qi = q0 + qb * 16 + col;
-    const uint16_t* qrow = a.q + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_k;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int k = ks * 32 + quad * 8;
-      qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
-    }
-  }
-  bf16x8 ones;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
-
-  f32x4 acc[QT][NCB], lacc[QT];
-  float m[QT];
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    m[qb] = -INFINITY;
-    lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  auto tiles_for = [&](int q_first) -> int {
-    if (q_first >= a.n_q) return 0;
-    const int pos_last = pos0 + min(a.n_q, q_first + QW) - 1;
-    return pos_last >= 0 ? min(pos_last, len - 1) / kTile + 1 : 0;
-  };
-  const int t_end = tiles_for(q0);
-  int t_end_wg = 0;
-#pragma unroll
-  for (int w = 0; w < 4; ++w) t_end_wg = max(t_end_wg, tiles_for((q_tile * 4 + w) * QW));
-  const int pos_first = pos0 + q0;
-
-  constexpr int KU = KS, VU = (NCB + 1) / 2;                    // 16-byte units per thread: 8*r_pad / 256 threads
-  const int k_units = g.r_k_pad * 8, v_units = g.r_v_pad * 8;
-  const int buf_elems = (g.r_k_pad + g.r_v_pad) * kTile;
-  u32x4 kreg[KU], vreg[VU];
-  auto tile_page = [&](int t) -> int {
-    const int page = a.page_table[(int64_t)b * g.max_pages + t / tiles_per_page];
-    return (page >= 0 && page < g.pool_pages) ? page : -1;
-  };
-  auto gload = [&](int t, int page) __attribute__((always_inline)) {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    const u32x4* kb = nullptr;
-    const u32x4* vb = nullptr;
-    if (page >= 0) {
-      kb = reinterpret_cast<const u32x4*>(a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
-                                          (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad));
-      vb = reinterpret_cast<const u32x4*>(a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
-                                          (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad));
-    }
-#pragma unroll
-    for (int i = 0; i < KU; ++i) kreg[i] = (page >= 0 && tid + 256 * i < k_units) ? kb[tid + 256 * i] : zero;
-#pragma unroll
-    for (int i = 0; i < VU; ++i) vreg[i] = (page >= 0 && tid + 256 * i < v_units) ? vb[tid + 256 * i] : zero;
-  };
-  auto lds_store = [&](int buf) __attribute__((always_inline)) {
-    u32x4* kd = reinterpret_cast<u32x4*>(smem + buf * buf_elems);
-    u32x4* vd = reinterpret_cast<u32x4*>(smem + buf * buf_elems + g.r_k_pad * kTile);
-#pragma unroll
-    for (int i = 0; i < KU; ++i)
-      if (tid + 256 * i < k_units) kd[tid + 256 * i] = kreg[i];
-#pragma unroll
-    for (int i = 0; i < VU; ++i)
-      if (tid + 256 * i < v_units) vd[tid + 256 * i] = vreg[i];
-  };
-
-  int page = -1;
-  if (t_end_wg > 0) {
-    page = tile_page(0);
-    gload(0, page);
-    lds_store(0);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < t_end_wg; ++t) {
-    const bool have_n = t + 1 < t_end_wg;
-    const int page_n = have_n ? tile_page(t + 1) : -1;
-    if (have_n) gload(t + 1, page_n);                           // in flight while this tile is computed
-
-    if (t < t_end) {
-      const uint16_t* ks_ = smem + (t & 1) * buf_elems;
-      const uint16_t* vs_ = ks_ + g.r_k_pad * kTile;
-      const int tok0 = t * kTile;
-      const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;
-      const int limit = page >= 0 ? len : 0;
-      bf16x8 kf[4][KS], vf[2][NCB];
-#pragma unroll
-      for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const int chunk = ks * 4 + quad;
-          kf[tb][ks] = chunk < nck ? *reinterpret_cast<const bf16x8*>(ks_ + (((tb * nck + chunk) * 16 + col) << 3))
-                                   : zero_frag();
-        }
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
-          vf[u][cb] = *reinterpret_cast<const bf16x8*>(vs_ + (((u * NCB + cb) * 64 + lane) << 3));
-      if (full) {
-#pragma unroll
-        for (int qb = 0; qb < QT; ++qb)
-          attend_block<KS, NCB, false>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad);
-      } else {
-        if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
-#pragma unroll
-        for (int qb = 0; qb < QT; ++qb) {
-          const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
-          attend_block<KS, NCB, true>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis, quad);
-        }
-      }
-    }
-    if (have_n) lds_store((t + 1) & 1);     // that buffer was last read in iteration t-1, which every wave has left
-    __syncthreads();
-    page = page_n;
-  }
-  write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
-}
-
-static int prefill_variant() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("EA_PREFILL_VARIANT");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
-
 template <int KS, int NCB>
 static void launch_prefill(const PrefillArgs& a_in, int32_t B, hipStream_t st) {
-  constexpr bool SMALL = (KS <= 2 && NCB <= 4);
-  const size_t lds = (size_t)2 * (a_in.g.r_k_pad + a_in.g.r_v_pad) * kTile * sizeof(uint16_t);   // <= 64 KiB
-  const int v = prefill_variant();
+  // 64 queries per wave while the accumulators fit the register file, 32 for the large ranks
+  constexpr int QT = (KS <= 2 && NCB <= 4) ? 4 : 2;
   PrefillArgs a = a_in;
   a.batch = B;
-  auto grid_for = [&](int qt) {
-    a.n_qtiles = (a.n_q + 64 * qt - 1) / (64 * qt);
-    return dim3((uint32_t)(a.n_qtiles * a.g.n_heads * B));
-  };
-#define EA_PREFILL(KERNEL, QT_, WPE_, LDS_)                              \
-  do {                                                                 \
-    const dim3 grid = grid_for(QT_);                                   \
-    KERNEL<KS, NCB, QT_, WPE_><<<grid, 256, LDS_, st>>>(a);            \
-  } while (0)
-  if constexpr (SMALL) {
-    switch (v) {
-      case 1: EA_PREFILL(prefill_bf16_lds_kernel, 4, 2, lds); break;
-      case 4: EA_PREFILL(prefill_bf16_direct_kernel, 2, 2, 0); break;
-      case 5: EA_PREFILL(prefill_bf16_lds_kernel, 2, 2, lds); break;
-      default: EA_PREFILL(prefill_bf16_direct_kernel, 4, 2, 0); break;
-    }
-  } else {
-    if (v == 1) EA_PREFILL(prefill_bf16_lds_kernel, 2, 2, lds);
-    else EA_PREFILL(prefill_bf16_direct_kernel, 2, 2, 0);
-  }
-#undef EA_PREFILL
+  a.n_qtiles = (a.n_q + 64 * QT - 1) / (64 * QT);
+  const dim3 grid((uint32_t)(a.n_qtiles * a.g.n_heads * B));
+  prefill_bf16_direct_kernel<KS, NCB, QT, 2><<<grid, 256, 0, st>>>(a);
 }
 
 template <int KS>
