@@ -1,17 +1,20 @@
 #!/usr/bin/env python3
-"""Benchmark of the Eigen Attention decode path on one MI355X.
+"""Benchmark of the Eigen Attention hot path on one MI355X.
 
-Workload (the paper's Introduction example, compressed to rank 80): a Llama-2-7B-shaped
-model, 32 attention layers, d_model 4096, 32 heads, d_head 128, r_k = r_v = 80, batch 16,
-32768 cached tokens per sequence; all 32 layers' rank-80 bf16 K/V pools (about 172 GB) are
-resident in HBM.  One step = one generated token = for every layer: fused low-rank QKV
-projection + cache append, decode attention over the 32768 cached tokens, output
-projection -- 32 x 3 library calls back to back on one stream.
+Default workload (`--workload cfg3`, the headline): the paper's Introduction example compressed to
+rank 80 -- a Llama-2-7B-shaped model, 32 attention layers, d_model 4096, 32 heads, d_head 128,
+r_k = r_v = 80, batch 16, 32768 cached tokens per sequence; all 32 layers' rank-80 bf16 K/V pools
+(about 172 GB) are resident in HBM.  One step = one generated token = for every layer: fused low-rank
+QKV projection + cache append, decode attention over the 32768 cached tokens, output projection --
+32 x 3 library calls back to back on one stream.
 
-Prints ONE JSON line.  `value` is the algorithmic HBM traffic of the whole step divided by
-its duration; `roofline` is for the dominant kernel (decode attention), timed live with
-events on the launch stream; `cpu_baseline` times the fp64 oracle on host cores on a
-bounded sample of the same attention workload.
+Other workloads (same step, other shapes): `cfg2` (n = 4096), `cfg5` (grouped-query attention, 32 query
+heads on 8 kv heads, B = 8, n = 16384, per-layer ranks drawn from {48,...,112}); `cfg4` is the causal
+prefill of B = 4 sequences of 8192 tokens at r = 64 (project_qkv + prefill_attn + out_proj of one layer).
+
+Prints ONE JSON line.  `value` is the algorithmic HBM traffic of the whole step divided by its duration
+(decode workloads) or the step's TFLOP/s (prefill); `roofline` is for the dominant kernel, timed live
+with events on the launch stream; `cpu_baseline` times the fp64 oracle on host cores on a bounded sample.
 """
 from __future__ import annotations
 
@@ -25,13 +28,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -56,70 +61,77 @@ def traffic_from_profiles():
     return None
 
 
-def cpu_oracle_baseline(n_streams: int, n_ctx: int, r: int, d_head: int):
-    """The fp64 oracle's decode attention on `n_streams` (sequence, head) streams of the bench
-    workload's shape, single-threaded BLAS, host-generated inputs with the same distribution."""
-    import numpy as np
-    from oracle import eigen_attention as ora
-    from paper_2408_05646_amd import synth
+def _timed_single_thread(fn):
     try:
         from threadpoolctl import threadpool_limits
     except Exception:       # pragma: no cover
         threadpool_limits = None
+
+    def run():
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            run()
+            return min(run(), run())
+    run()                   # pragma: no cover
+    return min(run(), run())
+
+
+def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int):
+    """The fp64 oracle's decode attention on `n_streams` (sequence, head) streams of the bench workload's
+    shape, single-threaded BLAS, host-generated inputs with the same distribution."""
+    import numpy as np
+    from oracle import eigen_attention as ora
+    from paper_2408_05646_amd import synth
     g = synth.rng(3, 777)
     heads = 32
     n_seq = max(1, n_streams // heads)
     # one sequence's worth of data, referenced by every sampled sequence (timing does not depend on values)
     K1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
     V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
-    K, V = [K1] * n_seq, [V1] * n_seq
     q = g.standard_normal((n_seq, heads, r))
-    cache = ora.RankCache.from_arrays(K, V)
-
-    def run():
-        t0 = time.perf_counter()
-        ora.decode_attention(q, cache, d_head)
-        return time.perf_counter() - t0
-
-    if threadpool_limits is not None:
-        with threadpool_limits(limits=1):
-            run()
-            dt = min(run(), run())
-    else:                   # pragma: no cover
-        run()
-        dt = min(run(), run())
+    cache = ora.RankCache.from_arrays([K1] * n_seq, [V1] * n_seq)
+    dt = _timed_single_thread(lambda: ora.decode_attention(q, cache, d_head))
     cache_bytes = n_seq * heads * n_ctx * 2 * r * 2          # what the GPU kernel would stream (bf16)
-    return {"value": cache_bytes / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{n_seq * heads} of 512 (sequence, head) streams of one layer (n={n_ctx}, r={r}), "
-                      f"fp64 numpy, {dt:.2f} s; one full 32-layer step would take {dt * 512 / (n_seq * heads) * 32:.0f} s",
-            "seconds": dt}
+    return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"decode attention of {n_seq * heads} (sequence, head) streams = one layer "
+                      f"(n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s; a full 32-layer step would take {dt * 32:.0f} s",
+            "seconds": round(dt, 3)}
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-
-    import paper_2408_05646_amd as ea
+def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
+    """The fp64 oracle's causal attention for the last `n_rows` query rows of one (sequence, head)."""
+    from oracle import eigen_attention as ora
     from paper_2408_05646_amd import synth
+    g = synth.rng(4, 777)
+    K = g.standard_normal((1, n_ctx, r))
+    V = g.standard_normal((1, n_ctx, r))
+    q = g.standard_normal((1, n_rows, 1, r))
+    cache = ora.RankCache.from_arrays([K], [V])
+    dt = _timed_single_thread(lambda: ora.prefill_attention(q, cache, d_head))
+    flops = sum(2 * (n_ctx - n_rows + j + 1) * 2 * r for j in range(n_rows))
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": f"causal attention of the last {n_rows} query rows of one (sequence, head) of the workload "
+                      f"(n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s",
+            "seconds": round(dt, 3)}
 
-    ea.load_library()                      # fail loudly if the HIP library is missing
-    torch.cuda.set_device(0)
+
+def bench_decode(args, torch, ea, synth):
     dev = "cuda"
-    s = synth.CFG3
+    s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[args.workload]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
-    H, Hkv, r_k, r_v, d = s.n_heads, s.n_kv_heads, s.r_k, s.r_v, s.d_model
-    desc = ea.LayerDesc(d, H, Hkv, s.d_head, r_k, r_v, ea.EA_BF16, P)
+    H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
+    ranks = synth.cfg5_layer_ranks(L) if args.workload == "cfg5" else tuple((s.r_k, s.r_v) for _ in range(L))
+    descs = [ea.LayerDesc(d, H, Hkv, s.d_head, rk, rv, ea.EA_BF16, P) for rk, rv in ranks]
     max_pages = n // P
     pool_pages = B * max_pages
-    n_qkv = H * r_k + Hkv * (r_k + r_v)
 
     free, _total = torch.cuda.mem_get_info()
-    lay = ea.cache_layout_query(desc)
-    need = L * pool_pages * (lay.k_page_elems + lay.v_page_elems) * 2
+    need = sum(pool_pages * (ea.cache_layout_query(dc).k_page_elems + ea.cache_layout_query(dc).v_page_elems) * 2
+               for dc in descs)
     if need + (12 << 30) > free:
         print(f"bench.py: {L} layers need {need / 2**30:.0f} GiB of HBM, only {free / 2**30:.0f} GiB free",
               file=sys.stderr)
@@ -128,42 +140,43 @@ def main():
     # ---- synthetic, seeded inputs, generated on the device (172 GB cannot be staged from the host).
     # Cached rank-space rows z.M + 0.05 eps.U with orthogonal M are N(0, (1 + 0.0025) I): fill the pools with that.
     gen = torch.Generator(device=dev)
-    gen.manual_seed(synth.BASE_SEED + 3)
+    gen.manual_seed(synth.BASE_SEED + int(args.workload[-1]))
     layers = []
     t_fill = time.perf_counter()
-    for l in range(L):
-        k_pool, v_pool = ea.alloc_pools(desc, pool_pages, zero=False)
+    for dc in descs:
+        n_qkv = H * dc.r_k + Hkv * (dc.r_k + dc.r_v)
+        k_pool, v_pool = ea.alloc_pools(dc, pool_pages, zero=False)
         k_pool.normal_(0.0, 1.00125, generator=gen)
         v_pool.normal_(0.0, 1.00125, generator=gen)
         perm = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32)   # pages in seeded random order
         layers.append(dict(
-            k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
-            wqkv_t=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
-            wo_t=ea.pack_weight((torch.randn((d, H * r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
+            desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
+            S=args.n_splits or ea.decode_auto_splits(dc, B, n),
+            wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
+            wo=ea.pack_weight((torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),
+            q_r=torch.empty((B, H, dc.r_k), dtype=torch.float32, device=dev),
+            o=torch.empty((B, H, dc.r_v), dtype=torch.float32, device=dev),
             y=torch.empty((B, d), dtype=torch.bfloat16, device=dev)))
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
 
     seq_before = torch.full((B,), n - 1, dtype=torch.int32, device=dev)    # the step appends token n-1 ...
     seq_after = torch.full((B,), n, dtype=torch.int32, device=dev)         # ... and attends over n tokens
-    q_r = torch.empty((B, H, r_k), dtype=torch.float32, device=dev)
-    o = torch.empty((B, H, r_v), dtype=torch.float32, device=dev)
-    S = args.n_splits or ea.decode_auto_splits(desc, B, n)
-    ws_bytes = ea.decode_workspace_bytes(desc, B, S)
+    ws_bytes = max(ea.decode_workspace_bytes(l["desc"], B, l["S"]) for l in layers)
     ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device=dev)
 
     def step(events=None):
-        for l, lay_ in enumerate(layers):
-            ea.project_qkv(desc, lay_["x"], lay_["wqkv_t"], q_r, lay_["k_pool"], lay_["v_pool"], lay_["page_table"],
+        for li, l in enumerate(layers):
+            ea.project_qkv(l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"],
                            seq_before, 1)
             if events is not None:
-                events[l][0].record()
-            ea.decode_attn(desc, q_r, lay_["k_pool"], lay_["v_pool"], lay_["page_table"], seq_after, o, n_splits=S,
-                           ws=ws)
+                events[li][0].record()
+            ea.decode_attn(l["desc"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_after, l["o"],
+                           n_splits=l["S"], ws=ws)
             if events is not None:
-                events[l][1].record()
-            ea.out_proj(desc, o.view(B, -1), lay_["wo_t"], lay_["y"])
+                events[li][1].record()
+            ea.out_proj(l["desc"], l["o"].view(B, -1), l["wo"], l["y"])
 
     for _ in range(args.warmup):
         step()
@@ -183,24 +196,33 @@ def main():
     attn_us = [a.elapsed_time(b_) * 1e3 for k in range(args.steps) for (a, b_) in ev[k]]
     attn_us_avg = sum(attn_us) / len(attn_us)
 
-    # ---- algorithmic bytes (what the method itself must move), per layer
-    cache_bytes = B * Hkv * n * (r_k + r_v) * 2
-    attn_bytes = cache_bytes + B * H * r_k * 4 + B * H * r_v * 4 + B * max_pages * 4
-    proj_bytes = n_qkv * d * 2 + B * d * 2 + B * H * r_k * 4 + B * Hkv * (r_k + r_v) * 2
-    out_bytes = H * r_v * d * 2 + B * H * r_v * 4 + B * d * 2
-    step_bytes = L * (attn_bytes + proj_bytes + out_bytes)
+    # ---- algorithmic bytes (what the method itself must move)
+    attn_bytes_sum, step_bytes = 0, 0
+    for dc in descs:
+        n_qkv = H * dc.r_k + Hkv * (dc.r_k + dc.r_v)
+        cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
+        attn = cache_bytes + B * H * dc.r_k * 4 + B * H * dc.r_v * 4 + B * max_pages * 4
+        proj = n_qkv * d * 2 + B * d * 2 + B * H * dc.r_k * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
+        outp = H * dc.r_v * d * 2 + B * H * dc.r_v * 4 + B * d * 2
+        attn_bytes_sum += attn
+        step_bytes += attn + proj + outp
+    attn_bytes = attn_bytes_sum / L
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     attn_gbps = attn_bytes / (attn_us_avg * 1e-6) / 1e9
+    splits = sorted(set(l["S"] for l in layers))
+    kern = "decode_bf16_kernel" + ("" if splits == [1] else " + merge_splits_kernel") + " (one ea_decode_attn call)"
 
+    rank_note = f"r_k=r_v={s.r_k}" if args.workload != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
-        "metric": "low-rank decode attn: achieved HBM GB/s over the whole decode step (B=16, n=32k, r=80)",
+        "metric": "low-rank decode attn: achieved HBM GB/s over the whole decode step"
+                  + (" (B=16, n=32k, r=80)" if args.workload == "cfg3" else f" ({args.workload})"),
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"cfg3 long-context decode: Llama-2-7B-shaped, {L} layers resident, B={B}, n={n}, "
-                               f"H={H}, d_h={s.d_head}, r_k=r_v={r_k}, bf16 paged cache (page {P} tokens, "
+        "config": {"workload": f"{args.workload} decode: Llama-2-7B-shaped, {L} layers resident, B={B}, n={n}, "
+                               f"H={H}, H_kv={Hkv}, d_h={s.d_head}, {rank_note}, bf16 paged cache (page {P} tokens, "
                                f"pages in random order), project_qkv + decode_attn + out_proj per layer",
-                   "layers": L, "batch": B, "n_ctx": n, "r_k": r_k, "r_v": r_v, "page_tokens": P, "n_splits": S},
+                   "layers": L, "batch": B, "n_ctx": n, "page_tokens": P, "n_splits": splits},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "us_per_step": round(ms_per_step * 1e3, 1),
         "tokens_per_s": round(B / (ms_per_step * 1e-3), 1),
@@ -208,9 +230,9 @@ def main():
         "step_algorithmic_bytes": step_bytes,
         "fill_seconds": round(t_fill, 1), "timed_wall_seconds": round(wall, 3),
         "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": traffic_from_profiles(),
-                     "kernel": "ea_decode_attn (split kernel + merge)", "bytes_per_launch": attn_bytes,
-                     "us_per_launch": round(attn_us_avg, 2)},
+                     "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic_from_profiles() if args.workload == "cfg3" else None,
+                     "kernel": kern, "bytes_per_launch": round(attn_bytes), "us_per_launch": round(attn_us_avg, 2)},
     }
 
     # ---- the same kernel at full rank (standard attention, d_h = 128) on one layer-sized buffer
@@ -235,11 +257,12 @@ def main():
         torch.cuda.synchronize()
         full_us = f0.elapsed_time(f1) * 1e3 / reps
         full_bytes = B * Hkv * n * 2 * s.d_head * 2
+        mean_rank = sum(rk + rv for rk, rv in ranks) / (2 * L)
         result["fullrank_baseline"] = {
             "decode_attn_us_per_layer": round(full_us, 1), "achieved_GBps": round(full_bytes / full_us / 1e3, 1),
             "latency_ratio_lowrank_over_fullrank": round(attn_us_avg / full_us, 4),
-            "ratio_predicted_by_rank": round(r_k / s.d_head, 4),
-            "note": "same kernel, r_k = r_v = d_h = 128, same B, n and page table, one 8.6 GB layer buffer"}
+            "ratio_predicted_by_rank": round(mean_rank / s.d_head, 4),
+            "note": "same kernel, r_k = r_v = d_h = 128, same B, n and page table, one layer-sized buffer"}
         del fk, fv
 
     if args.calibrate_copy:
@@ -251,8 +274,103 @@ def main():
         result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_oracle_baseline(args.cpu_streams, n, r_k, s.d_head)
+        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams, n, ranks[0][0], s.d_head)
+    return result
 
+
+def bench_prefill(args, torch, ea, synth):
+    dev = "cuda"
+    s = synth.CFG4
+    B, n, P = s.batch, s.n_ctx, args.page_tokens
+    H, d, r = s.n_heads, s.d_model, s.r_k
+    desc = ea.LayerDesc(d, H, H, s.d_head, r, r, ea.EA_BF16, P)
+    max_pages = n // P
+    pool_pages = B * max_pages
+    n_qkv = 3 * H * r
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED + 4)
+    k_pool, v_pool = ea.alloc_pools(desc, pool_pages)
+    pt = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32).reshape(B, max_pages).contiguous()
+    seq0 = torch.zeros((B,), dtype=torch.int32, device=dev)
+    seq1 = torch.full((B,), n, dtype=torch.int32, device=dev)
+    x = torch.randn((B * n, d), generator=gen, device=dev).to(torch.bfloat16)
+    wqkv = ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
+    wo = ea.pack_weight((torch.randn((d, H * r), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
+    q_r = torch.empty((B * n, H, r), dtype=torch.bfloat16, device=dev)
+    o = torch.empty((B, n, H, r), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((B * n, d), dtype=torch.bfloat16, device=dev)
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        ea.project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, pt, seq0, n)
+        if events is not None:
+            events[1].record()
+        ea.prefill_attn(desc, q_r.view(B, n, H, r), k_pool, v_pool, pt, seq1, o)
+        if events is not None:
+            events[2].record()
+        ea.out_proj(desc, o.view(B * n, H * r), wo, y)
+        if events is not None:
+            events[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(args.steps):
+        step(ev[k])
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    t = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps for i in range(3)]
+    f_proj = 2 * B * n * d * n_qkv
+    f_attn = B * H * n * n * 2 * r            # causal-counted: 2 * (n^2 / 2) * (r_k + r_v) per (sequence, head)
+    f_out = 2 * B * n * H * r * d
+    flops = f_proj + f_attn + f_out
+
+    def tf(f, ms):
+        return f / (ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "low-rank causal prefill: TFLOP/s of project_qkv + prefill_attn + out_proj (cfg4)",
+        "value": round(tf(flops, ms_per_step), 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg4 causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, "
+                               f"d_h={s.d_head}, r_k=r_v={r}, bf16, cache written to a paged pool (page {P} tokens, "
+                               f"random order)",
+                   "batch": B, "n_ctx": n, "r_k": r, "r_v": r, "page_tokens": P},
+        "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
+        "kernels": {"project_qkv": {"ms": round(t[0], 4), "tflops": round(tf(f_proj, t[0]), 1)},
+                    "prefill_attn": {"ms": round(t[1], 4), "tflops_causal_counted": round(tf(f_attn, t[1]), 1),
+                                     "tflops_dense_counted": round(tf(2 * f_attn, t[1]), 1)},
+                    "out_proj": {"ms": round(t[2], 4), "tflops": round(tf(f_out, t[2]), 1)}},
+        "roofline": {"bound": "mfma", "achieved": round(tf(f_proj, t[0]), 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf(f_proj, t[0]) / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "gemm_bf16_tiled_kernel (ea_project_qkv, the longest of the three calls)",
+                     "flops_per_launch": f_proj, "us_per_launch": round(t[0] * 1e3, 1)},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_oracle_prefill(512, n, r, s.d_head)
+    return result
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2408_05646_amd as ea
+    from paper_2408_05646_amd import synth
+
+    ea.load_library()                      # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    result = bench_prefill(args, torch, ea, synth) if args.workload == "cfg4" else bench_decode(args, torch, ea, synth)
     print(json.dumps(result))
 
 

@@ -141,7 +141,8 @@ def test_packed_weight_size():
 
 def test_auto_splits_fill_the_chip():
     d = ea.LayerDesc(4096, 32, 32, 128, 80, 80, ea.EA_BF16, 64)
-    assert ea.decode_auto_splits(d, 16, 32768) == 4          # 512 streams x 4 = 2048 workgroups
+    assert ea.decode_auto_splits(d, 16, 32768) == 1          # 512 streams: one workgroup per resident slot
     assert ea.decode_auto_splits(d, 16, 64) == 1
     g = ea.LayerDesc(4096, 32, 8, 128, 80, 80, ea.EA_BF16, 64)
-    assert ea.decode_auto_splits(g, 8, 16384) == 32           # 64 streams, 256 tiles each
+    assert ea.decode_auto_splits(g, 8, 16384) == 8            # 64 streams x 8 = 512 workgroups
+    assert ea.decode_auto_splits(g, 1, 16384) == 32           # 8 streams: capped at 8 tiles per workgroup
