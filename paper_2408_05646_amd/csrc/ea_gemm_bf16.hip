@@ -128,15 +128,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
 }
 
 // ---------------------------------------------------------------------------
-// Skinny kernel: M <= 16*MT rows.  One workgroup owns NB blocks of 16 output channels; its four
-// waves interleave the 32-wide K steps, each keeps UN steps of weight fragments in flight
-// (nontemporal: the weights are streamed exactly once), and the partial sums meet in LDS.
+// Skinny kernel: M <= 16*MT rows.  One workgroup owns NB blocks of 16 output channels; its eight
+// waves interleave the 32-wide K steps and each requests all the weight fragments of a round at once
+// (for K <= 4096 and M <= 16 that is the whole job: one memory round trip; nontemporal, the weights are
+// streamed exactly once); the partial sums meet in LDS.
 // A float A operand is split in hi + lo bf16 halves so it loses no precision.
 // ---------------------------------------------------------------------------
 template <typename Epilogue, bool A_F32, int MT, int NB>
-__global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __restrict__ A,
+__global__ __launch_bounds__(512) void gemm_bf16_skinny_kernel(const void* __restrict__ A,
                                                                const uint16_t* __restrict__ Wt, int32_t M, int32_t N,
                                                                int32_t K, Epilogue ep) {
+  constexpr int WAVES = 8;
+  constexpr int UN = 16 / MT;                              // k steps per wave and round, all requested up front
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 15, quad = lane >> 4;
   const int n0 = blockIdx.x * (16 * NB);
@@ -155,40 +158,66 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __res
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  constexpr int UN = 8;
-  for (int s0 = wave; s0 < steps; s0 += 4 * UN) {       // this wave: steps s0, s0 + 4, ..., s0 + 4*(UN-1)
+  // where this thread's outputs will go (its 4 rows of one column after the reduction): the dependent
+  // address loads of the epilogue overlap with the weight stream
+  typename Epilogue::Slot slot[4];
+  const bool writer = tid < MT * NB * 64;
+  {
+    const int ln = tid & 63, nb = (tid >> 6) % NB, i = (tid >> 6) / NB;
+    const int c = n0 + nb * 16 + (ln & 15);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int r = i * 16 + (ln >> 4) * 4 + e;
+      slot[e] = (writer && r < M && c < N) ? ep.locate(r, c) : typename Epilogue::Slot{};
+    }
+  }
+
+  // the waves interleave the k steps (neighbouring waves stream neighbouring kilobytes of the weights)
+  for (int s0 = wave; s0 < steps; s0 += WAVES * UN) {     // this wave: steps s0, s0 + WAVES, ...
     bf16x8 bw[UN][NB];
 #pragma unroll
     for (int u = 0; u < UN; ++u)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb)
-        bw[u][nb] = (n_ok[nb] && s0 + 4 * u < steps)
-                        ? __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(wfrag[nb] + ((int64_t)(s0 + 4 * u) << 9)))
+        bw[u][nb] = (n_ok[nb] && s0 + WAVES * u < steps)
+                        ? __builtin_nontemporal_load(
+                              reinterpret_cast<const bf16x8*>(wfrag[nb] + ((int64_t)(s0 + WAVES * u) << 9)))
                         : zero_frag();
+    // activations: a few rows, shared by every workgroup (L2 hits); float input is kept whole until it is split
+    bf16x8 ab[A_F32 ? 1 : UN][MT];
+    f32x4 af32[A_F32 ? UN : 1][MT][2];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int st = s0 + 4 * u;
-      if (st >= steps) break;
-      const int64_t koff = (int64_t)st * 32 + quad * 8;
+      const int64_t koff = (int64_t)(s0 + WAVES * u) * 32 + quad * 8;
+      const bool ok = s0 + WAVES * u < steps;
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int row = i * 16 + col;
         if (!A_F32) {
-          const bf16x8 af = row < M ? load_frag<false>(A, (int64_t)row * K + koff) : zero_frag();
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb) acc[i][nb] = mfma16(af, bw[u][nb], acc[i][nb]);
+          ab[u][i] = (ok && row < M) ? load_frag<false>(A, (int64_t)row * K + koff) : zero_frag();
         } else {
-          bf16x8 hi = zero_frag(), lo = zero_frag();
-          if (row < M) {
-            const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(A) + (int64_t)row * K + koff);
-            const float4 v0 = p[0], v1 = p[1];
-            const float f[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+          const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+          const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(A) + (int64_t)row * K + koff);
+          af32[u][i][0] = (ok && row < M) ? p[0] : z;
+          af32[u][i][1] = (ok && row < M) ? p[1] : z;
+        }
+      }
+    }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              const __bf16 h = (__bf16)f[j];
-              hi[j] = h;
-              lo[j] = (__bf16)(f[j] - (float)h);
-            }
+    for (int u = 0; u < UN; ++u) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        if (!A_F32) {
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[i][nb] = mfma16(ab[u][i], bw[u][nb], acc[i][nb]);
+        } else {
+          bf16x8 hi, lo;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float f = af32[u][i][j >> 2][j & 3];
+            const __bf16 h = (__bf16)f;
+            hi[j] = h;
+            lo[j] = (__bf16)(f - (float)h);
           }
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
@@ -199,20 +228,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_skinny_kernel(const void* __res
       }
     }
   }
-  __shared__ f32x4 red[4][MT][NB][64];
+  __shared__ f32x4 red[WAVES][MT][NB][64];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) red[wave][i][nb][lane] = acc[i][nb];
   __syncthreads();
-  for (int idx = tid; idx < MT * NB * 64; idx += 256) {
-    const int ln = idx & 63, nb = (idx >> 6) % NB, i = (idx >> 6) / NB;
-    const f32x4 v = red[0][i][nb][ln] + red[1][i][nb][ln] + red[2][i][nb][ln] + red[3][i][nb][ln];
+  static_assert(MT * NB * 64 <= 64 * WAVES, "one output quad per thread");
+  if (writer) {
+    const int ln = tid & 63, nb = (tid >> 6) % NB, i = (tid >> 6) / NB;
+    f32x4 v = red[0][i][nb][ln];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) v += red[w][i][nb][ln];
     const int c = n0 + nb * 16 + (ln & 15);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int r = i * 16 + (ln >> 4) * 4 + e;
-      if (r < M && c < N) ep(r, c, v[e]);
+      if (r < M && c < N) ep.commit(slot[e], r, c, v[e]);
     }
   }
 }
@@ -241,7 +273,9 @@ __device__ __forceinline__ void acc_coord(bool swap, int r0, int c0, int i, int 
 struct QkvEpBf16 {
   QkvDest d;
   int32_t fast_cols;
-  __device__ __forceinline__ void operator()(int r, int c, float v) const { qkv_store<true>(d, r, c, v); }
+  typedef QkvSlot Slot;
+  __device__ __forceinline__ Slot locate(int r, int c) const { return qkv_locate<true>(d, r, c); }
+  __device__ __forceinline__ void commit(const Slot& s, int r, int c, float v) const { qkv_commit<true>(d, s, r, c, v); }
   __device__ __forceinline__ bool swap_for(int c0) const {
     const Geo& g = d.g;
     return fast_cols && c0 < g.n_heads * g.r_k + g.n_kv_heads * g.r_k;
@@ -346,7 +380,11 @@ struct QkvEpBf16 {
 struct PlainEpBf16 {
   uint16_t* y;
   int32_t N;
-  __device__ void operator()(int r, int c, float v) const { y[(int64_t)r * N + c] = f32_to_bf16_rne(v); }
+  struct Slot {
+    uint16_t* p = nullptr;
+  };
+  __device__ __forceinline__ Slot locate(int r, int c) const { return Slot{y + (int64_t)r * N + c}; }
+  __device__ __forceinline__ void commit(const Slot& s, int, int, float v) const { *s.p = f32_to_bf16_rne(v); }
   __device__ __forceinline__ bool swap_for(int) const { return true; }
   template <int MI>
   __device__ __forceinline__ void store(bool, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int Ncols, int col,
@@ -377,8 +415,8 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
   const uint16_t* w = (const uint16_t*)Wt;
   if (M <= 64) {
     // two channel blocks per workgroup when that still leaves about one workgroup per compute unit
-    const int nb = (N / 32 >= 200) ? 2 : 1;
-    dim3 grid((N + 16 * nb - 1) / (16 * nb)), block(256);
+    const int nb = (!A_F32 && N / 32 >= 200) ? 2 : 1;     // (float activations need the registers themselves)
+    dim3 grid((N + 16 * nb - 1) / (16 * nb)), block(512);
     const int mt = (M + 15) / 16;
 #define EA_SKINNY(MT_, NB_) gemm_bf16_skinny_kernel<Epilogue, A_F32, MT_, NB_><<<grid, block, 0, st>>>(A, w, M, N, K, ep)
     if (nb == 2) {
