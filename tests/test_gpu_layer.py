@@ -248,3 +248,44 @@ def test_bf16_decode_step_end_to_end():
     y_ref = ora.decode_step(x_hist[:, n0], folded_q, cache, 128)
     assert_close(y_pre.float().cpu().numpy().reshape(B, n0, 512), y_pre_ref, TOL_BF16, "prefill y")
     assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, "decode y")
+
+
+def test_decode_step_is_graph_capturable():
+    """The library only enqueues kernels on the caller's stream (no allocation, no sync, no memset), so a whole
+    decode step can be captured in a HIP graph; every replay must reproduce the eager result."""
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(24)
+    Wq, Wk, Wv, Wo, Uk, Uv = make_weights(desc, g)
+    wqkv, wo, _ = device_weights(desc, ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, 8, 2))
+    B, n0, S = 4, 700, 3
+    K0, V0 = random_cache(desc, [n0] * B, g)
+    dc = DeviceCache(desc, K0, V0, g, extra_len=1)
+    x = to_dev(desc, quantize(desc, synth.gaussian(g, (B, 512))))
+    q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ea.decode_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    seq_after = dc.seq_len + 1
+
+    def step():
+        ea.project_qkv(desc, x, wqkv, q_r, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, 1)
+        ea.decode_attn(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, seq_after, o, n_splits=S, ws=ws)
+        ea.out_proj(desc, o.view(B, -1), wo, y)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        y.zero_(); o.zero_(); q_r.zero_()        # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep} differs from the eager result"
