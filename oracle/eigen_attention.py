@@ -299,6 +299,62 @@ def eigen_attention_block_projected_back(x_hist, Wq, Wk, Wv, Wo, Uk, Uv, n_heads
     return heads_out @ Wo
 
 
+# --------------------------------------------------------------------------
+# Sec. 4.3 (Rotational Position Embedding): the variant for models with RoPE
+# --------------------------------------------------------------------------
+def rope_rotate(x, pos, base: float = 10000.0):
+    """Rotary position embedding of d-dimensional rows x [.., d] at integer positions pos [..]:
+    the pairs (x[2j], x[2j+1]) are rotated by the angle pos * base**(-2j/d)  (Eq. 9: Q R, K R).
+
+    Reading (the paper cites the RoFormer definition and prints only "Q R"): adjacent channels form a
+    pair; x'[2j] = x[2j] cos - x[2j+1] sin, x'[2j+1] = x[2j] sin + x[2j+1] cos."""
+    x = np.asarray(x, F64)
+    d = x.shape[-1]
+    assert d % 2 == 0
+    theta = np.asarray(base, F64) ** (-np.arange(0, d, 2, dtype=F64) / d)
+    ang = np.asarray(pos, F64)[..., None] * theta
+    c, sn = np.cos(ang), np.sin(ang)
+    out = np.empty_like(x)
+    out[..., 0::2] = x[..., 0::2] * c - x[..., 1::2] * sn
+    out[..., 1::2] = x[..., 0::2] * sn + x[..., 1::2] * c
+    return out
+
+
+def decode_attention_rope(q, cache: RankCache, Uk, d_head: int, base: float = 10000.0):
+    """Generation-phase Eigen Attention for a RoPE model (Sec. 4.3, Eq. 10).
+
+    q [B, H, d_h]: the FULL-rank query of the new token (not projected, not yet rotated).
+    cache.K[b][g]: rank-r_k keys k_r = k U^K; Uk [d_h, r_k] is ONE basis shared by all heads.
+    Each cached key is brought back to d_h dimensions, k' = U^K k_r, then rotated to its position t;
+    the query is rotated to its position len_b - 1 (the token just appended).  Values are untouched.
+    """
+    q = np.asarray(q, F64)
+    Uk = np.asarray(Uk, F64)
+    B, H, d_h = q.shape
+    assert d_h == d_head and Uk.shape[0] == d_h
+    out = np.zeros((B, H, cache.r_v), F64)
+    for b in range(B):
+        n = cache.seq_len(b)
+        if n == 0:
+            raise ValueError("decode over an empty sequence")
+        for i in range(H):
+            g = _kv_head_of(i, H, cache.n_kv_heads)
+            K_up = cache.K[b][g] @ Uk.T                               # [n, d_h]: (U^K)^T applied back
+            K_pos = rope_rotate(K_up, np.arange(n), base)
+            q_pos = rope_rotate(q[b, i], n - 1, base)
+            s = (K_pos @ q_pos) / math.sqrt(d_head)
+            out[b, i] = softmax(s) @ cache.V[b][g]
+    return out
+
+
+def standard_rope_decode(q, K_full, V, d_head: int, base: float = 10000.0):
+    """Standard attention with RoPE for one head: q [d_h] at position n-1, K_full [n, d_h], V [n, r_v]."""
+    K_full = np.asarray(K_full, F64)
+    n = K_full.shape[0]
+    s = (rope_rotate(K_full, np.arange(n), base) @ rope_rotate(np.asarray(q, F64), n - 1, base)) / math.sqrt(d_head)
+    return softmax(s) @ np.asarray(V, F64)
+
+
 def project_to_basis(A, U):
     """Rank-space coordinates of d_h-dimensional rows: A [.., d_h] U [d_h, r] (what Eq. 8 caches)."""
     return np.asarray(A, F64) @ np.asarray(U, F64)
