@@ -166,6 +166,26 @@ EA_API int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const 
                    int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
                    void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* Generation-phase attention for models with rotary position embedding
+ * (Sec. 4.3, Eq. 9-10): the query keeps all d_head channels, the cache holds the
+ * rank-r_k keys k_r = k U^K of ONE basis U^K shared by all heads, and each cached
+ * key is brought back to d_head channels (U^K k_r) before the rotation:
+ *   s_t = rot(q, n-1) . rot(U^K K_r[t], t) / sqrt(d_h),  t < n = seq_len[b],
+ *   p = Softmax(s), o = sum_t p_t V_r[t],
+ * where rot(x, pos) turns the channel pair (2j, 2j+1) by pos * rope_base^(-2j/d_h)
+ * (x'[2j] = x[2j] cos - x[2j+1] sin, x'[2j+1] = x[2j] sin + x[2j+1] cos).
+ * The query is the token appended last (position seq_len[b] - 1).
+ *   dev_q   [B, H, d_head] float, NOT rotated
+ *   dev_u_k [d_head, r_k] row-major, desc dtype (EA_F32 float, EA_BF16 bfloat16: the basis enters the
+ *           matrix cores in the precision of the cache)
+ *   everything else as ea_decode_attn (same workspace size, same split rule).
+ * Requires r_k <= d_head; EA_BF16: d_head 64 or 128; EA_F32: d_head even, <= 256. */
+EA_API int ea_decode_attn_rope(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
+                    int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Prefill-phase attention in rank space, Eq. (2) with a causal mask: the n
  * queries of sequence b are its last n cached positions (query j sits at
  * position seq_len[b] - n + j and sees positions <= its own).

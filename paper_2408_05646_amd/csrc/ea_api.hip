@@ -189,6 +189,45 @@ int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* d
   return rc;
 }
 
+int ea_decode_attn_rope(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
+                        const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
+                        const int32_t* dev_seq_len, float* dev_out, int32_t B, int32_t max_pages, int32_t pool_pages,
+                        int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q || !dev_u_k || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || max_pages <= 0 || pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (!(rope_base > 1.0) || !(rope_base < 1e30)) return EA_ERR_ARG;
+  if (desc->r_k > desc->d_head) return EA_ERR_SHAPE;
+  if (desc->dtype == EA_BF16 ? (desc->d_head != 64 && desc->d_head != 128)
+                             : (desc->d_head % 2 != 0 || desc->d_head > 256))
+    return EA_ERR_SHAPE;
+  if (!aligned16(dev_q) || !aligned16(dev_u_k) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) ||
+      !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  if (n_splits == 0) {
+    const int64_t cap_tokens = (int64_t)max_pages * desc->page_tokens;
+    n_splits = ea_decode_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
+  }
+  if (n_splits > 1) {
+    if (!dev_ws || !aligned16(dev_ws)) return EA_ERR_WORKSPACE;
+    if (ws_bytes < ea_decode_workspace_bytes(desc, B, n_splits)) return EA_ERR_WORKSPACE;
+  }
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  if (desc->dtype == EA_BF16)
+    rc = decode_rope_bf16(desc, g, dev_q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len,
+                          dev_out, B, n_splits, (float*)dev_ws, st);
+  else
+    rc = decode_rope_f32(desc, g, dev_q, (const float*)dev_u_k, rope_base, (const float*)dev_k_pool, (const float*)dev_v_pool,
+                         dev_page_table, dev_seq_len, dev_out, B, n_splits, (float*)dev_ws, st);
+  if (rc != EA_OK) return rc;
+  if (n_splits > 1) rc = merge_splits(g, (const float*)dev_ws, dev_out, B, n_splits, st);
+  return rc;
+}
+
 int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
                     const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out, int32_t B, int32_t n,
                     int32_t max_pages, int32_t pool_pages, void* stream) {

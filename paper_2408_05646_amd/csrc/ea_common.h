@@ -129,6 +129,12 @@ int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void
 int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
                hipStream_t st);
+int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
+                     const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                     float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);
+int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
+                    const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                    float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st);
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,

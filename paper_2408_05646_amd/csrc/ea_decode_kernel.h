@@ -1,0 +1,474 @@
+// Generation-phase attention over the rank-r bf16 paged cache (Eq. 3 with the
+// rank-r operands of Eq. 7): split-K flash-decode on the gfx950 matrix cores.
+//
+// One workgroup (4 waves) owns one (sequence, kv head, split).  Each wave streams
+// whole 64-token tiles: the cache layout is the MFMA operand order, so every
+// global load is one contiguous 1 KiB wave access and nothing is shuffled
+// between lanes.  Per tile and wave:
+//   S[64 tok x 16 head cols]  = K_tile . q^T        v_mfma_f32_16x16x32_bf16, q split in hi+lo bf16
+//   online softmax in the D layout (lane = head column, 4 token rows per register quad)
+//   O^T[r_v x 16 head cols]  += V_tile^T . P^T      P rounded to bf16, row sums by an all-ones MFMA
+// The 16 head columns carry the G = H / H_kv query heads that share the kv head
+// (unused columns hold zeros), so grouped-query attention costs no extra traffic.
+//
+// NKK > 0 selects the variant for models with rotary position embedding (Sec. 4.3, Eq. 10): the query
+// arrives with all d_head = 32*NKK channels, and each 16-token block of cached rank-r keys is first
+// brought back to d_head channels on the matrix cores (K' = U^K k_r, the basis shared by all heads kept
+// in LDS in MFMA operand order), rotated to its position, rounded to bf16 and only then multiplied
+// with the query (hi + lo bf16).  Only the position DIFFERENCE enters a score, so the rotation is split: the query is
+// rotated (in fp32, once per iteration of a wave) by the distance between its own position and the first
+// token of the iteration, each key by its offset inside the iteration (a constant table in LDS).
+#pragma once
+#include <type_traits>
+#include "ea_common.h"
+
+namespace ea {
+
+constexpr float kLazy = 8.0f;
+
+struct DecodeArgs {
+  const float* q;
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  const int32_t* page_table;
+  const int32_t* seq_len;
+  float* out;
+  float* ws;
+  Geo g;
+  int32_t n_splits;
+  float scale_log2;   // log2(e) / sqrt(d_head)
+  // rotary variant only
+  const uint16_t* u_k;   // [d_head, r_k] bf16 basis shared by all heads
+  int32_t d_head;
+  double log2_base;   // log2 of the rotary base
+};
+
+// cos and sin of an angle given in REVOLUTIONS.  The whole turns are dropped in double precision (positions
+// reach 10^5 and more radians, where single precision no longer resolves the angle); v_cos_f32 / v_sin_f32 take
+// the remaining fraction of a turn directly.
+__device__ __forceinline__ void rot_turns(double x, float& c, float& s) {
+  const float f = (float)(x - rint(x));
+  c = __builtin_amdgcn_cosf(f);
+  s = __builtin_amdgcn_sinf(f);
+}
+
+template <int NCB>
+struct MergeSmem {
+  float m[4][16];
+  float l[4][16];
+  float acc[4][16][NCB * 16];
+};
+
+// Rotation tables of the rotary variant.  Pair j = 16*kk + 4*quad + i of lane (col, quad) rotates by
+// theta_j = base^(-2j/d_head) per position.
+template <int TBN, int NKK, int KS>
+struct RopeSmem {
+  // A operand of the up-projection: row m of block 2*kk + comp is channel 2*(16*kk + m) + comp of the basis
+  bf16x8 uf[2 * NKK][KS][64];
+  f32x4 tc[TBN][NKK][64], ts[TBN][NKK][64];   // angle (16*tb + col) * theta_j: a key's offset in the iteration
+  f32x4 sc[NKK][64], ss[NKK][64];             // angle -(4 * 16*TBN) * theta_j: one step of a wave
+  double turns[NKK * 16];                     // theta_j / (2 pi)
+};
+struct NoSmem {};
+
+constexpr int kReseed = 32;   // iterations between exact re-computations of the rotated query
+
+// TBN = 16-token blocks handled per loop iteration: 4 (a whole 64-token tile) or 2 (half a tile, for the
+// large ranks whose fragments would not fit the register file otherwise).
+template <int KS, int NCB, int TBN, int WPE, int NKK>
+__global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
+  constexpr bool ROPE = NKK > 0;
+  __shared__ union {
+    MergeSmem<NCB> mg;
+    std::conditional_t<ROPE, RopeSmem<TBN, ROPE ? NKK : 1, KS>, NoSmem> rp;
+  } sm;
+  constexpr int UN = TBN / 2;            // 32-token groups per iteration
+  constexpr int SUB = 4 / TBN;           // iterations per 64-token tile
+  constexpr int TOK = TBN * 16;          // tokens per iteration
+  const Geo& g = a.g;
+  // neighbouring workgroups take neighbouring kv heads of the same pages: their slabs are adjacent in memory
+  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 15, quad = lane >> 4;
+  const int G = g.group;
+  const int nck = g.r_k_pad >> 3;
+
+  int64_t n64 = a.seq_len[b];
+  const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
+  if (n64 > cap) n64 = cap;
+  if (n64 < 0) n64 = 0;
+  const int n = (int)n64;
+  const int n_tiles = (n + kTile - 1) / kTile;
+  const int per = (n_tiles + a.n_splits - 1) / a.n_splits;
+  const int t_begin = split * per;
+  const int t_end = min(n_tiles, t_begin + per);
+  const int tiles_per_page = g.page_tokens / kTile;
+
+  // B operand of the score MFMA: q^T, lane (col, quad) holds channels 32*ks + 8*quad .. +7 of head col.
+  bf16x8 qhi[ROPE ? 1 : KS], qlo[ROPE ? 1 : KS];
+  if constexpr (!ROPE) {
+    const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + col) * g.r_k;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int k = ks * 32 + quad * 8 + j;
+        const float v = (col < G && k < g.r_k) ? qrow[k] : 0.f;
+        const __bf16 hi = (__bf16)v;
+        qhi[ks][j] = hi;
+        qlo[ks][j] = (__bf16)(v - (float)hi);
+      }
+    }
+  }
+  bf16x8 ones;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
+
+  f32x4 acc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 lacc = {0.f, 0.f, 0.f, 0.f};
+  float m = -INFINITY;
+
+  bf16x8 kf[TBN][KS], vf[UN][NCB];
+
+  // ---- rotary variant: basis fragments, rotation tables, rotated query
+  constexpr int NK1 = ROPE ? NKK : 1;
+  float qa[NK1][4], qb[NK1][4];  // the query's pairs j = 16*kk + 4*quad + i, rotated to the current iteration
+  bf16x8 qfh[NK1], qfl[NK1];     // ... as B operand of the score MFMA (hi + lo): slot 4*comp + i of k-step kk
+  const int pos_q = n - 1;       // the query is the token appended last
+  auto seed_q = [&](int it) {
+    if constexpr (ROPE) {
+    const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + col) * a.d_head;
+    const double rel = (double)(pos_q - it * TOK);
+#pragma unroll
+    for (int kk = 0; kk < NK1; ++kk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int j = kk * 16 + quad * 4 + i;
+        const float q0 = col < G ? qrow[2 * j] : 0.f, q1 = col < G ? qrow[2 * j + 1] : 0.f;
+        float c, sn;
+        rot_turns(rel * sm.rp.turns[j], c, sn);
+        qa[kk][i] = q0 * c - q1 * sn;
+        qb[kk][i] = q0 * sn + q1 * c;
+      }
+    }
+    }
+  };
+  auto step_q = [&](int tl) {
+    if constexpr (ROPE) {
+#pragma unroll
+    for (int kk = 0; kk < NK1; ++kk) {
+      const f32x4 c4 = sm.rp.sc[kk][tl], s4 = sm.rp.ss[kk][tl];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float x0 = qa[kk][i], x1 = qb[kk][i];
+        qa[kk][i] = x0 * c4[i] - x1 * s4[i];
+        qb[kk][i] = x0 * s4[i] + x1 * c4[i];
+      }
+    }
+    }
+  };
+  auto pack_q = [&]() {
+    if constexpr (ROPE) {
+#pragma unroll
+    for (int kk = 0; kk < NK1; ++kk) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const __bf16 ha = (__bf16)qa[kk][i], hb = (__bf16)qb[kk][i];
+        qfh[kk][i] = ha;
+        qfh[kk][4 + i] = hb;
+        qfl[kk][i] = (__bf16)(qa[kk][i] - (float)ha);
+        qfl[kk][4 + i] = (__bf16)(qb[kk][i] - (float)hb);
+      }
+    }
+    }
+  };
+  if constexpr (ROPE) {
+    if (threadIdx.x < NKK * 16)
+      sm.rp.turns[threadIdx.x] =
+          exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base) * 0.15915494309189535;
+    for (int e = threadIdx.x; e < 2 * NKK * KS * 64; e += 256) {
+      const int ln = e & 63, ks = (e >> 6) % KS, fb = e / (64 * KS);
+      const uint16_t* urow = a.u_k + (int64_t)(2 * ((fb >> 1) * 16 + (ln & 15)) + (fb & 1)) * g.r_k;
+      typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
+      u16x8 w;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const int rho = ks * 32 + (ln >> 4) * 8 + x;
+        w[x] = rho < g.r_k ? urow[rho] : (uint16_t)0;
+      }
+      sm.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < TBN * NKK * 64; e += 256) {
+      const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
+      f32x4 c4, s4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float c, sn;
+        rot_turns((double)(tb * 16 + (ln & 15)) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        c4[i] = c;
+        s4[i] = sn;
+      }
+      sm.rp.tc[tb][kk][ln] = c4;
+      sm.rp.ts[tb][kk][ln] = s4;
+    }
+    for (int e = threadIdx.x; e < NKK * 64; e += 256) {
+      const int ln = e & 63, kk = e >> 6;
+      f32x4 c4, s4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float c, sn;
+        rot_turns(-(double)(4 * TOK) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        c4[i] = c;
+        s4[i] = sn;
+      }
+      sm.rp.sc[kk][ln] = c4;
+      sm.rp.ss[kk][ln] = s4;
+    }
+    __syncthreads();
+  }
+
+  // Physical page of tile t, or -1.
+  auto tile_page = [&](int it) -> int {
+    const int lp = (it / SUB) / tiles_per_page;
+    const int page = a.page_table[(int64_t)b * g.max_pages + lp];
+    return (page >= 0 && page < g.pool_pages) ? page : -1;
+  };
+  auto load_k = [&](int it, int page) {
+    const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
+                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_k_pad) +
+                           (it % SUB) * (TOK * g.r_k_pad);
+#pragma unroll
+    for (int tb = 0; tb < TBN; ++tb) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int chunk = ks * 4 + quad;
+        if (chunk < nck)
+          kf[tb][ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3)));
+        else
+          kf[tb][ks] = zero_frag();
+      }
+    }
+  };
+  auto load_v = [&](int it, int page) {
+    const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
+                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_v_pad) +
+                           (it % SUB) * (TOK * g.r_v_pad);
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+        vf[u][cb] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3)));
+    }
+  };
+  auto zero_kv = [&]() {
+#pragma unroll
+    for (int tb = 0; tb < TBN; ++tb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[tb][ks] = zero_frag();
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) vf[u][cb] = zero_frag();
+  };
+
+  // the four waves interleave the iterations of the split (neighbouring waves read neighbouring memory)
+  const int it_end = t_end * SUB;
+  int t = t_begin * SUB + wave;
+  bool have = t < it_end;
+  int page = -1;
+  if (have) {
+    page = tile_page(t);
+    if (page >= 0) {
+      load_k(t, page);
+      load_v(t, page);
+    } else {
+      zero_kv();
+    }
+    if constexpr (ROPE) {
+      seed_q(t);
+      pack_q();
+    }
+  }
+  int since_seed = 0;
+
+  while (have) {
+    // ---- scores: S[tb] (16 tokens x 16 head columns) = K_block . q^T
+    f32x4 s[TBN];
+    // The rotation tables never change, so the compiler would keep all of them in registers across the
+    // loop; an index it cannot see through makes it read them where they are used.
+    int tl = lane;
+    if constexpr (ROPE) asm volatile("" : "+v"(tl));
+    if constexpr (!ROPE) {
+#pragma unroll
+      for (int tb = 0; tb < TBN; ++tb) {
+        s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          s[tb] = mfma16(kf[tb][ks], qhi[ks], s[tb]);
+          s[tb] = mfma16(kf[tb][ks], qlo[ks], s[tb]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int tb = 0; tb < TBN; ++tb) s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < NK1; ++kk) {
+        // K'^T (32 of the d_head channels x 16 tokens) = U^K . k_r^T: lane (col, quad) receives, of token col,
+        // the channels 2j + comp with j = 16*kk + 4*quad + i in up[comp][tb][i]
+        f32x4 up[2][TBN];
+#pragma unroll
+        for (int tb = 0; tb < TBN; ++tb) up[0][tb] = up[1][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 u0 = sm.rp.uf[2 * kk][ks][tl], u1 = sm.rp.uf[2 * kk + 1][ks][tl];
+#pragma unroll
+          for (int tb = 0; tb < TBN; ++tb) {
+            up[0][tb] = mfma16(u0, kf[tb][ks], up[0][tb]);
+            up[1][tb] = mfma16(u1, kf[tb][ks], up[1][tb]);
+          }
+        }
+#pragma unroll
+        for (int tb = 0; tb < TBN; ++tb) {
+          const f32x4 c4 = sm.rp.tc[tb][kk][tl], s4 = sm.rp.ts[tb][kk][tl];
+          bf16x8 kr;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float x0 = up[0][tb][i], x1 = up[1][tb][i];
+            kr[i] = (__bf16)(x0 * c4[i] - x1 * s4[i]);
+            kr[4 + i] = (__bf16)(x0 * s4[i] + x1 * c4[i]);
+          }
+          s[tb] = mfma16(kr, qfh[kk], s[tb]);
+          s[tb] = mfma16(kr, qfl[kk], s[tb]);
+        }
+      }
+    }
+    const int rem = page >= 0 ? n - t * TOK : 0;   // valid tokens in this iteration (>= TOK: all)
+    const int tn = t + 4;
+    const bool have_n = tn < it_end;
+    const int page_n = have_n ? tile_page(tn) : -1;
+    if (have_n && page_n >= 0) load_k(tn, page_n);   // K registers are free again: prefetch the next tile
+    if constexpr (ROPE) {
+      if (have_n) {
+        if (++since_seed == kReseed) {
+          since_seed = 0;
+          seed_q(tn);
+        } else {
+          step_q(tl);
+        }
+        pack_q();
+      }
+    }
+
+    // ---- online softmax on s (lane: head column `col`, tokens tb*16 + 4*quad + i)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tb = 0; tb < TBN; ++tb) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (rem < TOK && tb * 16 + quad * 4 + i >= rem) s[tb][i] = -INFINITY;
+        mx = fmaxf(mx, s[tb][i]);
+      }
+    }
+    mx = quad_column_max(mx) * a.scale_log2;                  // the scale is positive: max commutes with it
+    // m is a reference exponent: it moves only when the max has grown by more than kLazy (log2 units), so
+    // P stays <= 2^kLazy and the accumulators are rescaled a few times per stream, not at every tile.
+    if (__any(mx > m + kLazy)) {
+      const float m_new = fmaxf(m, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_safe);  // m = -inf -> 0
+      lacc *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+      m = m_new;
+    }
+    const float m_use = m == -INFINITY ? 0.f : m;
+    bf16x8 pf[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], a.scale_log2, -m_use));
+      }
+    }
+    if (rem < TOK) {
+      // Partial tile: cache slots past the sequence end hold arbitrary bits; clear them so 0 * x stays 0.
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const int tok = u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
+            if (tok >= rem) vf[u][cb][j] = (__bf16)0.0f;
+          }
+        }
+      }
+    }
+    // ---- O^T += V^T . P^T, row sums of P through the all-ones operand
+#pragma unroll
+    for (int u = 0; u < UN; ++u) lacc = mfma16(ones, pf[u], lacc);
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+      for (int u = 0; u < UN; ++u) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
+    }
+    if (have_n) {
+      if (page_n >= 0) load_v(tn, page_n);
+      else zero_kv();
+    }
+    t = tn;
+    have = have_n;
+    page = page_n;
+  }
+
+  // ---- merge the four waves of the workgroup
+  if constexpr (ROPE) __syncthreads();   // the tables share their memory with the merge buffers
+  auto& sm_m = sm.mg.m;
+  auto& sm_l = sm.mg.l;
+  auto& sm_acc = sm.mg.acc;
+  if (quad == 0) {
+    sm_m[wave][col] = m;
+    sm_l[wave][col] = lacc[0];
+  }
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sm_acc[wave][col][cb * 16 + quad * 4 + i] = acc[cb][i];
+  __syncthreads();
+
+  const int r_v_pad = NCB * 16;
+  for (int idx = threadIdx.x; idx < G * r_v_pad; idx += blockDim.x) {
+    const int hd = idx / r_v_pad, c = idx % r_v_pad;
+    float mm = sm_m[0][hd];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mm = fmaxf(mm, sm_m[w][hd]);
+    float lsum = 0.f, val = 0.f;
+    if (mm != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float wt = __builtin_amdgcn_exp2f(sm_m[w][hd] - mm);
+        lsum += wt * sm_l[w][hd];
+        val += wt * sm_acc[w][hd][c];
+      }
+    }
+    const int head = kvh * G + hd;
+    if (a.n_splits == 1) {
+      if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
+    } else {
+      const int64_t BHS = (int64_t)gridDim.z * g.n_heads * a.n_splits;
+      const int64_t row = ((int64_t)b * g.n_heads + head) * a.n_splits + split;
+      if (c == 0) {
+        a.ws[row] = mm;
+        a.ws[BHS + row] = lsum;
+      }
+      a.ws[2 * BHS + row * r_v_pad + c] = val;
+    }
+  }
+}
+
+}  // namespace ea

@@ -7,20 +7,61 @@ namespace ea {
 
 constexpr int kChunk = 256;   // tokens per step = threads per workgroup
 
+// Score of one cached key against the rank-r query (Eq. 7: q_r . k_r).
+struct DotScore {
+  const float* sq;   // the query's r_k channels, in LDS
+  int r_k;
+  __device__ __forceinline__ float operator()(int /*tok*/, const float* __restrict__ krow) const {
+    float dot = 0.f;
+    for (int c = 0; c < r_k; ++c) dot = fmaf(sq[c], krow[c], dot);
+    return dot;
+  }
+};
+
+// Score for models with rotary position embedding (Sec. 4.3, Eq. 10): the cached rank-r key is brought back to
+// d_head channels with the shared basis U^K, rotated to its position, and multiplied with the query rotated to
+// its own position.  Only the difference of the two positions enters, so the key pair is rotated by
+// (tok - pos_q) theta_j and the query is left as it is.
+struct RopeScore {
+  const float* sq;      // the query's d_head channels, in LDS
+  const float* u_k;     // [d_head, r_k]
+  const double* theta;  // [d_head / 2], in LDS
+  int r_k, d_head, pos_q;
+  __device__ __forceinline__ float operator()(int tok, const float* __restrict__ krow) const {
+    float dot = 0.f;
+    for (int j = 0; j < d_head / 2; ++j) {
+      const float* u0 = u_k + (int64_t)(2 * j) * r_k;
+      const float* u1 = u0 + r_k;
+      float k0 = 0.f, k1 = 0.f;
+      for (int c = 0; c < r_k; ++c) {
+        k0 = fmaf(u0[c], krow[c], k0);
+        k1 = fmaf(u1[c], krow[c], k1);
+      }
+      // reduce the angle modulo 2 pi in double precision: positions reach 10^5 radians and more
+      const double x = (double)(tok - pos_q) * theta[j];
+      const double kq = rint(x * 0.15915494309189535);
+      double r = fma(-kq, 6.283185307179586, x);
+      r = fma(-kq, 2.4492935982947064e-16, r);
+      const float cs = cosf((float)r), sn = sinf((float)r);
+      dot = fmaf(sq[2 * j], k0 * cs - k1 * sn, dot);
+      dot = fmaf(sq[2 * j + 1], k0 * sn + k1 * cs, dot);
+    }
+    return dot;
+  }
+};
+
 // Online-softmax attention of one query over tokens [tok_begin, tok_end) of sequence b (Eq. 3 / Eq. 2 row).
 // Thread t scores token chunk*256 + t; afterwards thread c accumulates value channel c.
 // Returns through (m, l, acc): running max (log2 domain), denominator and numerator of channel threadIdx.x.
-__device__ __forceinline__ void attend_f32(const float* __restrict__ qrow, const float* __restrict__ k_pool,
+template <typename Score>
+__device__ __forceinline__ void attend_f32(const Score& score, const float* __restrict__ k_pool,
                                            const float* __restrict__ v_pool, const int32_t* __restrict__ pt_row,
                                            const Geo& g, int kvh, int tok_begin, int tok_end, float scale_log2,
                                            float& m_out, float& l_out, float& acc_out) {
-  __shared__ float sq[256];
   __shared__ float sp[kChunk];
   __shared__ int64_t svoff[kChunk];
   __shared__ float sred[4];
   const int tid = threadIdx.x;
-  __syncthreads();
-  if (tid < g.r_k) sq[tid] = qrow[tid];
   __syncthreads();
   float m = -INFINITY, l = 0.f, acc = 0.f;
   for (int base = tok_begin; base < tok_end; base += kChunk) {
@@ -33,9 +74,7 @@ __device__ __forceinline__ void attend_f32(const float* __restrict__ qrow, const
       if (page >= 0 && page < g.pool_pages) {
         const int tp = tok % g.page_tokens;
         const float* krow = k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tp * g.r_k_pad;
-        float dot = 0.f;
-        for (int c = 0; c < g.r_k; ++c) dot = fmaf(sq[c], krow[c], dot);
-        s = dot * scale_log2;
+        s = score(tok, krow) * scale_log2;
         voff = (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab + (int64_t)tp * g.r_v_pad;
       }
     }
@@ -79,6 +118,10 @@ struct AttnF32Args {
   int32_t n_splits;
   int32_t n_q;   // prefill: queries per sequence
   float scale_log2;
+  // rotary variant only
+  const float* u_k;
+  int32_t d_head;
+  double log2_base;
 };
 
 __device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
@@ -89,6 +132,7 @@ __device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
   return (int)n;
 }
 
+template <bool ROPE>
 __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
   const Geo& g = a.g;
   const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
@@ -99,8 +143,21 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
   const int tok_begin = min(n, split * per * kChunk);
   const int tok_end = min(n, (split + 1) * per * kChunk);
   float m, l, acc;
-  attend_f32(a.q + ((int64_t)b * g.n_heads + head) * g.r_k, a.k_pool, a.v_pool,
-             a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m, l, acc);
+  __shared__ float sq[256];
+  if (!ROPE) {
+    if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[((int64_t)b * g.n_heads + head) * g.r_k + threadIdx.x];
+    __syncthreads();
+    attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin,
+               tok_end, a.scale_log2, m, l, acc);
+  } else {
+    __shared__ double theta[128];
+    if (threadIdx.x < a.d_head) sq[threadIdx.x] = a.q[((int64_t)b * g.n_heads + head) * a.d_head + threadIdx.x];
+    if (threadIdx.x < a.d_head / 2)
+      theta[threadIdx.x] = exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base);
+    __syncthreads();
+    attend_f32(RopeScore{sq, a.u_k, theta, g.r_k, a.d_head, n - 1}, a.k_pool, a.v_pool,
+               a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m, l, acc);
+  }
   const int c = threadIdx.x;
   if (a.n_splits == 1) {
     if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = l > 0.f ? acc / l : 0.f;
@@ -124,7 +181,10 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
   const int pos = n - a.n_q + j;
   const int64_t row = (((int64_t)b * a.n_q + j) * g.n_heads + head);
   float m, l, acc;
-  attend_f32(a.q + row * g.r_k, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
+  __shared__ float sq[256];
+  if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[row * g.r_k + threadIdx.x];
+  __syncthreads();
+  attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
              pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
   const int c = threadIdx.x;
   if (c < g.r_v) a.out[row * g.r_v + c] = l > 0.f ? acc / l : 0.f;
@@ -145,6 +205,9 @@ static AttnF32Args make_args(const ea_layer_desc* d, const Geo& g, const float* 
   a.n_splits = n_splits;
   a.n_q = n_q;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
+  a.u_k = nullptr;
+  a.d_head = d->d_head;
+  a.log2_base = 0.0;
   return a;
 }
 
@@ -153,7 +216,19 @@ int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float
                hipStream_t st) {
   if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
-  decode_f32_kernel<<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  decode_f32_kernel<false><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
+                    const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                    float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  if (d->d_head > 256 || d->d_head % 2 != 0) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
+  a.u_k = u_k;
+  a.log2_base = log2(rope_base);
+  decode_f32_kernel<true><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 

@@ -1,0 +1,169 @@
+"""ea_decode_attn_rope (Sec. 4.3, Eq. 10: full-rank query, rank-r keys brought back to d_head channels and
+rotated) against the fp64 oracle on identical inputs."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_05646_amd as ea
+from oracle import eigen_attention as ora
+from paper_2408_05646_amd import synth
+from helpers import DeviceCache, TOL_BF16, TOL_F32, assert_close, quantize, random_cache, to_dev
+from test_gpu_fullsize import k_slabs_to_rows, stream_from_pool, v_slabs_to_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def run_rope(desc, K, V, q, U, base, g, n_splits, page_table_edit=None):
+    dc = DeviceCache(desc, K, V, g)
+    B = len(K)
+    pt = dc.page_table if page_table_edit is None else page_table_edit(dc)
+    out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = n_splits if n_splits else ea.decode_auto_splits(desc, B, dc.max_pages * desc.page_tokens)
+    ws = None
+    nbytes = ea.decode_workspace_bytes(desc, B, S)
+    if nbytes:
+        ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ea.decode_attn_rope(desc, torch.from_numpy(q.astype(np.float32)).cuda(),
+                        to_dev(desc, U), base, dc.k_pool, dc.v_pool, pt,
+                        dc.seq_len, out, n_splits=S, ws=ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_rope(desc, K, V, q, U, base):
+    keep = [b for b in range(len(K)) if K[b].shape[1] > 0]
+    ref = np.zeros((len(K), desc.n_heads, desc.r_v))
+    if keep:
+        cache = ora.RankCache.from_arrays([K[b] for b in keep], [V[b] for b in keep])
+        ref[keep] = ora.decode_attention_rope(q[keep], cache, U, desc.d_head, base)
+    return ref
+
+
+def inputs(desc, lens, g, std=1.0):
+    U = quantize(desc, synth.orthonormal_basis(g, desc.d_head, desc.r_k))   # one basis for all heads, layer dtype
+    K, V = random_cache(desc, lens, g, k_std=std)
+    q = np.float32(synth.gaussian(g, (len(lens), desc.n_heads, desc.d_head), std)).astype(np.float64)
+    return U, K, V, q
+
+
+@pytest.mark.parametrize("H,Hkv,d_h,r_k,r_v,lens,P,n_splits,base", [
+    (4, 4, 64, 32, 32, [1, 15, 16, 17], 16, 1, 10000.0),
+    (4, 2, 64, 30, 33, [255, 256, 257, 700], 32, 3, 10000.0),
+    (6, 2, 128, 80, 16, [1000, 3, 511], 64, 0, 500000.0),     # the larger base of the Llama-3 family
+    (2, 1, 48, 48, 64, [300], 16, 2, 10000.0),                # r_k = d_h: plain rotary attention
+    (4, 4, 64, 32, 32, [0, 40], 16, 1, 10000.0),              # an empty sequence gives a zero row
+])
+def test_f32_shapes(H, Hkv, d_h, r_k, r_v, lens, P, n_splits, base):
+    print(f"rope f32 H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) lens={lens} P={P} S={n_splits}", flush=True)
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_F32, P)
+    g = synth.rng(21, H, r_k, len(lens))
+    U, K, V, q = inputs(desc, lens, g)
+    got = run_rope(desc, K, V, q, U, base, g, n_splits)
+    assert_close(got, oracle_rope(desc, K, V, q, U, base), TOL_F32, "rope f32")
+
+
+def test_f32_far_positions_keep_their_angle():
+    """70 000 cached tokens: the fastest pair has turned 70 000 radians, which single precision alone
+    would resolve to 4e-3 only."""
+    desc = ea.LayerDesc(128, 1, 1, 128, 40, 24, ea.EA_F32, 64)
+    g = synth.rng(22)
+    U, K, V, q = inputs(desc, [70000], g, std=1.5)
+    got = run_rope(desc, K, V, q, U, 10000.0, g, 8)
+    assert_close(got, oracle_rope(desc, K, V, q, U, 10000.0), TOL_F32, "rope f32 far")
+
+
+@pytest.mark.parametrize("H,Hkv,d_h,r_k,r_v,lens,P,n_splits", [
+    (2, 2, 128, 80, 80, [1, 63, 64, 65], 64, 1),
+    (2, 2, 128, 80, 80, [200, 1000, 129], 64, 3),
+    (8, 2, 128, 48, 112, [777, 64, 1500], 128, 0),          # GQA 4:1, r_k != r_v
+    (8, 2, 128, 112, 48, [2048, 31], 64, 5),
+    (16, 1, 128, 96, 64, [300], 64, 2),                     # 16 query heads on one kv head
+    (4, 4, 128, 128, 128, [513, 100], 64, 2),               # r_k = d_h: plain rotary attention
+    (4, 2, 128, 72, 40, [150, 70], 64, 2),                  # ranks that need padding channels
+    (4, 2, 64, 40, 48, [900, 64], 64, 2),                   # d_h = 64
+    (2, 2, 64, 64, 16, [333], 192, 1),
+    (2, 2, 128, 80, 80, [0, 100], 64, 1),                   # an empty sequence gives a zero row
+    (2, 2, 128, 80, 80, [90], 64, 4),                       # more splits than tiles: empty workgroups
+    (2, 1, 128, 80, 80, [20000], 64, 1),                    # one workgroup walks 313 tiles: the stepped rotation
+                                                            # of the query is re-computed exactly on the way
+    (2, 2, 128, 128, 96, [9000], 64, 1),                    # same with half-tile iterations
+])
+def test_bf16_shapes(H, Hkv, d_h, r_k, r_v, lens, P, n_splits):
+    print(f"rope bf16 H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) lens={lens} P={P} S={n_splits}", flush=True)
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(23, H, r_k, len(lens), n_splits)
+    U, K, V, q = inputs(desc, lens, g, std=2.0)
+    got = run_rope(desc, K, V, q, U, 10000.0, g, n_splits)
+    err = assert_close(got, oracle_rope(desc, K, V, q, U, 10000.0), TOL_BF16, "rope bf16")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+def test_bf16_position_matters():
+    """Same cache, same query: moving the keys one page further (a different position for every key) must change
+    the result the way the oracle says -- a kernel that ignored positions would pass every test whose scores
+    happen to be position independent, so make sure this one is not."""
+    desc = ea.LayerDesc(256, 2, 2, 128, 80, 80, ea.EA_BF16, 64)
+    g = synth.rng(24)
+    U, K, V, q = inputs(desc, [640], g, std=2.0)
+    ref = oracle_rope(desc, K, V, q, U, 10000.0)
+    plain = ora.decode_attention(np.einsum("bhc,cr->bhr", q, U), ora.RankCache.from_arrays(K, V), 128)
+    assert ora.rel_l2(plain, ref) > 0.2                     # rotary and position-free attention differ a lot here
+    got = run_rope(desc, K, V, q, U, 10000.0, g, 2)
+    assert_close(got, ref, TOL_BF16, "rope position")
+
+
+def test_bf16_out_of_range_pages_are_masked_not_read():
+    desc = ea.LayerDesc(256, 2, 2, 128, 80, 80, ea.EA_BF16, 64)
+    g = synth.rng(25)
+    U, K, V, q = inputs(desc, [256], g)
+
+    def edit(dc):
+        pt = dc.page_table.clone()
+        pt[0, 1] = dc.pool_pages + 1000      # tokens 64..127 vanish (the others keep their positions)
+        pt[0, 2] = -5                        # tokens 128..191 vanish
+        return pt
+    got = run_rope(desc, K, V, q, U, 10000.0, g, 1, page_table_edit=edit)
+    # oracle: the same attention with those tokens' scores removed = keys kept at their own positions
+    keep = np.r_[0:64, 192:256]
+    Uq = U
+    refs = []
+    for i in range(2):
+        K_up = K[0][i] @ Uq.T
+        s = (ora.rope_rotate(K_up, np.arange(256)) @ ora.rope_rotate(q[0, i], 255)) / np.sqrt(128.0)
+        refs.append(ora.softmax(s[keep]) @ V[0][i][keep])
+    assert_close(got, np.stack(refs)[None], TOL_BF16, "rope masked pages")
+
+
+def test_cfg3_rope_one_layer_sampled():
+    """Llama-2-7B-shaped layer at B=16, n=32768, r=80 with rotary positions, split count as bench.py uses; sampled
+    (sequence, head) outputs against the oracle, cache contents read back from raw pool memory."""
+    s = synth.CFG3
+    desc = ea.LayerDesc(s.d_model, s.n_heads, s.n_kv_heads, s.d_head, s.r_k, s.r_v, ea.EA_BF16, 64)
+    B, n, P = s.batch, s.n_ctx, 64
+    g = synth.rng(26)
+    samples = [(0, 0), (15, 31)] + [(int(g.integers(16)), int(g.integers(32))) for _ in range(6)]
+    print("cfg3 rope samples", samples, flush=True)
+    max_pages = n // P
+    pool_pages = B * max_pages
+    gen = torch.Generator(device="cuda"); gen.manual_seed(66)
+    k_pool, v_pool = ea.alloc_pools(desc, pool_pages, zero=False)
+    k_pool.normal_(0.0, 1.00125, generator=gen); v_pool.normal_(0.0, 1.00125, generator=gen)
+    pt = torch.randperm(pool_pages, generator=gen, device="cuda").to(torch.int32).reshape(B, max_pages).contiguous()
+    seq = torch.full((B,), n, dtype=torch.int32, device="cuda")
+    q = torch.randn((B, desc.n_heads, desc.d_head), generator=gen, device="cuda")
+    U = quantize(desc, synth.orthonormal_basis(g, desc.d_head, desc.r_k))
+    out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), device="cuda")
+    S = ea.decode_auto_splits(desc, B, n)
+    ws = torch.empty(max(ea.decode_workspace_bytes(desc, B, S) // 4, 4), device="cuda")
+    ea.decode_attn_rope(desc, q, to_dev(desc, U), 10000.0, k_pool, v_pool, pt, seq, out, n_splits=S, ws=ws)
+    torch.cuda.synchronize()
+    got_all = out.cpu().numpy()
+    assert np.isfinite(got_all).all()
+    lay = ea.cache_layout_query(desc)
+    qh = q.cpu().numpy().astype(np.float64)
+    for (b, h) in samples:
+        K = stream_from_pool(k_pool, pt[b], h, desc.n_kv_heads, lay.r_k_pad, k_slabs_to_rows, P)[:, :desc.r_k]
+        V = stream_from_pool(v_pool, pt[b], h, desc.n_kv_heads, lay.r_v_pad, v_slabs_to_rows, P)[:, :desc.r_v]
+        cache = ora.RankCache.from_arrays([K[None]], [V[None]])
+        ref = ora.decode_attention_rope(qh[b:b + 1, h:h + 1], cache, U, desc.d_head)
+        assert_close(got_all[b:b + 1, h:h + 1], ref, TOL_BF16, f"rope stream b={b} h={h}")
