@@ -16,8 +16,8 @@
 // brought back to d_head channels on the matrix cores (K' = U^K k_r, the basis shared by all heads kept
 // in LDS in MFMA operand order), rotated to its position, rounded to bf16 and only then multiplied
 // with the query (hi + lo bf16).  Only the position DIFFERENCE enters a score, so the rotation is split: the query is
-// rotated (in fp32, once per iteration of a wave) by the distance between its own position and the first
-// token of the iteration, each key by its offset inside the iteration (a constant table in LDS).
+// rotated (in fp32, once per tile of a wave) by the distance between its own position and the first
+// token of the tile, each key by its offset inside the tile (a constant table in LDS).
 #pragma once
 #include <type_traits>
 #include "ea_common.h"
@@ -65,8 +65,8 @@ template <int TBN, int NKK, int KS>
 struct RopeSmem {
   // A operand of the up-projection: row m of block 2*kk + comp is channel 2*(16*kk + m) + comp of the basis
   bf16x8 uf[2 * NKK][KS][64];
-  f32x4 tc[TBN][NKK][64], ts[TBN][NKK][64];   // angle (16*tb + col) * theta_j: a key's offset in the iteration
-  f32x4 sc[NKK][64], ss[NKK][64];             // angle -(4 * 16*TBN) * theta_j: one step of a wave
+  f32x4 tc[4][NKK][64], ts[4][NKK][64];   // angle (16*tb + col) * theta_j: a key's offset in its 64-token tile
+  f32x4 sc[NKK][64], ss[NKK][64];         // angle -(4 * 64) * theta_j: from one tile of a wave to its next
   double turns[NKK * 16];                     // theta_j / (2 pi)
 };
 struct NoSmem {};
@@ -88,12 +88,19 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   const Geo& g = a.g;
   // neighbouring workgroups take neighbouring kv heads of the same pages: their slabs are adjacent in memory
   const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, so is all that follows from it
   const int col = lane & 15, quad = lane >> 4;
   const int G = g.group;
   const int nck = g.r_k_pad >> 3;
 
-  int64_t n64 = a.seq_len[b];
+  // Sequence lengths and page ids are the same for every lane and do not change while the kernel runs: read
+  // through the constant address space they arrive in scalar registers, and their loads do not queue up
+  // behind the cache tiles in flight.
+  typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+  const const_i32_ptr seq_len_c = (const_i32_ptr)a.seq_len;
+  const const_i32_ptr pt_row = (const_i32_ptr)(a.page_table + (int64_t)b * g.max_pages);
+  int64_t n64 = seq_len_c[b];
   const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
   if (n64 > cap) n64 = cap;
   if (n64 < 0) n64 = 0;
@@ -137,16 +144,18 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   float qa[NK1][4], qb[NK1][4];  // the query's pairs j = 16*kk + 4*quad + i, rotated to the current iteration
   bf16x8 qfh[NK1], qfl[NK1];     // ... as B operand of the score MFMA (hi + lo): slot 4*comp + i of k-step kk
   const int pos_q = n - 1;       // the query is the token appended last
-  auto seed_q = [&](int it) {
+  auto seed_q = [&](int tile) {
     if constexpr (ROPE) {
-    const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + col) * a.d_head;
-    const double rel = (double)(pos_q - it * TOK);
+    // head columns past the group read head 0 of the group (always there) and are zeroed
+    const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + (col < G ? col : 0)) * a.d_head;
+    const double rel = (double)(pos_q - tile * kTile);
 #pragma unroll
     for (int kk = 0; kk < NK1; ++kk) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = kk * 16 + quad * 4 + i;
-        const float q0 = col < G ? qrow[2 * j] : 0.f, q1 = col < G ? qrow[2 * j + 1] : 0.f;
+        const float g0 = qrow[2 * j], g1 = qrow[2 * j + 1];
+        const float q0 = col < G ? g0 : 0.f, q1 = col < G ? g1 : 0.f;
         float c, sn;
         rot_turns(rel * sm.rp.turns[j], c, sn);
         qa[kk][i] = q0 * c - q1 * sn;
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       sm.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < TBN * NKK * 64; e += 256) {
+    for (int e = threadIdx.x; e < 4 * NKK * 64; e += 256) {
       const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
       f32x4 c4, s4;
 #pragma unroll
@@ -220,7 +229,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float c, sn;
-        rot_turns(-(double)(4 * TOK) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        rot_turns(-(double)(4 * kTile) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
         c4[i] = c;
         s4[i] = sn;
       }
@@ -230,65 +239,78 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     __syncthreads();
   }
 
-  // Physical page of tile t, or -1.
-  auto tile_page = [&](int it) -> int {
-    const int lp = (it / SUB) / tiles_per_page;
-    const int page = a.page_table[(int64_t)b * g.max_pages + lp];
+  // Where a wave stands in its split.  Everything here is wave-uniform and lives in scalar registers; the
+  // logical page and the tile's place inside it are stepped along, not divided out, per iteration.
+  struct Pos {
+    int tile, sub, lp, tin;
+  };
+  // waves of the position-free kernel interleave iterations (half tiles when SUB = 2), those of the rotary
+  // variant whole tiles, so that a wave re-rotates its query once per 64 tokens
+  constexpr int kStride = ROPE ? 4 : 4 / SUB;
+  Pos cur;
+  cur.tile = t_begin + (ROPE ? wave : wave / SUB);
+  cur.sub = ROPE ? 0 : wave % SUB;
+  cur.lp = cur.tile / tiles_per_page;
+  cur.tin = cur.tile % tiles_per_page;
+  auto advance = [&](Pos p) -> Pos {
+    if (ROPE && p.sub + 1 < SUB) {
+      p.sub += 1;
+      return p;
+    }
+    if (ROPE) p.sub = 0;
+    p.tile += kStride;
+    p.tin += kStride;
+    while (p.tin >= tiles_per_page) {
+      p.tin -= tiles_per_page;
+      p.lp += 1;
+    }
+    return p;
+  };
+  // Physical page of a position, or -1.
+  auto page_of = [&](const Pos& p) -> int {
+    const int page = pt_row[p.lp];
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
-  auto load_k = [&](int it, int page) {
+  const int lane_off = lane << 3;
+  auto load_k = [&](const Pos& p, int page) {
     const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
-                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_k_pad) +
-                           (it % SUB) * (TOK * g.r_k_pad);
+                           (int64_t)p.tin * (kTile * g.r_k_pad) + p.sub * (TOK * g.r_k_pad);
 #pragma unroll
     for (int tb = 0; tb < TBN; ++tb) {
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const int chunk = ks * 4 + quad;
-        if (chunk < nck)
-          kf[tb][ks] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3)));
-        else
-          kf[tb][ks] = zero_frag();
+        // chunk ks*4 + quad of token row col: element ((tb*nck + ks*4 + quad)*16 + col)*8 = (tb*nck*16 + ks*64 + lane)*8.
+        // Only the last k-step can run past the nck chunks the rank has (r_k_pad > 32*(KS-1)); its surplus
+        // lanes read the last real chunk instead and drop what they read, so no load sits behind a branch.
+        const bool past = ks == KS - 1 && ks * 4 + quad >= nck;
+        const int off = past ? (((tb + 1) * nck - 1) * 16 + col) << 3 : ((tb * nck * 16 + ks * 64) << 3) + lane_off;
+        const bf16x8 got = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + off));
+        kf[tb][ks] = past ? zero_frag() : got;
       }
     }
   };
-  auto load_v = [&](int it, int page) {
+  auto load_v = [&](const Pos& p, int page) {
     const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
-                           (int64_t)((it / SUB) % tiles_per_page) * (kTile * g.r_v_pad) +
-                           (it % SUB) * (TOK * g.r_v_pad);
+                           (int64_t)p.tin * (kTile * g.r_v_pad) + p.sub * (TOK * g.r_v_pad);
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb)
-        vf[u][cb] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3)));
+        vf[u][cb] = __builtin_nontemporal_load(
+            reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64) << 3) + lane_off));
     }
-  };
-  auto zero_kv = [&]() {
-#pragma unroll
-    for (int tb = 0; tb < TBN; ++tb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[tb][ks] = zero_frag();
-#pragma unroll
-    for (int u = 0; u < UN; ++u)
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) vf[u][cb] = zero_frag();
   };
 
-  // the four waves interleave the iterations of the split (neighbouring waves read neighbouring memory)
-  const int it_end = t_end * SUB;
-  int t = t_begin * SUB + wave;
-  bool have = t < it_end;
+  bool have = cur.tile < t_end;
   int page = -1;
   if (have) {
-    page = tile_page(t);
-    if (page >= 0) {
-      load_k(t, page);
-      load_v(t, page);
-    } else {
-      zero_kv();
-    }
+    page = page_of(cur);
+    // A tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are
+    // masked below: the loads never depend on the page table's contents, only their address does.
+    load_k(cur, max(page, 0));
+    load_v(cur, max(page, 0));
     if constexpr (ROPE) {
-      seed_q(t);
+      seed_q(cur.tile);
       pack_q();
     }
   }
@@ -332,7 +354,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
         }
 #pragma unroll
         for (int tb = 0; tb < TBN; ++tb) {
-          const f32x4 c4 = sm.rp.tc[tb][kk][tl], s4 = sm.rp.ts[tb][kk][tl];
+          const f32x4 c4 = sm.rp.tc[cur.sub * TBN + tb][kk][tl], s4 = sm.rp.ts[cur.sub * TBN + tb][kk][tl];
           bf16x8 kr;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -345,16 +367,16 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
         }
       }
     }
-    const int rem = page >= 0 ? n - t * TOK : 0;   // valid tokens in this iteration (>= TOK: all)
-    const int tn = t + 4;
-    const bool have_n = tn < it_end;
-    const int page_n = have_n ? tile_page(tn) : -1;
-    if (have_n && page_n >= 0) load_k(tn, page_n);   // K registers are free again: prefetch the next tile
+    const int rem = page >= 0 ? n - (cur.tile * kTile + cur.sub * TOK) : 0;   // valid tokens here (>= TOK: all)
+    const Pos nxt = advance(cur);
+    const bool have_n = nxt.tile < t_end;
+    const int page_n = have_n ? page_of(nxt) : -1;
+    if (have_n) load_k(nxt, max(page_n, 0));   // K registers are free again: prefetch the next tile
     if constexpr (ROPE) {
-      if (have_n) {
+      if (have_n && nxt.sub == 0) {
         if (++since_seed == kReseed) {
           since_seed = 0;
-          seed_q(tn);
+          seed_q(nxt.tile);
         } else {
           step_q(tl);
         }
@@ -417,11 +439,8 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
 #pragma unroll
       for (int u = 0; u < UN; ++u) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
     }
-    if (have_n) {
-      if (page_n >= 0) load_v(tn, page_n);
-      else zero_kv();
-    }
-    t = tn;
+    if (have_n) load_v(nxt, max(page_n, 0));
+    cur = nxt;
     have = have_n;
     page = page_n;
   }
