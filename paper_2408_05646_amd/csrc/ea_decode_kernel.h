@@ -14,8 +14,10 @@
 // NKK > 0 selects the variant for models with rotary position embedding (Sec. 4.3, Eq. 10): the query
 // arrives with all d_head = 32*NKK channels, and each 16-token block of cached rank-r keys is first
 // brought back to d_head channels on the matrix cores (K' = U^K k_r, the basis shared by all heads kept
-// in LDS in MFMA operand order), rotated to its position, rounded to bf16 and only then multiplied
-// with the query (hi + lo bf16).  Only the position DIFFERENCE enters a score, so the rotation is split: the query is
+// in LDS in MFMA operand order), rotated to its position in packed half precision and only then multiplied
+// with the query on the fp16 matrix-core path (11 significant bits on both operands, against 8 of bf16: the
+// rotated keys exist in registers only, so their format is free; their magnitude is bounded by the cached
+// key's norm, far inside the fp16 range for attention keys).  Only the position DIFFERENCE enters a score, so the rotation is split: the query is
 // rotated (in fp32, once per tile of a wave) by the distance between its own position and the first
 // token of the tile, each key by its offset inside the tile (a constant table in LDS).
 #pragma once
@@ -52,6 +54,9 @@ __device__ __forceinline__ void rot_turns(double x, float& c, float& s) {
   s = __builtin_amdgcn_sinf(f);
 }
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+
 template <int NCB>
 struct MergeSmem {
   float m[4][16];
@@ -65,8 +70,8 @@ template <int TBN, int NKK, int KS>
 struct RopeSmem {
   // A operand of the up-projection: row m of block 2*kk + comp is channel 2*(16*kk + m) + comp of the basis
   bf16x8 uf[2 * NKK][KS][64];
-  f32x4 tc[4][NKK][64], ts[4][NKK][64];   // angle (16*tb + col) * theta_j: a key's offset in its 64-token tile
-  f32x4 sc[NKK][64], ss[NKK][64];         // angle -(4 * 64) * theta_j: from one tile of a wave to its next
+  f16x8 tcs[4][NKK][64];             // cos (slots 0-3) and sin (4-7) of (16*tb + col) * theta_j: a key's offset in its tile
+  f32x4 sc[NKK][64], ss[NKK][64];    // angle -(4 * 64) * theta_j: from one tile of a wave to its next
   double turns[NKK * 16];                     // theta_j / (2 pi)
 };
 struct NoSmem {};
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   // ---- rotary variant: basis fragments, rotation tables, rotated query
   constexpr int NK1 = ROPE ? NKK : 1;
   float qa[NK1][4], qb[NK1][4];  // the query's pairs j = 16*kk + 4*quad + i, rotated to the current iteration
-  bf16x8 qfh[NK1], qfl[NK1];     // ... as B operand of the score MFMA (hi + lo): slot 4*comp + i of k-step kk
+  f16x8 qf[NK1];                 // ... as B operand of the score MFMA: slot 4*comp + i of k-step kk
   const int pos_q = n - 1;       // the query is the token appended last
   auto seed_q = [&](int tile) {
     if constexpr (ROPE) {
@@ -184,11 +189,8 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     for (int kk = 0; kk < NK1; ++kk) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const __bf16 ha = (__bf16)qa[kk][i], hb = (__bf16)qb[kk][i];
-        qfh[kk][i] = ha;
-        qfh[kk][4 + i] = hb;
-        qfl[kk][i] = (__bf16)(qa[kk][i] - (float)ha);
-        qfl[kk][4 + i] = (__bf16)(qb[kk][i] - (float)hb);
+        qf[kk][i] = (_Float16)qa[kk][i];
+        qf[kk][4 + i] = (_Float16)qb[kk][i];
       }
     }
     }
@@ -212,16 +214,15 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     __syncthreads();
     for (int e = threadIdx.x; e < 4 * NKK * 64; e += 256) {
       const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
-      f32x4 c4, s4;
+      f16x8 cs;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float c, sn;
         rot_turns((double)(tb * 16 + (ln & 15)) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
-        c4[i] = c;
-        s4[i] = sn;
+        cs[i] = (_Float16)c;
+        cs[4 + i] = (_Float16)sn;
       }
-      sm.rp.tc[tb][kk][ln] = c4;
-      sm.rp.ts[tb][kk][ln] = s4;
+      sm.rp.tcs[tb][kk][ln] = cs;
     }
     for (int e = threadIdx.x; e < NKK * 64; e += 256) {
       const int ln = e & 63, kk = e >> 6;
@@ -354,16 +355,12 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
         }
 #pragma unroll
         for (int tb = 0; tb < TBN; ++tb) {
-          const f32x4 c4 = sm.rp.tc[cur.sub * TBN + tb][kk][tl], s4 = sm.rp.ts[cur.sub * TBN + tb][kk][tl];
-          bf16x8 kr;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float x0 = up[0][tb][i], x1 = up[1][tb][i];
-            kr[i] = (__bf16)(x0 * c4[i] - x1 * s4[i]);
-            kr[4 + i] = (__bf16)(x0 * s4[i] + x1 * c4[i]);
-          }
-          s[tb] = mfma16(kr, qfh[kk], s[tb]);
-          s[tb] = mfma16(kr, qfl[kk], s[tb]);
+          const f16x8 cs = sm.rp.tcs[cur.sub * TBN + tb][kk][tl];
+          const f16x4 c4 = cs.lo, s4 = cs.hi;
+          const f16x4 x0 = __builtin_convertvector(up[0][tb], f16x4), x1 = __builtin_convertvector(up[1][tb], f16x4);
+          const f16x4 r0 = x0 * c4 - x1 * s4, r1 = x0 * s4 + x1 * c4;
+          const f16x8 kr = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
+          s[tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kr, qf[kk], s[tb], 0, 0, 0);
         }
       }
     }
