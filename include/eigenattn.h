@@ -146,6 +146,18 @@ EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const vo
                    const int32_t* dev_page_table, const int32_t* dev_seq_len,
                    int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
 
+/* The same fused projection for models with rotary position embedding
+ * (Sec. 4.3): the query keeps all d_head channels (W^Q is not folded, the
+ * rotation has to be applied to the full query), keys are projected with the
+ * ONE basis all heads share (W^K' = W^K_g U^K), values as in Eq. (8).
+ *   dev_wqkv   packed from [H*d_head + H_kv*r_k + H_kv*r_v, d], same ordering
+ *   dev_q      [B*T, H, d_head] out
+ * Everything else as ea_project_qkv.  Requires r_k <= d_head. */
+EA_API int ea_project_qkv_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
+                   void* dev_q, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
+
 /* Number of splits of the cached sequence ea_decode_attn would pick for
  * n_splits = 0, and the workspace it needs for a given split count. */
 EA_API int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len);

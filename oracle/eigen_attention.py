@@ -355,6 +355,47 @@ def standard_rope_decode(q, K_full, V, d_head: int, base: float = 10000.0):
     return softmax(s) @ np.asarray(V, F64)
 
 
+def fold_weights_rope(Wq, Wk, Wv, Wo, Uk_shared, Uv, n_heads: int, n_kv_heads: int):
+    """Weight folding for a RoPE model (Sec. 4.3): W^Q stays as it is (the rotation acts on the full query),
+    W^K'_g = W^K_g U^K with ONE basis U^K [d_h, r_k] for all heads; values and output as in Eq. (8).
+    Returns Wq_h [H, d, d_h], Wk_f [H_kv, d, r_k], Wv_f [H_kv, d, r_v], Wo_f [H, r_v, d]."""
+    Wq, Wk, Wv, Wo = (np.asarray(a, F64) for a in (Wq, Wk, Wv, Wo))
+    Uk_shared, Uv = np.asarray(Uk_shared, F64), np.asarray(Uv, F64)
+    d_h = Uk_shared.shape[0]
+    Wq_h = [Wq[:, i * d_h:(i + 1) * d_h] for i in range(n_heads)]
+    Wk_f = [Wk[:, g * d_h:(g + 1) * d_h] @ Uk_shared for g in range(n_kv_heads)]
+    Wv_f = [Wv[:, g * d_h:(g + 1) * d_h] @ Uv[g] for g in range(n_kv_heads)]
+    Wo_f = [Uv[_kv_head_of(i, n_heads, n_kv_heads)].T @ Wo[i * d_h:(i + 1) * d_h, :] for i in range(n_heads)]
+    return np.stack(Wq_h), np.stack(Wk_f), np.stack(Wv_f), np.stack(Wo_f)
+
+
+def decode_step_rope(x, folded, Uk_shared, cache: RankCache, d_head: int, base: float = 10000.0):
+    """One generation step of a RoPE model: x [B, d] -> project (full q, rank-r k and v), append one token per
+    sequence, attend with Eq. (10), project out -> y [B, d]."""
+    Wq_h, Wk_f, Wv_f, Wo_f = folded
+    q, k, v = project_qkv(x, Wq_h, Wk_f, Wv_f)
+    for b in range(x.shape[0]):
+        cache.append(b, k[b:b + 1], v[b:b + 1])
+    return out_proj(decode_attention_rope(q, cache, Uk_shared, d_head, base), Wo_f)
+
+
+def standard_rope_attention_block(x_hist, Wq, Wk, Wv, Wo, n_heads: int, n_kv_heads: int, base: float = 10000.0):
+    """Standard attention with RoPE (Eq. 9) for the LAST token of one sequence x_hist [n, d]: full-rank q and k,
+    both rotated to their positions."""
+    x_hist = np.asarray(x_hist, F64)
+    Wq, Wk, Wv, Wo = (np.asarray(a, F64) for a in (Wq, Wk, Wv, Wo))
+    n = x_hist.shape[0]
+    d_h = Wq.shape[1] // n_heads
+    heads_out = np.zeros((1, n_heads * d_h), F64)
+    for i in range(n_heads):
+        g = _kv_head_of(i, n_heads, n_kv_heads)
+        q = x_hist[n - 1] @ Wq[:, i * d_h:(i + 1) * d_h]
+        K = x_hist @ Wk[:, g * d_h:(g + 1) * d_h]
+        V = x_hist @ Wv[:, g * d_h:(g + 1) * d_h]
+        heads_out[0, i * d_h:(i + 1) * d_h] = standard_rope_decode(q, K, V, d_h, base)
+    return heads_out @ Wo
+
+
 def project_to_basis(A, U):
     """Rank-space coordinates of d_h-dimensional rows: A [.., d_h] U [d_h, r] (what Eq. 8 caches)."""
     return np.asarray(A, F64) @ np.asarray(U, F64)

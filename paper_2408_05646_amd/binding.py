@@ -16,14 +16,14 @@ __all__ = [
     "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
-    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope",
+    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope",
 ]
 
 EA_F32, EA_BF16 = 0, 1
 
 EXPORTED_SYMBOLS = (
     "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
-    "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
+    "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_project_qkv_rope", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
     "ea_decode_attn", "ea_decode_attn_rope", "ea_prefill_attn", "ea_out_proj",
 )
 
@@ -85,6 +85,7 @@ def load_library():
     lib.ea_packed_weight_elems.argtypes = [I32, I32, I32]
     lib.ea_pack_weight.argtypes = [VP, VP, I32, I32, I32, VP]
     lib.ea_project_qkv.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
+    lib.ea_project_qkv_rope.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_auto_splits.restype = I32
     lib.ea_decode_auto_splits.argtypes = [D, I32, I32]
     lib.ea_decode_workspace_bytes.restype = I64
@@ -222,24 +223,33 @@ def pack_weight(w_t, stream=None):
     return packed
 
 
-def project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
-    """x [B*T, d]; wqkv = pack_weight([N_qkv, d]); q_r [B*T, H, r_k] (float32 or bfloat16) is written,
-    k and v go to the pools."""
+def _project_qkv(fn_name, q_dim, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream):
     B = seq_len.shape[0]
     if x.shape[0] != B * T:
         raise ValueError("x must have B*T rows")
     _expect(x, desc.dtype, "x"); _expect(wqkv, desc.dtype, "wqkv")
     _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
     _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
-    n_out = desc.n_heads * desc.r_k + desc.n_kv_heads * (desc.r_k + desc.r_v)
+    n_out = desc.n_heads * q_dim + desc.n_kv_heads * (desc.r_k + desc.r_v)
     if wqkv.numel() != packed_weight_elems(n_out, desc.d_model, desc.dtype) or x.shape[1] != desc.d_model:
         raise ValueError("packed weight / activation size does not match the layer")
-    if q_r.numel() != B * T * desc.n_heads * desc.r_k:
-        raise ValueError("q_r has the wrong size")
-    rc = load_library().ea_project_qkv(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(q_r), _dt(q_r), _ptr(k_pool),
-                                       _ptr(v_pool), _ptr(page_table), _ptr(seq_len), B, T, page_table.shape[1],
-                                       k_pool.shape[0], _stream(stream))
-    _check(rc, "ea_project_qkv")
+    if q.numel() != B * T * desc.n_heads * q_dim:
+        raise ValueError("q has the wrong size")
+    rc = getattr(load_library(), fn_name)(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(q), _dt(q), _ptr(k_pool),
+                                          _ptr(v_pool), _ptr(page_table), _ptr(seq_len), B, T, page_table.shape[1],
+                                          k_pool.shape[0], _stream(stream))
+    _check(rc, fn_name)
+
+
+def project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+    """x [B*T, d]; wqkv = pack_weight([N_qkv, d]); q_r [B*T, H, r_k] (float32 or bfloat16) is written,
+    k and v go to the pools."""
+    _project_qkv("ea_project_qkv", desc.r_k, desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T, stream)
+
+
+def project_qkv_rope(desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+    """Rotary variant: wqkv = pack_weight([H*d_head + H_kv*(r_k + r_v), d]); q [B*T, H, d_head] is written."""
+    _project_qkv("ea_project_qkv_rope", desc.d_head, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream)
 
 
 def decode_auto_splits(desc, B: int, max_seq_len: int) -> int:

@@ -17,6 +17,7 @@ constexpr int kTile = 64;          // tokens per cache tile of the bf16 layout
 struct Geo {
   int32_t n_heads, n_kv_heads, group;   // group = n_heads / n_kv_heads
   int32_t r_k, r_v, r_k_pad, r_v_pad;
+  int32_t q_dim;                        // channels per query head the projection writes: r_k, or d_head (rotary)
   int32_t page_tokens;
   int32_t max_pages, pool_pages;
   int64_t k_slab, v_slab, k_page, v_page;   // elements
@@ -49,6 +50,7 @@ inline Geo make_geo(const ea_layer_desc* d, int32_t max_pages, int32_t pool_page
   g.group = d->n_heads / d->n_kv_heads;
   g.r_k = d->r_k;
   g.r_v = d->r_v;
+  g.q_dim = d->r_k;
   if (d->dtype == EA_BF16) {
     g.r_k_pad = round_up(d->r_k, 8);
     g.r_v_pad = round_up(d->r_v, 16);

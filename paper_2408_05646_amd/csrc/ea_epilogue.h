@@ -20,7 +20,7 @@ __device__ __forceinline__ void cache_put(void* pool, int64_t off, float v) {
 template <bool BF16_CACHE>
 __device__ __forceinline__ void qkv_store(const QkvDest& d, int32_t row, int32_t col, float val) {
   const Geo& g = d.g;
-  const int32_t nq = g.n_heads * g.r_k;
+  const int32_t nq = g.n_heads * g.q_dim;
   if (col < nq) {
     const int64_t idx = (int64_t)row * nq + col;
     if (d.q_is_f32) reinterpret_cast<float*>(d.q)[idx] = val;
@@ -64,7 +64,7 @@ struct QkvSlot {
 template <bool BF16_CACHE>
 __device__ __forceinline__ QkvSlot qkv_locate(const QkvDest& d, int32_t row, int32_t col) {
   const Geo& g = d.g;
-  const int32_t nq = g.n_heads * g.r_k;
+  const int32_t nq = g.n_heads * g.q_dim;
   if (col < nq) {
     const int64_t idx = (int64_t)row * nq + col;
     if (d.q_is_f32) return QkvSlot{reinterpret_cast<float*>(d.q) + idx, 1};

@@ -278,7 +278,7 @@ struct QkvEpBf16 {
   __device__ __forceinline__ void commit(const Slot& s, int r, int c, float v) const { qkv_commit<true>(d, s, r, c, v); }
   __device__ __forceinline__ bool swap_for(int c0) const {
     const Geo& g = d.g;
-    return fast_cols && c0 < g.n_heads * g.r_k + g.n_kv_heads * g.r_k;
+    return fast_cols && c0 < g.n_heads * g.q_dim + g.n_kv_heads * g.r_k;
   }
   // I is a compile-time index: the accumulators must stay in registers (no dynamic indexing).
   template <int I, int MI>
@@ -350,7 +350,7 @@ struct QkvEpBf16 {
   __device__ __forceinline__ void store(bool swap, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int N, int col,
                                         int quad) const {
     const Geo& g = d.g;
-    const int nq = g.n_heads * g.r_k, nk = g.n_kv_heads * g.r_k;
+    const int nq = g.n_heads * g.q_dim, nk = g.n_kv_heads * g.r_k;
     if (!fast_cols || c0 + 64 > N) {
       store_slow_all<MI>(std::make_integer_sequence<int, MI>{}, swap, r0, c0, acc, M, N, col, quad);
       return;
@@ -449,7 +449,7 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
 int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst,
                   hipStream_t st) {
   const Geo& g = dst.g;
-  const int nq = g.n_heads * g.r_k, nk = g.n_kv_heads * g.r_k, nv = g.n_kv_heads * g.r_v;
+  const int nq = g.n_heads * g.q_dim, nk = g.n_kv_heads * g.r_k, nv = g.n_kv_heads * g.r_v;
   const int32_t fast_cols = nq % 64 == 0 && nk % 64 == 0 && nv % 64 == 0 && g.r_k % 16 == 0 && g.r_v % 16 == 0;
   return launch_gemm<QkvEpBf16, false>(x, w_t, M, N, K, QkvEpBf16{dst, fast_cols}, st);
 }

@@ -167,3 +167,89 @@ def test_cfg3_rope_one_layer_sampled():
         cache = ora.RankCache.from_arrays([K[None]], [V[None]])
         ref = ora.decode_attention_rope(qh[b:b + 1, h:h + 1], cache, U, desc.d_head)
         assert_close(got_all[b:b + 1, h:h + 1], ref, TOL_BF16, f"rope stream b={b} h={h}")
+
+
+# ---------------------------------------------------------------------------
+# whole generation steps of a rotary model: ea_project_qkv_rope -> ea_decode_attn_rope -> ea_out_proj
+# ---------------------------------------------------------------------------
+def rope_weights(desc, g):
+    """Unfolded weights ~ N(0, 1/d), ONE key basis for all heads, one value basis per kv head; folded
+    (Sec. 4.3), rounded to the layer dtype, in the library's out-major layout.  Returns the packed device
+    weights, the basis on the device, and the same rounded values as oracle operands."""
+    d, H, Hkv, d_h, r_k, r_v = desc.d_model, desc.n_heads, desc.n_kv_heads, desc.d_head, desc.r_k, desc.r_v
+    Wq = synth.gaussian(g, (d, H * d_h), d ** -0.5)
+    Wk = synth.gaussian(g, (d, Hkv * d_h), d ** -0.5)
+    Wv = synth.gaussian(g, (d, Hkv * d_h), d ** -0.5)
+    Wo = synth.gaussian(g, (H * d_h, d), d ** -0.5)
+    Uk = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+    Uv = np.stack([synth.orthonormal_basis(g, d_h, r_v) for _ in range(Hkv)])
+    Wq_h, Wk_f, Wv_f, Wo_f = ora.fold_weights_rope(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    rows = [w.T for w in Wq_h] + [w.T for w in Wk_f] + [w.T for w in Wv_f]
+    wqkv_t = quantize(desc, np.concatenate(rows, axis=0))                       # [H*d_h + Hkv*(r_k + r_v), d]
+    wo_t = quantize(desc, np.concatenate(list(Wo_f), axis=0).T)                 # [d, H*r_v]
+    nq, nk = H * d_h, Hkv * r_k
+    folded_q = (np.stack([wqkv_t[i * d_h:(i + 1) * d_h].T for i in range(H)]),
+                np.stack([wqkv_t[nq + i * r_k:nq + (i + 1) * r_k].T for i in range(Hkv)]),
+                np.stack([wqkv_t[nq + nk + i * r_v:nq + nk + (i + 1) * r_v].T for i in range(Hkv)]),
+                np.stack([wo_t.T[i * r_v:(i + 1) * r_v] for i in range(H)]))
+    return (ea.pack_weight(to_dev(desc, wqkv_t)), ea.pack_weight(to_dev(desc, wo_t)), to_dev(desc, Uk), Uk, folded_q,
+            (Wq, Wk, Wv, Wo))
+
+
+@pytest.mark.parametrize("r", [32, 64])
+def test_f32_rope_decode_step(r):
+    """Tiny fp32 layer (d=256, H=4, d_h=64, n=256): cache of n-1 tokens, one generation step on the last."""
+    print(f"rope step f32 r={r}", flush=True)
+    s = synth.CFG1
+    desc = ea.LayerDesc(s.d_model, s.n_heads, s.n_kv_heads, s.d_head, r, r, ea.EA_F32, 16)
+    g = synth.rng(27, r)
+    wqkv, wo, U_dev, Uk, folded_q, unfolded = rope_weights(desc, g)
+    x_hist = np.float32(synth.gaussian(g, (s.n_ctx, s.d_model))).astype(np.float64)
+    _, k_hist, v_hist = ora.project_qkv(x_hist[:-1], *folded_q[:3])
+    K0 = [quantize(desc, k_hist.transpose(1, 0, 2))]
+    V0 = [quantize(desc, v_hist.transpose(1, 0, 2))]
+    dc = DeviceCache(desc, K0, V0, g, extra_len=1)
+    q = torch.empty((1, s.n_heads, s.d_head), dtype=torch.float32, device="cuda")
+    o = torch.empty((1, s.n_heads, r), dtype=torch.float32, device="cuda")
+    y = torch.empty((1, s.d_model), dtype=torch.float32, device="cuda")
+    ea.project_qkv_rope(desc, to_dev(desc, x_hist[-1:]), wqkv, q, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, 1)
+    ea.decode_attn_rope(desc, q, U_dev, 10000.0, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len + 1, o, n_splits=1)
+    ea.out_proj(desc, o.view(1, -1), wo, y)
+    torch.cuda.synchronize()
+    y_ref = ora.decode_step_rope(x_hist[-1:], folded_q, Uk, ora.RankCache.from_arrays(K0, V0), s.d_head)
+    assert_close(y.cpu().numpy(), y_ref, TOL_F32, "rope step y")
+    if r == s.d_head:   # full rank: the variant IS standard rotary attention (up to float32 weights)
+        y_std = ora.standard_rope_attention_block(x_hist, *unfolded, s.n_heads, s.n_kv_heads)
+        assert ora.rel_l2(y.cpu().numpy(), y_std) <= 2e-5
+
+
+def test_bf16_rope_decode_steps_end_to_end():
+    """GQA layer (d=512, 8 query heads on 2 kv heads, d_h=128, r=(80,48)), bf16: the cache is filled through
+    ea_project_qkv_rope (T = 333 tokens at once), then three generation steps; against the un-rounded fp64
+    oracle, so the cache quantisation is part of what is compared."""
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(28)
+    wqkv, wo, U_dev, Uk, folded_q, _ = rope_weights(desc, g)
+    B, n0, steps = 4, 333, 3
+    x_hist = quantize(desc, synth.gaussian(g, (B, n0 + steps, 512)))
+    dc = DeviceCache(desc, [np.zeros((2, 0, 80))] * B, [np.zeros((2, 0, 48))] * B, g, extra_len=n0 + steps)
+    q_pre = torch.empty((B * n0, 8, 128), dtype=torch.bfloat16, device="cuda")
+    ea.project_qkv_rope(desc, to_dev(desc, x_hist[:, :n0].reshape(B * n0, 512)), wqkv, q_pre, dc.k_pool, dc.v_pool,
+                        dc.page_table, dc.seq_len, n0)
+    cache = ora.RankCache.empty(B, 2, 80, 48)
+    _, k_pre, v_pre = ora.project_qkv(x_hist[:, :n0].reshape(B * n0, 512), *folded_q[:3])
+    for b in range(B):
+        cache.append(b, k_pre[b * n0:(b + 1) * n0], v_pre[b * n0:(b + 1) * n0])
+    q = torch.empty((B, 8, 128), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    for t in range(steps):
+        ea.project_qkv_rope(desc, to_dev(desc, x_hist[:, n0 + t]), wqkv, q, dc.k_pool, dc.v_pool, dc.page_table,
+                            dc.seq_len + n0 + t, 1)
+        ea.decode_attn_rope(desc, q, U_dev, 10000.0, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len + n0 + t + 1, o,
+                            n_splits=1)
+        ea.out_proj(desc, o.view(B, -1), wo, y)
+        torch.cuda.synchronize()
+        y_ref = ora.decode_step_rope(x_hist[:, n0 + t], folded_q, Uk, cache, 128)
+        err = assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"rope bf16 step {t}")
+        print(f"  step {t}: rel-L2 {err:.2e}", flush=True)

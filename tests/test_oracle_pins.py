@@ -378,6 +378,38 @@ def test_rope_variant_without_rotation_is_plain_low_rank_scores():
     assert np.allclose(o[0, 0], V[0, 0])
 
 
+def test_rope_step_full_rank_and_in_subspace_keys_equal_the_standard_rope_block():
+    """Whole generation step of a RoPE model.  (a) r = d_h with square orthonormal bases: identical to standard
+    RoPE attention.  (b) r < d_h, but W^K maps into the span of U^K and W^V into the span of U^V: projecting
+    to the basis and back loses nothing, so the low-rank step is again identical -- the approximation of
+    Sec. 4.3 is exact whenever keys and values live in the subspaces."""
+    g = synth.rng(911)
+    d, H, Hkv, d_h, n = 24, 4, 2, 8, 13
+    x_hist = synth.gaussian(g, (n, d))
+    Wq, Wo = synth.gaussian(g, (d, H * d_h), 0.3), synth.gaussian(g, (H * d_h, d), 0.3)
+    for r in (d_h, 3):
+        Uk = synth.orthonormal_basis(g, d_h, r)
+        Uv = np.stack([synth.orthonormal_basis(g, d_h, r) for _ in range(Hkv)])
+        if r == d_h:
+            Wk, Wv = synth.gaussian(g, (d, Hkv * d_h), 0.3), synth.gaussian(g, (d, Hkv * d_h), 0.3)
+        else:   # keys / values confined to the subspaces
+            Wk = np.concatenate([synth.gaussian(g, (d, r), 0.3) @ Uk.T for _ in range(Hkv)], axis=1)
+            Wv = np.concatenate([synth.gaussian(g, (d, r), 0.3) @ Uv[h].T for h in range(Hkv)], axis=1)
+        folded = ora.fold_weights_rope(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+        cache = ora.RankCache.empty(1, Hkv, r, r)
+        for t in range(n):
+            y = ora.decode_step_rope(x_hist[t:t + 1], folded, Uk, cache, d_h)
+        ref = ora.standard_rope_attention_block(x_hist, Wq, Wk, Wv, Wo, H, Hkv)
+        assert np.allclose(y, ref, rtol=1e-10, atol=1e-12), r
+    # and a generic low-rank basis does change the result (the test above is not vacuous)
+    Wk = synth.gaussian(g, (d, Hkv * d_h), 0.3)
+    folded = ora.fold_weights_rope(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    cache = ora.RankCache.empty(1, Hkv, 3, 3)
+    for t in range(n):
+        y = ora.decode_step_rope(x_hist[t:t + 1], folded, Uk, cache, d_h)
+    assert ora.rel_l2(y, ora.standard_rope_attention_block(x_hist, Wq, Wk, Wv, Wo, H, Hkv)) > 1e-3
+
+
 def test_bf16_rounding_helpers():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.0, 3.4028e38, np.inf], np.float32)
     r = synth.round_to_bf16(x)
