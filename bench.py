@@ -28,6 +28,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+ROPE_BASE = 10000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # The paper's own figures (other hardware, whole PyTorch / Hugging Face models): context, not the target.
@@ -46,7 +47,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -91,7 +92,7 @@ def _timed_single_thread(fn):
     return min(run(), run())
 
 
-def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int):
+def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: bool = False):
     """The fp64 oracle's decode attention on `n_streams` (sequence, head) streams of the bench workload's
     shape, single-threaded BLAS, host-generated inputs with the same distribution."""
     import numpy as np
@@ -103,13 +104,18 @@ def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int):
     # one sequence's worth of data, referenced by every sampled sequence (timing does not depend on values)
     K1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
     V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
-    q = g.standard_normal((n_seq, heads, r))
+    q = g.standard_normal((n_seq, heads, d_head if rope else r))
     cache = ora.RankCache.from_arrays([K1] * n_seq, [V1] * n_seq)
-    dt = _timed_single_thread(lambda: ora.decode_attention(q, cache, d_head))
+    if rope:
+        U = synth.orthonormal_basis(g, d_head, r)
+        dt = _timed_single_thread(lambda: ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE))
+    else:
+        dt = _timed_single_thread(lambda: ora.decode_attention(q, cache, d_head))
     cache_bytes = n_seq * heads * n_ctx * 2 * r * 2          # what the GPU kernel would stream (bf16)
     return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"decode attention of {n_seq * heads} (sequence, head) streams = one layer "
-                      f"(n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s; a full 32-layer step would take {dt * 32:.0f} s",
+            "sample": f"{'rotary ' if rope else ''}decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
+                      f"streams (n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s; a full 32-layer step would take "
+                      f"{dt * 32 * 512 / (n_seq * heads):.0f} s",
             "seconds": round(dt, 3)}
 
 
@@ -132,10 +138,11 @@ def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
 
 def bench_decode(args, torch, ea, synth):
     dev = "cuda"
-    s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[args.workload]
+    base_name, rope = args.workload.split("-")[0], args.workload.endswith("-rope")
+    s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[base_name]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
     H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
-    ranks = synth.cfg5_layer_ranks(L) if args.workload == "cfg5" else tuple((s.r_k, s.r_v) for _ in range(L))
+    ranks = synth.cfg5_layer_ranks(L) if base_name == "cfg5" else tuple((s.r_k, s.r_v) for _ in range(L))
     descs = [ea.LayerDesc(d, H, Hkv, s.d_head, rk, rv, ea.EA_BF16, P) for rk, rv in ranks]
     max_pages = n // P
     pool_pages = B * max_pages
@@ -151,22 +158,26 @@ def bench_decode(args, torch, ea, synth):
     # ---- synthetic, seeded inputs, generated on the device (172 GB cannot be staged from the host).
     # Cached rank-space rows z.M + 0.05 eps.U with orthogonal M are N(0, (1 + 0.0025) I): fill the pools with that.
     gen = torch.Generator(device=dev)
-    gen.manual_seed(synth.BASE_SEED + int(args.workload[-1]))
+    gen.manual_seed(synth.BASE_SEED + int(base_name[-1]))
     layers = []
     t_fill = time.perf_counter()
     for dc in descs:
-        n_qkv = H * dc.r_k + Hkv * (dc.r_k + dc.r_v)
+        q_dim = s.d_head if rope else dc.r_k          # the rotary variant keeps the query at full rank (Sec. 4.3)
+        n_qkv = H * q_dim + Hkv * (dc.r_k + dc.r_v)
         k_pool, v_pool = ea.alloc_pools(dc, pool_pages, zero=False)
         k_pool.normal_(0.0, 1.00125, generator=gen)
         v_pool.normal_(0.0, 1.00125, generator=gen)
         perm = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32)   # pages in seeded random order
         layers.append(dict(
             desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
-            S=args.n_splits or ea.decode_auto_splits(dc, B, n),
+            S=args.n_splits or ea.decode_auto_splits(dc, B, n) * (2 if rope else 1),
             wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             wo=ea.pack_weight((torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),
-            q_r=torch.empty((B, H, dc.r_k), dtype=torch.float32, device=dev),
+            q_r=torch.empty((B, H, q_dim), dtype=torch.float32, device=dev),
+            # rotary variant: ONE key basis for all heads of the layer, orthonormal columns (QR of a Gaussian)
+            u_k=(torch.linalg.qr(torch.randn((s.d_head, dc.r_k), generator=gen, device=dev))[0].contiguous()
+                 .to(torch.bfloat16) if rope else None),
             o=torch.empty((B, H, dc.r_v), dtype=torch.float32, device=dev),
             y=torch.empty((B, d), dtype=torch.bfloat16, device=dev)))
     torch.cuda.synchronize()
@@ -179,12 +190,16 @@ def bench_decode(args, torch, ea, synth):
 
     def step(events=None):
         for li, l in enumerate(layers):
-            ea.project_qkv(l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"],
-                           seq_before, 1)
+            (ea.project_qkv_rope if rope else ea.project_qkv)(
+                l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_before, 1)
             if events is not None:
                 events[li][0].record()
-            ea.decode_attn(l["desc"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_after, l["o"],
-                           n_splits=l["S"], ws=ws)
+            if rope:
+                ea.decode_attn_rope(l["desc"], l["q_r"], l["u_k"], ROPE_BASE, l["k_pool"], l["v_pool"], l["page_table"],
+                                    seq_after, l["o"], n_splits=l["S"], ws=ws)
+            else:
+                ea.decode_attn(l["desc"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_after, l["o"],
+                               n_splits=l["S"], ws=ws)
             if events is not None:
                 events[li][1].record()
             ea.out_proj(l["desc"], l["o"].view(B, -1), l["wo"], l["y"])
@@ -232,10 +247,12 @@ def bench_decode(args, torch, ea, synth):
     # ---- algorithmic bytes (what the method itself must move)
     attn_bytes_sum, step_bytes = 0, 0
     for dc in descs:
-        n_qkv = H * dc.r_k + Hkv * (dc.r_k + dc.r_v)
+        q_dim = s.d_head if rope else dc.r_k
+        n_qkv = H * q_dim + Hkv * (dc.r_k + dc.r_v)
         cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
-        attn = cache_bytes + B * H * dc.r_k * 4 + B * H * dc.r_v * 4 + B * max_pages * 4
-        proj = n_qkv * d * 2 + B * d * 2 + B * H * dc.r_k * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
+        attn = cache_bytes + B * H * q_dim * 4 + B * H * dc.r_v * 4 + B * max_pages * 4 + \
+            (s.d_head * dc.r_k * 2 if rope else 0)
+        proj = n_qkv * d * 2 + B * d * 2 + B * H * q_dim * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
         outp = H * dc.r_v * d * 2 + B * H * dc.r_v * 4 + B * d * 2
         attn_bytes_sum += attn
         step_bytes += attn + proj + outp
@@ -243,9 +260,11 @@ def bench_decode(args, torch, ea, synth):
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     attn_gbps = attn_bytes / (attn_us_avg * 1e-6) / 1e9
     splits = sorted(set(l["S"] for l in layers))
-    kern = "decode_bf16_kernel" + ("" if splits == [1] else " + merge_splits_kernel") + " (one ea_decode_attn call)"
+    kern = "decode_bf16_kernel" + (" (rotary variant)" if rope else "") + \
+        ("" if splits == [1] else " + merge_splits_kernel") + \
+        (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
 
-    rank_note = f"r_k=r_v={s.r_k}" if args.workload != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
+    rank_note = f"r_k=r_v={s.r_k}" if base_name != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
         "metric": "low-rank decode attn: achieved HBM GB/s over the whole decode step"
                   + (" (B=16, n=32k, r=80)" if args.workload == "cfg3" else f" ({args.workload})"),
@@ -254,7 +273,10 @@ def bench_decode(args, torch, ea, synth):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload} decode: Llama-2-7B-shaped, {L} layers resident, B={B}, n={n}, "
                                f"H={H}, H_kv={Hkv}, d_h={s.d_head}, {rank_note}, bf16 paged cache (page {P} tokens, "
-                               f"pages in random order), project_qkv + decode_attn + out_proj per layer",
+                               f"pages in random order), "
+                               + ("rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope + out_proj "
+                                  "per layer, query at position n-1, base 10000" if rope else
+                                  "project_qkv + decode_attn + out_proj per layer"),
                    "layers": L, "batch": B, "n_ctx": n, "page_tokens": P, "n_splits": splits},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBPS, 2),
         "us_per_step": round(ms_per_step * 1e3, 1),
@@ -299,7 +321,9 @@ def bench_decode(args, torch, ea, synth):
             "decode_attn_us_per_layer": round(full_us, 1), "achieved_GBps": round(full_bytes / full_us / 1e3, 1),
             "latency_ratio_lowrank_over_fullrank": round(attn_us_avg / full_us, 4),
             "ratio_predicted_by_rank": round(mean_rank / s.d_head, 4),
-            "note": "same kernel, r_k = r_v = d_h = 128, same B, n and page table, one layer-sized buffer"}
+            "note": "position-free kernel, r_k = r_v = d_h = 128, same B, n and page table, one layer-sized buffer"
+                    + ("; this is also what standard attention with rotary positions costs per step, since its cache "
+                       "holds keys that are already rotated" if rope else "")}
         del fk, fv
 
     if args.calibrate_copy:
@@ -311,7 +335,8 @@ def bench_decode(args, torch, ea, synth):
         result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams, n, ranks[0][0], s.d_head)
+        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 1), n, ranks[0][0], s.d_head,
+                                                   rope=rope)
     return result
 
 

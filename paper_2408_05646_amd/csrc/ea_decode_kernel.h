@@ -195,50 +195,6 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     }
     }
   };
-  if constexpr (ROPE) {
-    if (threadIdx.x < NKK * 16)
-      sm.rp.turns[threadIdx.x] =
-          exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base) * 0.15915494309189535;
-    for (int e = threadIdx.x; e < 2 * NKK * KS * 64; e += 256) {
-      const int ln = e & 63, ks = (e >> 6) % KS, fb = e / (64 * KS);
-      const uint16_t* urow = a.u_k + (int64_t)(2 * ((fb >> 1) * 16 + (ln & 15)) + (fb & 1)) * g.r_k;
-      typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
-      u16x8 w;
-#pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int rho = ks * 32 + (ln >> 4) * 8 + x;
-        w[x] = rho < g.r_k ? urow[rho] : (uint16_t)0;
-      }
-      sm.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < 4 * NKK * 64; e += 256) {
-      const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
-      f16x8 cs;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float c, sn;
-        rot_turns((double)(tb * 16 + (ln & 15)) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
-        cs[i] = (_Float16)c;
-        cs[4 + i] = (_Float16)sn;
-      }
-      sm.rp.tcs[tb][kk][ln] = cs;
-    }
-    for (int e = threadIdx.x; e < NKK * 64; e += 256) {
-      const int ln = e & 63, kk = e >> 6;
-      f32x4 c4, s4;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float c, sn;
-        rot_turns(-(double)(4 * kTile) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
-        c4[i] = c;
-        s4[i] = sn;
-      }
-      sm.rp.sc[kk][ln] = c4;
-      sm.rp.ss[kk][ln] = s4;
-    }
-    __syncthreads();
-  }
 
   // Where a wave stands in its split.  Everything here is wave-uniform and lives in scalar registers; the
   // logical page and the tile's place inside it are stepped along, not divided out, per iteration.
@@ -310,7 +266,56 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     // masked below: the loads never depend on the page table's contents, only their address does.
     load_k(cur, max(page, 0));
     load_v(cur, max(page, 0));
-    if constexpr (ROPE) {
+  }
+  // the rotary tables are built while the first tile is on its way
+  if constexpr (ROPE) {
+    if (threadIdx.x < NKK * 16)
+      sm.rp.turns[threadIdx.x] =
+          exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base) * 0.15915494309189535;
+    for (int e = threadIdx.x; e < 2 * NKK * KS * 64; e += 256) {
+      const int ln = e & 63, ks = (e >> 6) % KS, fb = e / (64 * KS);
+      const uint16_t* urow = a.u_k + (int64_t)(2 * ((fb >> 1) * 16 + (ln & 15)) + (fb & 1)) * g.r_k;
+      typedef __attribute__((ext_vector_type(8))) uint16_t u16x8;
+      u16x8 w;
+      const int rho0 = ks * 32 + (ln >> 4) * 8;
+      if ((g.r_k & 7) == 0 && (reinterpret_cast<uintptr_t>(a.u_k) & 15) == 0) {   // rows are whole 16-byte units
+        w = rho0 < g.r_k ? *reinterpret_cast<const u16x8*>(urow + rho0) : u16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      } else {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) w[x] = rho0 + x < g.r_k ? urow[rho0 + x] : (uint16_t)0;
+      }
+      sm.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < 4 * NKK * 64; e += 256) {
+      const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
+      f16x8 cs;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float c, sn;
+        rot_turns((double)(tb * 16 + (ln & 15)) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        cs[i] = (_Float16)c;
+        cs[4 + i] = (_Float16)sn;
+      }
+      sm.rp.tcs[tb][kk][ln] = cs;
+    }
+    for (int e = threadIdx.x; e < NKK * 64; e += 256) {
+      const int ln = e & 63, kk = e >> 6;
+      f32x4 c4, s4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float c, sn;
+        rot_turns(-(double)(4 * kTile) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        c4[i] = c;
+        s4[i] = sn;
+      }
+      sm.rp.sc[kk][ln] = c4;
+      sm.rp.ss[kk][ln] = s4;
+    }
+    __syncthreads();
+  }
+  if constexpr (ROPE) {
+    if (have) {
       seed_q(cur.tile);
       pack_q();
     }
