@@ -61,9 +61,12 @@ def parse_args():
     return ap.parse_args()
 
 
-def traffic_from_profiles():
+def traffic_from_profiles(workload: str):
     """HBM bytes per decode-attention launch measured with rocprofv3 --pmc (committed summary), or None."""
-    path = os.path.join(ROOT, "profiles", "decode_attn_cfg3_hbm_traffic.txt")
+    name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt"}.get(workload)
+    if name is None:
+        return None
+    path = os.path.join(ROOT, "profiles", name)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -290,7 +293,7 @@ def bench_decode(args, torch, ea, synth):
         "paper_context": PAPER_CONTEXT,
         "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profiles() if args.workload == "cfg3" else None,
+                     "traffic": traffic_from_profiles(args.workload),
                      "kernel": kern, "bytes_per_launch": round(attn_bytes), "us_per_launch": round(attn_us_avg, 2)},
     }
 
