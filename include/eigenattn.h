@@ -207,6 +207,24 @@ EA_API int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const
                     const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out,
                     int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages, void* stream);
 
+/* Prefill-phase attention for models with rotary position embedding (Sec. 4.3,
+ * Eq. 9-10) with a causal mask: query j of sequence b sits at position
+ * p_j = seq_len[b] - n + j and sees the cached positions t <= p_j with
+ *   s_jt = rot(q_j, p_j) . rot(U^K K_r[t], t) / sqrt(d_h)
+ * (rot, U^K, rope_base as in ea_decode_attn_rope).
+ *   dev_q   [B, n, H, d_head], NOT rotated; dev_out [B, n, H, r_v]; dev_u_k [d_head, r_k]: desc dtype
+ *   dev_ws  EA_BF16: ea_prefill_rope_workspace_bytes(desc, B, n, max_pages) bytes, 16-byte aligned: the
+ *           keys, back at d_head channels and rotated, and the rotated queries are kept there for the
+ *           duration of the call (B * max_pages * H_kv * page_tokens * d_head + B * n * H * d_head
+ *           bfloat16 values).  EA_F32 needs none (0 bytes; dev_ws may be null).
+ * dev_seq_len [B] includes the n new tokens. */
+EA_API int64_t ea_prefill_rope_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_pages);
+EA_API int ea_prefill_attn_rope(const ea_layer_desc* desc, const void* dev_q, const void* dev_u_k, double rope_base,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out,
+                    int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -347,6 +347,29 @@ def decode_attention_rope(q, cache: RankCache, Uk, d_head: int, base: float = 10
     return out
 
 
+def prefill_attention_rope(q, cache: RankCache, Uk, d_head: int, base: float = 10000.0):
+    """Prefill-phase Eigen Attention for a RoPE model (Sec. 4.3, Eq. 10 with the causal mask of the prefill):
+    q [B, n, H, d_h] full-rank and not rotated -> o [B, n, H, r_v].  Query j of sequence b sits at position
+    len_b - n + j, is rotated to it, and attends to the cached keys at positions <= its own, each brought back
+    to d_h channels with the shared basis and rotated to its position."""
+    q = np.asarray(q, F64)
+    Uk = np.asarray(Uk, F64)
+    B, n, H, _ = q.shape
+    out = np.zeros((B, n, H, cache.r_v), F64)
+    for b in range(B):
+        L = cache.seq_len(b)
+        assert L >= n
+        for i in range(H):
+            g = _kv_head_of(i, H, cache.n_kv_heads)
+            K_pos = rope_rotate(cache.K[b][g] @ Uk.T, np.arange(L), base)
+            V = cache.V[b][g]
+            for j in range(n):
+                pos = L - n + j
+                s = (K_pos[:pos + 1] @ rope_rotate(q[b, j, i], pos, base)) / math.sqrt(d_head)
+                out[b, j, i] = softmax(s) @ V[:pos + 1]
+    return out
+
+
 def standard_rope_decode(q, K_full, V, d_head: int, base: float = 10000.0):
     """Standard attention with RoPE for one head: q [d_h] at position n-1, K_full [n, d_h], V [n, r_v]."""
     K_full = np.asarray(K_full, F64)
@@ -377,6 +400,20 @@ def decode_step_rope(x, folded, Uk_shared, cache: RankCache, d_head: int, base: 
     for b in range(x.shape[0]):
         cache.append(b, k[b:b + 1], v[b:b + 1])
     return out_proj(decode_attention_rope(q, cache, Uk_shared, d_head, base), Wo_f)
+
+
+def prefill_step_rope(x, folded, Uk_shared, cache: RankCache, d_head: int, base: float = 10000.0):
+    """Prefill of a RoPE model: x [B, n, d] -> project, append n tokens per sequence, causal attention with
+    Eq. (10), project out -> y [B, n, d]."""
+    Wq_h, Wk_f, Wv_f, Wo_f = folded
+    x = np.asarray(x, F64)
+    B, n, d = x.shape
+    q, k, v = project_qkv(x.reshape(B * n, d), Wq_h, Wk_f, Wv_f)
+    q, k, v = (a.reshape(B, n, *a.shape[1:]) for a in (q, k, v))
+    for b in range(B):
+        cache.append(b, k[b], v[b])
+    o = prefill_attention_rope(q, cache, Uk_shared, d_head, base)
+    return out_proj(o.reshape(B * n, *o.shape[2:]), Wo_f).reshape(B, n, -1)
 
 
 def standard_rope_attention_block(x_hist, Wq, Wk, Wv, Wo, n_heads: int, n_kv_heads: int, base: float = 10000.0):

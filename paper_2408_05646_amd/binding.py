@@ -16,7 +16,7 @@ __all__ = [
     "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
-    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope",
+    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -24,7 +24,8 @@ EA_F32, EA_BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
     "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_project_qkv_rope", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
-    "ea_decode_attn", "ea_decode_attn_rope", "ea_prefill_attn", "ea_out_proj",
+    "ea_decode_attn", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
+    "ea_out_proj",
 )
 
 
@@ -92,6 +93,9 @@ def load_library():
     lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_prefill_rope_workspace_bytes.argtypes = [D, I32, I32, I32]
+    lib.ea_prefill_rope_workspace_bytes.restype = I64
+    lib.ea_prefill_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_prefill_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_out_proj.argtypes = [D, VP, I32, VP, VP, I32, VP]
     _LIB = lib
@@ -311,6 +315,29 @@ def prefill_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, stream=Non
                                         _ptr(seq_len), _ptr(out), B, n, page_table.shape[1], k_pool.shape[0],
                                         _stream(stream))
     _check(rc, "ea_prefill_attn")
+
+
+def prefill_rope_workspace_bytes(desc, B: int, n: int, max_pages: int) -> int:
+    return int(load_library().ea_prefill_rope_workspace_bytes(ctypes.byref(desc), B, n, max_pages))
+
+
+def prefill_attn_rope(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table, seq_len, out, ws=None,
+                      stream=None) -> None:
+    """Rotary prefill: q [B, n, H, d_head] (layer dtype, not rotated) -> out [B, n, H, r_v], causal."""
+    B, n = q.shape[0], q.shape[1]
+    _expect(q, desc.dtype, "q"); _expect(out, desc.dtype, "out"); _expect(u_k, desc.dtype, "u_k")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    if q.numel() != B * n * desc.n_heads * desc.d_head or out.numel() != B * n * desc.n_heads * desc.r_v:
+        raise ValueError("q / out have the wrong size")
+    if u_k.numel() != desc.d_head * desc.r_k or not u_k.is_contiguous():
+        raise ValueError("u_k must be a contiguous [d_head, r_k] tensor")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_prefill_attn_rope(ctypes.byref(desc), _ptr(q), _ptr(u_k), float(rope_base), _ptr(k_pool),
+                                             _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(out), B, n,
+                                             page_table.shape[1], k_pool.shape[0], _ptr(ws), ws_bytes,
+                                             _stream(stream))
+    _check(rc, "ea_prefill_attn_rope")
 
 
 def out_proj(desc, o, wo, y, stream=None) -> None:

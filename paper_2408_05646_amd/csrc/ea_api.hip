@@ -266,6 +266,40 @@ int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* 
                      dev_page_table, dev_seq_len, (float*)dev_out, B, n, (hipStream_t)stream);
 }
 
+int64_t ea_prefill_rope_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_pages) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || n <= 0 || max_pages <= 0) return -1;
+  return prefill_rope_ws_bytes(desc, B, n, max_pages);
+}
+
+int ea_prefill_attn_rope(const ea_layer_desc* desc, const void* dev_q, const void* dev_u_k, double rope_base,
+                         const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
+                         const int32_t* dev_seq_len, void* dev_out, int32_t B, int32_t n, int32_t max_pages,
+                         int32_t pool_pages, void* dev_ws, int64_t ws_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q || !dev_u_k || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || n <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if (!(rope_base > 1.0) || !(rope_base < 1e30)) return EA_ERR_ARG;
+  if (desc->r_k > desc->d_head) return EA_ERR_SHAPE;
+  if (!aligned16(dev_q) || !aligned16(dev_u_k) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) ||
+      !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  clear_stale_error();
+  if (desc->dtype == EA_BF16) {
+    if (desc->d_head != 64 && desc->d_head != 128) return EA_ERR_SHAPE;
+    if (!dev_ws || !aligned16(dev_ws) || ws_bytes < prefill_rope_ws_bytes(desc, B, n, max_pages))
+      return EA_ERR_WORKSPACE;
+    return prefill_rope_bf16(desc, g, dev_q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len,
+                             dev_out, B, n, dev_ws, (hipStream_t)stream);
+  }
+  if (desc->d_head % 2 != 0 || desc->d_head > 256) return EA_ERR_SHAPE;
+  return prefill_rope_f32(desc, g, (const float*)dev_q, (const float*)dev_u_k, rope_base, (const float*)dev_k_pool,
+                          (const float*)dev_v_pool, dev_page_table, dev_seq_len, (float*)dev_out, B, n,
+                          (hipStream_t)stream);
+}
+
 int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, const void* dev_wo_t, void* dev_y,
                 int32_t M, void* stream) {
   int rc = validate_desc(desc);

@@ -113,6 +113,15 @@ __device__ __forceinline__ float quad_column_max(float x) {
   return fmaxf(__builtin_bit_cast(float, (unsigned)b[0]), __builtin_bit_cast(float, (unsigned)b[1]));
 }
 
+// cos and sin of an angle given in REVOLUTIONS.  The whole turns are dropped in double precision (positions
+// reach 10^5 and more radians, where single precision no longer resolves the angle); v_cos_f32 / v_sin_f32 take
+// the remaining fraction of a turn directly.
+__device__ __forceinline__ void rot_turns(double x, float& c, float& s) {
+  const float f = (float)(x - rint(x));
+  c = __builtin_amdgcn_cosf(f);
+  s = __builtin_amdgcn_sinf(f);
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // The HIP runtime keeps the last error of ANY earlier call of the process (another library's
@@ -140,7 +149,17 @@ int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const 
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st);
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
-                 const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st);
+                 const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,
+                 int32_t k_compact = 0);
+// Rotary prefill (bf16): rotated full-rank keys and rotated queries are written to the workspace, then the
+// position-free prefill kernel runs at rank d_head on them.
+int64_t prefill_rope_ws_bytes(const ea_layer_desc* d, int32_t B, int32_t n, int32_t max_pages);
+int prefill_rope_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* u_k, double rope_base,
+                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                      void* out, int32_t B, int32_t n, void* ws, hipStream_t st);
+int prefill_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
+                     const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                     float* out, int32_t B, int32_t n, hipStream_t st);
 int prefill_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n, hipStream_t st);
 

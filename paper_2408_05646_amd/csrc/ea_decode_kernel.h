@@ -45,15 +45,6 @@ struct DecodeArgs {
   double log2_base;   // log2 of the rotary base
 };
 
-// cos and sin of an angle given in REVOLUTIONS.  The whole turns are dropped in double precision (positions
-// reach 10^5 and more radians, where single precision no longer resolves the angle); v_cos_f32 / v_sin_f32 take
-// the remaining fraction of a turn directly.
-__device__ __forceinline__ void rot_turns(double x, float& c, float& s) {
-  const float f = (float)(x - rint(x));
-  c = __builtin_amdgcn_cosf(f);
-  s = __builtin_amdgcn_sinf(f);
-}
-
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 

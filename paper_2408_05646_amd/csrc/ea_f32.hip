@@ -173,6 +173,7 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
 }
 
 // Causal prefill: one workgroup per (query, head, sequence); query j sits at position len - n_q + j.
+template <bool ROPE>
 __global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
   const Geo& g = a.g;
   const int j = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
@@ -182,10 +183,20 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
   const int64_t row = (((int64_t)b * a.n_q + j) * g.n_heads + head);
   float m, l, acc;
   __shared__ float sq[256];
-  if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[row * g.r_k + threadIdx.x];
-  __syncthreads();
-  attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
-             pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+  if (!ROPE) {
+    if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[row * g.r_k + threadIdx.x];
+    __syncthreads();
+    attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
+               pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+  } else {
+    __shared__ double theta[128];
+    if (threadIdx.x < a.d_head) sq[threadIdx.x] = a.q[row * a.d_head + threadIdx.x];
+    if (threadIdx.x < a.d_head / 2)
+      theta[threadIdx.x] = exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base);
+    __syncthreads();
+    attend_f32(RopeScore{sq, a.u_k, theta, g.r_k, a.d_head, pos}, a.k_pool, a.v_pool,
+               a.page_table + (int64_t)b * g.max_pages, g, kvh, 0, pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+  }
   const int c = threadIdx.x;
   if (c < g.r_v) a.out[row * g.r_v + c] = l > 0.f ? acc / l : 0.f;
 }
@@ -236,7 +247,19 @@ int prefill_f32(const ea_layer_desc* d, const Geo& g, const float* q, const floa
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n, hipStream_t st) {
   if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
-  prefill_f32_kernel<<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  prefill_f32_kernel<false><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int prefill_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
+                     const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                     float* out, int32_t B, int32_t n, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  if (d->d_head > 256 || d->d_head % 2 != 0) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
+  a.u_k = u_k;
+  a.log2_base = log2(rope_base);
+  prefill_f32_kernel<true><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 

@@ -26,6 +26,7 @@ struct PrefillArgs {
   int32_t n_q;
   int32_t batch;
   int32_t n_qtiles;   // query tiles per (sequence, head) = gridDim.x / (H * batch)
+  int32_t k_compact;  // K pages are not looked up: logical page lp of sequence b is page b*max_pages + lp of k_pool
   float scale_log2;
 };
 
@@ -188,7 +189,8 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
   auto load_k = [&](int t, int page) __attribute__((always_inline)) {
-    const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
+    const int64_t kpage = a.k_compact ? (int64_t)b * g.max_pages + t / tiles_per_page : page;
+    const uint16_t* base = a.k_pool + kpage * g.k_page + (int64_t)kvh * g.k_slab +
                            (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad);
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb)
@@ -289,7 +291,8 @@ static int dispatch_ncb(int ncb, const PrefillArgs& a, int32_t B, hipStream_t st
 }
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
-                 const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st) {
+                 const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,
+                 int32_t k_compact) {
   if ((int64_t)((n + 127) / 128) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
   if (g.r_k % 8 != 0 || g.r_v % 4 != 0) return EA_ERR_SHAPE;     // 16-byte q rows, 8-byte output stores
   PrefillArgs a;
@@ -301,6 +304,7 @@ int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void
   a.out = (uint16_t*)out;
   a.g = g;
   a.n_q = n;
+  a.k_compact = k_compact;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   switch (ks) {

@@ -225,8 +225,8 @@ def test_f32_rope_decode_step(r):
 
 def test_bf16_rope_decode_steps_end_to_end():
     """GQA layer (d=512, 8 query heads on 2 kv heads, d_h=128, r=(80,48)), bf16: the cache is filled through
-    ea_project_qkv_rope (T = 333 tokens at once), then three generation steps; against the un-rounded fp64
-    oracle, so the cache quantisation is part of what is compared."""
+    ea_project_qkv_rope (T = 333 tokens at once) and the prompt attended with ea_prefill_attn_rope, then three
+    generation steps; against the un-rounded fp64 oracle, so the cache quantisation is part of what is compared."""
     desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
     g = synth.rng(28)
     wqkv, wo, U_dev, Uk, folded_q, _ = rope_weights(desc, g)
@@ -236,10 +236,18 @@ def test_bf16_rope_decode_steps_end_to_end():
     q_pre = torch.empty((B * n0, 8, 128), dtype=torch.bfloat16, device="cuda")
     ea.project_qkv_rope(desc, to_dev(desc, x_hist[:, :n0].reshape(B * n0, 512)), wqkv, q_pre, dc.k_pool, dc.v_pool,
                         dc.page_table, dc.seq_len, n0)
+    o_pre = torch.empty((B, n0, 8, 48), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((ea.prefill_rope_workspace_bytes(desc, B, n0, dc.max_pages) // 2,), dtype=torch.bfloat16,
+                     device="cuda")
+    ea.prefill_attn_rope(desc, q_pre.view(B, n0, 8, 128), U_dev, 10000.0, dc.k_pool, dc.v_pool, dc.page_table,
+                         dc.seq_len + n0, o_pre, ws=ws)
+    y_pre = torch.empty((B * n0, 512), dtype=torch.bfloat16, device="cuda")
+    ea.out_proj(desc, o_pre.view(B * n0, -1), wo, y_pre)
+    torch.cuda.synchronize()
     cache = ora.RankCache.empty(B, 2, 80, 48)
-    _, k_pre, v_pre = ora.project_qkv(x_hist[:, :n0].reshape(B * n0, 512), *folded_q[:3])
-    for b in range(B):
-        cache.append(b, k_pre[b * n0:(b + 1) * n0], v_pre[b * n0:(b + 1) * n0])
+    y_pre_ref = ora.prefill_step_rope(x_hist[:, :n0], folded_q, Uk, cache, 128)
+    err = assert_close(y_pre.float().cpu().numpy().reshape(B, n0, 512), y_pre_ref, TOL_BF16, "rope bf16 prefill y")
+    print(f"  prefill: rel-L2 {err:.2e}", flush=True)
     q = torch.empty((B, 8, 128), dtype=torch.float32, device="cuda")
     o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
     y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
@@ -253,3 +261,41 @@ def test_bf16_rope_decode_steps_end_to_end():
         y_ref = ora.decode_step_rope(x_hist[:, n0 + t], folded_q, Uk, cache, 128)
         err = assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"rope bf16 step {t}")
         print(f"  step {t}: rel-L2 {err:.2e}", flush=True)
+
+
+# ---------------------------------------------------------------------------
+# ea_prefill_attn_rope
+# ---------------------------------------------------------------------------
+def run_prefill_rope(desc, K, V, q, U, base, g):
+    dc = DeviceCache(desc, K, V, g)
+    B, n = q.shape[0], q.shape[1]
+    out = torch.full((B, n, desc.n_heads, desc.r_v), float("nan"), dtype=torch.float32, device="cuda").to(
+        torch.bfloat16 if desc.dtype == ea.EA_BF16 else torch.float32)
+    nbytes = ea.prefill_rope_workspace_bytes(desc, B, n, dc.max_pages)
+    ws = torch.full((max(nbytes // 2, 8),), float("nan"), dtype=torch.bfloat16, device="cuda") if nbytes else None
+    ea.prefill_attn_rope(desc, to_dev(desc, q), to_dev(desc, U), base, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len,
+                         out, ws=ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,d_h,r_k,r_v,lens,n,P", [
+    (ea.EA_F32, 4, 2, 64, 32, 24, [40, 17, 64], 17, 16),
+    (ea.EA_F32, 2, 2, 48, 48, 16, [130], 130, 32),
+    (ea.EA_BF16, 4, 2, 128, 80, 48, [300, 257, 512], 200, 64),        # queries = the last 200 positions
+    (ea.EA_BF16, 2, 2, 128, 80, 80, [333], 333, 64),                  # whole prompt
+    (ea.EA_BF16, 8, 2, 64, 40, 32, [129, 64], 64, 128),
+    (ea.EA_BF16, 2, 1, 128, 128, 64, [700], 100, 64),                 # r_k = d_h: plain rotary attention
+    (ea.EA_BF16, 2, 2, 128, 72, 40, [1500], 70, 192),                 # padded ranks, three tiles per page
+])
+def test_prefill_rope(dtype, H, Hkv, d_h, r_k, r_v, lens, n, P):
+    print(f"rope prefill dtype={dtype} H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) lens={lens} n={n} P={P}", flush=True)
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, dtype, P)
+    g = synth.rng(29, H, r_k, n)
+    U = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    q = quantize(desc, synth.gaussian(g, (len(lens), n, H, d_h), 1.5))
+    got = run_prefill_rope(desc, K, V, q, U, 10000.0, g)
+    ref = ora.prefill_attention_rope(q, ora.RankCache.from_arrays(K, V), U, d_h)
+    err = assert_close(got, ref, TOL_BF16 if dtype == ea.EA_BF16 else TOL_F32, "rope prefill")
+    print(f"  rel-L2 {err:.2e}", flush=True)

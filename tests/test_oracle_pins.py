@@ -410,6 +410,33 @@ def test_rope_step_full_rank_and_in_subspace_keys_equal_the_standard_rope_block(
     assert ora.rel_l2(y, ora.standard_rope_attention_block(x_hist, Wq, Wk, Wv, Wo, H, Hkv)) > 1e-3
 
 
+def test_rope_prefill_rows_are_the_decode_results_of_their_prefixes():
+    """Row j of the causal RoPE prefill = the RoPE decode of query j over the first pos_j + 1 cached tokens
+    (the generation phase is the prefill's last row, Sec. 2), and with r = d_h it is standard causal RoPE
+    attention computed from scratch."""
+    g = synth.rng(912)
+    H, Hkv, d_h, r_k, r_v, L, n = 4, 2, 8, 5, 3, 11, 4
+    U = synth.orthonormal_basis(g, d_h, r_k)
+    K_r, V = synth.gaussian(g, (Hkv, L, r_k)), synth.gaussian(g, (Hkv, L, r_v))
+    q = synth.gaussian(g, (1, n, H, d_h))
+    o = ora.prefill_attention_rope(q, ora.RankCache.from_arrays([K_r], [V]), U, d_h)
+    for j in range(n):
+        pos = L - n + j
+        prefix = ora.RankCache.from_arrays([K_r[:, :pos + 1]], [V[:, :pos + 1]])
+        assert np.allclose(o[0, j], ora.decode_attention_rope(q[:, j], prefix, U, d_h)[0], rtol=1e-12, atol=1e-14)
+    U_sq = synth.orthonormal_basis(g, d_h, d_h)
+    K_full = synth.gaussian(g, (Hkv, L, d_h))
+    o = ora.prefill_attention_rope(q, ora.RankCache.from_arrays([ora.project_to_basis(K_full, U_sq)], [V]), U_sq, d_h)
+    for i in range(H):
+        for j in range(n):
+            pos = L - n + j
+            s = [sum(a * b for a, b in zip(brute_rope(q[0, j, i].tolist(), pos, 10000.0),
+                                           brute_rope(K_full[i // 2, t].tolist(), t, 10000.0))) / math.sqrt(d_h)
+                 for t in range(pos + 1)]
+            e = np.exp(np.array(s) - max(s))
+            assert np.allclose(o[0, j, i], (e / e.sum()) @ V[i // 2, :pos + 1], rtol=1e-10, atol=1e-12)
+
+
 def test_bf16_rounding_helpers():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.0, 3.4028e38, np.inf], np.float32)
     r = synth.round_to_bf16(x)
