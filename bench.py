@@ -47,7 +47,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -351,7 +351,9 @@ def bench_prefill(args, torch, ea, synth):
     desc = ea.LayerDesc(d, H, H, s.d_head, r, r, ea.EA_BF16, P)
     max_pages = n // P
     pool_pages = B * max_pages
-    n_qkv = 3 * H * r
+    rope = args.workload.endswith("-rope")
+    q_dim = s.d_head if rope else r                  # the rotary variant keeps the query at full rank (Sec. 4.3)
+    n_qkv = H * q_dim + 2 * H * r
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.BASE_SEED + 4)
     k_pool, v_pool = ea.alloc_pools(desc, pool_pages)
@@ -361,17 +363,23 @@ def bench_prefill(args, torch, ea, synth):
     x = torch.randn((B * n, d), generator=gen, device=dev).to(torch.bfloat16)
     wqkv = ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
     wo = ea.pack_weight((torch.randn((d, H * r), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
-    q_r = torch.empty((B * n, H, r), dtype=torch.bfloat16, device=dev)
+    q_r = torch.empty((B * n, H, q_dim), dtype=torch.bfloat16, device=dev)
     o = torch.empty((B, n, H, r), dtype=torch.bfloat16, device=dev)
     y = torch.empty((B * n, d), dtype=torch.bfloat16, device=dev)
+    if rope:
+        u_k = torch.linalg.qr(torch.randn((s.d_head, r), generator=gen, device=dev))[0].contiguous().to(torch.bfloat16)
+        ws = torch.empty((ea.prefill_rope_workspace_bytes(desc, B, n, max_pages) // 2,), dtype=torch.bfloat16, device=dev)
 
     def step(events=None):
         if events is not None:
             events[0].record()
-        ea.project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, pt, seq0, n)
+        (ea.project_qkv_rope if rope else ea.project_qkv)(desc, x, wqkv, q_r, k_pool, v_pool, pt, seq0, n)
         if events is not None:
             events[1].record()
-        ea.prefill_attn(desc, q_r.view(B, n, H, r), k_pool, v_pool, pt, seq1, o)
+        if rope:
+            ea.prefill_attn_rope(desc, q_r.view(B, n, H, q_dim), u_k, ROPE_BASE, k_pool, v_pool, pt, seq1, o, ws=ws)
+        else:
+            ea.prefill_attn(desc, q_r.view(B, n, H, r), k_pool, v_pool, pt, seq1, o)
         if events is not None:
             events[2].record()
         ea.out_proj(desc, o.view(B * n, H * r), wo, y)
@@ -391,7 +399,9 @@ def bench_prefill(args, torch, ea, synth):
     ms_per_step = e0.elapsed_time(e1) / args.steps
     t = [sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(args.steps)) / args.steps for i in range(3)]
     f_proj = 2 * B * n * d * n_qkv
-    f_attn = B * H * n * n * 2 * r            # causal-counted: 2 * (n^2 / 2) * (r_k + r_v) per (sequence, head)
+    # causal-counted: 2 * (n^2 / 2) * (score width + r_v) per (sequence, head); the rotary variant scores at d_h
+    # channels and brings every cached key back to d_h channels once (2 * n * r * d_h per sequence and head)
+    f_attn = B * H * n * n * (q_dim + r) + (2 * B * H * n * r * s.d_head if rope else 0)
     f_out = 2 * B * n * H * r * d
     flops = f_proj + f_attn + f_out
 
@@ -399,13 +409,14 @@ def bench_prefill(args, torch, ea, synth):
         return f / (ms * 1e-3) / 1e12
 
     result = {
-        "metric": "low-rank causal prefill: TFLOP/s of project_qkv + prefill_attn + out_proj (cfg4)",
+        "metric": f"low-rank causal prefill: TFLOP/s of project_qkv + prefill_attn + out_proj ({args.workload})",
         "value": round(tf(flops, ms_per_step), 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"cfg4 causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, "
+        "config": {"workload": f"{args.workload} causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, "
                                f"d_h={s.d_head}, r_k=r_v={r}, bf16, cache written to a paged pool (page {P} tokens, "
-                               f"random order)",
+                               f"random order)" + (", rotary positions (Sec. 4.3): project_qkv_rope + "
+                                                   "prefill_attn_rope + out_proj" if rope else ""),
                    "batch": B, "n_ctx": n, "r_k": r, "r_v": r, "page_tokens": P},
         "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
         "kernels": {"project_qkv": {"ms": round(t[0], 4), "tflops": round(tf(f_proj, t[0]), 1)},
@@ -417,7 +428,7 @@ def bench_prefill(args, torch, ea, synth):
                      "kernel": "gemm_bf16_tiled_kernel (ea_project_qkv, the longest of the three calls)",
                      "flops_per_launch": f_proj, "us_per_launch": round(t[0] * 1e3, 1)},
     }
-    if not args.no_cpu:
+    if not args.no_cpu and not rope:
         result["cpu_baseline"] = cpu_oracle_prefill(512, n, r, s.d_head)
     return result
 
@@ -435,7 +446,8 @@ def main():
 
     ea.load_library()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    result = bench_prefill(args, torch, ea, synth) if args.workload == "cfg4" else bench_decode(args, torch, ea, synth)
+    result = bench_prefill(args, torch, ea, synth) if args.workload.startswith("cfg4") else \
+        bench_decode(args, torch, ea, synth)
     print(json.dumps(result))
 
 
