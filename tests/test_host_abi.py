@@ -146,3 +146,84 @@ def test_auto_splits_fill_the_chip():
     g = ea.LayerDesc(4096, 32, 8, 128, 80, 80, ea.EA_BF16, 64)
     assert ea.decode_auto_splits(g, 8, 16384) == 8            # 64 streams x 8 = 512 workgroups
     assert ea.decode_auto_splits(g, 1, 16384) == 32           # 8 streams: capped at 8 tiles per workgroup
+
+
+# ---------------------------------------------------------------------------
+# Error behaviour of the hot-path entry points: every check below fails BEFORE anything is launched or
+# dereferenced, so made-up addresses are enough and no GPU is needed.
+# ---------------------------------------------------------------------------
+OK_PTR, ODD_PTR = 0x10000, 0x10008          # 16-byte aligned / not aligned; never dereferenced
+
+
+def raw():
+    lib = ea.load_library()
+    return lib
+
+
+def call_decode(lib, d, q=OK_PTR, k=OK_PTR, v=OK_PTR, pt=OK_PTR, sl=OK_PTR, out=OK_PTR, B=2, max_pages=4,
+                pool_pages=8, n_splits=1, ws=None, ws_bytes=0):
+    return lib.ea_decode_attn(ctypes.byref(d), q, k, v, pt, sl, out, B, max_pages, pool_pages, n_splits, ws, ws_bytes,
+                              None)
+
+
+def call_decode_rope(lib, d, q=OK_PTR, u=OK_PTR, base=10000.0, k=OK_PTR, n_splits=1, ws=None, ws_bytes=0):
+    return lib.ea_decode_attn_rope(ctypes.byref(d), q, u, base, k, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 4, 8, n_splits,
+                                   ws, ws_bytes, None)
+
+
+def test_decode_attn_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+    assert call_decode(lib, d, q=None) == -1                              # EA_ERR_ARG: null pointer
+    assert call_decode(lib, d, B=0) == -1
+    assert call_decode(lib, d, n_splits=1025) == -1
+    assert call_decode(lib, d, k=ODD_PTR) == -3                           # EA_ERR_ALIGN
+    assert call_decode(lib, d, n_splits=4) == -4                          # EA_ERR_WORKSPACE: splits need a workspace
+    need = ea.decode_workspace_bytes(d, 2, 4)
+    assert need == 2 * 8 * 4 * (2 + 48) * 4
+    assert call_decode(lib, d, n_splits=4, ws=OK_PTR, ws_bytes=need - 1) == -4
+    assert call_decode(lib, desc(H=8, Hkv=3)) == -2                       # EA_ERR_SHAPE: heads do not group evenly
+    assert call_decode(lib, desc(r_k=136)) == -2                          # bf16 ranks stop at 128
+    assert call_decode(lib, desc(P=96)) == -2                             # bf16 pages hold whole 64-token tiles
+    bad = desc(); bad.dtype = 7
+    assert call_decode(lib, bad) == -1
+
+
+def test_rotary_entry_points_reject_bad_arguments_before_launching():
+    lib = raw()
+    d = desc()
+    assert call_decode_rope(lib, d, u=None) == -1
+    assert call_decode_rope(lib, d, base=1.0) == -1                       # the base must exceed 1
+    assert call_decode_rope(lib, d, base=float("nan")) == -1
+    assert call_decode_rope(lib, d, q=ODD_PTR) == -3
+    assert call_decode_rope(lib, d, n_splits=2) == -4
+    assert call_decode_rope(lib, desc(d_h=96, r_k=80)) == -2              # bf16 rotary kernels exist for d_head 64 and 128
+    assert call_decode_rope(lib, desc(d_h=64, r_k=80)) == -2              # a basis cannot have more columns than rows
+    assert call_decode_rope(lib, desc(ea.EA_F32, d_h=63, r_k=32, P=16)) == -2   # rotary pairs need an even d_head
+    need = ea.prefill_rope_workspace_bytes(d, 2, 100, 4)
+    assert need >= 2 * 4 * 2 * 128 * 128 * 2 + 2 * 100 * 8 * 128 * 2
+    rc = lib.ea_prefill_attn_rope(ctypes.byref(d), OK_PTR, OK_PTR, 10000.0, OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 100,
+                                  4, 8, OK_PTR, need - 1, None)
+    assert rc == -4
+    rc = lib.ea_project_qkv_rope(ctypes.byref(desc(d_h=64, r_k=80)), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR,
+                                 OK_PTR, OK_PTR, 2, 1, 4, 8, None)
+    assert rc == -2
+
+
+def test_projection_and_prefill_reject_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+    f = lib.ea_project_qkv
+    assert f(ctypes.byref(d), None, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
+    assert f(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, 5, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
+    assert f(ctypes.byref(d), OK_PTR, ODD_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -3
+    assert f(ctypes.byref(desc(d=1000)), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8,
+             None) == -2                                                   # bf16 needs d % 32 == 0
+    f32 = desc(ea.EA_F32, P=16)
+    assert f(ctypes.byref(f32), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
+    g = lib.ea_prefill_attn
+    assert g(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, None, 2, 5, 4, 8, None) == -1
+    assert g(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 0, 4, 8, None) == -1
+    assert g(ctypes.byref(d), OK_PTR, OK_PTR, ODD_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 5, 4, 8, None) == -3
+    h = lib.ea_out_proj
+    assert h(ctypes.byref(d), OK_PTR, ea.EA_F32, OK_PTR, None, 4, None) == -1
+    assert h(ctypes.byref(desc(H=3, Hkv=3, r_v=40)), OK_PTR, ea.EA_F32, OK_PTR, OK_PTR, 4, None) == -2   # (H r_v) % 32
+    assert ea.strerror(-4).startswith("workspace") and ea.strerror(-2) == "unsupported shape"
