@@ -73,22 +73,56 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
 
   bf16x8 ga[MI], gb[4];
   const int ksteps = K >> 5;
-  const int64_t nblks = (N + 15) >> 4;
+  const int nblks = (N + 15) >> 4;
+  // Global tiles come through buffer loads: one scalar descriptor per operand and tile (rows / channel blocks
+  // past the matrix read as zero, no branches), loop-invariant 32-bit lane offsets, and the K position in the
+  // instruction's scalar offset -- no per-load 64-bit address arithmetic in the loop.
+  constexpr int kEsz = A_F32 ? 4 : 2;
+  constexpr uint32_t kOob = 0x7ffffff0u;     // beyond any descriptor's size: reads as zero
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(reinterpret_cast<const char*>(A)) + (int64_t)m0 * K * kEsz, 0,
+      (int)((int64_t)min(BM, M - m0) * K * kEsz), 0x00020000);
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(Wt) + (((int64_t)(n0 >> 4) * ksteps) << 9), 0,
+      (int)((int64_t)min(BN / 16, nblks - (n0 >> 4)) * ksteps * 1024), 0x00020000);
+  uint32_t a_off[MI], w_off[4];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;     // A: 8 threads read 128 B of a row
+    a_off[i] = (uint32_t)((row * K + kc) * kEsz);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // W: this thread's 16-byte unit of fragment (channel block nb, k step kst): 64 threads read 1 KiB contiguous
+    const int chunk = tid + 256 * i;
+    const int frag = chunk >> 6, ln = chunk & 63, nb = frag >> 1, kst = frag & 1;
+    w_off[i] = (uint32_t)(((nb * ksteps + kst) << 10) + (ln << 4));
+  }
+  const bool k_even = (K & 63) == 0;          // otherwise the last step holds one 32-wide k step only
   auto gload = [&](int k0) __attribute__((always_inline)) {
+    const bool tail = !k_even && k0 + BK > K;
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
-      const int chunk = tid + 256 * i, row = chunk >> 3, kc = (chunk & 7) * 8;   // A: 8 threads read 128 B of a row
-      ga[i] = (k0 + kc < K && m0 + row < M) ? load_frag<A_F32>(A, (int64_t)(m0 + row) * K + k0 + kc) : zero_frag();
+      const int kc = ((tid + 256 * i) & 7) * 8;
+      const uint32_t off = (tail && kc >= 32) ? kOob : a_off[i];
+      if (!A_F32) {
+        ga[i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off, k0 * kEsz, 0));
+      } else {
+        const f32x4 lo = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off, k0 * kEsz, 0));
+        const f32x4 hi =
+            __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off + 16, k0 * kEsz, 0));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          ga[i][e] = (__bf16)lo[e];
+          ga[i][4 + e] = (__bf16)hi[e];
+        }
+      }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      // W: this thread's 16-byte unit of fragment (channel block nb, k step kst): 64 threads read 1 KiB contiguous
-      const int chunk = tid + 256 * i;
-      const int frag = chunk >> 6, ln = chunk & 63, nb = frag >> 1, kst = frag & 1;
-      const int64_t nblk = (n0 >> 4) + nb;
-      gb[i] = ((k0 >> 5) + kst < ksteps && nblk < nblks)
-                  ? *reinterpret_cast<const bf16x8*>(Wt + ((nblk * ksteps + (k0 >> 5) + kst) << 9) + (ln << 3))
-                  : zero_frag();
+      const int kst = ((tid + 256 * i) >> 6) & 1;
+      const uint32_t off = (tail && kst == 1) ? kOob : w_off[i];
+      gb[i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, (k0 >> 5) << 10, 0));
     }
   };
   auto mainloop = [&](auto swap_tag) __attribute__((always_inline)) {
@@ -107,18 +141,33 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
       if (k0 + BK < K) gload(k0 + BK);
 #pragma unroll
       for (int ks = 0; ks < BK / 32; ++ks) {
-        bf16x8 af[MI], bfr[4];
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * (16 * MI) + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+        bf16x8 bfr[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + i) * 2 + ks) * 64) + lane) << 3]);
+        auto read_a = [&](int i) __attribute__((always_inline)) {
+          return *reinterpret_cast<const bf16x8*>(&As[(wm * (16 * MI) + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+        };
+        // the next A fragment is on its way from LDS while the four MFMAs of the current one run
+        bf16x8 af = read_a(0);
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+          bf16x8 af_next = af;
+          if (i + 1 < MI) af_next = read_a(i + 1);
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            acc[i][j] = SWAP ? mfma16(bfr[j], af[i], acc[i][j]) : mfma16(af[i], bfr[j], acc[i][j]);
+            acc[i][j] = SWAP ? mfma16(bfr[j], af, acc[i][j]) : mfma16(af, bfr[j], acc[i][j]);
+          af = af_next;
+        }
+        // instruction order for the scheduler: the four W reads and the first A read, then "next A read, four
+        // MFMAs of the current one" -- LDS latency hides behind matrix-core work instead of in front of it
+        __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+#pragma unroll
+        for (int i = 0; i < MI - 1; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
     }
   };
