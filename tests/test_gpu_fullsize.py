@@ -153,3 +153,13 @@ def test_cfg4_prefill_chain_sampled():
         ref[ri] = ora.out_proj(o_j, Wo_q)[0]
     err = assert_close(y_gpu[b, rows], ref, TOL_BF16, "cfg4 y rows")
     print(f"  cfg4 end-to-end rel-L2 {err:.2e}", flush=True)
+
+
+def test_one_million_cached_tokens():
+    """One sequence of 2^20 tokens (16384 pages in random order), one kv head, r = 16: index arithmetic at the large
+    end, 64 splits, checked against the oracle in full (the oracle's cost is one 2^20 x 16 product)."""
+    desc = ea.LayerDesc(128, 2, 1, 128, 16, 16, ea.EA_BF16, 64)
+    n = 1 << 20
+    print("2^20 tokens", flush=True)
+    S = run_sampled_decode(desc, 1, n, [(0, 0)], seed=71, n_splits=64)
+    assert S == 64

@@ -299,3 +299,19 @@ def test_prefill_rope(dtype, H, Hkv, d_h, r_k, r_v, lens, n, P):
     ref = ora.prefill_attention_rope(q, ora.RankCache.from_arrays(K, V), U, d_h)
     err = assert_close(got, ref, TOL_BF16 if dtype == ea.EA_BF16 else TOL_F32, "rope prefill")
     print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+def test_bf16_rope_half_a_million_tokens():
+    """One sequence of 2^19 tokens, GQA 2:1, r = (32, 16): the query has turned 524 287 radians in its fastest pair;
+    the stepped rotation is re-seeded exactly 256 times per wave on the way."""
+    desc = ea.LayerDesc(256, 2, 1, 128, 32, 16, ea.EA_BF16, 64)
+    g = synth.rng(30)
+    n = 1 << 19
+    print("rope 2^19 tokens", flush=True)
+    U = quantize(desc, synth.orthonormal_basis(g, 128, 32))
+    K = [quantize(desc, g.standard_normal((1, n, 32), dtype=np.float32))]
+    V = [quantize(desc, g.standard_normal((1, n, 16), dtype=np.float32))]
+    q = np.float32(synth.gaussian(g, (1, 2, 128), 1.5)).astype(np.float64)
+    got = run_rope(desc, K, V, q, U, 10000.0, g, 2)
+    err = assert_close(got, oracle_rope(desc, K, V, q, U, 10000.0), TOL_BF16, "rope 2^19")
+    print(f"  rel-L2 {err:.2e}", flush=True)
