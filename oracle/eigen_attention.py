@@ -150,14 +150,21 @@ def softmax(s):
 # --------------------------------------------------------------------------
 # Eq. (3) in rank space: one new query per sequence over the whole cache
 # --------------------------------------------------------------------------
+def alibi_bias(slope: float, pos_q: int, n_keys: int):
+    """ALiBi (Sec. 5.1 names it as the MPT models' position scheme; the definition is that of the ALiBi paper):
+    the score of query position i against key position j <= i gets -slope * (i - j), slope > 0 per head."""
+    return -float(slope) * (pos_q - np.arange(n_keys, dtype=F64))
+
+
 def decode_attention(q_r, cache: RankCache, d_head: int, counter: Optional[OpCounter] = None,
-                     return_probs: bool = False):
+                     return_probs: bool = False, alibi_slopes=None):
     """q_r [B, H, r_k] -> o [B, H, r_v].
 
     s_t = q_r . K_r[t] / sqrt(d_h) for every cached token t (the one just
     appended included), p = Softmax(s), o = sum_t p_t V_r[t].  The divisor is
     sqrt(d_h), not sqrt(r): Eq. (7) keeps it because the rank-space product
     equals Q' K'^T of the d_h-dimensional projected vectors.
+    With alibi_slopes [H] the ALiBi bias of the query's distance to each key is added to s.
     """
     q_r = np.asarray(q_r, F64)
     B, H, _ = q_r.shape
@@ -171,6 +178,8 @@ def decode_attention(q_r, cache: RankCache, d_head: int, counter: Optional[OpCou
             g = _kv_head_of(i, H, cache.n_kv_heads)
             K, V = cache.K[b][g], cache.V[b][g]
             s = (K @ q_r[b, i]) / math.sqrt(d_head)
+            if alibi_slopes is not None:
+                s = s + alibi_bias(alibi_slopes[i], n - 1, n)
             p = softmax(s)
             out[b, i] = p @ V
             if return_probs:
@@ -183,7 +192,7 @@ def decode_attention(q_r, cache: RankCache, d_head: int, counter: Optional[OpCou
 # --------------------------------------------------------------------------
 # Eq. (2) in rank space with a causal mask: the prefill phase
 # --------------------------------------------------------------------------
-def prefill_attention(q_r, cache: RankCache, d_head: int):
+def prefill_attention(q_r, cache: RankCache, d_head: int, alibi_slopes=None):
     """q_r [B, n, H, r_k] -> o [B, n, H, r_v].
 
     The n queries of sequence b are its LAST n cached positions: query j sits
@@ -202,6 +211,8 @@ def prefill_attention(q_r, cache: RankCache, d_head: int):
             for j in range(n):
                 pos = L - n + j
                 s = (K[:pos + 1] @ q_r[b, j, i]) / math.sqrt(d_head)
+                if alibi_slopes is not None:
+                    s = s + alibi_bias(alibi_slopes[i], pos, pos + 1)
                 out[b, j, i] = softmax(s) @ V[:pos + 1]
     return out
 

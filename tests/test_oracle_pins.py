@@ -437,6 +437,44 @@ def test_rope_prefill_rows_are_the_decode_results_of_their_prefixes():
             assert np.allclose(o[0, j, i], (e / e.sum()) @ V[i // 2, :pos + 1], rtol=1e-10, atol=1e-12)
 
 
+# ---- ALiBi (the MPT family's position scheme) ---------------------------------------------------------------------
+def test_alibi_bias_definition_limits_and_shift_invariance():
+    g = synth.rng(913)
+    H, Hkv, r_k, r_v, n, d_h = 4, 2, 5, 3, 12, 8
+    K, V = synth.gaussian(g, (Hkv, n, r_k)), synth.gaussian(g, (Hkv, n, r_v))
+    q = synth.gaussian(g, (1, H, r_k))
+    cache = ora.RankCache.from_arrays([K], [V])
+    plain = ora.decode_attention(q, cache, d_h)
+    # zero slopes: nothing changes
+    assert np.array_equal(ora.decode_attention(q, cache, d_h, alibi_slopes=np.zeros(H)), plain)
+    # brute force from the definition: score - slope * (i - j)
+    slopes = np.array([0.5, 0.25, 0.125, 0.0625])
+    o = ora.decode_attention(q, cache, d_h, alibi_slopes=slopes)
+    for i in range(H):
+        s = [sum(q[0, i, c] * K[i // 2, t, c] for c in range(r_k)) / math.sqrt(d_h) - slopes[i] * (n - 1 - t)
+             for t in range(n)]
+        e = [math.exp(v - max(s)) for v in s]
+        ref = [sum(e[t] / sum(e) * V[i // 2, t, c] for t in range(n)) for c in range(r_v)]
+        assert np.allclose(o[0, i], ref, rtol=1e-12, atol=1e-14)
+    # a very steep slope leaves only the newest token: o = V[n-1]
+    steep = ora.decode_attention(q, cache, d_h, alibi_slopes=np.full(H, 1e4))
+    for i in range(H):
+        assert np.allclose(steep[0, i], V[i // 2, n - 1], atol=1e-12)
+    # the bias of a row is defined up to a constant (softmax): +slope * j alone gives the same result
+    for i in range(H):
+        s = (K[i // 2] @ q[0, i]) / math.sqrt(d_h)
+        a = ora.softmax(s + ora.alibi_bias(slopes[i], n - 1, n)) @ V[i // 2]
+        b = ora.softmax(s + slopes[i] * np.arange(n)) @ V[i // 2]
+        assert np.allclose(a, b, rtol=1e-12, atol=1e-14)
+    # prefill rows are the decode results of their prefixes, bias included
+    qp = synth.gaussian(g, (1, 3, H, r_k))
+    op = ora.prefill_attention(qp, cache, d_h, alibi_slopes=slopes)
+    for j in range(3):
+        pos = n - 3 + j
+        prefix = ora.RankCache.from_arrays([K[:, :pos + 1]], [V[:, :pos + 1]])
+        assert np.allclose(op[0, j], ora.decode_attention(qp[:, j], prefix, d_h, alibi_slopes=slopes)[0], rtol=1e-12)
+
+
 def test_bf16_rounding_helpers():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.0, 3.4028e38, np.inf], np.float32)
     r = synth.round_to_bf16(x)
