@@ -225,6 +225,23 @@ EA_API int ea_prefill_attn_rope(const ea_layer_desc* desc, const void* dev_q, co
                     int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* The two attention calls with the ALiBi position bias (Sec. 5.1 names ALiBi as
+ * the position scheme of the MPT models the method is applied to; the bias is
+ * the ALiBi paper's): the score of a query at position i against the cached key
+ * at position j <= i becomes  q_r . K_r[j] / sqrt(d_h) - slope_h * (i - j).
+ * The bias does not involve keys or queries, so it is the same in rank space.
+ *   dev_slopes [H] float, slope_h >= 0 (for instance 2^(-8 (h+1) / H))
+ * Everything else as ea_decode_attn / ea_prefill_attn (same workspace rule). */
+EA_API int ea_decode_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
+                    int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out,
+                    int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -16,7 +16,7 @@ __all__ = [
     "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
-    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes",
+    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
     "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_project_qkv_rope", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
     "ea_decode_attn", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
-    "ea_out_proj",
+    "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
 )
 
 
@@ -93,6 +93,8 @@ def load_library():
     lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_decode_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_prefill_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_prefill_rope_workspace_bytes.argtypes = [D, I32, I32, I32]
     lib.ea_prefill_rope_workspace_bytes.restype = I64
     lib.ea_prefill_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
@@ -315,6 +317,46 @@ def prefill_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, stream=Non
                                         _ptr(seq_len), _ptr(out), B, n, page_table.shape[1], k_pool.shape[0],
                                         _stream(stream))
     _check(rc, "ea_prefill_attn")
+
+
+def _slopes(desc, slopes):
+    import torch
+    if slopes.dtype != torch.float32 or slopes.numel() != desc.n_heads or not slopes.is_contiguous():
+        raise ValueError("slopes must be a contiguous float32 tensor with one entry per head")
+
+
+def decode_attn_alibi(desc, q_r, slopes, k_pool, v_pool, page_table, seq_len, out, n_splits: int = 0, ws=None,
+                      stream=None) -> None:
+    """decode_attn with the ALiBi bias -slopes[h] * (distance of the key to the query) added to the scores."""
+    import torch
+    B = seq_len.shape[0]
+    if q_r.dtype != torch.float32 or out.dtype != torch.float32:
+        raise ValueError("q_r and out must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    _slopes(desc, slopes)
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_decode_attn_alibi(ctypes.byref(desc), _ptr(q_r), _ptr(slopes), _ptr(k_pool), _ptr(v_pool),
+                                             _ptr(page_table), _ptr(seq_len), _ptr(out), B, page_table.shape[1],
+                                             k_pool.shape[0], n_splits, _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_decode_attn_alibi")
+
+
+def prefill_attn_alibi(desc, q_r, slopes, k_pool, v_pool, page_table, seq_len, out, stream=None) -> None:
+    """prefill_attn with the ALiBi bias."""
+    B, n = q_r.shape[0], q_r.shape[1]
+    _expect(q_r, desc.dtype, "q_r"); _expect(out, desc.dtype, "out")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    _slopes(desc, slopes)
+    if q_r.numel() != B * n * desc.n_heads * desc.r_k or out.numel() != B * n * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    rc = load_library().ea_prefill_attn_alibi(ctypes.byref(desc), _ptr(q_r), _ptr(slopes), _ptr(k_pool), _ptr(v_pool),
+                                              _ptr(page_table), _ptr(seq_len), _ptr(out), B, n, page_table.shape[1],
+                                              k_pool.shape[0], _stream(stream))
+    _check(rc, "ea_prefill_attn_alibi")
 
 
 def prefill_rope_workspace_bytes(desc, B: int, n: int, max_pages: int) -> int:

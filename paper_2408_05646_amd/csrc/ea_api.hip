@@ -266,6 +266,61 @@ int ea_prefill_attn(const ea_layer_desc* desc, const void* dev_q_r, const void* 
                      dev_page_table, dev_seq_len, (float*)dev_out, B, n, (hipStream_t)stream);
 }
 
+int ea_decode_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes, const void* dev_k_pool,
+                         const void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                         float* dev_out, int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
+                         void* dev_ws, int64_t ws_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_slopes || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || max_pages <= 0 || pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  if (n_splits == 0) {
+    const int64_t cap_tokens = (int64_t)max_pages * desc->page_tokens;
+    n_splits = ea_decode_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
+  }
+  if (n_splits > 1) {
+    if (!dev_ws || !aligned16(dev_ws)) return EA_ERR_WORKSPACE;
+    if (ws_bytes < ea_decode_workspace_bytes(desc, B, n_splits)) return EA_ERR_WORKSPACE;
+  }
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  if (desc->dtype == EA_BF16)
+    rc = decode_alibi_bf16(desc, g, (const float*)dev_q_r, dev_slopes, dev_k_pool, dev_v_pool, dev_page_table,
+                           dev_seq_len, dev_out, B, n_splits, (float*)dev_ws, st);
+  else
+    rc = decode_alibi_f32(desc, g, (const float*)dev_q_r, dev_slopes, (const float*)dev_k_pool,
+                          (const float*)dev_v_pool, dev_page_table, dev_seq_len, dev_out, B, n_splits, (float*)dev_ws,
+                          st);
+  if (rc != EA_OK) return rc;
+  if (n_splits > 1) rc = merge_splits(g, (const float*)dev_ws, dev_out, B, n_splits, st);
+  return rc;
+}
+
+int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                          const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
+                          const int32_t* dev_seq_len, void* dev_out, int32_t B, int32_t n, int32_t max_pages,
+                          int32_t pool_pages, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_slopes || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || n <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
+  if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  clear_stale_error();
+  if (desc->dtype == EA_BF16)
+    return prefill_alibi_bf16(desc, g, dev_q_r, dev_slopes, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len,
+                              dev_out, B, n, (hipStream_t)stream);
+  return prefill_alibi_f32(desc, g, (const float*)dev_q_r, dev_slopes, (const float*)dev_k_pool,
+                           (const float*)dev_v_pool, dev_page_table, dev_seq_len, (float*)dev_out, B, n,
+                           (hipStream_t)stream);
+}
+
 int64_t ea_prefill_rope_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_pages) {
   if (validate_desc(desc) != EA_OK || B <= 0 || n <= 0 || max_pages <= 0) return -1;
   return prefill_rope_ws_bytes(desc, B, n, max_pages);

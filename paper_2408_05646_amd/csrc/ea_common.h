@@ -12,6 +12,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kTile = 64;          // tokens per cache tile of the bf16 layout
+constexpr float kLazy = 8.0f;      // the softmax reference exponent moves when the maximum grew by more than 2^kLazy
 
 // Cache geometry, precomputed on the host and passed to kernels by value.
 struct Geo {
@@ -146,6 +147,18 @@ int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const
 int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
                     const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
                     float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);
+int decode_alibi_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const void* k_pool,
+                      const void* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
+                      int32_t n_splits, float* ws, hipStream_t st);
+int decode_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
+                     const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
+                     int32_t n_splits, float* ws, hipStream_t st);
+int prefill_alibi_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const float* slopes, const void* k_pool,
+                       const void* v_pool, const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B,
+                       int32_t n, hipStream_t st);
+int prefill_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
+                      const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
+                      int32_t n, hipStream_t st);
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st);
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,

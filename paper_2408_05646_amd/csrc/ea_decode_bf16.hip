@@ -71,6 +71,7 @@ int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
   a.u_k = nullptr;
   a.d_head = d->d_head;
+  a.alibi = nullptr;
   a.log2_base = 0.0;
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   switch (ks) {

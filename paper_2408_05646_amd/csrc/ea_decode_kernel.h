@@ -26,8 +26,6 @@
 
 namespace ea {
 
-constexpr float kLazy = 8.0f;
-
 struct DecodeArgs {
   const float* q;
   const uint16_t* k_pool;
@@ -43,6 +41,8 @@ struct DecodeArgs {
   const uint16_t* u_k;   // [d_head, r_k] bf16 basis shared by all heads
   int32_t d_head;
   double log2_base;   // log2 of the rotary base
+  // ALiBi variant only
+  const float* alibi;  // [H] slopes (natural-log units, >= 0)
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -71,9 +71,12 @@ constexpr int kReseed = 32;   // iterations between exact re-computations of the
 
 // TBN = 16-token blocks handled per loop iteration: 4 (a whole 64-token tile) or 2 (half a tile, for the
 // large ranks whose fragments would not fit the register file otherwise).
-template <int KS, int NCB, int TBN, int WPE, int NKK>
+// ALIBI adds the linear position bias of the ALiBi scheme to the scores: -slope_h * (distance of the key to
+// the query), in the position-free form only.
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false>
 __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   constexpr bool ROPE = NKK > 0;
+  static_assert(!(ROPE && ALIBI), "a model has one position scheme");
   __shared__ union {
     MergeSmem<NCB> mg;
     std::conditional_t<ROPE, RopeSmem<TBN, ROPE ? NKK : 1, KS>, NoSmem> rp;
@@ -140,6 +143,8 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   float qa[NK1][4], qb[NK1][4];  // the query's pairs j = 16*kk + 4*quad + i, rotated to the current iteration
   f16x8 qf[NK1];                 // ... as B operand of the score MFMA: slot 4*comp + i of k-step kk
   const int pos_q = n - 1;       // the query is the token appended last
+  float alibi_slope = 0.f;       // this lane's head, log2 units
+  if constexpr (ALIBI) alibi_slope = col < G ? a.alibi[kvh * G + col] * 1.4426950408889634f : 0.f;
   auto seed_q = [&](int tile) {
     if constexpr (ROPE) {
     // head columns past the group read head 0 of the group (always there) and are zeroed
@@ -378,6 +383,16 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     }
 
     // ---- online softmax on s (lane: head column `col`, tokens tb*16 + 4*quad + i)
+    if constexpr (ALIBI) {
+      // s <- s * scale + slope * (t - pos_q) in log2 units; from here on the scores are final
+      const float base = alibi_slope * (float)(cur.tile * kTile + cur.sub * TOK + quad * 4 - pos_q);
+#pragma unroll
+      for (int tb = 0; tb < TBN; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          s[tb][i] = fmaf(s[tb][i], a.scale_log2, fmaf(alibi_slope, (float)(tb * 16 + i), base));
+    }
+    const float score_scale = ALIBI ? 1.0f : a.scale_log2;
     float mx = -INFINITY;
 #pragma unroll
     for (int tb = 0; tb < TBN; ++tb) {
@@ -387,7 +402,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
         mx = fmaxf(mx, s[tb][i]);
       }
     }
-    mx = quad_column_max(mx) * a.scale_log2;                  // the scale is positive: max commutes with it
+    mx = quad_column_max(mx) * score_scale;                   // the scale is positive: max commutes with it
     // m is a reference exponent: it moves only when the max has grown by more than kLazy (log2 units), so
     // P stays <= 2^kLazy and the accumulators are rescaled a few times per stream, not at every tile.
     if (__any(mx > m + kLazy)) {
@@ -407,7 +422,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], a.scale_log2, -m_use));
+          pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], score_scale, -m_use));
       }
     }
     if (rem < TOK) {

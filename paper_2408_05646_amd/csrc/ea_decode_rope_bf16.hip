@@ -24,6 +24,7 @@ int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
   a.u_k = (const uint16_t*)u_k;
   a.d_head = d->d_head;
+  a.alibi = nullptr;
   a.log2_base = log2(rope_base);
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   if (d->d_head == 128) return decode_rope_bf16_d128(ks, ncb, a, B, st);

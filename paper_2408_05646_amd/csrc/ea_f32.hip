@@ -16,6 +16,21 @@ struct DotScore {
     for (int c = 0; c < r_k; ++c) dot = fmaf(sq[c], krow[c], dot);
     return dot;
   }
+  __device__ __forceinline__ float bias_log2(int /*tok*/) const { return 0.f; }
+};
+
+// The same with the ALiBi position bias: -slope * (query position - key position), here in log2 units.
+struct AlibiScore {
+  const float* sq;
+  int r_k;
+  float slope_log2;
+  int pos_q;
+  __device__ __forceinline__ float operator()(int /*tok*/, const float* __restrict__ krow) const {
+    float dot = 0.f;
+    for (int c = 0; c < r_k; ++c) dot = fmaf(sq[c], krow[c], dot);
+    return dot;
+  }
+  __device__ __forceinline__ float bias_log2(int tok) const { return slope_log2 * (float)(tok - pos_q); }
 };
 
 // Score for models with rotary position embedding (Sec. 4.3, Eq. 10): the cached rank-r key is brought back to
@@ -48,6 +63,7 @@ struct RopeScore {
     }
     return dot;
   }
+  __device__ __forceinline__ float bias_log2(int /*tok*/) const { return 0.f; }
 };
 
 // Online-softmax attention of one query over tokens [tok_begin, tok_end) of sequence b (Eq. 3 / Eq. 2 row).
@@ -74,7 +90,7 @@ __device__ __forceinline__ void attend_f32(const Score& score, const float* __re
       if (page >= 0 && page < g.pool_pages) {
         const int tp = tok % g.page_tokens;
         const float* krow = k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tp * g.r_k_pad;
-        s = score(tok, krow) * scale_log2;
+        s = fmaf(score(tok, krow), scale_log2, score.bias_log2(tok));
         voff = (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab + (int64_t)tp * g.r_v_pad;
       }
     }
@@ -122,6 +138,8 @@ struct AttnF32Args {
   const float* u_k;
   int32_t d_head;
   double log2_base;
+  // ALiBi variant only
+  const float* alibi;
 };
 
 __device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
@@ -132,8 +150,10 @@ __device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
   return (int)n;
 }
 
-template <bool ROPE>
+// MODE: 0 position-free, 1 rotary, 2 ALiBi
+template <int MODE>
 __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
+  constexpr bool ROPE = MODE == 1;
   const Geo& g = a.g;
   const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int kvh = head / g.group;
@@ -147,8 +167,12 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
   if (!ROPE) {
     if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[((int64_t)b * g.n_heads + head) * g.r_k + threadIdx.x];
     __syncthreads();
-    attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin,
-               tok_end, a.scale_log2, m, l, acc);
+    if (MODE == 2)
+      attend_f32(AlibiScore{sq, g.r_k, a.alibi[head] * 1.4426950408889634f, n - 1}, a.k_pool, a.v_pool,
+                 a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m, l, acc);
+    else
+      attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin,
+                 tok_end, a.scale_log2, m, l, acc);
   } else {
     __shared__ double theta[128];
     if (threadIdx.x < a.d_head) sq[threadIdx.x] = a.q[((int64_t)b * g.n_heads + head) * a.d_head + threadIdx.x];
@@ -173,8 +197,9 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
 }
 
 // Causal prefill: one workgroup per (query, head, sequence); query j sits at position len - n_q + j.
-template <bool ROPE>
+template <int MODE>
 __global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
+  constexpr bool ROPE = MODE == 1;
   const Geo& g = a.g;
   const int j = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int kvh = head / g.group;
@@ -186,8 +211,12 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(AttnF32Args a) {
   if (!ROPE) {
     if (threadIdx.x < g.r_k) sq[threadIdx.x] = a.q[row * g.r_k + threadIdx.x];
     __syncthreads();
-    attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
-               pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+    if (MODE == 2)
+      attend_f32(AlibiScore{sq, g.r_k, a.alibi[head] * 1.4426950408889634f, pos}, a.k_pool, a.v_pool,
+                 a.page_table + (int64_t)b * g.max_pages, g, kvh, 0, pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
+    else
+      attend_f32(DotScore{sq, g.r_k}, a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, 0,
+                 pos >= 0 ? pos + 1 : 0, a.scale_log2, m, l, acc);
   } else {
     __shared__ double theta[128];
     if (threadIdx.x < a.d_head) sq[threadIdx.x] = a.q[row * a.d_head + threadIdx.x];
@@ -219,6 +248,7 @@ static AttnF32Args make_args(const ea_layer_desc* d, const Geo& g, const float* 
   a.u_k = nullptr;
   a.d_head = d->d_head;
   a.log2_base = 0.0;
+  a.alibi = nullptr;
   return a;
 }
 
@@ -227,7 +257,7 @@ int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float
                hipStream_t st) {
   if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
-  decode_f32_kernel<false><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  decode_f32_kernel<0><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 
@@ -239,7 +269,7 @@ int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const 
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
   a.u_k = u_k;
   a.log2_base = log2(rope_base);
-  decode_f32_kernel<true><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  decode_f32_kernel<1><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 
@@ -247,7 +277,7 @@ int prefill_f32(const ea_layer_desc* d, const Geo& g, const float* q, const floa
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n, hipStream_t st) {
   if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
-  prefill_f32_kernel<false><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  prefill_f32_kernel<0><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 
@@ -259,7 +289,27 @@ int prefill_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
   a.u_k = u_k;
   a.log2_base = log2(rope_base);
-  prefill_f32_kernel<true><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  prefill_f32_kernel<1><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int decode_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
+                     const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
+                     int32_t n_splits, float* ws, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
+  a.alibi = slopes;
+  decode_f32_kernel<2><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int prefill_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
+                      const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
+                      int32_t n, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, nullptr, 1, n);
+  a.alibi = slopes;
+  prefill_f32_kernel<2><<<dim3(n, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
 

@@ -1,319 +1,12 @@
-// Prefill-phase attention in rank space (Eq. 2 with the rank-r operands of Eq. 7,
-// causal): flash attention on the gfx950 matrix cores, K and V read straight from
-// the paged cache in MFMA fragment order.
-//
-// One workgroup = 4 waves = 4 * QT * 16 consecutive queries of one (sequence, head).
-// A wave keeps QT blocks of 16 queries as MFMA columns and walks the 64-token cache
-// tiles up to its diagonal:
-//   S[64 kv x 16 q]   = K_tile . Q^T              (A = K fragments, B = q rows)
-//   online softmax per query column (rows = kv tokens: 16 registers + two cross-quad shuffles)
-//   O^T[r_v x 16 q]  += V_tile^T . P^T            (P rounded to bf16; row sums by an all-ones MFMA)
-// Every K / V fragment is loaded once per wave and tile and reused for the QT query blocks.
-// Tiles below the diagonal take a lean unmasked path; the grid is ordered by work (longest query tiles first).
-#include "ea_common.h"
-#include "ea_epilogue.h"
+// Launch side of the bf16 prefill-phase attention kernel, position-free form.
+#include "ea_prefill_kernel.h"
 
 namespace ea {
-
-struct PrefillArgs {
-  const uint16_t* q;
-  const uint16_t* k_pool;
-  const uint16_t* v_pool;
-  const int32_t* page_table;
-  const int32_t* seq_len;
-  uint16_t* out;
-  Geo g;
-  int32_t n_q;
-  int32_t batch;
-  int32_t n_qtiles;   // query tiles per (sequence, head) = gridDim.x / (H * batch)
-  int32_t k_compact;  // K pages are not looked up: logical page lp of sequence b is page b*max_pages + lp of k_pool
-  float scale_log2;
-};
-
-constexpr float kLazy = 8.0f;
-
-// One 64-token tile against one block of 16 queries: scores, online softmax, P.V.
-// MASKED = the tile is cut by the causal diagonal or by the end of the sequence (lane-wise limits);
-// unmasked tiles run the lean path.  `vis` = number of kv positions this lane's query may see.
-template <int KS, int NCB, bool MASKED>
-__device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf16x8 (&vf)[2][NCB],
-                                             const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
-                                             f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad) {
-  f32x4 s[4];
-#pragma unroll
-  for (int tb = 0; tb < 4; ++tb) {
-    s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
-  }
-  float mx = -INFINITY;
-#pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
-      mx = fmaxf(mx, s[tb][i]);
-    }
-  mx = quad_column_max(mx) * scale_log2;                     // the scale is positive: max commutes with it
-  // m is a reference exponent, not the exact running max: it only moves when the max has grown by more
-  // than kLazy (log2 units), so P stays <= 2^kLazy -- harmless in bf16 / fp32 -- and the accumulators are
-  // rescaled a handful of times per query instead of at every tile.  The final o = acc / l is unchanged.
-  if (__any(mx > m + kLazy)) {
-    const float m_new = fmaxf(m, mx);
-    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf -> 0
-    lacc *= alpha;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
-    m = m_new;
-  }
-  const float m_use = (MASKED && m == -INFINITY) ? 0.f : m;
-  bf16x8 pf[2];
-#pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], scale_log2, -m_use));
-  lacc = mfma16(ones, pf[0], lacc);
-  lacc = mfma16(ones, pf[1], lacc);
-#pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
-    acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
-  }
-}
-
-// Clears value slots of tokens >= limit (never written, arbitrary bits) so that 0 * x stays 0.
-template <int NCB>
-__device__ __forceinline__ void clear_tail(bf16x8 (&vf)[2][NCB], int tok0, int limit, int quad) {
-#pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int tok = tok0 + u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
-        if (tok >= limit) vf[u][cb][j] = (__bf16)0.0f;
-      }
-}
-
-template <int NCB, int QT>
-__device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&acc)[QT][NCB], const f32x4 (&lacc)[QT],
-                                          int b, int head, int q0, int col, int quad) {
-  const Geo& g = a.g;
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    const int qi = q0 + qb * 16 + col;
-    const float l = lacc[qb][0];
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-    uint16_t* orow = a.out + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_v;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      const int c = cb * 16 + quad * 4;
-      if (qi >= a.n_q) {
-      } else if (c + 3 < g.r_v) {
-        u32x2 w;
-        w[0] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][1] * inv) << 16);
-        w[1] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][3] * inv) << 16);
-        *reinterpret_cast<u32x2*>(orow + c) = w;
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (c + i < g.r_v) orow[c + i] = f32_to_bf16_rne(acc[qb][cb][i] * inv);
-      }
-    }
-  }
-}
-
-// Every wave reads its K / V fragments straight from global memory (the four waves of a workgroup walk
-// the same tiles, so three of four reads hit in L1/L2); the next tile is requested into the registers the
-// current one has just left.  (Staging the tiles through LDS was measured and is slower here.)
-template <int KS, int NCB, int QT, int WPE>
-__global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillArgs a) {
-  const Geo& g = a.g;
-  // 1-D grid ordered by work: the latest (longest) query tiles of every (sequence, head) come first
-  const int hb = g.n_heads * a.batch;
-  const int q_tile = a.n_qtiles - 1 - (int)(blockIdx.x / hb);
-  const int head = (blockIdx.x % hb) % g.n_heads, b = (blockIdx.x % hb) / g.n_heads;
-  const int kvh = head / g.group;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = lane & 15, quad = lane >> 4;
-  const int nck = g.r_k_pad >> 3;
-  constexpr int QW = QT * 16;                                   // queries per wave
-  const int q0 = (q_tile * 4 + wave) * QW;                      // first query of this wave
-  if (q0 >= a.n_q) return;
-
-  int64_t n64 = a.seq_len[b];
-  const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
-  if (n64 > cap) n64 = cap;
-  if (n64 < 0) n64 = 0;
-  const int len = (int)n64;
-  const int pos0 = len - a.n_q;                                  // position of query 0 (may be < 0: such queries see nothing)
-  const int tiles_per_page = g.page_tokens / kTile;
-
-  bf16x8 qf[QT][KS];
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    const int qi = q0 + qb * 16 + col;
-    const uint16_t* qrow = a.q + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_k;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const int k = ks * 32 + quad * 8;
-      qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
-    }
-  }
-  bf16x8 ones;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ones[j] = (__bf16)1.0f;
-
-  f32x4 acc[QT][NCB], lacc[QT];
-  float m[QT];
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    m[qb] = -INFINITY;
-    lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  const int q_last = min(a.n_q, q0 + QW) - 1;
-  const int pos_last = pos0 + q_last;                            // last position any query of this wave sees
-  const int pos_first = pos0 + q0;                               // every query of this wave sees positions <= this
-  const int t_end = pos_last >= 0 ? min(pos_last, len - 1) / kTile + 1 : 0;
-
-  bf16x8 kf[4][KS], vf[2][NCB];
-  auto tile_page = [&](int t) -> int {
-    const int page = a.page_table[(int64_t)b * g.max_pages + t / tiles_per_page];
-    return (page >= 0 && page < g.pool_pages) ? page : -1;
-  };
-  auto load_k = [&](int t, int page) __attribute__((always_inline)) {
-    const int64_t kpage = a.k_compact ? (int64_t)b * g.max_pages + t / tiles_per_page : page;
-    const uint16_t* base = a.k_pool + kpage * g.k_page + (int64_t)kvh * g.k_slab +
-                           (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad);
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int chunk = ks * 4 + quad;
-        kf[tb][ks] = chunk < nck ? *reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3))
-                                 : zero_frag();
-      }
-  };
-  auto load_v = [&](int t, int page) __attribute__((always_inline)) {
-    const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
-                           (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad);
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb)
-        vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
-  };
-  auto zero_kv = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[tb][ks] = zero_frag();
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) vf[u][cb] = zero_frag();
-  };
-
-  int page = -1;
-  if (t_end > 0) {
-    page = tile_page(0);
-    if (page >= 0) {
-      load_k(0, page);
-      load_v(0, page);
-    } else {
-      zero_kv();
-    }
-  }
-
-  for (int t = 0; t < t_end; ++t) {
-    const int tok0 = t * kTile;
-    const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;   // no masking needed
-    const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
-    const bool have_n = t + 1 < t_end;
-    const int page_n = have_n ? tile_page(t + 1) : -1;
-    if (full) {
-#pragma unroll
-      for (int qb = 0; qb < QT; ++qb)
-        attend_block<KS, NCB, false>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad);
-    } else {
-      if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
-#pragma unroll
-      for (int qb = 0; qb < QT; ++qb) {
-        const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
-        attend_block<KS, NCB, true>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis, quad);
-      }
-    }
-    if (have_n) {
-      if (page_n >= 0) {
-        load_k(t + 1, page_n);
-        load_v(t + 1, page_n);
-      } else {
-        zero_kv();
-      }
-    }
-    page = page_n;
-  }
-  write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
-}
-
-template <int KS, int NCB>
-static void launch_prefill(const PrefillArgs& a_in, int32_t B, hipStream_t st) {
-  // 64 queries per wave while the accumulators fit the register file, 32 for the large ranks
-  constexpr int QT = (KS <= 2 && NCB <= 4) ? 4 : 2;
-  PrefillArgs a = a_in;
-  a.batch = B;
-  a.n_qtiles = (a.n_q + 64 * QT - 1) / (64 * QT);
-  const dim3 grid((uint32_t)(a.n_qtiles * a.g.n_heads * B));
-  prefill_bf16_direct_kernel<KS, NCB, QT, 2><<<grid, 256, 0, st>>>(a);
-}
-
-template <int KS>
-static int dispatch_ncb(int ncb, const PrefillArgs& a, int32_t B, hipStream_t st) {
-  switch (ncb) {
-    case 1: launch_prefill<KS, 1>(a, B, st); break;
-    case 2: launch_prefill<KS, 2>(a, B, st); break;
-    case 3: launch_prefill<KS, 3>(a, B, st); break;
-    case 4: launch_prefill<KS, 4>(a, B, st); break;
-    case 5: launch_prefill<KS, 5>(a, B, st); break;
-    case 6: launch_prefill<KS, 6>(a, B, st); break;
-    case 7: launch_prefill<KS, 7>(a, B, st); break;
-    case 8: launch_prefill<KS, 8>(a, B, st); break;
-    default: return EA_ERR_SHAPE;
-  }
-  return launch_status();
-}
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
                  const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,
                  int32_t k_compact) {
-  if ((int64_t)((n + 127) / 128) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
-  if (g.r_k % 8 != 0 || g.r_v % 4 != 0) return EA_ERR_SHAPE;     // 16-byte q rows, 8-byte output stores
-  PrefillArgs a;
-  a.q = (const uint16_t*)q;
-  a.k_pool = (const uint16_t*)k_pool;
-  a.v_pool = (const uint16_t*)v_pool;
-  a.page_table = page_table;
-  a.seq_len = seq_len;
-  a.out = (uint16_t*)out;
-  a.g = g;
-  a.n_q = n;
-  a.k_compact = k_compact;
-  a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
-  const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
-  switch (ks) {
-    case 1: return dispatch_ncb<1>(ncb, a, B, st);
-    case 2: return dispatch_ncb<2>(ncb, a, B, st);
-    case 3: return dispatch_ncb<3>(ncb, a, B, st);
-    case 4: return dispatch_ncb<4>(ncb, a, B, st);
-    default: return EA_ERR_SHAPE;
-  }
+  return prefill_bf16_launch<false>(d, g, q, k_pool, v_pool, page_table, seq_len, out, B, n, st, k_compact, nullptr);
 }
 
 }  // namespace ea

@@ -1,0 +1,78 @@
+"""ea_decode_attn_alibi / ea_prefill_attn_alibi (ALiBi position bias, the MPT family's scheme) against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_05646_amd as ea
+from oracle import eigen_attention as ora
+from paper_2408_05646_amd import synth
+from helpers import DeviceCache, TOL_BF16, TOL_F32, assert_close, quantize, random_cache, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def mpt_slopes(H):
+    """The geometric sequence of the ALiBi paper for a power-of-two head count: 2^(-8 (h+1) / H)."""
+    return np.float32(2.0 ** (-8.0 * (np.arange(H) + 1) / H)).astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,r_k,r_v,lens,P,n_splits", [
+    (ea.EA_F32, 4, 2, 30, 33, [255, 256, 700, 1], 32, 3),
+    (ea.EA_F32, 8, 8, 32, 32, [40, 0], 16, 1),
+    (ea.EA_BF16, 8, 2, 80, 48, [777, 64, 1500], 64, 0),
+    (ea.EA_BF16, 4, 4, 128, 128, [513, 100], 64, 2),
+    (ea.EA_BF16, 16, 1, 96, 64, [3000], 128, 4),
+    (ea.EA_BF16, 2, 2, 72, 40, [0, 65], 64, 1),
+])
+def test_decode_alibi(dtype, H, Hkv, r_k, r_v, lens, P, n_splits):
+    print(f"alibi decode dtype={dtype} H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} S={n_splits}", flush=True)
+    d_h = 128 if dtype == ea.EA_BF16 else 64
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, dtype, P)
+    g = synth.rng(31, H, r_k, len(lens))
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    q = np.float32(synth.gaussian(g, (len(lens), H, r_k), 1.5)).astype(np.float64)
+    slopes = mpt_slopes(H)
+    dc = DeviceCache(desc, K, V, g)
+    B = len(lens)
+    out = torch.full((B, H, r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = n_splits if n_splits else ea.decode_auto_splits(desc, B, dc.max_pages * P)
+    nbytes = ea.decode_workspace_bytes(desc, B, S)
+    ws = torch.full((max(nbytes // 4, 4),), float("nan"), dtype=torch.float32, device="cuda") if nbytes else None
+    ea.decode_attn_alibi(desc, torch.from_numpy(q.astype(np.float32)).cuda(),
+                         torch.from_numpy(slopes.astype(np.float32)).cuda(), dc.k_pool, dc.v_pool, dc.page_table,
+                         dc.seq_len, out, n_splits=S, ws=ws)
+    torch.cuda.synchronize()
+    keep = [b for b in range(B) if lens[b] > 0]
+    ref = np.zeros((B, H, r_v))
+    ref[keep] = ora.decode_attention(q[keep], ora.RankCache.from_arrays([K[b] for b in keep], [V[b] for b in keep]),
+                                     d_h, alibi_slopes=slopes)
+    err = assert_close(out.cpu().numpy(), ref, TOL_BF16 if dtype == ea.EA_BF16 else TOL_F32, "alibi decode")
+    # the bias matters on these inputs (the test would not notice a kernel that dropped it otherwise)
+    plain = ora.decode_attention(q[keep], ora.RankCache.from_arrays([K[b] for b in keep], [V[b] for b in keep]), d_h)
+    assert ora.rel_l2(plain, ref[keep]) > 0.05
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,r_k,r_v,lens,n,P", [
+    (ea.EA_F32, 4, 2, 32, 24, [40, 17, 64], 17, 16),
+    (ea.EA_BF16, 4, 2, 80, 48, [300, 257, 512], 200, 64),
+    (ea.EA_BF16, 2, 2, 64, 64, [700], 700, 64),
+    (ea.EA_BF16, 8, 1, 128, 32, [129, 400], 100, 128),
+])
+def test_prefill_alibi(dtype, H, Hkv, r_k, r_v, lens, n, P):
+    print(f"alibi prefill dtype={dtype} H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} n={n}", flush=True)
+    d_h = 128 if dtype == ea.EA_BF16 else 64
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, dtype, P)
+    g = synth.rng(32, H, r_k, n)
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    q = quantize(desc, synth.gaussian(g, (len(lens), n, H, r_k), 1.5))
+    slopes = mpt_slopes(H)
+    dc = DeviceCache(desc, K, V, g)
+    out = torch.full((len(lens), n, H, r_v), float("nan"), dtype=torch.float32, device="cuda").to(
+        torch.bfloat16 if dtype == ea.EA_BF16 else torch.float32)
+    ea.prefill_attn_alibi(desc, to_dev(desc, q), torch.from_numpy(slopes.astype(np.float32)).cuda(), dc.k_pool,
+                          dc.v_pool, dc.page_table, dc.seq_len, out)
+    torch.cuda.synchronize()
+    ref = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), d_h, alibi_slopes=slopes)
+    err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16 if dtype == ea.EA_BF16 else TOL_F32, "alibi prefill")
+    print(f"  rel-L2 {err:.2e}", flush=True)
