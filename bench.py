@@ -109,16 +109,23 @@ def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: boo
     V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
     q = g.standard_normal((n_seq, heads, d_head if rope else r))
     cache = ora.RankCache.from_arrays([K1] * n_seq, [V1] * n_seq)
-    if rope:
-        U = synth.orthonormal_basis(g, d_head, r)
-        dt = _timed_single_thread(lambda: ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE))
-    else:
-        dt = _timed_single_thread(lambda: ora.decode_attention(q, cache, d_head))
+    # one call = the sampled streams of one layer; repeated so that the sample is several seconds of CPU work
+    reps = 1 if rope else 8
+
+    def work():
+        for _ in range(reps):
+            if rope:
+                ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE)
+            else:
+                ora.decode_attention(q, cache, d_head)
+
+    U = synth.orthonormal_basis(g, d_head, r) if rope else None
+    dt = _timed_single_thread(work) / reps
     cache_bytes = n_seq * heads * n_ctx * 2 * r * 2          # what the GPU kernel would stream (bf16)
     return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"{'rotary ' if rope else ''}decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
-                      f"streams (n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s; a full 32-layer step would take "
-                      f"{dt * 32 * 512 / (n_seq * heads):.0f} s",
+                      f"streams (n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s per pass, {reps} passes timed three times "
+                      f"(best kept); a full 32-layer step would take {dt * 32 * 512 / (n_seq * heads):.0f} s",
             "seconds": round(dt, 3)}
 
 
