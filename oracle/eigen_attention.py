@@ -12,6 +12,9 @@ time, in the order and notation of the paper:
   Eq. (7)  A' = Softmax(Q' K'^T / sqrt(d_h)) V'
   Eq. (8)  W^Q' = W^Q U^K, W^K' = W^K U^K, W^V' = W^V U^V, W^O' = U^V^T W^O
   Table 1  KV-cache size, parameter and generation-FLOP closed forms
+  Eq. (9)-(10), Sec. 4.3: the variant for RoPE models (full-rank query, rank-r keys of ONE shared
+           basis brought back to d_h channels before the rotation), generation and prefill
+  ALiBi bias (the MPT family's position scheme, named in Sec. 5.1; definition of the ALiBi paper)
 
 Row-vector convention (x W) throughout, as in Eq. (1).  With grouped-query
 attention query head i uses the bases of its KV head g(i) = i // (H / H_kv).
@@ -19,8 +22,12 @@ attention query head i uses the bases of its KV head g(i) = i // (H / H_kv).
 Pins (tests/test_oracle_pins.py): r = d_h equals standard attention; the
 rank-space form equals the project-back form of Eq. (6)-(7); softmax rows sum
 to one; brute force on tiny inputs; closed-form special cases; basis-rotation
-invariance; Table 1 and the Introduction's 256 GB worked example.
-No function here is "parity unpinned".
+invariance; Table 1 and the Introduction's 256 GB worked example; for the RoPE variant the rotation's
+definition and relative-position invariance, equality with standard RoPE attention at r = d_h and
+whenever the keys lie in the basis' span, prefill rows = decode results of their prefixes; for ALiBi
+the bias definition, its limits and the softmax shift invariance.
+No function here is "parity unpinned" with respect to its stated definition; the ALiBi definition itself
+comes from the ALiBi paper (this paper prints no formula for it).
 """
 from __future__ import annotations
 
