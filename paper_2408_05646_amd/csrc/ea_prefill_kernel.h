@@ -156,7 +156,11 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
   const int q0 = (q_tile * 4 + wave) * QW;                      // first query of this wave
   if (q0 >= a.n_q) return;
 
-  int64_t n64 = a.seq_len[b];
+  // Sequence lengths and page ids are the same for every lane and do not change while the kernel runs: read
+  // through the constant address space they arrive in scalar registers.
+  typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+  const const_i32_ptr pt_row = (const_i32_ptr)(a.page_table + (int64_t)b * g.max_pages);
+  int64_t n64 = ((const_i32_ptr)a.seq_len)[b];
   const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
   if (n64 > cap) n64 = cap;
   if (n64 < 0) n64 = 0;
@@ -198,7 +202,7 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
 
   bf16x8 kf[4][KS], vf[2][NCB];
   auto tile_page = [&](int t) -> int {
-    const int page = a.page_table[(int64_t)b * g.max_pages + t / tiles_per_page];
+    const int page = pt_row[t / tiles_per_page];
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
   auto load_k = [&](int t, int page) __attribute__((always_inline)) {
@@ -209,9 +213,12 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        const int chunk = ks * 4 + quad;
-        kf[tb][ks] = chunk < nck ? *reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3))
-                                 : zero_frag();
+        // only the last k-step can run past the rank's nck chunks; its surplus lanes read the last real chunk
+        // instead and drop what they read
+        const bool past = ks == KS - 1 && ks * 4 + quad >= nck;
+        const int chunk = past ? nck - 1 : ks * 4 + quad;
+        const bf16x8 got = *reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3));
+        kf[tb][ks] = past ? zero_frag() : got;
       }
   };
   auto load_v = [&](int t, int page) __attribute__((always_inline)) {
@@ -223,26 +230,14 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
       for (int cb = 0; cb < NCB; ++cb)
         vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
   };
-  auto zero_kv = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[tb][ks] = zero_frag();
-#pragma unroll
-    for (int u = 0; u < 2; ++u)
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) vf[u][cb] = zero_frag();
-  };
 
   int page = -1;
   if (t_end > 0) {
     page = tile_page(0);
-    if (page >= 0) {
-      load_k(0, page);
-      load_v(0, page);
-    } else {
-      zero_kv();
-    }
+    // a tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are masked
+    // (limit = 0 below): no load sits behind a data-dependent branch
+    load_k(0, max(page, 0));
+    load_v(0, max(page, 0));
   }
 
   for (int t = 0; t < t_end; ++t) {
@@ -265,13 +260,12 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
                                            slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
       }
     }
+    // the next tile is requested into the registers the current one has just left; without the barrier the
+    // scheduler would start these loads early into a second set of registers and spill
+    __builtin_amdgcn_sched_barrier(0);
     if (have_n) {
-      if (page_n >= 0) {
-        load_k(t + 1, page_n);
-        load_v(t + 1, page_n);
-      } else {
-        zero_kv();
-      }
+      load_k(t + 1, max(page_n, 0));
+      load_v(t + 1, max(page_n, 0));
     }
     page = page_n;
   }
