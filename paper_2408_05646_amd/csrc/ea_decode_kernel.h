@@ -136,7 +136,10 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   f32x4 lacc = {0.f, 0.f, 0.f, 0.f};
   float m = -INFINITY;
 
-  bf16x8 kf[TBN][KS], vf[UN][NCB];
+  // The rotary variant keeps TWO key buffers: its iterations are long, and a key tile requested only after the
+  // previous one's scores would be in flight for less than the memory latency.
+  constexpr bool KDB = ROPE;
+  bf16x8 kfA[TBN][KS], kfB[KDB ? TBN : 1][KDB ? KS : 1], vf[UN][NCB];
 
   // ---- rotary variant: basis fragments, rotation tables, rotated query
   constexpr int NK1 = ROPE ? NKK : 1;
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
   const int lane_off = lane << 3;
-  auto load_k = [&](const Pos& p, int page) {
+  auto load_k = [&](const Pos& p, int page, auto& kf) {
     const uint16_t* base = a.k_pool + (int64_t)page * g.k_page + (int64_t)kvh * g.k_slab +
                            (int64_t)p.tin * (kTile * g.r_k_pad) + p.sub * (TOK * g.r_k_pad);
 #pragma unroll
@@ -260,8 +263,15 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     page = page_of(cur);
     // A tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are
     // masked below: the loads never depend on the page table's contents, only their address does.
-    load_k(cur, max(page, 0));
+    load_k(cur, max(page, 0), kfA);
     load_v(cur, max(page, 0));
+  }
+  // the position after the current one (with two key buffers its keys are requested one iteration ahead)
+  Pos nxt = advance(cur);
+  bool have_n = have && nxt.tile < t_end;
+  int page_n = have_n ? page_of(nxt) : -1;
+  if constexpr (KDB) {
+    if (have_n) load_k(nxt, max(page_n, 0), kfB);
   }
   // the rotary tables are built while the first tile is on its way
   if constexpr (ROPE) {
@@ -318,7 +328,8 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
   }
   int since_seed = 0;
 
-  while (have) {
+  // One iteration; kf holds the current keys, kf_free is the buffer the keys after the next go to.
+  auto iteration = [&](auto& kf, auto& kf_free) __attribute__((always_inline)) {
     // ---- scores: S[tb] (16 tokens x 16 head columns) = K_block . q^T
     f32x4 s[TBN];
     // The rotation tables never change, so the compiler would keep all of them in registers across the
@@ -366,10 +377,19 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       }
     }
     const int rem = page >= 0 ? n - (cur.tile * kTile + cur.sub * TOK) : 0;   // valid tokens here (>= TOK: all)
-    const Pos nxt = advance(cur);
-    const bool have_n = nxt.tile < t_end;
-    const int page_n = have_n ? page_of(nxt) : -1;
-    if (have_n) load_k(nxt, max(page_n, 0));   // K registers are free again: prefetch the next tile
+    // the registers of the current keys are free again: request the next keys (one buffer) or the ones after
+    // the next (two buffers)
+    Pos nn = nxt;
+    bool have_nn = false;
+    int page_nn = -1;
+    if constexpr (KDB) {
+      nn = advance(nxt);
+      have_nn = have_n && nn.tile < t_end;
+      page_nn = have_nn ? page_of(nn) : -1;
+      if (have_nn) load_k(nn, max(page_nn, 0), kf_free);
+    } else {
+      if (have_n) load_k(nxt, max(page_n, 0), kf_free);
+    }
     if constexpr (ROPE) {
       if (have_n && nxt.sub == 0) {
         if (++since_seed == kReseed) {
@@ -451,6 +471,24 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
     cur = nxt;
     have = have_n;
     page = page_n;
+    if constexpr (KDB) {
+      nxt = nn;
+      have_n = have_nn;
+      page_n = page_nn;
+    } else {
+      nxt = advance(cur);
+      have_n = have && nxt.tile < t_end;
+      page_n = have_n ? page_of(nxt) : -1;
+    }
+  };
+  if constexpr (KDB) {
+    while (have) {
+      iteration(kfA, kfA);       // scores from A, then A takes the keys two iterations ahead
+      if (!have) break;
+      iteration(kfB, kfB);
+    }
+  } else {
+    while (have) iteration(kfA, kfA);
   }
 
   // ---- merge the four waves of the workgroup
