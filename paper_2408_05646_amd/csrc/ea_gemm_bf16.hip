@@ -139,36 +139,54 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
       for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8*>(&Bs[(tid + 256 * i) << 3]) = gb[i];
       __syncthreads();
       if (k0 + BK < K) gload(k0 + BK);
+      // One straight pipeline over the two k steps of the tile: while the four MFMAs of one A fragment run, the
+      // next A fragment (and, during the first k step, the W fragments of the second) come from LDS.
+      auto read_a = [&](int ks, int i) __attribute__((always_inline)) {
+        return *reinterpret_cast<const bf16x8*>(&As[(wm * (16 * MI) + i * 16 + col) * LDK + ks * 32 + quad * 8]);
+      };
+      auto read_w = [&](int ks, int j) __attribute__((always_inline)) {
+        return *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + j) * 2 + ks) * 64) + lane) << 3]);
+      };
+      bf16x8 w0[4], w1[4];
 #pragma unroll
-      for (int ks = 0; ks < BK / 32; ++ks) {
-        bf16x8 bfr[4];
+      for (int j = 0; j < 4; ++j) w0[j] = read_w(0, j);
+      bf16x8 af = read_a(0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          bfr[i] = *reinterpret_cast<const bf16x8*>(&Bs[((((wn * 4 + i) * 2 + ks) * 64) + lane) << 3]);
-        auto read_a = [&](int i) __attribute__((always_inline)) {
-          return *reinterpret_cast<const bf16x8*>(&As[(wm * (16 * MI) + i * 16 + col) * LDK + ks * 32 + quad * 8]);
-        };
-        // the next A fragment is on its way from LDS while the four MFMAs of the current one run
-        bf16x8 af = read_a(0);
+      for (int i = 0; i < MI; ++i) {
+        bf16x8 af_next = i + 1 < MI ? read_a(0, i + 1) : read_a(1, 0);
+        if (i < 4) w1[i] = read_w(1, i);
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-          bf16x8 af_next = af;
-          if (i + 1 < MI) af_next = read_a(i + 1);
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = SWAP ? mfma16(w0[j], af, acc[i][j]) : mfma16(af, w0[j], acc[i][j]);
+        af = af_next;
+      }
 #pragma unroll
-          for (int j = 0; j < 4; ++j)
-            acc[i][j] = SWAP ? mfma16(bfr[j], af, acc[i][j]) : mfma16(af, bfr[j], acc[i][j]);
-          af = af_next;
-        }
-        // instruction order for the scheduler: the four W reads and the first A read, then "next A read, four
-        // MFMAs of the current one" -- LDS latency hides behind matrix-core work instead of in front of it
-        __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+      for (int i = 0; i < MI; ++i) {
+        bf16x8 af_next = af;
+        if (i + 1 < MI) af_next = read_a(1, i + 1);
 #pragma unroll
-        for (int i = 0; i < MI - 1; ++i) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-          __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-        }
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = SWAP ? mfma16(w1[j], af, acc[i][j]) : mfma16(af, w1[j], acc[i][j]);
+        af = af_next;
+      }
+      // instruction order for the scheduler (LDS latency hides behind matrix-core work instead of in front of it)
+      __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
+#pragma unroll
+      for (int i = 4; i < MI; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < MI - 1; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
     }
   };
   if (swap) mainloop(std::true_type{});
