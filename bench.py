@@ -180,7 +180,7 @@ def bench_decode(args, torch, ea, synth):
         perm = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32)   # pages in seeded random order
         layers.append(dict(
             desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
-            S=args.n_splits or ea.decode_auto_splits(dc, B, n) * (2 if rope else 1),
+            S=args.n_splits or (ea.decode_rope_auto_splits(dc, B, n) if rope else ea.decode_auto_splits(dc, B, n)),
             wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             wo=ea.pack_weight((torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),

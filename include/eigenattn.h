@@ -190,8 +190,10 @@ EA_API int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const 
  *   dev_q   [B, H, d_head] float, NOT rotated
  *   dev_u_k [d_head, r_k] row-major, desc dtype (EA_F32 float, EA_BF16 bfloat16: the basis enters the
  *           matrix cores in the precision of the cache)
- *   everything else as ea_decode_attn (same workspace size, same split rule).
+ *   everything else as ea_decode_attn (same workspace size); n_splits = 0 picks
+ *   ea_decode_rope_auto_splits(desc, B, max_pages * page_tokens).
  * Requires r_k <= d_head; EA_BF16: d_head 64 or 128; EA_F32: d_head even, <= 256. */
+EA_API int32_t ea_decode_rope_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len);
 EA_API int ea_decode_attn_rope(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
                     const void* dev_k_pool, const void* dev_v_pool,
                     const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,

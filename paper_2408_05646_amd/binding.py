@@ -16,7 +16,7 @@ __all__ = [
     "EA_F32", "EA_BF16", "EigenAttnError", "LayerDesc", "CacheLayout", "library_path", "load_library",
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
-    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi",
+    "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -24,7 +24,7 @@ EA_F32, EA_BF16 = 0, 1
 EXPORTED_SYMBOLS = (
     "ea_cache_layout_query", "ea_cache_k_index", "ea_cache_v_index", "ea_cache_slot", "ea_strerror", "ea_version",
     "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_project_qkv_rope", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
-    "ea_decode_attn", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
+    "ea_decode_attn", "ea_decode_rope_auto_splits", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
 )
 
@@ -90,6 +90,8 @@ def load_library():
     lib.ea_decode_auto_splits.restype = I32
     lib.ea_decode_auto_splits.argtypes = [D, I32, I32]
     lib.ea_decode_workspace_bytes.restype = I64
+    lib.ea_decode_rope_auto_splits.argtypes = [D, I32, I32]
+    lib.ea_decode_rope_auto_splits.restype = I32
     lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
@@ -260,6 +262,10 @@ def project_qkv_rope(desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T: i
 
 def decode_auto_splits(desc, B: int, max_seq_len: int) -> int:
     return int(load_library().ea_decode_auto_splits(ctypes.byref(desc), B, max_seq_len))
+
+
+def decode_rope_auto_splits(desc, B: int, max_seq_len: int) -> int:
+    return int(load_library().ea_decode_rope_auto_splits(ctypes.byref(desc), B, max_seq_len))
 
 
 def decode_workspace_bytes(desc, B: int, n_splits: int) -> int:

@@ -170,6 +170,18 @@ int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_
   return (int32_t)want;
 }
 
+int32_t ea_decode_rope_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || max_seq_len <= 0) return 1;
+  // The rotary kernel builds tables before it streams: with a single workgroup per resident slot all of them
+  // would do that at the same time and leave the memory idle meanwhile; at least four rounds of workgroups
+  // measured best on MI355X.
+  int32_t s = ea_decode_auto_splits(desc, B, max_seq_len);
+  int32_t cap = ((max_seq_len + kTile - 1) / kTile) / 8;
+  if (cap < 1) cap = 1;
+  const int32_t want = cap < 4 ? cap : 4;
+  return s > want ? s : want;
+}
+
 int64_t ea_decode_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits) {
   if (validate_desc(desc) != EA_OK || B <= 0 || n_splits < 0) return -1;
   if (n_splits <= 1) return 0;
@@ -228,7 +240,7 @@ int ea_decode_attn_rope(const ea_layer_desc* desc, const float* dev_q, const voi
     return EA_ERR_ALIGN;
   if (n_splits == 0) {
     const int64_t cap_tokens = (int64_t)max_pages * desc->page_tokens;
-    n_splits = ea_decode_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
+    n_splits = ea_decode_rope_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
   }
   if (n_splits > 1) {
     if (!dev_ws || !aligned16(dev_ws)) return EA_ERR_WORKSPACE;

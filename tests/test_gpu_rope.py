@@ -18,7 +18,7 @@ def run_rope(desc, K, V, q, U, base, g, n_splits, page_table_edit=None):
     B = len(K)
     pt = dc.page_table if page_table_edit is None else page_table_edit(dc)
     out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), dtype=torch.float32, device="cuda")
-    S = n_splits if n_splits else ea.decode_auto_splits(desc, B, dc.max_pages * desc.page_tokens)
+    S = n_splits if n_splits else ea.decode_rope_auto_splits(desc, B, dc.max_pages * desc.page_tokens)
     ws = None
     nbytes = ea.decode_workspace_bytes(desc, B, S)
     if nbytes:
@@ -153,7 +153,8 @@ def test_cfg3_rope_one_layer_sampled():
     q = torch.randn((B, desc.n_heads, desc.d_head), generator=gen, device="cuda")
     U = quantize(desc, synth.orthonormal_basis(g, desc.d_head, desc.r_k))
     out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), device="cuda")
-    S = ea.decode_auto_splits(desc, B, n)
+    S = ea.decode_rope_auto_splits(desc, B, n)
+    assert S == 4
     ws = torch.empty(max(ea.decode_workspace_bytes(desc, B, S) // 4, 4), device="cuda")
     ea.decode_attn_rope(desc, q, to_dev(desc, U), 10000.0, k_pool, v_pool, pt, seq, out, n_splits=S, ws=ws)
     torch.cuda.synchronize()
