@@ -101,6 +101,10 @@ __global__ __launch_bounds__(256) void rope_expand_kernel(RopeExpandArgs a) {
 __global__ void rope_rotate_q_kernel(const uint16_t* __restrict__ q, uint16_t* __restrict__ q_rot,
                                      const int32_t* __restrict__ seq_len, int32_t B, int32_t n, int32_t H,
                                      int32_t d_head, int32_t max_tokens, double log2_base) {
+  __shared__ double turns_of[128];                               // theta_pair / (2 pi), once per workgroup
+  if (threadIdx.x < (d_head >> 1))
+    turns_of[threadIdx.x] = exp2(-(2.0 * (double)threadIdx.x / (double)d_head) * log2_base) * 0.15915494309189535;
+  __syncthreads();
   const int units = d_head >> 3;
   const int64_t total = (int64_t)B * n * H * units;
   for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
@@ -116,10 +120,8 @@ __global__ void rope_rotate_q_kernel(const uint16_t* __restrict__ q, uint16_t* _
     bf16x8 y;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int pair = u * 4 + i;
-      const double turns = exp2(-(2.0 * (double)pair / (double)d_head) * log2_base) * 0.15915494309189535;
       float c, s;
-      rot_turns((double)pos * turns, c, s);
+      rot_turns((double)pos * turns_of[u * 4 + i], c, s);
       const float x0 = (float)x[2 * i], x1 = (float)x[2 * i + 1];
       y[2 * i] = (__bf16)(x0 * c - x1 * s);
       y[2 * i + 1] = (__bf16)(x0 * s + x1 * c);
