@@ -23,6 +23,7 @@ def mpt_slopes(H):
     (ea.EA_BF16, 4, 4, 128, 128, [513, 100], 64, 2),
     (ea.EA_BF16, 16, 1, 96, 64, [3000], 128, 4),
     (ea.EA_BF16, 2, 2, 72, 40, [0, 65], 64, 1),
+    (ea.EA_BF16, 4, 2, 30, 33, [200, 3], 64, 2),
 ])
 def test_decode_alibi(dtype, H, Hkv, r_k, r_v, lens, P, n_splits):
     print(f"alibi decode dtype={dtype} H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} S={n_splits}", flush=True)

@@ -80,6 +80,7 @@ def test_f32_shapes(H, Hkv, r_k, r_v, lens, P, n_splits):
     (2, 2, 16, 16, [5000], 192, 7),
     (2, 2, 80, 80, [0, 100], 64, 1),                   # an empty sequence gives a zero row
     (2, 2, 80, 80, [90], 64, 4),                       # more splits than tiles: empty workgroups
+    (4, 2, 30, 33, [150, 70, 1], 64, 2),               # ranks that are no multiple of the 8-channel chunk
 ])
 def test_bf16_shapes(H, Hkv, r_k, r_v, lens, P, n_splits):
     print(f"bf16 H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} P={P} S={n_splits}", flush=True)

@@ -65,6 +65,8 @@ def assert_one_bf16_rounding(got: np.ndarray, ref: np.ndarray):
     (ea.EA_BF16, 256, 4, 4, 64, 48, 3, 48, 64, [0, 16, 40]),
     (ea.EA_BF16, 256, 8, 2, 32, 96, 2, 80, 128, [48, 7]),
     (ea.EA_BF16, 512, 4, 4, 80, 80, 1, 300, 64, [64]),                          # rows not a multiple of the tile
+    (ea.EA_BF16, 256, 32, 2, 30, 33, 3, 5, 64, [0, 14, 60]),                    # ranks off the 8-channel chunk
+    (ea.EA_BF16, 256, 32, 2, 30, 33, 2, 40, 64, [0, 50]),                       # same through the tiled GEMM
 ])
 def test_project_qkv(dtype, d, H, Hkv, r_k, r_v, B, T, P, lens):
     print(f"project dtype={dtype} d={d} H={H}/{Hkv} r=({r_k},{r_v}) B={B} T={T} lens={lens}", flush=True)

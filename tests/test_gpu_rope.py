@@ -87,6 +87,7 @@ def test_f32_far_positions_keep_their_angle():
     (2, 1, 128, 80, 80, [20000], 64, 1),                    # one workgroup walks 313 tiles: the stepped rotation
                                                             # of the query is re-computed exactly on the way
     (2, 2, 128, 128, 96, [9000], 64, 1),                    # same with half-tile iterations
+    (4, 2, 128, 30, 33, [150, 70], 64, 2),                  # basis rows that are no whole 16-byte units
 ])
 def test_bf16_shapes(H, Hkv, d_h, r_k, r_v, lens, P, n_splits):
     print(f"rope bf16 H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) lens={lens} P={P} S={n_splits}", flush=True)
@@ -262,6 +263,48 @@ def test_bf16_rope_decode_steps_end_to_end():
         y_ref = ora.decode_step_rope(x_hist[:, n0 + t], folded_q, Uk, cache, 128)
         err = assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"rope bf16 step {t}")
         print(f"  step {t}: rel-L2 {err:.2e}", flush=True)
+
+
+def test_rope_decode_step_is_graph_capturable():
+    """A rotary generation step (ea_project_qkv_rope -> ea_decode_attn_rope with splits -> ea_out_proj) captured in
+    a HIP graph: every replay, with eager work in between, reproduces the eager result bit for bit."""
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(29)
+    wqkv, wo, U_dev, _, _, _ = rope_weights(desc, g)
+    B, n0, S = 4, 700, 3
+    K0, V0 = random_cache(desc, [n0] * B, g)
+    dc = DeviceCache(desc, K0, V0, g, extra_len=1)
+    x = to_dev(desc, quantize(desc, synth.gaussian(g, (B, 512))))
+    q = torch.empty((B, 8, 128), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ea.decode_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    seq_after = dc.seq_len + 1
+
+    def step():
+        ea.project_qkv_rope(desc, x, wqkv, q, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, 1)
+        ea.decode_attn_rope(desc, q, U_dev, 10000.0, dc.k_pool, dc.v_pool, dc.page_table, seq_after, o, n_splits=S,
+                            ws=ws)
+        ea.out_proj(desc, o.view(B, -1), wo, y)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    assert float(y_eager.float().abs().sum()) > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        y.zero_(); o.zero_(); q.zero_()          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep} differs from the eager result"
 
 
 # ---------------------------------------------------------------------------
