@@ -1,0 +1,107 @@
+"""Plain CPU oracle of the integer group quantisation of the rank-r KV cache and of attention over it.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package, shares no code with the HIP kernels.
+
+What the paper fixes ("Eigen Attention with Quantization" paragraph of the results, and the quantisation table
+of the appendix): the rank-r cache is quantised to integers of a few bits in groups; keys are quantised per
+CHANNEL (the values that share a scale are one channel's values over a group of tokens), values per TOKEN (one
+token's values over a group of channels); precisions 3-4 bits and group sizes 16-128 for the compressed cache.
+The paper prints no rounding rule, no zero-point convention and no storage type for the scales, so everything
+below that goes beyond "uniform integer grid per group" is this build's reading, and the functions that depend
+on that reading are PARITY UNPINNED with respect to the paper; they are pinned only to what the mathematics
+fixes for any such quantiser (see tests/test_oracle_quant.py): codes in range, the round-trip error bound of
+half a step, exactness on constant groups and on values that lie on the grid, extremes mapping to the end
+codes, invariance of the codes under the affine map that the scale and zero absorb, and attention over the
+quantised cache being plain attention over the dequantised values.
+
+The reading:
+  * 4 bits, asymmetric: a group with minimum lo and maximum hi gets  zero = fp16(lo),
+    scale = fp16((hi - lo) / 15), both first clamped to the finite fp16 range; the quotient is taken in
+    float32.  A group whose scale rounds to 0 (all values equal, or a spread below fp16's smallest step)
+    gets code 0 everywhere.
+  * code = clip(rint((x - zero) / scale), 0, 15) with x, zero, scale as float32, IEEE division, round half
+    to even: the integer decision is taken in float32 on both sides of the parity tests.
+  * value = scale * code + zero (evaluated in float64 here).
+  * keys: groups of 64 consecutive tokens per channel (token 64 g .. 64 g + 63 of a sequence);
+    values: one group per token over all r_v channels.
+  * only whole groups of 64 tokens are quantised; the newest tokens of a sequence stay in the 16-bit cache
+    until their group is complete (the key groups need all 64 tokens before a scale exists).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import eigen_attention as ea_oracle
+
+GROUP_TOKENS = 64
+LEVELS = 15          # 4 bits: codes 0 .. 15
+F16_MAX = 65504.0
+
+
+def _scale_zero(lo, hi):
+    """fp16 scale and zero of groups with minima lo and maxima hi (float32 arrays)."""
+    lo = np.clip(lo.astype(np.float32), -F16_MAX, F16_MAX)
+    hi = np.clip(hi.astype(np.float32), -F16_MAX, F16_MAX)
+    step = np.minimum((hi - lo) / np.float32(LEVELS), np.float32(F16_MAX))
+    return step.astype(np.float16), lo.astype(np.float16)
+
+
+def _codes(x, scale, zero):
+    """clip(rint((x - zero) / scale), 0, 15) in float32; scale == 0 gives code 0."""
+    x32 = x.astype(np.float32)
+    s32 = scale.astype(np.float32)
+    z32 = zero.astype(np.float32)
+    safe = np.where(s32 > 0, s32, np.float32(1.0))
+    q = np.rint((x32 - z32) / safe)
+    q = np.where(s32 > 0, q, np.float32(0.0))
+    return np.clip(q, 0, LEVELS).astype(np.uint8)
+
+
+def quantize_keys(K):
+    """K [n, r] (n a multiple of 64) -> codes uint8 [n, r], scale fp16 [n/64, r], zero fp16 [n/64, r]:
+    one scale per channel and group of 64 tokens."""
+    n, r = K.shape
+    assert n % GROUP_TOKENS == 0
+    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)
+    scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1))
+    codes = _codes(Kg, scale[:, None, :], zero[:, None, :]).reshape(n, r)
+    return codes, scale, zero
+
+
+def quantize_values(V):
+    """V [n, r] -> codes uint8 [n, r], scale fp16 [n], zero fp16 [n]: one scale per token."""
+    V32 = V.astype(np.float32)
+    scale, zero = _scale_zero(V32.min(axis=1), V32.max(axis=1))
+    return _codes(V32, scale[:, None], zero[:, None]), scale, zero
+
+
+def dequantize_keys(codes, scale, zero):
+    n, r = codes.shape
+    c = codes.astype(np.float64).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)
+    return (scale.astype(np.float64)[:, None, :] * c + zero.astype(np.float64)[:, None, :]).reshape(n, r)
+
+
+def dequantize_values(codes, scale, zero):
+    return scale.astype(np.float64)[:, None] * codes.astype(np.float64) + zero.astype(np.float64)[:, None]
+
+
+def quantized_view(K, V, n_quant: int):
+    """The cache as attention sees it when its first n_quant tokens (a multiple of 64) are held in 4 bits:
+    K [H_kv, n, r_k], V [H_kv, n, r_v] -> arrays of the same shapes, the prefix replaced by its
+    quantise-dequantise round trip, the rest untouched."""
+    assert n_quant % GROUP_TOKENS == 0 and n_quant <= K.shape[1]
+    Kq, Vq = np.array(K, dtype=np.float64), np.array(V, dtype=np.float64)
+    for h in range(K.shape[0]):
+        if n_quant:
+            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant]))
+            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant]))
+    return Kq, Vq
+
+
+def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int):
+    """Generation-phase attention (Eq. 3 in the rank-r space) of one new token per sequence over a cache whose
+    first n_quant[b] tokens are quantised: plain attention over the dequantised values.
+    q_r [B, H, r_k]; K_list[b] [H_kv, n_b, r_k]; V_list[b] [H_kv, n_b, r_v]."""
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
+    return ea_oracle.decode_attention(q_r, cache, d_head)
