@@ -244,6 +244,87 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
                     const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_out,
                     int32_t B, int32_t n, int32_t max_pages, int32_t pool_pages, void* stream);
 
+/* ---- 4-bit group-quantised cache (results, "Eigen Attention with Quantization") ---- */
+
+/* The paper combines the rank-r cache with integer group quantisation: keys per
+ * channel, values per token (as in KIVI and KV-Quant), precisions of 3-4 bits in
+ * groups of 16-128.  This library implements one point of that family, EA_BF16
+ * layers only: 4 bits; a key scale covers one channel over the 64 tokens of a cache
+ * tile, a value scale covers one token over its r_v channels.  The paper gives no
+ * rounding rule; the one used here is
+ *   zero = fp16(lo), scale = fp16((hi - lo) / 15)   (lo / hi = minimum / maximum of
+ *          the group, clamped to +-65504; quotient in float),
+ *   code = clip(rint((x - zero) / scale), 0, 15) in float (round half to even), code 0
+ *          when the scale is 0,
+ *   value = scale * code + zero.
+ * Only whole pages are quantised (a key group needs its 64 tokens); the newest tokens
+ * of a sequence stay in the bfloat16 pools, and ea_decode_attn_q4 attends both parts.
+ *
+ * The 4-bit pools mirror the bfloat16 ones: page p of a pool starts at byte
+ * p * k_page_bytes (v_page_bytes); inside a page kv head after kv head, tile after
+ * tile, one tile block per (kv head, 64 tokens).  A tile block holds the codes in the
+ * order the matrix cores consume them, then the fp16 scales and zeros;
+ * ea_q4_k_code_pos and its siblings are the reference of the positions. */
+typedef struct ea_q4_layout {
+  int32_t r_k_pad;         /* multiple of 8  */
+  int32_t r_v_pad;         /* multiple of 16 */
+  int64_t k_tile_bytes;    /* 32 * r_k_pad + 128 * ceil(r_k_pad / 32) */
+  int64_t v_tile_bytes;    /* 32 * r_v_pad + 256                      */
+  int64_t k_page_bytes;    /* n_kv_heads * (page_tokens / 64) * k_tile_bytes */
+  int64_t v_page_bytes;
+} ea_q4_layout;
+
+EA_API int ea_q4_layout_query(const ea_layer_desc* desc, ea_q4_layout* out);
+
+/* Position of a code inside its pool: the return value is the BIT offset from the
+ * start of the pool of the 4-bit code of channel `channel` of the token at offset
+ * `token_in_page` of kv head `kv_head` in page `page` (always a multiple of 4).
+ * The *_scale_pos functions return the BYTE offset of the fp16 scale that code is
+ * multiplied with; its zero sits 16 bytes (keys) / 128 bytes (values) further.
+ * -1 on an argument out of range. */
+EA_API int64_t ea_q4_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
+EA_API int64_t ea_q4_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
+EA_API int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
+EA_API int64_t ea_q4_v_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page);
+
+/* Quantise n_pages full pages: page dev_src_pages[i] of the bfloat16 pools is written
+ * as page dev_dst_pages[i] of the 4-bit pools (all kv heads, keys and values).  The
+ * source pages are not modified and can be reused by the caller once the call has
+ * run.  Page ids outside their pool are skipped.
+ *   dev_kq_pool / dev_vq_pool: q4_pool_pages * k_page_bytes / v_page_bytes bytes,
+ *   16-byte aligned. */
+EA_API int ea_quantize_pages_q4(const ea_layer_desc* desc, const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_src_pages, void* dev_kq_pool, void* dev_vq_pool,
+                    const int32_t* dev_dst_pages, int32_t n_pages, int32_t pool_pages, int32_t q4_pool_pages,
+                    void* stream);
+
+/* Generation-phase attention (Eq. 3 with Eq. 7's rank-r operands, as ea_decode_attn)
+ * over a cache whose older part is quantised: sequence b consists of its first
+ * q4_len[b] tokens (a multiple of 64; a remainder is ignored) in the 4-bit pools,
+ * addressed by dev_q4_page_table [B, max_q4_pages], followed by tail_len[b] tokens in
+ * the bfloat16 pools, addressed by dev_tail_page_table [B, max_tail_pages] (entry 0 =
+ * the page of the first unquantised token; that token must sit at offset 0 of it,
+ * which holds when whole pages are quantised).  The result is attention over the
+ * dequantised values of the first part and the bfloat16 values of the second.
+ * The codes are expanded inside the matrix-core operands: the scales of a key tile
+ * multiply the query (fp16), those of the value tokens the probabilities (fp16).
+ *   dev_q_r [B, H, r_k] float; dev_out [B, H, r_v] float
+ *   dev_tail_page_table / dev_tail_len may both be NULL (no bfloat16 part)
+ *   n_splits: parts the 4-bit range is cut in (0 = ea_decode_auto_splits for
+ *             max_q4_pages * page_tokens tokens); the tail is one more part
+ *   dev_ws:  ea_decode_q4_workspace_bytes(desc, B, n_splits) bytes, always needed.
+ * Position-free form only (no rotary or ALiBi variant). */
+EA_API int64_t ea_decode_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits);
+EA_API int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    float* dev_out, int32_t B, int32_t n_splits,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -17,6 +17,8 @@ __all__ = [
     "cache_layout_query", "cache_k_index", "cache_v_index", "cache_slot", "cache_scatter", "cache_gather",
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
+    "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
+    "quantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -26,6 +28,8 @@ EXPORTED_SYMBOLS = (
     "ea_cache_scatter", "ea_cache_gather", "ea_packed_weight_elems", "ea_pack_weight", "ea_project_qkv", "ea_project_qkv_rope", "ea_decode_auto_splits", "ea_decode_workspace_bytes",
     "ea_decode_attn", "ea_decode_rope_auto_splits", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
+    "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
+    "ea_quantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4",
 )
 
 
@@ -47,6 +51,11 @@ class CacheLayout(ctypes.Structure):
     _fields_ = [("layout_id", ctypes.c_int32), ("elem_bytes", ctypes.c_int32), ("r_k_pad", ctypes.c_int32),
                 ("r_v_pad", ctypes.c_int32), ("k_slab_elems", ctypes.c_int64), ("v_slab_elems", ctypes.c_int64),
                 ("k_page_elems", ctypes.c_int64), ("v_page_elems", ctypes.c_int64)]
+
+
+class Q4Layout(ctypes.Structure):
+    _fields_ = [("r_k_pad", ctypes.c_int32), ("r_v_pad", ctypes.c_int32), ("k_tile_bytes", ctypes.c_int64),
+                ("v_tile_bytes", ctypes.c_int64), ("k_page_bytes", ctypes.c_int64), ("v_page_bytes", ctypes.c_int64)]
 
 
 _LIB = None
@@ -102,6 +111,16 @@ def load_library():
     lib.ea_prefill_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_prefill_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_out_proj.argtypes = [D, VP, I32, VP, VP, I32, VP]
+    lib.ea_q4_layout_query.argtypes = [D, P(Q4Layout)]
+    for f in (lib.ea_q4_k_code_pos, lib.ea_q4_v_code_pos, lib.ea_q4_k_scale_pos):
+        f.restype = I64
+        f.argtypes = [D, I32, I32, I32, I32]
+    lib.ea_q4_v_scale_pos.restype = I64
+    lib.ea_q4_v_scale_pos.argtypes = [D, I32, I32, I32]
+    lib.ea_quantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
+    lib.ea_decode_q4_workspace_bytes.restype = I64
+    lib.ea_decode_q4_workspace_bytes.argtypes = [D, I32, I32]
+    lib.ea_decode_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
     _LIB = lib
     return lib
 
@@ -397,3 +416,83 @@ def out_proj(desc, o, wo, y, stream=None) -> None:
         raise ValueError("o / packed wo size does not match the layer")
     rc = load_library().ea_out_proj(ctypes.byref(desc), _ptr(o), _dt(o), _ptr(wo), _ptr(y), M, _stream(stream))
     _check(rc, "ea_out_proj")
+
+
+# ---- 4-bit group-quantised cache ----------------------------------------------
+def q4_layout_query(desc: LayerDesc) -> Q4Layout:
+    out = Q4Layout()
+    _check(load_library().ea_q4_layout_query(ctypes.byref(desc), ctypes.byref(out)), "ea_q4_layout_query")
+    return out
+
+
+def q4_k_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
+    return int(load_library().ea_q4_k_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def q4_v_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
+    return int(load_library().ea_q4_v_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def q4_k_scale_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
+    return int(load_library().ea_q4_k_scale_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def q4_v_scale_pos(desc, page: int, kv_head: int, token_in_page: int) -> int:
+    return int(load_library().ea_q4_v_scale_pos(ctypes.byref(desc), page, kv_head, token_in_page))
+
+
+def alloc_q4_pools(desc: LayerDesc, q4_pool_pages: int, device="cuda", zero: bool = True):
+    """Device memory for the 4-bit K and V page pools of one layer: uint8 [q4_pool_pages, page_bytes] each."""
+    import torch
+    lay = q4_layout_query(desc)
+    mk = torch.zeros if zero else torch.empty
+    return (mk((q4_pool_pages, lay.k_page_bytes), dtype=torch.uint8, device=device),
+            mk((q4_pool_pages, lay.v_page_bytes), dtype=torch.uint8, device=device))
+
+
+def _u8(t, name: str) -> None:
+    import torch
+    if t.dtype != torch.uint8:
+        raise ValueError(f"{name} must be uint8")
+
+
+def quantize_pages_q4(desc, k_pool, v_pool, src_pages, kq_pool, vq_pool, dst_pages, stream=None) -> None:
+    """Full pages src_pages[i] of the bfloat16 pools -> pages dst_pages[i] of the 4-bit pools."""
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _u8(kq_pool, "kq_pool"); _u8(vq_pool, "vq_pool")
+    _i32(src_pages, "src_pages"); _i32(dst_pages, "dst_pages")
+    if src_pages.numel() != dst_pages.numel():
+        raise ValueError("src_pages and dst_pages must have the same length")
+    rc = load_library().ea_quantize_pages_q4(ctypes.byref(desc), _ptr(k_pool), _ptr(v_pool), _ptr(src_pages),
+                                             _ptr(kq_pool), _ptr(vq_pool), _ptr(dst_pages), src_pages.numel(),
+                                             k_pool.shape[0], kq_pool.shape[0], _stream(stream))
+    _check(rc, "ea_quantize_pages_q4")
+
+
+def decode_q4_workspace_bytes(desc, B: int, n_splits: int) -> int:
+    return int(load_library().ea_decode_q4_workspace_bytes(ctypes.byref(desc), B, n_splits))
+
+
+def decode_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
+                   n_splits: int, ws, stream=None) -> None:
+    """q_r [B, H, r_k] float32 -> out [B, H, r_v] float32 over q4_len[b] tokens of the 4-bit pools followed by
+    tail_len[b] tokens of the bfloat16 pools (k_pool, v_pool, tail_page_table, tail_len may all be None)."""
+    import torch
+    B = q4_len.shape[0]
+    if q_r.dtype != torch.float32 or out.dtype != torch.float32:
+        raise ValueError("q_r and out must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    _u8(kq_pool, "kq_pool"); _u8(vq_pool, "vq_pool")
+    _i32(q4_page_table, "q4_page_table"); _i32(q4_len, "q4_len")
+    tail = tail_page_table is not None
+    if tail:
+        _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+        _i32(tail_page_table, "tail_page_table"); _i32(tail_len, "tail_len")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_decode_attn_q4(
+        ctypes.byref(desc), _ptr(q_r), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
+        q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool) if tail else None, _ptr(v_pool) if tail else None,
+        _ptr(tail_page_table), _ptr(tail_len) if tail else None, tail_page_table.shape[1] if tail else 0,
+        k_pool.shape[0] if tail else 0, _ptr(out), B, n_splits, _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_decode_attn_q4")

@@ -43,6 +43,10 @@ struct DecodeArgs {
   double log2_base;   // log2 of the rotary base
   // ALiBi variant only
   const float* alibi;  // [H] slopes (natural-log units, >= 0)
+  // When ws_slots > 0 the kernel always writes split partials, into slots ws_slot0 .. ws_slot0 + n_splits - 1
+  // of a workspace laid out for ws_slots splits (another kernel fills the other slots).
+  int32_t ws_slots = 0;
+  int32_t ws_slot0 = 0;
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -522,11 +526,12 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       }
     }
     const int head = kvh * G + hd;
-    if (a.n_splits == 1) {
+    if (a.n_splits == 1 && a.ws_slots == 0) {
       if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
     } else {
-      const int64_t BHS = (int64_t)gridDim.z * g.n_heads * a.n_splits;
-      const int64_t row = ((int64_t)b * g.n_heads + head) * a.n_splits + split;
+      const int slots = a.ws_slots > 0 ? a.ws_slots : a.n_splits;
+      const int64_t BHS = (int64_t)gridDim.z * g.n_heads * slots;
+      const int64_t row = ((int64_t)b * g.n_heads + head) * slots + a.ws_slot0 + split;
       if (c == 0) {
         a.ws[row] = mm;
         a.ws[BHS + row] = lsum;

@@ -1,0 +1,341 @@
+// Generation-phase attention over the 4-bit group-quantised part of the rank-r cache (keys: scale and zero per
+// channel and 64-token tile; values: per token).  The codes never become 16-bit values in memory:
+//   scores   s[t,h] = sum_c (scale_c code[t,c] + zero_c) q[h,c]
+//                   = sum_c (64 + code[t,c]) (scale_c q[h,c]) + sum_c zero_c q[h,c] - 64 sum_c scale_c q[h,c]:
+//            the scales go into the query once per tile, the nibbles become the fp16 numbers 64 + code with one
+//            mask-and-or (0x5400 is 64.0 and its mantissa bits 4-7 count units), and the two constant terms
+//            are two more matrix-core products whose result starts the score accumulators;
+//   output   o[h,c] = sum_t p[h,t] (scale_t code[t,c] + zero_t)
+//                   = sum_t (p scale)[h,t] (64 + code[t,c]) + sum_t p[h,t] zero_t - 64 sum_t (p scale)[h,t]:
+//            the scales go into the probabilities, the constant terms ride in the product that also makes the
+//            softmax denominators.
+// The kernel always writes split partials (m, l, acc); the 16-bit tail of the sequences is attended by the
+// bfloat16 kernel into further slots of the same workspace and one merge finishes.
+#include "ea_q4.h"
+
+namespace ea {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+struct DecodeQ4Args {
+  const float* q;
+  const uint8_t* kq_pool;
+  const uint8_t* vq_pool;
+  const int32_t* page_table;
+  const int32_t* q4_len;
+  float* ws;
+  Geo g;            // max_pages / pool_pages are those of the 4-bit pools
+  Q4Geo qg;
+  int32_t n_splits;
+  int32_t ws_slots;
+  float scale_log2;
+};
+
+template <int NCB>
+struct MergeSmemQ4 {
+  float m[4][16];
+  float l[4][16];
+  float bias[4][16];
+  float acc[4][16][NCB * 16];
+};
+
+__device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight nibbles -> the eight fp16 numbers 64 + code; element 2i is nibble i, element 2i+1 nibble i+4.
+__device__ __forceinline__ f16x8 unpack_q4(uint32_t w) {
+  constexpr uint32_t mask = 0x00f000f0u, magic = 0x54005400u;
+  u32x4 r;
+  r[0] = ((w << 4) & mask) | magic;
+  r[1] = (w & mask) | magic;
+  r[2] = ((w >> 4) & mask) | magic;
+  r[3] = ((w >> 8) & mask) | magic;
+  return __builtin_bit_cast(f16x8, r);
+}
+
+template <int KS, int NCB>
+__global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
+  __shared__ MergeSmemQ4<NCB> sm;
+  constexpr int NVP = NCB / 2;          // 16-byte units of value codes per lane
+  constexpr bool VODD = (NCB & 1) != 0; // ... plus one 8-byte unit
+  const Geo& g = a.g;
+  const Q4Geo& qg = a.qg;
+  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int col = lane & 15, quad = lane >> 4;
+  const int G = g.group;
+
+  typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+  const const_i32_ptr len_c = (const_i32_ptr)a.q4_len;
+  const const_i32_ptr pt_row = (const_i32_ptr)(a.page_table + (int64_t)b * g.max_pages);
+  int64_t n64 = len_c[b];
+  const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
+  if (n64 > cap) n64 = cap;
+  if (n64 < 0) n64 = 0;
+  const int n_tiles = (int)(n64 / kTile);          // whole tiles only: a ragged end is not part of the 4-bit cache
+  const int per = (n_tiles + a.n_splits - 1) / a.n_splits;
+  const int t_begin = split * per;
+  const int t_end = min(n_tiles, t_begin + per);
+  const int tiles_per_page = qg.tiles_per_page;
+
+  // B operand of the score product: q^T in fp16, already times log2(e)/sqrt(d_head); lane (col, quad) holds
+  // channels 32*ks + 8*quad .. +7 of head col.
+  f16x8 q16[KS];
+  {
+    const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + (col < G ? col : 0)) * g.r_k;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int k = ks * 32 + quad * 8 + j;
+        const float v = (col < G && k < g.r_k) ? qrow[k < g.r_k ? k : 0] * a.scale_log2 : 0.f;
+        q16[ks][j] = (_Float16)v;
+      }
+    }
+  }
+  f16x8 neg64, ones;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    neg64[j] = (_Float16)-64.0f;
+    ones[j] = (_Float16)1.0f;
+  }
+
+  f32x4 acc[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  f32x4 stat = {0.f, 0.f, 0.f, 0.f};   // row 0: sum_t p; row 1: sum_t p zero_t   (lanes of quad 0, registers 0 and 1)
+  f32x4 corr = {0.f, 0.f, 0.f, 0.f};   // every row: -64 sum_t p scale_t
+  float m = -INFINITY;
+
+  u32x4 kc[KS];
+  f16x8 ksc[KS], kzr[KS];
+  u32x4 vc[NVP > 0 ? NVP : 1];
+  u32x2 vcl = {0u, 0u};
+  f16x8 vsc[2], vzr[2];
+
+  struct Pos {
+    int tile, lp, tin;
+  };
+  Pos cur;
+  cur.tile = t_begin + wave;           // the four waves interleave tiles
+  cur.lp = cur.tile / tiles_per_page;
+  cur.tin = cur.tile % tiles_per_page;
+  auto advance = [&](Pos p) -> Pos {
+    p.tile += 4;
+    p.tin += 4;
+    while (p.tin >= tiles_per_page) {
+      p.tin -= tiles_per_page;
+      p.lp += 1;
+    }
+    return p;
+  };
+  auto page_of = [&](const Pos& p) -> int {
+    const int page = pt_row[p.lp];
+    return (page >= 0 && page < g.pool_pages) ? page : -1;
+  };
+  auto load_k = [&](const Pos& p, int page) {
+    const uint8_t* base = a.kq_pool + (int64_t)page * qg.k_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.k_tile;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      // lanes of a quad the last k-step does not have re-read quad 0's unit; their query channels are zero
+      const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
+      const int off = kk * 1024 + (past ? col : lane) * 16;
+      kc[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+      const uint8_t* sp = base + qg.nch * 256 + (kk * 4 + quad) * 32;
+      ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
+      kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
+    }
+  };
+  auto load_v = [&](const Pos& p, int page) {
+    const uint8_t* base = a.vq_pool + (int64_t)page * qg.v_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.v_tile;
+#pragma unroll
+    for (int pp = 0; pp < NVP; ++pp)
+      vc[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + pp * 1024 + lane * 16));
+    if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * 1024 + lane * 8));
+    const uint8_t* sp = base + NCB * 512;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      vsc[u] = *reinterpret_cast<const f16x8*>(sp + (u * 4 + quad) * 16);
+      vzr[u] = *reinterpret_cast<const f16x8*>(sp + 128 + (u * 4 + quad) * 16);
+    }
+  };
+  auto v_dword = [&](int cb, int u) -> uint32_t {
+    if (VODD && cb == NCB - 1) return vcl[u];
+    return vc[cb >> 1][(cb & 1) * 2 + u];
+  };
+
+  bool have = cur.tile < t_end;
+  int page = -1;
+  if (have) {
+    page = page_of(cur);
+    // a tile without a valid page is still read -- from page 0 -- and masked below
+    load_k(cur, max(page, 0));
+    load_v(cur, max(page, 0));
+  }
+  Pos nxt = advance(cur);
+  bool have_n = have && nxt.tile < t_end;
+  int page_n = have_n ? page_of(nxt) : -1;
+
+  const f16x8 zero8 = __builtin_bit_cast(f16x8, u32x4{0u, 0u, 0u, 0u});
+
+  while (have) {
+    // ---- scores (log2 units): lane (col, quad) gets tokens 16*tb + 4*quad + i of head col
+    f16x8 qs[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) qs[kk] = q16[kk] * ksc[kk];
+    f32x4 sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      sb = mfma16h(kzr[kk], q16[kk], sb);      // every row: sum_c zero_c q_c
+      sb = mfma16h(neg64, qs[kk], sb);         // every row: -64 sum_c scale_c q_c
+    }
+    f32x4 s[4];
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+      s[tb] = sb;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(unpack_q4(kc[kk][tb]), qs[kk], s[tb]);
+    }
+    if (have_n) load_k(nxt, max(page_n, 0));
+
+    // ---- online softmax
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (page < 0) s[tb][i] = -INFINITY;
+        mx = fmaxf(mx, s[tb][i]);
+      }
+    }
+    mx = quad_column_max(mx);
+    if (__any(mx > m + kLazy)) {
+      const float m_new = fmaxf(m, mx);
+      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
+      stat *= alpha;
+      corr *= alpha;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+      m = m_new;
+    }
+    const float m_use = m == -INFINITY ? 0.f : m;
+    f16x8 pf[2], ps[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (_Float16)__builtin_amdgcn_exp2f(s[2 * u + h][i] - m_use);
+      }
+      // scales and zeros of a page that is not there are whatever page 0 holds: drop them
+      const f16x8 sc_u = page < 0 ? zero8 : vsc[u];
+      const f16x8 zr_u = page < 0 ? zero8 : vzr[u];
+      ps[u] = pf[u] * sc_u;
+      stat = mfma16h(col == 0 ? ones : zr_u, pf[u], stat);
+      corr = mfma16h(neg64, ps[u], corr);
+    }
+    // ---- O^T += (64 + codes)^T . (p scale)^T
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(unpack_q4(v_dword(cb, u)), ps[u], acc[cb]);
+    }
+    if (have_n) load_v(nxt, max(page_n, 0));
+    cur = nxt;
+    have = have_n;
+    page = page_n;
+    nxt = advance(cur);
+    have_n = have && nxt.tile < t_end;
+    page_n = have_n ? page_of(nxt) : -1;
+  }
+
+  // ---- merge the four waves, fold the constant terms in, write the split's partial
+  if (quad == 0) {
+    sm.m[wave][col] = m;
+    sm.l[wave][col] = stat[0];
+    sm.bias[wave][col] = stat[1];
+  }
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sm.acc[wave][col][cb * 16 + quad * 4 + i] = acc[cb][i] + corr[i];
+  __syncthreads();
+
+  constexpr int r_v_pad = NCB * 16;
+  for (int idx = threadIdx.x; idx < G * r_v_pad; idx += blockDim.x) {
+    const int hd = idx / r_v_pad, c = idx % r_v_pad;
+    float mm = sm.m[0][hd];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mm = fmaxf(mm, sm.m[w][hd]);
+    float lsum = 0.f, val = 0.f;
+    if (mm != -INFINITY) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float wt = __builtin_amdgcn_exp2f(sm.m[w][hd] - mm);
+        lsum += wt * sm.l[w][hd];
+        val += wt * (sm.acc[w][hd][c] + sm.bias[w][hd]);
+      }
+    }
+    const int head = kvh * G + hd;
+    const int64_t BHS = (int64_t)gridDim.z * g.n_heads * a.ws_slots;
+    const int64_t row = ((int64_t)b * g.n_heads + head) * a.ws_slots + split;
+    if (c == 0) {
+      a.ws[row] = mm;
+      a.ws[BHS + row] = lsum;
+    }
+    a.ws[2 * BHS + row * r_v_pad + c] = val;
+  }
+}
+
+template <int KS, int NCB>
+static void launch_q4(const DecodeQ4Args& a, int32_t B, hipStream_t st) {
+  decode_q4_kernel<KS, NCB><<<dim3(a.g.n_kv_heads, a.n_splits, B), dim3(256), 0, st>>>(a);
+}
+
+template <int KS>
+static int dispatch_ncb_q4(int ncb, const DecodeQ4Args& a, int32_t B, hipStream_t st) {
+  switch (ncb) {
+    case 1: launch_q4<KS, 1>(a, B, st); break;
+    case 2: launch_q4<KS, 2>(a, B, st); break;
+    case 3: launch_q4<KS, 3>(a, B, st); break;
+    case 4: launch_q4<KS, 4>(a, B, st); break;
+    case 5: launch_q4<KS, 5>(a, B, st); break;
+    case 6: launch_q4<KS, 6>(a, B, st); break;
+    case 7: launch_q4<KS, 7>(a, B, st); break;
+    case 8: launch_q4<KS, 8>(a, B, st); break;
+    default: return EA_ERR_SHAPE;
+  }
+  return launch_status();
+}
+
+int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* kq_pool,
+              const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
+              int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st) {
+  if (B > 65535 || g.n_kv_heads > 65535 || n_splits > 65535) return EA_ERR_SHAPE;
+  DecodeQ4Args a;
+  a.q = q;
+  a.kq_pool = (const uint8_t*)kq_pool;
+  a.vq_pool = (const uint8_t*)vq_pool;
+  a.page_table = q4_page_table;
+  a.q4_len = q4_len;
+  a.ws = ws;
+  a.g = g;
+  a.g.max_pages = max_q4_pages;
+  a.g.pool_pages = q4_pool_pages;
+  a.qg = qg;
+  a.n_splits = n_splits;
+  a.ws_slots = ws_slots;
+  a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
+  switch (qg.ks) {
+    case 1: return dispatch_ncb_q4<1>(qg.ncb, a, B, st);
+    case 2: return dispatch_ncb_q4<2>(qg.ncb, a, B, st);
+    case 3: return dispatch_ncb_q4<3>(qg.ncb, a, B, st);
+    case 4: return dispatch_ncb_q4<4>(qg.ncb, a, B, st);
+    default: return EA_ERR_SHAPE;
+  }
+}
+
+}  // namespace ea

@@ -1,0 +1,77 @@
+// The 4-bit group-quantised form of the rank-r cache (keys per channel over the 64 tokens of a tile, values
+// per token; results paragraph on quantisation): geometry and the position of every code and scale.
+//
+// A page of the 4-bit pools holds the same tokens as a page of the bfloat16 pools: kv head after kv head,
+// tile after tile; one tile block is 64 tokens of one kv head.
+//
+// K tile block  = codes, then scales.
+//   codes : for k-step kk (32 channels) a run of 16-byte units, one per lane l = 16*quad + t of the quads that
+//           exist in this step (4*kk + quad < r_k_pad/8); the unit's dword tb holds the 8 channels
+//           32*kk + 8*quad .. +7 of token 16*tb + t.          -> 64 * r_k_pad / 2 bytes
+//   scales: [k-step][quad][scale x8, zero x8] fp16, channel 32*kk + 8*quad + e at slot e.   -> KS * 128 bytes
+// V tile block  = codes, then scales.
+//   codes : dword (cb, u) of lane l = 16*quad + ch holds channel 16*cb + ch of the 8 tokens
+//           32*u + 16*(j/4) + 4*quad + j%4, j = 0..7.  Dwords are stored four to a 16-byte unit per lane:
+//           unit p = (cb = 2p, u = 0), (2p, 1), (2p+1, 0), (2p+1, 1); an odd last cb has 8-byte units.
+//                                                             -> 64 * r_v_pad / 2 bytes
+//   scales: [scale, zero][u][quad][8 token slots] fp16.       -> 256 bytes
+// Inside a dword, element e (channel / token slot e of the 8) sits in nibble e/2 if e is even, 4 + e/2 if odd:
+// the kernel's unpacking puts nibbles i and i+4 into the two halves of one register.
+#pragma once
+#include "ea_common.h"
+
+namespace ea {
+
+struct Q4Geo {
+  int32_t nch;             // 8-channel chunks of a key row: r_k_pad / 8
+  int32_t ks;              // 32-channel k-steps: ceil(nch / 4)
+  int32_t ncb;             // 16-channel blocks of a value row: r_v_pad / 16
+  int32_t tiles_per_page;
+  int64_t k_tile, v_tile;  // bytes of a tile block
+  int64_t k_page, v_page;  // bytes of a page (all kv heads)
+};
+
+__host__ __device__ inline Q4Geo make_q4_geo(int32_t r_k, int32_t r_v, int32_t n_kv_heads, int32_t page_tokens) {
+  Q4Geo q;
+  q.nch = (r_k + 7) / 8;
+  q.ks = (q.nch + 3) / 4;
+  q.ncb = (r_v + 15) / 16;
+  q.tiles_per_page = page_tokens / kTile;
+  q.k_tile = (int64_t)q.nch * 256 + (int64_t)q.ks * 128;
+  q.v_tile = (int64_t)q.ncb * 512 + 256;
+  q.k_page = q.k_tile * q.tiles_per_page * n_kv_heads;
+  q.v_page = q.v_tile * q.tiles_per_page * n_kv_heads;
+  return q;
+}
+
+__host__ __device__ inline int32_t q4_nibble_shift(int32_t e) { return 4 * ((e & 1) ? 4 + (e >> 1) : (e >> 1)); }
+
+// Byte offset inside a K tile block of the dword holding (token tt of the tile, channel c); c < 8 * nch.
+__host__ __device__ inline int32_t q4_k_dword_off(int32_t tt, int32_t c) {
+  const int32_t kk = c >> 5, quad = (c >> 3) & 3, tb = tt >> 4, t = tt & 15;
+  return kk * 1024 + (quad * 16 + t) * 16 + tb * 4;
+}
+__host__ __device__ inline int32_t q4_k_scale_off(const Q4Geo& q, int32_t c) {
+  return q.nch * 256 + ((c >> 5) * 4 + ((c >> 3) & 3)) * 32 + (c & 7) * 2;       // the zero is 16 bytes further
+}
+// Byte offset inside a V tile block of the dword holding (token tt, channel c), and the element slot of the token.
+__host__ __device__ inline int32_t q4_v_dword_off(const Q4Geo& q, int32_t tt, int32_t c, int32_t* slot) {
+  const int32_t u = tt >> 5, t32 = tt & 31, half = t32 >> 4, quad = (t32 & 15) >> 2;
+  *slot = half * 4 + (t32 & 3);
+  const int32_t cb = c >> 4, lane = quad * 16 + (c & 15), p = cb >> 1;
+  if ((q.ncb & 1) && cb == q.ncb - 1) return p * 1024 + lane * 8 + u * 4;
+  return p * 1024 + lane * 16 + ((cb & 1) * 2 + u) * 4;
+}
+__host__ __device__ inline int32_t q4_v_scale_off(const Q4Geo& q, int32_t tt) {
+  const int32_t u = tt >> 5, t32 = tt & 31, half = t32 >> 4, quad = (t32 & 15) >> 2;
+  return q.ncb * 512 + ((u * 4 + quad) * 8 + half * 4 + (t32 & 3)) * 2;          // the zero is 128 bytes further
+}
+
+int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
+                      void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
+                      hipStream_t st);
+int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* kq_pool,
+              const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
+              int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st);
+
+}  // namespace ea

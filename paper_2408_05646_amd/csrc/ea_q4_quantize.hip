@@ -1,0 +1,153 @@
+// Quantises whole pages of the bfloat16 rank-r cache to the 4-bit group form (keys: one scale per channel and
+// 64-token tile; values: one scale per token).  A group with minimum lo and maximum hi gets
+// zero = fp16(lo), scale = fp16((hi - lo) / 15) and codes clip(rint((x - zero) / scale), 0, 15), all in float;
+// a scale that rounds to 0 gives code 0.  Not a hot kernel: it runs once per page, when the page is full.
+#include "ea_q4.h"
+
+namespace ea {
+
+struct QuantArgs {
+  const uint16_t* k_pool;
+  const uint16_t* v_pool;
+  const int32_t* src_pages;
+  uint8_t* kq_pool;
+  uint8_t* vq_pool;
+  const int32_t* dst_pages;
+  Geo g;
+  Q4Geo qg;
+  int32_t q4_pool_pages;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
+
+// scale and zero of a group, as the fp16 values they are stored as
+__device__ __forceinline__ void group_scale_zero(float lo, float hi, _Float16& s, _Float16& z) {
+  lo = fminf(fmaxf(lo, -65504.f), 65504.f);
+  hi = fminf(fmaxf(hi, -65504.f), 65504.f);
+  s = (_Float16)fminf((hi - lo) / 15.0f, 65504.f);
+  z = (_Float16)lo;
+}
+
+__device__ __forceinline__ uint32_t code_of(float x, float s, float z) {
+  if (!(s > 0.f)) return 0u;
+  return (uint32_t)fminf(fmaxf(rintf((x - z) / s), 0.f), 15.f);
+}
+
+__global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
+  __shared__ float x[kTile][129];
+  __shared__ float sc[128], zr[128];
+  const Geo& g = a.g;
+  const Q4Geo& qg = a.qg;
+  const int tile = blockIdx.x, kvh = blockIdx.y;
+  const int src = a.src_pages[blockIdx.z], dst = a.dst_pages[blockIdx.z];
+  if (src < 0 || src >= g.pool_pages || dst < 0 || dst >= a.q4_pool_pages) return;   // the whole workgroup leaves
+  const int tid = threadIdx.x;
+
+  // ---- keys: x[token][channel] <- the tile in its fragment order [4 blocks][nch chunks][16 tokens][8 channels]
+  {
+    const uint16_t* kb = a.k_pool + (int64_t)src * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tile * (kTile * g.r_k_pad);
+    for (int e = tid; e < kTile * g.r_k_pad; e += 256) {
+      const int ce = e & 7, t = (e >> 3) & 15, rest = e >> 7;
+      const int chunk = rest % qg.nch, tb = rest / qg.nch;
+      x[tb * 16 + t][chunk * 8 + ce] = bf16_bits_to_float(kb[e]);
+    }
+    __syncthreads();
+    if (tid < 128) {
+      _Float16 s = (_Float16)0.f, z = (_Float16)0.f;
+      if (tid < g.r_k) {
+        float lo = x[0][tid], hi = lo;
+        for (int t = 1; t < kTile; ++t) {
+          lo = fminf(lo, x[t][tid]);
+          hi = fmaxf(hi, x[t][tid]);
+        }
+        group_scale_zero(lo, hi, s, z);
+      }
+      sc[tid] = (float)s;
+      zr[tid] = (float)z;
+    }
+    __syncthreads();
+    uint8_t* ko = a.kq_pool + (int64_t)dst * qg.k_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.k_tile;
+    for (int c = tid; c < qg.ks * 32; c += 256) {
+      _Float16* p = reinterpret_cast<_Float16*>(ko + q4_k_scale_off(qg, c));
+      p[0] = (_Float16)sc[c];
+      p[8] = (_Float16)zr[c];
+    }
+    for (int e = tid; e < qg.nch * 64; e += 256) {
+      const int tb = e & 3, t = (e >> 2) & 15, chunk = e >> 6;
+      uint32_t w = 0;
+#pragma unroll
+      for (int ce = 0; ce < 8; ++ce) {
+        const int c = chunk * 8 + ce;
+        w |= code_of(x[tb * 16 + t][c], sc[c], zr[c]) << q4_nibble_shift(ce);
+      }
+      *reinterpret_cast<uint32_t*>(ko + q4_k_dword_off(tb * 16 + t, chunk * 8)) = w;
+    }
+    __syncthreads();
+  }
+
+  // ---- values: fragment order [2 groups][ncb blocks][4 quads][16 channels][8 token slots]
+  {
+    const uint16_t* vb = a.v_pool + (int64_t)src * g.v_page + (int64_t)kvh * g.v_slab + (int64_t)tile * (kTile * g.r_v_pad);
+    for (int e = tid; e < kTile * g.r_v_pad; e += 256) {
+      const int j = e & 7, ch = (e >> 3) & 15, quad = (e >> 7) & 3, rest = e >> 9;
+      const int cb = rest % qg.ncb, u = rest / qg.ncb;
+      x[u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3)][cb * 16 + ch] = bf16_bits_to_float(vb[e]);
+    }
+    __syncthreads();
+    uint8_t* vo = a.vq_pool + (int64_t)dst * qg.v_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.v_tile;
+    if (tid < kTile) {
+      float lo = x[tid][0], hi = lo;
+      for (int c = 1; c < g.r_v; ++c) {
+        lo = fminf(lo, x[tid][c]);
+        hi = fmaxf(hi, x[tid][c]);
+      }
+      _Float16 s, z;
+      group_scale_zero(lo, hi, s, z);
+      sc[tid] = (float)s;
+      zr[tid] = (float)z;
+      _Float16* p = reinterpret_cast<_Float16*>(vo + q4_v_scale_off(qg, tid));
+      p[0] = s;
+      p[64] = z;
+    }
+    __syncthreads();
+    for (int e = tid; e < qg.ncb * 128; e += 256) {
+      const int lane = e & 63, u = (e >> 6) & 1, cb = e >> 7;
+      const int quad = lane >> 4, c = cb * 16 + (lane & 15);
+      uint32_t w = 0;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int tt = u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
+        const uint32_t code = c < g.r_v ? code_of(x[tt][c], sc[tt], zr[tt]) : 0u;
+        w |= code << q4_nibble_shift(j);
+      }
+      int slot;
+      *reinterpret_cast<uint32_t*>(vo + q4_v_dword_off(qg, u * 32 + quad * 4, c, &slot)) = w;
+    }
+  }
+}
+
+int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
+                      void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
+                      hipStream_t st) {
+  if (g.n_kv_heads > 65535) return EA_ERR_SHAPE;
+  QuantArgs a;
+  a.k_pool = (const uint16_t*)k_pool;
+  a.v_pool = (const uint16_t*)v_pool;
+  a.src_pages = src_pages;
+  a.kq_pool = (uint8_t*)kq_pool;
+  a.vq_pool = (uint8_t*)vq_pool;
+  a.dst_pages = dst_pages;
+  a.g = g;
+  a.qg = qg;
+  a.q4_pool_pages = q4_pool_pages;
+  for (int32_t done = 0; done < n_pages; done += 65535) {        // grid.z is limited to 65535
+    const int32_t now = n_pages - done < 65535 ? n_pages - done : 65535;
+    QuantArgs b = a;
+    b.src_pages = src_pages + done;
+    b.dst_pages = dst_pages + done;
+    quantize_q4_kernel<<<dim3(qg.tiles_per_page, g.n_kv_heads, now), dim3(256), 0, st>>>(b);
+  }
+  return launch_status();
+}
+
+}  // namespace ea

@@ -1,0 +1,231 @@
+"""4-bit group-quantised rank-r cache (results paragraph on quantisation): ea_quantize_pages_q4 against the oracle's
+quantiser bit for bit, ea_decode_attn_q4 against the oracle's attention over the dequantised values."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_05646_amd as ea
+from oracle import quant_cache as oq
+from paper_2408_05646_amd import synth
+from helpers import DeviceCache, TOL_BF16, assert_close, quantize
+
+pytestmark = pytest.mark.gpu
+
+
+def tile_positions(desc):
+    """Bit position of every code and byte position of every scale of ONE tile block, relative to its start,
+    from the library's reference functions (page 0, kv head 0, tokens 0..63)."""
+    kc = np.array([[ea.q4_k_code_pos(desc, 0, 0, t, c) for c in range(desc.r_k)] for t in range(64)])
+    vc = np.array([[ea.q4_v_code_pos(desc, 0, 0, t, c) for c in range(desc.r_v)] for t in range(64)])
+    ks = np.array([ea.q4_k_scale_pos(desc, 0, 0, 0, c) for c in range(desc.r_k)])
+    vs = np.array([ea.q4_v_scale_pos(desc, 0, 0, t) for t in range(64)])
+    for t in (1, 17, 63):   # key scales do not depend on the token
+        assert ea.q4_k_scale_pos(desc, 0, 0, t, 3 % desc.r_k) == ks[3 % desc.r_k]
+    return kc, vc, ks, vs
+
+
+def read_codes(buf, bitpos):
+    return (buf[bitpos >> 3] >> (bitpos & 7).astype(np.uint8)) & 15
+
+
+def read_f16(buf, bytepos):
+    return (buf[bytepos].astype(np.uint16) | (buf[bytepos + 1].astype(np.uint16) << 8)).view(np.float16)
+
+
+def read_tile(desc, lay, pos, kq, vq, page, kvh, tile):
+    """codes [64, r_k], scale [r_k], zero [r_k] of the keys and codes [64, r_v], scale [64], zero [64] of the
+    values of one tile block, from host copies of the pools."""
+    kc, vc, ks, vs = pos
+    tpp = desc.page_tokens // 64
+    k0 = page * lay.k_page_bytes + (kvh * tpp + tile) * lay.k_tile_bytes
+    v0 = page * lay.v_page_bytes + (kvh * tpp + tile) * lay.v_tile_bytes
+    return (read_codes(kq, kc + 8 * k0), read_f16(kq, ks + k0), read_f16(kq, ks + k0 + 16),
+            read_codes(vq, vc + 8 * v0), read_f16(vq, vs + v0), read_f16(vq, vs + v0 + 128))
+
+
+class Q4Cache:
+    """bf16 pools holding every token, then the first n_quant[b] tokens of each sequence quantised into 4-bit
+    pools with their own random page ids; the bf16 pages of the quantised part are overwritten with NaN
+    afterwards, so attention cannot have read them."""
+
+    def __init__(self, desc, K, V, n_quant, g, poison_sources=True):
+        P = desc.page_tokens
+        B = len(K)
+        self.dc = DeviceCache(desc, K, V, g)
+        nq_pages = [n // P for n in n_quant]
+        assert all(n % P == 0 for n in n_quant)
+        self.max_q4_pages = max(1, max(nq_pages))
+        self.q4_pool_pages = sum(nq_pages) + 3
+        self.kq, self.vq = ea.alloc_q4_pools(desc, self.q4_pool_pages)
+        self.kq.fill_(0xFF)          # fp16 NaN patterns and code 15 wherever nothing is written
+        self.vq.fill_(0xFF)
+        ids = g.permutation(self.q4_pool_pages).astype(np.int32)
+        table = np.full((B, self.max_q4_pages), -1, np.int32)
+        src, dst, k = [], [], 0
+        for b in range(B):
+            for p in range(nq_pages[b]):
+                table[b, p] = ids[k]
+                src.append(self.dc.page_table_host[b, p])
+                dst.append(ids[k])
+                k += 1
+        self.q4_table_host = table
+        self.q4_table = torch.from_numpy(table).cuda()
+        self.q4_len = torch.tensor(list(n_quant), dtype=torch.int32).cuda()
+        if src:
+            ea.quantize_pages_q4(desc, self.dc.k_pool, self.dc.v_pool, torch.tensor(src, dtype=torch.int32).cuda(),
+                                 self.kq, self.vq, torch.tensor(dst, dtype=torch.int32).cuda())
+            torch.cuda.synchronize()
+            if poison_sources:
+                self.dc.k_pool[torch.tensor(src, dtype=torch.int64).cuda()] = float("nan")
+                self.dc.v_pool[torch.tensor(src, dtype=torch.int64).cuda()] = float("nan")
+        lens = [k_.shape[1] for k_ in K]
+        tails = [lens[b] - n_quant[b] for b in range(B)]
+        self.max_tail_pages = max(1, max(-(-t // P) for t in tails))
+        tt = np.full((B, self.max_tail_pages), -1, np.int32)
+        for b in range(B):
+            n_t = -(-tails[b] // P)
+            tt[b, :n_t] = self.dc.page_table_host[b, nq_pages[b]:nq_pages[b] + n_t]
+        self.tail_table = torch.from_numpy(tt).cuda()
+        self.tail_len = torch.tensor(tails, dtype=torch.int32).cuda()
+
+
+def offset_cache(desc, lens, g, k_std=1.0):
+    """Keys with a different mean per channel and values with a different mean per token, the shape that makes
+    the zero terms of the quantised products matter."""
+    K, V = [], []
+    for n in lens:
+        k = synth.gaussian(g, (desc.n_kv_heads, n, desc.r_k), k_std) + 2.0 * synth.gaussian(g, (desc.n_kv_heads, 1, desc.r_k))
+        v = synth.gaussian(g, (desc.n_kv_heads, n, desc.r_v)) + 1.5 * synth.gaussian(g, (desc.n_kv_heads, n, 1))
+        K.append(quantize(desc, k))
+        V.append(quantize(desc, v))
+    return K, V
+
+
+@pytest.mark.parametrize("Hkv,r_k,r_v,P,lens,n_quant", [
+    (2, 80, 80, 64, [200, 64], [128, 64]),
+    (1, 30, 33, 128, [300], [256]),            # ranks off the chunk sizes, two tiles per page
+    (2, 128, 16, 64, [64], [64]),
+    (1, 8, 128, 192, [192], [192]),
+])
+def test_quantize_pages_bit_exact(Hkv, r_k, r_v, P, lens, n_quant):
+    print(f"q4 quantize Hkv={Hkv} r=({r_k},{r_v}) P={P} lens={lens}", flush=True)
+    desc = ea.LayerDesc(Hkv * 128, Hkv, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(41, r_k, P)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    K[0][0, :64, 0] = 0.75                      # a constant group: scale 0
+    qc = Q4Cache(desc, K, V, n_quant, g, poison_sources=False)
+    lay = ea.q4_layout_query(desc)
+    assert lay.k_tile_bytes == 32 * lay.r_k_pad + 128 * ((lay.r_k_pad + 31) // 32)
+    assert lay.v_tile_bytes == 32 * lay.r_v_pad + 256
+    pos = tile_positions(desc)
+    kq = qc.kq.cpu().numpy().reshape(-1)
+    vq = qc.vq.cpu().numpy().reshape(-1)
+    for b in range(len(lens)):
+        for kvh in range(Hkv):
+            ck, sk, zk = oq.quantize_keys(K[b][kvh, :n_quant[b]])
+            cv, sv, zv = oq.quantize_values(V[b][kvh, :n_quant[b]])
+            for t0 in range(0, n_quant[b], 64):
+                page, tile = qc.q4_table_host[b, t0 // P], (t0 % P) // 64
+                gk, gs, gz, gv, gvs, gvz = read_tile(desc, lay, pos, kq, vq, page, kvh, tile)
+                where = f"b={b} kvh={kvh} tokens {t0}.."
+                assert np.array_equal(gk, ck[t0:t0 + 64]), f"key codes {where}"
+                assert np.array_equal(gs.view(np.uint16), sk[t0 // 64].view(np.uint16)), f"key scales {where}"
+                assert np.array_equal(gz.view(np.uint16), zk[t0 // 64].view(np.uint16)), f"key zeros {where}"
+                assert np.array_equal(gv, cv[t0:t0 + 64]), f"value codes {where}"
+                assert np.array_equal(gvs.view(np.uint16), sv[t0:t0 + 64].view(np.uint16)), f"value scales {where}"
+                assert np.array_equal(gvz.view(np.uint16), zv[t0:t0 + 64].view(np.uint16)), f"value zeros {where}"
+
+
+def run_q4(desc, qc, q, n_splits, with_tail=True):
+    B = q.shape[0]
+    out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = n_splits if n_splits else ea.decode_auto_splits(desc, B, qc.max_q4_pages * desc.page_tokens)
+    ws = torch.full((ea.decode_q4_workspace_bytes(desc, B, S) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    dc = qc.dc
+    if with_tail:
+        ea.decode_attn_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len,
+                          dc.k_pool, dc.v_pool, qc.tail_table, qc.tail_len, out, S, ws)
+    else:
+        ea.decode_attn_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len,
+                          None, None, None, None, out, S, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_q4(desc, K, V, q, n_quant):
+    keep = [b for b in range(len(K)) if K[b].shape[1] > 0]
+    ref = np.zeros((len(K), desc.n_heads, desc.r_v))
+    if keep:
+        ref[keep] = oq.decode_attention_quantized(q[keep], [K[b] for b in keep], [V[b] for b in keep],
+                                                  [n_quant[b] for b in keep], desc.d_head)
+    return ref
+
+
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,lens,n_quant,n_splits", [
+    (2, 2, 80, 80, 64, [200, 130, 64], [128, 128, 64], 1),      # the last sequence has no 16-bit part
+    (2, 2, 80, 80, 64, [1000, 513, 129], [960, 512, 128], 3),
+    (8, 2, 48, 112, 128, [777, 1500], [768, 1280], 0),           # GQA 4:1, r_k != r_v, two tiles per page
+    (8, 2, 112, 48, 64, [2048, 70], [1984, 64], 5),
+    (16, 1, 96, 64, 64, [330], [320], 2),                        # 16 query heads on one kv head
+    (4, 4, 128, 128, 64, [513, 100], [512, 64], 2),              # full rank
+    (4, 2, 72, 40, 64, [150, 70], [128, 64], 2),                 # ranks that need padding channels
+    (4, 2, 30, 33, 64, [150, 70], [128, 64], 1),                 # ... and are off the 8-channel chunk
+    (2, 2, 16, 16, 192, [5000], [4800], 7),
+    (2, 2, 80, 80, 64, [300, 50, 0], [0, 0, 0], 2),              # nothing quantised yet; an empty sequence
+    (2, 2, 80, 80, 64, [90, 200], [64, 192], 4),                 # more splits than tiles: empty workgroups
+    (2, 1, 64, 64, 64, [20000], [19968], 1),                     # one workgroup walks 312 tiles
+])
+def test_decode_q4_matches_oracle(H, Hkv, r_k, r_v, P, lens, n_quant, n_splits):
+    print(f"q4 decode H={H}/{Hkv} r=({r_k},{r_v}) P={P} lens={lens} quantised={n_quant} S={n_splits}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(42, H, r_k, len(lens), n_splits)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    q = np.float32(synth.gaussian(g, (len(lens), H, r_k), 1.5)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    got = run_q4(desc, qc, q, n_splits)
+    ref = oracle_q4(desc, K, V, q, n_quant)
+    err = assert_close(got, ref, TOL_BF16, "q4 decode")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+def test_decode_q4_without_a_tail_and_with_missing_pages():
+    """No 16-bit part passed at all; and 4-bit page-table entries outside the pool make their tokens vanish
+    instead of being read."""
+    desc = ea.LayerDesc(512, 4, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(43)
+    lens = [256, 320]
+    K, V = offset_cache(desc, lens, g)
+    q = np.float32(synth.gaussian(g, (2, 4, 80))).astype(np.float64)
+    qc = Q4Cache(desc, K, V, lens, g)
+    got = run_q4(desc, qc, q, 2, with_tail=False)
+    assert_close(got, oracle_q4(desc, K, V, q, lens), TOL_BF16, "q4 no tail")
+    table = qc.q4_table.clone()
+    table[0, 1] = qc.q4_pool_pages + 7        # tokens 64..127 of sequence 0 vanish
+    table[1, 3] = -2                          # tokens 192..255 of sequence 1 vanish
+    qc.q4_table = table
+    got = run_q4(desc, qc, q, 1, with_tail=False)
+    keep = [np.r_[0:64, 128:256], np.r_[0:192, 256:320]]
+    ref = np.zeros_like(got, dtype=np.float64)
+    from oracle import eigen_attention as ora
+    for b in range(2):
+        Kq, Vq = oq.quantized_view(K[b], V[b], lens[b])
+        cache = ora.RankCache.from_arrays([Kq[:, keep[b]]], [Vq[:, keep[b]]])
+        ref[b] = ora.decode_attention(q[b:b + 1], cache, 128)[0]
+    assert_close(got, ref, TOL_BF16, "q4 missing pages")
+
+
+def test_quantisation_is_what_is_measured():
+    """The result follows the oracle's quantised attention, not the unquantised one (the two differ by far more
+    than the tolerance on these inputs), so the parity above is not blind to the quantiser."""
+    desc = ea.LayerDesc(256, 2, 2, 128, 80, 80, ea.EA_BF16, 64)
+    g = synth.rng(44)
+    lens = [640]
+    K, V = offset_cache(desc, lens, g, k_std=2.0)
+    q = np.float32(synth.gaussian(g, (1, 2, 80), 2.0)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, lens, g)
+    got = run_q4(desc, qc, q, 2)
+    from oracle import eigen_attention as ora
+    plain = ora.decode_attention(q, ora.RankCache.from_arrays(K, V), 128)
+    ref = oracle_q4(desc, K, V, q, lens)
+    assert ora.rel_l2(plain, ref) > 5 * TOL_BF16
+    assert_close(got, ref, TOL_BF16, "q4 vs quantised oracle")

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 23
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 31
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -227,3 +227,99 @@ def test_projection_and_prefill_reject_bad_arguments_before_launching():
     assert h(ctypes.byref(d), OK_PTR, ea.EA_F32, OK_PTR, None, 4, None) == -1
     assert h(ctypes.byref(desc(H=3, Hkv=3, r_v=40)), OK_PTR, ea.EA_F32, OK_PTR, OK_PTR, 4, None) == -2   # (H r_v) % 32
     assert ea.strerror(-4).startswith("workspace") and ea.strerror(-2) == "unsupported shape"
+
+
+# ---------------------------------------------------------------------------
+# 4-bit group-quantised cache: layout reference functions and argument checks
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("P,r_k,r_v,Hkv", [(64, 80, 80, 2), (128, 30, 33, 1), (192, 128, 16, 3), (64, 8, 128, 1)])
+def test_q4_positions_tile_the_page_exactly(P, r_k, r_v, Hkv):
+    """Every code has its own nibble, every scale and zero its own two bytes, nothing overlaps, and all of it
+    lies inside the page; the sizes are the documented ones."""
+    d = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
+    lay = ea.q4_layout_query(d)
+    assert lay.r_k_pad == -(-r_k // 8) * 8 and lay.r_v_pad == -(-r_v // 16) * 16
+    assert lay.k_tile_bytes == 32 * lay.r_k_pad + 128 * (-(-lay.r_k_pad // 32))
+    assert lay.v_tile_bytes == 32 * lay.r_v_pad + 256
+    assert lay.k_page_bytes == Hkv * (P // 64) * lay.k_tile_bytes
+    assert lay.v_page_bytes == Hkv * (P // 64) * lay.v_tile_bytes
+    page = 2
+    used_k = np.zeros(lay.k_page_bytes * 2, np.int32)          # per nibble
+    used_v = np.zeros(lay.v_page_bytes * 2, np.int32)
+    for h in range(Hkv):
+        for t in range(P):
+            for c in range(r_k):
+                pos = ea.q4_k_code_pos(d, page, h, t, c)
+                assert pos % 4 == 0
+                used_k[pos // 4 - page * lay.k_page_bytes * 2] += 1
+            for c in range(r_v):
+                pos = ea.q4_v_code_pos(d, page, h, t, c)
+                assert pos % 4 == 0
+                used_v[pos // 4 - page * lay.v_page_bytes * 2] += 1
+            sp = ea.q4_v_scale_pos(d, page, h, t) - page * lay.v_page_bytes
+            for off in (sp, sp + 128):                          # scale, zero
+                used_v[2 * off:2 * off + 4] += 1
+        for tile in range(P // 64):
+            for c in range(r_k):
+                sp = ea.q4_k_scale_pos(d, page, h, tile * 64 + 5, c) - page * lay.k_page_bytes
+                assert sp == ea.q4_k_scale_pos(d, page, h, tile * 64, c) - page * lay.k_page_bytes
+                for off in (sp, sp + 16):
+                    used_k[2 * off:2 * off + 4] += 1
+    assert used_k.max() == 1 and used_v.max() == 1
+    # what is left over are the padding channels only
+    assert used_k.sum() == Hkv * P * r_k + Hkv * (P // 64) * r_k * 8
+    assert used_v.sum() == Hkv * P * r_v + Hkv * P * 8
+    assert ea.q4_k_code_pos(d, 0, Hkv, 0, 0) == -1 and ea.q4_k_code_pos(d, 0, 0, P, 0) == -1
+    assert ea.q4_v_code_pos(d, 0, 0, 0, r_v) == -1 and ea.q4_v_scale_pos(d, -1, 0, 0) == -1
+    assert ea.q4_k_scale_pos(d, 0, 0, 0, r_k) == -1
+
+
+def test_q4_code_order_matches_its_description():
+    """Keys: the dword of (token 16*tb + t, channels 32*kk + 8*quad ..) is dword tb of the 16-byte unit of lane
+    16*quad + t in the run of k-step kk; element e of the eight sits in nibble e/2 (even) or 4 + e/2 (odd)."""
+    d = desc(Hkv=1, H=1, r_k=80, r_v=80, P=64)
+    for (t, c) in [(0, 0), (17, 9), (63, 79), (35, 44)]:
+        tb, tt, kk, quad, e = t // 16, t % 16, c // 32, (c // 8) % 4, c % 8
+        byte = kk * 1024 + (quad * 16 + tt) * 16 + tb * 4
+        nib = e // 2 if e % 2 == 0 else 4 + e // 2
+        assert ea.q4_k_code_pos(d, 0, 0, t, c) == byte * 8 + 4 * nib
+        assert ea.q4_k_scale_pos(d, 0, 0, t, c) == 10 * 256 + (kk * 4 + quad) * 32 + 2 * e
+    # values: dword (cb, u) of lane 16*quad + ch, token slot j <-> token 32*u + 16*(j/4) + 4*quad + j%4; the odd
+    # last channel block (cb = 4 of 5) has 8-byte units
+    for (t, c) in [(0, 0), (21, 37), (63, 79), (40, 64)]:
+        u, t32 = t // 32, t % 32
+        half, quad, j = t32 // 16, (t32 % 16) // 4, (t32 // 16) * 4 + t32 % 4
+        cb, ch = c // 16, c % 16
+        lane = quad * 16 + ch
+        byte = (cb // 2) * 1024 + (lane * 8 + u * 4 if cb == 4 else lane * 16 + ((cb % 2) * 2 + u) * 4)
+        nib = j // 2 if j % 2 == 0 else 4 + j // 2
+        assert ea.q4_v_code_pos(d, 0, 0, t, c) == byte * 8 + 4 * nib
+        assert ea.q4_v_scale_pos(d, 0, 0, t) == 5 * 512 + ((u * 4 + quad) * 8 + j) * 2
+
+
+def test_q4_entry_points_reject_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def quant(dd=d, k=OK_PTR, kq=OK_PTR, src=OK_PTR, n=3, pool=8, qpool=8):
+        return lib.ea_quantize_pages_q4(ctypes.byref(dd), k, OK_PTR, src, kq, OK_PTR, OK_PTR, n, pool, qpool, None)
+
+    assert quant(src=None) == -1 and quant(n=-1) == -1 and quant(qpool=0) == -1
+    assert quant(kq=ODD_PTR) == -3
+    assert quant(dd=desc(dtype=ea.EA_F32, P=64)) == -2                     # bf16 layers only
+    assert quant(n=0) == 0                                                 # nothing to do, nothing launched
+
+    def dec(dd=d, q=OK_PTR, kq=OK_PTR, tail_pt=OK_PTR, tail_len=OK_PTR, k=OK_PTR, max_tail=2, pool=8, n_splits=2,
+            ws=OK_PTR, ws_bytes=1 << 30, max_q=4):
+        return lib.ea_decode_attn_q4(ctypes.byref(dd), q, kq, OK_PTR, OK_PTR, OK_PTR, max_q, 8, k, OK_PTR, tail_pt,
+                                     tail_len, max_tail, pool, OK_PTR, 2, n_splits, ws, ws_bytes, None)
+
+    assert dec(q=None) == -1 and dec(max_q=0) == -1 and dec(n_splits=1025) == -1
+    assert dec(tail_len=None) == -1                                        # half a tail
+    assert dec(k=None) == -1 and dec(max_tail=0) == -1
+    assert dec(kq=ODD_PTR) == -3 and dec(k=ODD_PTR) == -3
+    assert dec(ws=None) == -4                                              # the workspace is always needed
+    need = ea.decode_q4_workspace_bytes(d, 2, 2)
+    assert need == 2 * 8 * 3 * (2 + 48) * 4                                # n_splits + 1 slots
+    assert dec(ws_bytes=need - 1) == -4
+    assert dec(dd=desc(dtype=ea.EA_F32, P=64)) == -2
+    assert ea.decode_q4_workspace_bytes(d, 0, 2) == -1
