@@ -47,7 +47,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
+                             "cfg5-q4"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -129,6 +130,40 @@ def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: boo
             "seconds": round(dt, 3)}
 
 
+def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_tokens: int):
+    """The oracle of the quantised-cache step on `n_streams` (sequence, head) streams: codes and scales are
+    prepared outside the timed region (they are the cache's content); timed is what a generation step does with
+    them, dequantisation of the 4-bit part and fp64 attention over it and the 16-bit newest page."""
+    import numpy as np
+    from oracle import eigen_attention as ora
+    from oracle import quant_cache as oq
+    from paper_2408_05646_amd import synth
+    g = synth.rng(3, 778)
+    heads = 32
+    n_seq = max(1, n_streams // heads)
+    nq = n_ctx - page_tokens
+    K1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
+    V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
+    kq = [oq.quantize_keys(K1[h, :nq]) for h in range(heads)]
+    vq = [oq.quantize_values(V1[h, :nq]) for h in range(heads)]
+    q = g.standard_normal((n_seq, heads, r))
+
+    def work():
+        Kd = np.stack([np.concatenate([oq.dequantize_keys(*kq[h]), K1[h, nq:]]) for h in range(heads)])
+        Vd = np.stack([np.concatenate([oq.dequantize_values(*vq[h]), V1[h, nq:]]) for h in range(heads)])
+        ora.decode_attention(q, ora.RankCache.from_arrays([Kd] * n_seq, [Vd] * n_seq), d_head)
+
+    dt = _timed_single_thread(work)
+    tiles = nq // 64
+    cache_bytes = n_seq * heads * (tiles * (2 * 32 * ((r + 15) // 16 * 16) + 128 * ((r + 31) // 32) + 256)
+                                   + page_tokens * 2 * r * 2)      # what the GPU kernels would stream
+    return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"dequantisation and decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
+                      f"streams (n={n_ctx}, r={r}, all but the last {page_tokens} tokens in 4 bits), fp64 numpy, "
+                      f"{dt:.2f} s per pass, timed three times (best kept)",
+            "seconds": round(dt, 3)}
+
+
 def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
     """The fp64 oracle's causal attention for the last `n_rows` query rows of one (sequence, head)."""
     from oracle import eigen_attention as ora
@@ -149,6 +184,7 @@ def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
 def bench_decode(args, torch, ea, synth):
     dev = "cuda"
     base_name, rope = args.workload.split("-")[0], args.workload.endswith("-rope")
+    q4 = args.workload.endswith("-q4")       # all pages but the newest of every sequence held in 4 bits
     s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[base_name]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
     H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
@@ -158,8 +194,12 @@ def bench_decode(args, torch, ea, synth):
     pool_pages = B * max_pages
 
     free, _total = torch.cuda.mem_get_info()
-    need = sum(pool_pages * (ea.cache_layout_query(dc).k_page_elems + ea.cache_layout_query(dc).v_page_elems) * 2
-               for dc in descs)
+    if q4:
+        need = sum(pool_pages * (ea.q4_layout_query(dc).k_page_bytes + ea.q4_layout_query(dc).v_page_bytes)
+                   for dc in descs)
+    else:
+        need = sum(pool_pages * (ea.cache_layout_query(dc).k_page_elems + ea.cache_layout_query(dc).v_page_elems) * 2
+                   for dc in descs)
     if need + (12 << 30) > free:
         print(f"bench.py: {L} layers need {need / 2**30:.0f} GiB of HBM, only {free / 2**30:.0f} GiB free",
               file=sys.stderr)
@@ -174,11 +214,35 @@ def bench_decode(args, torch, ea, synth):
     for dc in descs:
         q_dim = s.d_head if rope else dc.r_k          # the rotary variant keeps the query at full rank (Sec. 4.3)
         n_qkv = H * q_dim + Hkv * (dc.r_k + dc.r_v)
-        k_pool, v_pool = ea.alloc_pools(dc, pool_pages, zero=False)
+        extra = {}
+        if q4:
+            # The first n - P tokens of every sequence are in the 4-bit pools: uniformly random codes, and scales /
+            # zeros as unit-variance groups have them (range of 64 samples ~ 4.7 sigma -> step ~ 0.31, zero ~ -2.3).
+            # The newest page (P tokens once the step's token is appended) is in the bfloat16 pools.
+            lay = ea.q4_layout_query(dc)
+            tpp = P // 64
+            kq_pool, vq_pool = ea.alloc_q4_pools(dc, pool_pages, zero=False)
+            for pool, tile_bytes, code_bytes in ((kq_pool, lay.k_tile_bytes, 32 * lay.r_k_pad),
+                                                 (vq_pool, lay.v_tile_bytes, 32 * lay.r_v_pad)):
+                pool.random_(0, 256, generator=gen)
+                tiles = pool.view(pool_pages, Hkv * tpp, tile_bytes)
+                half = (tile_bytes - code_bytes) // 4          # fp16 scales, then as many zeros, per 16 / 128 bytes
+                sz = torch.empty((pool_pages, Hkv * tpp, 2 * half), dtype=torch.float16, device=dev)
+                grp = 8 if pool is kq_pool else 64              # run length of scales before their zeros
+                szv = sz.view(pool_pages, Hkv * tpp, -1, 2, grp)
+                szv[:, :, :, 0].uniform_(0.28, 0.34, generator=gen)
+                szv[:, :, :, 1].normal_(-2.3, 0.3, generator=gen)
+                tiles[:, :, code_bytes:] = sz.view(torch.uint8)
+            k_pool, v_pool = ea.alloc_pools(dc, B, zero=False)
+            extra = dict(kq_pool=kq_pool, vq_pool=vq_pool,
+                         tail_table=torch.arange(B, dtype=torch.int32, device=dev).reshape(B, 1).contiguous())
+        else:
+            k_pool, v_pool = ea.alloc_pools(dc, pool_pages, zero=False)
         k_pool.normal_(0.0, 1.00125, generator=gen)
         v_pool.normal_(0.0, 1.00125, generator=gen)
         perm = torch.randperm(pool_pages, generator=gen, device=dev).to(torch.int32)   # pages in seeded random order
         layers.append(dict(
+            **extra,
             desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
             S=args.n_splits or (ea.decode_rope_auto_splits(dc, B, n) if rope else ea.decode_auto_splits(dc, B, n)),
             wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
@@ -195,16 +259,27 @@ def bench_decode(args, torch, ea, synth):
 
     seq_before = torch.full((B,), n - 1, dtype=torch.int32, device=dev)    # the step appends token n-1 ...
     seq_after = torch.full((B,), n, dtype=torch.int32, device=dev)         # ... and attends over n tokens
-    ws_bytes = max(ea.decode_workspace_bytes(l["desc"], B, l["S"]) for l in layers)
+    ws_bytes = max((ea.decode_q4_workspace_bytes if q4 else ea.decode_workspace_bytes)(l["desc"], B, l["S"])
+                   for l in layers)
+    q4_len = torch.full((B,), n - P, dtype=torch.int32, device=dev)
+    tail_before = torch.full((B,), P - 1, dtype=torch.int32, device=dev)
+    tail_after = torch.full((B,), P, dtype=torch.int32, device=dev)
     ws = torch.empty(max(ws_bytes // 4, 4), dtype=torch.float32, device=dev)
 
     def step(events=None):
         for li, l in enumerate(layers):
-            (ea.project_qkv_rope if rope else ea.project_qkv)(
-                l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_before, 1)
+            if q4:
+                ea.project_qkv(l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["tail_table"],
+                               tail_before, 1)
+            else:
+                (ea.project_qkv_rope if rope else ea.project_qkv)(
+                    l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_before, 1)
             if events is not None:
                 events[li][0].record()
-            if rope:
+            if q4:
+                ea.decode_attn_q4(l["desc"], l["q_r"], l["kq_pool"], l["vq_pool"], l["page_table"], q4_len,
+                                  l["k_pool"], l["v_pool"], l["tail_table"], tail_after, l["o"], l["S"], ws)
+            elif rope:
                 ea.decode_attn_rope(l["desc"], l["q_r"], l["u_k"], ROPE_BASE, l["k_pool"], l["v_pool"], l["page_table"],
                                     seq_after, l["o"], n_splits=l["S"], ws=ws)
             else:
@@ -259,7 +334,12 @@ def bench_decode(args, torch, ea, synth):
     for dc in descs:
         q_dim = s.d_head if rope else dc.r_k
         n_qkv = H * q_dim + Hkv * (dc.r_k + dc.r_v)
-        cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
+        if q4:
+            lay = ea.q4_layout_query(dc)
+            cache_bytes = B * Hkv * ((n - P) // 64) * (lay.k_tile_bytes + lay.v_tile_bytes) + \
+                B * Hkv * P * (dc.r_k + dc.r_v) * 2
+        else:
+            cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
         attn = cache_bytes + B * H * q_dim * 4 + B * H * dc.r_v * 4 + B * max_pages * 4 + \
             (s.d_head * dc.r_k * 2 if rope else 0)
         proj = n_qkv * d * 2 + B * d * 2 + B * H * q_dim * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
@@ -273,6 +353,8 @@ def bench_decode(args, torch, ea, synth):
     kern = "decode_bf16_kernel" + (" (rotary variant)" if rope else "") + \
         ("" if splits == [1] else " + merge_splits_kernel") + \
         (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
+    if q4:
+        kern = "decode_q4_kernel + decode_bf16_kernel (newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
 
     rank_note = f"r_k=r_v={s.r_k}" if base_name != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
@@ -282,9 +364,13 @@ def bench_decode(args, torch, ea, synth):
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload} decode: Llama-2-7B-shaped, {L} layers resident, B={B}, n={n}, "
-                               f"H={H}, H_kv={Hkv}, d_h={s.d_head}, {rank_note}, bf16 paged cache (page {P} tokens, "
-                               f"pages in random order), "
-                               + ("rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope + out_proj "
+                               f"H={H}, H_kv={Hkv}, d_h={s.d_head}, {rank_note}, "
+                               + ("cache in 4-bit groups (keys per channel over 64 tokens, values per token; fp16 "
+                                  "scales and zeros) except the newest page of each sequence, which is bf16; "
+                                  if q4 else "bf16 ") +
+                               f"paged cache (page {P} tokens, pages in random order), "
+                               + ("project_qkv + decode_attn_q4 + out_proj per layer" if q4 else
+                                  "rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope + out_proj "
                                   "per layer, query at position n-1, base 10000" if rope else
                                   "project_qkv + decode_attn + out_proj per layer"),
                    "layers": L, "batch": B, "n_ctx": n, "page_tokens": P, "n_splits": splits},
@@ -344,7 +430,9 @@ def bench_decode(args, torch, ea, synth):
         torch.cuda.synchronize()
         result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
-    if not args.no_cpu:
+    if not args.no_cpu and q4:
+        result["cpu_baseline"] = cpu_oracle_decode_q4(args.cpu_streams // 8, n, ranks[0][0], s.d_head, P)
+    elif not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 1), n, ranks[0][0], s.d_head,
                                                    rope=rope)
     return result

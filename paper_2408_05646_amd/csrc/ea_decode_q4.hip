@@ -1,14 +1,14 @@
 // Generation-phase attention over the 4-bit group-quantised part of the rank-r cache (keys: scale and zero per
 // channel and 64-token tile; values: per token).  The codes never become 16-bit values in memory:
 //   scores   s[t,h] = sum_c (scale_c code[t,c] + zero_c) q[h,c]
-//                   = sum_c (64 + code[t,c]) (scale_c q[h,c]) + sum_c zero_c q[h,c] - 64 sum_c scale_c q[h,c]:
-//            the scales go into the query once per tile, the nibbles become the fp16 numbers 64 + code with one
-//            mask-and-or (0x5400 is 64.0 and its mantissa bits 4-7 count units), and the two constant terms
-//            are two more matrix-core products whose result starts the score accumulators;
+//                   = sum_c (off_c + code[t,c]) (scale_c q[h,c]) + sum_c zero_c q[h,c] - sum_c off_c scale_c q[h,c]:
+//            the scales go into the query once per tile, the nibbles become fp16 numbers "offset + code" with
+//            one mask-and-or each (see unpack_q4), and the two constant terms are two more matrix-core products
+//            whose result starts the score accumulators;
 //   output   o[h,c] = sum_t p[h,t] (scale_t code[t,c] + zero_t)
-//                   = sum_t (p scale)[h,t] (64 + code[t,c]) + sum_t p[h,t] zero_t - 64 sum_t (p scale)[h,t]:
-//            the scales go into the probabilities, the constant terms ride in the product that also makes the
-//            softmax denominators.
+//                   = sum_t (p scale)[h,t] (off_t + code[t,c]) + sum_t p[h,t] zero_t - sum_t off_t (p scale)[h,t]:
+//            the scales go into the probabilities, the constant terms are matrix-core products again, beside
+//            the one that makes the softmax denominators.
 // The kernel always writes split partials (m, l, acc); the 16-bit tail of the sequences is attended by the
 // bfloat16 kernel into further slots of the same workspace and one merge finishes.
 #include "ea_q4.h"
@@ -35,7 +35,6 @@ template <int NCB>
 struct MergeSmemQ4 {
   float m[4][16];
   float l[4][16];
-  float bias[4][16];
   float acc[4][16][NCB * 16];
 };
 
@@ -43,14 +42,19 @@ __device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
-// Eight nibbles -> the eight fp16 numbers 64 + code; element 2i is nibble i, element 2i+1 nibble i+4.
-__device__ __forceinline__ f16x8 unpack_q4(uint32_t w) {
-  constexpr uint32_t mask = 0x00f000f0u, magic = 0x54005400u;
+// Eight nibbles -> eight fp16 numbers offset + code; element 2i is nibble i, element 2i+1 nibble i+4.
+// A nibble in bits 0-3 of a half word, under the exponent of 1024.0 (0x6400, one unit per mantissa step), reads
+// 1024 + code; one in bits 4-7 under the exponent of 64.0 (0x5400, sixteen steps per unit) reads 64 + code.  So
+// the nibbles 0,1 (and 4,5) of the dword need no shift at all and the other four share one: elements 0,1,4,5
+// carry the offset 1024, elements 2,3,6,7 the offset 64.  The two magic words come in registers (a mask-and-or
+// takes one of its two constants from a vector register).
+__device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint32_t magic64) {
+  const uint32_t w8 = w >> 8;
   u32x4 r;
-  r[0] = ((w << 4) & mask) | magic;
-  r[1] = (w & mask) | magic;
-  r[2] = ((w >> 4) & mask) | magic;
-  r[3] = ((w >> 8) & mask) | magic;
+  r[0] = (w & 0x000f000fu) | magic1024;
+  r[1] = (w & 0x00f000f0u) | magic64;
+  r[2] = (w8 & 0x000f000fu) | magic1024;
+  r[3] = (w8 & 0x00f000f0u) | magic64;
   return __builtin_bit_cast(f16x8, r);
 }
 
@@ -95,18 +99,21 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
       }
     }
   }
-  f16x8 neg64, ones;
+  // minus the offsets the unpacked codes carry, and ones
+  f16x8 negoff, ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    neg64[j] = (_Float16)-64.0f;
+    negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;
     ones[j] = (_Float16)1.0f;
   }
+  uint32_t magic1024 = 0x64006400u, magic64 = 0x54005400u;
+  asm volatile("" : "+v"(magic1024), "+v"(magic64));   // keep them in vector registers
 
   f32x4 acc[NCB];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  f32x4 stat = {0.f, 0.f, 0.f, 0.f};   // row 0: sum_t p; row 1: sum_t p zero_t   (lanes of quad 0, registers 0 and 1)
-  f32x4 corr = {0.f, 0.f, 0.f, 0.f};   // every row: -64 sum_t p scale_t
+  f32x4 lacc = {0.f, 0.f, 0.f, 0.f};   // every row: sum_t p
+  f32x4 corr = {0.f, 0.f, 0.f, 0.f};   // every row: sum_t p zero_t - sum_t offset (p scale)_t
   float m = -INFINITY;
 
   u32x4 kc[KS];
@@ -181,67 +188,74 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   const f16x8 zero8 = __builtin_bit_cast(f16x8, u32x4{0u, 0u, 0u, 0u});
 
   while (have) {
-    // ---- scores (log2 units): lane (col, quad) gets tokens 16*tb + 4*quad + i of head col
+    // ---- scores (log2 units) relative to the reference exponent: lane (col, quad) gets tokens
+    //      16*tb + 4*quad + i of head col
     f16x8 qs[KS];
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) qs[kk] = q16[kk] * ksc[kk];
-    f32x4 sb = {0.f, 0.f, 0.f, 0.f};
+    const float m_base = m == -INFINITY ? 0.f : m;
+    f32x4 sb = {-m_base, -m_base, -m_base, -m_base};
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       sb = mfma16h(kzr[kk], q16[kk], sb);      // every row: sum_c zero_c q_c
-      sb = mfma16h(neg64, qs[kk], sb);         // every row: -64 sum_c scale_c q_c
+      sb = mfma16h(negoff, qs[kk], sb);        // every row: - sum_c offset_c scale_c q_c
     }
     f32x4 s[4];
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
       s[tb] = sb;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(unpack_q4(kc[kk][tb]), qs[kk], s[tb]);
+      for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(unpack_q4(kc[kk][tb], magic1024, magic64), qs[kk], s[tb]);
     }
     if (have_n) load_k(nxt, max(page_n, 0));
 
-    // ---- online softmax
+    if (page < 0) {
+      // a page that is not there: its tokens do not take part, and the scales read from page 0 are dropped
+      asm volatile("");
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) s[tb] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll
+      for (int u = 0; u < 2; ++u) vsc[u] = vzr[u] = zero8;
+    }
+    // ---- online softmax; m moves only when the maximum has grown by more than 2^kLazy
     float mx = -INFINITY;
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (page < 0) s[tb][i] = -INFINITY;
-        mx = fmaxf(mx, s[tb][i]);
-      }
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[tb][i]);
     }
     mx = quad_column_max(mx);
-    if (__any(mx > m + kLazy)) {
-      const float m_new = fmaxf(m, mx);
+    if (__any(m == -INFINITY ? mx > -INFINITY : mx > kLazy)) {
+      const float m_new = fmaxf(m, mx + m_base);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
-      stat *= alpha;
+      const float delta = m_safe - m_base;
+      lacc *= alpha;
       corr *= alpha;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb) s[tb] -= delta;
       m = m_new;
     }
-    const float m_use = m == -INFINITY ? 0.f : m;
     f16x8 pf[2], ps[2];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (_Float16)__builtin_amdgcn_exp2f(s[2 * u + h][i] - m_use);
+        for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (_Float16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
       }
-      // scales and zeros of a page that is not there are whatever page 0 holds: drop them
-      const f16x8 sc_u = page < 0 ? zero8 : vsc[u];
-      const f16x8 zr_u = page < 0 ? zero8 : vzr[u];
-      ps[u] = pf[u] * sc_u;
-      stat = mfma16h(col == 0 ? ones : zr_u, pf[u], stat);
-      corr = mfma16h(neg64, ps[u], corr);
+      ps[u] = pf[u] * vsc[u];
+      lacc = mfma16h(ones, pf[u], lacc);
+      corr = mfma16h(vzr[u], pf[u], corr);
+      corr = mfma16h(negoff, ps[u], corr);
     }
-    // ---- O^T += (64 + codes)^T . (p scale)^T
+    // ---- O^T += (offset + codes)^T . (p scale)^T
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(unpack_q4(v_dword(cb, u)), ps[u], acc[cb]);
+      for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(unpack_q4(v_dword(cb, u), magic1024, magic64), ps[u], acc[cb]);
     }
     if (have_n) load_v(nxt, max(page_n, 0));
     cur = nxt;
@@ -255,8 +269,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   // ---- merge the four waves, fold the constant terms in, write the split's partial
   if (quad == 0) {
     sm.m[wave][col] = m;
-    sm.l[wave][col] = stat[0];
-    sm.bias[wave][col] = stat[1];
+    sm.l[wave][col] = lacc[0];
   }
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
@@ -276,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
       for (int w = 0; w < 4; ++w) {
         const float wt = __builtin_amdgcn_exp2f(sm.m[w][hd] - mm);
         lsum += wt * sm.l[w][hd];
-        val += wt * (sm.acc[w][hd][c] + sm.bias[w][hd]);
+        val += wt * sm.acc[w][hd][c];
       }
     }
     const int head = kvh * G + hd;

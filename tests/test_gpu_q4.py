@@ -229,3 +229,75 @@ def test_quantisation_is_what_is_measured():
     ref = oracle_q4(desc, K, V, q, lens)
     assert ora.rel_l2(plain, ref) > 5 * TOL_BF16
     assert_close(got, ref, TOL_BF16, "q4 vs quantised oracle")
+
+
+def test_cfg3_q4_one_layer_sampled():
+    """B=16, n=32768, H=32, r=80, one of the 32 resident layers, in the launch configuration bench.py times
+    (--workload cfg3-q4): all pages but the newest of every sequence in the 4-bit pools (random codes, scales and
+    zeros as unit-variance groups have them), the newest page bfloat16; sampled (sequence, head) streams are read
+    back, decoded on the host from the documented positions and attended by the fp64 oracle."""
+    from oracle import eigen_attention as ora
+    s = synth.CFG3
+    P, B, n, H = 64, s.batch, s.n_ctx, s.n_heads
+    desc = ea.LayerDesc(s.d_model, H, s.n_kv_heads, s.d_head, s.r_k, s.r_v, ea.EA_BF16, P)
+    lay = ea.q4_layout_query(desc)
+    pages = n // P
+    pool_pages = B * pages
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 34)
+    kq, vq = ea.alloc_q4_pools(desc, pool_pages, zero=False)
+    for pool, tile_bytes, code_bytes, grp in ((kq, lay.k_tile_bytes, 32 * lay.r_k_pad, 8),
+                                              (vq, lay.v_tile_bytes, 32 * lay.r_v_pad, 64)):
+        pool.random_(0, 256, generator=gen)
+        tiles = pool.view(pool_pages, H, tile_bytes)
+        sz = torch.empty((pool_pages, H, (tile_bytes - code_bytes) // 2), dtype=torch.float16, device="cuda")
+        szv = sz.view(pool_pages, H, -1, 2, grp)
+        szv[:, :, :, 0].uniform_(0.28, 0.34, generator=gen)
+        szv[:, :, :, 1].normal_(-2.3, 0.3, generator=gen)
+        tiles[:, :, code_bytes:] = sz.view(torch.uint8)
+    table = torch.randperm(pool_pages, generator=gen, device="cuda").to(torch.int32).reshape(B, pages).contiguous()
+    q4_len = torch.full((B,), n - P, dtype=torch.int32, device="cuda")
+    k_pool, v_pool = ea.alloc_pools(desc, B, zero=False)
+    k_pool.normal_(generator=gen)
+    v_pool.normal_(generator=gen)
+    tail_table = torch.arange(B, dtype=torch.int32, device="cuda").reshape(B, 1).contiguous()
+    tail_len = torch.full((B,), P, dtype=torch.int32, device="cuda")
+    q = torch.randn((B, H, s.r_k), generator=gen, device="cuda")
+    out = torch.full((B, H, s.r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = ea.decode_auto_splits(desc, B, n)
+    assert S == 1
+    ws = torch.empty(ea.decode_q4_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    ea.decode_attn_q4(desc, q, kq, vq, table, q4_len, k_pool, v_pool, tail_table, tail_len, out, S, ws)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+
+    pos = tile_positions(desc)
+    kc, vc, ks, vs = pos
+    table_h = table.cpu().numpy()
+    g = synth.rng(3, 2)
+    samples = [(0, 0), (15, 31)] + [(int(g.integers(B)), int(g.integers(H))) for _ in range(6)]
+    print("cfg3-q4 samples", samples, flush=True)
+    for (b, h) in samples:
+        ids = torch.from_numpy(table_h[b, :pages - 1].astype(np.int64)).cuda()
+        kt = kq.view(pool_pages, H, lay.k_tile_bytes)[ids, h].cpu().numpy()          # [pages-1, tile bytes]
+        vt = vq.view(pool_pages, H, lay.v_tile_bytes)[ids, h].cpu().numpy()
+        k_codes = ((kt[:, kc >> 3] >> (kc & 7).astype(np.uint8)) & 15).astype(np.float64)      # [pages-1, 64, r_k]
+        v_codes = ((vt[:, vc >> 3] >> (vc & 7).astype(np.uint8)) & 15).astype(np.float64)
+
+        def f16_at(buf, off):
+            return (buf[:, off].astype(np.uint16) | (buf[:, off + 1].astype(np.uint16) << 8)).view(np.float16) \
+                .astype(np.float64)
+        Kd = k_codes * f16_at(kt, ks)[:, None, :] + f16_at(kt, ks + 16)[:, None, :]
+        Vd = v_codes * f16_at(vt, vs)[:, :, None] + f16_at(vt, vs + 128)[:, :, None]
+        # the bf16 page of this sequence, via the layout's reference index
+        kp = k_pool[b].float().cpu().numpy()
+        vp = v_pool[b].float().cpu().numpy()
+        k_idx = np.array([[ea.cache_k_index(desc, 0, h, t, c) for c in range(s.r_k)] for t in range(P)])
+        v_idx = np.array([[ea.cache_v_index(desc, 0, h, t, c) for c in range(s.r_v)] for t in range(P)])
+        K = np.concatenate([Kd.reshape(-1, s.r_k), kp[k_idx].astype(np.float64)])
+        V = np.concatenate([Vd.reshape(-1, s.r_v), vp[v_idx].astype(np.float64)])
+        assert K.shape == (n, s.r_k)
+        ref = ora.decode_attention(q[b:b + 1, h:h + 1].double().cpu().numpy(),
+                                   ora.RankCache.from_arrays([K[None]], [V[None]]), s.d_head)
+        assert_close(got[b:b + 1, h:h + 1], ref, TOL_BF16, f"cfg3-q4 stream b={b} h={h}")
