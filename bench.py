@@ -11,6 +11,9 @@ QKV projection + cache append, decode attention over the 32768 cached tokens, ou
 Other workloads (same step, other shapes): `cfg2` (n = 4096), `cfg5` (grouped-query attention, 32 query
 heads on 8 kv heads, B = 8, n = 16384, per-layer ranks drawn from {48,...,112}); `cfg4` is the causal
 prefill of B = 4 sequences of 8192 tokens at r = 64 (project_qkv + prefill_attn + out_proj of one layer).
+`cfgN-rope` is the variant for models with rotary positions (Sec. 4.3); `cfgN-q4` keeps all pages but the newest
+of every sequence in the 4-bit group-quantised form the paper combines the method with (quantisation paragraph
+of the results) and attends with ea_decode_attn_q4.
 
 Prints ONE JSON line.  `value` is the algorithmic HBM traffic of the whole step divided by its duration
 (decode workloads) or the step's TFLOP/s (prefill); `roofline` is for the dominant kernel, timed live
@@ -64,7 +67,8 @@ def parse_args():
 
 def traffic_from_profiles(workload: str):
     """HBM bytes per decode-attention launch measured with rocprofv3 --pmc (committed summary), or None."""
-    name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt"}.get(workload)
+    name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
+            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt"}.get(workload)
     if name is None:
         return None
     path = os.path.join(ROOT, "profiles", name)
