@@ -301,3 +301,48 @@ def test_cfg3_q4_one_layer_sampled():
         ref = ora.decode_attention(q[b:b + 1, h:h + 1].double().cpu().numpy(),
                                    ora.RankCache.from_arrays([K[None]], [V[None]]), s.d_head)
         assert_close(got[b:b + 1, h:h + 1], ref, TOL_BF16, f"cfg3-q4 stream b={b} h={h}")
+
+
+def test_q4_decode_step_is_graph_capturable():
+    """project_qkv (appending to the bfloat16 page) -> ea_decode_attn_q4 (three launches) -> out_proj captured in
+    a HIP graph; every replay, with eager work in between, reproduces the eager result bit for bit."""
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(45)
+    B, n_q, S = 4, 640, 3
+    K, V = offset_cache(desc, [n_q + 20] * B, g)
+    qc = Q4Cache(desc, K, V, [n_q] * B, g)
+    n_qkv = 8 * 80 + 2 * (80 + 48)
+    wqkv = ea.pack_weight((torch.from_numpy(synth.gaussian(g, (n_qkv, 512), 512 ** -0.5)).float()).to(torch.bfloat16).cuda())
+    wo = ea.pack_weight((torch.from_numpy(synth.gaussian(g, (512, 8 * 48), 512 ** -0.5)).float()).to(torch.bfloat16).cuda())
+    x = torch.from_numpy(synth.gaussian(g, (B, 512))).float().to(torch.bfloat16).cuda()
+    q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ea.decode_q4_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    tail_after = qc.tail_len + 1
+    dc = qc.dc
+
+    def step():
+        ea.project_qkv(desc, x, wqkv, q_r, dc.k_pool, dc.v_pool, qc.tail_table, qc.tail_len, 1)
+        ea.decode_attn_q4(desc, q_r, qc.kq, qc.vq, qc.q4_table, qc.q4_len, dc.k_pool, dc.v_pool, qc.tail_table,
+                          tail_after, o, S, ws)
+        ea.out_proj(desc, o.view(B, -1), wo, y)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    assert torch.isfinite(y_eager.float()).all() and float(y_eager.float().abs().sum()) > 0
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        y.zero_(); o.zero_(); q_r.zero_(); ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep} differs from the eager result"
