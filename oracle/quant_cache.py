@@ -105,3 +105,13 @@ def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int):
     views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
     return ea_oracle.decode_attention(q_r, cache, d_head)
+
+
+def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0):
+    """The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10): the cached rank-r keys (of the one
+    shared basis Uk) are quantised BEFORE they are brought back to d_head channels and rotated, so this is the
+    rotary generation-phase attention over the dequantised rank-r keys and values.
+    q [B, H, d_head] (not rotated); the rest as decode_attention_quantized."""
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
+    return ea_oracle.decode_attention_rope(q, cache, Uk, d_head, base)

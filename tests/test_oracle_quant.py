@@ -175,3 +175,46 @@ def test_attention_over_a_quantised_cache():
     # (d)
     diff = ora.rel_l2(got, plain)
     assert 1e-3 < diff < 0.2
+
+
+def test_rotary_attention_over_a_quantised_cache():
+    """(a) nothing quantised = the rotary oracle; (b) a cache on the grid is attended exactly; (c) brute force: keys
+    dequantised by hand, brought back to d_head channels, rotated pair by pair at their positions."""
+    g = synth.rng(108)
+    H, Hkv, r_k, r_v, d_h, n = 2, 1, 8, 8, 16, 130
+    Uk = synth.orthonormal_basis(g, d_h, r_k)
+    q = synth.gaussian(g, (1, H, d_h))
+    K = [synth.gaussian(g, (Hkv, n, r_k))]
+    V = [synth.gaussian(g, (Hkv, n, r_v))]
+    plain = ora.decode_attention_rope(q, ora.RankCache.from_arrays(K, V), Uk, d_h, 100.0)
+    assert np.array_equal(oq.decode_attention_rope_quantized(q, K, V, [0], Uk, d_h, 100.0), plain)
+    Kg = [np.stack([grid_keys(g, 128, r_k)[0]])]
+    Vg = [np.stack([grid_values(g, 128, r_v)[0]])]
+    exact = ora.decode_attention_rope(q, ora.RankCache.from_arrays(Kg, Vg), Uk, d_h, 100.0)
+    assert np.allclose(oq.decode_attention_rope_quantized(q, Kg, Vg, [128], Uk, d_h, 100.0), exact, rtol=0, atol=1e-13)
+    got = oq.decode_attention_rope_quantized(q, K, V, [128], Uk, d_h, 100.0)
+    ck, sk, zk = oq.quantize_keys(K[0][0, :128])
+    cv, sv, zv = oq.quantize_values(V[0][0, :128])
+
+    def rot(x, pos):
+        y = np.array(x, dtype=np.float64)
+        for j in range(d_h // 2):
+            th = pos * 100.0 ** (-2.0 * j / d_h)
+            y[2 * j] = x[2 * j] * np.cos(th) - x[2 * j + 1] * np.sin(th)
+            y[2 * j + 1] = x[2 * j] * np.sin(th) + x[2 * j + 1] * np.cos(th)
+        return y
+    for h in range(H):
+        scores, vals = [], []
+        qr = rot(q[0, h], n - 1)
+        for t in range(n):
+            if t < 128:
+                key = np.array([float(sk[t // 64, c]) * int(ck[t, c]) + float(zk[t // 64, c]) for c in range(r_k)])
+                val = np.array([float(sv[t]) * int(cv[t, c]) + float(zv[t]) for c in range(r_v)])
+            else:
+                key, val = K[0][0, t], V[0][0, t]
+            scores.append(float(rot(Uk @ key, t) @ qr) / np.sqrt(d_h))
+            vals.append(val)
+        w = np.exp(np.array(scores) - max(scores))
+        ref = (w[:, None] * np.array(vals)).sum(axis=0) / w.sum()
+        assert np.allclose(got[0, h], ref, rtol=0, atol=1e-12)
+    assert 1e-3 < ora.rel_l2(got, plain) < 0.3
