@@ -325,6 +325,26 @@ EA_API int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r,
                     float* dev_out, int32_t B, int32_t n_splits,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama
+ * models of the paper's quantisation experiment are of this kind): the 4-bit pools
+ * hold the quantised rank-r keys k_r = k U^K of the one shared basis; every key is
+ * dequantised, brought back to d_head channels (U^K k_r) and rotated by its position
+ * (token i of the 4-bit part sits at position i, token i of the tail at position
+ * q4_len[b] + i, the query is the newest token), exactly as ea_decode_attn_rope does
+ * for the bfloat16 cache.  q4_len[b] must be a multiple of 64.
+ *   dev_q [B, H, d_head] float, NOT rotated; dev_u_k [d_head, r_k] bfloat16; rope_base as in
+ *   ea_decode_attn_rope; n_splits = 0 picks ea_decode_rope_auto_splits; workspace
+ *   ea_decode_q4_workspace_bytes(desc, B, n_splits).  d_head 64 or 128, r_k <= d_head. */
+EA_API int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    float* dev_out, int32_t B, int32_t n_splits,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -134,4 +134,47 @@ int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const voi
   return merge_splits(gq, (const float*)dev_ws, dev_out, B, slots, st);
 }
 
+int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
+                           const void* dev_kq_pool, const void* dev_vq_pool, const int32_t* dev_q4_page_table,
+                           const int32_t* dev_q4_len, int32_t max_q4_pages, int32_t q4_pool_pages,
+                           const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_tail_page_table,
+                           const int32_t* dev_tail_len, int32_t max_tail_pages, int32_t pool_pages, float* dev_out,
+                           int32_t B, int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream) {
+  int rc = validate_q4(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q || !dev_u_k || !dev_kq_pool || !dev_vq_pool || !dev_q4_page_table || !dev_q4_len || !dev_out)
+    return EA_ERR_ARG;
+  const bool tail = dev_tail_page_table != nullptr || dev_tail_len != nullptr;
+  if (tail && (!dev_tail_page_table || !dev_tail_len || !dev_k_pool || !dev_v_pool || max_tail_pages <= 0 ||
+               pool_pages <= 0))
+    return EA_ERR_ARG;
+  if (B <= 0 || max_q4_pages <= 0 || q4_pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (!(rope_base > 1.0) || !(rope_base < 1e30)) return EA_ERR_ARG;
+  if (desc->r_k > desc->d_head || (desc->d_head != 64 && desc->d_head != 128)) return EA_ERR_SHAPE;
+  if (!aligned16(dev_q) || !aligned16(dev_u_k) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool) ||
+      !aligned16(dev_out) || (tail && (!aligned16(dev_k_pool) || !aligned16(dev_v_pool))))
+    return EA_ERR_ALIGN;
+  if (n_splits == 0) {
+    const int64_t cap_tokens = (int64_t)max_q4_pages * desc->page_tokens;
+    n_splits = ea_decode_rope_auto_splits(desc, B, cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens);
+  }
+  if (!dev_ws || !aligned16(dev_ws)) return EA_ERR_WORKSPACE;
+  if (ws_bytes < ea_decode_q4_workspace_bytes(desc, B, n_splits)) return EA_ERR_WORKSPACE;
+  const int32_t slots = n_splits + (tail ? 1 : 0);
+  const Geo gq = make_geo(desc, max_q4_pages, q4_pool_pages);
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  rc = decode_rope_q4(desc, gq, q4_geo_of(desc), dev_q, dev_u_k, rope_base, dev_kq_pool, dev_vq_pool,
+                      dev_q4_page_table, dev_q4_len, tail ? dev_tail_len : nullptr, max_q4_pages, q4_pool_pages, B,
+                      n_splits, slots, (float*)dev_ws, st);
+  if (rc != EA_OK) return rc;
+  if (tail) {
+    const Geo gt = make_geo(desc, max_tail_pages, pool_pages);
+    rc = decode_rope_bf16(desc, gt, dev_q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_tail_page_table,
+                          dev_tail_len, dev_out, B, 1, (float*)dev_ws, st, slots, n_splits);
+    if (rc != EA_OK) return rc;
+  }
+  return merge_splits(gq, (const float*)dev_ws, dev_out, B, slots, st);
+}
+
 }  // extern "C"

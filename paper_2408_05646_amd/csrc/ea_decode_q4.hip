@@ -15,8 +15,6 @@
 
 namespace ea {
 
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-
 struct DecodeQ4Args {
   const float* q;
   const uint8_t* kq_pool;
@@ -30,33 +28,6 @@ struct DecodeQ4Args {
   int32_t ws_slots;
   float scale_log2;
 };
-
-template <int NCB>
-struct MergeSmemQ4 {
-  float m[4][16];
-  float l[4][16];
-  float acc[4][16][NCB * 16];
-};
-
-__device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
-
-// Eight nibbles -> eight fp16 numbers offset + code; element 2i is nibble i, element 2i+1 nibble i+4.
-// A nibble in bits 0-3 of a half word, under the exponent of 1024.0 (0x6400, one unit per mantissa step), reads
-// 1024 + code; one in bits 4-7 under the exponent of 64.0 (0x5400, sixteen steps per unit) reads 64 + code.  So
-// the nibbles 0,1 (and 4,5) of the dword need no shift at all and the other four share one: elements 0,1,4,5
-// carry the offset 1024, elements 2,3,6,7 the offset 64.  The two magic words come in registers (a mask-and-or
-// takes one of its two constants from a vector register).
-__device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint32_t magic64) {
-  const uint32_t w8 = w >> 8;
-  u32x4 r;
-  r[0] = (w & 0x000f000fu) | magic1024;
-  r[1] = (w & 0x00f000f0u) | magic64;
-  r[2] = (w8 & 0x000f000fu) | magic1024;
-  r[3] = (w8 & 0x00f000f0u) | magic64;
-  return __builtin_bit_cast(f16x8, r);
-}
 
 template <int KS, int NCB>
 __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {

@@ -67,11 +67,45 @@ __host__ __device__ inline int32_t q4_v_scale_off(const Q4Geo& q, int32_t tt) {
   return q.ncb * 512 + ((u * 4 + quad) * 8 + half * 4 + (t32 & 3)) * 2;          // the zero is 128 bytes further
 }
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+
+template <int NCB>
+struct MergeSmemQ4 {
+  float m[4][16];
+  float l[4][16];
+  float acc[4][16][NCB * 16];
+};
+
+__device__ __forceinline__ f32x4 mfma16h(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// Eight nibbles -> eight fp16 numbers offset + code; element 2i is nibble i, element 2i+1 nibble i+4.
+// A nibble in bits 0-3 of a half word, under the exponent of 1024.0 (0x6400, one unit per mantissa step), reads
+// 1024 + code; one in bits 4-7 under the exponent of 64.0 (0x5400, sixteen steps per unit) reads 64 + code.  So
+// the nibbles 0,1 (and 4,5) of the dword need no shift at all and the other four share one: elements 0,1,4,5
+// carry the offset 1024, elements 2,3,6,7 the offset 64.  The two magic words come in registers (a mask-and-or
+// takes one of its two constants from a vector register).
+__device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint32_t magic64) {
+  const uint32_t w8 = w >> 8;
+  u32x4 r;
+  r[0] = (w & 0x000f000fu) | magic1024;
+  r[1] = (w & 0x00f000f0u) | magic64;
+  r[2] = (w8 & 0x000f000fu) | magic1024;
+  r[3] = (w8 & 0x00f000f0u) | magic64;
+  return __builtin_bit_cast(f16x8, r);
+}
+
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
                       void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
                       hipStream_t st);
 int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* kq_pool,
               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
               int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st);
+int decode_rope_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* u_k,
+                   double rope_base, const void* kq_pool, const void* vq_pool, const int32_t* q4_page_table,
+                   const int32_t* q4_len, const int32_t* tail_len, int32_t max_q4_pages, int32_t q4_pool_pages,
+                   int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st);
 
 }  // namespace ea

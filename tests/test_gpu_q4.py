@@ -346,3 +346,80 @@ def test_q4_decode_step_is_graph_capturable():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(y, y_eager), f"replay {rep} differs from the eager result"
+
+
+# ---------------------------------------------------------------------------
+# rotary variant: ea_decode_attn_rope_q4
+# ---------------------------------------------------------------------------
+def run_rope_q4(desc, qc, q, U, base, n_splits, with_tail=True):
+    from helpers import to_dev
+    B = q.shape[0]
+    out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = n_splits if n_splits else ea.decode_rope_auto_splits(desc, B, qc.max_q4_pages * desc.page_tokens)
+    ws = torch.full((ea.decode_q4_workspace_bytes(desc, B, S) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    dc = qc.dc
+    qd = torch.from_numpy(q.astype(np.float32)).cuda()
+    if with_tail:
+        ea.decode_attn_rope_q4(desc, qd, to_dev(desc, U), base, qc.kq, qc.vq, qc.q4_table, qc.q4_len, dc.k_pool,
+                               dc.v_pool, qc.tail_table, qc.tail_len, out, S, ws)
+    else:
+        ea.decode_attn_rope_q4(desc, qd, to_dev(desc, U), base, qc.kq, qc.vq, qc.q4_table, qc.q4_len, None, None, None,
+                               None, out, S, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def oracle_rope_q4(desc, K, V, q, n_quant, U, base):
+    keep = [b for b in range(len(K)) if K[b].shape[1] > 0]
+    ref = np.zeros((len(K), desc.n_heads, desc.r_v))
+    if keep:
+        ref[keep] = oq.decode_attention_rope_quantized(q[keep], [K[b] for b in keep], [V[b] for b in keep],
+                                                       [n_quant[b] for b in keep], U, desc.d_head, base)
+    return ref
+
+
+@pytest.mark.parametrize("H,Hkv,d_h,r_k,r_v,P,lens,n_quant,n_splits", [
+    (2, 2, 128, 80, 80, 64, [200, 130, 64], [128, 128, 64], 1),
+    (2, 2, 128, 80, 80, 64, [1000, 513, 129], [960, 512, 128], 3),
+    (8, 2, 128, 48, 112, 128, [777, 1500], [768, 1280], 0),       # GQA 4:1, r_k != r_v, two tiles per page
+    (16, 1, 128, 96, 64, 64, [330], [320], 2),
+    (4, 4, 128, 128, 128, 64, [513, 100], [512, 64], 2),          # r_k = d_h
+    (4, 2, 128, 72, 40, 64, [150, 70], [128, 64], 2),             # ranks that need padding channels
+    (4, 2, 128, 30, 33, 64, [150, 70], [128, 64], 1),
+    (4, 2, 64, 40, 48, 64, [900, 64], [896, 64], 2),              # d_h = 64
+    (2, 2, 128, 80, 80, 64, [300, 50, 0], [0, 0, 0], 2),          # nothing quantised yet; an empty sequence
+    (2, 2, 128, 80, 80, 64, [90, 200], [64, 192], 4),             # more splits than tiles
+    (2, 1, 128, 80, 80, 64, [20000], [19968], 1),                 # one workgroup walks 312 tiles: the stepped rotation
+                                                                  # of the query is re-computed exactly on the way
+])
+def test_decode_rope_q4_matches_oracle(H, Hkv, d_h, r_k, r_v, P, lens, n_quant, n_splits):
+    print(f"q4 rope decode H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) P={P} lens={lens} quantised={n_quant} S={n_splits}",
+          flush=True)
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(46, H, r_k, len(lens), n_splits)
+    U = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    q = np.float32(synth.gaussian(g, (len(lens), H, d_h), 1.5)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    got = run_rope_q4(desc, qc, q, U, 10000.0, n_splits)
+    ref = oracle_rope_q4(desc, K, V, q, n_quant, U, 10000.0)
+    err = assert_close(got, ref, TOL_BF16, "q4 rope decode")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+def test_decode_rope_q4_positions_and_no_tail():
+    """Without a bfloat16 part the query is the last quantised token; and the result follows the rotary oracle,
+    not the position-free one (they differ by far more than the tolerance here)."""
+    from oracle import eigen_attention as ora
+    desc = ea.LayerDesc(256, 2, 2, 128, 80, 80, ea.EA_BF16, 64)
+    g = synth.rng(47)
+    lens = [640]
+    U = quantize(desc, synth.orthonormal_basis(g, 128, 80))
+    K, V = offset_cache(desc, lens, g, k_std=2.0)
+    q = np.float32(synth.gaussian(g, (1, 2, 128), 2.0)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, lens, g)
+    got = run_rope_q4(desc, qc, q, U, 10000.0, 2, with_tail=False)
+    ref = oracle_rope_q4(desc, K, V, q, lens, U, 10000.0)
+    flat = oq.decode_attention_quantized(np.einsum("bhc,cr->bhr", q, U), K, V, lens, 128)
+    assert ora.rel_l2(flat, ref) > 0.2
+    assert_close(got, ref, TOL_BF16, "q4 rope, no tail")
