@@ -51,7 +51,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
-                             "cfg5-q4"])
+                             "cfg5-q4", "cfg3-rope-q4"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -134,7 +134,7 @@ def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: boo
             "seconds": round(dt, 3)}
 
 
-def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_tokens: int):
+def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_tokens: int, rope: bool = False):
     """The oracle of the quantised-cache step on `n_streams` (sequence, head) streams: codes and scales are
     prepared outside the timed region (they are the cache's content); timed is what a generation step does with
     them, dequantisation of the 4-bit part and fp64 attention over it and the 16-bit newest page."""
@@ -150,19 +150,24 @@ def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_t
     V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
     kq = [oq.quantize_keys(K1[h, :nq]) for h in range(heads)]
     vq = [oq.quantize_values(V1[h, :nq]) for h in range(heads)]
-    q = g.standard_normal((n_seq, heads, r))
+    q = g.standard_normal((n_seq, heads, d_head if rope else r))
+    U = synth.orthonormal_basis(g, d_head, r) if rope else None
 
     def work():
         Kd = np.stack([np.concatenate([oq.dequantize_keys(*kq[h]), K1[h, nq:]]) for h in range(heads)])
         Vd = np.stack([np.concatenate([oq.dequantize_values(*vq[h]), V1[h, nq:]]) for h in range(heads)])
-        ora.decode_attention(q, ora.RankCache.from_arrays([Kd] * n_seq, [Vd] * n_seq), d_head)
+        cache = ora.RankCache.from_arrays([Kd] * n_seq, [Vd] * n_seq)
+        if rope:
+            ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE)
+        else:
+            ora.decode_attention(q, cache, d_head)
 
     dt = _timed_single_thread(work)
     tiles = nq // 64
     cache_bytes = n_seq * heads * (tiles * (2 * 32 * ((r + 15) // 16 * 16) + 128 * ((r + 31) // 32) + 256)
                                    + page_tokens * 2 * r * 2)      # what the GPU kernels would stream
     return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"dequantisation and decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
+            "sample": f"dequantisation and {'rotary ' if rope else ''}decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
                       f"streams (n={n_ctx}, r={r}, all but the last {page_tokens} tokens in 4 bits), fp64 numpy, "
                       f"{dt:.2f} s per pass, timed three times (best kept)",
             "seconds": round(dt, 3)}
@@ -187,7 +192,7 @@ def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
 
 def bench_decode(args, torch, ea, synth):
     dev = "cuda"
-    base_name, rope = args.workload.split("-")[0], args.workload.endswith("-rope")
+    base_name, rope = args.workload.split("-")[0], "-rope" in args.workload
     q4 = args.workload.endswith("-q4")       # all pages but the newest of every sequence held in 4 bits
     s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[base_name]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
@@ -248,7 +253,8 @@ def bench_decode(args, torch, ea, synth):
         layers.append(dict(
             **extra,
             desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
-            S=args.n_splits or (ea.decode_rope_auto_splits(dc, B, n) if rope else ea.decode_auto_splits(dc, B, n)),
+            S=args.n_splits or (ea.decode_auto_splits(dc, B, n) if (q4 or not rope) else
+                                ea.decode_rope_auto_splits(dc, B, n)),
             wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             wo=ea.pack_weight((torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),
@@ -273,14 +279,18 @@ def bench_decode(args, torch, ea, synth):
     def step(events=None):
         for li, l in enumerate(layers):
             if q4:
-                ea.project_qkv(l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["tail_table"],
-                               tail_before, 1)
+                (ea.project_qkv_rope if rope else ea.project_qkv)(
+                    l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["tail_table"], tail_before, 1)
             else:
                 (ea.project_qkv_rope if rope else ea.project_qkv)(
                     l["desc"], l["x"], l["wqkv"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_before, 1)
             if events is not None:
                 events[li][0].record()
-            if q4:
+            if q4 and rope:
+                ea.decode_attn_rope_q4(l["desc"], l["q_r"], l["u_k"], ROPE_BASE, l["kq_pool"], l["vq_pool"],
+                                       l["page_table"], q4_len, l["k_pool"], l["v_pool"], l["tail_table"], tail_after,
+                                       l["o"], l["S"], ws)
+            elif q4:
                 ea.decode_attn_q4(l["desc"], l["q_r"], l["kq_pool"], l["vq_pool"], l["page_table"], q4_len,
                                   l["k_pool"], l["v_pool"], l["tail_table"], tail_after, l["o"], l["S"], ws)
             elif rope:
@@ -359,6 +369,9 @@ def bench_decode(args, torch, ea, synth):
         (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
     if q4:
         kern = "decode_q4_kernel + decode_bf16_kernel (newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
+    if q4 and rope:
+        kern = ("decode_rope_q4_kernel + decode_bf16_kernel (rotary variant, newest page) + merge_splits_kernel "
+                "(one ea_decode_attn_rope_q4 call)")
 
     rank_note = f"r_k=r_v={s.r_k}" if base_name != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
@@ -373,7 +386,9 @@ def bench_decode(args, torch, ea, synth):
                                   "scales and zeros) except the newest page of each sequence, which is bf16; "
                                   if q4 else "bf16 ") +
                                f"paged cache (page {P} tokens, pages in random order), "
-                               + ("project_qkv + decode_attn_q4 + out_proj per layer" if q4 else
+                               + ("rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope_q4 + out_proj "
+                                  "per layer, query at position n-1, base 10000" if (q4 and rope) else
+                                  "project_qkv + decode_attn_q4 + out_proj per layer" if q4 else
                                   "rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope + out_proj "
                                   "per layer, query at position n-1, base 10000" if rope else
                                   "project_qkv + decode_attn + out_proj per layer"),
@@ -435,7 +450,8 @@ def bench_decode(args, torch, ea, synth):
         result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
     if not args.no_cpu and q4:
-        result["cpu_baseline"] = cpu_oracle_decode_q4(args.cpu_streams // 8, n, ranks[0][0], s.d_head, P)
+        result["cpu_baseline"] = cpu_oracle_decode_q4(args.cpu_streams // (32 if rope else 8), n, ranks[0][0], s.d_head,
+                                                      P, rope=rope)
     elif not args.no_cpu:
         result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 1), n, ranks[0][0], s.d_head,
                                                    rope=rope)

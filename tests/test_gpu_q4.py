@@ -231,12 +231,14 @@ def test_quantisation_is_what_is_measured():
     assert_close(got, ref, TOL_BF16, "q4 vs quantised oracle")
 
 
-def test_cfg3_q4_one_layer_sampled():
+@pytest.mark.parametrize("rope", [False, True])
+def test_cfg3_q4_one_layer_sampled(rope):
     """B=16, n=32768, H=32, r=80, one of the 32 resident layers, in the launch configuration bench.py times
-    (--workload cfg3-q4): all pages but the newest of every sequence in the 4-bit pools (random codes, scales and
-    zeros as unit-variance groups have them), the newest page bfloat16; sampled (sequence, head) streams are read
-    back, decoded on the host from the documented positions and attended by the fp64 oracle."""
+    (--workload cfg3-q4 / cfg3-rope-q4): all pages but the newest of every sequence in the 4-bit pools (random
+    codes, scales and zeros as unit-variance groups have them), the newest page bfloat16; sampled (sequence, head)
+    streams are read back, decoded on the host from the documented positions and attended by the fp64 oracle."""
     from oracle import eigen_attention as ora
+    from helpers import to_dev
     s = synth.CFG3
     P, B, n, H = 64, s.batch, s.n_ctx, s.n_heads
     desc = ea.LayerDesc(s.d_model, H, s.n_kv_heads, s.d_head, s.r_k, s.r_v, ea.EA_BF16, P)
@@ -262,12 +264,17 @@ def test_cfg3_q4_one_layer_sampled():
     v_pool.normal_(generator=gen)
     tail_table = torch.arange(B, dtype=torch.int32, device="cuda").reshape(B, 1).contiguous()
     tail_len = torch.full((B,), P, dtype=torch.int32, device="cuda")
-    q = torch.randn((B, H, s.r_k), generator=gen, device="cuda")
+    q = torch.randn((B, H, s.d_head if rope else s.r_k), generator=gen, device="cuda")
+    U = quantize(desc, synth.orthonormal_basis(synth.rng(3, 3), s.d_head, s.r_k))
     out = torch.full((B, H, s.r_v), float("nan"), dtype=torch.float32, device="cuda")
     S = ea.decode_auto_splits(desc, B, n)
     assert S == 1
     ws = torch.empty(ea.decode_q4_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
-    ea.decode_attn_q4(desc, q, kq, vq, table, q4_len, k_pool, v_pool, tail_table, tail_len, out, S, ws)
+    if rope:
+        ea.decode_attn_rope_q4(desc, q, to_dev(desc, U), 10000.0, kq, vq, table, q4_len, k_pool, v_pool, tail_table,
+                               tail_len, out, S, ws)
+    else:
+        ea.decode_attn_q4(desc, q, kq, vq, table, q4_len, k_pool, v_pool, tail_table, tail_len, out, S, ws)
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     assert np.isfinite(got).all()
@@ -276,7 +283,7 @@ def test_cfg3_q4_one_layer_sampled():
     kc, vc, ks, vs = pos
     table_h = table.cpu().numpy()
     g = synth.rng(3, 2)
-    samples = [(0, 0), (15, 31)] + [(int(g.integers(B)), int(g.integers(H))) for _ in range(6)]
+    samples = [(0, 0), (15, 31)] + [(int(g.integers(B)), int(g.integers(H))) for _ in range(2 if rope else 6)]
     print("cfg3-q4 samples", samples, flush=True)
     for (b, h) in samples:
         ids = torch.from_numpy(table_h[b, :pages - 1].astype(np.int64)).cuda()
@@ -298,8 +305,10 @@ def test_cfg3_q4_one_layer_sampled():
         K = np.concatenate([Kd.reshape(-1, s.r_k), kp[k_idx].astype(np.float64)])
         V = np.concatenate([Vd.reshape(-1, s.r_v), vp[v_idx].astype(np.float64)])
         assert K.shape == (n, s.r_k)
-        ref = ora.decode_attention(q[b:b + 1, h:h + 1].double().cpu().numpy(),
-                                   ora.RankCache.from_arrays([K[None]], [V[None]]), s.d_head)
+        q_bh = q[b:b + 1, h:h + 1].double().cpu().numpy()
+        cache = ora.RankCache.from_arrays([K[None]], [V[None]])
+        ref = ora.decode_attention_rope(q_bh, cache, U, s.d_head, 10000.0) if rope else \
+            ora.decode_attention(q_bh, cache, s.d_head)
         assert_close(got[b:b + 1, h:h + 1], ref, TOL_BF16, f"cfg3-q4 stream b={b} h={h}")
 
 

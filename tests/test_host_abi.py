@@ -323,3 +323,19 @@ def test_q4_entry_points_reject_bad_arguments_before_launching():
     assert dec(ws_bytes=need - 1) == -4
     assert dec(dd=desc(dtype=ea.EA_F32, P=64)) == -2
     assert ea.decode_q4_workspace_bytes(d, 0, 2) == -1
+
+
+def test_rotary_q4_entry_point_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def dec(dd=d, q=OK_PTR, u=OK_PTR, base=10000.0, tail_pt=OK_PTR, tail_len=OK_PTR, n_splits=2, ws=OK_PTR,
+            ws_bytes=1 << 30):
+        return lib.ea_decode_attn_rope_q4(ctypes.byref(dd), q, u, base, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, OK_PTR,
+                                          OK_PTR, tail_pt, tail_len, 2, 8, OK_PTR, 2, n_splits, ws, ws_bytes, None)
+
+    assert dec(u=None) == -1 and dec(base=1.0) == -1 and dec(tail_pt=None) == -1
+    assert dec(u=ODD_PTR) == -3
+    assert dec(ws=None) == -4 and dec(ws_bytes=16) == -4
+    assert dec(dd=desc(d_h=96)) == -2                                      # d_head 64 or 128
+    assert dec(dd=desc(d_h=64, r_k=80)) == -2                              # r_k <= d_head
+    assert dec(dd=desc(dtype=ea.EA_F32, P=64)) == -2
