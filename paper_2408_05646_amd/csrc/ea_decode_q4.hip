@@ -178,7 +178,9 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(unpack_q4(kc[kk][tb], magic1024, magic64), qs[kk], s[tb]);
     }
-    if (have_n) load_k(nxt, max(page_n, 0));
+    // unconditional (a wave's last tile re-reads itself): a load behind a branch would cost a second copy of the
+    // registers for the path on which nothing is loaded
+    load_k(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
 
     if (page < 0) {
       // a page that is not there: its tokens do not take part, and the scales read from page 0 are dropped
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
 #pragma unroll
       for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(unpack_q4(v_dword(cb, u), magic1024, magic64), ps[u], acc[cb]);
     }
-    if (have_n) load_v(nxt, max(page_n, 0));
+    load_v(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
     cur = nxt;
     have = have_n;
     page = page_n;

@@ -271,7 +271,9 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
           kf[tb][ks] = (unpack_q4(kc[ks][2 * sub + tb], magic1024, magic64) + negoff) * ksc[ks] + kzr[ks];
-      if (sub == 1 && have_n) load_k(nxt, max(page_n, 0));    // the key registers are free again
+      // the key registers are free again; the load is unconditional (a wave's last tile re-reads itself), so that
+      // the registers need no second copy for the path on which nothing is loaded
+      if (sub == 1) load_k(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
 
       // ---- scores (log2 units) relative to the reference exponent
       const float m_base = m == -INFINITY ? 0.f : m;
@@ -345,8 +347,8 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
       for (int cb = 0; cb < NCB; ++cb)
         acc[cb] = mfma16h(unpack_q4(v_dword(cb, sub), magic1024, magic64), ps, acc[cb]);
     }
+    load_v(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
     if (have_n) {
-      load_v(nxt, max(page_n, 0));
       if (++since_seed == kReseedQ4) {
         since_seed = 0;
         seed_q(nxt.tile);
