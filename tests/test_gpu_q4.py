@@ -432,3 +432,94 @@ def test_decode_rope_q4_positions_and_no_tail():
     flat = oq.decode_attention_quantized(np.einsum("bhc,cr->bhr", q, U), K, V, lens, 128)
     assert ora.rel_l2(flat, ref) > 0.2
     assert_close(got, ref, TOL_BF16, "q4 rope, no tail")
+
+
+def test_q4_generation_lifecycle():
+    """A prompt is projected into the bfloat16 cache; from then on every page that fills up is quantised (and its
+    bfloat16 page given back), while generation steps append to the newest page and attend over both parts:
+    40 steps that cross a page boundary, every step's layer output against the fp64 oracle that follows the same
+    policy (its own projections, rounded to bfloat16 as the cache holds them, quantised by its own quantiser)."""
+    from oracle import eigen_attention as ora
+    from helpers import to_dev
+    from test_gpu_layer import make_weights, device_weights
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    P, B, n0, steps = 64, 2, 100, 40
+    g = synth.rng(48)
+    Wq, Wk, Wv, Wo, Uk, Uv = make_weights(desc, g)
+    wqkv_t, wo_t, folded_q = device_weights(desc, ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, 8, 2))
+    Wq_q, Wk_q, Wv_q, Wo_q = folded_q
+    x_hist = quantize(desc, synth.gaussian(g, (B, n0 + steps, 512)))
+
+    # pools: 3 bfloat16 pages per sequence (ids drawn at random), room for 2 quantised pages per sequence
+    max_pages = 3
+    pool_pages = B * max_pages + 2
+    k_pool, v_pool = ea.alloc_pools(desc, pool_pages)
+    k_pool.fill_(float("nan"))
+    v_pool.fill_(float("nan"))
+    pt = synth.random_page_table(g, B, max_pages, pool_pages)
+    kq, vq = ea.alloc_q4_pools(desc, 2 * B + 1)
+    kq.fill_(0xFF)
+    vq.fill_(0xFF)
+    free_q4 = list(g.permutation(2 * B + 1).astype(np.int32))
+    q4_table = np.full((B, 2), -1, np.int32)
+    n_q4 = [0] * B                       # tokens of each sequence held in 4 bits
+    first_page = [0] * B                 # index into pt[b] of the page the bfloat16 part starts with
+
+    def quantise_full_pages(lens):
+        for b in range(B):
+            while lens[b] - n_q4[b] >= P:
+                src, dst = pt[b, first_page[b]], free_q4.pop()
+                ea.quantize_pages_q4(desc, k_pool, v_pool, torch.tensor([src], dtype=torch.int32).cuda(), kq, vq,
+                                     torch.tensor([dst], dtype=torch.int32).cuda())
+                torch.cuda.synchronize()
+                k_pool[int(src)] = float("nan")          # the bfloat16 page is given back
+                v_pool[int(src)] = float("nan")
+                q4_table[b, n_q4[b] // P] = dst
+                n_q4[b] += P
+                first_page[b] += 1
+
+    def tail_views(lens):
+        tt = np.full((B, max_pages), -1, np.int32)
+        for b in range(B):
+            tt[b, :max_pages - first_page[b]] = pt[b, first_page[b]:]
+        return (torch.from_numpy(tt).cuda(), torch.tensor([lens[b] - n_q4[b] for b in range(B)], dtype=torch.int32).cuda())
+
+    # ---- prompt
+    lens = [0] * B
+    tail_table, tail_len = tail_views(lens)
+    q_pre = torch.empty((B * n0, 8, 80), dtype=torch.bfloat16, device="cuda")
+    ea.project_qkv(desc, to_dev(desc, x_hist[:, :n0].reshape(B * n0, 512)), wqkv_t, q_pre, k_pool, v_pool, tail_table,
+                   tail_len, n0)
+    torch.cuda.synchronize()
+    lens = [n0] * B
+    quantise_full_pages(lens)
+    assert n_q4 == [64, 64]
+    # oracle state: what the cache holds, from the oracle's own projections
+    _, k_all, v_all = ora.project_qkv(x_hist.reshape(B * (n0 + steps), 512), Wq_q, Wk_q, Wv_q)
+    k_all = quantize(desc, k_all).reshape(B, n0 + steps, 2, 80).transpose(0, 2, 1, 3)     # [B, H_kv, n, r_k]
+    v_all = quantize(desc, v_all).reshape(B, n0 + steps, 2, 48).transpose(0, 2, 1, 3)
+
+    q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    S = 2
+    ws = torch.empty(ea.decode_q4_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    worst = 0.0
+    for t in range(steps):
+        tail_table, tail_len = tail_views(lens)
+        x_t = x_hist[:, n0 + t]
+        ea.project_qkv(desc, to_dev(desc, x_t), wqkv_t, q_r, k_pool, v_pool, tail_table, tail_len, 1)
+        ea.decode_attn_q4(desc, q_r, kq, vq, torch.from_numpy(q4_table).cuda(),
+                          torch.tensor(n_q4, dtype=torch.int32).cuda(), k_pool, v_pool, tail_table, tail_len + 1, o, S,
+                          ws)
+        ea.out_proj(desc, o.view(B, -1), wo_t, y)
+        torch.cuda.synchronize()
+        lens = [n + 1 for n in lens]
+        q_ref, _, _ = ora.project_qkv(x_t, Wq_q, Wk_q, Wv_q)
+        o_ref = oq.decode_attention_quantized(q_ref, [k_all[b][:, :lens[b]] for b in range(B)],
+                                              [v_all[b][:, :lens[b]] for b in range(B)], n_q4, 128)
+        y_ref = ora.out_proj(o_ref, Wo_q)
+        worst = max(worst, assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"lifecycle step {t}"))
+        quantise_full_pages(lens)
+    assert n_q4 == [128, 128] and lens == [140, 140]
+    print(f"  worst step rel-L2 {worst:.2e}", flush=True)
