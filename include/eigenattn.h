@@ -264,7 +264,9 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
  * p * k_page_bytes (v_page_bytes); inside a page kv head after kv head, tile after
  * tile, one tile block per (kv head, 64 tokens).  A tile block holds the codes in the
  * order the matrix cores consume them, then the fp16 scales and zeros;
- * ea_q4_k_code_pos and its siblings are the reference of the positions. */
+ * ea_q4_k_code_pos and its siblings are the reference of the positions.  The scale
+ * and zero slots of padding channels (r_k .. the next multiple of 32) are written as 0
+ * by the quantiser; whoever fills the pools by other means must leave finite values there. */
 typedef struct ea_q4_layout {
   int32_t r_k_pad;         /* multiple of 8  */
   int32_t r_v_pad;         /* multiple of 16 */
