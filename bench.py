@@ -368,7 +368,7 @@ def bench_decode(args, torch, ea, synth):
         ("" if splits == [1] else " + merge_splits_kernel") + \
         (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
     if q4:
-        kern = "decode_q4_kernel + decode_bf16_kernel (newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
+        kern = "decode_q4_kernel (4-bit part and, in its last grid slices, the bf16 newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
     if q4 and rope:
         kern = ("decode_rope_q4_kernel + decode_bf16_kernel (rotary variant, newest page) + merge_splits_kernel "
                 "(one ea_decode_attn_rope_q4 call)")

@@ -122,15 +122,11 @@ int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const voi
   const Geo gq = make_geo(desc, max_q4_pages, q4_pool_pages);
   hipStream_t st = (hipStream_t)stream;
   clear_stale_error();
+  const Geo gt = make_geo(desc, tail ? max_tail_pages : 1, tail ? pool_pages : 1);
   rc = decode_q4(desc, gq, q4_geo_of(desc), dev_q_r, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
-                 max_q4_pages, q4_pool_pages, B, n_splits, slots, (float*)dev_ws, st);
+                 max_q4_pages, q4_pool_pages, B, n_splits, slots, (float*)dev_ws, st, tail ? &gt : nullptr, dev_k_pool,
+                 dev_v_pool, dev_tail_page_table, dev_tail_len);
   if (rc != EA_OK) return rc;
-  if (tail) {
-    const Geo gt = make_geo(desc, max_tail_pages, pool_pages);
-    rc = decode_bf16(desc, gt, dev_q_r, dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len, dev_out, B, 1,
-                     (float*)dev_ws, st, slots, n_splits);
-    if (rc != EA_OK) return rc;
-  }
   return merge_splits(gq, (const float*)dev_ws, dev_out, B, slots, st);
 }
 

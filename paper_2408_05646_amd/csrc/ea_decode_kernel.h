@@ -77,20 +77,23 @@ constexpr int kReseed = 32;   // iterations between exact re-computations of the
 // large ranks whose fragments would not fit the register file otherwise).
 // ALIBI adds the linear position bias of the ALiBi scheme to the scores: -slope_h * (distance of the key to
 // the query), in the position-free form only.
+// LDS of one workgroup: the rotary tables while the cache streams, the merge buffers afterwards.
+template <int KS, int NCB, int TBN, int NKK>
+union DecodeSmem {
+  MergeSmem<NCB> mg;
+  std::conditional_t<(NKK > 0), RopeSmem<TBN, (NKK > 0) ? NKK : 1, KS>, NoSmem> rp;
+};
+
 template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false>
-__global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
+__device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int kvh, const int split, const int b,
+                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK>& sm) {
   constexpr bool ROPE = NKK > 0;
   static_assert(!(ROPE && ALIBI), "a model has one position scheme");
-  __shared__ union {
-    MergeSmem<NCB> mg;
-    std::conditional_t<ROPE, RopeSmem<TBN, ROPE ? NKK : 1, KS>, NoSmem> rp;
-  } sm;
   constexpr int UN = TBN / 2;            // 32-token groups per iteration
   constexpr int SUB = 4 / TBN;           // iterations per 64-token tile
   constexpr int TOK = TBN * 16;          // tokens per iteration
   const Geo& g = a.g;
   // neighbouring workgroups take neighbouring kv heads of the same pages: their slabs are adjacent in memory
-  const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, so is all that follows from it
   const int col = lane & 15, quad = lane >> 4;
@@ -530,7 +533,7 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
     } else {
       const int slots = a.ws_slots > 0 ? a.ws_slots : a.n_splits;
-      const int64_t BHS = (int64_t)gridDim.z * g.n_heads * slots;
+      const int64_t BHS = (int64_t)n_batch * g.n_heads * slots;
       const int64_t row = ((int64_t)b * g.n_heads + head) * slots + a.ws_slot0 + split;
       if (c == 0) {
         a.ws[row] = mm;
@@ -539,6 +542,14 @@ __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
       a.ws[2 * BHS + row * r_v_pad + c] = val;
     }
   }
+}
+
+// The kernel: one workgroup per (kv head, split, sequence).  (The body is a function of its own because the
+// kernel over the 4-bit cache runs it, too, for the bfloat16 tail of the sequences.)
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false>
+__global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
+  __shared__ DecodeSmem<KS, NCB, TBN, NKK> sm;
+  decode_bf16_body<KS, NCB, TBN, WPE, NKK, ALIBI>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, sm);
 }
 
 }  // namespace ea

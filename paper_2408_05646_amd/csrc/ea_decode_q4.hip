@@ -9,8 +9,10 @@
 //                   = sum_t (p scale)[h,t] (off_t + code[t,c]) + sum_t p[h,t] zero_t - sum_t off_t (p scale)[h,t]:
 //            the scales go into the probabilities, the constant terms are matrix-core products again, beside
 //            the one that makes the softmax denominators.
-// The kernel always writes split partials (m, l, acc); the 16-bit tail of the sequences is attended by the
-// bfloat16 kernel into further slots of the same workspace and one merge finishes.
+// The kernel always writes split partials (m, l, acc).  The 16-bit tail of the sequences is attended in the same
+// launch: the workgroups of one more grid row run the bfloat16 kernel's body (half-tile form, which needs no more
+// registers than the 4-bit path) into the last slot of the workspace; one merge finishes.
+#include "ea_decode_kernel.h"
 #include "ea_q4.h"
 
 namespace ea {
@@ -27,16 +29,31 @@ struct DecodeQ4Args {
   int32_t n_splits;
   int32_t ws_slots;
   float scale_log2;
+  int32_t n_batch;
+  int32_t has_tail;     // further grid slices attend the bfloat16 tail described by `tail`
+  DecodeArgs tail;
 };
 
 template <int KS, int NCB>
 __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
-  __shared__ MergeSmemQ4<NCB> sm;
+  __shared__ union {
+    MergeSmemQ4<NCB> q4;
+    DecodeSmem<KS, NCB, 2, 0> tail;
+  } smu;
   constexpr int NVP = NCB / 2;          // 16-byte units of value codes per lane
   constexpr bool VODD = (NCB & 1) != 0; // ... plus one 8-byte unit
   const Geo& g = a.g;
   const Q4Geo& qg = a.qg;
   const int kvh = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+  if (b >= a.n_batch) {
+    // The grid's last slices (they are dispatched last, so they do not disturb the placement of the long
+    // workgroups) attend the bfloat16 tails: one workgroup per (sequence, kv head).
+    const int t = ((b - a.n_batch) * a.n_splits + split) * g.n_kv_heads + kvh;
+    const int tb = t / g.n_kv_heads;
+    if (tb < a.n_batch) decode_bf16_body<KS, NCB, 2, 2, 0, false>(a.tail, t % g.n_kv_heads, 0, tb, a.n_batch, smu.tail);
+    return;
+  }
+  MergeSmemQ4<NCB>& sm = smu.q4;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 15, quad = lane >> 4;
@@ -266,7 +283,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
       }
     }
     const int head = kvh * G + hd;
-    const int64_t BHS = (int64_t)gridDim.z * g.n_heads * a.ws_slots;
+    const int64_t BHS = (int64_t)a.n_batch * g.n_heads * a.ws_slots;
     const int64_t row = ((int64_t)b * g.n_heads + head) * a.ws_slots + split;
     if (c == 0) {
       a.ws[row] = mm;
@@ -278,7 +295,8 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
 
 template <int KS, int NCB>
 static void launch_q4(const DecodeQ4Args& a, int32_t B, hipStream_t st) {
-  decode_q4_kernel<KS, NCB><<<dim3(a.g.n_kv_heads, a.n_splits, B), dim3(256), 0, st>>>(a);
+  const int extra = a.has_tail ? (B + a.n_splits - 1) / a.n_splits : 0;
+  decode_q4_kernel<KS, NCB><<<dim3(a.g.n_kv_heads, a.n_splits, B + extra), dim3(256), 0, st>>>(a);
 }
 
 template <int KS>
@@ -299,8 +317,10 @@ static int dispatch_ncb_q4(int ncb, const DecodeQ4Args& a, int32_t B, hipStream_
 
 int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* kq_pool,
               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
-              int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st) {
-  if (B > 65535 || g.n_kv_heads > 65535 || n_splits > 65535) return EA_ERR_SHAPE;
+              int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st,
+              const Geo* tail_geo, const void* k_pool, const void* v_pool, const int32_t* tail_page_table,
+              const int32_t* tail_len) {
+  if (2 * B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   DecodeQ4Args a;
   a.q = q;
   a.kq_pool = (const uint8_t*)kq_pool;
@@ -315,6 +335,27 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
   a.n_splits = n_splits;
   a.ws_slots = ws_slots;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
+  a.has_tail = tail_geo != nullptr;
+  a.n_batch = B;
+  a.tail = DecodeArgs{};
+  if (tail_geo) {
+    a.tail.q = q;
+    a.tail.k_pool = (const uint16_t*)k_pool;
+    a.tail.v_pool = (const uint16_t*)v_pool;
+    a.tail.page_table = tail_page_table;
+    a.tail.seq_len = tail_len;
+    a.tail.out = nullptr;
+    a.tail.ws = ws;
+    a.tail.g = *tail_geo;
+    a.tail.n_splits = 1;
+    a.tail.scale_log2 = a.scale_log2;
+    a.tail.u_k = nullptr;
+    a.tail.d_head = d->d_head;
+    a.tail.log2_base = 0.0;
+    a.tail.alibi = nullptr;
+    a.tail.ws_slots = ws_slots;
+    a.tail.ws_slot0 = n_splits;
+  }
   switch (qg.ks) {
     case 1: return dispatch_ncb_q4<1>(qg.ncb, a, B, st);
     case 2: return dispatch_ncb_q4<2>(qg.ncb, a, B, st);
