@@ -300,6 +300,15 @@ EA_API int ea_quantize_pages_q4(const ea_layer_desc* desc, const void* dev_k_poo
                     const int32_t* dev_dst_pages, int32_t n_pages, int32_t pool_pages, int32_t q4_pool_pages,
                     void* stream);
 
+/* The way back, for export and inspection: page dev_src_pages[i] of the 4-bit pools is
+ * written as page dev_dst_pages[i] of the bfloat16 pools, value = scale * code + zero
+ * evaluated in float and rounded once to bfloat16 (padding channels zero).  The
+ * attention calls never do this: they work on the codes. */
+EA_API int ea_dequantize_pages_q4(const ea_layer_desc* desc, const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_src_pages, void* dev_k_pool, void* dev_v_pool,
+                    const int32_t* dev_dst_pages, int32_t n_pages, int32_t q4_pool_pages, int32_t pool_pages,
+                    void* stream);
+
 /* Generation-phase attention (Eq. 3 with Eq. 7's rank-r operands, as ea_decode_attn)
  * over a cache whose older part is quantised: sequence b consists of its first
  * q4_len[b] tokens (a multiple of 64; a remainder is ignored) in the 4-bit pools,

@@ -18,7 +18,7 @@ __all__ = [
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
-    "quantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4",
+    "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_attn", "ea_decode_rope_auto_splits", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
-    "ea_quantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4",
+    "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4",
 )
 
 
@@ -118,6 +118,7 @@ def load_library():
     lib.ea_q4_v_scale_pos.restype = I64
     lib.ea_q4_v_scale_pos.argtypes = [D, I32, I32, I32]
     lib.ea_quantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
+    lib.ea_dequantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
     lib.ea_decode_q4_workspace_bytes.restype = I64
     lib.ea_decode_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
@@ -469,6 +470,19 @@ def quantize_pages_q4(desc, k_pool, v_pool, src_pages, kq_pool, vq_pool, dst_pag
                                              _ptr(kq_pool), _ptr(vq_pool), _ptr(dst_pages), src_pages.numel(),
                                              k_pool.shape[0], kq_pool.shape[0], _stream(stream))
     _check(rc, "ea_quantize_pages_q4")
+
+
+def dequantize_pages_q4(desc, kq_pool, vq_pool, src_pages, k_pool, v_pool, dst_pages, stream=None) -> None:
+    """Pages src_pages[i] of the 4-bit pools -> pages dst_pages[i] of the bfloat16 pools (export / inspection)."""
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _u8(kq_pool, "kq_pool"); _u8(vq_pool, "vq_pool")
+    _i32(src_pages, "src_pages"); _i32(dst_pages, "dst_pages")
+    if src_pages.numel() != dst_pages.numel():
+        raise ValueError("src_pages and dst_pages must have the same length")
+    rc = load_library().ea_dequantize_pages_q4(ctypes.byref(desc), _ptr(kq_pool), _ptr(vq_pool), _ptr(src_pages),
+                                               _ptr(k_pool), _ptr(v_pool), _ptr(dst_pages), src_pages.numel(),
+                                               kq_pool.shape[0], k_pool.shape[0], _stream(stream))
+    _check(rc, "ea_dequantize_pages_q4")
 
 
 def decode_q4_workspace_bytes(desc, B: int, n_splits: int) -> int:

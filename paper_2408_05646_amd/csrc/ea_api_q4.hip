@@ -90,6 +90,23 @@ int ea_quantize_pages_q4(const ea_layer_desc* desc, const void* dev_k_pool, cons
                            dev_dst_pages, n_pages, q4_pool_pages, (hipStream_t)stream);
 }
 
+int ea_dequantize_pages_q4(const ea_layer_desc* desc, const void* dev_kq_pool, const void* dev_vq_pool,
+                           const int32_t* dev_src_pages, void* dev_k_pool, void* dev_v_pool,
+                           const int32_t* dev_dst_pages, int32_t n_pages, int32_t q4_pool_pages, int32_t pool_pages,
+                           void* stream) {
+  int rc = validate_q4(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_k_pool || !dev_v_pool || !dev_src_pages || !dev_kq_pool || !dev_vq_pool || !dev_dst_pages) return EA_ERR_ARG;
+  if (n_pages < 0 || pool_pages <= 0 || q4_pool_pages <= 0) return EA_ERR_ARG;
+  if (!aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool))
+    return EA_ERR_ALIGN;
+  if (n_pages == 0) return EA_OK;
+  const Geo g = make_geo(desc, 1, pool_pages);
+  clear_stale_error();
+  return dequantize_pages_q4(g, q4_geo_of(desc), dev_kq_pool, dev_vq_pool, dev_src_pages, dev_k_pool, dev_v_pool,
+                             dev_dst_pages, n_pages, q4_pool_pages, (hipStream_t)stream);
+}
+
 int64_t ea_decode_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits) {
   if (validate_q4(desc) != EA_OK || B <= 0 || n_splits <= 0) return -1;
   return ws_floats(B, desc->n_heads, n_splits + 1, round_up(desc->r_v, 16)) * (int64_t)sizeof(float);

@@ -100,6 +100,9 @@ __device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint3
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
                       void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
                       hipStream_t st);
+int dequantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* kq_pool, const void* vq_pool, const int32_t* src_pages,
+                        void* k_pool, void* v_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
+                        hipStream_t st);
 int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* kq_pool,
               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
               int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st,

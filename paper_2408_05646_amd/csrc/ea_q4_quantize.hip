@@ -126,6 +126,68 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
   }
 }
 
+// The inverse direction, for export and inspection: value = scale * code + zero in float, rounded once to bfloat16,
+// written in the bfloat16 pools' fragment order (padding channels zero).
+__global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
+  const Geo& g = a.g;
+  const Q4Geo& qg = a.qg;
+  const int tile = blockIdx.x, kvh = blockIdx.y;
+  const int src = a.src_pages[blockIdx.z], dst = a.dst_pages[blockIdx.z];      // src: 4-bit page, dst: bfloat16 page
+  if (src < 0 || src >= a.q4_pool_pages || dst < 0 || dst >= g.pool_pages) return;
+  const int tid = threadIdx.x;
+  const uint8_t* kb = a.kq_pool + (int64_t)src * qg.k_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.k_tile;
+  const uint8_t* vb = a.vq_pool + (int64_t)src * qg.v_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.v_tile;
+  uint16_t* ko = const_cast<uint16_t*>(a.k_pool) + (int64_t)dst * g.k_page + (int64_t)kvh * g.k_slab;
+  uint16_t* vo = const_cast<uint16_t*>(a.v_pool) + (int64_t)dst * g.v_page + (int64_t)kvh * g.v_slab;
+  auto to_bf16 = [](float f) -> uint16_t {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7fffu + ((u >> 16) & 1u);                       // round to nearest even (finite inputs)
+    return (uint16_t)(u >> 16);
+  };
+  for (int e = tid; e < kTile * g.r_k_pad; e += 256) {
+    const int tt = e / g.r_k_pad, c = e % g.r_k_pad;
+    float val = 0.f;
+    if (c < g.r_k) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c));
+      const _Float16* sp = reinterpret_cast<const _Float16*>(kb + q4_k_scale_off(qg, c));
+      val = fmaf((float)sp[0], (float)((w >> q4_nibble_shift(c & 7)) & 15u), (float)sp[8]);
+    }
+    ko[bf16_k_slab_off(tile * kTile + tt, c, g.r_k_pad)] = to_bf16(val);
+  }
+  for (int e = tid; e < kTile * g.r_v_pad; e += 256) {
+    const int tt = e / g.r_v_pad, c = e % g.r_v_pad;
+    float val = 0.f;
+    if (c < g.r_v) {
+      int slot;
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt, c, &slot));
+      const _Float16* sp = reinterpret_cast<const _Float16*>(vb + q4_v_scale_off(qg, tt));
+      val = fmaf((float)sp[0], (float)((w >> q4_nibble_shift(slot)) & 15u), (float)sp[64]);
+    }
+    vo[bf16_v_slab_off(tile * kTile + tt, c, g.r_v_pad)] = to_bf16(val);
+  }
+}
+
+int dequantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* kq_pool, const void* vq_pool, const int32_t* src_pages,
+                        void* k_pool, void* v_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
+                        hipStream_t st) {
+  if (g.n_kv_heads > 65535) return EA_ERR_SHAPE;
+  QuantArgs a;
+  a.k_pool = (const uint16_t*)k_pool;
+  a.v_pool = (const uint16_t*)v_pool;
+  a.kq_pool = (uint8_t*)const_cast<void*>(kq_pool);
+  a.vq_pool = (uint8_t*)const_cast<void*>(vq_pool);
+  a.g = g;
+  a.qg = qg;
+  a.q4_pool_pages = q4_pool_pages;
+  for (int32_t done = 0; done < n_pages; done += 65535) {
+    const int32_t now = n_pages - done < 65535 ? n_pages - done : 65535;
+    a.src_pages = src_pages + done;
+    a.dst_pages = dst_pages + done;
+    dequantize_q4_kernel<<<dim3(qg.tiles_per_page, g.n_kv_heads, now), dim3(256), 0, st>>>(a);
+  }
+  return launch_status();
+}
+
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
                       void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
                       hipStream_t st) {

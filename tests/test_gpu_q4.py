@@ -523,3 +523,31 @@ def test_q4_generation_lifecycle():
         quantise_full_pages(lens)
     assert n_q4 == [128, 128] and lens == [140, 140]
     print(f"  worst step rel-L2 {worst:.2e}", flush=True)
+
+
+def test_dequantize_pages_round_trip():
+    """quantise -> dequantise through the library = the oracle's quantise -> dequantise, rounded once to bfloat16
+    (read back through ea_cache_gather); padding channels come back as zeros."""
+    desc = ea.LayerDesc(256, 2, 2, 128, 72, 40, ea.EA_BF16, 128)
+    g = synth.rng(49)
+    lens = [256, 128]
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    qc = Q4Cache(desc, K, V, lens, g)               # every page quantised, the bf16 pages poisoned
+    dc = qc.dc
+    src = [int(qc.q4_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    dst = [int(dc.page_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    ea.dequantize_pages_q4(desc, qc.kq, qc.vq, torch.tensor(src, dtype=torch.int32).cuda(), dc.k_pool, dc.v_pool,
+                           torch.tensor(dst, dtype=torch.int32).cuda())
+    torch.cuda.synchronize()
+    for b in range(2):
+        kd = torch.zeros((1, 2, lens[b], 72), dtype=torch.bfloat16, device="cuda")
+        vd = torch.zeros((1, 2, lens[b], 40), dtype=torch.bfloat16, device="cuda")
+        ea.cache_gather(desc, kd, vd, dc.k_pool, dc.v_pool, dc.page_table[b:b + 1].contiguous())
+        torch.cuda.synchronize()
+        Kq, Vq = oq.quantized_view(K[b], V[b], lens[b])
+        assert np.array_equal(kd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Kq)))
+        assert np.array_equal(vd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Vq)))
+    lay = ea.cache_layout_query(desc)
+    page = dc.k_pool[dst[0]].float().cpu().numpy()
+    pad = [ea.cache_k_index(desc, 0, 1, 5, 71) + 1 + i for i in range(lay.r_k_pad - 72)] if lay.r_k_pad > 72 else []
+    assert np.isfinite(page).all() and all(page[i] == 0 for i in pad)

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 32
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 33
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -307,6 +307,12 @@ def test_q4_entry_points_reject_bad_arguments_before_launching():
     assert quant(kq=ODD_PTR) == -3
     assert quant(dd=desc(dtype=ea.EA_F32, P=64)) == -2                     # bf16 layers only
     assert quant(n=0) == 0                                                 # nothing to do, nothing launched
+
+    def dequant(dd=d, kq=OK_PTR, src=OK_PTR, n=3, qpool=8, pool=8):
+        return lib.ea_dequantize_pages_q4(ctypes.byref(dd), kq, OK_PTR, src, OK_PTR, OK_PTR, OK_PTR, n, qpool, pool, None)
+
+    assert dequant(src=None) == -1 and dequant(pool=0) == -1 and dequant(kq=ODD_PTR) == -3 and dequant(n=0) == 0
+    assert dequant(dd=desc(dtype=ea.EA_F32, P=64)) == -2
 
     def dec(dd=d, q=OK_PTR, kq=OK_PTR, tail_pt=OK_PTR, tail_len=OK_PTR, k=OK_PTR, max_tail=2, pool=8, n_splits=2,
             ws=OK_PTR, ws_bytes=1 << 30, max_q=4):
