@@ -551,3 +551,24 @@ def test_dequantize_pages_round_trip():
     page = dc.k_pool[dst[0]].float().cpu().numpy()
     pad = [ea.cache_k_index(desc, 0, 1, 5, 71) + 1 + i for i in range(lay.r_k_pad - 72)] if lay.r_k_pad > 72 else []
     assert np.isfinite(page).all() and all(page[i] == 0 for i in pad)
+
+
+def test_q4_len_remainder_is_ignored_and_auto_splits():
+    """q4_len counts whole 64-token groups only (a key group has no scale before it is complete): a length of
+    190 attends 128 tokens of the 4-bit part; n_splits = 0 lets the library choose."""
+    desc = ea.LayerDesc(512, 4, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(50)
+    lens = [256, 192]
+    K, V = offset_cache(desc, lens, g)
+    q = np.float32(synth.gaussian(g, (2, 4, 80))).astype(np.float64)
+    qc = Q4Cache(desc, K, V, lens, g)
+    qc.q4_len = torch.tensor([190, 192], dtype=torch.int32).cuda()
+    B = 2
+    out = torch.full((B, 4, 48), float("nan"), dtype=torch.float32, device="cuda")
+    S = ea.decode_auto_splits(desc, B, qc.max_q4_pages * 64)
+    ws = torch.empty(ea.decode_q4_workspace_bytes(desc, B, S) // 4, dtype=torch.float32, device="cuda")
+    ea.decode_attn_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len, None,
+                      None, None, None, out, 0, ws)
+    torch.cuda.synchronize()
+    ref = oracle_q4(desc, [K[0][:, :128], K[1]], [V[0][:, :128], V[1]], q, [128, 192])
+    assert_close(out.cpu().numpy(), ref, TOL_BF16, "q4 remainder")
