@@ -27,7 +27,9 @@ struct PrefillArgs {
   int32_t n_q;
   int32_t batch;
   int32_t n_qtiles;   // query tiles per (sequence, head) = gridDim.x / (H * batch)
-  int32_t k_compact;  // K pages are not looked up: logical page lp of sequence b is page b*max_pages + lp of k_pool
+  // Operands prepared by the rotary path: K pages are not looked up (logical page lp of sequence b is page
+  // b*max_pages + lp of k_pool) and the query already carries the factor log2(e)/sqrt(d_head).
+  int32_t k_compact;
   const float* alibi; // [H] ALiBi slopes (natural-log units, >= 0), ALIBI kernels only
   float scale_log2;
 };
@@ -42,10 +44,13 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
                                              const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
                                              f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad,
                                              float slope, int dist0) {
+  // The query arrives already multiplied by log2(e)/sqrt(d_head), and the score accumulators start at minus the
+  // reference exponent: what the matrix cores return is the argument of exp2, no vector instruction in between.
+  const float m_base = m == -INFINITY ? 0.f : m;
   f32x4 s[4];
 #pragma unroll
   for (int tb = 0; tb < 4; ++tb) {
-    s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    s[tb] = f32x4{-m_base, -m_base, -m_base, -m_base};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
@@ -54,8 +59,7 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s[tb][i] = fmaf(s[tb][i], scale_log2, fmaf(slope, (float)(tb * 16 + i), base));
-    scale_log2 = 1.0f;                                       // the scores are final from here on
+      for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(slope, (float)(tb * 16 + i), base);
   }
   float mx = -INFINITY;
 #pragma unroll
@@ -65,28 +69,29 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
       if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
       mx = fmaxf(mx, s[tb][i]);
     }
-  mx = quad_column_max(mx) * scale_log2;                     // the scale is positive: max commutes with it
+  mx = quad_column_max(mx);                                  // relative to m_base
   // m is a reference exponent, not the exact running max: it only moves when the max has grown by more
   // than kLazy (log2 units), so P stays <= 2^kLazy -- harmless in bf16 / fp32 -- and the accumulators are
   // rescaled a handful of times per query instead of at every tile.  The final o = acc / l is unchanged.
-  if (__any(mx > m + kLazy)) {
-    const float m_new = fmaxf(m, mx);
+  if (__any(m == -INFINITY ? mx > -INFINITY : mx > kLazy)) {
+    const float m_new = fmaxf(m, mx + m_base);
     const float m_safe = m_new == -INFINITY ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m - m_safe);   // m = -inf -> 0
+    const float delta = m_safe - m_base;
     lacc *= alpha;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb) s[tb] -= delta;
     m = m_new;
   }
-  const float m_use = (MASKED && m == -INFINITY) ? 0.f : m;
   bf16x8 pf[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u)
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], scale_log2, -m_use));
+      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
   lacc = mfma16(ones, pf[0], lacc);
   lacc = mfma16(ones, pf[1], lacc);
 #pragma unroll
@@ -177,6 +182,11 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
     for (int ks = 0; ks < KS; ++ks) {
       const int k = ks * 32 + quad * 8;
       qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
+      // the softmax scale goes into the query (one more rounding to bfloat16, of the size of P's own)
+      if (!a.k_compact) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) qf[qb][ks][j] = (__bf16)((float)qf[qb][ks][j] * a.scale_log2);
+      }
     }
   }
   bf16x8 ones;

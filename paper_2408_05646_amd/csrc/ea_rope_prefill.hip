@@ -97,10 +97,11 @@ __global__ __launch_bounds__(256) void rope_expand_kernel(RopeExpandArgs a) {
   (void)nck_dst;
 }
 
-// q [B, n, H, d_head] bf16 -> the same rotated to position seq_len[b] - n + j; one thread per 8 channels.
+// q [B, n, H, d_head] bf16 -> the same rotated to position seq_len[b] - n + j and multiplied by `scale` (the
+// softmax scale in log2 units, which the attention kernel expects inside the query); one thread per 8 channels.
 __global__ void rope_rotate_q_kernel(const uint16_t* __restrict__ q, uint16_t* __restrict__ q_rot,
                                      const int32_t* __restrict__ seq_len, int32_t B, int32_t n, int32_t H,
-                                     int32_t d_head, int32_t max_tokens, double log2_base) {
+                                     int32_t d_head, int32_t max_tokens, double log2_base, float scale) {
   __shared__ double turns_of[128];                               // theta_pair / (2 pi), once per workgroup
   if (threadIdx.x < (d_head >> 1))
     turns_of[threadIdx.x] = exp2(-(2.0 * (double)threadIdx.x / (double)d_head) * log2_base) * 0.15915494309189535;
@@ -122,7 +123,7 @@ __global__ void rope_rotate_q_kernel(const uint16_t* __restrict__ q, uint16_t* _
     for (int i = 0; i < 4; ++i) {
       float c, s;
       rot_turns((double)pos * turns_of[u * 4 + i], c, s);
-      const float x0 = (float)x[2 * i], x1 = (float)x[2 * i + 1];
+      const float x0 = (float)x[2 * i] * scale, x1 = (float)x[2 * i + 1] * scale;
       y[2 * i] = (__bf16)(x0 * c - x1 * s);
       y[2 * i + 1] = (__bf16)(x0 * s + x1 * c);
     }
@@ -180,7 +181,8 @@ int prefill_rope_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const
   const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
   rope_rotate_q_kernel<<<dim3((uint32_t)blocks), 256, 0, st>>>((const uint16_t*)q, q_rot, seq_len, B, n, d->n_heads,
                                                                d->d_head, cap > INT32_MAX ? INT32_MAX : (int32_t)cap,
-                                                               a.log2_base);
+                                                               a.log2_base,
+                                                               1.4426950408889634f / sqrtf((float)d->d_head));
   rc = launch_status();
   if (rc != EA_OK) return rc;
   // the position-free kernel at rank d_head on the rotated operands; K pages are addressed without a lookup
