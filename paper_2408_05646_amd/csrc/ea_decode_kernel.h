@@ -126,7 +126,8 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const int k = ks * 32 + quad * 8 + j;
-        const float v = (col < G && k < g.r_k) ? qrow[k] : 0.f;
+        // times log2(e)/sqrt(d_head): the scores then come out of the matrix cores in log2 units
+        const float v = (col < G && k < g.r_k) ? qrow[k] * a.scale_log2 : 0.f;
         const __bf16 hi = (__bf16)v;
         qhi[ks][j] = hi;
         qlo[ks][j] = (__bf16)(v - (float)hi);
@@ -165,7 +166,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int j = kk * 16 + quad * 4 + i;
-        const float g0 = qrow[2 * j], g1 = qrow[2 * j + 1];
+        const float g0 = qrow[2 * j] * a.scale_log2, g1 = qrow[2 * j + 1] * a.scale_log2;
         const float q0 = col < G ? g0 : 0.f, q1 = col < G ? g1 : 0.f;
         float c, sn;
         rot_turns(rel * sm.rp.turns[j], c, sn);
@@ -343,10 +344,12 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
     // loop; an index it cannot see through makes it read them where they are used.
     int tl = lane;
     if constexpr (ROPE) asm volatile("" : "+v"(tl));
+    // the accumulators start at minus the reference exponent: what comes out is the argument of exp2
+    const float m_base = m == -INFINITY ? 0.f : m;
     if constexpr (!ROPE) {
 #pragma unroll
       for (int tb = 0; tb < TBN; ++tb) {
-        s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        s[tb] = f32x4{-m_base, -m_base, -m_base, -m_base};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
           s[tb] = mfma16(kf[tb][ks], qhi[ks], s[tb]);
@@ -355,7 +358,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       }
     } else {
 #pragma unroll
-      for (int tb = 0; tb < TBN; ++tb) s[tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int tb = 0; tb < TBN; ++tb) s[tb] = f32x4{-m_base, -m_base, -m_base, -m_base};
 #pragma unroll
       for (int kk = 0; kk < NK1; ++kk) {
         // K'^T (32 of the d_head channels x 16 tokens) = U^K . k_r^T: lane (col, quad) receives, of token col,
@@ -411,15 +414,13 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 
     // ---- online softmax on s (lane: head column `col`, tokens tb*16 + 4*quad + i)
     if constexpr (ALIBI) {
-      // s <- s * scale + slope * (t - pos_q) in log2 units; from here on the scores are final
+      // s <- s + slope * (t - pos_q) in log2 units
       const float base = alibi_slope * (float)(cur.tile * kTile + cur.sub * TOK + quad * 4 - pos_q);
 #pragma unroll
       for (int tb = 0; tb < TBN; ++tb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          s[tb][i] = fmaf(s[tb][i], a.scale_log2, fmaf(alibi_slope, (float)(tb * 16 + i), base));
+        for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(alibi_slope, (float)(tb * 16 + i), base);
     }
-    const float score_scale = ALIBI ? 1.0f : a.scale_log2;
     float mx = -INFINITY;
 #pragma unroll
     for (int tb = 0; tb < TBN; ++tb) {
@@ -429,27 +430,28 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
         mx = fmaxf(mx, s[tb][i]);
       }
     }
-    mx = quad_column_max(mx) * score_scale;                   // the scale is positive: max commutes with it
+    mx = quad_column_max(mx);                                 // relative to m_base
     // m is a reference exponent: it moves only when the max has grown by more than kLazy (log2 units), so
     // P stays <= 2^kLazy and the accumulators are rescaled a few times per stream, not at every tile.
-    if (__any(mx > m + kLazy)) {
-      const float m_new = fmaxf(m, mx);
+    if (__any(m == -INFINITY ? mx > -INFINITY : mx > kLazy)) {
+      const float m_new = fmaxf(m, mx + m_base);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m - m_safe);  // m = -inf -> 0
+      const float delta = m_safe - m_base;
       lacc *= alpha;
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
+#pragma unroll
+      for (int tb = 0; tb < TBN; ++tb) s[tb] -= delta;
       m = m_new;
     }
-    const float m_use = m == -INFINITY ? 0.f : m;
     bf16x8 pf[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(fmaf(s[2 * u + h][i], score_scale, -m_use));
+        for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
       }
     }
     if (rem < TOK) {
