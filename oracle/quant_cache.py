@@ -98,13 +98,14 @@ def quantized_view(K, V, n_quant: int):
     return Kq, Vq
 
 
-def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int):
+def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_slopes=None):
     """Generation-phase attention (Eq. 3 in the rank-r space) of one new token per sequence over a cache whose
-    first n_quant[b] tokens are quantised: plain attention over the dequantised values.
+    first n_quant[b] tokens are quantised: plain attention over the dequantised values (with the ALiBi bias of the
+    MPT models when slopes are given: it involves positions only, so quantisation does not touch it).
     q_r [B, H, r_k]; K_list[b] [H_kv, n_b, r_k]; V_list[b] [H_kv, n_b, r_v]."""
     views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
-    return ea_oracle.decode_attention(q_r, cache, d_head)
+    return ea_oracle.decode_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)
 
 
 def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0):

@@ -218,3 +218,20 @@ def test_rotary_attention_over_a_quantised_cache():
         ref = (w[:, None] * np.array(vals)).sum(axis=0) / w.sum()
         assert np.allclose(got[0, h], ref, rtol=0, atol=1e-12)
     assert 1e-3 < ora.rel_l2(got, plain) < 0.3
+
+
+def test_alibi_attention_over_a_quantised_cache():
+    """The bias is added to the scores of the dequantised keys, by distance to the newest token: brute force."""
+    g = synth.rng(109)
+    H, r, d_h, n = 2, 8, 16, 70
+    q = synth.gaussian(g, (1, H, r))
+    K = [synth.gaussian(g, (1, n, r))]
+    V = [synth.gaussian(g, (1, n, r))]
+    slopes = np.array([0.5, 0.0625])
+    got = oq.decode_attention_quantized(q, K, V, [64], d_h, alibi_slopes=slopes)
+    Kq, Vq = oq.quantized_view(K[0], V[0], 64)
+    for h in range(H):
+        sc = np.array([Kq[0, t] @ q[0, h] / np.sqrt(d_h) - slopes[h] * (n - 1 - t) for t in range(n)])
+        w = np.exp(sc - sc.max())
+        assert np.allclose(got[0, h], (w[:, None] * Vq[0]).sum(axis=0) / w.sum(), rtol=0, atol=1e-12)
+    assert ora.rel_l2(got, oq.decode_attention_quantized(q, K, V, [64], d_h)) > 0.05
