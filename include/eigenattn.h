@@ -336,6 +336,21 @@ EA_API int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r,
                     float* dev_out, int32_t B, int32_t n_splits,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* ea_decode_attn_q4 with the ALiBi position bias (as ea_decode_attn_alibi): the score
+ * of the cached token at position j becomes q_r . K_r[j] / sqrt(d_h) - slope_h * (i - j),
+ * i = q4_len[b] + tail_len[b] - 1 the position of the newest token; token t of the
+ * 4-bit part sits at position t, token t of the tail at q4_len[b] + t (q4_len[b] a
+ * multiple of 64).  dev_slopes [H] float, >= 0. */
+EA_API int ea_decode_attn_alibi_q4(const ea_layer_desc* desc, const float* dev_q_r, const float* dev_slopes,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    float* dev_out, int32_t B, int32_t n_splits,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama
  * models of the paper's quantisation experiment are of this kind): the 4-bit pools
  * hold the quantised rank-r keys k_r = k U^K of the one shared basis; every key is

@@ -18,7 +18,7 @@ __all__ = [
     "packed_weight_elems", "pack_weight", "project_qkv", "decode_auto_splits", "decode_workspace_bytes", "decode_attn", "prefill_attn", "out_proj",
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
-    "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4",
+    "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -29,7 +29,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_attn", "ea_decode_rope_auto_splits", "ea_decode_attn_rope", "ea_prefill_attn", "ea_prefill_rope_workspace_bytes", "ea_prefill_attn_rope",
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
-    "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4",
+    "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
 )
 
 
@@ -122,6 +122,8 @@ def load_library():
     lib.ea_decode_q4_workspace_bytes.restype = I64
     lib.ea_decode_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
+    lib.ea_decode_attn_alibi_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64,
+                                            VP]
     lib.ea_decode_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
                                            VP, I32, I32, VP, I64, VP]
     _LIB = lib
@@ -490,10 +492,13 @@ def decode_q4_workspace_bytes(desc, B: int, n_splits: int) -> int:
 
 
 def decode_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
-                   n_splits: int, ws, stream=None) -> None:
+                   n_splits: int, ws, stream=None, alibi_slopes=None) -> None:
     """q_r [B, H, r_k] float32 -> out [B, H, r_v] float32 over q4_len[b] tokens of the 4-bit pools followed by
-    tail_len[b] tokens of the bfloat16 pools (k_pool, v_pool, tail_page_table, tail_len may all be None)."""
+    tail_len[b] tokens of the bfloat16 pools (k_pool, v_pool, tail_page_table, tail_len may all be None).
+    With alibi_slopes ([H] float32) the ALiBi bias is added (ea_decode_attn_alibi_q4)."""
     import torch
+    if alibi_slopes is not None:
+        _slopes(desc, alibi_slopes)
     B = q4_len.shape[0]
     if q_r.dtype != torch.float32 or out.dtype != torch.float32:
         raise ValueError("q_r and out must be float32")
@@ -506,12 +511,22 @@ def decode_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v
         _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
         _i32(tail_page_table, "tail_page_table"); _i32(tail_len, "tail_len")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
-    rc = load_library().ea_decode_attn_q4(
-        ctypes.byref(desc), _ptr(q_r), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
-        q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool) if tail else None, _ptr(v_pool) if tail else None,
-        _ptr(tail_page_table), _ptr(tail_len) if tail else None, tail_page_table.shape[1] if tail else 0,
-        k_pool.shape[0] if tail else 0, _ptr(out), B, n_splits, _ptr(ws), ws_bytes, _stream(stream))
-    _check(rc, "ea_decode_attn_q4")
+    rest = (_ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
+            q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool) if tail else None, _ptr(v_pool) if tail else None,
+            _ptr(tail_page_table), _ptr(tail_len) if tail else None, tail_page_table.shape[1] if tail else 0,
+            k_pool.shape[0] if tail else 0, _ptr(out), B, n_splits, _ptr(ws), ws_bytes, _stream(stream))
+    if alibi_slopes is None:
+        _check(load_library().ea_decode_attn_q4(ctypes.byref(desc), _ptr(q_r), *rest), "ea_decode_attn_q4")
+    else:
+        _check(load_library().ea_decode_attn_alibi_q4(ctypes.byref(desc), _ptr(q_r), _ptr(alibi_slopes), *rest),
+               "ea_decode_attn_alibi_q4")
+
+
+def decode_attn_alibi_q4(desc, q_r, slopes, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table,
+                         tail_len, out, n_splits: int, ws, stream=None) -> None:
+    """decode_attn_q4 with the ALiBi bias -slopes[h] * (distance of the key to the newest token)."""
+    decode_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
+                   n_splits, ws, stream=stream, alibi_slopes=slopes)
 
 
 def decode_attn_rope_q4(desc, q, u_k, rope_base: float, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool,

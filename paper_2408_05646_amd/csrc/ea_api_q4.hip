@@ -112,7 +112,8 @@ int64_t ea_decode_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32
   return ws_floats(B, desc->n_heads, n_splits + 1, round_up(desc->r_v, 16)) * (int64_t)sizeof(float);
 }
 
-int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_kq_pool, const void* dev_vq_pool,
+static int decode_attn_q4_impl(const ea_layer_desc* desc, const float* dev_q_r, const float* dev_slopes, bool alibi,
+                      const void* dev_kq_pool, const void* dev_vq_pool,
                       const int32_t* dev_q4_page_table, const int32_t* dev_q4_len, int32_t max_q4_pages,
                       int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
                       const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
@@ -121,6 +122,7 @@ int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const voi
   int rc = validate_q4(desc);
   if (rc != EA_OK) return rc;
   if (!dev_q_r || !dev_kq_pool || !dev_vq_pool || !dev_q4_page_table || !dev_q4_len || !dev_out) return EA_ERR_ARG;
+  if (alibi && !dev_slopes) return EA_ERR_ARG;
   const bool tail = dev_tail_page_table != nullptr || dev_tail_len != nullptr;
   if (tail && (!dev_tail_page_table || !dev_tail_len || !dev_k_pool || !dev_v_pool || max_tail_pages <= 0 ||
                pool_pages <= 0))
@@ -142,9 +144,31 @@ int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const voi
   const Geo gt = make_geo(desc, tail ? max_tail_pages : 1, tail ? pool_pages : 1);
   rc = decode_q4(desc, gq, q4_geo_of(desc), dev_q_r, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
                  max_q4_pages, q4_pool_pages, B, n_splits, slots, (float*)dev_ws, st, tail ? &gt : nullptr, dev_k_pool,
-                 dev_v_pool, dev_tail_page_table, dev_tail_len);
+                 dev_v_pool, dev_tail_page_table, dev_tail_len, alibi ? dev_slopes : nullptr);
   if (rc != EA_OK) return rc;
   return merge_splits(gq, (const float*)dev_ws, dev_out, B, slots, st);
+}
+
+int ea_decode_attn_q4(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_kq_pool, const void* dev_vq_pool,
+                      const int32_t* dev_q4_page_table, const int32_t* dev_q4_len, int32_t max_q4_pages,
+                      int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
+                      const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
+                      int32_t pool_pages, float* dev_out, int32_t B, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                      void* stream) {
+  return decode_attn_q4_impl(desc, dev_q_r, nullptr, false, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
+                             max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len,
+                             max_tail_pages, pool_pages, dev_out, B, n_splits, dev_ws, ws_bytes, stream);
+}
+
+int ea_decode_attn_alibi_q4(const ea_layer_desc* desc, const float* dev_q_r, const float* dev_slopes,
+                            const void* dev_kq_pool, const void* dev_vq_pool, const int32_t* dev_q4_page_table,
+                            const int32_t* dev_q4_len, int32_t max_q4_pages, int32_t q4_pool_pages,
+                            const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_tail_page_table,
+                            const int32_t* dev_tail_len, int32_t max_tail_pages, int32_t pool_pages, float* dev_out,
+                            int32_t B, int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream) {
+  return decode_attn_q4_impl(desc, dev_q_r, dev_slopes, true, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
+                             max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len,
+                             max_tail_pages, pool_pages, dev_out, B, n_splits, dev_ws, ws_bytes, stream);
 }
 
 int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,

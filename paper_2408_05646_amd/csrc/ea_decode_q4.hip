@@ -32,9 +32,13 @@ struct DecodeQ4Args {
   int32_t n_batch;
   int32_t has_tail;     // further grid slices attend the bfloat16 tail described by `tail`
   DecodeArgs tail;
+  // ALiBi variant only: slopes [H] (natural-log units, >= 0); the newest token (the query) is the last one of the
+  // tail, or of the 4-bit part when there is no tail
+  const float* alibi;
+  const int32_t* tail_len;
 };
 
-template <int KS, int NCB>
+template <int KS, int NCB, bool ALIBI>
 __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   __shared__ union {
     MergeSmemQ4<NCB> q4;
@@ -50,7 +54,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
     // workgroups) attend the bfloat16 tails: one workgroup per (sequence, kv head).
     const int t = ((b - a.n_batch) * a.n_splits + split) * g.n_kv_heads + kvh;
     const int tb = t / g.n_kv_heads;
-    if (tb < a.n_batch) decode_bf16_body<KS, NCB, 2, 2, 0, false>(a.tail, t % g.n_kv_heads, 0, tb, a.n_batch, smu.tail);
+    if (tb < a.n_batch) decode_bf16_body<KS, NCB, 2, 2, 0, ALIBI>(a.tail, t % g.n_kv_heads, 0, tb, a.n_batch, smu.tail);
     return;
   }
   MergeSmemQ4<NCB>& sm = smu.q4;
@@ -71,6 +75,14 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   const int t_begin = split * per;
   const int t_end = min(n_tiles, t_begin + per);
   const int tiles_per_page = qg.tiles_per_page;
+  float alibi_slope = 0.f;       // this lane's head, log2 units
+  int pos_q = 0;                 // position of the query
+  if constexpr (ALIBI) {
+    alibi_slope = col < G ? a.alibi[kvh * G + col] * 1.4426950408889634f : 0.f;
+    int64_t tail = a.tail_len ? (int64_t)((const_i32_ptr)a.tail_len)[b] : 0;
+    if (tail < 0) tail = 0;
+    pos_q = (int)((int64_t)n_tiles * kTile + tail - 1);
+  }
 
   // B operand of the score product: q^T in fp16, already times log2(e)/sqrt(d_head); lane (col, quad) holds
   // channels 32*ks + 8*quad .. +7 of head col.
@@ -199,6 +211,14 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
     // registers for the path on which nothing is loaded
     load_k(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
 
+    if constexpr (ALIBI) {
+      // s <- s + slope * (t - pos_q) in log2 units
+      const float base = alibi_slope * (float)(cur.tile * kTile + quad * 4 - pos_q);
+#pragma unroll
+      for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(alibi_slope, (float)(tb * 16 + i), base);
+    }
     if (page < 0) {
       // a page that is not there: its tokens do not take part, and the scales read from page 0 are dropped
       asm volatile("");
@@ -296,7 +316,9 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
 template <int KS, int NCB>
 static void launch_q4(const DecodeQ4Args& a, int32_t B, hipStream_t st) {
   const int extra = a.has_tail ? (B + a.n_splits - 1) / a.n_splits : 0;
-  decode_q4_kernel<KS, NCB><<<dim3(a.g.n_kv_heads, a.n_splits, B + extra), dim3(256), 0, st>>>(a);
+  const dim3 grid(a.g.n_kv_heads, a.n_splits, B + extra);
+  if (a.alibi) decode_q4_kernel<KS, NCB, true><<<grid, dim3(256), 0, st>>>(a);
+  else decode_q4_kernel<KS, NCB, false><<<grid, dim3(256), 0, st>>>(a);
 }
 
 template <int KS>
@@ -319,7 +341,7 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
               int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st,
               const Geo* tail_geo, const void* k_pool, const void* v_pool, const int32_t* tail_page_table,
-              const int32_t* tail_len) {
+              const int32_t* tail_len, const float* alibi_slopes) {
   if (2 * B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   DecodeQ4Args a;
   a.q = q;
@@ -337,6 +359,8 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
   a.has_tail = tail_geo != nullptr;
   a.n_batch = B;
+  a.alibi = alibi_slopes;
+  a.tail_len = tail_geo ? tail_len : nullptr;
   a.tail = DecodeArgs{};
   if (tail_geo) {
     a.tail.q = q;
@@ -352,7 +376,7 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
     a.tail.u_k = nullptr;
     a.tail.d_head = d->d_head;
     a.tail.log2_base = 0.0;
-    a.tail.alibi = nullptr;
+    a.tail.alibi = alibi_slopes;
     a.tail.ws_slots = ws_slots;
     a.tail.ws_slot0 = n_splits;
   }

@@ -107,7 +107,8 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, int32_t max_q4_pages,
               int32_t q4_pool_pages, int32_t B, int32_t n_splits, int32_t ws_slots, float* ws, hipStream_t st,
               const Geo* tail_geo, const void* k_pool, const void* v_pool, const int32_t* tail_page_table,
-              const int32_t* tail_len);     // tail_geo == nullptr: no bfloat16 tail
+              const int32_t* tail_len,      // tail_geo == nullptr: no bfloat16 tail
+              const float* alibi_slopes = nullptr);
 int decode_rope_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* u_k,
                    double rope_base, const void* kq_pool, const void* vq_pool, const int32_t* q4_page_table,
                    const int32_t* q4_len, const int32_t* tail_len, int32_t max_q4_pages, int32_t q4_pool_pages,

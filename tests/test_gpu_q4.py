@@ -572,3 +572,43 @@ def test_q4_len_remainder_is_ignored_and_auto_splits():
     torch.cuda.synchronize()
     ref = oracle_q4(desc, [K[0][:, :128], K[1]], [V[0][:, :128], V[1]], q, [128, 192])
     assert_close(out.cpu().numpy(), ref, TOL_BF16, "q4 remainder")
+
+
+# ---------------------------------------------------------------------------
+# ALiBi variant: ea_decode_attn_alibi_q4
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,lens,n_quant,n_splits,with_tail", [
+    (8, 2, 80, 48, 64, [777, 64, 1500], [768, 64, 1472], 0, True),
+    (4, 4, 128, 128, 64, [513, 100], [512, 64], 2, True),
+    (16, 1, 96, 64, 128, [3000], [2944], 4, True),
+    (2, 2, 72, 40, 64, [0, 65], [0, 64], 1, True),
+    (4, 2, 30, 33, 64, [256, 128], [256, 128], 2, False),      # no bfloat16 part: the query is the last 4-bit token
+])
+def test_decode_alibi_q4_matches_oracle(H, Hkv, r_k, r_v, P, lens, n_quant, n_splits, with_tail):
+    from oracle import eigen_attention as ora
+    print(f"q4 alibi decode H={H}/{Hkv} r=({r_k},{r_v}) P={P} lens={lens} quantised={n_quant} S={n_splits}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(51, H, r_k, len(lens))
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    B = len(lens)
+    q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+    slopes = np.float32(2.0 ** (-8.0 * (np.arange(H) + 1) / H)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    out = torch.full((B, H, r_v), float("nan"), dtype=torch.float32, device="cuda")
+    S = n_splits if n_splits else ea.decode_auto_splits(desc, B, qc.max_q4_pages * P)
+    ws = torch.full((ea.decode_q4_workspace_bytes(desc, B, S) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    dc = qc.dc
+    tail = (dc.k_pool, dc.v_pool, qc.tail_table, qc.tail_len) if with_tail else (None, None, None, None)
+    ea.decode_attn_alibi_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(),
+                            torch.from_numpy(slopes.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len,
+                            *tail, out, S, ws)
+    torch.cuda.synchronize()
+    keep = [b for b in range(B) if lens[b] > 0]
+    ref = np.zeros((B, H, r_v))
+    ref[keep] = oq.decode_attention_quantized(q[keep], [K[b] for b in keep], [V[b] for b in keep],
+                                              [n_quant[b] for b in keep], 128, alibi_slopes=slopes)
+    err = assert_close(out.cpu().numpy(), ref, TOL_BF16, "q4 alibi decode")
+    flat = oq.decode_attention_quantized(q[keep], [K[b] for b in keep], [V[b] for b in keep],
+                                         [n_quant[b] for b in keep], 128)
+    assert ora.rel_l2(flat, ref[keep]) > 0.05       # the bias matters on these inputs
+    print(f"  rel-L2 {err:.2e}", flush=True)
