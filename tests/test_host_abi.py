@@ -329,6 +329,8 @@ def test_q4_entry_points_reject_bad_arguments_before_launching():
     assert dec(ws_bytes=need - 1) == -4
     assert dec(dd=desc(dtype=ea.EA_F32, P=64)) == -2
     assert ea.decode_q4_workspace_bytes(d, 0, 2) == -1
+    assert lib.ea_decode_attn_alibi_q4(ctypes.byref(d), OK_PTR, None, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, OK_PTR, OK_PTR,
+                                       OK_PTR, OK_PTR, 2, 8, OK_PTR, 2, 2, OK_PTR, 1 << 30, None) == -1      # no slopes
 
 
 def test_rotary_q4_entry_point_rejects_bad_arguments_before_launching():
