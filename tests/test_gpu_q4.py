@@ -612,3 +612,29 @@ def test_decode_alibi_q4_matches_oracle(H, Hkv, r_k, r_v, P, lens, n_quant, n_sp
                                          [n_quant[b] for b in keep], 128)
     assert ora.rel_l2(flat, ref[keep]) > 0.05       # the bias matters on these inputs
     print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_every_rank_shape_of_the_q4_kernels(rope):
+    """One small case per (key k-steps, value channel blocks) instantiation of the 4-bit kernels: r_k in
+    {8, 40, 72, 104} x r_v in {16, 32, ..., 128}."""
+    g = synth.rng(52, int(rope))
+    worst = 0.0
+    for r_k in (8, 40, 72, 104):
+        for r_v in range(16, 129, 16):
+            desc = ea.LayerDesc(256, 2, 1, 128, r_k, r_v, ea.EA_BF16, 64)
+            lens, n_quant = [200, 64], [128, 64]
+            K, V = offset_cache(desc, lens, g)
+            qc = Q4Cache(desc, K, V, n_quant, g)
+            print(f"q4 shapes rope={rope} r=({r_k},{r_v})", flush=True)
+            if rope:
+                U = quantize(desc, synth.orthonormal_basis(g, 128, r_k))
+                q = np.float32(synth.gaussian(g, (2, 2, 128))).astype(np.float64)
+                got = run_rope_q4(desc, qc, q, U, 10000.0, 2)
+                ref = oracle_rope_q4(desc, K, V, q, n_quant, U, 10000.0)
+            else:
+                q = np.float32(synth.gaussian(g, (2, 2, r_k))).astype(np.float64)
+                got = run_q4(desc, qc, q, 2)
+                ref = oracle_q4(desc, K, V, q, n_quant)
+            worst = max(worst, assert_close(got, ref, TOL_BF16, f"q4 shapes r=({r_k},{r_v})"))
+    print(f"  worst rel-L2 {worst:.2e}", flush=True)
