@@ -371,6 +371,28 @@ EA_API int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q,
                     float* dev_out, int32_t B, int32_t n_splits,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* ---- attention statistics for token-eviction policies ----------------------- */
+
+/* The paper combines the rank-r cache with H2O token pruning (results, "Eigen
+ * Attention with token pruning"): H2O keeps the tokens that have received the most
+ * attention so far plus the most recent ones.  What it accumulates is the softmax
+ * probability every cached token receives from each new query; in the rank-r space
+ * that is the p of Eq. (3) with Eq. (7)'s operands.  This call adds, for the queries
+ * dev_q_r [B, H, r_k] (float) of one generation step,
+ *   dev_mass[b, g, t] += sum over the query heads i of kv head g of p_i[t],  t < seq_len[b]
+ * (position-free scores, as ea_decode_attn; entries t >= seq_len[b] are not touched).
+ * The policy stays with the caller: a dropped token's slot is overwritten by the next
+ * append (pass the slot as that sequence's position to ea_project_qkv), because the
+ * position-free cache does not care where a token sits.
+ *   dev_mass [B, H_kv, max_pages * page_tokens] float
+ *   dev_ws   ea_attn_mass_workspace_bytes(desc, B, max_pages) bytes, 16-byte aligned
+ * Reads the keys once (the values not at all).  H / H_kv <= 16. */
+EA_API int64_t ea_attn_mass_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t max_pages);
+EA_API int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_k_pool,
+                    const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_mass,
+                    int32_t B, int32_t max_pages, int32_t pool_pages,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -19,6 +19,7 @@ __all__ = [
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
+    "attn_mass", "attn_mass_workspace_bytes",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -30,6 +31,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
+    "ea_attn_mass_workspace_bytes", "ea_attn_mass",
 )
 
 
@@ -122,6 +124,9 @@ def load_library():
     lib.ea_decode_q4_workspace_bytes.restype = I64
     lib.ea_decode_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
+    lib.ea_attn_mass_workspace_bytes.restype = I64
+    lib.ea_attn_mass_workspace_bytes.argtypes = [D, I32, I32]
+    lib.ea_attn_mass.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_alibi_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64,
                                             VP]
     lib.ea_decode_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
@@ -555,3 +560,28 @@ def decode_attn_rope_q4(desc, q, u_k, rope_base: float, kq_pool, vq_pool, q4_pag
         tail_page_table.shape[1] if tail else 0, k_pool.shape[0] if tail else 0, _ptr(out), B, n_splits, _ptr(ws),
         ws_bytes, _stream(stream))
     _check(rc, "ea_decode_attn_rope_q4")
+
+
+# ---- attention statistics for token-eviction policies ---------------------------
+def attn_mass_workspace_bytes(desc, B: int, max_pages: int) -> int:
+    return int(load_library().ea_attn_mass_workspace_bytes(ctypes.byref(desc), B, max_pages))
+
+
+def attn_mass(desc, q_r, k_pool, page_table, seq_len, mass, ws, stream=None) -> None:
+    """mass [B, H_kv, max_pages * page_tokens] float32 += the softmax probability every cached token receives from
+    the queries q_r [B, H, r_k] (summed over the query heads of each kv head)."""
+    import torch
+    B = seq_len.shape[0]
+    if q_r.dtype != torch.float32 or mass.dtype != torch.float32:
+        raise ValueError("q_r and mass must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k:
+        raise ValueError("q_r has the wrong size")
+    if mass.numel() != B * desc.n_kv_heads * page_table.shape[1] * desc.page_tokens:
+        raise ValueError("mass must be [B, H_kv, max_pages * page_tokens]")
+    _expect(k_pool, desc.dtype, "k_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_attn_mass(ctypes.byref(desc), _ptr(q_r), _ptr(k_pool), _ptr(page_table), _ptr(seq_len),
+                                     _ptr(mass), B, page_table.shape[1], k_pool.shape[0], _ptr(ws), ws_bytes,
+                                     _stream(stream))
+    _check(rc, "ea_attn_mass")

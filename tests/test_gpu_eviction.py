@@ -1,0 +1,143 @@
+"""ea_attn_mass (the attention statistic H2O-style eviction accumulates; results, "Eigen Attention with token
+pruning") against the fp64 oracle, and a generation loop over a fixed-budget cache whose dropped tokens' slots are
+overwritten by the new ones."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_05646_amd as ea
+from oracle import eigen_attention as ora
+from oracle import eviction as oe
+from paper_2408_05646_amd import synth
+from helpers import DeviceCache, TOL_BF16, TOL_F32, assert_close, quantize, random_cache, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def run_mass(desc, dc, q, mass=None):
+    B = q.shape[0]
+    n_cap = dc.max_pages * desc.page_tokens
+    if mass is None:
+        mass = torch.zeros((B, desc.n_kv_heads, n_cap), dtype=torch.float32, device="cuda")
+    ws = torch.full((ea.attn_mass_workspace_bytes(desc, B, dc.max_pages) // 4,), float("nan"), dtype=torch.float32,
+                    device="cuda")
+    ea.attn_mass(desc, torch.from_numpy(q.astype(np.float32)).cuda(), dc.k_pool, dc.page_table, dc.seq_len, mass, ws)
+    torch.cuda.synchronize()
+    return mass
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,r_k,lens,P", [
+    (ea.EA_F32, 4, 2, 30, [255, 256, 700, 1], 16),
+    (ea.EA_F32, 8, 8, 32, [40, 0], 48),                       # 64-token tiles that straddle pages of 48
+    (ea.EA_BF16, 2, 2, 80, [1, 63, 64, 65], 64),
+    (ea.EA_BF16, 8, 2, 48, [777, 64, 1500], 128),             # GQA 4:1
+    (ea.EA_BF16, 16, 1, 96, [300], 64),                       # 16 query heads on one kv head
+    (ea.EA_BF16, 4, 4, 128, [513, 100, 0], 64),
+    (ea.EA_BF16, 4, 2, 30, [150, 70], 64),
+    (ea.EA_BF16, 2, 1, 80, [20000], 64),                      # 313 tiles to normalise across
+])
+def test_attn_mass_matches_oracle(dtype, H, Hkv, r_k, lens, P):
+    print(f"mass dtype={dtype} H={H}/{Hkv} r_k={r_k} lens={lens} P={P}", flush=True)
+    d_h = 128 if dtype == ea.EA_BF16 else 64
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, 16, dtype, P)
+    g = synth.rng(61, H, r_k, len(lens))
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    B = len(lens)
+    q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+    dc = DeviceCache(desc, K, V, g)
+    mass = run_mass(desc, dc, q)
+    got = mass.cpu().numpy()
+    keep = [b for b in range(B) if lens[b] > 0]
+    ref = oe.attention_mass(q[keep], ora.RankCache.from_arrays([K[b] for b in keep], [V[b] for b in keep]), d_h)
+    tol = TOL_F32 if dtype == ea.EA_F32 else TOL_BF16
+    for b in range(B):
+        assert not got[b, :, lens[b]:].any(), "entries past the sequence end must stay untouched"
+    for i, b in enumerate(keep):
+        assert_close(got[b, :, :lens[b]], ref[i], tol, f"mass b={b}")
+        assert np.allclose(got[b, :, :lens[b]].sum(axis=1), H // Hkv, rtol=0, atol=1e-3)
+    # a second call accumulates
+    mass2 = run_mass(desc, dc, q, mass.clone())
+    assert torch.allclose(mass2, 2 * mass, rtol=1e-6, atol=1e-7)
+
+
+def test_attn_mass_skips_pages_that_are_not_there():
+    desc = ea.LayerDesc(256, 2, 2, 128, 80, 16, ea.EA_BF16, 64)
+    g = synth.rng(62)
+    K, V = random_cache(desc, [256], g)
+    q = np.float32(synth.gaussian(g, (1, 2, 80))).astype(np.float64)
+    dc = DeviceCache(desc, K, V, g)
+    pt = dc.page_table.clone()
+    pt[0, 1] = dc.pool_pages + 5
+    dc.page_table = pt
+    got = run_mass(desc, dc, q).cpu().numpy()[0]
+    keep = np.r_[0:64, 128:256]
+    ref = oe.attention_mass(q, ora.RankCache.from_arrays([K[0][:, keep]], [V[0][:, keep]]), 128)[0]
+    assert not got[:, 64:128].any()
+    assert_close(got[:, keep], ref, TOL_BF16, "mass with a missing page")
+
+
+def test_h2o_generation_loop_over_a_fixed_budget():
+    """A cache of `budget` slots per sequence.  Every step: project the new token into the slot the policy freed
+    (the oldest-first H2O rule on the accumulated mass, the newest n_recent tokens protected; the decision is the
+    oracle's, so that a near-tie cannot send the two sides down different paths), attend over the budget, add the
+    step's attention mass.  Outputs and accumulated masses must follow the oracle, which keeps its kept tokens
+    in a plain list."""
+    from test_gpu_layer import make_weights, device_weights
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    B, budget, n_recent, steps = 2, 128, 16, 60
+    g = synth.rng(63)
+    Wq, Wk, Wv, Wo, Uk, Uv = make_weights(desc, g)
+    wqkv_t, wo_t, folded_q = device_weights(desc, ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, 8, 2))
+    Wq_q, Wk_q, Wv_q, Wo_q = folded_q
+    x_hist = quantize(desc, synth.gaussian(g, (B, budget + steps, 512)))
+    _, k_all, v_all = ora.project_qkv(x_hist.reshape(B * (budget + steps), 512), Wq_q, Wk_q, Wv_q)
+    k_all = quantize(desc, k_all).reshape(B, budget + steps, 2, 80).transpose(0, 2, 1, 3)
+    v_all = quantize(desc, v_all).reshape(B, budget + steps, 2, 48).transpose(0, 2, 1, 3)
+
+    # the first `budget` tokens fill the cache through the library; slot s holds token s
+    dc = DeviceCache(desc, [np.zeros((2, 0, 80))] * B, [np.zeros((2, 0, 48))] * B, g, extra_len=budget)
+    q_pre = torch.empty((B * budget, 8, 80), dtype=torch.bfloat16, device="cuda")
+    ea.project_qkv(desc, to_dev(desc, x_hist[:, :budget].reshape(B * budget, 512)), wqkv_t, q_pre, dc.k_pool, dc.v_pool,
+                   dc.page_table, dc.seq_len, budget)
+    full = torch.full((B,), budget, dtype=torch.int32, device="cuda")
+    slot_token = [list(range(budget)) for _ in range(B)]          # which token sits in which slot
+    acc_ref = [np.zeros((2, budget)) for _ in range(B)]           # accumulated mass per slot, oracle
+    mass = torch.zeros((B, 2, budget), dtype=torch.float32, device="cuda")
+    ws_m = torch.empty(ea.attn_mass_workspace_bytes(desc, B, dc.max_pages) // 4, dtype=torch.float32, device="cuda")
+    q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    worst = 0.0
+    for t in range(steps):
+        tok = budget + t
+        # the policy (oracle side): drop the slot with the least mass (summed over kv heads) that is not recent
+        slots = []
+        for b in range(B):
+            age_order = np.argsort(slot_token[b])                 # slots from oldest to newest token
+            victim_rank = oe.h2o_victim(acc_ref[b].sum(axis=0)[age_order], n_recent)
+            slots.append(int(age_order[victim_rank]))
+        slot_t = torch.tensor(slots, dtype=torch.int32).cuda()
+        for b in range(B):
+            slot_token[b][slots[b]] = tok
+            acc_ref[b][:, slots[b]] = 0.0
+        mass[torch.arange(B), :, slot_t.long()] = 0.0
+        # the step: the new token goes to the freed slot (its "position"), attention runs over all slots
+        ea.project_qkv(desc, to_dev(desc, x_hist[:, tok]), wqkv_t, q_r, dc.k_pool, dc.v_pool, dc.page_table, slot_t, 1)
+        ea.decode_attn(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, full, o, n_splits=1)
+        ea.attn_mass(desc, q_r, dc.k_pool, dc.page_table, full, mass, ws_m)
+        ea.out_proj(desc, o.view(B, -1), wo_t, y)
+        torch.cuda.synchronize()
+        # oracle: the kept tokens, in slot order
+        q_ref, _, _ = ora.project_qkv(x_hist[:, tok], Wq_q, Wk_q, Wv_q)
+        cache = ora.RankCache.from_arrays([k_all[b][:, slot_token[b]] for b in range(B)],
+                                          [v_all[b][:, slot_token[b]] for b in range(B)])
+        y_ref = ora.out_proj(ora.decode_attention(q_ref, cache, 128), Wo_q)
+        step_mass = oe.attention_mass(q_ref, cache, 128)
+        for b in range(B):
+            acc_ref[b] += step_mass[b]
+        worst = max(worst, assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"h2o step {t}"))
+    got = mass.cpu().numpy()
+    for b in range(B):
+        assert_close(got[b], acc_ref[b], TOL_BF16, f"accumulated mass b={b}")
+        assert len(set(slot_token[b])) == budget and max(slot_token[b]) == budget + steps - 1
+    print(f"  worst step rel-L2 {worst:.2e}", flush=True)

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 34
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 36
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -347,3 +347,23 @@ def test_rotary_q4_entry_point_rejects_bad_arguments_before_launching():
     assert dec(dd=desc(d_h=96)) == -2                                      # d_head 64 or 128
     assert dec(dd=desc(d_h=64, r_k=80)) == -2                              # r_k <= d_head
     assert dec(dd=desc(dtype=ea.EA_F32, P=64)) == -2
+
+
+def test_attn_mass_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def mass(dd=d, q=OK_PTR, k=OK_PTR, pt=OK_PTR, out=OK_PTR, B=2, max_pages=4, pool=8, ws=OK_PTR, ws_bytes=1 << 30):
+        return lib.ea_attn_mass(ctypes.byref(dd), q, k, pt, OK_PTR, out, B, max_pages, pool, ws, ws_bytes, None)
+
+    assert mass(q=None) == -1 and mass(pt=None) == -1 and mass(out=None) == -1
+    assert mass(B=0) == -1 and mass(max_pages=0) == -1 and mass(pool=0) == -1
+    assert mass(k=ODD_PTR) == -3 and mass(out=ODD_PTR) == -3
+    assert mass(ws=None) == -4 and mass(ws=ODD_PTR) == -4
+    need = ea.attn_mass_workspace_bytes(d, 2, 4)
+    tiles = 4 * 128 // 64
+    assert need == 2 * 8 * (tiles * 64 + tiles * 2) * 4                    # e rows of whole tiles + (m, l) per tile
+    assert mass(ws_bytes=need - 1) == -4
+    assert mass(dd=desc(H=34, Hkv=2, d=34 * 128)) == -2                    # at most 16 query heads per kv head
+    assert ea.attn_mass_workspace_bytes(d, 0, 4) == -1
+    # fp32 pages of 48 tokens: the rows of e are rounded up to whole tiles
+    assert ea.attn_mass_workspace_bytes(desc(dtype=ea.EA_F32, P=48), 1, 3) == 8 * (3 * 64 + 3 * 2) * 4
