@@ -51,7 +51,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
-                             "cfg5-q4", "cfg3-rope-q4"])
+                             "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -68,7 +68,7 @@ def parse_args():
 def traffic_from_profiles(workload: str):
     """HBM bytes per decode-attention launch measured with rocprofv3 --pmc (committed summary), or None."""
     name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
-            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt"}.get(workload)
+            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt"}.get(workload)
     if name is None:
         return None
     path = os.path.join(ROOT, "profiles", name)
@@ -100,7 +100,7 @@ def _timed_single_thread(fn):
     return min(run(), run())
 
 
-def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: bool = False):
+def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: bool = False, h2o: bool = False):
     """The fp64 oracle's decode attention on `n_streams` (sequence, head) streams of the bench workload's
     shape, single-threaded BLAS, host-generated inputs with the same distribution."""
     import numpy as np
@@ -123,12 +123,16 @@ def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: boo
                 ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE)
             else:
                 ora.decode_attention(q, cache, d_head)
+                if h2o:
+                    oe.attention_mass(q, cache, d_head)
 
+    if h2o:
+        from oracle import eviction as oe
     U = synth.orthonormal_basis(g, d_head, r) if rope else None
     dt = _timed_single_thread(work) / reps
     cache_bytes = n_seq * heads * n_ctx * 2 * r * 2          # what the GPU kernel would stream (bf16)
     return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{'rotary ' if rope else ''}decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
+            "sample": f"{'rotary ' if rope else ''}decode attention {'and attention mass per cached token ' if h2o else ''}of {n_seq * heads} of one layer's 512 (sequence, head) "
                       f"streams (n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s per pass, {reps} passes timed three times "
                       f"(best kept); a full 32-layer step would take {dt * 32 * 512 / (n_seq * heads):.0f} s",
             "seconds": round(dt, 3)}
@@ -194,6 +198,7 @@ def bench_decode(args, torch, ea, synth):
     dev = "cuda"
     base_name, rope = args.workload.split("-")[0], "-rope" in args.workload
     q4 = args.workload.endswith("-q4")       # all pages but the newest of every sequence held in 4 bits
+    h2o = args.workload.endswith("-h2o")     # the step also accumulates the attention mass every cached token receives
     s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[base_name]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
     H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
@@ -263,14 +268,18 @@ def bench_decode(args, torch, ea, synth):
             u_k=(torch.linalg.qr(torch.randn((s.d_head, dc.r_k), generator=gen, device=dev))[0].contiguous()
                  .to(torch.bfloat16) if rope else None),
             o=torch.empty((B, H, dc.r_v), dtype=torch.float32, device=dev),
+            mass=torch.zeros((B, Hkv, n), dtype=torch.float32, device=dev) if h2o else None,
             y=torch.empty((B, d), dtype=torch.bfloat16, device=dev)))
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
 
     seq_before = torch.full((B,), n - 1, dtype=torch.int32, device=dev)    # the step appends token n-1 ...
     seq_after = torch.full((B,), n, dtype=torch.int32, device=dev)         # ... and attends over n tokens
-    ws_bytes = max((ea.decode_q4_workspace_bytes if q4 else ea.decode_workspace_bytes)(l["desc"], B, l["S"])
-                   for l in layers)
+    if h2o:
+        ws_bytes = max(ea.decode_attn_mass_workspace_bytes(l["desc"], B, max_pages, l["S"]) for l in layers)
+    else:
+        ws_bytes = max((ea.decode_q4_workspace_bytes if q4 else ea.decode_workspace_bytes)(l["desc"], B, l["S"])
+                       for l in layers)
     q4_len = torch.full((B,), n - P, dtype=torch.int32, device=dev)
     tail_before = torch.full((B,), P - 1, dtype=torch.int32, device=dev)
     tail_after = torch.full((B,), P, dtype=torch.int32, device=dev)
@@ -293,6 +302,9 @@ def bench_decode(args, torch, ea, synth):
             elif q4:
                 ea.decode_attn_q4(l["desc"], l["q_r"], l["kq_pool"], l["vq_pool"], l["page_table"], q4_len,
                                   l["k_pool"], l["v_pool"], l["tail_table"], tail_after, l["o"], l["S"], ws)
+            elif h2o:
+                ea.decode_attn_mass(l["desc"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_after, l["o"],
+                                    l["mass"], l["S"], ws)
             elif rope:
                 ea.decode_attn_rope(l["desc"], l["q_r"], l["u_k"], ROPE_BASE, l["k_pool"], l["v_pool"], l["page_table"],
                                     seq_after, l["o"], n_splits=l["S"], ws=ws)
@@ -355,7 +367,8 @@ def bench_decode(args, torch, ea, synth):
         else:
             cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
         attn = cache_bytes + B * H * q_dim * 4 + B * H * dc.r_v * 4 + B * max_pages * 4 + \
-            (s.d_head * dc.r_k * 2 if rope else 0)
+            (s.d_head * dc.r_k * 2 if rope else 0) + \
+            (B * Hkv * n * 8 if h2o else 0)        # the accumulator, read and written (the staged scores are overhead)
         proj = n_qkv * d * 2 + B * d * 2 + B * H * q_dim * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
         outp = H * dc.r_v * d * 2 + B * H * dc.r_v * 4 + B * d * 2
         attn_bytes_sum += attn
@@ -369,6 +382,9 @@ def bench_decode(args, torch, ea, synth):
         (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
     if q4:
         kern = "decode_q4_kernel (4-bit part and, in its last grid slices, the bf16 newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
+    if h2o:
+        kern = ("decode_bf16_kernel (score-storing form) + merge_splits_kernel + mass_from_scores_kernel "
+                "(one ea_decode_attn_mass call)")
     if q4 and rope:
         kern = ("decode_rope_q4_kernel + decode_bf16_kernel (rotary variant, newest page) + merge_splits_kernel "
                 "(one ea_decode_attn_rope_q4 call)")
@@ -389,6 +405,9 @@ def bench_decode(args, torch, ea, synth):
                                + ("rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope_q4 + out_proj "
                                   "per layer, query at position n-1, base 10000" if (q4 and rope) else
                                   "project_qkv + decode_attn_q4 + out_proj per layer" if q4 else
+                                  "project_qkv + decode_attn_mass (attention output and, for an H2O-style eviction "
+                                  "policy, the attention mass of every cached token added to a per-layer accumulator) "
+                                  "+ out_proj per layer" if h2o else
                                   "rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope + out_proj "
                                   "per layer, query at position n-1, base 10000" if rope else
                                   "project_qkv + decode_attn + out_proj per layer"),
@@ -453,8 +472,8 @@ def bench_decode(args, torch, ea, synth):
         result["cpu_baseline"] = cpu_oracle_decode_q4(args.cpu_streams // (32 if rope else 8), n, ranks[0][0], s.d_head,
                                                       P, rope=rope)
     elif not args.no_cpu:
-        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 1), n, ranks[0][0], s.d_head,
-                                                   rope=rope)
+        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 2 if h2o else 1), n, ranks[0][0],
+                                                   s.d_head, rope=rope, h2o=h2o)
     return result
 
 

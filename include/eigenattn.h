@@ -393,6 +393,20 @@ EA_API int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const v
                     int32_t B, int32_t max_pages, int32_t pool_pages,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* ea_decode_attn and ea_attn_mass in one pass over the cache (bfloat16 layers; the position-free form): the
+ * attention kernel also stores its scaled scores, the split merge each row's maximum and normaliser, and a
+ * last kernel turns the scores into probabilities and adds them to dev_mass -- so the keys are read once for
+ * the output and the statistic.  Arguments as in ea_decode_attn plus dev_mass as in ea_attn_mass.
+ *   n_splits 0 = ea_decode_auto_splits; dev_ws ea_decode_attn_mass_workspace_bytes(desc, B, max_pages, n_splits)
+ *   bytes (n_splits >= 1 there), 16-byte aligned, always required.  EA_F32 layers: EA_ERR_SHAPE (call the two
+ *   separately).  H / H_kv <= 16. */
+EA_API int64_t ea_decode_attn_mass_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t max_pages,
+                                                   int32_t n_splits);
+EA_API int ea_decode_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_k_pool,
+                           const void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                           float* dev_out, float* dev_mass, int32_t B, int32_t max_pages, int32_t pool_pages,
+                           int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -19,7 +19,7 @@ __all__ = [
     "strerror", "version", "alloc_pools", "EXPORTED_SYMBOLS", "decode_attn_rope", "project_qkv_rope", "prefill_attn_rope", "prefill_rope_workspace_bytes", "decode_attn_alibi", "prefill_attn_alibi", "decode_rope_auto_splits",
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
-    "attn_mass", "attn_mass_workspace_bytes",
+    "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -31,7 +31,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_attn_alibi", "ea_prefill_attn_alibi", "ea_out_proj",
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
-    "ea_attn_mass_workspace_bytes", "ea_attn_mass",
+    "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
 )
 
 
@@ -127,6 +127,9 @@ def load_library():
     lib.ea_attn_mass_workspace_bytes.restype = I64
     lib.ea_attn_mass_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_attn_mass.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, VP, I64, VP]
+    lib.ea_decode_attn_mass_workspace_bytes.restype = I64
+    lib.ea_decode_attn_mass_workspace_bytes.argtypes = [D, I32, I32, I32]
+    lib.ea_decode_attn_mass.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_alibi_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64,
                                             VP]
     lib.ea_decode_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
@@ -585,3 +588,27 @@ def attn_mass(desc, q_r, k_pool, page_table, seq_len, mass, ws, stream=None) -> 
                                      _ptr(mass), B, page_table.shape[1], k_pool.shape[0], _ptr(ws), ws_bytes,
                                      _stream(stream))
     _check(rc, "ea_attn_mass")
+
+
+def decode_attn_mass_workspace_bytes(desc, B: int, max_pages: int, n_splits: int) -> int:
+    return int(load_library().ea_decode_attn_mass_workspace_bytes(ctypes.byref(desc), B, max_pages, n_splits))
+
+
+def decode_attn_mass(desc, q_r, k_pool, v_pool, page_table, seq_len, out, mass, n_splits: int, ws, stream=None) -> None:
+    """decode_attn and attn_mass in one pass over the cache (bfloat16 layers): out [B, H, r_v] float32 is written,
+    mass [B, H_kv, max_pages * page_tokens] float32 is added to."""
+    import torch
+    B = seq_len.shape[0]
+    if q_r.dtype != torch.float32 or out.dtype != torch.float32 or mass.dtype != torch.float32:
+        raise ValueError("q_r, out and mass must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    if mass.numel() != B * desc.n_kv_heads * page_table.shape[1] * desc.page_tokens:
+        raise ValueError("mass must be [B, H_kv, max_pages * page_tokens]")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_decode_attn_mass(ctypes.byref(desc), _ptr(q_r), _ptr(k_pool), _ptr(v_pool), _ptr(page_table),
+                                            _ptr(seq_len), _ptr(out), _ptr(mass), B, page_table.shape[1],
+                                            k_pool.shape[0], n_splits, _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_decode_attn_mass")

@@ -15,6 +15,11 @@
 
 namespace ea {
 
+// Row length (floats) of the per-head scratch rows e / scores for a cache of n_cap tokens: whole tiles, plus a pad
+// of 17 * 256 bytes.  Without it the rows of long sequences start a power of two apart, and all the workgroups,
+// which advance through their rows in step, would write to the same memory channel at the same time.
+__host__ __device__ inline int64_t mass_row_floats(int64_t n_cap) { return (n_cap + kTile - 1) / kTile * kTile + 1088; }
+
 struct MassArgs {
   const float* q;            // [B, H, r_k]
   const void* k_pool;
@@ -25,7 +30,7 @@ struct MassArgs {
   float* mass;               // [B, H_kv, n_cap]
   Geo g;
   int32_t n_cap;             // max_pages * page_tokens: row length of mass, and the bound of seq_len
-  int32_t e_row;             // row length of e: n_cap rounded up to whole tiles
+  int32_t e_row;             // row length of e: mass_row_floats(n_cap)
   int32_t tiles_cap;         // ceil(n_cap / 64)
   int32_t tiles_wg;          // tiles of one (sequence, kv head) per workgroup of the bf16 tile kernel
   float scale_log2;
@@ -267,11 +272,50 @@ __global__ __launch_bounds__(256) void mass_finish_kernel(MassArgs a) {
   }
 }
 
+// The finish of the fused form: the decode kernel has stored the scores s (log2 units, masked tokens -inf) and the
+// split merge each row's reference exponent M and normaliser L;  mass[t] += sum_heads 2^(s_t - M) / L.
+struct MassFromScoresArgs {
+  const float* scores;       // [B, H, s_row]
+  const float* ml;           // [B, H, 2]
+  const int32_t* seq_len;
+  float* mass;               // [B, H_kv, n_cap]
+  int32_t n_heads, n_kv_heads, group, n_cap, s_row;
+};
+
+__global__ __launch_bounds__(256) void mass_from_scores_kernel(MassFromScoresArgs a) {
+  const int chunk = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  int n = a.seq_len[b];
+  n = n < 0 ? 0 : (n > a.n_cap ? a.n_cap : n);
+  const int t0 = chunk * kFinishTokens;
+  if (t0 >= n) return;
+  const int t_end = min(n, t0 + kFinishTokens);
+  const int64_t bh0 = (int64_t)b * a.n_heads + (int64_t)kvh * a.group;
+  float* mrow = a.mass + ((int64_t)b * a.n_kv_heads + kvh) * a.n_cap;
+  for (int t = t0 + threadIdx.x * 4; t < t_end; t += 1024) {
+    f32x4 w = {0.f, 0.f, 0.f, 0.f};
+    for (int hd = 0; hd < a.group; ++hd) {
+      const float M = a.ml[2 * (bh0 + hd)], L = a.ml[2 * (bh0 + hd) + 1];
+      if (M != -INFINITY && L > 0.f) {
+        const f32x4 sv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.scores + (bh0 + hd) * a.s_row + t));
+        const float inv = 1.0f / L;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] += __builtin_amdgcn_exp2f(sv[i] - M) * inv;
+      }
+    }
+    if (t + 4 <= n) {
+      f32x4* p = reinterpret_cast<f32x4*>(mrow + t);
+      *p = *p + w;
+    } else {
+      for (int i = 0; t + i < n; ++i) mrow[t + i] += w[i];
+    }
+  }
+}
+
 static int64_t mass_ws_floats(const ea_layer_desc* d, int32_t B, int32_t max_pages) {
   const int64_t n_cap = (int64_t)max_pages * d->page_tokens;
   const int64_t tiles = (n_cap + kTile - 1) / kTile;
   // e is sized for whole tiles, so the tile kernels may write a full 64-token row at the end of a sequence
-  return (int64_t)B * d->n_heads * (tiles * kTile + tiles * 2);
+  return (int64_t)B * d->n_heads * (mass_row_floats(n_cap) + tiles * 2);
 }
 
 }  // namespace ea
@@ -296,7 +340,7 @@ int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* de
   if (!dev_ws || !aligned16(dev_ws) || ws_bytes < ea_attn_mass_workspace_bytes(desc, B, max_pages))
     return EA_ERR_WORKSPACE;
   const int64_t n_cap64 = (int64_t)max_pages * desc->page_tokens;
-  if (n_cap64 > (int64_t)INT32_MAX - kTile) return EA_ERR_SHAPE;
+  if (n_cap64 > (int64_t)INT32_MAX - 2048) return EA_ERR_SHAPE;
   const Geo g = make_geo(desc, max_pages, pool_pages);
   if (B > 65535 || g.n_kv_heads > 65535 || g.group > 16) return EA_ERR_SHAPE;
   MassArgs a;
@@ -307,7 +351,7 @@ int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* de
   a.g = g;
   a.n_cap = (int32_t)n_cap64;
   a.tiles_cap = (a.n_cap + kTile - 1) / kTile;
-  a.e_row = a.tiles_cap * kTile;
+  a.e_row = (int32_t)mass_row_floats(a.n_cap);
   a.e = (float*)dev_ws;
   a.ml = a.e + (int64_t)B * g.n_heads * a.e_row;
   a.mass = dev_mass;
@@ -336,5 +380,61 @@ int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* de
   mass_finish_kernel<<<dim3((uint32_t)((a.n_cap + kFinishTokens - 1) / kFinishTokens), g.n_kv_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }
+
+int64_t ea_decode_attn_mass_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t max_pages, int32_t n_splits) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || max_pages <= 0 || n_splits < 1 || n_splits > 1024) return -1;
+  const int64_t n_cap = (int64_t)max_pages * desc->page_tokens;
+  const int64_t s_row = mass_row_floats(n_cap);
+  const int64_t partials = ws_floats(B, desc->n_heads, n_splits, round_up(desc->r_v, 16));
+  return ((partials + 3) / 4 * 4 + (int64_t)B * desc->n_heads * (s_row + 2)) * (int64_t)sizeof(float);
+}
+
+int ea_decode_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_k_pool, const void* dev_v_pool,
+                        const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out, float* dev_mass,
+                        int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
+                        int64_t ws_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_out || !dev_mass)
+    return EA_ERR_ARG;
+  if (B <= 0 || max_pages <= 0 || pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (desc->dtype != EA_BF16) return EA_ERR_SHAPE;      // fp32 layers: ea_decode_attn, then ea_attn_mass
+  if (!aligned16(dev_q_r) || !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out) ||
+      !aligned16(dev_mass))
+    return EA_ERR_ALIGN;
+  const int64_t n_cap64 = (int64_t)max_pages * desc->page_tokens;
+  if (n_cap64 > (int64_t)INT32_MAX - 2048) return EA_ERR_SHAPE;
+  if (n_splits == 0) n_splits = ea_decode_auto_splits(desc, B, (int32_t)n_cap64);
+  if (!dev_ws || !aligned16(dev_ws) || ws_bytes < ea_decode_attn_mass_workspace_bytes(desc, B, max_pages, n_splits))
+    return EA_ERR_WORKSPACE;
+  const Geo g = make_geo(desc, max_pages, pool_pages);
+  if (B > 65535 || g.n_kv_heads > 65535 || g.group > 16) return EA_ERR_SHAPE;
+  const int32_t n_cap = (int32_t)n_cap64;
+  const int32_t s_row = (int32_t)mass_row_floats(n_cap);
+  float* partials = (float*)dev_ws;
+  float* scores = partials + (ws_floats(B, g.n_heads, n_splits, g.r_v_pad) + 3) / 4 * 4;   // rows of 16-byte units
+  float* ml = scores + (int64_t)B * g.n_heads * s_row;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stale_error();
+  rc = decode_scores_bf16(desc, g, dev_q_r, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, B, n_splits, partials,
+                          scores, s_row, st);
+  if (rc != EA_OK) return rc;
+  rc = merge_splits(g, partials, dev_out, B, n_splits, st, ml);
+  if (rc != EA_OK) return rc;
+  MassFromScoresArgs a;
+  a.scores = scores;
+  a.ml = ml;
+  a.seq_len = dev_seq_len;
+  a.mass = dev_mass;
+  a.n_heads = g.n_heads;
+  a.n_kv_heads = g.n_kv_heads;
+  a.group = g.group;
+  a.n_cap = n_cap;
+  a.s_row = s_row;
+  mass_from_scores_kernel<<<dim3((uint32_t)((n_cap + kFinishTokens - 1) / kFinishTokens), g.n_kv_heads, B), dim3(256), 0,
+                            st>>>(a);
+  return launch_status();
+}
+
 
 }  // extern "C"

@@ -161,7 +161,13 @@ int prefill_alibi_bf16(const ea_layer_desc* d, const Geo& g, const void* q, cons
 int prefill_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
                       const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
                       int32_t n, hipStream_t st);
-int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st);
+// The position-free bf16 kernel in the form that also stores the scaled scores (log2 units) [B, H, s_row]; always
+// leaves split partials in ws (n_splits slots) for merge_splits.
+int decode_scores_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
+                       const int32_t* page_table, const int32_t* seq_len, int32_t B, int32_t n_splits, float* ws,
+                       float* scores, int32_t s_row, hipStream_t st);
+int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st,
+                 float* ml_out = nullptr);   // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
                  const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,

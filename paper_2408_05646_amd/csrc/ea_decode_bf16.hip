@@ -3,9 +3,10 @@
 
 namespace ea {
 
-// out[b, h, :] = sum_s w_s acc_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).
+// out[b, h, :] = sum_s w_s acc_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).  With ml_out, the row's
+// reference exponent max_s m_s and normaliser sum_s w_s l_s are stored too, as ml_out[2 (b H + h)], [.. + 1].
 __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, int32_t BH, int32_t S,
-                                    int32_t r_v, int32_t r_v_pad) {
+                                    int32_t r_v, int32_t r_v_pad, float* __restrict__ ml_out) {
   const int64_t bh = blockIdx.x;
   const int64_t BHS = (int64_t)BH * S;
   const float* pm = ws + bh * S;
@@ -13,6 +14,13 @@ __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restr
   const float* pa = ws + 2 * BHS + bh * S * r_v_pad;
   float mm = -INFINITY;
   for (int s = 0; s < S; ++s) mm = fmaxf(mm, pm[s]);
+  if (ml_out && threadIdx.x == 0) {
+    float lsum = 0.f;
+    if (mm != -INFINITY)
+      for (int s = 0; s < S; ++s) lsum += __builtin_amdgcn_exp2f(pm[s] - mm) * pl[s];
+    ml_out[2 * bh] = mm;
+    ml_out[2 * bh + 1] = lsum;
+  }
   for (int c = threadIdx.x; c < r_v; c += blockDim.x) {
     float lsum = 0.f, val = 0.f;
     if (mm != -INFINITY) {
@@ -26,8 +34,9 @@ __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restr
   }
 }
 
-int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st) {
-  merge_splits_kernel<<<dim3(B * g.n_heads), dim3(64), 0, st>>>(ws, out, B * g.n_heads, n_splits, g.r_v, g.r_v_pad);
+int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st, float* ml_out) {
+  merge_splits_kernel<<<dim3(B * g.n_heads), dim3(64), 0, st>>>(ws, out, B * g.n_heads, n_splits, g.r_v, g.r_v_pad,
+                                                               ml_out);
   return launch_status();
 }
 

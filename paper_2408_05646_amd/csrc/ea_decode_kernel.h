@@ -47,6 +47,9 @@ struct DecodeArgs {
   // of a workspace laid out for ws_slots splits (another kernel fills the other slots).
   int32_t ws_slots = 0;
   int32_t ws_slot0 = 0;
+  // SCORES variant only: the scaled scores (log2 units) of every (sequence, head, token) are written here as well
+  float* scores = nullptr;   // [B, H, s_row]
+  int32_t s_row = 0;         // row length: the cache capacity rounded up to whole tiles
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -77,16 +80,26 @@ constexpr int kReseed = 32;   // iterations between exact re-computations of the
 // large ranks whose fragments would not fit the register file otherwise).
 // ALIBI adds the linear position bias of the ALiBi scheme to the scores: -slope_h * (distance of the key to
 // the query), in the position-free form only.
+// SCORES also stores the scores (log2 units): what a caller that accumulates attention probabilities per cached
+// token needs, without a second pass over the keys.  A wave collects the scores of several iterations in LDS and
+// writes them out 2048 floats at a time with full-width stores (a store per tile from the four lanes that hold a
+// head's scores measured slower: one counter covers loads and stores, so the next wait for loaded data also
+// waits for the store).
 // LDS of one workgroup: the rotary tables while the cache streams, the merge buffers afterwards.
-template <int KS, int NCB, int TBN, int NKK>
+constexpr int kScoreStage = 2048;      // floats of staged scores per wave (SCORES form)
+struct ScoreSmem {
+  float s[4][kScoreStage];
+};
+template <int KS, int NCB, int TBN, int NKK, bool SCORES = false>
 union DecodeSmem {
   MergeSmem<NCB> mg;
   std::conditional_t<(NKK > 0), RopeSmem<TBN, (NKK > 0) ? NKK : 1, KS>, NoSmem> rp;
+  std::conditional_t<SCORES, ScoreSmem, NoSmem> sc;
 };
 
-template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false>
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false>
 __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int kvh, const int split, const int b,
-                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK>& sm) {
+                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK, SCORES>& sm) {
   constexpr bool ROPE = NKK > 0;
   static_assert(!(ROPE && ALIBI), "a model has one position scheme");
   constexpr int UN = TBN / 2;            // 32-token groups per iteration
@@ -336,6 +349,25 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
   }
   int since_seed = 0;
 
+  // SCORES: iterations staged so far, the tile of the first of them, and how many fit
+  static_assert(!(SCORES && ROPE), "the score-storing form is position-free");
+  int stage_n = 0, stage_tile0 = cur.tile;
+  const int cur_sub_tokens = cur.sub * TOK;     // position-free form: a wave keeps its half of the tiles
+  const int stage_cap = SCORES ? kScoreStage / (G * TOK) : 0;        // G <= 16, TOK <= 64: at least 2
+  auto flush_scores = [&]() {
+    if constexpr (SCORES) {
+      // staged order: [iteration f][head hd][TOK tokens]; iteration f of this wave is tile stage_tile0 + f * kStride
+      const int per_it = G * TOK, total = stage_n * per_it;
+      float* rows = a.scores + ((int64_t)b * g.n_heads + (int64_t)kvh * G) * a.s_row + cur_sub_tokens;
+      for (int i = lane * 4; i < total; i += 256) {
+        const int f = i / per_it, r = i - f * per_it, hd = r / TOK, off = r - hd * TOK;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&sm.sc.s[wave][i]);
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(rows + (int64_t)hd * a.s_row + (stage_tile0 + f * kStride) * kTile + off));
+      }
+      stage_n = 0;
+    }
+  };
+
   // One iteration; kf holds the current keys, kf_free is the buffer the keys after the next go to.
   auto iteration = [&](auto& kf, auto& kf_free) __attribute__((always_inline)) {
     // ---- scores: S[tb] (16 tokens x 16 head columns) = K_block . q^T
@@ -387,6 +419,15 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       }
     }
     const int rem = page >= 0 ? n - (cur.tile * kTile + cur.sub * TOK) : 0;   // valid tokens here (>= TOK: all)
+    if constexpr (SCORES) {
+      // tokens past the sequence's end are never read back; a tile without a page must read as "no probability"
+      if (col < G) {
+        float* dst = &sm.sc.s[wave][(stage_n * G + col) * TOK + quad * 4];
+        const float add = page >= 0 ? m_base : -INFINITY;
+#pragma unroll
+        for (int tb = 0; tb < TBN; ++tb) *reinterpret_cast<f32x4*>(dst + tb * 16) = s[tb] + add;
+      }
+    }
     // the registers of the current keys are free again: request the next keys (one buffer) or the ones after
     // the next (two buffers)
     Pos nn = nxt;
@@ -496,6 +537,16 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       if (!have) break;
       iteration(kfB, kfB);
     }
+  } else if constexpr (SCORES) {
+    while (have) {
+      iteration(kfA, kfA);
+      if (++stage_n == stage_cap) {
+        flush_scores();
+        stage_tile0 = cur.tile;      // the iteration that comes next
+      }
+    }
+    if (stage_n > 0) flush_scores();
+    __syncthreads();                 // the staging buffers share their memory with the merge buffers
   } else {
     while (have) iteration(kfA, kfA);
   }
@@ -548,10 +599,10 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 
 // The kernel: one workgroup per (kv head, split, sequence).  (The body is a function of its own because the
 // kernel over the 4-bit cache runs it, too, for the bfloat16 tail of the sequences.)
-template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false>
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false>
 __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
-  __shared__ DecodeSmem<KS, NCB, TBN, NKK> sm;
-  decode_bf16_body<KS, NCB, TBN, WPE, NKK, ALIBI>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, sm);
+  __shared__ DecodeSmem<KS, NCB, TBN, NKK, SCORES> sm;
+  decode_bf16_body<KS, NCB, TBN, WPE, NKK, ALIBI, SCORES>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, sm);
 }
 
 }  // namespace ea

@@ -1,5 +1,5 @@
-"""ea_attn_mass (the attention statistic H2O-style eviction accumulates; results, "Eigen Attention with token
-pruning") against the fp64 oracle, and a generation loop over a fixed-budget cache whose dropped tokens' slots are
+"""ea_attn_mass and its fused form ea_decode_attn_mass (the attention statistic H2O-style eviction accumulates;
+results, "Eigen Attention with token pruning") against the fp64 oracle, and a generation loop over a fixed-budget cache whose dropped tokens' slots are
 overwritten by the new ones."""
 import numpy as np
 import pytest
@@ -60,6 +60,54 @@ def test_attn_mass_matches_oracle(dtype, H, Hkv, r_k, lens, P):
     assert torch.allclose(mass2, 2 * mass, rtol=1e-6, atol=1e-7)
 
 
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,lens,P,S", [
+    (2, 2, 80, 80, [1, 63, 64, 65], 64, 1),                   # a single split still goes through the merge
+    (8, 2, 48, 64, [777, 64, 1500], 128, 3),                  # GQA 4:1, splits that some sequences leave empty
+    (16, 1, 96, 112, [300, 2000], 64, 2),                     # half-tile iterations (large ranks)
+    (4, 4, 128, 128, [513, 100, 0], 64, 4),                   # an empty sequence
+    (4, 2, 30, 20, [150, 70], 64, 0),                         # odd ranks, automatic split count
+    (2, 1, 80, 80, [20000], 64, 8),
+])
+def test_decode_attn_mass_matches_oracle_and_the_two_separate_calls(H, Hkv, r_k, r_v, lens, P, S):
+    """One pass over the cache: the attention output of ea_decode_attn and the statistic of ea_attn_mass."""
+    print(f"fused mass H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} P={P} S={S}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(64, H, r_k, len(lens))
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    B = len(lens)
+    q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+    dc = DeviceCache(desc, K, V, g)
+    q_t = torch.from_numpy(q.astype(np.float32)).cuda()
+    n_cap = dc.max_pages * P
+    S_eff = S or ea.decode_auto_splits(desc, B, n_cap)
+    ws = torch.full((ea.decode_attn_mass_workspace_bytes(desc, B, dc.max_pages, S_eff) // 4,), float("nan"),
+                    dtype=torch.float32, device="cuda")
+    prior = torch.rand((B, Hkv, n_cap), dtype=torch.float32, device="cuda")      # the call adds to what is there
+    mass = prior.clone()
+    out = torch.full((B, H, r_v), float("nan"), dtype=torch.float32, device="cuda")
+    ea.decode_attn_mass(desc, q_t, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, out, mass, S, ws)
+    torch.cuda.synchronize()
+    got = (mass - prior).cpu().numpy()
+    keep = [b for b in range(B) if lens[b] > 0]
+    cache = ora.RankCache.from_arrays([K[b] for b in keep], [V[b] for b in keep])
+    ref_m = oe.attention_mass(q[keep], cache, 128)
+    ref_o = ora.decode_attention(q[keep], cache, 128)
+    assert_close(out.cpu().numpy()[keep], ref_o, TOL_BF16, "fused output")
+    for b in range(B):
+        assert torch.equal(mass[b, :, lens[b]:], prior[b, :, lens[b]:]), "entries past the sequence end were touched"
+    for i, b in enumerate(keep):
+        assert_close(got[b, :, :lens[b]], ref_m[i], TOL_BF16, f"fused mass b={b}")
+        assert np.allclose(got[b, :, :lens[b]].sum(axis=1), H // Hkv, rtol=0, atol=2e-3)
+    # against the two calls it replaces: the same output, and the same statistic up to the normaliser, which here is
+    # the attention kernel's own row sum (of probabilities rounded to bfloat16: within one bf16 step, 2^-8, relative)
+    out2 = torch.empty_like(out)
+    ws2 = torch.empty(max(ea.decode_workspace_bytes(desc, B, S_eff) // 4, 4), dtype=torch.float32, device="cuda")
+    ea.decode_attn(desc, q_t, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, out2, n_splits=S_eff, ws=ws2)
+    sep = run_mass(desc, dc, q).cpu().numpy()
+    assert torch.allclose(out, out2, rtol=1e-5, atol=1e-6)
+    assert np.allclose(got, sep, rtol=4e-3, atol=1e-6)
+
+
 def test_attn_mass_skips_pages_that_are_not_there():
     desc = ea.LayerDesc(256, 2, 2, 128, 80, 16, ea.EA_BF16, 64)
     g = synth.rng(62)
@@ -76,7 +124,8 @@ def test_attn_mass_skips_pages_that_are_not_there():
     assert_close(got[:, keep], ref, TOL_BF16, "mass with a missing page")
 
 
-def test_h2o_generation_loop_over_a_fixed_budget():
+@pytest.mark.parametrize("fused", [False, True])
+def test_h2o_generation_loop_over_a_fixed_budget(fused):
     """A cache of `budget` slots per sequence.  Every step: project the new token into the slot the policy freed
     (the oldest-first H2O rule on the accumulated mass, the newest n_recent tokens protected; the decision is the
     oracle's, so that a near-tie cannot send the two sides down different paths), attend over the budget, add the
@@ -104,6 +153,8 @@ def test_h2o_generation_loop_over_a_fixed_budget():
     acc_ref = [np.zeros((2, budget)) for _ in range(B)]           # accumulated mass per slot, oracle
     mass = torch.zeros((B, 2, budget), dtype=torch.float32, device="cuda")
     ws_m = torch.empty(ea.attn_mass_workspace_bytes(desc, B, dc.max_pages) // 4, dtype=torch.float32, device="cuda")
+    ws_f = torch.empty(ea.decode_attn_mass_workspace_bytes(desc, B, dc.max_pages, 2) // 4, dtype=torch.float32,
+                       device="cuda")
     q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
     o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
     y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
@@ -123,8 +174,11 @@ def test_h2o_generation_loop_over_a_fixed_budget():
         mass[torch.arange(B), :, slot_t.long()] = 0.0
         # the step: the new token goes to the freed slot (its "position"), attention runs over all slots
         ea.project_qkv(desc, to_dev(desc, x_hist[:, tok]), wqkv_t, q_r, dc.k_pool, dc.v_pool, dc.page_table, slot_t, 1)
-        ea.decode_attn(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, full, o, n_splits=1)
-        ea.attn_mass(desc, q_r, dc.k_pool, dc.page_table, full, mass, ws_m)
+        if fused:
+            ea.decode_attn_mass(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, full, o, mass, 2, ws_f)
+        else:
+            ea.decode_attn(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, full, o, n_splits=1)
+            ea.attn_mass(desc, q_r, dc.k_pool, dc.page_table, full, mass, ws_m)
         ea.out_proj(desc, o.view(B, -1), wo_t, y)
         torch.cuda.synchronize()
         # oracle: the kept tokens, in slot order

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 36
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 38
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -361,9 +361,28 @@ def test_attn_mass_rejects_bad_arguments_before_launching():
     assert mass(ws=None) == -4 and mass(ws=ODD_PTR) == -4
     need = ea.attn_mass_workspace_bytes(d, 2, 4)
     tiles = 4 * 128 // 64
-    assert need == 2 * 8 * (tiles * 64 + tiles * 2) * 4                    # e rows of whole tiles + (m, l) per tile
+    assert need == 2 * 8 * (tiles * 64 + 1088 + tiles * 2) * 4             # e rows (whole tiles + pad) + (m, l) per tile
     assert mass(ws_bytes=need - 1) == -4
     assert mass(dd=desc(H=34, Hkv=2, d=34 * 128)) == -2                    # at most 16 query heads per kv head
     assert ea.attn_mass_workspace_bytes(d, 0, 4) == -1
     # fp32 pages of 48 tokens: the rows of e are rounded up to whole tiles
-    assert ea.attn_mass_workspace_bytes(desc(dtype=ea.EA_F32, P=48), 1, 3) == 8 * (3 * 64 + 3 * 2) * 4
+    assert ea.attn_mass_workspace_bytes(desc(dtype=ea.EA_F32, P=48), 1, 3) == 8 * (3 * 64 + 1088 + 3 * 2) * 4
+
+
+def test_decode_attn_mass_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def call(dd=d, q=OK_PTR, k=OK_PTR, out=OK_PTR, mass=OK_PTR, B=2, max_pages=4, pool=8, S=2, ws=OK_PTR, ws_bytes=1 << 30):
+        return lib.ea_decode_attn_mass(ctypes.byref(dd), q, k, OK_PTR, OK_PTR, OK_PTR, out, mass, B, max_pages, pool, S,
+                                       ws, ws_bytes, None)
+
+    assert call(q=None) == -1 and call(mass=None) == -1 and call(B=0) == -1 and call(S=-1) == -1 and call(S=1025) == -1
+    assert call(k=ODD_PTR) == -3 and call(mass=ODD_PTR) == -3
+    assert call(ws=None) == -4                                             # needed for any split count
+    need = ea.decode_attn_mass_workspace_bytes(d, 2, 4, 2)
+    partials = 2 * 8 * 2 * (2 + 48)                                        # B H S (m, l, r_v_pad)
+    assert need == (partials + 2 * 8 * (4 * 128 + 1088 + 2)) * 4           # + scores rows (padded) + (M, L) per row
+    assert call(ws_bytes=need - 1) == -4
+    assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
+    assert call(dd=desc(H=34, Hkv=2, d=34 * 128)) == -2
+    assert ea.decode_attn_mass_workspace_bytes(d, 2, 4, 0) == -1           # the size depends on the split count
