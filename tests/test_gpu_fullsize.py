@@ -10,6 +10,7 @@ import torch
 
 import paper_2408_05646_amd as ea
 from oracle import eigen_attention as ora
+from oracle import eviction as oe
 from paper_2408_05646_amd import synth
 from helpers import TOL_BF16, assert_close
 
@@ -36,7 +37,7 @@ def stream_from_pool(pool, page_table_row, head, n_kv_heads, r_pad, rows_fn, pag
     return rows_fn(got.reshape(-1, 64 * r_pad), r_pad).astype(np.float64)
 
 
-def run_sampled_decode(desc, B, n, samples, seed, n_splits=0):
+def run_sampled_decode(desc, B, n, samples, seed, n_splits=0, with_mass=False):
     P = desc.page_tokens
     max_pages = n // P
     pool_pages = B * max_pages
@@ -48,8 +49,14 @@ def run_sampled_decode(desc, B, n, samples, seed, n_splits=0):
     q = torch.randn((B, desc.n_heads, desc.r_k), generator=gen, device="cuda")
     out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), device="cuda")
     S = n_splits or ea.decode_auto_splits(desc, B, n)
-    ws = torch.empty(max(ea.decode_workspace_bytes(desc, B, S) // 4, 4), device="cuda")
-    ea.decode_attn(desc, q, k_pool, v_pool, pt, seq, out, n_splits=S, ws=ws)
+    mass = None
+    if with_mass:      # the fused call: the same output, and the attention mass of every cached token
+        mass = torch.zeros((B, desc.n_kv_heads, n), device="cuda")
+        ws = torch.empty(ea.decode_attn_mass_workspace_bytes(desc, B, max_pages, S) // 4, device="cuda")
+        ea.decode_attn_mass(desc, q, k_pool, v_pool, pt, seq, out, mass, S, ws)
+    else:
+        ws = torch.empty(max(ea.decode_workspace_bytes(desc, B, S) // 4, 4), device="cuda")
+        ea.decode_attn(desc, q, k_pool, v_pool, pt, seq, out, n_splits=S, ws=ws)
     torch.cuda.synchronize()
     got_all = out.cpu().numpy()
     assert np.isfinite(got_all).all()
@@ -63,6 +70,12 @@ def run_sampled_decode(desc, B, n, samples, seed, n_splits=0):
         heads = list(range(kvh * G, (kvh + 1) * G))
         ref = ora.decode_attention(qh[b:b + 1, heads], cache, desc.d_head)
         assert_close(got_all[b:b + 1, heads], ref, TOL_BF16, f"stream b={b} kvh={kvh}")
+        if with_mass:
+            ref_m = oe.attention_mass(qh[b:b + 1, heads], cache, desc.d_head)[0]
+            assert_close(mass[b, kvh].cpu().numpy()[None], ref_m, TOL_BF16, f"mass b={b} kvh={kvh}")
+    if with_mass:      # any size: every row of the statistic sums to the group's number of query heads
+        sums = mass.sum(dim=2).cpu().numpy()
+        assert np.allclose(sums, G, rtol=0, atol=2e-3), (sums.min(), sums.max())
     # any size: the output is a convex combination of value rows
     assert np.abs(got_all).max() <= float(v_pool.abs().max()) * 1.001
     return S
@@ -77,6 +90,16 @@ def test_cfg3_one_layer_sampled():
     print("cfg3 samples", samples, flush=True)
     S = run_sampled_decode(desc, s.batch, s.n_ctx, samples, seed=33)
     assert S == ea.decode_auto_splits(desc, s.batch, s.n_ctx) == 1
+
+
+def test_cfg3_one_layer_with_attention_mass_sampled():
+    """The same shape through ea_decode_attn_mass, as `bench.py --workload cfg3-h2o` runs it."""
+    s = synth.CFG3
+    desc = ea.LayerDesc(s.d_model, s.n_heads, s.n_kv_heads, s.d_head, s.r_k, s.r_v, ea.EA_BF16, 64)
+    g = synth.rng(3, 2)
+    samples = [(0, 0), (15, 31)] + [(int(g.integers(16)), int(g.integers(32))) for _ in range(6)]
+    print("cfg3 mass samples", samples, flush=True)
+    run_sampled_decode(desc, s.batch, s.n_ctx, samples, seed=35, with_mass=True)
 
 
 def test_cfg3_fullrank_baseline_sampled():
