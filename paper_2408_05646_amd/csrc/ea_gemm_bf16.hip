@@ -487,11 +487,13 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
     const int mt = (M + 15) / 16;
 #define EA_SKINNY(MT_, NB_) gemm_bf16_skinny_kernel<Epilogue, A_F32, MT_, NB_><<<grid, block, 0, st>>>(A, w, M, N, K, ep)
     if (nb == 2) {
-      switch (mt) {
-        case 1: EA_SKINNY(1, 2); break;
-        case 2: EA_SKINNY(2, 2); break;
-        case 3: EA_SKINNY(3, 2); break;
-        default: EA_SKINNY(4, 2); break;
+      if constexpr (!A_F32) {                 // (never instantiated for float activations: it would spill)
+        switch (mt) {
+          case 1: EA_SKINNY(1, 2); break;
+          case 2: EA_SKINNY(2, 2); break;
+          case 3: EA_SKINNY(3, 2); break;
+          default: EA_SKINNY(4, 2); break;
+        }
       }
     } else {
       switch (mt) {
