@@ -399,7 +399,10 @@ EA_API int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const v
  * the output and the statistic.  Arguments as in ea_decode_attn plus dev_mass as in ea_attn_mass.
  *   n_splits 0 = ea_decode_auto_splits; dev_ws ea_decode_attn_mass_workspace_bytes(desc, B, max_pages, n_splits)
  *   bytes (n_splits >= 1 there), 16-byte aligned, always required.  EA_F32 layers: EA_ERR_SHAPE (call the two
- *   separately).  H / H_kv <= 16. */
+ *   separately).  H / H_kv <= 16.
+ * The probabilities are normalised with the attention kernel's own row sum (of probabilities rounded to
+ * bfloat16), so they can differ from ea_attn_mass's by one bfloat16 step, relative; each row still sums to
+ * H / H_kv within 2e-3.  dev_out is computed as by ea_decode_attn with the same n_splits. */
 EA_API int64_t ea_decode_attn_mass_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t max_pages,
                                                    int32_t n_splits);
 EA_API int ea_decode_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_k_pool,
