@@ -195,3 +195,50 @@ def test_h2o_generation_loop_over_a_fixed_budget(fused):
         assert_close(got[b], acc_ref[b], TOL_BF16, f"accumulated mass b={b}")
         assert len(set(slot_token[b])) == budget and max(slot_token[b]) == budget + steps - 1
     print(f"  worst step rel-L2 {worst:.2e}", flush=True)
+
+
+def test_decode_attn_mass_step_is_graph_capturable():
+    """project_qkv -> ea_decode_attn_mass (three launches) -> out_proj captured in a HIP graph; every replay, with
+    eager work in between, reproduces the eager output bit for bit and adds the eager step's statistic once more."""
+    desc = ea.LayerDesc(512, 8, 2, 128, 80, 48, ea.EA_BF16, 64)
+    g = synth.rng(65)
+    B, n, S = 3, 700, 3
+    K, V = random_cache(desc, [n] * B, g)
+    dc = DeviceCache(desc, K, V, g, extra_len=1)
+    n_qkv = 8 * 80 + 2 * (80 + 48)
+    wqkv = ea.pack_weight(torch.from_numpy(synth.gaussian(g, (n_qkv, 512), 512 ** -0.5)).float().to(torch.bfloat16).cuda())
+    wo = ea.pack_weight(torch.from_numpy(synth.gaussian(g, (512, 8 * 48), 512 ** -0.5)).float().to(torch.bfloat16).cuda())
+    x = torch.from_numpy(synth.gaussian(g, (B, 512))).float().to(torch.bfloat16).cuda()
+    q_r = torch.empty((B, 8, 80), dtype=torch.float32, device="cuda")
+    o = torch.empty((B, 8, 48), dtype=torch.float32, device="cuda")
+    y = torch.empty((B, 512), dtype=torch.bfloat16, device="cuda")
+    mass = torch.zeros((B, 2, dc.max_pages * 64), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ea.decode_attn_mass_workspace_bytes(desc, B, dc.max_pages, S) // 4, dtype=torch.float32, device="cuda")
+    before = dc.seq_len.clone()
+    after = before + 1
+
+    def step():
+        ea.project_qkv(desc, x, wqkv, q_r, dc.k_pool, dc.v_pool, dc.page_table, before, 1)
+        ea.decode_attn_mass(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, after, o, mass, S, ws)
+        ea.out_proj(desc, o.view(B, -1), wo, y)
+
+    step()
+    torch.cuda.synchronize()
+    y_eager, mass_eager = y.clone(), mass.clone()
+    assert float(y_eager.float().abs().sum()) > 0
+    assert np.allclose(mass_eager.sum(dim=2).cpu().numpy(), 4, rtol=0, atol=2e-3)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(4):
+        y.zero_(); o.zero_(); q_r.zero_(); ws.zero_(); mass.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {rep}: output differs from the eager result"
+        assert torch.equal(mass, mass_eager), f"replay {rep}: statistic differs from the eager result"
