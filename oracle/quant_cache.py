@@ -98,6 +98,23 @@ def quantized_view(K, V, n_quant: int):
     return Kq, Vq
 
 
+def quantized_cache_bytes(n_elements, bits: int, group: int, meta_bits_per_group: int = 16) -> float:
+    """Bytes of n_elements cached scalars held as `bits`-bit codes in groups of `group`, every group carrying
+    meta_bits_per_group bits of metadata: n * (bits + meta / group) / 8.
+    The KV-cache sizes the appendix's quantisation table prints (15 rows: Llama-2-7b and -13b, standard and Eigen
+    Attention at 0.6x, 2-4 bits, groups of 16-512, sequence length 2048, GB = 2^30 bytes) are reproduced by this
+    count with 16 bits of metadata per group -- one 16-bit scale -- and by neither 0 nor 32 (a pin).  The paper does
+    not say whether a zero point exists or where it is kept; this build's format stores a 16-bit scale AND a 16-bit
+    zero per group (32 bits), so its pools are larger than the paper's accounting: see bits_per_element_q4."""
+    return n_elements * (bits + meta_bits_per_group / group) / 8.0
+
+
+def bits_per_element_q4(r_k: int, r_v: int):
+    """Bits per cached scalar of this build's 4-bit format, without layout padding: keys in groups of 64 tokens,
+    values in groups of r_v channels, 32 bits of metadata (fp16 scale, fp16 zero) per group."""
+    return 4 + 32 / GROUP_TOKENS, 4 + 32 / r_v
+
+
 def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_slopes=None):
     """Generation-phase attention (Eq. 3 in the rank-r space) of one new token per sequence over a cache whose
     first n_quant[b] tokens are quantised: plain attention over the dequantised values (with the ALiBi bias of the

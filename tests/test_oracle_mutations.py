@@ -134,6 +134,10 @@ QUANT = [
      "    return scale.astype(np.float64)[:, None] * codes.astype(np.float64) + zero.astype(np.float64)[:, None]",
      "    return scale.astype(np.float64)[:, None] * (codes.astype(np.float64) + zero.astype(np.float64)[:, None])",
      "test_constant_group_is_exact_and_has_code_zero"),
+    ("metadata counted per scalar instead of per group",
+     "    return n_elements * (bits + meta_bits_per_group / group) / 8.0",
+     "    return n_elements * (bits + meta_bits_per_group) / 8.0",
+     "test_cache_size_accounting_reproduces_the_papers_quantisation_table"),
     ("the 16-bit tail quantised as well",
      "        if n_quant:\n            Kq[h, :n_quant]",
      "        if n_quant:\n            n_quant = K.shape[1] // GROUP_TOKENS * GROUP_TOKENS\n            Kq[h, :n_quant]",

@@ -235,3 +235,30 @@ def test_alibi_attention_over_a_quantised_cache():
         w = np.exp(sc - sc.max())
         assert np.allclose(got[0, h], (w[:, None] * Vq[0]).sum(axis=0) / w.sum(), rtol=0, atol=1e-12)
     assert ora.rel_l2(got, oq.decode_attention_quantized(q, K, V, [64], d_h)) > 0.05
+
+
+def test_cache_size_accounting_reproduces_the_papers_quantisation_table():
+    """Appendix, Quantization Results: every printed KV-cache size equals elements * (bits + 16 / group) / 8 in GiB,
+    rounded to two decimals -- 16 bits of metadata per group; 0 or 32 bits do not reproduce the table."""
+    import json, os
+    t = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
+    t = t["appendix_quantization_kv_sizes_GB"]
+    rows = []
+    for model in ("llama2_13b", "llama2_7b"):
+        m = t[model]
+        full = 2 * t["sequence_length"] * m["d_model"] * m["n_layers"]          # K and V scalars of one sequence
+        for bits, group, printed in m["standard"]:
+            rows.append((full, bits, group, printed))
+        for bits, group, printed in m["eigen"]:
+            rows.append((full * t["eigen_attention_compression"], bits, group, printed))
+    assert len(rows) == 15
+
+    def misses(meta):
+        return sum(abs(oq.quantized_cache_bytes(n, b, g, meta) / 2 ** 30 - printed) > 0.005 + 1e-12
+                   for n, b, g, printed in rows)
+    assert misses(16) == 0
+    assert misses(0) >= 5 and misses(32) >= 5
+    # the 16-bit baseline of the same accounting: 2 * 2048 * 4096 * 32 scalars at 16 bits and no groups = 1 GiB
+    assert oq.quantized_cache_bytes(2 * 2048 * 4096 * 32, 16, 1, 0) == 2 ** 30
+    # this build's format carries a scale and a zero: 4.5 bits per key scalar, 4.4 per value scalar at r_v = 80
+    assert oq.bits_per_element_q4(80, 80) == (4.5, 4.4)
