@@ -14,6 +14,9 @@ half a step, exactness on constant groups and on values that lie on the grid, ex
 codes, invariance of the codes under the affine map that the scale and zero absorb, and attention over the
 quantised cache being plain attention over the dequantised values.
 
+One thing here IS pinned to the paper: quantized_cache_bytes, the size accounting (bits + 16 / group per scalar), reproduces
+all 15 KV-cache sizes of the appendix's quantisation table.
+
 The reading:
   * 4 bits, asymmetric: a group with minimum lo and maximum hi gets  zero = fp16(lo),
     scale = fp16((hi - lo) / 15), both first clamped to the finite fp16 range; the quotient is taken in
