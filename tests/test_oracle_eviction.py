@@ -64,3 +64,19 @@ def test_h2o_selection_rule():
     assert oe.h2o_victim(acc, 2) == 3              # the two newest are protected
     assert oe.h2o_victim(acc, 3) == 1
     assert oe.h2o_victim(np.array([1.0, 1.0, 1.0]), 1) == 0     # ties: the oldest
+
+
+def test_combined_cache_size_is_the_product_the_paper_prints():
+    """Rank compression and token pruning shrink the cache along different axes: 0.6x ranks and 40 % of the tokens
+    give the 0.24x of the paper's H2O table."""
+    import json, os
+    v = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))["h2o_combination"]
+    n, H, d_h, L = 2000, 32, 100, 4
+    r = round(d_h * v["eigen_attention_cache"])
+    kept = round(n * v["tokens_kept"])
+    full = ora.kv_cache_bytes(1, n, H, d_h, d_h, L, 2)
+    assert abs(ora.kv_cache_bytes(1, kept, H, r, r, L, 2) / full - v["combined_cache"]) < 1e-12
+    # ... and that is what a fixed-budget cache of `kept` slots holds, whatever the policy evicts
+    cache = ora.RankCache.empty(1, H, r, r)
+    cache.append(0, np.zeros((kept, H, r)), np.zeros((kept, H, r)))
+    assert cache.elements() * 2 * L == ora.kv_cache_bytes(1, kept, H, r, r, L, 2)
