@@ -386,7 +386,9 @@ EA_API int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q,
  * position-free cache does not care where a token sits.
  *   dev_mass [B, H_kv, max_pages * page_tokens] float
  *   dev_ws   ea_attn_mass_workspace_bytes(desc, B, max_pages) bytes, 16-byte aligned
- * Reads the keys once (the values not at all).  H / H_kv <= 16. */
+ * Reads the keys once (the values not at all).  H / H_kv <= 16.
+ * The accumulator is updated with plain loads and stores: calls that overlap in time (other streams) must not
+ * share dev_mass or dev_ws. */
 EA_API int64_t ea_attn_mass_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t max_pages);
 EA_API int ea_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const void* dev_k_pool,
                     const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_mass,
