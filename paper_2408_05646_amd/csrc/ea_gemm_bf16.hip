@@ -138,6 +138,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
 #pragma unroll
       for (int i = 0; i < 4; ++i) *reinterpret_cast<bf16x8*>(&Bs[(tid + 256 * i) << 3]) = gb[i];
       __syncthreads();
+      __builtin_amdgcn_s_setprio(1);
       if (k0 + BK < K) gload(k0 + BK);
       // One straight pipeline over the two k steps of the tile: while the four MFMAs of one A fragment run, the
       // next A fragment (and, during the first k step, the W fragments of the second) come from LDS.
@@ -187,6 +188,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_s_setprio(0);
     }
   };
   if (swap) mainloop(std::true_type{});
