@@ -4,8 +4,10 @@
 // A is row-major (K contiguous).  W is packed in MFMA fragment order
 // [N/16][K/32][4 quads][16 channels][8 k]: the B operand of one (channel block, k step) is one
 // contiguous 1 KiB wave load, and a channel block's K range is one contiguous stream.
-//  - tiled kernel (M > 64): 128x128x64 (256x128x64 for M >= 2048) workgroup tiles staged
-//    through LDS, 2x2 waves, v_mfma_f32_16x16x32_bf16, XCD-aware banded tile order;
+//  - asynchronous kernel (M >= 2048, bf16 activations: the prefill): 256x256x64 workgroup tiles, eight waves,
+//    global tiles loaded straight into LDS, two stages;
+//  - tiled kernel (other M > 64): 128x128x64 (256x128x64 for M >= 2048 with float activations) workgroup tiles
+//    staged through registers and LDS, 2x2 waves, v_mfma_f32_16x16x32_bf16, XCD-aware banded tile order;
 //  - skinny kernel (M <= 64, the generation phase): one workgroup per 16 output
 //    channels, the four waves split K and stream the weight rows straight from
 //    HBM (the weights are read exactly once; x stays in L2).
@@ -188,6 +190,158 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
         __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
       }
       __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      __builtin_amdgcn_s_setprio(0);
+    }
+  };
+  if (swap) mainloop(std::true_type{});
+  else mainloop(std::false_type{});
+  ep.template store<MI>(swap, r0, c0, acc, M, N, col, quad);
+}
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// A raw buffer descriptor over n_bytes at base (reads past the end return zero).
+__device__ __forceinline__ i32x4 raw_buffer(const void* base, int64_t n_bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  return i32x4{(int)(a & 0xffffffffu), (int)((a >> 32) & 0xffffu), (int)n_bytes, 0x00020000};
+}
+
+// One 16-byte-per-lane buffer load whose data goes to LDS instead of registers: lane l's 16 bytes land at
+// lds_addr + 16 l (lds_addr wave-uniform), read from the descriptor at voff (per lane) + soff (uniform).
+// Written as an instruction rather than through the compiler's builtin: the compiler would otherwise make every
+// later LDS read wait for ALL such loads in flight, the prefetched stages included.  The waits are placed by hand.
+__device__ __forceinline__ void load_to_lds_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+
+// ---------------------------------------------------------------------------
+// Tiled kernel, asynchronous form (bf16 activations): 256x256 output tiles, eight waves of 128x64 each, and the global
+// tiles go straight into LDS (buffer loads with the LDS flag: lane l of a wave lands 16 bytes at base + 16 l, wherever
+// it read them from) -- two 64-wide stages, one barrier per stage, no staging registers and no LDS stores.
+//   A stage: 256 rows x 128 bytes, a 1 KiB unit = 8 rows; the eight 16-byte k chunks of a row sit at position
+//            chunk ^ ((row >> 1) & 7), so the 16 rows a fragment read touches fall into 16 different bank groups;
+//   W stage: 16 channel blocks x 2 k steps x 1 KiB in fragment order, as in memory.
+// ---------------------------------------------------------------------------
+constexpr int kAsyncLds = 2 * (256 * 64 + 256 * 64) * 2;      // bytes of dynamic LDS: two stages of A and W
+
+template <typename Epilogue>
+__global__ __launch_bounds__(512, 1) void gemm_bf16_async_kernel(const uint16_t* __restrict__ A,
+                                                                 const uint16_t* __restrict__ Wt, int32_t M, int32_t N,
+                                                                 int32_t K, Epilogue ep) {
+  constexpr int MI = 8, BM = 256, BN = 256, BK = 64;
+  extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+  // stage s: A at s * 32768 elements (A then W, 16384 elements each)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 15, quad = lane >> 4;
+  const int wm = wave >> 2, wn = wave & 3;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int per_xcd = (total + 7) / 8;
+    const int remapped = (pid % 8) * per_xcd + pid / 8;
+    if (per_xcd * 8 == total) pid = remapped;
+  }
+  constexpr int kGroupM = 8;
+  const int band = pid / (kGroupM * tiles_n);
+  const int band_rows = min(kGroupM, tiles_m - band * kGroupM);
+  const int in_band = pid - band * kGroupM * tiles_n;
+  const int tm = band * kGroupM + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int r0 = m0 + wm * (16 * MI), c0 = n0 + wn * 64;
+  const bool swap = ep.swap_for(c0);
+
+  f32x4 acc[MI][4];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int ksteps = K >> 5;                 // 32-wide k steps of the packed weights
+  const int nst = (K + BK - 1) / BK;         // 64-wide stages (the last may hold one k step only)
+  const int nblks = (N + 15) >> 4;
+  const i32x4 a_rsrc = raw_buffer(A + (int64_t)m0 * K, (int64_t)min(BM, M - m0) * K * 2);
+  const i32x4 w_rsrc = raw_buffer(Wt + (((int64_t)(n0 >> 4) * ksteps) << 9),
+                                  (int64_t)min(BN / 16, nblks - (n0 >> 4)) * ksteps * 1024);
+  // this wave's units of a stage: A units 4 wave .. + 3 (8 rows each), W units 4 wave .. + 3
+  // (unit = channel block 2 wave + i / 2, k step i % 2)
+  constexpr uint32_t kOob = 0x7ffffff0u;     // beyond any descriptor: reads as zero
+  uint32_t a_off[4], w_off[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = (wave * 4 + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);           // the k chunk that belongs at this lane's LDS position
+    a_off[i] = (uint32_t)((row * K + chunk * 8) * 2);
+    const int nb = wave * 2 + (i >> 1), kst = i & 1;
+    w_off[i] = (uint32_t)(((nb * ksteps + kst) << 10) + (lane << 4));
+  }
+  const bool k_even = (K & 63) == 0;
+  const uint32_t lds0 = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const uint16_t*)smem);
+  auto issue = [&](int buf, int s) __attribute__((always_inline)) {
+    const bool tail = !k_even && s == nst - 1;                 // only the first 32 of this stage's 64 columns exist
+    const uint32_t a_dst = lds0 + buf * 65536 + wave * 4096, w_dst = lds0 + buf * 65536 + 32768 + wave * 4096;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int chunk = (lane & 7) ^ ((((wave * 4 + i) * 8 + (lane >> 3)) >> 1) & 7);
+      load_to_lds_b128(a_rsrc, a_dst + i * 1024, (tail && chunk >= 4) ? kOob : a_off[i], s * 128);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      load_to_lds_b128(w_rsrc, w_dst + i * 1024, (tail && (i & 1)) ? kOob : w_off[i], s << 11);
+  };
+  // fragment reads: row wm*128 + 16 i + col, k chunk 4 ks + quad at its swizzled place
+  const int a_lane0 = (wm * 128 + col) * BK + ((quad ^ ((col >> 1) & 7)) << 3);
+  const int a_lane1 = (wm * 128 + col) * BK + (((4 + quad) ^ ((col >> 1) & 7)) << 3);
+  const int w_lane = (wn * 4 * 2 * 64 + lane) << 3;            // unit (channel block 4 wn + j, k step ks) = 2 (4 wn + j) + ks
+
+  auto mainloop = [&](auto swap_tag) __attribute__((always_inline)) {
+    constexpr bool SWAP = decltype(swap_tag)::value;
+    issue(0, 0);
+    for (int s = 0; s < nst; ++s) {
+      const int buf = s & 1;
+      __builtin_amdgcn_s_waitcnt(0x0f70);                           // vmcnt(0): this wave's loads of stage s landed
+      __builtin_amdgcn_s_barrier();                                 // ... so have everybody's, and stage s-1 is left
+      asm volatile("" ::: "memory");                                // (no LDS read may move above the barrier)
+      __builtin_amdgcn_s_setprio(1);
+      if (s + 1 < nst) issue(buf ^ 1, s + 1);
+      const uint16_t* as = smem + buf * 32768;
+      const uint16_t* bs = as + 16384;
+      bf16x8 w0[4], w1[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w0[j] = *reinterpret_cast<const bf16x8*>(bs + w_lane + j * 1024);
+      bf16x8 af[3];
+      af[0] = *reinterpret_cast<const bf16x8*>(as + a_lane0);
+      af[1] = *reinterpret_cast<const bf16x8*>(as + a_lane0 + 16 * BK);
+#pragma unroll
+      for (int x = 0; x < 2 * MI; ++x) {
+        const int ks = x / MI, i = x % MI;
+        if (x + 2 < 2 * MI) {
+          const int ks2 = (x + 2) / MI, i2 = (x + 2) % MI;
+          af[(x + 2) % 3] = *reinterpret_cast<const bf16x8*>(as + (ks2 ? a_lane1 : a_lane0) + i2 * 16 * BK);
+        }
+        if (x < 4) w1[x] = *reinterpret_cast<const bf16x8*>(bs + w_lane + x * 1024 + 512);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bf16x8 w = ks == 0 ? w0[j] : w1[j];
+          acc[i][j] = SWAP ? mfma16(w, af[x % 3], acc[i][j]) : mfma16(af[x % 3], w, acc[i][j]);
+        }
+      }
+      __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+#pragma unroll
+      for (int x = 4; x < 2 * MI - 2; ++x) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
       __builtin_amdgcn_s_setprio(0);
     }
   };
@@ -511,6 +665,22 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
     const int64_t tiles = (int64_t)((N + 127) / 128) * ((M + bm - 1) / bm);
     if (tiles > INT32_MAX) return EA_ERR_SHAPE;
     dim3 grid((uint32_t)tiles), block(256);
+    if constexpr (!A_F32) {
+      if (bm == 256) {
+        // bf16 activations, many rows: the asynchronous 256x256 kernel (128 KiB of dynamic LDS, one workgroup per CU)
+        const int64_t t2 = (int64_t)((N + 255) / 256) * ((M + 255) / 256);
+        if (t2 > INT32_MAX) return EA_ERR_SHAPE;
+        static bool attr_set = false;      // (a benign race: the attribute is idempotent)
+        if (!attr_set) {
+          if (hipFuncSetAttribute((const void*)gemm_bf16_async_kernel<Epilogue>,
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, kAsyncLds) != hipSuccess)
+            return EA_ERR_DEVICE;
+          attr_set = true;
+        }
+        gemm_bf16_async_kernel<Epilogue><<<dim3((uint32_t)t2), dim3(512), kAsyncLds, st>>>((const uint16_t*)A, w, M, N, K, ep);
+        return launch_status();
+      }
+    }
     if (bm == 256) gemm_bf16_tiled_kernel<Epilogue, A_F32, 8><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
     else gemm_bf16_tiled_kernel<Epilogue, A_F32, 4><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
   }
