@@ -666,8 +666,8 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
     if (tiles > INT32_MAX) return EA_ERR_SHAPE;
     dim3 grid((uint32_t)tiles), block(256);
     if constexpr (!A_F32) {
-      if (bm == 256) {
-        // bf16 activations, many rows: the asynchronous 256x256 kernel (128 KiB of dynamic LDS, one workgroup per CU)
+      if (bm == 256 && N > 128) {
+        // bf16 activations, many rows (and more than one 128-wide column tile): the asynchronous 256x256 kernel (128 KiB of dynamic LDS, one workgroup per CU)
         const int64_t t2 = (int64_t)((N + 255) / 256) * ((M + 255) / 256);
         if (t2 > INT32_MAX) return EA_ERR_SHAPE;
         static bool attr_set = false;      // (a benign race: the attribute is idempotent)

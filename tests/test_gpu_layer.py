@@ -117,6 +117,7 @@ def test_project_qkv(dtype, d, H, Hkv, r_k, r_v, B, T, P, lens):
     (ea.EA_BF16, 256, 4, 80, 16), (ea.EA_BF16, 512, 8, 48, 37), (ea.EA_BF16, 256, 4, 40, 300),
     (ea.EA_BF16, 4096, 32, 80, 16),
     (ea.EA_BF16, 256, 4, 40, 2100), (ea.EA_BF16, 200, 2, 16, 2048), (ea.EA_BF16, 640, 4, 16, 2305),   # tall tiles; 5, 1, 2 k steps
+    (ea.EA_BF16, 128, 4, 16, 2100),                                # tall tiles, a single 128-wide column tile
 ])
 def test_out_proj(dtype, d, H, r_v, M):
     print(f"out_proj dtype={dtype} d={d} H={H} r_v={r_v} M={M}", flush=True)
