@@ -46,10 +46,16 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
   // ---- keys: x[token][channel] <- the tile in its fragment order [4 blocks][nch chunks][16 tokens][8 channels]
   {
     const uint16_t* kb = a.k_pool + (int64_t)src * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tile * (kTile * g.r_k_pad);
-    for (int e = tid; e < kTile * g.r_k_pad; e += 256) {
-      const int ce = e & 7, t = (e >> 3) & 15, rest = e >> 7;
+    for (int u = tid; u < kTile * qg.nch; u += 256) {           // 16-byte units: 8 channels of one token
+      const int t = u & 15, rest = u >> 4;
       const int chunk = rest % qg.nch, tb = rest / qg.nch;
-      x[tb * 16 + t][chunk * 8 + ce] = bf16_bits_to_float(kb[e]);
+      const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (u << 3));
+      float* dst = &x[tb * 16 + t][chunk * 8];
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        dst[2 * p] = __builtin_bit_cast(float, w[p] << 16);
+        dst[2 * p + 1] = __builtin_bit_cast(float, w[p] & 0xffff0000u);
+      }
     }
     __syncthreads();
     if (tid < 128) {
@@ -88,10 +94,16 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
   // ---- values: fragment order [2 groups][ncb blocks][4 quads][16 channels][8 token slots]
   {
     const uint16_t* vb = a.v_pool + (int64_t)src * g.v_page + (int64_t)kvh * g.v_slab + (int64_t)tile * (kTile * g.r_v_pad);
-    for (int e = tid; e < kTile * g.r_v_pad; e += 256) {
-      const int j = e & 7, ch = (e >> 3) & 15, quad = (e >> 7) & 3, rest = e >> 9;
+    for (int un = tid; un < kTile * g.r_v_pad / 8; un += 256) {  // 16-byte units: 8 token slots of one channel
+      const int ch = un & 15, quad = (un >> 4) & 3, rest = un >> 6;
       const int cb = rest % qg.ncb, u = rest / qg.ncb;
-      x[u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3)][cb * 16 + ch] = bf16_bits_to_float(vb[e]);
+      const u32x4 w = *reinterpret_cast<const u32x4*>(vb + (un << 3));
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int j0 = 2 * p, j1 = 2 * p + 1;
+        x[u * 32 + (j0 >> 2) * 16 + quad * 4 + (j0 & 3)][cb * 16 + ch] = __builtin_bit_cast(float, w[p] << 16);
+        x[u * 32 + (j1 >> 2) * 16 + quad * 4 + (j1 & 3)][cb * 16 + ch] = __builtin_bit_cast(float, w[p] & 0xffff0000u);
+      }
     }
     __syncthreads();
     uint8_t* vo = a.vq_pool + (int64_t)dst * qg.v_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.v_tile;
@@ -144,26 +156,37 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     u += 0x7fffu + ((u >> 16) & 1u);                       // round to nearest even (finite inputs)
     return (uint16_t)(u >> 16);
   };
-  for (int e = tid; e < kTile * g.r_k_pad; e += 256) {
-    const int tt = e / g.r_k_pad, c = e % g.r_k_pad;
-    float val = 0.f;
-    if (c < g.r_k) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c));
-      const _Float16* sp = reinterpret_cast<const _Float16*>(kb + q4_k_scale_off(qg, c));
-      val = fmaf((float)sp[0], (float)((w >> q4_nibble_shift(c & 7)) & 15u), (float)sp[8]);
-    }
-    ko[bf16_k_slab_off(tile * kTile + tt, c, g.r_k_pad)] = to_bf16(val);
+  auto pack2 = [&](float lo, float hi) -> uint32_t { return (uint32_t)to_bf16(lo) | ((uint32_t)to_bf16(hi) << 16); };
+  // keys: one 16-byte unit of the bfloat16 tile = the 8 channels of one code dword
+  for (int u = tid; u < kTile * qg.nch; u += 256) {
+    const int t = u & 15, rest = u >> 4;
+    const int chunk = rest % qg.nch, tb = rest / qg.nch;
+    const int tt = tb * 16 + t, c0 = chunk * 8;
+    const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c0));
+    const _Float16* sp = reinterpret_cast<const _Float16*>(kb + q4_k_scale_off(qg, c0));
+    float val[8];
+#pragma unroll
+    for (int ce = 0; ce < 8; ++ce)
+      val[ce] = c0 + ce < g.r_k ? fmaf((float)sp[ce], (float)((w >> q4_nibble_shift(ce)) & 15u), (float)sp[8 + ce]) : 0.f;
+    *reinterpret_cast<u32x4*>(ko + bf16_k_slab_off(tile * kTile + tt, c0, g.r_k_pad)) =
+        u32x4{pack2(val[0], val[1]), pack2(val[2], val[3]), pack2(val[4], val[5]), pack2(val[6], val[7])};
   }
-  for (int e = tid; e < kTile * g.r_v_pad; e += 256) {
-    const int tt = e / g.r_v_pad, c = e % g.r_v_pad;
-    float val = 0.f;
+  // values: one 16-byte unit = the 8 token slots of one channel, one code dword
+  for (int un = tid; un < kTile * g.r_v_pad / 8; un += 256) {
+    const int ch = un & 15, quad = (un >> 4) & 3, rest = un >> 6;
+    const int cb = rest % qg.ncb, u = rest / qg.ncb;
+    const int c = cb * 16 + ch, tt0 = u * 32 + quad * 4;
+    float val[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (c < g.r_v) {
-      int slot;
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt, c, &slot));
-      const _Float16* sp = reinterpret_cast<const _Float16*>(vb + q4_v_scale_off(qg, tt));
-      val = fmaf((float)sp[0], (float)((w >> q4_nibble_shift(slot)) & 15u), (float)sp[64]);
+      int slot0;
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt0, c, &slot0));
+      const _Float16* sp = reinterpret_cast<const _Float16*>(vb + q4_v_scale_off(qg, tt0));
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj)
+        val[jj] = fmaf((float)sp[jj], (float)((w >> q4_nibble_shift(jj)) & 15u), (float)sp[64 + jj]);
     }
-    vo[bf16_v_slab_off(tile * kTile + tt, c, g.r_v_pad)] = to_bf16(val);
+    *reinterpret_cast<u32x4*>(vo + bf16_v_slab_off(tile * kTile + tt0, c, g.r_v_pad)) =
+        u32x4{pack2(val[0], val[1]), pack2(val[2], val[3]), pack2(val[4], val[5]), pack2(val[6], val[7])};
   }
 }
 
