@@ -225,6 +225,27 @@ def test_f32_rope_decode_step(r):
         assert ora.rel_l2(y.cpu().numpy(), y_std) <= 2e-5
 
 
+def test_bf16_project_qkv_rope_many_rows():
+    """2100 prompt tokens of one sequence at once (the tall-tile GEMM with the rotary layout of its output: full-rank
+    query, rank-r keys of the shared basis, rank-r values): q and the cache contents against the oracle."""
+    desc = ea.LayerDesc(256, 4, 2, 64, 40, 32, ea.EA_BF16, 64)
+    g = synth.rng(30)
+    wqkv, _, _, _, folded_q, _ = rope_weights(desc, g)
+    T = 2100
+    x = quantize(desc, synth.gaussian(g, (T, 256)))
+    dc = DeviceCache(desc, [np.zeros((2, 0, 40))], [np.zeros((2, 0, 32))], g, extra_len=T)
+    q = torch.full((T, 4, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ea.project_qkv_rope(desc, to_dev(desc, x), wqkv, q, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, T)
+    kd = torch.zeros((1, 2, T, 40), dtype=torch.bfloat16, device="cuda")
+    vd = torch.zeros((1, 2, T, 32), dtype=torch.bfloat16, device="cuda")
+    ea.cache_gather(desc, kd, vd, dc.k_pool, dc.v_pool, dc.page_table, pos0=0)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref = ora.project_qkv(x, *folded_q[:3])             # [T, H, d_h], [T, Hkv, r_k], [T, Hkv, r_v]
+    assert_close(q.float().cpu().numpy(), q_ref, TOL_BF16, "q")
+    assert_close(kd.float().cpu().numpy()[0], k_ref.transpose(1, 0, 2), TOL_BF16, "cached keys")
+    assert_close(vd.float().cpu().numpy()[0], v_ref.transpose(1, 0, 2), TOL_BF16, "cached values")
+
+
 def test_bf16_rope_decode_steps_end_to_end():
     """GQA layer (d=512, 8 query heads on 2 kv heads, d_h=128, r=(80,48)), bf16: the cache is filled through
     ea_project_qkv_rope (T = 333 tokens at once) and the prompt attended with ea_prefill_attn_rope, then three
