@@ -210,6 +210,8 @@ __device__ __forceinline__ i32x4 raw_buffer(const void* base, int64_t n_bytes) {
 // lds_addr + 16 l (lds_addr wave-uniform), read from the descriptor at voff (per lane) + soff (uniform).
 // Written as an instruction rather than through the compiler's builtin: the compiler would otherwise make every
 // later LDS read wait for ALL such loads in flight, the prefetched stages included.  The waits are placed by hand.
+// The instruction takes its LDS base from M0, which this statement overwrites; the compiler keeps M0 reserved and does not
+// hold values in it (the kernel using this has no other M0 consumer: no LDS-direct builtins, no sendmsg, no movrel).
 __device__ __forceinline__ void load_to_lds_b128(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :
