@@ -129,7 +129,7 @@ __device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&ac
     for (int cb = 0; cb < NCB; ++cb) {
       const int c = cb * 16 + quad * 4;
       if (qi >= a.n_q) {
-      } else if (c + 3 < g.r_v) {
+      } else if (c + 3 < g.r_v && (g.r_v & 3) == 0) {          // rows of whole 8-byte units
         u32x2 w;
         w[0] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][1] * inv) << 16);
         w[1] = (uint32_t)f32_to_bf16_rne(acc[qb][cb][2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[qb][cb][3] * inv) << 16);
@@ -181,7 +181,16 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int k = ks * 32 + quad * 8;
-      qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
+      if ((g.r_k & 7) == 0) {                                     // rows of whole 16-byte units
+        qf[qb][ks] = (qi < a.n_q && k < g.r_k) ? *reinterpret_cast<const bf16x8*>(qrow + k) : zero_frag();
+      } else {                                                    // any rank: channel by channel, zero past the rank
+        qf[qb][ks] = zero_frag();
+        if (qi < a.n_q) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (k + j < g.r_k) qf[qb][ks][j] = __builtin_bit_cast(__bf16, qrow[k + j]);
+        }
+      }
       // the softmax scale goes into the query (one more rounding to bfloat16, of the size of P's own)
       if (!a.k_compact) {
 #pragma unroll
@@ -314,7 +323,6 @@ static int prefill_bf16_launch(const ea_layer_desc* d, const Geo& g, const void*
                                const void* v_pool, const int32_t* page_table, const int32_t* seq_len, void* out,
                                int32_t B, int32_t n, hipStream_t st, int32_t k_compact, const float* alibi) {
   if ((int64_t)((n + 127) / 128) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
-  if (g.r_k % 8 != 0 || g.r_v % 4 != 0) return EA_ERR_SHAPE;     // 16-byte q rows, 8-byte output stores
   PrefillArgs a;
   a.q = (const uint16_t*)q;
   a.k_pool = (const uint16_t*)k_pool;

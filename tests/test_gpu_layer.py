@@ -148,6 +148,8 @@ def test_out_proj(dtype, d, H, r_v, M):
     (ea.EA_BF16, 2, 2, 128, 128, [200], 200, 128),                # full rank
     (ea.EA_BF16, 2, 1, 16, 112, [129], 129, 64),
     (ea.EA_BF16, 2, 2, 64, 64, [64, 1], 1, 64),                   # a single query row
+    (ea.EA_BF16, 4, 2, 30, 33, [150, 70], 70, 64),                # ranks off the 8-channel chunk and the 4-channel store
+    (ea.EA_BF16, 2, 2, 83, 50, [300], 300, 128),
 ])
 def test_prefill_attn(dtype, H, Hkv, r_k, r_v, lens, n, P):
     print(f"prefill dtype={dtype} H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} n={n}", flush=True)
