@@ -111,3 +111,26 @@ def test_q4_prefill_alibi_and_rotary_random_shapes(seed):
                             dc.v_pool, dc.page_table, dc.seq_len, orr, n_splits=S_r, ws=ws)
         torch.cuda.synchronize()
         assert_close(orr.cpu().numpy(), ora.decode_attention_rope(qr, cache, U, 128), TOL_BF16, "rotary decode")
+
+
+@pytest.mark.parametrize("seed", [301])
+def test_projection_gemms_random_shapes(seed):
+    """ea_project_qkv (q, and the cache contents it appends) and ea_out_proj over random widths, ranks, row counts from
+    one to a few thousand (the generation-phase kernel, the 128- and 256-row tiled kernels, the asynchronous one) and
+    sequences that already hold a few tokens."""
+    import contextlib
+    import io
+    import test_gpu_layer as layer
+    rs = np.random.default_rng(seed)
+    for case in range(40):
+        H, Hkv = 4, int(rs.choice([1, 2, 4]))
+        r_k, r_v = int(rs.integers(8, 129)), int(rs.integers(1, 17)) * 8          # (H r_v) % 32 == 0 for the packing
+        P, d = int(rs.choice([64, 128, 192])), int(rs.integers(3, 21)) * 32
+        B = int(rs.integers(1, 4))
+        T = int(rs.choice([1, 5, 16, 21, 64, 100, 333, 700, 2048 // B + 1, 2500 // B]))
+        lens = [int(rs.choice([0, 5, 63, 64, 100])) for _ in range(B)]
+        M = int(rs.choice([1, 16, 37, 64, 65, 127, 300, 2047, 2048, 2100, 2600, 3000]))
+        print(f"seed {seed} case {case}: d={d} H={H}/{Hkv} r=({r_k},{r_v}) P={P} B={B} T={T} lens={lens} M={M}", flush=True)
+        with contextlib.redirect_stdout(io.StringIO()):
+            layer.test_project_qkv(ea.EA_BF16, d, H, Hkv, r_k, r_v, B, T, P, lens)
+            layer.test_out_proj(ea.EA_BF16, d, H, r_v, M)
