@@ -1,7 +1,7 @@
 """Seeded random shapes through the C ABI against the fp64 oracle: group sizes, head counts, ranks 8..128 (mostly off
 every chunk size), page sizes, ragged / empty / tile-edge lengths and split counts drawn at random, for the
 generation-phase attention in its five forms (plain, with the attention mass, over the 4-bit cache, ALiBi, rotary)
-and the causal prefill attention."""
+and the causal prefill attention, the projection GEMMs, and the fp32 form of every call."""
 import numpy as np
 import pytest
 import torch
@@ -134,3 +134,38 @@ def test_projection_gemms_random_shapes(seed):
         with contextlib.redirect_stdout(io.StringIO()):
             layer.test_project_qkv(ea.EA_BF16, d, H, Hkv, r_k, r_v, B, T, P, lens)
             layer.test_out_proj(ea.EA_BF16, d, H, r_v, M)
+
+
+@pytest.mark.parametrize("seed", [401])
+def test_f32_path_random_shapes(seed):
+    """The fp32 (reference-precision) form of every call: any rank from 1, any page size that is a multiple of 16,
+    group sizes 1..4, empty and tile-edge lengths, through the parametrised tests of the other files."""
+    import contextlib
+    import io
+    import test_gpu_alibi as alibi
+    import test_gpu_eviction as evict
+    import test_gpu_layer as layer
+    import test_gpu_rope as rope
+    rs = np.random.default_rng(seed)
+    for case in range(40):
+        G, Hkv = int(rs.choice([1, 2, 3, 4])), int(rs.choice([1, 2, 3]))
+        H = G * Hkv
+        r_k, r_v = int(rs.integers(1, 129)), int(rs.integers(1, 129))
+        P, B = int(rs.choice([16, 32, 48, 64, 80])), int(rs.integers(1, 4))
+        lens = [int(rs.choice([0, 1, 15, 16, 17, int(rs.integers(1, 1500))])) for _ in range(B)]
+        if max(lens) == 0:
+            lens[0] = 9
+        S = int(rs.choice([0, 1, 2, 3]))
+        d_h = int(rs.choice([32, 48, 64, 128]))
+        rk_rot = int(rs.integers(1, d_h + 1))
+        full = [max(1, n) for n in lens]
+        n = int(rs.integers(1, min(full) + 1))
+        print(f"seed {seed} case {case}: H={H}/{Hkv} r=({r_k},{r_v}) d_h={d_h} r_k(rotary)={rk_rot} P={P} lens={lens} "
+              f"S={S} n={n}", flush=True)
+        with contextlib.redirect_stdout(io.StringIO()):
+            dec.test_f32_shapes(H, Hkv, r_k, r_v, lens, P, S)
+            rope.test_f32_shapes(H, Hkv, d_h, rk_rot, r_v, lens, P, S, 10000.0)
+            layer.test_prefill_attn(ea.EA_F32, H, Hkv, r_k, r_v, full, n, P)
+            alibi.test_prefill_alibi(ea.EA_F32, H, Hkv, r_k, r_v, full, n, P)
+            rope.test_prefill_rope(ea.EA_F32, H, Hkv, d_h, rk_rot, r_v, full, n, P)
+            evict.test_attn_mass_matches_oracle(ea.EA_F32, H, Hkv, r_k, lens, P)
