@@ -9,7 +9,8 @@
 //   online softmax per query column (rows = kv tokens: 16 registers + two cross-quad shuffles)
 //   O^T[r_v x 16 q]  += V_tile^T . P^T            (P rounded to bf16; row sums by an all-ones MFMA)
 // Every K / V fragment is loaded once per wave and tile and reused for the QT query blocks.
-// Tiles below the diagonal take a lean unmasked path; the grid is ordered by work (longest query tiles first).
+// Tiles below the diagonal take an unmasked path that does not search for the tile's maximum (the row sums are
+// inspected every few tiles instead, see the tile loop); the grid is ordered by work (longest query tiles first).
 #pragma once
 #include "ea_common.h"
 #include "ea_epilogue.h"
@@ -84,6 +85,38 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
 #pragma unroll
     for (int tb = 0; tb < 4; ++tb) s[tb] -= delta;
     m = m_new;
+  }
+  bf16x8 pf[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
+  lacc = mfma16(ones, pf[0], lacc);
+  lacc = mfma16(ones, pf[1], lacc);
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
+    acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
+  }
+}
+
+// The same tile against the same block when nothing is masked and the reference exponent m is already finite,
+// without looking for the tile's maximum: the exponentials are taken against the reference as it stands and the
+// caller inspects the row sums afterwards (see the tile loop).  Per score that leaves the exponential and half a
+// conversion for the vector unit.
+template <int KS, int NCB>
+__device__ __forceinline__ void attend_block_optimistic(const bf16x8 (&kf)[4][KS], const bf16x8 (&vf)[2][NCB],
+                                                        const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
+                                                        f32x4& lacc, float m) {
+  const f32x4 neg_m{-m, -m, -m, -m};
+  f32x4 s[4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb) {
+    s[tb] = mfma16(kf[tb][0], q[0], neg_m);
+#pragma unroll
+    for (int ks = 1; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
   bf16x8 pf[2];
 #pragma unroll
@@ -250,6 +283,19 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
         vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
   };
 
+
+  // Unmasked tiles after the first run optimistically: no search for the tile's maximum, the exponentials are
+  // taken against the reference exponent the earlier tiles left (exact in floating point whatever the reference,
+  // as long as nothing overflows).  Every eighth tile, and after the last, the row sums are looked at -- they only
+  // grow between two looks, so nothing is missed: one that passed 2^kGrow moves its reference by kGrow
+  // (accumulators scaled down, a handful of times per query at most); one that passed 2^kAbort, or is not a
+  // number, means the scores rose by more than the headroom since the last look -- then the wave starts over and
+  // takes every tile with the exact maximum (P <= row sum < 2^kAbort otherwise, so the output accumulators are as
+  // far from overflow as the values allow).  ALiBi tiles always take the exact form.
+  constexpr float kGrow = 32.0f, kAbort = 64.0f;
+  bool optimistic = !ALIBI;
+  for (;;) {                                                     // one walk; a second, exact one if the first was lost
+  bool lost_walk = false;
   int page = -1;
   if (t_end > 0) {
     page = tile_page(0);
@@ -258,14 +304,17 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
     load_k(0, max(page, 0));
     load_v(0, max(page, 0));
   }
-
   for (int t = 0; t < t_end; ++t) {
     const int tok0 = t * kTile;
     const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;   // no masking needed
     const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
     const bool have_n = t + 1 < t_end;
     const int page_n = have_n ? tile_page(t + 1) : -1;
-    if (full) {
+    if (full && optimistic && t > 0) {
+#pragma unroll
+      for (int qb = 0; qb < QT; ++qb)
+        attend_block_optimistic<KS, NCB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
+    } else if (full) {
 #pragma unroll
       for (int qb = 0; qb < QT; ++qb)
         attend_block<KS, NCB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad,
@@ -279,6 +328,30 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
                                            slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
       }
     }
+    if (optimistic && ((t & 7) == 7 || t + 1 == t_end)) {
+      bool grown = false;
+#pragma unroll
+      for (int qb = 0; qb < QT; ++qb) grown |= !(lacc[qb][0] < __builtin_exp2f(kGrow));
+      if (__any(grown)) {
+        bool lost = false;
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb) lost |= !(lacc[qb][0] < __builtin_exp2f(kAbort));
+        if (__any(lost)) {                                       // wave-uniform
+          lost_walk = true;
+          break;
+        } else {
+#pragma unroll
+          for (int qb = 0; qb < QT; ++qb) {
+            const bool g_qb = !(lacc[qb][0] < __builtin_exp2f(kGrow));
+            const float alpha = g_qb ? __builtin_exp2f(-kGrow) : 1.0f;
+            m[qb] += g_qb ? kGrow : 0.0f;
+            lacc[qb] *= alpha;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] *= alpha;
+          }
+        }
+      }
+    }
     // the next tile is requested into the registers the current one has just left; without the barrier the
     // scheduler would start these loads early into a second set of registers and spill
     __builtin_amdgcn_sched_barrier(0);
@@ -287,6 +360,16 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
       load_v(t + 1, max(page_n, 0));
     }
     page = page_n;
+  }
+  if (!lost_walk) break;
+  optimistic = false;
+#pragma unroll
+  for (int qb = 0; qb < QT; ++qb) {
+    m[qb] = -INFINITY;
+    lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   }
   write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
 }

@@ -169,6 +169,37 @@ def test_prefill_attn(dtype, H, Hkv, r_k, r_v, lens, n, P):
     print(f"  rel-L2 {err:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("shape", ["slow rise", "steep rise", "one giant key"])
+@pytest.mark.parametrize("r_k,r_v", [(64, 64), (128, 128), (80, 48)])
+def test_prefill_attn_scores_far_above_the_first_tile(shape, r_k, r_v):
+    """The bf16 kernel takes unmasked tiles without searching for their maximum and looks at the row sums every few
+    tiles.  Scores that climb along the sequence make it move its reference exponent (slow rise: 48 binary orders
+    over the sequence), or give the walk up and redo it with the exact maximum (steep rise: 200 orders within eight
+    tiles; one key whose score overflows fp32 when exponentiated against the old reference)."""
+    print(f"prefill {shape} r=({r_k},{r_v})", flush=True)
+    H, d_h, n, P = 2, 128, 1536, 64
+    desc = ea.LayerDesc(H * d_h, H, H, d_h, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(23, r_k, len(shape))
+    u = synth.gaussian(g, (H, r_k))
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    rise = {"slow rise": 48.0, "steep rise": 600.0, "one giant key": 0.0}[shape]       # in binary orders over n tokens
+    c = rise * np.sqrt(d_h) / (np.log2(np.e) * 4.0)
+    ramp = (np.arange(n) / n)[None, :, None]
+    K = c * ramp * u[:, None, :] + 0.3 * synth.gaussian(g, (H, n, r_k))
+    if shape == "one giant key":
+        K[:, 700] = 1000.0 * u
+    V = synth.gaussian(g, (H, n, r_v))
+    q = 4.0 * u[None, None] + 0.3 * synth.gaussian(g, (1, n, H, r_k))
+    K, V, q = quantize(desc, K), quantize(desc, V), quantize(desc, q)
+    dc = DeviceCache(desc, [K], [V], g)
+    out = torch.full((1, n, H, r_v), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ea.prefill_attn(desc, to_dev(desc, q), dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, out)
+    torch.cuda.synchronize()
+    ref = ora.prefill_attention(q, ora.RankCache.from_arrays([K], [V]), d_h)
+    err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "prefill")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
 # ---------------------------------------------------------------------------
 # config 1 end to end: project -> append -> decode -> out_proj, r = 32 and the full-rank rerun r = 64
 # ---------------------------------------------------------------------------
