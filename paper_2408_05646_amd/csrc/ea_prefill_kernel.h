@@ -295,81 +295,81 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
   constexpr float kGrow = 32.0f, kAbort = 64.0f;
   bool optimistic = !ALIBI;
   for (;;) {                                                     // one walk; a second, exact one if the first was lost
-  bool lost_walk = false;
-  int page = -1;
-  if (t_end > 0) {
-    page = tile_page(0);
-    // a tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are masked
-    // (limit = 0 below): no load sits behind a data-dependent branch
-    load_k(0, max(page, 0));
-    load_v(0, max(page, 0));
-  }
-  for (int t = 0; t < t_end; ++t) {
-    const int tok0 = t * kTile;
-    const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;   // no masking needed
-    const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
-    const bool have_n = t + 1 < t_end;
-    const int page_n = have_n ? tile_page(t + 1) : -1;
-    if (full && optimistic && t > 0) {
-#pragma unroll
-      for (int qb = 0; qb < QT; ++qb)
-        attend_block_optimistic<KS, NCB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
-    } else if (full) {
-#pragma unroll
-      for (int qb = 0; qb < QT; ++qb)
-        attend_block<KS, NCB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0, quad,
-                                            slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
-    } else {
-      if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
-#pragma unroll
-      for (int qb = 0; qb < QT; ++qb) {
-        const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
-        attend_block<KS, NCB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis, quad,
-                                           slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
-      }
+    bool lost_walk = false;
+    int page = -1;
+    if (t_end > 0) {
+      page = tile_page(0);
+      // a tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are masked
+      // (limit = 0 below): no load sits behind a data-dependent branch
+      load_k(0, max(page, 0));
+      load_v(0, max(page, 0));
     }
-    if (optimistic && ((t & 7) == 7 || t + 1 == t_end)) {
-      bool grown = false;
+    for (int t = 0; t < t_end; ++t) {
+      const int tok0 = t * kTile;
+      const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;   // no masking needed
+      const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
+      const bool have_n = t + 1 < t_end;
+      const int page_n = have_n ? tile_page(t + 1) : -1;
+      if (full && optimistic && t > 0) {
 #pragma unroll
-      for (int qb = 0; qb < QT; ++qb) grown |= !(lacc[qb][0] < __builtin_exp2f(kGrow));
-      if (__any(grown)) {
-        bool lost = false;
+        for (int qb = 0; qb < QT; ++qb)
+          attend_block_optimistic<KS, NCB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
+      } else if (full) {
 #pragma unroll
-        for (int qb = 0; qb < QT; ++qb) lost |= !(lacc[qb][0] < __builtin_exp2f(kAbort));
-        if (__any(lost)) {                                       // wave-uniform
-          lost_walk = true;
-          break;
-        } else {
+        for (int qb = 0; qb < QT; ++qb)
+          attend_block<KS, NCB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0,
+                                              quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
+      } else {
+        if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
 #pragma unroll
-          for (int qb = 0; qb < QT; ++qb) {
-            const bool g_qb = !(lacc[qb][0] < __builtin_exp2f(kGrow));
-            const float alpha = g_qb ? __builtin_exp2f(-kGrow) : 1.0f;
-            m[qb] += g_qb ? kGrow : 0.0f;
-            lacc[qb] *= alpha;
+        for (int qb = 0; qb < QT; ++qb) {
+          const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
+          attend_block<KS, NCB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis,
+                                             quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
+        }
+      }
+      if (optimistic && ((t & 7) == 7 || t + 1 == t_end)) {
+        bool grown = false;
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] *= alpha;
+        for (int qb = 0; qb < QT; ++qb) grown |= !(lacc[qb][0] < __builtin_exp2f(kGrow));
+        if (__any(grown)) {
+          bool lost = false;
+#pragma unroll
+          for (int qb = 0; qb < QT; ++qb) lost |= !(lacc[qb][0] < __builtin_exp2f(kAbort));
+          if (__any(lost)) {                                       // wave-uniform
+            lost_walk = true;
+            break;
+          } else {
+#pragma unroll
+            for (int qb = 0; qb < QT; ++qb) {
+              const bool g_qb = !(lacc[qb][0] < __builtin_exp2f(kGrow));
+              const float alpha = g_qb ? __builtin_exp2f(-kGrow) : 1.0f;
+              m[qb] += g_qb ? kGrow : 0.0f;
+              lacc[qb] *= alpha;
+#pragma unroll
+              for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] *= alpha;
+            }
           }
         }
       }
+      // the next tile is requested into the registers the current one has just left; without the barrier the
+      // scheduler would start these loads early into a second set of registers and spill
+      __builtin_amdgcn_sched_barrier(0);
+      if (have_n) {
+        load_k(t + 1, max(page_n, 0));
+        load_v(t + 1, max(page_n, 0));
+      }
+      page = page_n;
     }
-    // the next tile is requested into the registers the current one has just left; without the barrier the
-    // scheduler would start these loads early into a second set of registers and spill
-    __builtin_amdgcn_sched_barrier(0);
-    if (have_n) {
-      load_k(t + 1, max(page_n, 0));
-      load_v(t + 1, max(page_n, 0));
+    if (!lost_walk) break;
+    optimistic = false;
+#pragma unroll
+    for (int qb = 0; qb < QT; ++qb) {
+      m[qb] = -INFINITY;
+      lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    page = page_n;
-  }
-  if (!lost_walk) break;
-  optimistic = false;
-#pragma unroll
-  for (int qb = 0; qb < QT; ++qb) {
-    m[qb] = -INFINITY;
-    lacc[qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
   }
   write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
 }
