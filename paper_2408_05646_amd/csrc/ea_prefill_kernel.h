@@ -376,13 +376,17 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
 
 template <int KS, int NCB, bool ALIBI>
 static void launch_prefill(const PrefillArgs& a_in, int32_t B, hipStream_t st) {
-  // 64 queries per wave while the accumulators fit the register file, 32 for the large ranks
+  // 64 queries per wave while the accumulators fit the register file, 32 for the larger ranks.  For the largest
+  // (the K and V fragments of a tile alone take 112..128 registers) two waves per SIMD leave 256 registers each and
+  // the tile loop spills, which costs far more than the second wave brings: those run one wave per SIMD.
+  constexpr bool kBig = 2 * KS + NCB >= 14;
   constexpr int QT = (KS <= 2 && NCB <= 4) ? 4 : 2;
+  constexpr int WPE = kBig ? 1 : 2;
   PrefillArgs a = a_in;
   a.batch = B;
   a.n_qtiles = (a.n_q + 64 * QT - 1) / (64 * QT);
   const dim3 grid((uint32_t)(a.n_qtiles * a.g.n_heads * B));
-  prefill_bf16_direct_kernel<KS, NCB, QT, 2, ALIBI><<<grid, 256, 0, st>>>(a);
+  prefill_bf16_direct_kernel<KS, NCB, QT, WPE, ALIBI><<<grid, 256, 0, st>>>(a);
 }
 
 template <int KS, bool ALIBI>
@@ -405,7 +409,7 @@ template <bool ALIBI>
 static int prefill_bf16_launch(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool,
                                const void* v_pool, const int32_t* page_table, const int32_t* seq_len, void* out,
                                int32_t B, int32_t n, hipStream_t st, int32_t k_compact, const float* alibi) {
-  if ((int64_t)((n + 127) / 128) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
+  if ((int64_t)((n + 63) / 64) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
   PrefillArgs a;
   a.q = (const uint16_t*)q;
   a.k_pool = (const uint16_t*)k_pool;
