@@ -40,17 +40,17 @@ struct PrefillArgs {
 // unmasked tiles run the lean path.  `vis` = number of kv positions this lane's query may see.
 // ALIBI: every score gets slope * (key position - query position) (log2 units) before the softmax; `dist0` is
 // the distance of this lane's query to the tile's first token of this register quad (tok0 + 4*quad - pos).
-template <int KS, int NCB, bool MASKED, bool ALIBI>
-__device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf16x8 (&vf)[2][NCB],
+template <int KS, int NCB, int TB, bool MASKED, bool ALIBI>
+__device__ __forceinline__ void attend_block(const bf16x8 (&kf)[TB][KS], const bf16x8 (&vf)[TB / 2][NCB],
                                              const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
                                              f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad,
                                              float slope, int dist0) {
   // The query arrives already multiplied by log2(e)/sqrt(d_head), and the score accumulators start at minus the
   // reference exponent: what the matrix cores return is the argument of exp2, no vector instruction in between.
   const float m_base = m == -INFINITY ? 0.f : m;
-  f32x4 s[4];
+  f32x4 s[TB];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb) {
+  for (int tb = 0; tb < TB; ++tb) {
     s[tb] = f32x4{-m_base, -m_base, -m_base, -m_base};
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
@@ -58,13 +58,13 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
   if (ALIBI) {
     const float base = slope * (float)dist0;
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
+    for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(slope, (float)(tb * 16 + i), base);
   }
   float mx = -INFINITY;
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
+  for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
@@ -83,62 +83,60 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[4][KS], const bf
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[cb] *= alpha;
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb) s[tb] -= delta;
+    for (int tb = 0; tb < TB; ++tb) s[tb] -= delta;
     m = m_new;
   }
-  bf16x8 pf[2];
+  bf16x8 pf[TB / 2];
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
-  lacc = mfma16(ones, pf[0], lacc);
-  lacc = mfma16(ones, pf[1], lacc);
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
-    acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
-  }
+  for (int u = 0; u < TB / 2; ++u) lacc = mfma16(ones, pf[u], lacc);
+#pragma unroll
+  for (int u = 0; u < TB / 2; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
 }
 
 // The same tile against the same block when nothing is masked and the reference exponent m is already finite,
 // without looking for the tile's maximum: the exponentials are taken against the reference as it stands and the
 // caller inspects the row sums afterwards (see the tile loop).  Per score that leaves the exponential and half a
 // conversion for the vector unit.
-template <int KS, int NCB>
-__device__ __forceinline__ void attend_block_optimistic(const bf16x8 (&kf)[4][KS], const bf16x8 (&vf)[2][NCB],
+template <int KS, int NCB, int TB>
+__device__ __forceinline__ void attend_block_optimistic(const bf16x8 (&kf)[TB][KS], const bf16x8 (&vf)[TB / 2][NCB],
                                                         const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
                                                         f32x4& lacc, float m) {
   const f32x4 neg_m{-m, -m, -m, -m};
-  f32x4 s[4];
+  f32x4 s[TB];
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb) {
+  for (int tb = 0; tb < TB; ++tb) {
     s[tb] = mfma16(kf[tb][0], q[0], neg_m);
 #pragma unroll
     for (int ks = 1; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
-  bf16x8 pf[2];
+  bf16x8 pf[TB / 2];
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
-  lacc = mfma16(ones, pf[0], lacc);
-  lacc = mfma16(ones, pf[1], lacc);
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) {
-    acc[cb] = mfma16(vf[0][cb], pf[0], acc[cb]);
-    acc[cb] = mfma16(vf[1][cb], pf[1], acc[cb]);
-  }
+  for (int u = 0; u < TB / 2; ++u) lacc = mfma16(ones, pf[u], lacc);
+#pragma unroll
+  for (int u = 0; u < TB / 2; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[cb] = mfma16(vf[u][cb], pf[u], acc[cb]);
 }
 
 // Clears value slots of tokens >= limit (never written, arbitrary bits) so that 0 * x stays 0.
-template <int NCB>
-__device__ __forceinline__ void clear_tail(bf16x8 (&vf)[2][NCB], int tok0, int limit, int quad) {
+template <int NCB, int TB>
+__device__ __forceinline__ void clear_tail(bf16x8 (&vf)[TB / 2][NCB], int tok0, int limit, int quad) {
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
@@ -179,8 +177,13 @@ __device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&ac
 // Every wave reads its K / V fragments straight from global memory (the four waves of a workgroup walk
 // the same tiles, so three of four reads hit in L1/L2); the next tile is requested into the registers the
 // current one has just left.  (Staging the tiles through LDS was measured and is slower here.)
-template <int KS, int NCB, int QT, int WPE, bool ALIBI>
+// TB = 16-token blocks per step of the walk: 4 (a whole 64-token cache tile per step) or 2 (half a tile: half the
+// fragment registers, for the ranks whose whole tile does not fit beside the accumulators).
+template <int KS, int NCB, int QT, int WPE, bool ALIBI, int TB>
 __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillArgs a) {
+  static_assert(TB == 4 || TB == 2, "a step is a whole or half a cache tile");
+  constexpr int kStep = 16 * TB;                                // tokens per step
+  constexpr int kSpt = 4 / TB;                                  // steps per cache tile
   const Geo& g = a.g;
   // 1-D grid ordered by work: the latest (longest) query tiles of every (sequence, head) come first
   const int hb = g.n_heads * a.batch;
@@ -250,39 +253,41 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
   const int q_last = min(a.n_q, q0 + QW) - 1;
   const int pos_last = pos0 + q_last;                            // last position any query of this wave sees
   const int pos_first = pos0 + q0;                               // every query of this wave sees positions <= this
-  const int t_end = pos_last >= 0 ? min(pos_last, len - 1) / kTile + 1 : 0;
+  const int t_end = pos_last >= 0 ? min(pos_last, len - 1) / kStep + 1 : 0;     // in steps
 
-  bf16x8 kf[4][KS], vf[2][NCB];
-  auto tile_page = [&](int t) -> int {
-    const int page = pt_row[t / tiles_per_page];
+  bf16x8 kf[TB][KS], vf[TB / 2][NCB];
+  // step st covers blocks (st % kSpt) * TB .. + TB - 1 of cache tile st / kSpt
+  auto tile_page = [&](int st) -> int {
+    const int page = pt_row[(st / kSpt) / tiles_per_page];
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
-  auto load_k = [&](int t, int page) __attribute__((always_inline)) {
+  auto load_k = [&](int st, int page) __attribute__((always_inline)) {
+    const int t = st / kSpt, tb0 = (st % kSpt) * TB;
     const int64_t kpage = a.k_compact ? (int64_t)b * g.max_pages + t / tiles_per_page : page;
     const uint16_t* base = a.k_pool + kpage * g.k_page + (int64_t)kvh * g.k_slab +
                            (int64_t)(t % tiles_per_page) * (kTile * g.r_k_pad);
 #pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
+    for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         // only the last k-step can run past the rank's nck chunks; its surplus lanes read the last real chunk
         // instead and drop what they read
         const bool past = ks == KS - 1 && ks * 4 + quad >= nck;
         const int chunk = past ? nck - 1 : ks * 4 + quad;
-        const bf16x8 got = *reinterpret_cast<const bf16x8*>(base + (((tb * nck + chunk) * 16 + col) << 3));
+        const bf16x8 got = *reinterpret_cast<const bf16x8*>(base + ((((tb0 + tb) * nck + chunk) * 16 + col) << 3));
         kf[tb][ks] = past ? zero_frag() : got;
       }
   };
-  auto load_v = [&](int t, int page) __attribute__((always_inline)) {
+  auto load_v = [&](int st, int page) __attribute__((always_inline)) {
+    const int t = st / kSpt, u0 = (st % kSpt) * (TB / 2);
     const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
                            (int64_t)(t % tiles_per_page) * (kTile * g.r_v_pad);
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb)
-        vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + (((u * NCB + cb) * 64 + lane) << 3));
+        vf[u][cb] = *reinterpret_cast<const bf16x8*>(base + ((((u0 + u) * NCB + cb) * 64 + lane) << 3));
   };
-
 
   // Unmasked tiles after the first run optimistically: no search for the tile's maximum, the exponentials are
   // taken against the reference exponent the earlier tiles left (exact in floating point whatever the reference,
@@ -305,26 +310,26 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
       load_v(0, max(page, 0));
     }
     for (int t = 0; t < t_end; ++t) {
-      const int tok0 = t * kTile;
-      const bool full = page >= 0 && tok0 + kTile - 1 <= pos_first && tok0 + kTile <= len;   // no masking needed
+      const int tok0 = t * kStep;
+      const bool full = page >= 0 && tok0 + kStep - 1 <= pos_first && tok0 + kStep <= len;   // no masking needed
       const int limit = page >= 0 ? len : 0;                       // tokens >= limit do not exist
       const bool have_n = t + 1 < t_end;
       const int page_n = have_n ? tile_page(t + 1) : -1;
       if (full && optimistic && t > 0) {
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb)
-          attend_block_optimistic<KS, NCB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
+          attend_block_optimistic<KS, NCB, TB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
       } else if (full) {
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb)
-          attend_block<KS, NCB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0,
+          attend_block<KS, NCB, TB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0,
                                               quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
       } else {
-        if (tok0 + kTile > limit) clear_tail<NCB>(vf, tok0, limit, quad);
+        if (tok0 + kStep > limit) clear_tail<NCB, TB>(vf, tok0, limit, quad);
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb) {
           const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
-          attend_block<KS, NCB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis,
+          attend_block<KS, NCB, TB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis,
                                              quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
         }
       }
@@ -376,17 +381,21 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
 
 template <int KS, int NCB, bool ALIBI>
 static void launch_prefill(const PrefillArgs& a_in, int32_t B, hipStream_t st) {
-  // 64 queries per wave while the accumulators fit the register file, 32 for the larger ranks.  For the largest
-  // (the K and V fragments of a tile alone take 112..128 registers) two waves per SIMD leave 256 registers each and
-  // the tile loop spills, which costs far more than the second wave brings: those run one wave per SIMD.
-  constexpr bool kBig = 2 * KS + NCB >= 14;
-  constexpr int QT = (KS <= 2 && NCB <= 4) ? 4 : 2;
-  constexpr int WPE = kBig ? 1 : 2;
+  // Queries per wave (QT blocks of 16) and tokens per step (TB blocks of 16) from a register estimate: QT
+  // accumulator sets (output, row sum, query fragments), the K and V fragments of one step, scores and P, and about
+  // 40 for addresses and the rest.  More queries per wave reuse each fragment more often; whole-tile steps have fewer,
+  // longer MFMA runs.  A tile loop that spills costs far more than either, so the first shape that fits is taken.
+  constexpr auto fits = [](int qt, int tb) {
+    return qt * (4 * NCB + 4 + 4 * KS) + 4 * tb * KS + 2 * tb * NCB + 6 * tb + 40 <= 244;
+  };
+  constexpr int QT = (fits(4, 4) || fits(4, 2)) ? 4 : 2;
+  constexpr int TB = fits(QT, 4) ? 4 : 2;
+  constexpr int WPE = 2;
   PrefillArgs a = a_in;
   a.batch = B;
   a.n_qtiles = (a.n_q + 64 * QT - 1) / (64 * QT);
   const dim3 grid((uint32_t)(a.n_qtiles * a.g.n_heads * B));
-  prefill_bf16_direct_kernel<KS, NCB, QT, WPE, ALIBI><<<grid, 256, 0, st>>>(a);
+  prefill_bf16_direct_kernel<KS, NCB, QT, WPE, ALIBI, TB><<<grid, 256, 0, st>>>(a);
 }
 
 template <int KS, bool ALIBI>
