@@ -4,7 +4,8 @@
 //
 // One workgroup = 4 waves = 4 * QT * 16 consecutive queries of one (sequence, head).
 // A wave keeps QT blocks of 16 queries as MFMA columns and walks the 64-token cache
-// tiles up to its diagonal:
+// tiles up to its diagonal, a whole tile per step or (for the ranks whose whole-tile
+// fragments do not fit beside the accumulators) half a tile:
 //   S[64 kv x 16 q]   = K_tile . Q^T              (A = K fragments, B = q rows)
 //   online softmax per query column (rows = kv tokens: 16 registers + two cross-quad shuffles)
 //   O^T[r_v x 16 q]  += V_tile^T . P^T            (P rounded to bf16; row sums by an all-ones MFMA)
