@@ -663,14 +663,17 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
     }
 #undef EA_SKINNY
   } else {
-    const int bm = M >= 2048 ? 256 : 128;      // taller tiles re-read the weights half as often
+    // taller tiles re-read the weights half as often, but only pay once there are enough of them for the chip:
+    // below about 3/4 of the compute units' worth of 256x256 tiles the 128-row kernel's finer grid is faster
+    const int64_t tiles256 = (int64_t)((N + 255) / 256) * ((M + 255) / 256);
+    const int bm = (M >= 2048 && tiles256 >= 192) ? 256 : 128;
     const int64_t tiles = (int64_t)((N + 127) / 128) * ((M + bm - 1) / bm);
     if (tiles > INT32_MAX) return EA_ERR_SHAPE;
     dim3 grid((uint32_t)tiles), block(256);
     if constexpr (!A_F32) {
       if (bm == 256 && N > 128) {
         // bf16 activations, many rows (and more than one 128-wide column tile): the asynchronous 256x256 kernel (128 KiB of dynamic LDS, one workgroup per CU)
-        const int64_t t2 = (int64_t)((N + 255) / 256) * ((M + 255) / 256);
+        const int64_t t2 = tiles256;
         if (t2 > INT32_MAX) return EA_ERR_SHAPE;
         static bool attr_set = false;      // (a benign race: the attribute is idempotent)
         if (!attr_set) {
