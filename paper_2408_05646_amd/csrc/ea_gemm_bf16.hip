@@ -164,6 +164,8 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const void* __r
         af = af_next;
       }
 #pragma unroll
+      for (int j = MI; j < 4; ++j) w1[j] = read_w(1, j);     // (tiles lower than 128 rows: the loop above took MI of them)
+#pragma unroll
       for (int i = 0; i < MI; ++i) {
         bf16x8 af_next = af;
         if (i + 1 < MI) af_next = read_a(1, i + 1);
@@ -686,8 +688,19 @@ static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int3
         return launch_status();
       }
     }
-    if (bm == 256) gemm_bf16_tiled_kernel<Epilogue, A_F32, 8><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
-    else gemm_bf16_tiled_kernel<Epilogue, A_F32, 4><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
+    if (bm == 256) {
+      gemm_bf16_tiled_kernel<Epilogue, A_F32, 8><<<grid, block, 0, st>>>(A, w, M, N, K, ep);
+    } else {
+      // a few hundred rows: 128-row tiles would leave most compute units idle (32 tiles at M = 128, N = 4096), so
+      // the tile height is halved until there are about as many tiles as compute units
+      const int64_t tiles_n = (N + 127) / 128;
+      int rows = 128;
+      while (rows > 32 && tiles_n * ((M + rows - 1) / rows) < 200) rows >>= 1;
+      const dim3 g2((uint32_t)(tiles_n * ((M + rows - 1) / rows)));
+      if (rows == 128) gemm_bf16_tiled_kernel<Epilogue, A_F32, 4><<<g2, block, 0, st>>>(A, w, M, N, K, ep);
+      else if (rows == 64) gemm_bf16_tiled_kernel<Epilogue, A_F32, 2><<<g2, block, 0, st>>>(A, w, M, N, K, ep);
+      else gemm_bf16_tiled_kernel<Epilogue, A_F32, 1><<<g2, block, 0, st>>>(A, w, M, N, K, ep);
+    }
   }
   return launch_status();
 }
