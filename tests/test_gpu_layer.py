@@ -69,6 +69,7 @@ def assert_one_bf16_rounding(got: np.ndarray, ref: np.ndarray):
     (ea.EA_BF16, 256, 32, 2, 30, 33, 2, 40, 64, [0, 50]),                       # same through the tiled GEMM
     (ea.EA_BF16, 256, 4, 2, 80, 48, 1, 2100, 64, [37]),                         # 2100 rows: the tall (256-row) tiles, ragged
     (ea.EA_BF16, 96, 4, 4, 32, 32, 2, 1100, 64, [0, 5]),                        # ... with three k steps only
+    (ea.EA_BF16, 2048, 32, 32, 64, 64, 2, 130, 64, [0, 70]),                    # 260 rows x 6144 columns: 64-row tiles
 ])
 def test_project_qkv(dtype, d, H, Hkv, r_k, r_v, B, T, P, lens):
     print(f"project dtype={dtype} d={d} H={H}/{Hkv} r=({r_k},{r_v}) B={B} T={T} lens={lens}", flush=True)
@@ -118,6 +119,7 @@ def test_project_qkv(dtype, d, H, Hkv, r_k, r_v, B, T, P, lens):
     (ea.EA_BF16, 4096, 32, 80, 16),
     (ea.EA_BF16, 256, 4, 40, 2100), (ea.EA_BF16, 200, 2, 16, 2048), (ea.EA_BF16, 640, 4, 16, 2305),   # tall tiles; 5, 1, 2 k steps
     (ea.EA_BF16, 128, 4, 16, 2100),                                # tall tiles, a single 128-wide column tile
+    (ea.EA_BF16, 4096, 32, 16, 512), (ea.EA_BF16, 4096, 32, 16, 130),   # 64-row and 32-row tiles over 32 column tiles
 ])
 def test_out_proj(dtype, d, H, r_v, M):
     print(f"out_proj dtype={dtype} d={d} H={H} r_v={r_v} M={M}", flush=True)
