@@ -42,7 +42,8 @@ enum {
   EA_ERR_SHAPE = -2,       /* shape the kernels do not support (see each call)   */
   EA_ERR_ALIGN = -3,       /* pointer not 16-byte aligned                         */
   EA_ERR_WORKSPACE = -4,   /* workspace missing or too small                      */
-  EA_ERR_DEVICE = -5       /* the HIP runtime reported a launch error             */
+  EA_ERR_DEVICE = -5,      /* the HIP runtime reported a launch error             */
+  EA_ERR_SCRATCH_LIMIT = -6 /* the call needs more than the library's built-in scratch buffer holds */
 };
 
 enum { EA_F32 = 0, EA_BF16 = 1 };
@@ -177,6 +178,24 @@ EA_API int ea_decode_attn(const ea_layer_desc* desc, const void* dev_q_r, const 
                    const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
                    int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
                    void* dev_ws, int64_t ws_bytes, void* stream);
+
+/* ea_decode_attn for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, serving loops with a fixed memory plan, harnesses that forbid hipMalloc.  Same arguments and result
+ * as ea_decode_attn (same kernels, same n_splits rule) without dev_ws / ws_bytes: the split partials go to a
+ * buffer of EA_STATIC_SCRATCH_BYTES that is part of the library's image (every GPU the library is used on holds
+ * its own copy until the process ends).  The call allocates and frees nothing.
+ *   - A call whose partials need more (ea_decode_workspace_bytes(desc, B, n_splits) > EA_STATIC_SCRATCH_BYTES)
+ *     is rejected with EA_ERR_SCRATCH_LIMIT before anything is launched; pass a smaller n_splits or use
+ *     ea_decode_attn.
+ *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents; nothing in it has
+ *     to be cleared (the attention kernel writes every partial the merge reads).  Calls that overlap in time on
+ *     one GPU (different streams) race on it: serialise them, or use ea_decode_attn with a workspace each.
+ *   - The first call on a device looks the buffer's address up (no allocation); make that call before starting
+ *     a graph capture. */
+#define EA_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+EA_API int ea_decode_attn_static(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_k_pool,
+                   const void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
+                   int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* stream);
 
 /* Generation-phase attention for models with rotary position embedding
  * (Sec. 4.3, Eq. 9-10): the query keeps all d_head channels, the cache holds the

@@ -20,6 +20,7 @@ __all__ = [
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
+    "decode_attn_static", "STATIC_SCRATCH_BYTES",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -32,7 +33,10 @@ EXPORTED_SYMBOLS = (
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
+    "ea_decode_attn_static",
 )
+
+STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
 
 
 class EigenAttnError(RuntimeError):
@@ -105,6 +109,7 @@ def load_library():
     lib.ea_decode_rope_auto_splits.restype = I32
     lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_decode_attn_static.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_prefill_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
@@ -319,6 +324,23 @@ def decode_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, n_splits: i
                                        _ptr(seq_len), _ptr(out), B, page_table.shape[1], k_pool.shape[0], n_splits,
                                        _ptr(ws), ws_bytes, _stream(stream))
     _check(rc, "ea_decode_attn")
+
+
+def decode_attn_static(desc, q_r, k_pool, v_pool, page_table, seq_len, out, n_splits: int = 0, stream=None) -> None:
+    """decode_attn without a workspace argument: the split partials go to the library's built-in buffer
+    (STATIC_SCRATCH_BYTES); nothing is allocated."""
+    import torch
+    B = seq_len.shape[0]
+    if q_r.dtype != torch.float32 or out.dtype != torch.float32:
+        raise ValueError("q_r and out must be float32")
+    if q_r.numel() != B * desc.n_heads * desc.r_k or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    rc = load_library().ea_decode_attn_static(ctypes.byref(desc), _ptr(q_r), _ptr(k_pool), _ptr(v_pool),
+                                              _ptr(page_table), _ptr(seq_len), _ptr(out), B, page_table.shape[1],
+                                              k_pool.shape[0], n_splits, _stream(stream))
+    _check(rc, "ea_decode_attn_static")
 
 
 def decode_attn_rope(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table, seq_len, out, n_splits: int = 0,

@@ -15,6 +15,7 @@ const char* ea_strerror(int code) {
     case EA_ERR_ALIGN: return "pointer is not 16-byte aligned";
     case EA_ERR_WORKSPACE: return "workspace missing or too small";
     case EA_ERR_DEVICE: return "HIP launch error";
+    case EA_ERR_SCRATCH_LIMIT: return "the call needs more than the library's built-in scratch buffer holds";
     default: return "unknown error code";
   }
 }

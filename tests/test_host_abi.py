@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 38
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 39
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -186,6 +186,25 @@ def test_decode_attn_rejects_bad_arguments_before_launching():
     assert call_decode(lib, desc(P=96)) == -2                             # bf16 pages hold whole 64-token tiles
     bad = desc(); bad.dtype = 7
     assert call_decode(lib, bad) == -1
+
+
+def test_static_decode_entry_point_rejects_bad_arguments_and_oversized_calls_before_launching():
+    lib, d = raw(), desc()
+
+    def call(dd=d, q=OK_PTR, k=OK_PTR, B=2, n_splits=1):
+        return lib.ea_decode_attn_static(ctypes.byref(dd), q, k, OK_PTR, OK_PTR, OK_PTR, OK_PTR, B, 4, 8, n_splits, None)
+
+    assert call(q=None) == -1 and call(B=0) == -1 and call(n_splits=1025) == -1
+    assert call(k=ODD_PTR) == -3
+    assert call(desc(r_k=136)) == -2
+    # the partials of a call must fit the library's built-in buffer: checked on the host, nothing is launched
+    big = ea.LayerDesc(4096, 32, 32, 128, 128, 128, ea.EA_BF16, 64)
+    assert ea.decode_workspace_bytes(big, 16, 31) <= ea.STATIC_SCRATCH_BYTES < ea.decode_workspace_bytes(big, 16, 32)
+    assert call(big, B=16, n_splits=32) == -6                             # EA_ERR_SCRATCH_LIMIT
+    assert "scratch" in ea.strerror(-6)
+    header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
+    assert re.search(r"#define\s+EA_STATIC_SCRATCH_BYTES\s+\(8 \* 1024 \* 1024\)", header)
+    assert ea.STATIC_SCRATCH_BYTES == 8 * 1024 * 1024
 
 
 def test_rotary_entry_points_reject_bad_arguments_before_launching():
