@@ -19,7 +19,9 @@
  *  - Host-side argument, shape and alignment checks happen before any launch.
  *    Errors that only the device can see (a page id outside the pool, a position
  *    beyond the page table) never fault: the affected tokens are skipped on
- *    write and masked out on read.
+ *    write and masked out on read.  A skipped write is a lost token: the
+ *    projection calls count them in a device status word the caller may pass
+ *    (dev_status), which the host can read after its next synchronisation.
  *  - dtype EA_F32: x, weights, q_r, o, y and the cache are float.  dtype
  *    EA_BF16: x, weights, y and the cache are bfloat16 with fp32 accumulation;
  *    q_r and o are float or bfloat16 as the q_dtype / o_dtype arguments say.
@@ -141,11 +143,17 @@ EA_API int ea_pack_weight(const void* dev_w_t, void* dev_packed, int32_t N, int3
  *   dev_seq_len[B]: length of each sequence BEFORE this call; token t is
  *              appended at position seq_len[b] + t.  Not modified.
  *   dev_page_table [B, max_pages] int32 physical page ids (< pool_pages).
+ *   dev_status NULL, or one int32 in device memory (4-byte aligned) to which the call ADDS the number of
+ *              (sequence, token) appends it could not store -- position seq_len[b] + t at or beyond
+ *              max_pages * page_tokens (the cache of that sequence is full), or a page id outside
+ *              [0, pool_pages).  Such a token's k and v are not written anywhere (its q_r row still is), and
+ *              later attention calls see the sequence without it.  The word is never cleared by the library:
+ *              zero it once, read it after any synchronisation, nonzero = tokens were lost since.
  * Requires d % 32 == 0 for EA_BF16 (d % 4 == 0 for EA_F32). */
 EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
                    void* dev_q_r, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
                    const int32_t* dev_page_table, const int32_t* dev_seq_len,
-                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream);
 
 /* The same fused projection for models with rotary position embedding
  * (Sec. 4.3): the query keeps all d_head channels (W^Q is not folded, the
@@ -157,7 +165,7 @@ EA_API int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const vo
 EA_API int ea_project_qkv_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
                    void* dev_q, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
                    const int32_t* dev_page_table, const int32_t* dev_seq_len,
-                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream);
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream);
 
 /* Number of splits of the cached sequence ea_decode_attn would pick for
  * n_splits = 0, and the workspace it needs for a given split count. */

@@ -100,8 +100,8 @@ def load_library():
     lib.ea_packed_weight_elems.restype = I64
     lib.ea_packed_weight_elems.argtypes = [I32, I32, I32]
     lib.ea_pack_weight.argtypes = [VP, VP, I32, I32, I32, VP]
-    lib.ea_project_qkv.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
-    lib.ea_project_qkv_rope.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP]
+    lib.ea_project_qkv.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP, VP]
+    lib.ea_project_qkv_rope.argtypes = [D, VP, VP, VP, I32, VP, VP, VP, VP, I32, I32, I32, I32, VP, VP]
     lib.ea_decode_auto_splits.restype = I32
     lib.ea_decode_auto_splits.argtypes = [D, I32, I32]
     lib.ea_decode_workspace_bytes.restype = I64
@@ -268,7 +268,7 @@ def pack_weight(w_t, stream=None):
     return packed
 
 
-def _project_qkv(fn_name, q_dim, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream):
+def _project_qkv(fn_name, q_dim, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream, status):
     B = seq_len.shape[0]
     if x.shape[0] != B * T:
         raise ValueError("x must have B*T rows")
@@ -280,21 +280,26 @@ def _project_qkv(fn_name, q_dim, desc, x, wqkv, q, k_pool, v_pool, page_table, s
         raise ValueError("packed weight / activation size does not match the layer")
     if q.numel() != B * T * desc.n_heads * q_dim:
         raise ValueError("q has the wrong size")
+    if status is not None:
+        _i32(status, "status")
     rc = getattr(load_library(), fn_name)(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(q), _dt(q), _ptr(k_pool),
                                           _ptr(v_pool), _ptr(page_table), _ptr(seq_len), B, T, page_table.shape[1],
-                                          k_pool.shape[0], _stream(stream))
+                                          k_pool.shape[0], _ptr(status), _stream(stream))
     _check(rc, fn_name)
 
 
-def project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+def project_qkv(desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T: int, stream=None, status=None) -> None:
     """x [B*T, d]; wqkv = pack_weight([N_qkv, d]); q_r [B*T, H, r_k] (float32 or bfloat16) is written,
-    k and v go to the pools."""
-    _project_qkv("ea_project_qkv", desc.r_k, desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T, stream)
+    k and v go to the pools.  status: an int32 device tensor of one element to which the number of appends that
+    could not be stored (cache full, bad page id) is added, or None."""
+    _project_qkv("ea_project_qkv", desc.r_k, desc, x, wqkv, q_r, k_pool, v_pool, page_table, seq_len, T, stream,
+                 status)
 
 
-def project_qkv_rope(desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T: int, stream=None) -> None:
+def project_qkv_rope(desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T: int, stream=None, status=None) -> None:
     """Rotary variant: wqkv = pack_weight([H*d_head + H_kv*(r_k + r_v), d]); q [B*T, H, d_head] is written."""
-    _project_qkv("ea_project_qkv_rope", desc.d_head, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream)
+    _project_qkv("ea_project_qkv_rope", desc.d_head, desc, x, wqkv, q, k_pool, v_pool, page_table, seq_len, T, stream,
+                 status)
 
 
 def decode_auto_splits(desc, B: int, max_seq_len: int) -> int:

@@ -108,7 +108,7 @@ int ea_pack_weight(const void* dev_w_t, void* dev_packed, int32_t N, int32_t K, 
 static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void* dev_x, const void* dev_wqkv_t,
                             void* dev_q, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
                             const int32_t* dev_page_table, const int32_t* dev_seq_len, int32_t B, int32_t T,
-                            int32_t max_pages, int32_t pool_pages, void* stream) {
+                            int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream) {
   if (!dev_x || !dev_wqkv_t || !dev_q || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len)
     return EA_ERR_ARG;
   if (B <= 0 || T <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
@@ -118,6 +118,7 @@ static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void
   if (!aligned16(dev_x) || !aligned16(dev_wqkv_t) || !aligned16(dev_q) || !aligned16(dev_k_pool) ||
       !aligned16(dev_v_pool))
     return EA_ERR_ALIGN;
+  if (dev_status && (reinterpret_cast<uintptr_t>(dev_status) & 3u)) return EA_ERR_ALIGN;
   if (desc->d_model % (desc->dtype == EA_BF16 ? 32 : 4) != 0) return EA_ERR_SHAPE;
   clear_stale_error();
   QkvDest dst;
@@ -128,6 +129,7 @@ static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void
   dst.page_table = dev_page_table;
   dst.seq_len = dev_seq_len;
   dst.T = T;
+  dst.status = dev_status;
   dst.g = make_geo(desc, max_pages, pool_pages);
   dst.g.q_dim = q_dim;
   const int32_t N = desc->n_heads * q_dim + desc->n_kv_heads * (desc->r_k + desc->r_v);
@@ -138,22 +140,22 @@ static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void
 
 int ea_project_qkv(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t, void* dev_q_r, int32_t q_dtype,
                    void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
-                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, void* stream) {
+                   int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream) {
   int rc = validate_desc(desc);
   if (rc != EA_OK) return rc;
   return project_qkv_impl(desc, desc->r_k, dev_x, dev_wqkv_t, dev_q_r, q_dtype, dev_k_pool, dev_v_pool, dev_page_table,
-                          dev_seq_len, B, T, max_pages, pool_pages, stream);
+                          dev_seq_len, B, T, max_pages, pool_pages, dev_status, stream);
 }
 
 int ea_project_qkv_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv_t, void* dev_q,
                         int32_t q_dtype, void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
                         const int32_t* dev_seq_len, int32_t B, int32_t T, int32_t max_pages, int32_t pool_pages,
-                        void* stream) {
+                        int32_t* dev_status, void* stream) {
   int rc = validate_desc(desc);
   if (rc != EA_OK) return rc;
   if (desc->r_k > desc->d_head) return EA_ERR_SHAPE;
   return project_qkv_impl(desc, desc->d_head, dev_x, dev_wqkv_t, dev_q, q_dtype, dev_k_pool, dev_v_pool,
-                          dev_page_table, dev_seq_len, B, T, max_pages, pool_pages, stream);
+                          dev_page_table, dev_seq_len, B, T, max_pages, pool_pages, dev_status, stream);
 }
 
 int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len) {

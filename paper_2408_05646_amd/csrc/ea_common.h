@@ -194,6 +194,7 @@ struct QkvDest {
   const int32_t* seq_len;
   int32_t T;
   Geo g;
+  int32_t* status = nullptr;   // device word that counts the (sequence, token) appends that could not be stored, or null
 };
 int pack_weight(const void* w_t, void* packed, int32_t N, int32_t K, bool bf16, hipStream_t st);
 int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);

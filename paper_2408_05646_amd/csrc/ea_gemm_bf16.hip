@@ -355,29 +355,39 @@ __global__ __launch_bounds__(512, 1) void gemm_bf16_async_kernel(const uint16_t*
 }
 
 // ---------------------------------------------------------------------------
-// Skinny kernel: M <= 16*MT rows.  One workgroup owns NB blocks of 16 output channels; its eight
-// waves interleave the 32-wide K steps and each requests all the weight fragments of a round at once
-// (for K <= 4096 and M <= 16 that is the whole job: one memory round trip; nontemporal, the weights are
-// streamed exactly once); the partial sums meet in LDS.
+// Skinny kernel: M <= 16*MT rows (the generation phase).  One workgroup owns NB blocks of 16 output channels; its
+// eight waves interleave the 32-wide K steps and each requests all the weight fragments of a round at once (for
+// K <= 4096 and M <= 16 that is the whole job: one memory round trip; nontemporal, the weights are streamed exactly
+// once); the partial sums meet in LDS.  Every load goes through a buffer descriptor (the workgroup's channel blocks
+// of W; the M rows of A), so rows past M, channel blocks past N and k steps past K read as zero and no load sits
+// behind a branch: all of a wave's requests are out within a few dozen cycles of its start.  What the epilogue has
+// to look up per row (the cache slot of the appended token) is fetched by M threads AFTER the loads are issued.
 // A float A operand is split in hi + lo bf16 halves so it loses no precision.
 // ---------------------------------------------------------------------------
+constexpr int kSkinnyWaves = 8;
+
 template <typename Epilogue, bool A_F32, int MT, int NB>
 __global__ __launch_bounds__(512) void gemm_bf16_skinny_kernel(const void* __restrict__ A,
                                                                const uint16_t* __restrict__ Wt, int32_t M, int32_t N,
                                                                int32_t K, Epilogue ep) {
-  constexpr int WAVES = 8;
+  constexpr int WAVES = kSkinnyWaves;
   constexpr int UN = 16 / MT;                              // k steps per wave and round, all requested up front
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int kEsz = A_F32 ? 4 : 2;
+  constexpr uint32_t kOob = 0x7ffffff0u;                   // beyond any descriptor's size: reads as zero
+  constexpr int kNt = 2;                                   // cache policy of the weight loads: nontemporal
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 15, quad = lane >> 4;
   const int n0 = blockIdx.x * (16 * NB);
   const int steps = K / 32;
-  const uint16_t* wfrag[NB];                              // fragment (channel block, step 0) + this lane's unit
-  bool n_ok[NB];
-#pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
-    n_ok[nb] = n0 + nb * 16 < N;                          // packed rows beyond N exist and are zero
-    wfrag[nb] = Wt + ((((int64_t)(n_ok[nb] ? (n0 >> 4) + nb : 0) * steps) << 9) + (lane << 3));
-  }
+  const int nblks = (N + 15) >> 4;
+  // this workgroup's channel blocks: [NB][steps] fragments of 1 KiB, contiguous in the packed weights
+  const int my_blks = min(NB, nblks - (n0 >> 4));
+  const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(Wt) + (((int64_t)(n0 >> 4) * steps) << 9), 0, (int)((int64_t)my_blks * steps * 1024),
+      0x00020000);
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(reinterpret_cast<const char*>(A)), 0, (int)((int64_t)M * K * kEsz), 0x00020000);
 
   f32x4 acc[MT][NB];
 #pragma unroll
@@ -385,51 +395,52 @@ __global__ __launch_bounds__(512) void gemm_bf16_skinny_kernel(const void* __res
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // where this thread's outputs will go (its 4 rows of one column after the reduction): the dependent
-  // address loads of the epilogue overlap with the weight stream
-  typename Epilogue::Slot slot[4];
-  const bool writer = tid < MT * NB * 64;
-  {
-    const int ln = tid & 63, nb = (tid >> 6) % NB, i = (tid >> 6) / NB;
-    const int c = n0 + nb * 16 + (ln & 15);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = i * 16 + (ln >> 4) * 4 + e;
-      slot[e] = (writer && r < M && c < N) ? ep.locate(r, c) : typename Epilogue::Slot{};
-    }
-  }
+  __shared__ typename Epilogue::Row rows[64];
+  __shared__ f32x4 red[WAVES][MT][NB][64];
+  // The epilogue's per-row lookup is a chain of two dependent loads (sequence length, then page id).  Loads return in
+  // order, so the first is issued before the weight requests (waiting for it then waits for nothing younger) and the
+  // second right behind them; its value is needed only after the matrix products.
+  // (Every thread goes through the lookup, the ones past M for row 0: a branch around a load would make the
+  // compiler wait for it on the spot.)
+  typename Epilogue::RowLookup look = ep.lookup_begin(tid < M ? tid : 0);
+  bool looked = false;
 
   // the waves interleave the k steps (neighbouring waves stream neighbouring kilobytes of the weights)
   for (int s0 = wave; s0 < steps; s0 += WAVES * UN) {     // this wave: steps s0, s0 + WAVES, ...
     bf16x8 bw[UN][NB];
 #pragma unroll
-    for (int u = 0; u < UN; ++u)
+    for (int u = 0; u < UN; ++u) {
+      const int s = s0 + WAVES * u;
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        bw[u][nb] = (n_ok[nb] && s0 + WAVES * u < steps)
-                        ? __builtin_nontemporal_load(
-                              reinterpret_cast<const bf16x8*>(wfrag[nb] + ((int64_t)(s0 + WAVES * u) << 9)))
-                        : zero_frag();
+      for (int nb = 0; nb < NB; ++nb) {
+        const uint32_t off = s < steps ? (uint32_t)(((nb * steps + s) << 10) + (lane << 4)) : kOob;
+        bw[u][nb] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, kNt));
+      }
+    }
     // activations: a few rows, shared by every workgroup (L2 hits); float input is kept whole until it is split
     bf16x8 ab[A_F32 ? 1 : UN][MT];
     f32x4 af32[A_F32 ? UN : 1][MT][2];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const int64_t koff = (int64_t)(s0 + WAVES * u) * 32 + quad * 8;
-      const bool ok = s0 + WAVES * u < steps;
+      const int s = s0 + WAVES * u;
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
-        const int row = i * 16 + col;
+        const int row = i * 16 + col;                      // rows >= M lie beyond the descriptor
+        const uint32_t off = s < steps ? (uint32_t)((row * K + s * 32 + quad * 8) * kEsz) : kOob;
         if (!A_F32) {
-          ab[u][i] = (ok && row < M) ? load_frag<false>(A, (int64_t)row * K + koff) : zero_frag();
+          ab[u][i] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off, 0, 0));
         } else {
-          const f32x4 z = {0.f, 0.f, 0.f, 0.f};
-          const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(A) + (int64_t)row * K + koff);
-          af32[u][i][0] = (ok && row < M) ? p[0] : z;
-          af32[u][i][1] = (ok && row < M) ? p[1] : z;
+          af32[u][i][0] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off, 0, 0));
+          af32[u][i][1] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, off, 16, 0));
         }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);                     // every request of the round goes out before anything else
+    if (!looked) {                                         // (first round only)
+      ep.lookup_next(look);
+      looked = true;
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
 #pragma unroll
@@ -455,23 +466,129 @@ __global__ __launch_bounds__(512) void gemm_bf16_skinny_kernel(const void* __res
       }
     }
   }
-  __shared__ f32x4 red[WAVES][MT][NB][64];
+  if (!looked) ep.lookup_next(look);                     // (a wave without a k step: K < 256)
+  if (tid < M) rows[tid] = ep.lookup_end(look, blockIdx.x == 0);
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) red[wave][i][nb][lane] = acc[i][nb];
   __syncthreads();
   static_assert(MT * NB * 64 <= 64 * WAVES, "one output quad per thread");
-  if (writer) {
-    const int ln = tid & 63, nb = (tid >> 6) % NB, i = (tid >> 6) / NB;
-    f32x4 v = red[0][i][nb][ln];
+  if (tid < MT * NB * 64) {
+    const int nb = (tid >> 6) % NB, i = (tid >> 6) / NB;
+    f32x4 v = red[0][i][nb][lane];
 #pragma unroll
-    for (int w = 1; w < WAVES; ++w) v += red[w][i][nb][ln];
-    const int c = n0 + nb * 16 + (ln & 15);
+    for (int w = 1; w < WAVES; ++w) v += red[w][i][nb][lane];
+    const int c = n0 + nb * 16 + col;
+    if (c < N) {
+      const typename Epilogue::Col cl = ep.column(c);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int r = i * 16 + (ln >> 4) * 4 + e;
-      if (r < M && c < N) ep.commit(slot[e], r, c, v[e]);
+      for (int e = 0; e < 4; ++e) {
+        const int r = i * 16 + quad * 4 + e;
+        if (r < M) ep.put(cl, rows[r], r, v[e]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Skinny kernel, pipelined form: M <= 16 rows of bf16 activations, K <= 4096 -- the fused QKV projection of a
+// generation step.  One workgroup per compute unit walks the 16-channel blocks blk = blockIdx.x, + gridDim.x, ...:
+// the weights of the block after the current one are requested before the current block's matrix products, so a
+// compute unit always has one or two blocks (K * 32 bytes each) in flight, however many blocks there are per
+// workgroup; the activations (this wave's 16 k steps of all rows) are fetched once and stay in registers.  Results
+// are collected in LDS and stored after the last block: with no store between the loads, waiting for one block's
+// weights never has to wait for the next block's.
+// ---------------------------------------------------------------------------
+constexpr int kPipeMaxUnits = 16;       // channel blocks per workgroup (the launch grows the grid beyond one per CU if needed)
+
+template <typename Epilogue>
+__global__ __launch_bounds__(512) void gemm_bf16_skinny_pipe_kernel(const uint16_t* __restrict__ A,
+                                                                    const uint16_t* __restrict__ Wt, int32_t M,
+                                                                    int32_t N, int32_t K, Epilogue ep) {
+  constexpr int WAVES = kSkinnyWaves, UN = 16;
+  constexpr uint32_t kOob = 0x7ffffff0u;
+  constexpr int kNt = 2;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 15, quad = lane >> 4;
+  const int steps = K / 32;                                  // <= WAVES * UN
+  const int nblks = (N + 15) >> 4;
+  const int stride = gridDim.x;
+
+  __shared__ typename Epilogue::Row rows[16];
+  __shared__ f32x4 red[2][WAVES][64];
+  __shared__ f32x4 stage[kPipeMaxUnits][64];
+
+  typename Epilogue::RowLookup look = ep.lookup_begin(tid < M ? tid : 0);
+  // this lane's part of the weight / activation fragment of its wave's u-th k step, or beyond every descriptor
+  uint32_t w_off[UN], a_off[UN];
+#pragma unroll
+  for (int u = 0; u < UN; ++u) {
+    const int s = wave + WAVES * u;
+    w_off[u] = s < steps ? (uint32_t)((s << 10) + (lane << 4)) : kOob;
+    a_off[u] = s < steps ? (uint32_t)((col * K + s * 32 + quad * 8) * 2) : kOob;      // rows >= M: beyond the descriptor
+  }
+  auto load_w = [&](int blk, bf16x8 (&bw)[UN]) __attribute__((always_inline)) {
+    // a block past the last reads through an empty descriptor: zeros, no memory traffic, no branch around the loads
+    const bool real = blk < nblks;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(Wt) + (((int64_t)(real ? blk : 0) * steps) << 9), 0, real ? steps * 1024 : 0, 0x00020000);
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+      bw[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rsrc, w_off[u], 0, kNt));
+  };
+  bf16x8 w0[UN], w1[UN], af[UN];
+  int blk = blockIdx.x;
+  load_w(blk, w0);
+  {
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(A), 0, (int)((int64_t)M * K * 2), 0x00020000);
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+      af[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, a_off[u], 0, 0));
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  ep.lookup_next(look);
+  __builtin_amdgcn_sched_barrier(0);
+
+  int it = 0;
+  auto unit = [&](bf16x8 (&wc)[UN], bf16x8 (&wn)[UN]) __attribute__((always_inline)) {
+    load_w(blk + stride, wn);
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < UN; ++u) acc = mfma16(af[u], wc[u], acc);
+    red[it & 1][wave][lane] = acc;
+    __syncthreads();
+    if (wave == (it & 7)) {                                  // the waves take turns at summing up a block
+      f32x4 v = red[it & 1][0][lane];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) v += red[it & 1][w][lane];
+      stage[it][lane] = v;
+    }
+    ++it;
+    blk += stride;
+  };
+  while (true) {
+    unit(w0, w1);
+    if (blk >= nblks) break;
+    unit(w1, w0);
+    if (blk >= nblks) break;
+  }
+  if (tid < M) rows[tid] = ep.lookup_end(look, blockIdx.x == 0);
+  __syncthreads();
+  // stores: wave w writes the blocks it summed up (lane = column, 4 rows per lane)
+  for (int j = wave; j < it; j += WAVES) {
+    const f32x4 v = stage[j][lane];
+    const int c = (blockIdx.x + j * stride) * 16 + col;
+    if (c < N) {
+      const typename Epilogue::Col cl = ep.column(c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = quad * 4 + e;
+        if (r < M) ep.put(cl, rows[r], r, v[e]);
+      }
     }
   }
 }
@@ -500,9 +617,47 @@ __device__ __forceinline__ void acc_coord(bool swap, int r0, int c0, int i, int 
 struct QkvEpBf16 {
   QkvDest d;
   int32_t fast_cols;
-  typedef QkvSlot Slot;
-  __device__ __forceinline__ Slot locate(int r, int c) const { return qkv_locate<true>(d, r, c); }
-  __device__ __forceinline__ void commit(const Slot& s, int r, int c, float v) const { qkv_commit<true>(d, s, r, c, v); }
+  // generation-phase kernel: a row's cache slot is looked up once (and a dropped append reported once), a
+  // column's section once, then elements are stored
+  typedef QkvRow Row;
+  typedef QkvCol Col;
+  struct RowLookup {
+    int32_t b, t, len, page, tp;
+    bool ok;
+  };
+  __device__ __forceinline__ RowLookup lookup_begin(int r) const {
+    RowLookup l;
+    l.b = r / d.T;
+    l.t = r % d.T;
+    l.len = d.seq_len[l.b];
+    l.page = -1;
+    l.tp = 0;
+    l.ok = false;
+    return l;
+  }
+  __device__ __forceinline__ void lookup_next(RowLookup& l) const {
+    int32_t len = l.len;
+    asm volatile("" : "+v"(len));            // the loaded length is first looked at HERE (not where it was requested)
+    const int64_t p64 = (int64_t)len + l.t;
+    l.ok = p64 >= 0 && p64 <= (int64_t)INT32_MAX;
+    const uint32_t pos = l.ok ? (uint32_t)p64 : 0u, P = (uint32_t)d.g.page_tokens;
+    const uint32_t lp = pos / P;
+    l.tp = (int32_t)(pos - lp * P);
+    l.ok = l.ok && lp < (uint32_t)d.g.max_pages;
+    l.page = d.page_table[(int64_t)l.b * d.g.max_pages + (l.ok ? lp : 0u)];     // (no branch around the load)
+  }
+  __device__ __forceinline__ Row lookup_end(const RowLookup& l, bool report) const {
+    Row rw{-1, 0};
+    if (l.ok && l.page >= 0 && l.page < d.g.pool_pages) {
+      rw.page = l.page;
+      rw.tp = l.tp;
+    } else if (report) {
+      qkv_report_drop(d);
+    }
+    return rw;
+  }
+  __device__ __forceinline__ Col column(int c) const { return qkv_col(d, c); }
+  __device__ __forceinline__ void put(const Col& cl, const Row& rw, int r, float v) const { qkv_put<true>(d, cl, rw, r, v); }
   __device__ __forceinline__ bool swap_for(int c0) const {
     const Geo& g = d.g;
     return fast_cols && c0 < g.n_heads * g.q_dim + g.n_kv_heads * g.r_k;
@@ -607,11 +762,14 @@ struct QkvEpBf16 {
 struct PlainEpBf16 {
   uint16_t* y;
   int32_t N;
-  struct Slot {
-    uint16_t* p = nullptr;
-  };
-  __device__ __forceinline__ Slot locate(int r, int c) const { return Slot{y + (int64_t)r * N + c}; }
-  __device__ __forceinline__ void commit(const Slot& s, int, int, float v) const { *s.p = f32_to_bf16_rne(v); }
+  struct Row {};
+  struct RowLookup {};
+  typedef int Col;
+  __device__ __forceinline__ RowLookup lookup_begin(int) const { return RowLookup{}; }
+  __device__ __forceinline__ void lookup_next(RowLookup&) const {}
+  __device__ __forceinline__ Row lookup_end(const RowLookup&, bool) const { return Row{}; }
+  __device__ __forceinline__ Col column(int c) const { return c; }
+  __device__ __forceinline__ void put(const Col& c, const Row&, int r, float v) const { y[(int64_t)r * N + c] = f32_to_bf16_rne(v); }
   __device__ __forceinline__ bool swap_for(int) const { return true; }
   template <int MI>
   __device__ __forceinline__ void store(bool, int r0, int c0, const f32x4 (&acc)[MI][4], int M, int Ncols, int col,
@@ -636,10 +794,35 @@ struct PlainEpBf16 {
   }
 };
 
+// Compute units of the current device (asked once per process; 256 on MI355X, which is also the fallback).
+static int compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0)
+      n = cu;
+    else
+      n = 256;
+    (void)hipGetLastError();
+  }
+  return n;
+}
+
 template <typename Epilogue, bool A_F32>
 static int launch_gemm(const void* A, const void* Wt, int32_t M, int32_t N, int32_t K, const Epilogue& ep,
                        hipStream_t st) {
   const uint16_t* w = (const uint16_t*)Wt;
+  if constexpr (!A_F32) {
+    if (M <= 16 && K <= 32 * kSkinnyWaves * 16) {
+      // one workgroup per compute unit (more only when a workgroup would otherwise get more blocks than it can stage)
+      const int nblks = (N + 15) / 16;
+      int grid = nblks < compute_units() ? nblks : compute_units();
+      if ((nblks + grid - 1) / grid > kPipeMaxUnits) grid = (nblks + kPipeMaxUnits - 1) / kPipeMaxUnits;
+      gemm_bf16_skinny_pipe_kernel<Epilogue><<<dim3(grid), dim3(512), 0, st>>>((const uint16_t*)A, w, M, N, K, ep);
+      return launch_status();
+    }
+  }
   if (M <= 64) {
     // two channel blocks per workgroup when that still leaves about one workgroup per compute unit
     const int nb = (!A_F32 && N / 32 >= 200) ? 2 : 1;     // (float activations need the registers themselves)

@@ -75,3 +75,67 @@ def test_pack_weight_fragment_order(N, K):
     assert (packed[mask] == 0).all()
     wf = torch.from_numpy(g.standard_normal((N, K)).astype(np.float32)).cuda()
     assert torch.equal(ea.pack_weight(wf).view(N, K), wf)
+
+
+# ---------------------------------------------------------------------------
+# A token that cannot be stored (position past the page table, page id outside the pool) is skipped, never
+# written anywhere else, and COUNTED in the caller's status word.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,T,rope", [
+    (ea.EA_BF16, 1, False),      # generation step: pipelined skinny GEMM
+    (ea.EA_BF16, 1, True),       # ... rotary projection
+    (ea.EA_BF16, 9, False),      # 27 rows: general skinny GEMM
+    (ea.EA_BF16, 40, False),     # 120 rows: tiled GEMM, element-wise and fragment-wise stores
+    (ea.EA_BF16, 48, False),     # 16-token aligned appends (fragment-wise stores where the page exists)
+    (ea.EA_BF16, 700, False),    # 2100 rows: the asynchronous GEMM
+    (ea.EA_F32, 5, False),
+])
+def test_dropped_appends_are_counted_and_nothing_else_is_touched(dtype, T, rope):
+    print(f"dropped appends dtype={dtype} T={T} rope={rope}", flush=True)
+    P = 64 if dtype == ea.EA_BF16 else 16
+    H, Hkv, d_h, r_k, r_v, d = 4, 2, 64, 48, 32, 256
+    desc = ea.LayerDesc(d, H, Hkv, d_h, r_k, r_v, dtype, P)
+    B = 3
+    max_pages = -(-(T + 10) // P) + 1
+    cap = max_pages * P
+    pool_pages = B * max_pages + 1
+    g = synth.rng(701, T, int(rope), dtype)
+    pt_host = synth.random_page_table(g, B, max_pages, pool_pages)
+    # sequence 0 fits; sequence 1 ends `over` tokens past its page table; sequence 2's LAST page id is outside the pool
+    over = min(T, 3)
+    lens = np.array([5, cap - T + over, cap - T], dtype=np.int32)
+    pt_bad = pt_host.copy()
+    pt_bad[2, max_pages - 1] = pool_pages + 7
+    in_last_page_2 = sum(1 for t in range(T) if (lens[2] + t) // P == max_pages - 1)
+    expect_dropped = over + in_last_page_2
+    q_dim = d_h if rope else r_k
+    n_out = H * q_dim + Hkv * (r_k + r_v)
+    w = ea.pack_weight(to_dev(desc, synth.gaussian(g, (n_out, d), d ** -0.5)))
+    x = to_dev(desc, synth.gaussian(g, (B * T, d)))
+    k_pool, v_pool = ea.alloc_pools(desc, pool_pages)
+    k_pool.fill_(-77.0); v_pool.fill_(-77.0)
+    q = torch.empty((B * T, H, q_dim), dtype=torch.float32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    fn = ea.project_qkv_rope if rope else ea.project_qkv
+    seq = torch.from_numpy(lens).cuda()
+    fn(desc, x, w, q, k_pool, v_pool, torch.from_numpy(pt_bad).cuda(), seq, T, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == expect_dropped
+    # a second call adds to the word (it is never cleared by the library); without a word the call still works
+    fn(desc, x, w, q, k_pool, v_pool, torch.from_numpy(pt_bad).cuda(), seq, T, status=status)
+    fn(desc, x, w, q, k_pool, v_pool, torch.from_numpy(pt_bad).cuda(), seq, T)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 2 * expect_dropped
+    assert torch.isfinite(q).all()
+    # exactly the storable tokens were written: every other element of the pools still holds the fill value
+    lay = ea.cache_layout_query(desc)
+    stored = B * T - expect_dropped
+    kp, vp = k_pool.float().cpu().numpy().ravel(), v_pool.float().cpu().numpy().ravel()
+    assert int((kp != -77.0).sum()) == stored * Hkv * lay.r_k_pad
+    assert int((vp != -77.0).sum()) == stored * Hkv * lay.r_v_pad
+    # a clean call (everything fits) leaves the word alone
+    status.zero_()
+    fn(desc, x, w, q, k_pool, v_pool, torch.from_numpy(pt_host).cuda(),
+       torch.tensor([5, 0, 7], dtype=torch.int32).cuda(), T, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0

@@ -118,7 +118,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.ea_cache_layout_query(None, ctypes.byref(out)) == -1
     # null pointers / bad sizes: rejected on the host, nothing is launched
     assert lib.ea_decode_attn(ctypes.byref(good), None, None, None, None, None, None, 1, 1, 1, 0, None, 0, None) == -1
-    assert lib.ea_project_qkv(ctypes.byref(good), None, None, None, 0, None, None, None, None, 1, 1, 1, 1, None) == -1
+    assert lib.ea_project_qkv(ctypes.byref(good), None, None, None, 0, None, None, None, None, 1, 1, 1, 1, None, None) == -1
     assert lib.ea_out_proj(ctypes.byref(good), None, 0, None, None, 4, None) == -1
     assert lib.ea_prefill_attn(ctypes.byref(good), None, None, None, None, None, None, 1, 1, 1, 1, None) == -1
     # misaligned pointer (fake, never dereferenced: the check comes first)
@@ -224,20 +224,22 @@ def test_rotary_entry_points_reject_bad_arguments_before_launching():
                                   4, 8, OK_PTR, need - 1, None)
     assert rc == -4
     rc = lib.ea_project_qkv_rope(ctypes.byref(desc(d_h=64, r_k=80)), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR,
-                                 OK_PTR, OK_PTR, 2, 1, 4, 8, None)
+                                 OK_PTR, OK_PTR, 2, 1, 4, 8, None, None)
     assert rc == -2
 
 
 def test_projection_and_prefill_reject_bad_arguments_before_launching():
     lib, d = raw(), desc()
     f = lib.ea_project_qkv
-    assert f(ctypes.byref(d), None, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
-    assert f(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, 5, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
-    assert f(ctypes.byref(d), OK_PTR, ODD_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -3
+    assert f(ctypes.byref(d), None, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None, None) == -1
+    assert f(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, 5, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None, None) == -1
+    assert f(ctypes.byref(d), OK_PTR, ODD_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None, None) == -3
+    # the status word is optional, but when given it must be a 4-byte aligned address
+    assert f(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, OK_PTR + 2, None) == -3
     assert f(ctypes.byref(desc(d=1000)), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8,
-             None) == -2                                                   # bf16 needs d % 32 == 0
+             None, None) == -2                                             # bf16 needs d % 32 == 0
     f32 = desc(ea.EA_F32, P=16)
-    assert f(ctypes.byref(f32), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None) == -1
+    assert f(ctypes.byref(f32), OK_PTR, OK_PTR, OK_PTR, ea.EA_BF16, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 1, 4, 8, None, None) == -1
     g = lib.ea_prefill_attn
     assert g(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, None, 2, 5, 4, 8, None) == -1
     assert g(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 2, 0, 4, 8, None) == -1
