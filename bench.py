@@ -61,24 +61,53 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 4 GiB device copy, so that a rocprofv3 --pmc run of this command has a "
                          "kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
-    ap.add_argument("--cpu-streams", type=int, default=512, help="(sequence, head) streams the oracle is timed on")
+    ap.add_argument("--cpu-streams", type=int, default=64,
+                    help="(sequence, kv head) streams of the first layer copied back for the oracle timing")
+    ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of the timed step")
+    ap.add_argument("--parity-samples", type=int, default=64,
+                    help="(layer, sequence, kv head) triples of the timed step compared with the oracle")
     return ap.parse_args()
 
 
+def source_stamp() -> str:
+    """First 16 hex digits of the SHA-256 over the library's sources (csrc/ and include/, names and contents, in
+    sorted order): what a committed profile summary is stamped with, so that a figure taken from it can be told
+    apart from one that no longer belongs to the kernels being timed."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in (os.path.join(ROOT, "paper_2408_05646_amd", "csrc"), os.path.join(ROOT, "include")):
+        for name in sorted(os.listdir(d)):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def traffic_from_profiles(workload: str):
-    """HBM bytes per decode-attention launch measured with rocprofv3 --pmc (committed summary), or None."""
+    """(HBM bytes per decode-attention launch measured with rocprofv3 --pmc, where that figure comes from), read
+    from the committed summary of that measurement; (None, None) if there is none for this workload.  The
+    counters cannot be read from inside this process, so the figure is only as fresh as its file: the summary
+    carries the stamp of the sources it was measured on, and `stale` says whether they have changed since."""
     name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
-            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt"}.get(workload)
+            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt",
+            "cfg2": "decode_attn_cfg2_hbm_traffic.txt", "cfg5": "decode_attn_cfg5_hbm_traffic.txt"}.get(workload)
     if name is None:
-        return None
+        return None, None
     path = os.path.join(ROOT, "profiles", name)
+    traffic, stamp = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                traffic = float(line.split(":")[1])
+            if line.startswith("kernel_sources_sha16:"):
+                stamp = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None, None
+    if traffic is None:
+        return None, None
+    now = source_stamp()
+    return traffic, {"file": "profiles/" + name, "measured_on_sources": stamp, "sources_now": now,
+                     "stale": stamp != now}
 
 
 def _timed_single_thread(fn):
@@ -100,42 +129,160 @@ def _timed_single_thread(fn):
     return min(run(), run())
 
 
-def cpu_oracle_decode(n_streams: int, n_ctx: int, r: int, d_head: int, rope: bool = False, h2o: bool = False):
-    """The fp64 oracle's decode attention on `n_streams` (sequence, head) streams of the bench workload's
-    shape, single-threaded BLAS, host-generated inputs with the same distribution."""
+def usable_cores() -> int:
+    """Host cores this process may use for the oracle timing: its affinity mask, capped by the thread count the
+    environment grants (OMP_NUM_THREADS on a shared box)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:      # pragma: no cover
+        n = os.cpu_count() or 1
+    cap = os.environ.get("OMP_NUM_THREADS", "")
+    if cap.isdigit() and int(cap) > 0:
+        n = min(n, int(cap))
+    return max(1, n)
+
+
+def oracle_worker_main(path: str, d_head: int, rope_base: float, reps: int) -> None:
+    """One host core's share of the all-core oracle timing; runs in a fresh process of its own
+    (`bench.py --oracle-worker ...`): loads its streams, says "ready", waits for "go" on stdin, runs the fp64
+    oracle's decode attention over its streams `reps` times (single-threaded BLAS), prints the seconds it took."""
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)
+    except Exception:       # pragma: no cover
+        limiter = None
+    from oracle import eigen_attention as ora
+    from paper_2408_05646_amd import synth
+    z = np.load(path)
+    K = synth.bf16_bits_to_f32(z["k"]).astype(np.float64)          # [streams, n, r_k]
+    V = synth.bf16_bits_to_f32(z["v"]).astype(np.float64)
+    q = z["q"].astype(np.float64)                                  # [streams, G, q_dim]
+    U = z["u"].astype(np.float64) if "u" in z.files else None
+    caches = [ora.RankCache.from_arrays([K[i][None]], [V[i][None]]) for i in range(K.shape[0])]
+    print("ready", flush=True)
+    if sys.stdin.readline().strip() != "go":
+        return
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for i, c in enumerate(caches):
+            if U is None:
+                ora.decode_attention(q[i][None], c, d_head)
+            else:
+                ora.decode_attention_rope(q[i][None], c, U, d_head, rope_base)
+    print(f"done {time.perf_counter() - t0:.6f}", flush=True)
+    del limiter
+
+
+def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False):
+    """The fp64 oracle's decode attention timed on host cores, on cache slices copied back from the device.
+    `streams` = list of (K bits [n, r_k] uint16, V bits [n, r_v] uint16, q [G, q_dim] float32): the bfloat16 contents
+    of (sequence, kv head) streams of the first resident layer, exactly as the GPU kernel reads them.  Timed twice:
+    on one core, and on every core this process may use (one fresh single-threaded process per core over disjoint
+    streams)."""
+    import tempfile
+
     import numpy as np
     from oracle import eigen_attention as ora
     from paper_2408_05646_amd import synth
-    g = synth.rng(3, 777)
-    heads = 32
-    n_seq = max(1, n_streams // heads)
-    # one sequence's worth of data, referenced by every sampled sequence (timing does not depend on values)
-    K1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
-    V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
-    q = g.standard_normal((n_seq, heads, d_head if rope else r))
-    cache = ora.RankCache.from_arrays([K1] * n_seq, [V1] * n_seq)
-    # one call = the sampled streams of one layer; repeated so that the sample is several seconds of CPU work
-    reps = 1 if rope else 8
-
-    def work():
-        for _ in range(reps):
-            if rope:
-                ora.decode_attention_rope(q, cache, U, d_head, ROPE_BASE)
-            else:
-                ora.decode_attention(q, cache, d_head)
-                if h2o:
-                    oe.attention_mass(q, cache, d_head)
-
     if h2o:
         from oracle import eviction as oe
-    U = synth.orthonormal_basis(g, d_head, r) if rope else None
-    dt = _timed_single_thread(work) / reps
-    cache_bytes = n_seq * heads * n_ctx * 2 * r * 2          # what the GPU kernel would stream (bf16)
-    return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{'rotary ' if rope else ''}decode attention {'and attention mass per cached token ' if h2o else ''}of {n_seq * heads} of one layer's 512 (sequence, head) "
-                      f"streams (n={n_ctx}, r={r}), fp64 numpy, {dt:.2f} s per pass, {reps} passes timed three times "
-                      f"(best kept); a full 32-layer step would take {dt * 32 * 512 / (n_seq * heads):.0f} s",
-            "seconds": round(dt, 3)}
+    n_ctx, r_k = streams[0][0].shape
+    r_v = streams[0][1].shape[1]
+    G = streams[0][2].shape[0]
+    bytes_per_stream = n_ctx * (r_k + r_v) * 2                     # what the GPU kernel streams for it (bf16)
+    U = None if rope_u is None else rope_u.astype(np.float64)
+
+    # ---- one core
+    caches = [ora.RankCache.from_arrays([synth.bf16_bits_to_f32(k).astype(np.float64)[None]],
+                                        [synth.bf16_bits_to_f32(v).astype(np.float64)[None]]) for k, v, _ in streams]
+    qs = [q.astype(np.float64)[None] for _, _, q in streams]
+
+    def one_pass():
+        for c, q in zip(caches, qs):
+            if U is None:
+                ora.decode_attention(q, c, d_head)
+                if h2o:
+                    oe.attention_mass(q, c, d_head)
+            else:
+                ora.decode_attention_rope(q, c, U, d_head, ROPE_BASE)
+
+    t_probe = _timed_single_thread(one_pass)
+    reps1 = max(1, int(round(2.0 / max(t_probe, 1e-4))))           # about two seconds per timing
+
+    def work():
+        for _ in range(reps1):
+            one_pass()
+
+    dt1 = _timed_single_thread(work) / reps1
+    single = len(streams) * bytes_per_stream / dt1 / 1e9
+    del caches
+
+    # ---- all cores: one fresh process per core, each with its own share of the streams
+    cores = min(usable_cores(), len(streams))
+    multi, dt_all, reps_all = None, None, None
+    note = None
+    if cores > 1 and not h2o:
+        import subprocess
+        tmp = tempfile.mkdtemp(prefix="ea_oracle_", dir="/dev/shm" if os.path.isdir("/dev/shm") else None)
+        shares = [streams[i::cores] for i in range(cores)]
+        per_worker = max(len(sh) for sh in shares)
+        reps_all = max(1, int(round(3.0 / max(dt1 / len(streams) * per_worker, 1e-4))))      # about three seconds
+        procs = []
+        try:
+            for i, sh in enumerate(shares):
+                path = os.path.join(tmp, f"share{i}.npz")
+                arrays = dict(k=np.stack([k for k, _, _ in sh]), v=np.stack([v for _, v, _ in sh]),
+                              q=np.stack([q for _, _, q in sh]))
+                if U is not None:
+                    arrays["u"] = U
+                np.savez(path, **arrays)
+                procs.append(subprocess.Popen(
+                    [sys.executable, "-u", os.path.abspath(__file__), "--oracle-worker", path, str(d_head),
+                     repr(ROPE_BASE), str(reps_all)], stdin=subprocess.PIPE, stdout=subprocess.PIPE, text=True, cwd=ROOT))
+            if all(pr.stdout.readline().strip() == "ready" for pr in procs):     # every worker holds its data in fp64
+                t0 = time.perf_counter()
+                for pr in procs:
+                    pr.stdin.write("go\n")
+                    pr.stdin.flush()
+                done = [pr.stdout.readline().split() for pr in procs]
+                dt_wall = time.perf_counter() - t0
+                if all(len(dn) == 2 and dn[0] == "done" for dn in done):
+                    dt_all = dt_wall / reps_all
+                    multi = sum(len(sh) for sh in shares) * bytes_per_stream / dt_all / 1e9
+                else:
+                    note = "an oracle worker process ended early: all-core figure not available"
+            else:
+                note = "an oracle worker process did not start: all-core figure not available"
+        finally:
+            for pr in procs:
+                try:
+                    pr.stdin.close()
+                    pr.wait(timeout=30)
+                except Exception:
+                    pr.kill()
+            for f in os.listdir(tmp):
+                os.remove(os.path.join(tmp, f))
+            os.rmdir(tmp)
+    what = ("rotary " if U is not None else "") + "decode attention" + \
+        (" and attention mass per cached token" if h2o else "")
+    res = {"value": round(multi if multi is not None else single, 3), "unit": "GB/s",
+           "cores": cores if multi is not None else 1, "kind": "oracle",
+           "sample": f"{what} of {len(streams)} (sequence, kv head) streams of the first resident layer (n={n_ctx}, "
+                     f"r_k={r_k}, r_v={r_v}, {G} query head(s) each), their bfloat16 cache slices and the step's queries "
+                     f"copied back from the device; fp64 numpy; GB/s = the bf16 bytes the GPU kernel streams for these "
+                     f"streams per second of oracle time",
+           "single_core": {"value": round(single, 3), "unit": "GB/s", "cores": 1,
+                           "seconds_per_pass": round(dt1, 4), "passes_timed": reps1},
+           "seconds": round(dt_all if dt_all is not None else dt1, 4)}
+    if note:
+        res["note"] = note
+    if multi is not None:
+        res["all_cores"] = {"value": round(multi, 3), "unit": "GB/s", "cores": cores,
+                            "seconds_per_pass": round(dt_all, 4), "passes_timed": reps_all,
+                            "how": "one fresh single-threaded process per core over disjoint streams, started "
+                                   "together, timed from the common start to the last one's end"}
+    return res
 
 
 def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_tokens: int, rope: bool = False):
@@ -194,6 +341,108 @@ def cpu_oracle_prefill(n_rows: int, n_ctx: int, r: int, d_head: int):
             "seconds": round(dt, 3)}
 
 
+# ---- the bf16 cache layout, undone on the host (index arithmetic from the header's description of the layout):
+# what the oracle is handed never passes through the library
+def _k_tiles_to_rows(tiles, r_pad):
+    """[n_tiles, 64 * r_pad] K tiles -> [n_tiles * 64, r_pad]; a tile is [4 blocks][r_pad/8 chunks][16 tokens][8 channels]."""
+    t = tiles.reshape(-1, 4, r_pad // 8, 16, 8)
+    return t.transpose(0, 1, 3, 2, 4).reshape(-1, r_pad)
+
+
+def _v_tiles_to_rows(tiles, r_pad):
+    """V tile = [2 groups][r_pad/16 blocks][4 quads][16 channels][8 slots], slot j of quad q = token 16*(j/4) + 4*q + j%4."""
+    t = tiles.reshape(-1, 2, r_pad // 16, 4, 16, 2, 4)            # tile, group, block, quad, channel, j/4, j%4
+    return t.transpose(0, 1, 5, 3, 6, 2, 4).reshape(-1, r_pad)
+
+
+def _stream_bits(torch, pool, page_table_row, head, n_kv_heads, r, r_pad, rows_fn, page_tokens, n):
+    """bfloat16 bit patterns [n, r] (uint16) of one (sequence, kv head) stream, read from raw pool memory."""
+    slab = page_tokens * r_pad
+    view = pool.view(torch.int16).view(pool.shape[0], n_kv_heads, slab)
+    got = view[page_table_row.long(), head].cpu().numpy().view("uint16")        # [pages, slab]
+    return rows_fn(got.reshape(-1, 64 * r_pad), r_pad)[:n, :r].copy()
+
+
+def check_step_parity(torch, ea, synth, layers, s, B, n, P, rope, n_samples, seed):
+    """The resident step that was just timed, against the fp64 oracle: sampled (layer, sequence, kv head) triples
+    spread over all layers for the attention (cache slices and the step's own queries copied back from the device),
+    and, for the first and last layer, the projection (queries of all heads, the appended key and value rows of the
+    sampled heads) and the output projection (all of y)."""
+    import numpy as np
+    from oracle import eigen_attention as ora
+    L, H, Hkv, d_h = len(layers), s.n_heads, s.n_kv_heads, s.d_head
+    G = H // Hkv
+    g = synth.rng(33, seed)
+    triples = [(0, 0, 0), (L - 1, B - 1, Hkv - 1)]
+    while len(triples) < n_samples:
+        li = (len(triples) - 2) % L
+        triples.append((li, int(g.integers(B)), int(g.integers(Hkv))))
+    worst, where, errs = 0.0, None, []
+    streams0 = {}
+    for li, b, kvh in triples:
+        l = layers[li]
+        dc = l["desc"]
+        lay = ea.cache_layout_query(dc)
+        Kb = _stream_bits(torch, l["k_pool"], l["page_table"][b], kvh, Hkv, dc.r_k, lay.r_k_pad, _k_tiles_to_rows, P, n)
+        Vb = _stream_bits(torch, l["v_pool"], l["page_table"][b], kvh, Hkv, dc.r_v, lay.r_v_pad, _v_tiles_to_rows, P, n)
+        heads = list(range(kvh * G, (kvh + 1) * G))
+        q = l["q_r"][b, heads].cpu().numpy()
+        if li == 0:
+            streams0[(b, kvh)] = (Kb, Vb, q)
+        cache = ora.RankCache.from_arrays([synth.bf16_bits_to_f32(Kb).astype(np.float64)[None]],
+                                          [synth.bf16_bits_to_f32(Vb).astype(np.float64)[None]])
+        if rope:
+            ref = ora.decode_attention_rope(q[None].astype(np.float64), cache, l["u_k"].float().cpu().numpy(), d_h,
+                                            ROPE_BASE)
+        else:
+            ref = ora.decode_attention(q[None].astype(np.float64), cache, d_h)
+        got = l["o"][b, heads].cpu().numpy()[None]
+        if not np.isfinite(got).all():
+            return {"samples": len(errs), "worst_rel_l2": float("inf"), "where": f"non-finite output, layer {li}"}, streams0
+        e = ora.rel_l2(got, ref)
+        errs.append(e)
+        if e > worst:
+            worst, where = e, f"layer {li}, sequence {b}, kv head {kvh}"
+    res = {"samples": len(errs), "worst_rel_l2": float(f"{worst:.3e}"), "mean_rel_l2": float(f"{np.mean(errs):.3e}"),
+           "where_worst": where, "bar": 1e-2,
+           "what": "decode attention outputs of the timed resident step vs the fp64 oracle on the same bfloat16 "
+                   "cache slices and queries (copied back from the device), sampled over all resident layers"}
+    # ---- first and last layer: projection + append + output projection of the same step
+    proj = {}
+    for li in sorted({0, L - 1}):
+        l = layers[li]
+        if "wqkv_raw" not in l:
+            continue
+        dc = l["desc"]
+        q_dim = d_h if rope else dc.r_k
+        x = l["x"].float().cpu().numpy().astype(np.float64)
+        w = l["wqkv_raw"].float().cpu().numpy().astype(np.float64)                  # [N_qkv, d], out-major
+        nq, nk = H * q_dim, Hkv * dc.r_k
+        Wq = [w[i * q_dim:(i + 1) * q_dim].T for i in range(H)]
+        Wk = [w[nq + i * dc.r_k:nq + (i + 1) * dc.r_k].T for i in range(Hkv)]
+        Wv = [w[nq + nk + i * dc.r_v:nq + nk + (i + 1) * dc.r_v].T for i in range(Hkv)]
+        q_ref, k_ref, v_ref = ora.project_qkv(x, Wq, Wk, Wv)
+        e_q = ora.rel_l2(l["q_r"].cpu().numpy(), q_ref)
+        lay = ea.cache_layout_query(dc)
+        e_kv = 0.0
+        for b, kvh in ((0, 0), (B - 1, Hkv - 1)):
+            Kb = _stream_bits(torch, l["k_pool"], l["page_table"][b], kvh, Hkv, dc.r_k, lay.r_k_pad, _k_tiles_to_rows, P, n)
+            Vb = _stream_bits(torch, l["v_pool"], l["page_table"][b], kvh, Hkv, dc.r_v, lay.r_v_pad, _v_tiles_to_rows, P, n)
+            e_kv = max(e_kv, ora.rel_l2(synth.bf16_bits_to_f32(Kb[n - 1]), k_ref[b, kvh]),
+                       ora.rel_l2(synth.bf16_bits_to_f32(Vb[n - 1]), v_ref[b, kvh]))
+        wo = l["wo_raw"].float().cpu().numpy().astype(np.float64)                   # [d, H * r_v], out-major
+        Wo = np.stack([wo[:, i * dc.r_v:(i + 1) * dc.r_v].T for i in range(H)])
+        y_ref = ora.out_proj(l["o"].cpu().numpy().astype(np.float64), Wo)
+        e_y = ora.rel_l2(l["y"].float().cpu().numpy(), y_ref)
+        proj[f"layer_{li}"] = {"q_rel_l2": float(f"{e_q:.3e}"), "appended_kv_rel_l2": float(f"{e_kv:.3e}"),
+                               "y_rel_l2": float(f"{e_y:.3e}")}
+        worst = max(worst, e_q, e_kv, e_y)
+    res["projections"] = proj
+    res["worst_rel_l2"] = float(f"{worst:.3e}")
+    res["ok"] = bool(np.isfinite(worst) and worst <= 1e-2)
+    return res, streams0
+
+
 def bench_decode(args, torch, ea, synth):
     dev = "cuda"
     base_name, rope = args.workload.split("-")[0], "-rope" in args.workload
@@ -225,7 +474,7 @@ def bench_decode(args, torch, ea, synth):
     gen.manual_seed(synth.BASE_SEED + int(base_name[-1]))
     layers = []
     t_fill = time.perf_counter()
-    for dc in descs:
+    for li, dc in enumerate(descs):
         q_dim = s.d_head if rope else dc.r_k          # the rotary variant keeps the query at full rank (Sec. 4.3)
         n_qkv = H * q_dim + Hkv * (dc.r_k + dc.r_v)
         extra = {}
@@ -260,8 +509,8 @@ def bench_decode(args, torch, ea, synth):
             desc=dc, k_pool=k_pool, v_pool=v_pool, page_table=perm.reshape(B, max_pages).contiguous(),
             S=args.n_splits or (ea.decode_auto_splits(dc, B, n) if (q4 or not rope) else
                                 ea.decode_rope_auto_splits(dc, B, n)),
-            wqkv=ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
-            wo=ea.pack_weight((torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)),
+            wqkv_raw=(torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16),
+            wo_raw=(torch.randn((d, H * dc.r_v), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16),
             x=torch.randn((B, d), generator=gen, device=dev).to(torch.bfloat16),
             q_r=torch.empty((B, H, q_dim), dtype=torch.float32, device=dev),
             # rotary variant: ONE key basis for all heads of the layer, orthonormal columns (QR of a Gaussian)
@@ -270,6 +519,10 @@ def bench_decode(args, torch, ea, synth):
             o=torch.empty((B, H, dc.r_v), dtype=torch.float32, device=dev),
             mass=torch.zeros((B, Hkv, n), dtype=torch.float32, device=dev) if h2o else None,
             y=torch.empty((B, d), dtype=torch.bfloat16, device=dev)))
+        l = layers[-1]
+        l["wqkv"], l["wo"] = ea.pack_weight(l["wqkv_raw"]), ea.pack_weight(l["wo_raw"])
+        if li not in (0, L - 1):          # the unpacked weights of the first and last layer stay for the parity check
+            del l["wqkv_raw"], l["wo_raw"]
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
 
@@ -389,6 +642,11 @@ def bench_decode(args, torch, ea, synth):
         kern = ("decode_rope_q4_kernel + decode_bf16_kernel (rotary variant, newest page) + merge_splits_kernel "
                 "(one ea_decode_attn_rope_q4 call)")
 
+    traffic, traffic_src = traffic_from_profiles(args.workload)
+    if traffic_src is not None and traffic_src["stale"]:
+        print(f"bench.py: {traffic_src['file']} was measured on other kernel sources "
+              f"({traffic_src['measured_on_sources']} != {traffic_src['sources_now']}): roofline.traffic may be out of date",
+              file=sys.stderr)
     rank_note = f"r_k=r_v={s.r_k}" if base_name != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
         "metric": "low-rank decode attn: achieved HBM GB/s over the whole decode step"
@@ -424,7 +682,7 @@ def bench_decode(args, torch, ea, synth):
         "paper_context": PAPER_CONTEXT,
         "roofline": {"bound": "hbm", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic_from_profiles(args.workload),
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": kern, "bytes_per_launch": round(attn_bytes), "us_per_launch": round(attn_us_avg, 2)},
     }
 
@@ -468,12 +726,40 @@ def bench_decode(args, torch, ea, synth):
         torch.cuda.synchronize()
         result["calibration_copy_bytes_each_way"] = src.numel() * 4
 
+    # ---- what was timed, checked: sampled outputs of the resident step against the oracle (outside the timed region)
+    streams0 = {}
+    if not q4 and not args.no_parity:
+        result["parity"], streams0 = check_step_parity(torch, ea, synth, layers, s, B, n, P, rope,
+                                                       max(args.parity_samples, 2), int(base_name[-1]))
+    elif q4:
+        result["parity"] = {"samples": 0, "note": "not checked in this run: the 4-bit workloads are compared with the "
+                                                  "oracle by the GPU tests (tests/test_gpu_q4.py)"}
+
     if not args.no_cpu and q4:
-        result["cpu_baseline"] = cpu_oracle_decode_q4(args.cpu_streams // (32 if rope else 8), n, ranks[0][0], s.d_head,
+        result["cpu_baseline"] = cpu_oracle_decode_q4(512 // (32 if rope else 8), n, ranks[0][0], s.d_head,
                                                       P, rope=rope)
     elif not args.no_cpu:
-        result["cpu_baseline"] = cpu_oracle_decode(args.cpu_streams // (8 if rope else 2 if h2o else 1), n, ranks[0][0],
-                                                   s.d_head, rope=rope, h2o=h2o)
+        # streams of the first resident layer, copied back from the device (those the parity check already holds first)
+        l = layers[0]
+        dc = l["desc"]
+        lay = ea.cache_layout_query(dc)
+        G = H // Hkv
+        want = max(1, min(args.cpu_streams // (4 if rope else 1), B * Hkv))
+        keys = list(streams0.keys())
+        for b in range(B):
+            for kvh in range(Hkv):
+                if len(keys) < want and (b, kvh) not in streams0:
+                    keys.append((b, kvh))
+        streams = []
+        for b, kvh in keys[:want]:
+            if (b, kvh) in streams0:
+                streams.append(streams0[(b, kvh)])
+                continue
+            Kb = _stream_bits(torch, l["k_pool"], l["page_table"][b], kvh, Hkv, dc.r_k, lay.r_k_pad, _k_tiles_to_rows, P, n)
+            Vb = _stream_bits(torch, l["v_pool"], l["page_table"][b], kvh, Hkv, dc.r_v, lay.r_v_pad, _v_tiles_to_rows, P, n)
+            streams.append((Kb, Vb, l["q_r"][b, kvh * G:(kvh + 1) * G].cpu().numpy()))
+        result["cpu_baseline"] = cpu_oracle_decode(streams, s.d_head,
+                                                   rope_u=l["u_k"].float().cpu().numpy() if rope else None, h2o=h2o)
     return result
 
 
@@ -495,8 +781,9 @@ def bench_prefill(args, torch, ea, synth):
     seq0 = torch.zeros((B,), dtype=torch.int32, device=dev)
     seq1 = torch.full((B,), n, dtype=torch.int32, device=dev)
     x = torch.randn((B * n, d), generator=gen, device=dev).to(torch.bfloat16)
-    wqkv = ea.pack_weight((torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
-    wo = ea.pack_weight((torch.randn((d, H * r), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16))
+    wqkv_raw = (torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)
+    wo_raw = (torch.randn((d, H * r), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)
+    wqkv, wo = ea.pack_weight(wqkv_raw), ea.pack_weight(wo_raw)
     q_r = torch.empty((B * n, H, q_dim), dtype=torch.bfloat16, device=dev)
     o = torch.empty((B, n, H, r), dtype=torch.bfloat16, device=dev)
     y = torch.empty((B * n, d), dtype=torch.bfloat16, device=dev)
@@ -569,12 +856,57 @@ def bench_prefill(args, torch, ea, synth):
                     "out_proj": {"ms": round(t[2], 4), "tflops": round(tf(f_out, t[2]), 1)}},
         "roofline": roofline,
     }
+    # ---- what was timed, checked: sampled query rows of the step's attention output and rows of its projections
+    # against the oracle, on the cache contents and queries the step itself produced (copied back from the device)
+    if not args.no_parity:
+        import numpy as np
+        from oracle import eigen_attention as ora
+        lay = ea.cache_layout_query(desc)
+        g = synth.rng(44, int(rope))
+        worst, errs = 0.0, []
+        u_host = u_k.float().cpu().numpy().astype(np.float64) if rope else None
+        picks = [(0, 0, 64), (B - 1, H - 1, n)] + [(int(g.integers(B)), int(g.integers(H)), int(g.integers(65, n)))
+                                                    for _ in range(max(args.parity_samples // 8, 2))]
+        for b, h, m in picks:                         # the 64 queries that end at position m - 1 of (sequence b, head h)
+            Kb = _stream_bits(torch, k_pool, pt[b], h, H, r, lay.r_k_pad, _k_tiles_to_rows, P, m)
+            Vb = _stream_bits(torch, v_pool, pt[b], h, H, r, lay.r_v_pad, _v_tiles_to_rows, P, m)
+            cache = ora.RankCache.from_arrays([synth.bf16_bits_to_f32(Kb).astype(np.float64)[None]],
+                                              [synth.bf16_bits_to_f32(Vb).astype(np.float64)[None]])
+            qrows = q_r.view(B, n, H, q_dim)[b, m - 64:m, h].float().cpu().numpy().astype(np.float64)[None, :, None, :]
+            if rope:
+                ref = ora.prefill_attention_rope(qrows, cache, u_host, s.d_head, ROPE_BASE)
+            else:
+                ref = ora.prefill_attention(qrows, cache, s.d_head)
+            got = o[b, m - 64:m, h].float().cpu().numpy()[None, :, None, :]
+            e = ora.rel_l2(got, ref) if np.isfinite(got).all() else float("inf")
+            errs.append(e)
+            worst = max(worst, e)
+        # projection and output projection on 64 sampled rows
+        rows = np.sort(g.choice(B * n, size=64, replace=False))
+        xr = x[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        w = wqkv_raw.float().cpu().numpy().astype(np.float64)
+        q_ref = xr @ w[:H * q_dim].T
+        e_q = ora.rel_l2(q_r.view(B * n, H * q_dim)[torch.from_numpy(rows).cuda()].float().cpu().numpy(), q_ref)
+        orows = o.view(B * n, H * r)[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        wo_h = wo_raw.float().cpu().numpy().astype(np.float64)
+        e_y = ora.rel_l2(y[torch.from_numpy(rows).cuda()].float().cpu().numpy(), orows @ wo_h.T)
+        worst = max(worst, e_q, e_y)
+        result["parity"] = {"samples": len(errs), "worst_rel_l2": float(f"{worst:.3e}"),
+                            "attention_mean_rel_l2": float(f"{np.mean(errs):.3e}"),
+                            "q_rel_l2": float(f"{e_q:.3e}"), "y_rel_l2": float(f"{e_y:.3e}"), "bar": 1e-2,
+                            "ok": bool(np.isfinite(worst) and worst <= 1e-2),
+                            "what": "blocks of 64 query rows of the timed step's attention output (first rows, last rows, "
+                                    "seeded random positions) and 64 rows of its two projections vs the fp64 oracle, on "
+                                    "the cache slices and queries the step produced"}
     if not args.no_cpu and not rope:
         result["cpu_baseline"] = cpu_oracle_prefill(512, n, r, s.d_head)
     return result
 
 
 def main():
+    if len(sys.argv) >= 6 and sys.argv[1] == "--oracle-worker":       # a child of cpu_oracle_decode: no GPU, no torch
+        oracle_worker_main(sys.argv[2], int(sys.argv[3]), float(sys.argv[4]), int(sys.argv[5]))
+        return
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -590,6 +922,10 @@ def main():
     result = bench_prefill(args, torch, ea, synth) if args.workload.startswith("cfg4") else \
         bench_decode(args, torch, ea, synth)
     print(json.dumps(result))
+    par = result.get("parity")
+    if isinstance(par, dict) and par.get("ok") is False:
+        print(f"bench.py: the timed step does not match the oracle: {par}", file=sys.stderr)
+        sys.exit(4)
 
 
 if __name__ == "__main__":

@@ -68,5 +68,7 @@ def assert_close(got: np.ndarray, ref: np.ndarray, tol: float, what: str = ""):
     rows_r = ref.reshape(-1, ref.shape[-1])
     row_err = np.linalg.norm(rows_g - rows_r, axis=1) / np.maximum(np.linalg.norm(rows_r, axis=1), 1e-300)
     assert err <= tol, f"{what}: rel-L2 {err:.3e} > {tol:.1e}"
-    assert row_err.max() <= 10 * tol, f"{what}: worst row rel-L2 {row_err.max():.3e}"
+    # no single (sequence, head) row may hide behind the others: measured worst rows are about 3e-3 (bf16), so 3x the
+    # bar on the whole tensor is already generous
+    assert row_err.max() <= 3 * tol, f"{what}: worst row rel-L2 {row_err.max():.3e}"
     return err

@@ -37,7 +37,28 @@ def stream_from_pool(pool, page_table_row, head, n_kv_heads, r_pad, rows_fn, pag
     return rows_fn(got.reshape(-1, 64 * r_pad), r_pad).astype(np.float64)
 
 
-def run_sampled_decode(desc, B, n, samples, seed, n_splits=0, with_mass=False):
+def shape_stream(desc, k_pool, pt, q, b, kvh, kind, n):
+    """Rewrites the keys of one (sequence, kv head) stream in place so that its scores against the stream's first
+    query head follow a pattern: "peak" = one token (two thirds into the sequence) scores 40 above the rest,
+    "ramp" = the scores climb by 30 over the sequence (the softmax reference moves many times on the way)."""
+    Hkv, G = desc.n_kv_heads, desc.n_heads // desc.n_kv_heads
+    row = pt[b:b + 1].contiguous()
+    kd = torch.empty((1, Hkv, n, desc.r_k), dtype=torch.bfloat16, device="cuda")
+    ea.cache_gather(desc, kd, None, k_pool, None, row)
+    qv = q[b, kvh * G].double()
+    t = torch.arange(n, device="cuda", dtype=torch.float64)
+    alpha = torch.zeros(n, dtype=torch.float64, device="cuda")
+    if kind == "peak":
+        alpha[(2 * n) // 3] = 40.0
+    else:
+        alpha = 30.0 * t / n
+    along = alpha[:, None] * (desc.d_head ** 0.5 / float(qv.norm()) ** 2) * qv[None, :]     # q . along[t] / sqrt(d_h) = alpha[t]
+    kd[0, kvh] = (0.1 * kd[0, kvh].double() + along).to(torch.bfloat16)
+    ea.cache_scatter(desc, kd, None, k_pool, None, row)
+    torch.cuda.synchronize()
+
+
+def run_sampled_decode(desc, B, n, samples, seed, n_splits=0, with_mass=False, shaped=None):
     P = desc.page_tokens
     max_pages = n // P
     pool_pages = B * max_pages
@@ -48,6 +69,8 @@ def run_sampled_decode(desc, B, n, samples, seed, n_splits=0, with_mass=False):
     seq = torch.full((B,), n, dtype=torch.int32, device="cuda")
     q = torch.randn((B, desc.n_heads, desc.r_k), generator=gen, device="cuda")
     out = torch.full((B, desc.n_heads, desc.r_v), float("nan"), device="cuda")
+    for (b, kvh), kind in (shaped or {}).items():
+        shape_stream(desc, k_pool, pt, q, b, kvh, kind, n)
     S = n_splits or ea.decode_auto_splits(desc, B, n)
     mass = None
     if with_mass:      # the fused call: the same output, and the attention mass of every cached token
@@ -90,6 +113,16 @@ def test_cfg3_one_layer_sampled():
     print("cfg3 samples", samples, flush=True)
     S = run_sampled_decode(desc, s.batch, s.n_ctx, samples, seed=33)
     assert S == ea.decode_auto_splits(desc, s.batch, s.n_ctx) == 1
+
+
+def test_cfg3_full_length_peaked_and_ramped_streams():
+    """The same launch with two streams whose softmax is far from flat over all 32768 tokens: one token that takes
+    (almost) all of the probability, and scores that climb steadily to the end of the sequence."""
+    s = synth.CFG3
+    desc = ea.LayerDesc(s.d_model, s.n_heads, s.n_kv_heads, s.d_head, s.r_k, s.r_v, ea.EA_BF16, 64)
+    shaped = {(3, 5): "peak", (12, 30): "ramp", (0, 0): "ramp", (15, 31): "peak"}
+    print("cfg3 shaped streams", shaped, flush=True)
+    run_sampled_decode(desc, s.batch, s.n_ctx, list(shaped) + [(3, 6), (12, 29)], seed=36, shaped=shaped)
 
 
 def test_cfg3_one_layer_with_attention_mass_sampled():
