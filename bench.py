@@ -608,6 +608,30 @@ def bench_decode(args, torch, ea, synth):
         torch.cuda.synchronize()
         ms_per_step_graph = g0.elapsed_time(g1) / args.steps
 
+    # ---- the same step with ONE library call per layer (ea_decode_layer: q_r and o stay in its workspace)
+    ms_per_step_layer = None
+    if not q4 and not h2o:
+        lws = torch.empty(max(ea.decode_layer_workspace_bytes(l["desc"], B, l["S"], rope) for l in layers) // 4,
+                          dtype=torch.float32, device=dev)
+
+        def layer_step():
+            for l in layers:
+                ea.decode_layer(l["desc"], l["x"], l["wqkv"], l["wo"], l["k_pool"], l["v_pool"], l["page_table"],
+                                seq_before, l["y"], l["S"], lws, u_k=l["u_k"], rope_base=ROPE_BASE)
+
+        for _ in range(max(args.warmup, 1)):
+            layer_step()
+        torch.cuda.synchronize()
+        l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        l0.record()
+        for _ in range(args.steps):
+            layer_step()
+        l1.record()
+        torch.cuda.synchronize()
+        ms_per_step_layer = l0.elapsed_time(l1) / args.steps
+        step()                              # leaves q_r / o / y of the separate calls in place for the parity check
+        torch.cuda.synchronize()
+
     # ---- algorithmic bytes (what the method itself must move)
     attn_bytes_sum, step_bytes = 0, 0
     for dc in descs:
@@ -677,6 +701,10 @@ def bench_decode(args, torch, ea, synth):
         "hip_graph_replay": None if ms_per_step_graph is None else {
             "ms_per_step": round(ms_per_step_graph, 4),
             "GBps": round(step_bytes / (ms_per_step_graph * 1e-3) / 1e9, 1)},
+        "one_call_per_layer": None if ms_per_step_layer is None else {
+            "ms_per_step": round(ms_per_step_layer, 4),
+            "GBps": round(step_bytes / (ms_per_step_layer * 1e-3) / 1e9, 1),
+            "what": "the same step through ea_decode_layer" + ("_rope" if rope else "") + " (one call per layer)"},
         "step_algorithmic_bytes": step_bytes,
         "fill_seconds": round(t_fill, 1), "timed_wall_seconds": round(wall, 3),
         "paper_context": PAPER_CONTEXT,

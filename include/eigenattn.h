@@ -205,6 +205,34 @@ EA_API int ea_decode_attn_static(const ea_layer_desc* desc, const void* dev_q_r,
                    const void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len, float* dev_out,
                    int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* stream);
 
+/* The whole generation step of one attention layer in a single call (Sec. 2, "LLM inference", with the folded
+ * weights of Eq. 8): for the newest token of each of B <= 64 sequences
+ *   [q_r | k_r | v_r] = x [W^Q' | W^K' | W^V'],  K_r <- Concat(K_r, k_r), V_r <- Concat(V_r, v_r)   (ea_project_qkv, T = 1)
+ *   o = Softmax(q_r K_r^T / sqrt(d_h)) V_r over the seq_len[b] + 1 cached tokens                       (ea_decode_attn)
+ *   y = [o_1 .. o_H] W^O'                                                                                (ea_out_proj)
+ * enqueued back to back on the stream: three launches, four when the sequence is split (the merge of the split
+ * partials is a launch of its own: merging inside the attention launch, by the workgroup that finishes last, was
+ * built and measured no faster on MI355X).  q_r and o never leave the workspace.  EA_BF16 layers only.
+ *   dev_x [B, d] bfloat16; dev_wqkv / dev_wo packed as for ea_project_qkv / ea_out_proj; dev_y [B, d] bfloat16
+ *   dev_seq_len [B]: lengths BEFORE this step (the token is appended at that position); not modified
+ *   n_splits: as ea_decode_attn (0 = choose)
+ *   dev_ws: ea_decode_layer_workspace_bytes(desc, B, n_splits, rotary) bytes (n_splits >= 1 there: pass what
+ *           ea_decode_auto_splits / ea_decode_rope_auto_splits returns if the call is to choose), 256-byte aligned;
+ *           needs no preparation
+ *   dev_status: as ea_project_qkv (NULL, or the word that counts appends that could not be stored)
+ * ea_decode_layer_rope is the same step for models with rotary position embedding (Sec. 4.3): dev_wqkv as for
+ * ea_project_qkv_rope, dev_u_k [d_head, r_k] bfloat16 and rope_base as for ea_decode_attn_rope. */
+EA_API int64_t ea_decode_layer_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t rotary);
+EA_API int ea_decode_layer(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                   void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                   void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits,
+                   void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream);
+EA_API int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                   const void* dev_u_k, double rope_base, void* dev_k_pool, void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                   int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                   int32_t* dev_status, void* stream);
+
 /* Generation-phase attention for models with rotary position embedding
  * (Sec. 4.3, Eq. 9-10): the query keeps all d_head channels, the cache holds the
  * rank-r_k keys k_r = k U^K of ONE basis U^K shared by all heads, and each cached

@@ -20,7 +20,7 @@ __all__ = [
     "Q4Layout", "q4_layout_query", "q4_k_code_pos", "q4_v_code_pos", "q4_k_scale_pos", "q4_v_scale_pos", "alloc_q4_pools",
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
-    "decode_attn_static", "STATIC_SCRATCH_BYTES",
+    "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = (
     "ea_q4_layout_query", "ea_q4_k_code_pos", "ea_q4_v_code_pos", "ea_q4_k_scale_pos", "ea_q4_v_scale_pos",
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
-    "ea_decode_attn_static",
+    "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
 )
 
 STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
@@ -109,6 +109,11 @@ def load_library():
     lib.ea_decode_rope_auto_splits.restype = I32
     lib.ea_decode_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_decode_layer_workspace_bytes.restype = I64
+    lib.ea_decode_layer_workspace_bytes.argtypes = [D, I32, I32, I32]
+    lib.ea_decode_layer.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP, VP]
+    lib.ea_decode_layer_rope.argtypes = [D, VP, VP, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP,
+                                         I64, VP, VP]
     lib.ea_decode_attn_static.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
@@ -346,6 +351,51 @@ def decode_attn_static(desc, q_r, k_pool, v_pool, page_table, seq_len, out, n_sp
                                               _ptr(page_table), _ptr(seq_len), _ptr(out), B, page_table.shape[1],
                                               k_pool.shape[0], n_splits, _stream(stream))
     _check(rc, "ea_decode_attn_static")
+
+
+def decode_layer_workspace_bytes(desc, B: int, n_splits: int, rotary: bool = False) -> int:
+    return int(load_library().ea_decode_layer_workspace_bytes(ctypes.byref(desc), B, n_splits, int(rotary)))
+
+
+def decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws, u_k=None,
+                 rope_base: float = 10000.0, status=None, stream=None) -> None:
+    """One generation step of a layer (projection + append, attention over seq_len + 1 tokens, output projection) in
+    one call: x [B, d] -> y [B, d], both bfloat16.  With u_k ([d_head, r_k] bfloat16) the rotary form
+    (ea_decode_layer_rope).  ws: decode_layer_workspace_bytes bytes."""
+    B = seq_len.shape[0]
+    _expect(x, desc.dtype, "x"); _expect(y, desc.dtype, "y"); _expect(wqkv, desc.dtype, "wqkv"); _expect(wo, desc.dtype, "wo")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len")
+    q_dim = desc.d_head if u_k is not None else desc.r_k
+    n_out = desc.n_heads * q_dim + desc.n_kv_heads * (desc.r_k + desc.r_v)
+    if (x.numel() != B * desc.d_model or y.numel() != B * desc.d_model
+            or wqkv.numel() != packed_weight_elems(n_out, desc.d_model, desc.dtype)
+            or wo.numel() != packed_weight_elems(desc.d_model, desc.n_heads * desc.r_v, desc.dtype)):
+        raise ValueError("x / y / packed weight sizes do not match the layer")
+    if status is not None:
+        _i32(status, "status")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    lib = load_library()
+    if u_k is None:
+        rc = lib.ea_decode_layer(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(k_pool), _ptr(v_pool),
+                                 _ptr(page_table), _ptr(seq_len), _ptr(y), B, page_table.shape[1], k_pool.shape[0],
+                                 n_splits, _ptr(ws), ws_bytes, _ptr(status), _stream(stream))
+        _check(rc, "ea_decode_layer")
+    else:
+        _expect(u_k, desc.dtype, "u_k")
+        if u_k.numel() != desc.d_head * desc.r_k or not u_k.is_contiguous():
+            raise ValueError("u_k must be a contiguous [d_head, r_k] tensor")
+        rc = lib.ea_decode_layer_rope(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(u_k), float(rope_base),
+                                      _ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(y), B,
+                                      page_table.shape[1], k_pool.shape[0], n_splits, _ptr(ws), ws_bytes,
+                                      _ptr(status), _stream(stream))
+        _check(rc, "ea_decode_layer_rope")
+
+
+def decode_layer_rope(desc, x, wqkv, wo, u_k, rope_base, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws,
+                      status=None, stream=None) -> None:
+    decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits, ws, u_k=u_k, rope_base=rope_base,
+                 status=status, stream=stream)
 
 
 def decode_attn_rope(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table, seq_len, out, n_splits: int = 0,

@@ -387,4 +387,90 @@ int ea_out_proj(const ea_layer_desc* desc, const void* dev_o, int32_t o_dtype, c
                       (hipStream_t)stream);
 }
 
+
+// ---- the whole generation step of a layer in one call ------------------------------------------------------
+
+static int64_t align256(int64_t x) { return (x + 255) / 256 * 256; }
+
+static int64_t layer_ws_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t q_dim) {
+  return align256(ea_decode_workspace_bytes(desc, B, n_splits)) + align256((int64_t)B * desc->n_heads * q_dim * 4) +
+         align256((int64_t)B * desc->n_heads * desc->r_v * 4);
+}
+
+int64_t ea_decode_layer_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t rotary) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || n_splits < 1 || n_splits > 1024) return -1;
+  return layer_ws_bytes(desc, B, n_splits, rotary ? desc->d_head : desc->r_k);
+}
+
+static int decode_layer_impl(const ea_layer_desc* desc, bool rope, const void* dev_x, const void* dev_wqkv,
+                             const void* dev_wo, const void* dev_u_k, double rope_base, void* dev_k_pool,
+                             void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y,
+                             int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
+                             int64_t ws_bytes, int32_t* dev_status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc != EA_OK) return rc;
+  if (desc->dtype != EA_BF16) return EA_ERR_SHAPE;
+  if (!dev_x || !dev_wqkv || !dev_wo || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len || !dev_y ||
+      (rope && !dev_u_k))
+    return EA_ERR_ARG;
+  if (B <= 0 || B > 64 || max_pages <= 0 || pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
+  if (rope && (!(rope_base > 1.0) || !(rope_base < 1e30))) return EA_ERR_ARG;
+  if (rope && (desc->r_k > desc->d_head || (desc->d_head != 64 && desc->d_head != 128))) return EA_ERR_SHAPE;
+  if (!aligned16(dev_x) || !aligned16(dev_wqkv) || !aligned16(dev_wo) || !aligned16(dev_k_pool) ||
+      !aligned16(dev_v_pool) || !aligned16(dev_y) || (rope && !aligned16(dev_u_k)))
+    return EA_ERR_ALIGN;
+  if ((desc->n_heads * desc->r_v) % 32 != 0 || desc->d_model % 32 != 0) return EA_ERR_SHAPE;
+  if (n_splits == 0) {
+    const int64_t cap_tokens = (int64_t)max_pages * desc->page_tokens;
+    const int32_t cap32 = cap_tokens > INT32_MAX ? INT32_MAX : (int32_t)cap_tokens;
+    n_splits = rope ? ea_decode_rope_auto_splits(desc, B, cap32) : ea_decode_auto_splits(desc, B, cap32);
+  }
+  const int32_t q_dim = rope ? desc->d_head : desc->r_k;
+  if (!dev_ws || (reinterpret_cast<uintptr_t>(dev_ws) & 255u)) return EA_ERR_WORKSPACE;
+  if (ws_bytes < layer_ws_bytes(desc, B, n_splits, q_dim)) return EA_ERR_WORKSPACE;
+  char* w = (char*)dev_ws;
+  float* part = (float*)w;                                   // split partials (nothing when n_splits == 1)
+  w += align256(ea_decode_workspace_bytes(desc, B, n_splits));
+  float* q = (float*)w;
+  w += align256((int64_t)B * desc->n_heads * q_dim * 4);
+  float* o = (float*)w;
+  hipStream_t st = (hipStream_t)stream;
+  // a1 + a2: projection and append
+  rc = project_qkv_impl(desc, q_dim, dev_x, dev_wqkv, q, EA_F32, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, B,
+                        1, max_pages, pool_pages, dev_status, stream);
+  if (rc != EA_OK) return rc;
+  // a3 over the sequences including the token just appended (the kernels add one to the lengths they read)
+  Geo g = make_geo(desc, max_pages, pool_pages);
+  if (rope)
+    rc = decode_rope_bf16(desc, g, q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B,
+                          n_splits, part, st, 0, 0, 1);
+  else
+    rc = decode_bf16(desc, g, q, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B, n_splits, part, st, 0, 0, 1);
+  if (rc != EA_OK) return rc;
+  if (n_splits > 1) {
+    rc = merge_splits(g, part, o, B, n_splits, st);
+    if (rc != EA_OK) return rc;
+  }
+  // a5
+  return gemm_out_bf16(o, 1, dev_wo, dev_y, B, desc->d_model, desc->n_heads * desc->r_v, st);
+}
+
+int ea_decode_layer(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                    void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                    void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
+                    int64_t ws_bytes, int32_t* dev_status, void* stream) {
+  return decode_layer_impl(desc, false, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool, dev_page_table,
+                           dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes, dev_status, stream);
+}
+
+int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                         const void* dev_u_k, double rope_base, void* dev_k_pool, void* dev_v_pool,
+                         const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                         int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                         int32_t* dev_status, void* stream) {
+  return decode_layer_impl(desc, true, dev_x, dev_wqkv, dev_wo, dev_u_k, rope_base, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream);
+}
+
 }  // extern "C"

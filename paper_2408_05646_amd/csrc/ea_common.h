@@ -138,14 +138,14 @@ int cache_copy(const ea_layer_desc* d, const Geo& g, bool scatter, void* k_dense
 // ws_slots > 0: write split partials only, into slots ws_slot0 .. of a workspace laid out for ws_slots splits.
 int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
-                hipStream_t st, int32_t ws_slots = 0, int32_t ws_slot0 = 0);
+                hipStream_t st, int32_t ws_slots = 0, int32_t ws_slot0 = 0, int32_t seq_add = 0);
 int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
                hipStream_t st);
 int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
                      float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st, int32_t ws_slots = 0,
-                     int32_t ws_slot0 = 0);
+                     int32_t ws_slot0 = 0, int32_t seq_add = 0);
 int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
                     const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
                     float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);

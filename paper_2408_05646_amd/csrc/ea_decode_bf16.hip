@@ -65,7 +65,7 @@ static int dispatch_ncb(int ncb, const DecodeArgs& a, int32_t B, hipStream_t st)
 
 int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
-                hipStream_t st, int32_t ws_slots, int32_t ws_slot0) {
+                hipStream_t st, int32_t ws_slots, int32_t ws_slot0, int32_t seq_add) {
   if (B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   DecodeArgs a;
   a.q = q;
@@ -84,6 +84,7 @@ int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void
   a.log2_base = 0.0;
   a.ws_slots = ws_slots;
   a.ws_slot0 = ws_slot0;
+  a.seq_add = seq_add;
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   switch (ks) {
     case 1: return dispatch_ncb<1>(ncb, a, B, st);

@@ -50,6 +50,7 @@ struct DecodeArgs {
   // SCORES variant only: the scaled scores (log2 units) of every (sequence, head, token) are written here as well
   float* scores = nullptr;   // [B, H, s_row]
   int32_t s_row = 0;         // row length: the cache capacity rounded up to whole tiles
+  int32_t seq_add = 0;       // added to seq_len[b]: 1 when seq_len holds the lengths BEFORE the token this step appends
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -119,7 +120,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
   typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
   const const_i32_ptr seq_len_c = (const_i32_ptr)a.seq_len;
   const const_i32_ptr pt_row = (const_i32_ptr)(a.page_table + (int64_t)b * g.max_pages);
-  int64_t n64 = seq_len_c[b];
+  int64_t n64 = (int64_t)seq_len_c[b] + a.seq_add;
   const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
   if (n64 > cap) n64 = cap;
   if (n64 < 0) n64 = 0;
