@@ -158,13 +158,30 @@ int ea_project_qkv_rope(const ea_layer_desc* desc, const void* dev_x, const void
                           dev_page_table, dev_seq_len, B, T, max_pages, pool_pages, dev_status, stream);
 }
 
+// Compute units of the current device, asked once per process; 256 (MI355X) when no device can be asked.
+static int resident_compute_units() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0)
+      n = cu;
+    else
+      n = 256;
+    (void)hipGetLastError();
+  }
+  return n;
+}
+
 int32_t ea_decode_auto_splits(const ea_layer_desc* desc, int32_t B, int32_t max_seq_len) {
   if (validate_desc(desc) != EA_OK || B <= 0 || max_seq_len <= 0) return 1;
-  // One workgroup per resident slot (256 CUs x 2 workgroups) measured best on MI355X: more splits only add
-  // merge work, fewer leave compute units without a stream.  Every workgroup keeps at least eight tiles.
+  // One workgroup per resident slot (compute units x 2 workgroups: the attention kernels run two 4-wave workgroups
+  // per compute unit) measured best on MI355X: more splits only add merge work, fewer leave compute units without
+  // a stream.  Every workgroup keeps at least eight tiles.
   const int64_t streams = (int64_t)B * (desc->dtype == EA_BF16 ? desc->n_kv_heads : desc->n_heads);
   const int32_t tiles = (max_seq_len + kTile - 1) / kTile;
-  int64_t want = (512 + streams - 1) / streams;
+  const int64_t slots = 2 * (int64_t)resident_compute_units();
+  int64_t want = (slots + streams - 1) / streams;
   int64_t cap = tiles / 8;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
