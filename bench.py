@@ -69,17 +69,22 @@ def parse_args():
     return ap.parse_args()
 
 
-def source_stamp() -> str:
-    """First 16 hex digits of the SHA-256 over the library's sources (csrc/ and include/, names and contents, in
-    sorted order): what a committed profile summary is stamped with, so that a figure taken from it can be told
-    apart from one that no longer belongs to the kernels being timed."""
+def source_stamp(files=None) -> str:
+    """First 16 hex digits of the SHA-256 over library sources (names and contents, in sorted order): the named
+    files of csrc/ and include/, or all of them.  A committed profile summary lists the sources of the kernels it
+    measured and carries their stamp, so that a figure taken from it can be told apart from one that no longer
+    belongs to the kernels being timed."""
     import hashlib
     h = hashlib.sha256()
+    found = {}
     for d in (os.path.join(ROOT, "paper_2408_05646_amd", "csrc"), os.path.join(ROOT, "include")):
-        for name in sorted(os.listdir(d)):
+        for name in os.listdir(d):
             if name.endswith((".hip", ".h")):
-                h.update(name.encode())
-                h.update(open(os.path.join(d, name), "rb").read())
+                found[name] = os.path.join(d, name)
+    names = sorted(found) if files is None else sorted(files)
+    for name in names:
+        h.update(name.encode())
+        h.update(open(found[name], "rb").read() if name in found else b"<missing>")
     return h.hexdigest()[:16]
 
 
@@ -87,27 +92,30 @@ def traffic_from_profiles(workload: str):
     """(HBM bytes per decode-attention launch measured with rocprofv3 --pmc, where that figure comes from), read
     from the committed summary of that measurement; (None, None) if there is none for this workload.  The
     counters cannot be read from inside this process, so the figure is only as fresh as its file: the summary
-    carries the stamp of the sources it was measured on, and `stale` says whether they have changed since."""
+    names the kernel sources it was measured on and carries their stamp, and `stale` says whether they have
+    changed since."""
     name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
             "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt",
             "cfg2": "decode_attn_cfg2_hbm_traffic.txt", "cfg5": "decode_attn_cfg5_hbm_traffic.txt"}.get(workload)
     if name is None:
         return None, None
     path = os.path.join(ROOT, "profiles", name)
-    traffic, stamp = None, None
+    traffic, stamp, files = None, None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
+            if line.startswith("kernel_sources:"):
+                files = line.split(":")[1].split()
             if line.startswith("kernel_sources_sha16:"):
                 stamp = line.split(":")[1].strip()
     except OSError:
         return None, None
     if traffic is None:
         return None, None
-    now = source_stamp()
-    return traffic, {"file": "profiles/" + name, "measured_on_sources": stamp, "sources_now": now,
-                     "stale": stamp != now}
+    now = source_stamp(files)
+    return traffic, {"file": "profiles/" + name, "kernel_sources": files, "measured_on_sources": stamp,
+                     "sources_now": now, "stale": stamp != now}
 
 
 def _timed_single_thread(fn):
