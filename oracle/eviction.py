@@ -12,6 +12,14 @@ every new query.  In the rank-r space those probabilities are the p_t of Eq. (3)
                    p_i = Softmax(q_r,i . K_r[g]^T / sqrt(d_h))      (Eq. 3 with Eq. 7's operands)
   h2o_victim       the cached token to drop: smallest accumulated mass among all but the n_recent newest
 
+Rotary models (the paper's token-pruning table is on Llama models, whose attention is the form of Sec. 4.3): a token
+that survives an eviction keeps the position it had in the text, so once tokens have been dropped the position of the
+key in cache slot t is no longer t.  The two functions below are Eq. 10 with the position of every cached key, and of
+the query, given explicitly:
+
+  decode_attention_rope_positions   s_t = rot(q, pos_q) . rot(U^K k_r[t], pos_k[t]) / sqrt(d_h), o = Softmax(s) V_r
+  attention_mass_rope_positions     the same probabilities summed over the query heads of a kv head
+
 Pins (tests/test_oracle_eviction.py): every (sequence, kv head) row of the mass sums to the number of query heads
 in the group; brute force; closed-form cases (zero query: uniform; one dominant key); permutation equivariance;
 heads of different kv heads do not mix; the selection rule on hand-made accumulators.
@@ -45,3 +53,52 @@ def h2o_victim(acc, n_recent: int) -> int:
     n = acc.shape[0]
     assert 0 <= n_recent < n
     return int(np.argmin(acc[:n - n_recent]))
+
+
+def decode_attention_rope_positions(q, pos_q, cache: "ea_oracle.RankCache", pos_k, Uk, d_head: int,
+                                    base: float = 10000.0, return_probs: bool = False):
+    """Generation-phase Eigen Attention of a rotary model (Sec. 4.3, Eq. 10) over a cache whose slots hold tokens
+    of arbitrary original positions (what is left after token pruning).
+
+    q [B, H, d_h]: full-rank query, not rotated; pos_q [B]: its position in the text.
+    cache.K[b][g] [n_b, r_k]: rank-r keys k_r = k U^K (never rotated); pos_k[b] [n_b]: the position of the token in
+    each slot; Uk [d_h, r_k]: the basis shared by all heads.
+    Each key is brought back to d_h channels, k' = U^K k_r, rotated to ITS position; the query to its own.
+    Returns o [B, H, r_v] (and, with return_probs, the list over b*H + i of the probabilities p[n_b])."""
+    q = np.asarray(q, np.float64)
+    Uk = np.asarray(Uk, np.float64)
+    B, H, d_h = q.shape
+    assert d_h == d_head and Uk.shape[0] == d_h
+    out = np.zeros((B, H, cache.r_v))
+    probs = []
+    for b in range(B):
+        n = cache.seq_len(b)
+        if n == 0:
+            raise ValueError("decode over an empty sequence")
+        pk = np.asarray(pos_k[b])
+        assert pk.shape == (n,)
+        for i in range(H):
+            g = i // (H // cache.n_kv_heads)
+            K_up = cache.K[b][g] @ Uk.T                                            # [n, d_h]
+            K_rot = ea_oracle.rope_rotate(K_up, pk, base)
+            q_rot = ea_oracle.rope_rotate(q[b, i], int(pos_q[b]), base)
+            p = ea_oracle.softmax((K_rot @ q_rot) / np.sqrt(d_head))
+            probs.append(p)
+            out[b, i] = p @ cache.V[b][g]
+    return (out, probs) if return_probs else out
+
+
+def attention_mass_rope_positions(q, pos_q, cache: "ea_oracle.RankCache", pos_k, Uk, d_head: int,
+                                  base: float = 10000.0):
+    """mass[b][g, t] = sum over the query heads i of kv head g of p_i[t], p from decode_attention_rope_positions."""
+    q = np.asarray(q, np.float64)
+    B, H, _ = q.shape
+    _, probs = decode_attention_rope_positions(q, pos_q, cache, pos_k, Uk, d_head, base, return_probs=True)
+    G = H // cache.n_kv_heads
+    out = []
+    for b in range(B):
+        per_kv_head = np.zeros((cache.n_kv_heads, cache.seq_len(b)))
+        for i in range(H):
+            per_kv_head[i // G] += probs[b * H + i]
+        out.append(per_kv_head)
+    return out

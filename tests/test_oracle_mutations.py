@@ -156,6 +156,24 @@ EVICTION = [
     ("the heaviest token is evicted",
      "    return int(np.argmin(acc[:n - n_recent]))", "    return int(np.argmax(acc[:n - n_recent]))",
      "test_h2o_selection_rule"),
+    ("rotary, after pruning: a key is rotated to its slot index, not to its position",
+     "K_rot = ea_oracle.rope_rotate(K_up, pk, base)", "K_rot = ea_oracle.rope_rotate(K_up, np.arange(n), base)",
+     "test_a_kept_token_scores_as_in_the_sequence_it_was_kept_from"),
+    ("rotary, after pruning: the query is rotated to the last slot index",
+     "q_rot = ea_oracle.rope_rotate(q[b, i], int(pos_q[b]), base)", "q_rot = ea_oracle.rope_rotate(q[b, i], n - 1, base)",
+     "test_a_kept_token_scores_as_in_the_sequence_it_was_kept_from"),
+    ("rotary, after pruning: the query turns the other way",
+     "q_rot = ea_oracle.rope_rotate(q[b, i], int(pos_q[b]), base)", "q_rot = ea_oracle.rope_rotate(q[b, i], -int(pos_q[b]), base)",
+     "test_rope_positions_against_the_complex_form_slot_order_and_a_common_shift"),
+    ("rotary, after pruning: scores divided by sqrt(r_k)",
+     "p = ea_oracle.softmax((K_rot @ q_rot) / np.sqrt(d_head))", "p = ea_oracle.softmax((K_rot @ q_rot) / np.sqrt(Uk.shape[1]))",
+     "test_rope_positions_against_the_complex_form_slot_order_and_a_common_shift"),
+    ("rotary, after pruning: keys brought back to d_h channels with rows of the basis instead of its transpose",
+     "K_up = cache.K[b][g] @ Uk.T ", "K_up = cache.K[b][g] @ Uk[:cache.K[b][g].shape[1], :] ",
+     "test_rope_positions_reduce_to_the_plain_rotary_form_when_nothing_was_dropped"),
+    ("rotary, after pruning: the mass of a kv head sums the wrong heads",
+     "            per_kv_head[i // G] += probs[b * H + i]", "            per_kv_head[i % cache.n_kv_heads] += probs[b * H + i]",
+     "test_a_kept_token_scores_as_in_the_sequence_it_was_kept_from"),
 ]
 
 
