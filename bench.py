@@ -51,7 +51,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
-                             "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o"])
+                             "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o", "cfg2-rope-h2o", "cfg3-rope-h2o"])
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -96,7 +96,8 @@ def traffic_from_profiles(workload: str):
     changed since."""
     name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
             "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt",
-            "cfg2": "decode_attn_cfg2_hbm_traffic.txt", "cfg5": "decode_attn_cfg5_hbm_traffic.txt"}.get(workload)
+            "cfg2": "decode_attn_cfg2_hbm_traffic.txt", "cfg5": "decode_attn_cfg5_hbm_traffic.txt",
+            "cfg3-rope-h2o": "decode_attn_mass_rope_pos_cfg3_hbm_traffic.txt"}.get(workload)
     if name is None:
         return None, None
     path = os.path.join(ROOT, "profiles", name)
@@ -182,12 +183,13 @@ def oracle_worker_main(path: str, d_head: int, rope_base: float, reps: int) -> N
     del limiter
 
 
-def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False):
+def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False, positions=None):
     """The fp64 oracle's decode attention timed on host cores, on cache slices copied back from the device.
     `streams` = list of (K bits [n, r_k] uint16, V bits [n, r_v] uint16, q [G, q_dim] float32): the bfloat16 contents
     of (sequence, kv head) streams of the first resident layer, exactly as the GPU kernel reads them.  Timed twice:
     on one core, and on every core this process may use (one fresh single-threaded process per core over disjoint
-    streams)."""
+    streams).  positions (rotary + h2o: the cache of a pruned sequence) = list, per stream, of (position of the token
+    in every slot [n], position of the query)."""
     import tempfile
 
     import numpy as np
@@ -207,8 +209,11 @@ def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False):
     qs = [q.astype(np.float64)[None] for _, _, q in streams]
 
     def one_pass():
-        for c, q in zip(caches, qs):
-            if U is None:
+        for i, (c, q) in enumerate(zip(caches, qs)):
+            if positions is not None:
+                oe.attention_mass_rope_positions(q, [positions[i][1]], c, [positions[i][0]], U, d_head, ROPE_BASE)
+                oe.decode_attention_rope_positions(q, [positions[i][1]], c, [positions[i][0]], U, d_head, ROPE_BASE)
+            elif U is None:
                 ora.decode_attention(q, c, d_head)
                 if h2o:
                     oe.attention_mass(q, c, d_head)
@@ -273,7 +278,8 @@ def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False):
                 os.remove(os.path.join(tmp, f))
             os.rmdir(tmp)
     what = ("rotary " if U is not None else "") + "decode attention" + \
-        (" and attention mass per cached token" if h2o else "")
+        (" and attention mass per cached token" if h2o else "") + \
+        (" over a pruned cache (explicit positions)" if positions is not None else "")
     res = {"value": round(multi if multi is not None else single, 3), "unit": "GB/s",
            "cores": cores if multi is not None else 1, "kind": "oracle",
            "sample": f"{what} of {len(streams)} (sequence, kv head) streams of the first resident layer (n={n_ctx}, "
@@ -371,7 +377,7 @@ def _stream_bits(torch, pool, page_table_row, head, n_kv_heads, r, r_pad, rows_f
     return rows_fn(got.reshape(-1, 64 * r_pad), r_pad)[:n, :r].copy()
 
 
-def check_step_parity(torch, ea, synth, layers, s, B, n, P, rope, n_samples, seed):
+def check_step_parity(torch, ea, synth, layers, s, B, n, P, rope, n_samples, seed, slot_pos=None, q_pos=None):
     """The resident step that was just timed, against the fp64 oracle: sampled (layer, sequence, kv head) triples
     spread over all layers for the attention (cache slices and the step's own queries copied back from the device),
     and, for the first and last layer, the projection (queries of all heads, the appended key and value rows of the
@@ -399,7 +405,12 @@ def check_step_parity(torch, ea, synth, layers, s, B, n, P, rope, n_samples, see
             streams0[(b, kvh)] = (Kb, Vb, q)
         cache = ora.RankCache.from_arrays([synth.bf16_bits_to_f32(Kb).astype(np.float64)[None]],
                                           [synth.bf16_bits_to_f32(Vb).astype(np.float64)[None]])
-        if rope:
+        if rope and slot_pos is not None:
+            from oracle import eviction as oe
+            ref = oe.decode_attention_rope_positions(q[None].astype(np.float64), [int(q_pos[b])], cache,
+                                                     [slot_pos[b, :n].cpu().numpy()], l["u_k"].float().cpu().numpy(),
+                                                     d_h, ROPE_BASE)
+        elif rope:
             ref = ora.decode_attention_rope(q[None].astype(np.float64), cache, l["u_k"].float().cpu().numpy(), d_h,
                                             ROPE_BASE)
         else:
@@ -456,6 +467,7 @@ def bench_decode(args, torch, ea, synth):
     base_name, rope = args.workload.split("-")[0], "-rope" in args.workload
     q4 = args.workload.endswith("-q4")       # all pages but the newest of every sequence held in 4 bits
     h2o = args.workload.endswith("-h2o")     # the step also accumulates the attention mass every cached token receives
+    pruned = rope and h2o                    # rotary + eviction: every cache slot carries the position its token had
     s = {"cfg2": synth.CFG2, "cfg3": synth.CFG3, "cfg5": synth.CFG5}[base_name]
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
     H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
@@ -534,6 +546,14 @@ def bench_decode(args, torch, ea, synth):
     torch.cuda.synchronize()
     t_fill = time.perf_counter() - t_fill
 
+    slot_pos, q_pos = None, None
+    if pruned:
+        # what is left of a text four times as long: n kept tokens per sequence, in whatever slot eviction left them
+        gp = torch.Generator(device=dev)
+        gp.manual_seed(20240805 + 77)
+        slot_pos = torch.stack([torch.randperm(4 * n, generator=gp, device=dev)[:n] for _ in range(B)]).to(torch.int32)
+        slot_pos = slot_pos.contiguous()
+        q_pos = torch.full((B,), 4 * n, dtype=torch.int32, device=dev)
     seq_before = torch.full((B,), n - 1, dtype=torch.int32, device=dev)    # the step appends token n-1 ...
     seq_after = torch.full((B,), n, dtype=torch.int32, device=dev)         # ... and attends over n tokens
     if h2o:
@@ -563,6 +583,9 @@ def bench_decode(args, torch, ea, synth):
             elif q4:
                 ea.decode_attn_q4(l["desc"], l["q_r"], l["kq_pool"], l["vq_pool"], l["page_table"], q4_len,
                                   l["k_pool"], l["v_pool"], l["tail_table"], tail_after, l["o"], l["S"], ws)
+            elif pruned:
+                ea.decode_attn_mass_rope_pos(l["desc"], l["q_r"], l["u_k"], ROPE_BASE, l["k_pool"], l["v_pool"],
+                                             l["page_table"], seq_after, slot_pos, q_pos, l["o"], l["mass"], l["S"], ws)
             elif h2o:
                 ea.decode_attn_mass(l["desc"], l["q_r"], l["k_pool"], l["v_pool"], l["page_table"], seq_after, l["o"],
                                     l["mass"], l["S"], ws)
@@ -653,7 +676,8 @@ def bench_decode(args, torch, ea, synth):
             cache_bytes = B * Hkv * n * (dc.r_k + dc.r_v) * 2
         attn = cache_bytes + B * H * q_dim * 4 + B * H * dc.r_v * 4 + B * max_pages * 4 + \
             (s.d_head * dc.r_k * 2 if rope else 0) + \
-            (B * Hkv * n * 8 if h2o else 0)        # the accumulator, read and written (the staged scores are overhead)
+            (B * Hkv * n * 8 if h2o else 0) + \
+            (B * n * 4 if pruned else 0)           # the accumulator, read and written (the staged scores are overhead); the positions
         proj = n_qkv * d * 2 + B * d * 2 + B * H * q_dim * 4 + B * Hkv * (dc.r_k + dc.r_v) * 2
         outp = H * dc.r_v * d * 2 + B * H * dc.r_v * 4 + B * d * 2
         attn_bytes_sum += attn
@@ -673,6 +697,9 @@ def bench_decode(args, torch, ea, synth):
     if q4 and rope:
         kern = ("decode_rope_q4_kernel + decode_bf16_kernel (rotary variant, newest page) + merge_splits_kernel "
                 "(one ea_decode_attn_rope_q4 call)")
+    if pruned:
+        kern = ("decode_bf16_kernel (rotary variant with explicit positions, score-storing form) + merge_splits_kernel + "
+                "mass_from_scores_kernel (one ea_decode_attn_mass_rope_pos call)")
 
     traffic, traffic_src = traffic_from_profiles(args.workload)
     if traffic_src is not None and traffic_src["stale"]:
@@ -695,6 +722,10 @@ def bench_decode(args, torch, ea, synth):
                                + ("rotary position variant (Sec. 4.3): project_qkv_rope + decode_attn_rope_q4 + out_proj "
                                   "per layer, query at position n-1, base 10000" if (q4 and rope) else
                                   "project_qkv + decode_attn_q4 + out_proj per layer" if q4 else
+                                  "rotary model after token pruning (Sec. 4.3 with H2O): project_qkv_rope + "
+                                  "decode_attn_mass_rope_pos + out_proj per layer; the n cached tokens of a sequence are "
+                                  "a random subset of a text of 4n tokens, each at its original position, in random slot "
+                                  "order; query at position 4n, base 10000" if pruned else
                                   "project_qkv + decode_attn_mass (attention output and, for an H2O-style eviction "
                                   "policy, the attention mass of every cached token added to a per-layer accumulator) "
                                   "+ out_proj per layer" if h2o else
@@ -766,7 +797,8 @@ def bench_decode(args, torch, ea, synth):
     streams0 = {}
     if not q4 and not args.no_parity:
         result["parity"], streams0 = check_step_parity(torch, ea, synth, layers, s, B, n, P, rope,
-                                                       max(args.parity_samples, 2), int(base_name[-1]))
+                                                       max(args.parity_samples, 2), int(base_name[-1]),
+                                                       slot_pos=slot_pos, q_pos=q_pos)
     elif q4:
         result["parity"] = {"samples": 0, "note": "not checked in this run: the 4-bit workloads are compared with the "
                                                   "oracle by the GPU tests (tests/test_gpu_q4.py)"}
@@ -787,6 +819,7 @@ def bench_decode(args, torch, ea, synth):
                 if len(keys) < want and (b, kvh) not in streams0:
                     keys.append((b, kvh))
         streams = []
+        positions = ([(slot_pos[b, :n].cpu().numpy(), int(q_pos[b])) for b, _ in keys[:want]] if pruned else None)
         for b, kvh in keys[:want]:
             if (b, kvh) in streams0:
                 streams.append(streams0[(b, kvh)])
@@ -795,7 +828,8 @@ def bench_decode(args, torch, ea, synth):
             Vb = _stream_bits(torch, l["v_pool"], l["page_table"][b], kvh, Hkv, dc.r_v, lay.r_v_pad, _v_tiles_to_rows, P, n)
             streams.append((Kb, Vb, l["q_r"][b, kvh * G:(kvh + 1) * G].cpu().numpy()))
         result["cpu_baseline"] = cpu_oracle_decode(streams, s.d_head,
-                                                   rope_u=l["u_k"].float().cpu().numpy() if rope else None, h2o=h2o)
+                                                   rope_u=l["u_k"].float().cpu().numpy() if rope else None, h2o=h2o,
+                                                   positions=positions)
     return result
 
 

@@ -467,6 +467,40 @@ EA_API int ea_decode_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, 
                            float* dev_out, float* dev_mass, int32_t B, int32_t max_pages, int32_t pool_pages,
                            int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* Rotary models after token pruning (results, "Eigen Attention with token pruning": the paper's table is on
+ * Llama models, whose attention is the form of Sec. 4.3, Eq. (10)).  A token that stays in the cache keeps the
+ * position it had in the text, so once tokens have been dropped the key in cache slot t is no longer at position t:
+ *   s_t = rot(q, q_pos[b]) . rot(U^K k_r[t], slot_pos[b][t]) / sqrt(d_h),  o = Softmax(s) V_r
+ * ea_decode_attn_rope_pos is ea_decode_attn_rope with those positions given explicitly.  The cache itself is
+ * unchanged (rank-r keys, never rotated), so a freed slot is overwritten by ea_project_qkv_rope (pass the slot as
+ * that sequence's length) and the caller writes the new token's position into dev_slot_pos.
+ *   dev_slot_pos [B, pos_stride] int32: position in the text of the token in logical slot t of sequence b
+ *                (slot = index into the sequence's pages, as everywhere); pos_stride >= max_pages * page_tokens;
+ *                entries of slots >= seq_len[b] are read (whole 64-token tiles) but not used
+ *   dev_q_pos    [B] int32: position of the query
+ *   positions must lie in [0, 2^24): the kernel forms angle = position * theta_j exactly from single-precision
+ *   parts (EA_F32 layers: in double precision); only position differences enter a score
+ *   everything else as in ea_decode_attn_rope (n_splits 0 = ea_decode_rope_auto_splits, dev_ws
+ *   ea_decode_workspace_bytes when n_splits > 1).
+ * Errors: EA_ERR_ARG also for pos_stride below the page table's capacity; EA_ERR_ALIGN for position arrays that are
+ * not 4-byte aligned.
+ *
+ * ea_decode_attn_mass_rope_pos also adds the attention probability every slot received to dev_mass, as
+ * ea_decode_attn_mass does for the position-free form (bfloat16 layers; dev_mass [B, H_kv, max_pages * page_tokens]
+ * float; dev_ws ea_decode_attn_mass_workspace_bytes(desc, B, max_pages, n_splits) bytes, always required;
+ * H / H_kv <= 16). */
+EA_API int ea_decode_attn_rope_pos(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
+                               const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_page_table,
+                               const int32_t* dev_seq_len, const int32_t* dev_slot_pos, int32_t pos_stride,
+                               const int32_t* dev_q_pos, float* dev_out, int32_t B, int32_t max_pages,
+                               int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream);
+EA_API int ea_decode_attn_mass_rope_pos(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k,
+                                    double rope_base, const void* dev_k_pool, const void* dev_v_pool,
+                                    const int32_t* dev_page_table, const int32_t* dev_seq_len,
+                                    const int32_t* dev_slot_pos, int32_t pos_stride, const int32_t* dev_q_pos,
+                                    float* dev_out, float* dev_mass, int32_t B, int32_t max_pages, int32_t pool_pages,
+                                    int32_t n_splits, void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* Output projection from rank r_v: y = [o_1 .. o_H] W^O' with
  * W^O'_i = U^V_{g(i)}^T W^O_i (Eq. 2, second line, and Eq. 8).
  *   dev_o    [M, H*r_v] float (o_dtype EA_F32) or bfloat16 (EA_BF16), M = B*T

@@ -21,6 +21,7 @@ __all__ = [
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
+    "decode_attn_rope_pos", "decode_attn_mass_rope_pos",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -34,6 +35,7 @@ EXPORTED_SYMBOLS = (
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
+    "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos",
 )
 
 STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
@@ -116,6 +118,10 @@ def load_library():
                                          I64, VP, VP]
     lib.ea_decode_attn_static.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
+    lib.ea_decode_attn_rope_pos.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, VP, VP, I32, I32, I32, I32,
+                                            VP, I64, VP]
+    lib.ea_decode_attn_mass_rope_pos.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, VP, VP, VP, I32, I32,
+                                                 I32, I32, VP, I64, VP]
     lib.ea_decode_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_prefill_attn_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_prefill_rope_workspace_bytes.argtypes = [D, I32, I32, I32]
@@ -418,6 +424,49 @@ def decode_attn_rope(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table,
                                             page_table.shape[1], k_pool.shape[0], n_splits, _ptr(ws), ws_bytes,
                                             _stream(stream))
     _check(rc, "ea_decode_attn_rope")
+
+
+def decode_attn_rope_pos(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table, seq_len, slot_pos, q_pos, out,
+                         n_splits: int = 0, ws=None, mass=None, stream=None) -> None:
+    """decode_attn_rope over a cache from which tokens have been dropped: slot_pos [B, >= max_pages * page_tokens]
+    int32 holds the position in the text of the token in every cache slot, q_pos [B] int32 the query's.  With mass
+    ([B, H_kv, max_pages * page_tokens] float32, bfloat16 layers) the probability every slot received is added to it
+    (ea_decode_attn_mass_rope_pos; ws: decode_attn_mass_workspace_bytes, n_splits >= 1)."""
+    import torch
+    B = seq_len.shape[0]
+    if q.dtype != torch.float32 or out.dtype != torch.float32:
+        raise ValueError("q and out must be float32")
+    _expect(u_k, desc.dtype, "u_k")
+    if q.numel() != B * desc.n_heads * desc.d_head or out.numel() != B * desc.n_heads * desc.r_v:
+        raise ValueError("q / out have the wrong size")
+    if u_k.numel() != desc.d_head * desc.r_k or not u_k.is_contiguous():
+        raise ValueError("u_k must be a contiguous [d_head, r_k] tensor")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    _i32(page_table, "page_table"); _i32(seq_len, "seq_len"); _i32(slot_pos, "slot_pos"); _i32(q_pos, "q_pos")
+    if slot_pos.dim() != 2 or slot_pos.shape[0] != B or not slot_pos.is_contiguous() or q_pos.numel() != B:
+        raise ValueError("slot_pos must be a contiguous [B, stride] tensor, q_pos [B]")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    lib = load_library()
+    if mass is None:
+        rc = lib.ea_decode_attn_rope_pos(ctypes.byref(desc), _ptr(q), _ptr(u_k), float(rope_base), _ptr(k_pool),
+                                         _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(slot_pos),
+                                         slot_pos.shape[1], _ptr(q_pos), _ptr(out), B, page_table.shape[1],
+                                         k_pool.shape[0], n_splits, _ptr(ws), ws_bytes, _stream(stream))
+        _check(rc, "ea_decode_attn_rope_pos")
+        return
+    if mass.dtype != torch.float32 or mass.numel() != B * desc.n_kv_heads * page_table.shape[1] * desc.page_tokens:
+        raise ValueError("mass must be float32 [B, H_kv, max_pages * page_tokens]")
+    rc = lib.ea_decode_attn_mass_rope_pos(ctypes.byref(desc), _ptr(q), _ptr(u_k), float(rope_base), _ptr(k_pool),
+                                          _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(slot_pos),
+                                          slot_pos.shape[1], _ptr(q_pos), _ptr(out), _ptr(mass), B, page_table.shape[1],
+                                          k_pool.shape[0], n_splits, _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_decode_attn_mass_rope_pos")
+
+
+def decode_attn_mass_rope_pos(desc, q, u_k, rope_base: float, k_pool, v_pool, page_table, seq_len, slot_pos, q_pos, out,
+                              mass, n_splits: int, ws, stream=None) -> None:
+    decode_attn_rope_pos(desc, q, u_k, rope_base, k_pool, v_pool, page_table, seq_len, slot_pos, q_pos, out,
+                         n_splits=n_splits, ws=ws, mass=mass, stream=stream)
 
 
 def prefill_attn(desc, q_r, k_pool, v_pool, page_table, seq_len, out, stream=None) -> None:

@@ -15,10 +15,6 @@
 
 namespace ea {
 
-// Row length (floats) of the per-head scratch rows e / scores for a cache of n_cap tokens: whole tiles, plus a pad
-// of 17 * 256 bytes.  Without it the rows of long sequences start a power of two apart, and all the workgroups,
-// which advance through their rows in step, would write to the same memory channel at the same time.
-__host__ __device__ inline int64_t mass_row_floats(int64_t n_cap) { return (n_cap + kTile - 1) / kTile * kTile + 1088; }
 
 struct MassArgs {
   const float* q;            // [B, H, r_k]
@@ -311,6 +307,23 @@ __global__ __launch_bounds__(256) void mass_from_scores_kernel(MassFromScoresArg
   }
 }
 
+int mass_from_scores(const Geo& g, const float* scores, const float* ml, const int32_t* seq_len, float* mass, int32_t B,
+                     int32_t n_cap, int32_t s_row, hipStream_t st) {
+  MassFromScoresArgs a;
+  a.scores = scores;
+  a.ml = ml;
+  a.seq_len = seq_len;
+  a.mass = mass;
+  a.n_heads = g.n_heads;
+  a.n_kv_heads = g.n_kv_heads;
+  a.group = g.group;
+  a.n_cap = n_cap;
+  a.s_row = s_row;
+  mass_from_scores_kernel<<<dim3((uint32_t)((n_cap + kFinishTokens - 1) / kFinishTokens), g.n_kv_heads, B), dim3(256), 0,
+                            st>>>(a);
+  return launch_status();
+}
+
 static int64_t mass_ws_floats(const ea_layer_desc* d, int32_t B, int32_t max_pages) {
   const int64_t n_cap = (int64_t)max_pages * d->page_tokens;
   const int64_t tiles = (n_cap + kTile - 1) / kTile;
@@ -421,19 +434,7 @@ int ea_decode_attn_mass(const ea_layer_desc* desc, const float* dev_q_r, const v
   if (rc != EA_OK) return rc;
   rc = merge_splits(g, partials, dev_out, B, n_splits, st, ml);
   if (rc != EA_OK) return rc;
-  MassFromScoresArgs a;
-  a.scores = scores;
-  a.ml = ml;
-  a.seq_len = dev_seq_len;
-  a.mass = dev_mass;
-  a.n_heads = g.n_heads;
-  a.n_kv_heads = g.n_kv_heads;
-  a.group = g.group;
-  a.n_cap = n_cap;
-  a.s_row = s_row;
-  mass_from_scores_kernel<<<dim3((uint32_t)((n_cap + kFinishTokens - 1) / kFinishTokens), g.n_kv_heads, B), dim3(256), 0,
-                            st>>>(a);
-  return launch_status();
+  return mass_from_scores(g, scores, ml, dev_seq_len, dev_mass, B, n_cap, s_row, st);
 }
 
 

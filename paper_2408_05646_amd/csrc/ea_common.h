@@ -168,6 +168,13 @@ int decode_scores_bf16(const ea_layer_desc* d, const Geo& g, const float* q, con
                        float* scores, int32_t s_row, hipStream_t st);
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st,
                  float* ml_out = nullptr);   // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
+// Row length (floats) of the per-head scratch rows e / scores for a cache of n_cap tokens: whole tiles, plus a pad
+// of 17 * 256 bytes.  Without it the rows of long sequences start a power of two apart, and all the workgroups,
+// which advance through their rows in step, would write to the same memory channel at the same time.
+__host__ __device__ inline int64_t mass_row_floats(int64_t n_cap) { return (n_cap + kTile - 1) / kTile * kTile + 1088; }
+// mass[b, kv head, t] += sum over the kv head's query heads of 2^(scores[b, head, t] - M) / L, (M, L) = ml[b, head]
+int mass_from_scores(const Geo& g, const float* scores, const float* ml, const int32_t* seq_len, float* mass, int32_t B,
+                     int32_t n_cap, int32_t s_row, hipStream_t st);
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
                  const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,

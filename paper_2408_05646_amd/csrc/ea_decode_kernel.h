@@ -20,6 +20,13 @@
 // key's norm, far inside the fp16 range for attention keys).  Only the position DIFFERENCE enters a score, so the rotation is split: the query is
 // rotated (in fp32, once per tile of a wave) by the distance between its own position and the first
 // token of the tile, each key by its offset inside the tile (a constant table in LDS).
+//
+// POS (rotary only) is the form for a cache from which tokens have been dropped (the token-pruning experiment of the
+// results; a kept token keeps the position it had in the text): the position of the token in every cache slot comes
+// from an array, so the split above no longer works -- the query is rotated once to its own position, each key to
+// its own, with cos and sin computed where they are used (angle in turns, reduced exactly in two single-precision
+// steps; v_sin_f32 / v_cos_f32 on the remaining fraction).  With SCORES the kernel also stores its scores, as the
+// position-free form does.
 #pragma once
 #include <type_traits>
 #include "ea_common.h"
@@ -51,6 +58,10 @@ struct DecodeArgs {
   float* scores = nullptr;   // [B, H, s_row]
   int32_t s_row = 0;         // row length: the cache capacity rounded up to whole tiles
   int32_t seq_add = 0;       // added to seq_len[b]: 1 when seq_len holds the lengths BEFORE the token this step appends
+  // POS variant only: positions in the text
+  const int32_t* slot_pos = nullptr;   // [B, pos_stride]: of the token in logical cache slot t (0 <= value < 2^24)
+  const int32_t* q_pos = nullptr;      // [B]: of the query
+  int32_t pos_stride = 0;              // >= max_pages * page_tokens
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -65,13 +76,15 @@ struct MergeSmem {
 
 // Rotation tables of the rotary variant.  Pair j = 16*kk + 4*quad + i of lane (col, quad) rotates by
 // theta_j = base^(-2j/d_head) per position.
-template <int TBN, int NKK, int KS>
+template <int TBN, int NKK, int KS, bool POS>
 struct RopeSmem {
   // A operand of the up-projection: row m of block 2*kk + comp is channel 2*(16*kk + m) + comp of the basis
   bf16x8 uf[2 * NKK][KS][64];
-  f16x8 tcs[4][NKK][64];             // cos (slots 0-3) and sin (4-7) of (16*tb + col) * theta_j: a key's offset in its tile
-  f32x4 sc[NKK][64], ss[NKK][64];    // angle -(4 * 64) * theta_j: from one tile of a wave to its next
+  // (not in the POS form, which has no use for tables over offsets)
+  f16x8 tcs[POS ? 1 : 4][POS ? 1 : NKK][POS ? 1 : 64];   // cos (slots 0-3) and sin (4-7) of (16*tb + col) * theta_j: a key's offset in its tile
+  f32x4 sc[POS ? 1 : NKK][POS ? 1 : 64], ss[POS ? 1 : NKK][POS ? 1 : 64];    // angle -(4 * 64) * theta_j: from one tile of a wave to its next
   double turns[NKK * 16];                     // theta_j / (2 pi)
+  f32x4 thi[NKK][4], tlo[NKK][4];             // POS: the same as single-precision hi + lo, [kk][quad] = pairs 16*kk + 4*quad ..+3
 };
 struct NoSmem {};
 
@@ -91,18 +104,23 @@ constexpr int kScoreStage = 2048;      // floats of staged scores per wave (SCOR
 struct ScoreSmem {
   float s[4][kScoreStage];
 };
-template <int KS, int NCB, int TBN, int NKK, bool SCORES = false>
-union DecodeSmem {
-  MergeSmem<NCB> mg;
-  std::conditional_t<(NKK > 0), RopeSmem<TBN, (NKK > 0) ? NKK : 1, KS>, NoSmem> rp;
+template <int KS, int NCB, int TBN, int NKK, bool SCORES, bool POS>
+struct StreamSmem {    // what is live while the cache streams
+  std::conditional_t<(NKK > 0), RopeSmem<TBN, (NKK > 0) ? NKK : 1, KS, POS>, NoSmem> rp;
   std::conditional_t<SCORES, ScoreSmem, NoSmem> sc;
 };
+template <int KS, int NCB, int TBN, int NKK, bool SCORES = false, bool POS = false>
+union DecodeSmem {
+  MergeSmem<NCB> mg;
+  StreamSmem<KS, NCB, TBN, NKK, SCORES, POS> st;
+};
 
-template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false>
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false, bool POS = false>
 __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int kvh, const int split, const int b,
-                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK, SCORES>& sm) {
+                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK, SCORES, POS>& sm) {
   constexpr bool ROPE = NKK > 0;
   static_assert(!(ROPE && ALIBI), "a model has one position scheme");
+  static_assert(!POS || ROPE, "explicit positions matter to the rotary form only");
   constexpr int UN = TBN / 2;            // 32-token groups per iteration
   constexpr int SUB = 4 / TBN;           // iterations per 64-token tile
   constexpr int TOK = TBN * 16;          // tokens per iteration
@@ -167,14 +185,16 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
   constexpr int NK1 = ROPE ? NKK : 1;
   float qa[NK1][4], qb[NK1][4];  // the query's pairs j = 16*kk + 4*quad + i, rotated to the current iteration
   f16x8 qf[NK1];                 // ... as B operand of the score MFMA: slot 4*comp + i of k-step kk
-  const int pos_q = n - 1;       // the query is the token appended last
+  int pos_q = n - 1;             // the query is the token appended last
+  if constexpr (POS) pos_q = ((const_i32_ptr)a.q_pos)[b];
   float alibi_slope = 0.f;       // this lane's head, log2 units
   if constexpr (ALIBI) alibi_slope = col < G ? a.alibi[kvh * G + col] * 1.4426950408889634f : 0.f;
   auto seed_q = [&](int tile) {
     if constexpr (ROPE) {
     // head columns past the group read head 0 of the group (always there) and are zeroed
     const float* qrow = a.q + ((int64_t)b * g.n_heads + (int64_t)kvh * G + (col < G ? col : 0)) * a.d_head;
-    const double rel = (double)(pos_q - tile * kTile);
+    // POS: keys are rotated to their absolute positions, so the query is, too (once)
+    const double rel = POS ? (double)pos_q : (double)(pos_q - tile * kTile);
 #pragma unroll
     for (int kk = 0; kk < NK1; ++kk) {
 #pragma unroll
@@ -183,7 +203,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
         const float g0 = qrow[2 * j] * a.scale_log2, g1 = qrow[2 * j + 1] * a.scale_log2;
         const float q0 = col < G ? g0 : 0.f, q1 = col < G ? g1 : 0.f;
         float c, sn;
-        rot_turns(rel * sm.rp.turns[j], c, sn);
+        rot_turns(rel * sm.st.rp.turns[j], c, sn);
         qa[kk][i] = q0 * c - q1 * sn;
         qb[kk][i] = q0 * sn + q1 * c;
       }
@@ -194,7 +214,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
     if constexpr (ROPE) {
 #pragma unroll
     for (int kk = 0; kk < NK1; ++kk) {
-      const f32x4 c4 = sm.rp.sc[kk][tl], s4 = sm.rp.ss[kk][tl];
+      const f32x4 c4 = sm.st.rp.sc[kk][tl], s4 = sm.st.rp.ss[kk][tl];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const float x0 = qa[kk][i], x1 = qb[kk][i];
@@ -267,6 +287,15 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       }
     }
   };
+  // POS: the positions of the tokens this lane's keys belong to (token col of each 16-token block)
+  int kpA[POS ? TBN : 1], kpB[POS ? TBN : 1];
+  auto load_pos = [&](const Pos& p, auto& kp) {
+    if constexpr (POS) {
+      const int32_t* prow = a.slot_pos + (int64_t)b * a.pos_stride + p.tile * kTile + p.sub * TOK + col;
+#pragma unroll
+      for (int tb = 0; tb < TBN; ++tb) kp[tb] = prow[tb * 16];
+    }
+  };
   auto load_v = [&](const Pos& p, int page) {
     const uint16_t* base = a.v_pool + (int64_t)page * g.v_page + (int64_t)kvh * g.v_slab +
                            (int64_t)p.tin * (kTile * g.r_v_pad) + p.sub * (TOK * g.r_v_pad);
@@ -286,6 +315,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
     // A tile without a valid page is still read -- from page 0, which exists -- and all of its tokens are
     // masked below: the loads never depend on the page table's contents, only their address does.
     load_k(cur, max(page, 0), kfA);
+    load_pos(cur, kpA);
     load_v(cur, max(page, 0));
   }
   // the position after the current one (with two key buffers its keys are requested one iteration ahead)
@@ -293,12 +323,15 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
   bool have_n = have && nxt.tile < t_end;
   int page_n = have_n ? page_of(nxt) : -1;
   if constexpr (KDB) {
-    if (have_n) load_k(nxt, max(page_n, 0), kfB);
+    if (have_n) {
+      load_k(nxt, max(page_n, 0), kfB);
+      load_pos(nxt, kpB);
+    }
   }
   // the rotary tables are built while the first tile is on its way
   if constexpr (ROPE) {
     if (threadIdx.x < NKK * 16)
-      sm.rp.turns[threadIdx.x] =
+      sm.st.rp.turns[threadIdx.x] =
           exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base) * 0.15915494309189535;
     for (int e = threadIdx.x; e < 2 * NKK * KS * 64; e += 256) {
       const int ln = e & 63, ks = (e >> 6) % KS, fb = e / (64 * KS);
@@ -312,33 +345,41 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 #pragma unroll
         for (int x = 0; x < 8; ++x) w[x] = rho0 + x < g.r_k ? urow[rho0 + x] : (uint16_t)0;
       }
-      sm.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
+      sm.st.rp.uf[fb][ks][ln] = __builtin_bit_cast(bf16x8, w);
     }
     __syncthreads();
-    for (int e = threadIdx.x; e < 4 * NKK * 64; e += 256) {
+    if constexpr (POS) {
+      if (threadIdx.x < NKK * 16) {
+        const double t = sm.st.rp.turns[threadIdx.x];
+        const float hi = (float)t;
+        sm.st.rp.thi[threadIdx.x >> 4][(threadIdx.x >> 2) & 3][threadIdx.x & 3] = hi;
+        sm.st.rp.tlo[threadIdx.x >> 4][(threadIdx.x >> 2) & 3][threadIdx.x & 3] = (float)(t - (double)hi);
+      }
+    }
+    for (int e = threadIdx.x; !POS && e < 4 * NKK * 64; e += 256) {
       const int ln = e & 63, kk = (e >> 6) % NKK, tb = e / (64 * NKK);
       f16x8 cs;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float c, sn;
-        rot_turns((double)(tb * 16 + (ln & 15)) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        rot_turns((double)(tb * 16 + (ln & 15)) * sm.st.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
         cs[i] = (_Float16)c;
         cs[4 + i] = (_Float16)sn;
       }
-      sm.rp.tcs[tb][kk][ln] = cs;
+      sm.st.rp.tcs[tb][kk][ln] = cs;
     }
-    for (int e = threadIdx.x; e < NKK * 64; e += 256) {
+    for (int e = threadIdx.x; !POS && e < NKK * 64; e += 256) {
       const int ln = e & 63, kk = e >> 6;
       f32x4 c4, s4;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float c, sn;
-        rot_turns(-(double)(4 * kTile) * sm.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
+        rot_turns(-(double)(4 * kTile) * sm.st.rp.turns[kk * 16 + (ln >> 4) * 4 + i], c, sn);
         c4[i] = c;
         s4[i] = sn;
       }
-      sm.rp.sc[kk][ln] = c4;
-      sm.rp.ss[kk][ln] = s4;
+      sm.st.rp.sc[kk][ln] = c4;
+      sm.st.rp.ss[kk][ln] = s4;
     }
     __syncthreads();
   }
@@ -351,26 +392,29 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
   int since_seed = 0;
 
   // SCORES: iterations staged so far, the tile of the first of them, and how many fit
-  static_assert(!(SCORES && ROPE), "the score-storing form is position-free");
+  static_assert(!(SCORES && ROPE && !POS), "the rotary score-storing form is built with explicit positions only");
   int stage_n = 0, stage_tile0 = cur.tile;
-  const int cur_sub_tokens = cur.sub * TOK;     // position-free form: a wave keeps its half of the tiles
-  const int stage_cap = SCORES ? kScoreStage / (G * TOK) : 0;        // G <= 16, TOK <= 64: at least 2
+  const int cur_sub_tokens = ROPE ? 0 : cur.sub * TOK;     // position-free form: a wave keeps its half of the tiles
+  // G <= 16, TOK <= 64: at least 2; the rotary form stages whole tiles (SUB iterations each)
+  const int stage_cap = SCORES ? (kScoreStage / (G * TOK)) / (ROPE ? SUB : 1) * (ROPE ? SUB : 1) : 0;
   auto flush_scores = [&]() {
     if constexpr (SCORES) {
       // staged order: [iteration f][head hd][TOK tokens]; iteration f of this wave is tile stage_tile0 + f * kStride
+      // (rotary form: tile stage_tile0 + (f / SUB) * kStride, part f % SUB of it)
       const int per_it = G * TOK, total = stage_n * per_it;
       float* rows = a.scores + ((int64_t)b * g.n_heads + (int64_t)kvh * G) * a.s_row + cur_sub_tokens;
       for (int i = lane * 4; i < total; i += 256) {
         const int f = i / per_it, r = i - f * per_it, hd = r / TOK, off = r - hd * TOK;
-        const f32x4 v = *reinterpret_cast<const f32x4*>(&sm.sc.s[wave][i]);
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(rows + (int64_t)hd * a.s_row + (stage_tile0 + f * kStride) * kTile + off));
+        const f32x4 v = *reinterpret_cast<const f32x4*>(&sm.st.sc.s[wave][i]);
+        const int first = ROPE ? (stage_tile0 + (f / SUB) * kStride) * kTile + (f % SUB) * TOK : (stage_tile0 + f * kStride) * kTile;
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(rows + (int64_t)hd * a.s_row + first + off));
       }
       stage_n = 0;
     }
   };
 
   // One iteration; kf holds the current keys, kf_free is the buffer the keys after the next go to.
-  auto iteration = [&](auto& kf, auto& kf_free) __attribute__((always_inline)) {
+  auto iteration = [&](auto& kf, auto& kf_free, auto& kp, auto& kp_free) __attribute__((always_inline)) {
     // ---- scores: S[tb] (16 tokens x 16 head columns) = K_block . q^T
     f32x4 s[TBN];
     // The rotation tables never change, so the compiler would keep all of them in registers across the
@@ -401,7 +445,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
         for (int tb = 0; tb < TBN; ++tb) up[0][tb] = up[1][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 u0 = sm.rp.uf[2 * kk][ks][tl], u1 = sm.rp.uf[2 * kk + 1][ks][tl];
+          const bf16x8 u0 = sm.st.rp.uf[2 * kk][ks][tl], u1 = sm.st.rp.uf[2 * kk + 1][ks][tl];
 #pragma unroll
           for (int tb = 0; tb < TBN; ++tb) {
             up[0][tb] = mfma16(u0, kf[tb][ks], up[0][tb]);
@@ -410,8 +454,25 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
         }
 #pragma unroll
         for (int tb = 0; tb < TBN; ++tb) {
-          const f16x8 cs = sm.rp.tcs[cur.sub * TBN + tb][kk][tl];
-          const f16x4 c4 = cs.lo, s4 = cs.hi;
+          f16x4 c4, s4;
+          if constexpr (POS) {
+            // angle of pair j at position p, in turns: p * (hi_j + lo_j).  p * hi_j is split exactly into its
+            // rounded value and the rounding error (fma), the whole turns leave with v_fract_f32
+            const float p = (float)kp[tb];
+            const f32x4 hi = sm.st.rp.thi[kk][tl >> 4], lo = sm.st.rp.tlo[kk][tl >> 4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float t = p * hi[i];
+              const float err = __builtin_fmaf(p, hi[i], -t);
+              const float f = __builtin_fmaf(p, lo[i], __builtin_amdgcn_fractf(t) + err);
+              c4[i] = (_Float16)__builtin_amdgcn_cosf(f);
+              s4[i] = (_Float16)__builtin_amdgcn_sinf(f);
+            }
+          } else {
+            const f16x8 cs = sm.st.rp.tcs[cur.sub * TBN + tb][kk][tl];
+            c4 = cs.lo;
+            s4 = cs.hi;
+          }
           const f16x4 x0 = __builtin_convertvector(up[0][tb], f16x4), x1 = __builtin_convertvector(up[1][tb], f16x4);
           const f16x4 r0 = x0 * c4 - x1 * s4, r1 = x0 * s4 + x1 * c4;
           const f16x8 kr = __builtin_shufflevector(r0, r1, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -423,7 +484,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
     if constexpr (SCORES) {
       // tokens past the sequence's end are never read back; a tile without a page must read as "no probability"
       if (col < G) {
-        float* dst = &sm.sc.s[wave][(stage_n * G + col) * TOK + quad * 4];
+        float* dst = &sm.st.sc.s[wave][(stage_n * G + col) * TOK + quad * 4];
         const float add = page >= 0 ? m_base : -INFINITY;
 #pragma unroll
         for (int tb = 0; tb < TBN; ++tb) *reinterpret_cast<f32x4*>(dst + tb * 16) = s[tb] + add;
@@ -438,11 +499,14 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       nn = advance(nxt);
       have_nn = have_n && nn.tile < t_end;
       page_nn = have_nn ? page_of(nn) : -1;
-      if (have_nn) load_k(nn, max(page_nn, 0), kf_free);
+      if (have_nn) {
+        load_k(nn, max(page_nn, 0), kf_free);
+        load_pos(nn, kp_free);
+      }
     } else {
       if (have_n) load_k(nxt, max(page_n, 0), kf_free);
     }
-    if constexpr (ROPE) {
+    if constexpr (ROPE && !POS) {
       if (have_n && nxt.sub == 0) {
         if (++since_seed == kReseed) {
           since_seed = 0;
@@ -532,24 +596,31 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
       page_n = have_n ? page_of(nxt) : -1;
     }
   };
-  if constexpr (KDB) {
-    while (have) {
-      iteration(kfA, kfA);       // scores from A, then A takes the keys two iterations ahead
-      if (!have) break;
-      iteration(kfB, kfB);
-    }
-  } else if constexpr (SCORES) {
-    while (have) {
-      iteration(kfA, kfA);
+  auto staged = [&]() {
+    if constexpr (SCORES) {
       if (++stage_n == stage_cap) {
         flush_scores();
         stage_tile0 = cur.tile;      // the iteration that comes next
       }
     }
-    if (stage_n > 0) flush_scores();
-    __syncthreads();                 // the staging buffers share their memory with the merge buffers
+  };
+  if constexpr (KDB) {
+    while (have) {
+      iteration(kfA, kfA, kpA, kpA);       // scores from A, then A takes the keys two iterations ahead
+      staged();
+      if (!have) break;
+      iteration(kfB, kfB, kpB, kpB);
+      staged();
+    }
   } else {
-    while (have) iteration(kfA, kfA);
+    while (have) {
+      iteration(kfA, kfA, kpA, kpA);
+      staged();
+    }
+  }
+  if constexpr (SCORES) {
+    if (stage_n > 0) flush_scores();
+    if constexpr (!ROPE) __syncthreads();   // the staging buffers share their memory with the merge buffers
   }
 
   // ---- merge the four waves of the workgroup
@@ -600,10 +671,10 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
 
 // The kernel: one workgroup per (kv head, split, sequence).  (The body is a function of its own because the
 // kernel over the 4-bit cache runs it, too, for the bfloat16 tail of the sequences.)
-template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false>
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false, bool POS = false>
 __global__ __launch_bounds__(256, WPE) void decode_bf16_kernel(DecodeArgs a) {
-  __shared__ DecodeSmem<KS, NCB, TBN, NKK, SCORES> sm;
-  decode_bf16_body<KS, NCB, TBN, WPE, NKK, ALIBI, SCORES>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, sm);
+  __shared__ DecodeSmem<KS, NCB, TBN, NKK, SCORES, POS> sm;
+  decode_bf16_body<KS, NCB, TBN, WPE, NKK, ALIBI, SCORES, POS>(a, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.z, sm);
 }
 
 }  // namespace ea

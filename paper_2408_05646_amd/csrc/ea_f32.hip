@@ -36,12 +36,14 @@ struct AlibiScore {
 // Score for models with rotary position embedding (Sec. 4.3, Eq. 10): the cached rank-r key is brought back to
 // d_head channels with the shared basis U^K, rotated to its position, and multiplied with the query rotated to
 // its own position.  Only the difference of the two positions enters, so the key pair is rotated by
-// (tok - pos_q) theta_j and the query is left as it is.
+// (tok - pos_q) theta_j and the query is left as it is.  After token pruning the key in slot tok is at position
+// slot_pos[tok] of the text instead of tok.
 struct RopeScore {
   const float* sq;      // the query's d_head channels, in LDS
   const float* u_k;     // [d_head, r_k]
   const double* theta;  // [d_head / 2], in LDS
   int r_k, d_head, pos_q;
+  const int32_t* slot_pos = nullptr;   // this sequence's row of positions, or null: slot t holds position t
   __device__ __forceinline__ float operator()(int tok, const float* __restrict__ krow) const {
     float dot = 0.f;
     for (int j = 0; j < d_head / 2; ++j) {
@@ -53,7 +55,7 @@ struct RopeScore {
         k1 = fmaf(u1[c], krow[c], k1);
       }
       // reduce the angle modulo 2 pi in double precision: positions reach 10^5 radians and more
-      const double x = (double)(tok - pos_q) * theta[j];
+      const double x = (double)((slot_pos ? slot_pos[tok] : tok) - pos_q) * theta[j];
       const double kq = rint(x * 0.15915494309189535);
       double r = fma(-kq, 6.283185307179586, x);
       r = fma(-kq, 2.4492935982947064e-16, r);
@@ -140,6 +142,10 @@ struct AttnF32Args {
   double log2_base;
   // ALiBi variant only
   const float* alibi;
+  // rotary variant over a pruned cache: positions of the cached tokens [B, pos_stride] and of the queries [B], or null
+  const int32_t* slot_pos = nullptr;
+  const int32_t* q_pos = nullptr;
+  int32_t pos_stride = 0;
 };
 
 __device__ __forceinline__ int clamp_len(const AttnF32Args& a, int b) {
@@ -179,8 +185,10 @@ __global__ __launch_bounds__(256) void decode_f32_kernel(AttnF32Args a) {
     if (threadIdx.x < a.d_head / 2)
       theta[threadIdx.x] = exp2(-(2.0 * (double)threadIdx.x / (double)a.d_head) * a.log2_base);
     __syncthreads();
-    attend_f32(RopeScore{sq, a.u_k, theta, g.r_k, a.d_head, n - 1}, a.k_pool, a.v_pool,
-               a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m, l, acc);
+    attend_f32(RopeScore{sq, a.u_k, theta, g.r_k, a.d_head, a.q_pos ? a.q_pos[b] : n - 1,
+                         a.slot_pos ? a.slot_pos + (int64_t)b * a.pos_stride : nullptr},
+               a.k_pool, a.v_pool, a.page_table + (int64_t)b * g.max_pages, g, kvh, tok_begin, tok_end, a.scale_log2, m,
+               l, acc);
   }
   const int c = threadIdx.x;
   if (a.n_splits == 1) {
@@ -269,6 +277,22 @@ int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const 
   AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
   a.u_k = u_k;
   a.log2_base = log2(rope_base);
+  decode_f32_kernel<1><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
+  return launch_status();
+}
+
+int decode_rope_pos_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
+                        const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                        const int32_t* slot_pos, int32_t pos_stride, const int32_t* q_pos, float* out, int32_t B,
+                        int32_t n_splits, float* ws, hipStream_t st) {
+  if (B > 65535 || g.n_heads > 65535) return EA_ERR_SHAPE;
+  if (d->d_head > 256 || d->d_head % 2 != 0) return EA_ERR_SHAPE;
+  AttnF32Args a = make_args(d, g, q, k_pool, v_pool, page_table, seq_len, out, ws, n_splits, 1);
+  a.u_k = u_k;
+  a.log2_base = log2(rope_base);
+  a.slot_pos = slot_pos;
+  a.q_pos = q_pos;
+  a.pos_stride = pos_stride;
   decode_f32_kernel<1><<<dim3(n_splits, g.n_heads, B), dim3(256), 0, st>>>(a);
   return launch_status();
 }

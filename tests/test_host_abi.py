@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 42
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 44
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -407,3 +407,27 @@ def test_decode_attn_mass_rejects_bad_arguments_before_launching():
     assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
     assert call(dd=desc(H=34, Hkv=2, d=34 * 128)) == -2
     assert ea.decode_attn_mass_workspace_bytes(d, 2, 4, 0) == -1           # the size depends on the split count
+
+
+def test_rotary_entry_points_with_explicit_positions_reject_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def call(dd=d, q=OK_PTR, u=OK_PTR, base=10000.0, pos=OK_PTR, stride=4 * 128, qpos=OK_PTR, out=OK_PTR, mass=False,
+             B=2, max_pages=4, pool=8, S=1, ws=OK_PTR, ws_bytes=1 << 30):
+        if mass is False:
+            return lib.ea_decode_attn_rope_pos(ctypes.byref(dd), q, u, base, OK_PTR, OK_PTR, OK_PTR, OK_PTR, pos, stride,
+                                               qpos, out, B, max_pages, pool, S, ws, ws_bytes, None)
+        return lib.ea_decode_attn_mass_rope_pos(ctypes.byref(dd), q, u, base, OK_PTR, OK_PTR, OK_PTR, OK_PTR, pos, stride,
+                                                qpos, out, mass, B, max_pages, pool, S, ws, ws_bytes, None)
+
+    for m in (False, OK_PTR):
+        assert call(q=None, mass=m) == -1 and call(pos=None, mass=m) == -1 and call(qpos=None, mass=m) == -1
+        assert call(base=1.0, mass=m) == -1 and call(B=0, mass=m) == -1 and call(S=1025, mass=m) == -1
+        assert call(stride=4 * 128 - 1, mass=m) == -1                       # shorter than the page table's capacity
+        assert call(q=ODD_PTR, mass=m) == -3 and call(pos=0x10002, mass=m) == -3 and call(qpos=0x10002, mass=m) == -3   # int32 arrays: 4-byte aligned
+        assert call(dd=desc(d_h=96, r_k=80), mass=m) == -2
+    assert call(S=2, ws=None) == -4 and call(S=2, ws_bytes=ea.decode_workspace_bytes(d, 2, 2) - 1) == -4
+    assert call(mass=None) == -1 and call(mass=ODD_PTR) == -3
+    assert call(mass=OK_PTR, ws=None) == -4
+    assert call(mass=OK_PTR, S=2, ws_bytes=ea.decode_attn_mass_workspace_bytes(d, 2, 4, 2) - 1) == -4
+    assert call(mass=OK_PTR, dd=desc(dtype=ea.EA_F32, P=64)) == -2         # the statistic: bf16 layers only
