@@ -25,10 +25,11 @@ The reading:
   * code = clip(rint((x - zero) / scale), 0, 15) with x, zero, scale as float32, IEEE division, round half
     to even: the integer decision is taken in float32 on both sides of the parity tests.
   * value = scale * code + zero (evaluated in float64 here).
-  * keys: groups of 64 consecutive tokens per channel (token 64 g .. 64 g + 63 of a sequence);
+  * keys: groups of 64 consecutive tokens per channel (token 64 g .. 64 g + 63 of a sequence), or -- the
+    group size of the appendix table's 4-bit Eigen Attention rows -- of 128 (group_tokens = 128);
     values: one group per token over all r_v channels.
-  * only whole groups of 64 tokens are quantised; the newest tokens of a sequence stay in the 16-bit cache
-    until their group is complete (the key groups need all 64 tokens before a scale exists).
+  * only whole key groups are quantised; the newest tokens of a sequence stay in the 16-bit cache
+    until their group is complete (the key groups need all their tokens before a scale exists).
 """
 from __future__ import annotations
 
@@ -60,12 +61,12 @@ def _codes(x, scale, zero):
     return np.clip(q, 0, LEVELS).astype(np.uint8)
 
 
-def quantize_keys(K):
-    """K [n, r] (n a multiple of 64) -> codes uint8 [n, r], scale fp16 [n/64, r], zero fp16 [n/64, r]:
-    one scale per channel and group of 64 tokens."""
+def quantize_keys(K, group_tokens: int = GROUP_TOKENS):
+    """K [n, r] (n a multiple of the group) -> codes uint8 [n, r], scale fp16 [n/group, r], zero fp16 [n/group, r]:
+    one scale per channel and group of `group_tokens` consecutive tokens."""
     n, r = K.shape
-    assert n % GROUP_TOKENS == 0
-    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)
+    assert n % group_tokens == 0
+    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)
     scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1))
     codes = _codes(Kg, scale[:, None, :], zero[:, None, :]).reshape(n, r)
     return codes, scale, zero
@@ -80,7 +81,8 @@ def quantize_values(V):
 
 def dequantize_keys(codes, scale, zero):
     n, r = codes.shape
-    c = codes.astype(np.float64).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)
+    group_tokens = n // scale.shape[0]                     # the scales say how long a group is
+    c = codes.astype(np.float64).reshape(n // group_tokens, group_tokens, r)
     return (scale.astype(np.float64)[:, None, :] * c + zero.astype(np.float64)[:, None, :]).reshape(n, r)
 
 
@@ -88,15 +90,15 @@ def dequantize_values(codes, scale, zero):
     return scale.astype(np.float64)[:, None] * codes.astype(np.float64) + zero.astype(np.float64)[:, None]
 
 
-def quantized_view(K, V, n_quant: int):
-    """The cache as attention sees it when its first n_quant tokens (a multiple of 64) are held in 4 bits:
-    K [H_kv, n, r_k], V [H_kv, n, r_v] -> arrays of the same shapes, the prefix replaced by its
+def quantized_view(K, V, n_quant: int, group_tokens: int = GROUP_TOKENS):
+    """The cache as attention sees it when its first n_quant tokens (a multiple of the key group) are held in 4
+    bits: K [H_kv, n, r_k], V [H_kv, n, r_v] -> arrays of the same shapes, the prefix replaced by its
     quantise-dequantise round trip, the rest untouched."""
-    assert n_quant % GROUP_TOKENS == 0 and n_quant <= K.shape[1]
+    assert n_quant % group_tokens == 0 and n_quant <= K.shape[1]
     Kq, Vq = np.array(K, dtype=np.float64), np.array(V, dtype=np.float64)
     for h in range(K.shape[0]):
         if n_quant:
-            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant]))
+            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens))
             Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant]))
     return Kq, Vq
 
@@ -112,27 +114,29 @@ def quantized_cache_bytes(n_elements, bits: int, group: int, meta_bits_per_group
     return n_elements * (bits + meta_bits_per_group / group) / 8.0
 
 
-def bits_per_element_q4(r_k: int, r_v: int):
-    """Bits per cached scalar of this build's 4-bit format, without layout padding: keys in groups of 64 tokens,
-    values in groups of r_v channels, 32 bits of metadata (fp16 scale, fp16 zero) per group."""
-    return 4 + 32 / GROUP_TOKENS, 4 + 32 / r_v
+def bits_per_element_q4(r_k: int, r_v: int, group_tokens: int = GROUP_TOKENS):
+    """Bits per cached scalar of this build's 4-bit format, without layout padding: keys in groups of 64 (or 128)
+    tokens, values in groups of r_v channels, 32 bits of metadata (fp16 scale, fp16 zero) per group."""
+    return 4 + 32 / group_tokens, 4 + 32 / r_v
 
 
-def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_slopes=None):
+def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_slopes=None,
+                               group_tokens: int = GROUP_TOKENS):
     """Generation-phase attention (Eq. 3 in the rank-r space) of one new token per sequence over a cache whose
     first n_quant[b] tokens are quantised: plain attention over the dequantised values (with the ALiBi bias of the
     MPT models when slopes are given: it involves positions only, so quantisation does not touch it).
     q_r [B, H, r_k]; K_list[b] [H_kv, n_b, r_k]; V_list[b] [H_kv, n_b, r_v]."""
-    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
     return ea_oracle.decode_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)
 
 
-def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0):
+def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0,
+                                    group_tokens: int = GROUP_TOKENS):
     """The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10): the cached rank-r keys (of the one
     shared basis Uk) are quantised BEFORE they are brought back to d_head channels and rotated, so this is the
     rotary generation-phase attention over the dequantised rank-r keys and values.
     q [B, H, d_head] (not rotated); the rest as decode_attention_quantized."""
-    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b])) for b in range(len(K_list))]
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
     return ea_oracle.decode_attention_rope(q, cache, Uk, d_head, base)

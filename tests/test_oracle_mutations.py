@@ -115,6 +115,12 @@ QUANT = [
      "test_rounding_is_to_nearest_not_truncation"),
     ("seventeen levels", "LEVELS = 15 ", "LEVELS = 16 ", "test_values_on_the_grid_round_trip_exactly"),
     ("key groups of 32 tokens", "GROUP_TOKENS = 64", "GROUP_TOKENS = 32", "test_key_groups_are_64_tokens_long"),
+    ("the key quantiser ignores the group length it is given",
+     "    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)",
+     "    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)", "test_key_groups_of_128_tokens"),
+    ("the view of a partly quantised cache ignores the group length",
+     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens))",
+     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant]))", "test_key_groups_of_128_tokens"),
     ("zero point at the group's maximum",
      "    return step.astype(np.float16), lo.astype(np.float16)", "    return step.astype(np.float16), hi.astype(np.float16)",
      "test_values_on_the_grid_round_trip_exactly"),
