@@ -61,6 +61,8 @@ typedef struct ea_layer_desc {
   int32_t r_v;
   int32_t dtype;         /* EA_F32 or EA_BF16                                      */
   int32_t page_tokens;   /* tokens per cache page: multiple of 64 (EA_BF16), of 16 (EA_F32) */
+  int32_t q4_key_group;  /* 4-bit cache only: tokens that share a key scale, 64 (also meant by 0) or 128;
+                            with 128, page_tokens must be a multiple of 128.  Ignored by every other call. */
 } ea_layer_desc;
 
 /* Geometry of the two page pools of a layer (K and V are separate pools, page p
@@ -303,31 +305,36 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
 
 /* The paper combines the rank-r cache with integer group quantisation: keys per
  * channel, values per token (as in KIVI and KV-Quant), precisions of 3-4 bits in
- * groups of 16-128.  This library implements one point of that family, EA_BF16
+ * groups of 16-128.  This library implements two points of that family, EA_BF16
  * layers only: 4 bits; a key scale covers one channel over the 64 tokens of a cache
- * tile, a value scale covers one token over its r_v channels.  The paper gives no
+ * tile or (desc.q4_key_group = 128, the group size of the paper's 4-bit rows) over the
+ * 128 tokens of two neighbouring tiles; a value scale covers one token over its r_v
+ * channels.  3-bit codes are NOT implemented.  The paper gives no
  * rounding rule; the one used here is
  *   zero = fp16(lo), scale = fp16((hi - lo) / 15)   (lo / hi = minimum / maximum of
  *          the group, clamped to +-65504; quotient in float),
  *   code = clip(rint((x - zero) / scale), 0, 15) in float (round half to even), code 0
  *          when the scale is 0,
  *   value = scale * code + zero.
- * Only whole pages are quantised (a key group needs its 64 tokens); the newest tokens
+ * Only whole pages are quantised (a key group needs all its tokens); the newest tokens
  * of a sequence stay in the bfloat16 pools, and ea_decode_attn_q4 attends both parts.
  *
  * The 4-bit pools mirror the bfloat16 ones: page p of a pool starts at byte
  * p * k_page_bytes (v_page_bytes); inside a page kv head after kv head, tile after
  * tile, one tile block per (kv head, 64 tokens).  A tile block holds the codes in the
- * order the matrix cores consume them, then the fp16 scales and zeros;
+ * order the matrix cores consume them, then the fp16 scales and zeros; with key groups
+ * of 128 tokens only the first K tile block of every pair carries scales (they are the
+ * pair's) and the second one is codes only.
  * ea_q4_k_code_pos and its siblings are the reference of the positions.  The scale
  * and zero slots of padding channels (r_k .. the next multiple of 32) are written as 0
  * by the quantiser; whoever fills the pools by other means must leave finite values there. */
 typedef struct ea_q4_layout {
   int32_t r_k_pad;         /* multiple of 8  */
   int32_t r_v_pad;         /* multiple of 16 */
-  int64_t k_tile_bytes;    /* 32 * r_k_pad + 128 * ceil(r_k_pad / 32) */
+  int64_t k_tile_bytes;    /* of a K tile block WITH scales: 32 * r_k_pad + 128 * ceil(r_k_pad / 32) */
   int64_t v_tile_bytes;    /* 32 * r_v_pad + 256                      */
-  int64_t k_page_bytes;    /* n_kv_heads * (page_tokens / 64) * k_tile_bytes */
+  int64_t k_page_bytes;    /* n_kv_heads * (page_tokens / 64) * k_tile_bytes with key groups of 64 tokens; with 128,
+                              every second tile block is 128 * ceil(r_k_pad / 32) bytes shorter */
   int64_t v_page_bytes;
 } ea_q4_layout;
 

@@ -48,8 +48,9 @@ class EigenAttnError(RuntimeError):
 
 
 class LayerDesc(ctypes.Structure):
+    # q4_key_group (last, optional): tokens that share a key scale in the 4-bit cache, 64 (also meant by 0) or 128
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("d_model", "n_heads", "n_kv_heads", "d_head", "r_k", "r_v", "dtype", "page_tokens")]
+                ("d_model", "n_heads", "n_kv_heads", "d_head", "r_k", "r_v", "dtype", "page_tokens", "q4_key_group")]
 
     def __repr__(self):
         return "LayerDesc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"

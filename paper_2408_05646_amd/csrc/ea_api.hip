@@ -5,7 +5,7 @@ using namespace ea;
 
 extern "C" {
 
-int ea_version(void) { return 100; }
+int ea_version(void) { return 101; }
 
 const char* ea_strerror(int code) {
   switch (code) {

@@ -10,7 +10,7 @@ static int validate_q4(const ea_layer_desc* desc) {
 }
 
 static Q4Geo q4_geo_of(const ea_layer_desc* desc) {
-  return make_q4_geo(desc->r_k, desc->r_v, desc->n_kv_heads, desc->page_tokens);
+  return make_q4_geo(desc->r_k, desc->r_v, desc->n_kv_heads, desc->page_tokens, desc->q4_key_group);
 }
 
 static bool q4_pos_args_ok(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
@@ -21,7 +21,7 @@ static bool q4_pos_args_ok(const ea_layer_desc* desc, int32_t page, int32_t kv_h
 }
 
 static int64_t k_tile0(const Q4Geo& q, int32_t page, int32_t kv_head, int32_t token_in_page) {
-  return (int64_t)page * q.k_page + ((int64_t)kv_head * q.tiles_per_page + token_in_page / kTile) * q.k_tile;
+  return (int64_t)page * q.k_page + (int64_t)kv_head * q.k_slab + q4_k_tile_off(q, token_in_page / kTile);
 }
 static int64_t v_tile0(const Q4Geo& q, int32_t page, int32_t kv_head, int32_t token_in_page) {
   return (int64_t)page * q.v_page + ((int64_t)kv_head * q.tiles_per_page + token_in_page / kTile) * q.v_tile;
@@ -55,7 +55,8 @@ int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_he
                           int32_t channel) {
   if (!q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true)) return -1;
   const Q4Geo q = q4_geo_of(desc);
-  return k_tile0(q, page, kv_head, token_in_page) + q4_k_scale_off(q, channel);
+  return (int64_t)page * q.k_page + (int64_t)kv_head * q.k_slab + q4_k_group_scales_off(q, token_in_page / kTile) +
+         q4_k_scale_off(channel);
 }
 
 int64_t ea_q4_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,

@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
   const int64_t cap = (int64_t)g.max_pages * g.page_tokens;
   if (n64 > cap) n64 = cap;
   if (n64 < 0) n64 = 0;
-  const int n_tiles = (int)(n64 / kTile);
+  const int n_tiles = (int)(n64 / (kTile * qg.tpg)) * qg.tpg;      // whole key groups only
   const int per = (n_tiles + a.n_splits - 1) / a.n_splits;
   const int t_begin = split * per;
   const int t_end = min(n_tiles, t_begin + per);
@@ -163,14 +163,16 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
     return (page >= 0 && page < g.pool_pages) ? page : -1;
   };
   auto load_k = [&](const Pos& p, int page) {
-    const uint8_t* base = a.kq_pool + (int64_t)page * qg.k_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.k_tile;
+    const uint8_t* slab = a.kq_pool + (int64_t)page * qg.k_page + (int64_t)kvh * qg.k_slab;
+    const uint8_t* base = slab + q4_k_tile_off(qg, p.tin);
+    const uint8_t* scales = slab + q4_k_group_scales_off(qg, p.tin);     // of the tile's key group
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       // lanes of a quad the last k-step does not have re-read quad 0's unit; the basis is zero in their channels
       const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
       const int off = kk * 1024 + (past ? col : lane) * 16;
       kc[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
-      const uint8_t* sp = base + qg.nch * 256 + (kk * 4 + quad) * 32;
+      const uint8_t* sp = scales + (kk * 4 + quad) * 32;
       ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
       kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
     }

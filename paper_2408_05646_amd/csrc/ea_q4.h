@@ -1,5 +1,6 @@
-// The 4-bit group-quantised form of the rank-r cache (keys per channel over the 64 tokens of a tile, values
-// per token; results paragraph on quantisation): geometry and the position of every code and scale.
+// The 4-bit group-quantised form of the rank-r cache (keys per channel over the 64 tokens of a tile -- or over the
+// 128 tokens of two neighbouring tiles --, values per token; results paragraph on quantisation): geometry and the
+// position of every code and scale.
 //
 // A page of the 4-bit pools holds the same tokens as a page of the bfloat16 pools: kv head after kv head,
 // tile after tile; one tile block is 64 tokens of one kv head.
@@ -15,6 +16,9 @@
 //           unit p = (cb = 2p, u = 0), (2p, 1), (2p+1, 0), (2p+1, 1); an odd last cb has 8-byte units.
 //                                                             -> 64 * r_v_pad / 2 bytes
 //   scales: [scale, zero][u][quad][8 token slots] fp16.       -> 256 bytes
+// Key groups of 128 tokens (tpg = 2 tiles per group): the tile blocks of a kv head still follow each other, but only
+// the first block of every pair carries scales -- the pair's -- and the second is codes only:
+//   [codes 0][scales 0+1][codes 1] [codes 2][scales 2+3][codes 3] ...
 // Inside a dword, element e (channel / token slot e of the 8) sits in nibble e/2 if e is even, 4 + e/2 if odd:
 // the kernel's unpacking puts nibbles i and i+4 into the two halves of one register.
 #pragma once
@@ -27,21 +31,39 @@ struct Q4Geo {
   int32_t ks;              // 32-channel k-steps: ceil(nch / 4)
   int32_t ncb;             // 16-channel blocks of a value row: r_v_pad / 16
   int32_t tiles_per_page;
-  int64_t k_tile, v_tile;  // bytes of a tile block
+  int32_t tpg;             // tiles per key group: 1 (64 tokens) or 2 (128 tokens)
+  int32_t k_codes;         // bytes of the codes of a K tile block: nch * 256
+  int32_t k_scales;        // bytes of the scales and zeros of a key group: ks * 128
+  int64_t k_tile, v_tile;  // bytes of a tile block (K: of one that carries scales)
+  int64_t k_slab;          // bytes of the K tile blocks of one kv head in a page
   int64_t k_page, v_page;  // bytes of a page (all kv heads)
 };
 
-__host__ __device__ inline Q4Geo make_q4_geo(int32_t r_k, int32_t r_v, int32_t n_kv_heads, int32_t page_tokens) {
+__host__ __device__ inline Q4Geo make_q4_geo(int32_t r_k, int32_t r_v, int32_t n_kv_heads, int32_t page_tokens,
+                                             int32_t key_group) {
   Q4Geo q;
   q.nch = (r_k + 7) / 8;
   q.ks = (q.nch + 3) / 4;
   q.ncb = (r_v + 15) / 16;
   q.tiles_per_page = page_tokens / kTile;
-  q.k_tile = (int64_t)q.nch * 256 + (int64_t)q.ks * 128;
+  q.tpg = key_group == 128 ? 2 : 1;
+  q.k_codes = q.nch * 256;
+  q.k_scales = q.ks * 128;
+  q.k_tile = (int64_t)q.k_codes + q.k_scales;
   q.v_tile = (int64_t)q.ncb * 512 + 256;
-  q.k_page = q.k_tile * q.tiles_per_page * n_kv_heads;
+  q.k_slab = (int64_t)q.tiles_per_page * q.k_codes + (int64_t)(q.tiles_per_page / q.tpg) * q.k_scales;
+  q.k_page = q.k_slab * n_kv_heads;
   q.v_page = q.v_tile * q.tiles_per_page * n_kv_heads;
   return q;
+}
+
+// Byte offset, inside a kv head's part of a K page, of tile `tin`'s block, and of the scales that belong to it
+// (those of its group: right behind the codes of the group's first tile).
+__host__ __device__ inline int64_t q4_k_tile_off(const Q4Geo& q, int32_t tin) {
+  return (int64_t)tin * q.k_codes + (int64_t)((tin + q.tpg - 1) / q.tpg) * q.k_scales;
+}
+__host__ __device__ inline int64_t q4_k_group_scales_off(const Q4Geo& q, int32_t tin) {
+  return q4_k_tile_off(q, tin - tin % q.tpg) + q.k_codes;
 }
 
 __host__ __device__ inline int32_t q4_nibble_shift(int32_t e) { return 4 * ((e & 1) ? 4 + (e >> 1) : (e >> 1)); }
@@ -51,8 +73,9 @@ __host__ __device__ inline int32_t q4_k_dword_off(int32_t tt, int32_t c) {
   const int32_t kk = c >> 5, quad = (c >> 3) & 3, tb = tt >> 4, t = tt & 15;
   return kk * 1024 + (quad * 16 + t) * 16 + tb * 4;
 }
-__host__ __device__ inline int32_t q4_k_scale_off(const Q4Geo& q, int32_t c) {
-  return q.nch * 256 + ((c >> 5) * 4 + ((c >> 3) & 3)) * 32 + (c & 7) * 2;       // the zero is 16 bytes further
+// Byte offset inside a group's block of scales of channel c's scale; the zero is 16 bytes further.
+__host__ __device__ inline int32_t q4_k_scale_off(int32_t c) {
+  return ((c >> 5) * 4 + ((c >> 3) & 3)) * 32 + (c & 7) * 2;
 }
 // Byte offset inside a V tile block of the dword holding (token tt, channel c), and the element slot of the token.
 __host__ __device__ inline int32_t q4_v_dword_off(const Q4Geo& q, int32_t tt, int32_t c, int32_t* slot) {

@@ -1,5 +1,5 @@
 // Quantises whole pages of the bfloat16 rank-r cache to the 4-bit group form (keys: one scale per channel and
-// 64-token tile; values: one scale per token).  A group with minimum lo and maximum hi gets
+// 64-token tile, or per pair of tiles; values: one scale per token).  A group with minimum lo and maximum hi gets
 // zero = fp16(lo), scale = fp16((hi - lo) / 15) and codes clip(rint((x - zero) / scale), 0, 15), all in float;
 // a scale that rounds to 0 gives code 0.  Not a hot kernel: it runs once per page, when the page is full.
 #include "ea_q4.h"
@@ -45,24 +45,40 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
 
   // ---- keys: x[token][channel] <- the tile in its fragment order [4 blocks][nch chunks][16 tokens][8 channels]
   {
-    const uint16_t* kb = a.k_pool + (int64_t)src * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tile * (kTile * g.r_k_pad);
-    for (int u = tid; u < kTile * qg.nch; u += 256) {           // 16-byte units: 8 channels of one token
-      const int t = u & 15, rest = u >> 4;
-      const int chunk = rest % qg.nch, tb = rest / qg.nch;
-      const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (u << 3));
-      float* dst = &x[tb * 16 + t][chunk * 8];
+    auto load_tile = [&](int tl) {
+      const uint16_t* kb = a.k_pool + (int64_t)src * g.k_page + (int64_t)kvh * g.k_slab + (int64_t)tl * (kTile * g.r_k_pad);
+      for (int u = tid; u < kTile * qg.nch; u += 256) {           // 16-byte units: 8 channels of one token
+        const int t = u & 15, rest = u >> 4;
+        const int chunk = rest % qg.nch, tb = rest / qg.nch;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(kb + (u << 3));
+        float* dst = &x[tb * 16 + t][chunk * 8];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        dst[2 * p] = __builtin_bit_cast(float, w[p] << 16);
-        dst[2 * p + 1] = __builtin_bit_cast(float, w[p] & 0xffff0000u);
+        for (int p = 0; p < 4; ++p) {
+          dst[2 * p] = __builtin_bit_cast(float, w[p] << 16);
+          dst[2 * p + 1] = __builtin_bit_cast(float, w[p] & 0xffff0000u);
+        }
       }
+    };
+    // A key group of two tiles: this workgroup quantises its own tile, but the extremes are the pair's, so it first
+    // looks at the other tile of the pair (a second read of it; this kernel runs once per page).
+    float lo = INFINITY, hi = -INFINITY;
+    if (qg.tpg == 2) {
+      load_tile(tile ^ 1);
+      __syncthreads();
+      if (tid < g.r_k) {
+        for (int t = 0; t < kTile; ++t) {
+          lo = fminf(lo, x[t][tid]);
+          hi = fmaxf(hi, x[t][tid]);
+        }
+      }
+      __syncthreads();
     }
+    load_tile(tile);
     __syncthreads();
     if (tid < 128) {
       _Float16 s = (_Float16)0.f, z = (_Float16)0.f;
       if (tid < g.r_k) {
-        float lo = x[0][tid], hi = lo;
-        for (int t = 1; t < kTile; ++t) {
+        for (int t = 0; t < kTile; ++t) {
           lo = fminf(lo, x[t][tid]);
           hi = fmaxf(hi, x[t][tid]);
         }
@@ -72,11 +88,15 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
       zr[tid] = (float)z;
     }
     __syncthreads();
-    uint8_t* ko = a.kq_pool + (int64_t)dst * qg.k_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.k_tile;
-    for (int c = tid; c < qg.ks * 32; c += 256) {
-      _Float16* p = reinterpret_cast<_Float16*>(ko + q4_k_scale_off(qg, c));
-      p[0] = (_Float16)sc[c];
-      p[8] = (_Float16)zr[c];
+    uint8_t* slab = a.kq_pool + (int64_t)dst * qg.k_page + (int64_t)kvh * qg.k_slab;
+    uint8_t* ko = slab + q4_k_tile_off(qg, tile);
+    if (tile % qg.tpg == 0) {                                   // the group's first tile carries the scales
+      uint8_t* so = slab + q4_k_group_scales_off(qg, tile);
+      for (int c = tid; c < qg.ks * 32; c += 256) {
+        _Float16* p = reinterpret_cast<_Float16*>(so + q4_k_scale_off(c));
+        p[0] = (_Float16)sc[c];
+        p[8] = (_Float16)zr[c];
+      }
     }
     for (int e = tid; e < qg.nch * 64; e += 256) {
       const int tb = e & 3, t = (e >> 2) & 15, chunk = e >> 6;
@@ -147,7 +167,9 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
   const int src = a.src_pages[blockIdx.z], dst = a.dst_pages[blockIdx.z];      // src: 4-bit page, dst: bfloat16 page
   if (src < 0 || src >= a.q4_pool_pages || dst < 0 || dst >= g.pool_pages) return;
   const int tid = threadIdx.x;
-  const uint8_t* kb = a.kq_pool + (int64_t)src * qg.k_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.k_tile;
+  const uint8_t* k_slab = a.kq_pool + (int64_t)src * qg.k_page + (int64_t)kvh * qg.k_slab;
+  const uint8_t* kb = k_slab + q4_k_tile_off(qg, tile);
+  const uint8_t* ks_grp = k_slab + q4_k_group_scales_off(qg, tile);
   const uint8_t* vb = a.vq_pool + (int64_t)src * qg.v_page + ((int64_t)kvh * qg.tiles_per_page + tile) * qg.v_tile;
   uint16_t* ko = const_cast<uint16_t*>(a.k_pool) + (int64_t)dst * g.k_page + (int64_t)kvh * g.k_slab;
   uint16_t* vo = const_cast<uint16_t*>(a.v_pool) + (int64_t)dst * g.v_page + (int64_t)kvh * g.v_slab;
@@ -163,7 +185,7 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     const int chunk = rest % qg.nch, tb = rest / qg.nch;
     const int tt = tb * 16 + t, c0 = chunk * 8;
     const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c0));
-    const _Float16* sp = reinterpret_cast<const _Float16*>(kb + q4_k_scale_off(qg, c0));
+    const _Float16* sp = reinterpret_cast<const _Float16*>(ks_grp + q4_k_scale_off(c0));
     float val[8];
 #pragma unroll
     for (int ce = 0; ce < 8; ++ce)

@@ -638,3 +638,154 @@ def test_every_rank_shape_of_the_q4_kernels(rope):
                 ref = oracle_q4(desc, K, V, q, n_quant)
             worst = max(worst, assert_close(got, ref, TOL_BF16, f"q4 shapes r=({r_k},{r_v})"))
     print(f"  worst rel-L2 {worst:.2e}", flush=True)
+
+
+# ---------------------------------------------------------------------------
+# Key groups of 128 tokens (desc.q4_key_group = 128: the group size of the paper's 4-bit rows)
+# ---------------------------------------------------------------------------
+def desc128(H, Hkv, d_h, r_k, r_v, P):
+    d = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P)
+    d.q4_key_group = 128
+    return d
+
+
+def loud_cache(desc, lens, g, factor=20.0):
+    """offset_cache with a stretch of 64 loud tokens in every other 128-token group of kv head 0: what makes
+    64- and 128-token key groups give different codes."""
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    for b, n in enumerate(lens):
+        for t0 in range(64, n - 63, 256):
+            K[b][0, t0:t0 + 64] = quantize(desc, K[b][0, t0:t0 + 64] * factor)
+    return K, V
+
+
+@pytest.mark.parametrize("Hkv,r_k,r_v,P,lens,n_quant", [
+    (2, 80, 80, 128, [300, 128], [256, 128]),
+    (1, 30, 33, 256, [600], [512]),
+    (2, 128, 16, 384, [384], [384]),
+])
+def test_quantize_pages_key_group_128_bit_exact(Hkv, r_k, r_v, P, lens, n_quant):
+    """Codes, scales and zeros against the oracle's quantiser with 128-token key groups, every position taken from
+    the library's reference functions; the value side is what it is with 64-token key groups."""
+    print(f"q4 quantize, key group 128: Hkv={Hkv} r=({r_k},{r_v}) P={P} lens={lens}", flush=True)
+    desc = desc128(Hkv, Hkv, 128, r_k, r_v, P)
+    g = synth.rng(141, r_k, P)
+    K, V = loud_cache(desc, lens, g)
+    K[0][0, :128, 0] = 0.75                      # a constant group: scale 0
+    qc = Q4Cache(desc, K, V, n_quant, g, poison_sources=False)
+    lay = ea.q4_layout_query(desc)
+    kq = qc.kq.cpu().numpy().reshape(-1)
+    vq = qc.vq.cpu().numpy().reshape(-1)
+    # positions inside page 0 of kv head 0; other pages and heads are whole strides further
+    kc = np.array([[ea.q4_k_code_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(P)])
+    ks = np.array([[ea.q4_k_scale_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(0, P, 128)])
+    vc = np.array([[ea.q4_v_code_pos(desc, 0, 0, t, c) for c in range(r_v)] for t in range(P)])
+    vs = np.array([ea.q4_v_scale_pos(desc, 0, 0, t) for t in range(P)])
+    k_slab, v_slab = lay.k_page_bytes // Hkv, lay.v_page_bytes // Hkv
+    assert ea.q4_k_code_pos(desc, 3, Hkv - 1, 0, 0) == (3 * lay.k_page_bytes + (Hkv - 1) * k_slab) * 8 + kc[0, 0]
+    for b in range(len(lens)):
+        for kvh in range(Hkv):
+            ck, sk, zk = oq.quantize_keys(K[b][kvh, :n_quant[b]], 128)
+            cv, sv, zv = oq.quantize_values(V[b][kvh, :n_quant[b]])
+            for p in range(n_quant[b] // P):
+                page = int(qc.q4_table_host[b, p])
+                k0, v0 = page * lay.k_page_bytes + kvh * k_slab, page * lay.v_page_bytes + kvh * v_slab
+                where = f"b={b} kvh={kvh} page {p}"
+                assert np.array_equal(read_codes(kq, kc + 8 * k0), ck[p * P:(p + 1) * P]), f"key codes {where}"
+                grp = slice(p * P // 128, (p + 1) * P // 128)
+                assert np.array_equal(read_f16(kq, ks + k0).view(np.uint16), sk[grp].view(np.uint16)), f"key scales {where}"
+                assert np.array_equal(read_f16(kq, ks + k0 + 16).view(np.uint16), zk[grp].view(np.uint16)), f"key zeros {where}"
+                assert np.array_equal(read_codes(vq, vc + 8 * v0), cv[p * P:(p + 1) * P]), f"value codes {where}"
+                assert np.array_equal(read_f16(vq, vs + v0).view(np.uint16), sv[p * P:(p + 1) * P].view(np.uint16))
+                assert np.array_equal(read_f16(vq, vs + v0 + 128).view(np.uint16), zv[p * P:(p + 1) * P].view(np.uint16))
+    # the group length is really 128: with 64-token groups the loud stretches would have scales of their own
+    assert not np.array_equal(oq.quantize_keys(K[0][0, :n_quant[0]], 64)[0], oq.quantize_keys(K[0][0, :n_quant[0]], 128)[0])
+
+
+@pytest.mark.parametrize("form", ["plain", "alibi", "rope"])
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,lens,n_quant,n_splits", [
+    (2, 2, 80, 80, 128, [300, 130, 128], [256, 128, 128], 1),      # the last sequence has no 16-bit part
+    (8, 2, 48, 112, 128, [777, 1500], [768, 1408], 0),             # GQA 4:1, r_k != r_v
+    (4, 4, 128, 128, 256, [1100, 300], [1024, 256], 3),            # full rank, two groups per page
+    (4, 2, 30, 33, 128, [150, 400], [128, 384], 2),                # ranks off the chunk sizes
+    (2, 2, 80, 80, 128, [300, 50, 0], [0, 0, 0], 2),               # nothing quantised yet; an empty sequence
+    (2, 1, 64, 64, 128, [20000], [19968], 1),                      # one workgroup walks 312 tiles
+    (2, 2, 80, 80, 128, [700], [640], 7),                          # splits that begin in the middle of a pair
+])
+def test_decode_over_key_groups_of_128_matches_oracle(form, H, Hkv, r_k, r_v, P, lens, n_quant, n_splits):
+    from oracle import eigen_attention as ora
+    print(f"q4 decode, key group 128, {form}: H={H}/{Hkv} r=({r_k},{r_v}) P={P} lens={lens} quantised={n_quant} "
+          f"S={n_splits}", flush=True)
+    desc = desc128(H, Hkv, 128, r_k, r_v, P)
+    g = synth.rng(142, H, r_k, len(lens), n_splits)
+    # (the rotary kernel rounds its rotated keys to fp16: scores of several hundred, which 20-fold keys give, would
+    # measure that rounding and not the layout)
+    K, V = loud_cache(desc, lens, g, 2.5 if form == "rope" else 20.0)
+    B = len(lens)
+    keep = [b for b in range(B) if lens[b] > 0]
+    sub = lambda xs: [xs[b] for b in keep]
+    ref = np.zeros((B, H, r_v))
+    if form == "rope":
+        U = quantize(desc, synth.orthonormal_basis(g, 128, r_k))
+        q = np.float32(synth.gaussian(g, (B, H, 128), 1.5)).astype(np.float64)
+        qc = Q4Cache(desc, K, V, n_quant, g)
+        got = run_rope_q4(desc, qc, q, U, 10000.0, n_splits)
+        ref[keep] = oq.decode_attention_rope_quantized(q[keep], sub(K), sub(V), sub(n_quant), U, 128, 10000.0,
+                                                       group_tokens=128)
+        other = oq.decode_attention_rope_quantized(q[keep], sub(K), sub(V), sub(n_quant), U, 128, 10000.0)
+    else:
+        q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+        qc = Q4Cache(desc, K, V, n_quant, g)
+        slopes = np.float32(2.0 ** (-8.0 * (np.arange(H) + 1) / H)).astype(np.float64) if form == "alibi" else None
+        if form == "alibi":
+            out = torch.full((B, H, r_v), float("nan"), dtype=torch.float32, device="cuda")
+            S = n_splits if n_splits else ea.decode_auto_splits(desc, B, qc.max_q4_pages * P)
+            ws = torch.full((ea.decode_q4_workspace_bytes(desc, B, S) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+            ea.decode_attn_alibi_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(),
+                                    torch.from_numpy(slopes.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table,
+                                    qc.q4_len, qc.dc.k_pool, qc.dc.v_pool, qc.tail_table, qc.tail_len, out, S, ws)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy()
+        else:
+            got = run_q4(desc, qc, q, n_splits)
+        ref[keep] = oq.decode_attention_quantized(q[keep], sub(K), sub(V), sub(n_quant), 128, alibi_slopes=slopes,
+                                                  group_tokens=128)
+        other = oq.decode_attention_quantized(q[keep], sub(K), sub(V), sub(n_quant), 128, alibi_slopes=slopes)
+    err = assert_close(got, ref, TOL_BF16, f"q4 decode, key group 128, {form}")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+    if any(n >= 256 for n in n_quant):
+        # the kernel follows the 128-token quantiser, not the 64-token one (they differ on these inputs)
+        assert ora.rel_l2(other, ref[keep]) > 3 * err
+
+
+def test_key_group_128_remainder_and_round_trip():
+    """q4_len counts whole 128-token groups: 200 attends 128 tokens of the 4-bit part.  And quantise -> dequantise
+    through the library = the oracle's round trip with 128-token key groups, rounded once to bfloat16."""
+    desc = desc128(4, 2, 128, 80, 48, 128)
+    g = synth.rng(143)
+    lens = [256, 384]
+    K, V = loud_cache(desc, lens, g)
+    q = np.float32(synth.gaussian(g, (2, 4, 80))).astype(np.float64)
+    qc = Q4Cache(desc, K, V, lens, g)
+    qc.q4_len = torch.tensor([200, 384], dtype=torch.int32).cuda()
+    out = torch.full((2, 4, 48), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ea.decode_q4_workspace_bytes(desc, 2, 2) // 4, dtype=torch.float32, device="cuda")
+    ea.decode_attn_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len, None,
+                      None, None, None, out, 2, ws)
+    torch.cuda.synchronize()
+    ref = oq.decode_attention_quantized(q, [K[0][:, :128], K[1]], [V[0][:, :128], V[1]], [128, 384], 128, group_tokens=128)
+    assert_close(out.cpu().numpy(), ref, TOL_BF16, "q4 remainder, key group 128")
+    dc = qc.dc
+    src = [int(qc.q4_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    dst = [int(dc.page_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    ea.dequantize_pages_q4(desc, qc.kq, qc.vq, torch.tensor(src, dtype=torch.int32).cuda(), dc.k_pool, dc.v_pool,
+                           torch.tensor(dst, dtype=torch.int32).cuda())
+    torch.cuda.synchronize()
+    for b in range(2):
+        kd = torch.zeros((1, 2, lens[b], 80), dtype=torch.bfloat16, device="cuda")
+        vd = torch.zeros((1, 2, lens[b], 48), dtype=torch.bfloat16, device="cuda")
+        ea.cache_gather(desc, kd, vd, dc.k_pool, dc.v_pool, dc.page_table[b:b + 1].contiguous())
+        torch.cuda.synchronize()
+        Kq, Vq = oq.quantized_view(K[b], V[b], lens[b], 128)
+        assert np.array_equal(kd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Kq)))
+        assert np.array_equal(vd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Vq)))

@@ -431,3 +431,52 @@ def test_rotary_entry_points_with_explicit_positions_reject_bad_arguments_before
     assert call(mass=OK_PTR, ws=None) == -4
     assert call(mass=OK_PTR, S=2, ws_bytes=ea.decode_attn_mass_workspace_bytes(d, 2, 4, 2) - 1) == -4
     assert call(mass=OK_PTR, dd=desc(dtype=ea.EA_F32, P=64)) == -2         # the statistic: bf16 layers only
+
+
+@pytest.mark.parametrize("P,r_k,r_v,Hkv", [(128, 80, 80, 2), (256, 30, 33, 1), (384, 128, 16, 2)])
+def test_q4_key_groups_of_128_tokens_share_one_block_of_scales(P, r_k, r_v, Hkv):
+    """q4_key_group = 128: every code still has its own nibble, the two tiles of a pair point at the same scales
+    (stored once, behind the codes of the pair's first tile), nothing overlaps, the page is shorter by one block of
+    scales per pair, and the value side is untouched."""
+    d = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
+    d64 = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
+    d.q4_key_group = 128
+    d64.q4_key_group = 64
+    lay, lay64, lay0 = ea.q4_layout_query(d), ea.q4_layout_query(d64), ea.q4_layout_query(desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P))
+    assert (lay64.k_page_bytes, lay64.k_tile_bytes) == (lay0.k_page_bytes, lay0.k_tile_bytes)      # 0 means 64
+    scales = 128 * (-(-lay.r_k_pad // 32))
+    assert lay.k_tile_bytes == lay64.k_tile_bytes == 32 * lay.r_k_pad + scales
+    assert lay.k_page_bytes == lay64.k_page_bytes - Hkv * (P // 128) * scales
+    assert lay.v_page_bytes == lay64.v_page_bytes and lay.v_tile_bytes == lay64.v_tile_bytes
+    page = 1
+    used = np.zeros(lay.k_page_bytes * 2, np.int32)
+    for h in range(Hkv):
+        for t in range(P):
+            for c in range(r_k):
+                pos = ea.q4_k_code_pos(d, page, h, t, c)
+                assert pos % 4 == 0
+                used[pos // 4 - page * lay.k_page_bytes * 2] += 1
+            assert ea.q4_v_code_pos(d, page, h, t, 0) == ea.q4_v_code_pos(d64, page, h, t, 0)
+        for grp in range(P // 128):
+            for c in range(r_k):
+                sp = ea.q4_k_scale_pos(d, page, h, grp * 128, c) - page * lay.k_page_bytes
+                assert all(ea.q4_k_scale_pos(d, page, h, grp * 128 + t, c) - page * lay.k_page_bytes == sp
+                           for t in (1, 63, 64, 100, 127))
+                for off in (sp, sp + 16):
+                    used[2 * off:2 * off + 4] += 1
+    assert used.max() == 1
+    assert used.sum() == Hkv * P * r_k + Hkv * (P // 128) * r_k * 8
+    # the first tile of a pair sits where a 64-token layout would put it if every earlier pair were one block of scales shorter
+    codes = 32 * lay.r_k_pad
+    assert ea.q4_k_code_pos(d, 0, 0, 64, 0) == (codes + scales) * 8
+    assert ea.q4_k_scale_pos(d, 0, 0, 64, 0) == codes
+    if P >= 256:
+        assert ea.q4_k_code_pos(d, 0, 0, 128, 0) == (2 * codes + scales) * 8
+        assert ea.q4_k_scale_pos(d, 0, 0, 200, 0) == 3 * codes + scales
+    # groups of 128 tokens need pages of whole groups; other group lengths are not built
+    bad = desc(P=192)
+    bad.q4_key_group = 128
+    assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -2
+    bad = desc()
+    bad.q4_key_group = 32
+    assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -1
