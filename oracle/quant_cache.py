@@ -140,3 +140,34 @@ def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int,
     views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
     return ea_oracle.decode_attention_rope(q, cache, Uk, d_head, base)
+
+
+def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group_tokens: int = GROUP_TOKENS):
+    """Prefill-phase attention (Eq. 2 in the rank-r space, causal) of the LAST n tokens of every sequence over a
+    cache whose first n_quant[b] tokens are quantised: plain causal attention over the dequantised values.
+    q_r [B, n, H, r_k]; K_list[b] [H_kv, len_b, r_k]; V_list[b] [H_kv, len_b, r_v]; n <= len_b - n_quant[b] (the
+    queries belong to tokens that are still held in 16 bits)."""
+    n = np.asarray(q_r).shape[1]
+    for b in range(len(K_list)):
+        assert n <= K_list[b].shape[1] - int(n_quant[b])
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
+    return ea_oracle.prefill_attention(q_r, cache, d_head)
+
+
+def chunked_prefill_quantized(q_r, K, V, chunk: int, d_head: int, group_tokens: int = GROUP_TOKENS):
+    """A prompt of n tokens prefilled chunk by chunk, every chunk's keys and values quantised as soon as the chunk
+    has been attended -- so that at no time more than one chunk exists in 16 bits (what the quantisation paragraph
+    of the results amounts to for a long prompt): the queries of chunk c see the tokens of chunks < c as their
+    quantise-dequantise round trip and those of chunk c itself, causally, as they are.
+    q_r [n, H, r_k], K [H_kv, n, r_k], V [H_kv, n, r_v] of ONE sequence; chunk a multiple of the key group;
+    returns o [n, H, r_v]."""
+    q_r = np.asarray(q_r, np.float64)
+    n = q_r.shape[0]
+    assert chunk % group_tokens == 0
+    out = np.zeros((n, q_r.shape[1], V.shape[2]))
+    for c0 in range(0, n, chunk):
+        c1 = min(n, c0 + chunk)
+        out[c0:c1] = prefill_attention_quantized(q_r[None, c0:c1], [K[:, :c1]], [V[:, :c1]], [c0], d_head,
+                                                 group_tokens)[0]
+    return out

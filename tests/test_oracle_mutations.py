@@ -115,6 +115,12 @@ QUANT = [
      "test_rounding_is_to_nearest_not_truncation"),
     ("seventeen levels", "LEVELS = 15 ", "LEVELS = 16 ", "test_values_on_the_grid_round_trip_exactly"),
     ("key groups of 32 tokens", "GROUP_TOKENS = 64", "GROUP_TOKENS = 32", "test_key_groups_are_64_tokens_long"),
+    ("a chunked prefill never quantises the chunks it has finished",
+     "[V[:, :c1]], [c0], d_head,", "[V[:, :c1]], [0], d_head,", "test_prefill_attention_over_a_partly_quantised_cache"),
+    ("the prefill over a partly quantised cache drops the causal mask (every query sees the whole cache)",
+     "    return ea_oracle.prefill_attention(q_r, cache, d_head)",
+     "    return np.stack([ea_oracle.decode_attention(np.asarray(q_r)[:, j], cache, d_head) for j in range(n)], axis=1)",
+     "test_prefill_attention_over_a_partly_quantised_cache"),
     ("the key quantiser ignores the group length it is given",
      "    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)",
      "    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)", "test_key_groups_of_128_tokens"),

@@ -327,3 +327,46 @@ def test_group_128_against_the_tables_rows():
         ours = scalars / 2 * (bk + bv) / 8 / 2 ** 30
         assert 1.04 < ours / (oq.quantized_cache_bytes(scalars, 4, 128) / 2 ** 30) < 1.06
     assert oq.bits_per_element_q4(80, 80, 64)[0] == 4.5
+
+
+def test_prefill_attention_over_a_partly_quantised_cache():
+    """(a) nothing quantised = plain causal attention; (b) the last query row = the generation-phase function on the
+    same cache; (c) brute force for one (query, head); (d) a prompt prefilled in chunks: the first chunk is plain
+    attention, later chunks see the earlier ones quantised, and each chunk equals the one-shot function at its cut."""
+    g = synth.rng(121)
+    H, Hkv, r_k, r_v, d_h, L, n = 4, 2, 8, 6, 16, 200, 70
+    K = [synth.gaussian(g, (Hkv, L, r_k))]
+    V = [synth.gaussian(g, (Hkv, L, r_v))]
+    q = synth.gaussian(g, (1, n, H, r_k))
+    plain = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), d_h)
+    assert np.array_equal(oq.prefill_attention_quantized(q, K, V, [0], d_h), plain)
+    got = oq.prefill_attention_quantized(q, K, V, [128], d_h)
+    assert not np.allclose(got, plain, atol=1e-3)
+    assert np.allclose(got[:, -1], oq.decode_attention_quantized(q[:, -1], K, V, [128], d_h), rtol=0, atol=1e-13)
+    # (c) query j = 10 (position 140), head 3 (kv head 1): keys 0..127 dequantised, 128..140 as they are
+    j, h, kv = 10, 3, 1
+    pos = L - n + j
+    ck, sk, zk = oq.quantize_keys(K[0][kv, :128])
+    cv, sv, zv = oq.quantize_values(V[0][kv, :128])
+    sc, vals = [], []
+    for t in range(pos + 1):
+        if t < 128:
+            key = [float(sk[t // 64, c]) * int(ck[t, c]) + float(zk[t // 64, c]) for c in range(r_k)]
+            val = [float(sv[t]) * int(cv[t, c]) + float(zv[t]) for c in range(r_v)]
+        else:
+            key, val = K[0][kv, t], V[0][kv, t]
+        sc.append(sum(a * b for a, b in zip(q[0, j, h], key)) / np.sqrt(d_h))
+        vals.append(val)
+    w = np.exp(np.array(sc) - max(sc))
+    assert np.allclose(got[0, j, h], (w[:, None] * np.array(vals)).sum(axis=0) / w.sum(), rtol=0, atol=1e-12)
+    # (d)
+    n_all = 192
+    qa = synth.gaussian(g, (n_all, H, r_k))
+    Ka, Va = K[0][:, :n_all], V[0][:, :n_all]
+    ch = oq.chunked_prefill_quantized(qa, Ka, Va, 64, d_h)
+    one = ora.prefill_attention(qa[None], ora.RankCache.from_arrays([Ka], [Va]), d_h)[0]
+    assert np.allclose(ch[:64], one[:64], rtol=0, atol=1e-13) and not np.allclose(ch[64:], one[64:], atol=1e-3)
+    assert np.allclose(ch[128:], oq.prefill_attention_quantized(qa[None, 128:], [Ka], [Va], [128], d_h)[0], rtol=0, atol=1e-13)
+    # with 128-token key groups the third chunk sees one group, not two
+    ch128 = oq.chunked_prefill_quantized(qa[:256], Ka, Va, 128, d_h, group_tokens=128)
+    assert np.allclose(ch128[128:], oq.prefill_attention_quantized(qa[None, 128:], [Ka], [Va], [128], d_h, 128)[0], atol=1e-13)
