@@ -53,7 +53,9 @@ def parse_args():
     ap.add_argument("--q4-key-group", type=int, default=64, choices=[64, 128],
                     help="-q4 workloads: tokens that share a key scale (128 needs --page-tokens 128 or more)")
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
-                             "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o", "cfg2-rope-h2o", "cfg3-rope-h2o"])
+                             "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o", "cfg2-rope-h2o", "cfg3-rope-h2o", "cfg4-q4"])
+    ap.add_argument("--prefill-chunk", type=int, default=2048,
+                    help="cfg4-q4: tokens per sequence that are prefilled (and then quantised) at a time")
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -980,6 +982,152 @@ def bench_prefill(args, torch, ea, synth):
     return result
 
 
+def bench_prefill_q4(args, torch, ea, synth):
+    """cfg4-q4: the config-4 prompt prefilled chunk by chunk, every finished chunk quantised to 4 bits at once, so that
+    only one chunk per sequence ever exists in 16 bits.  A step = the whole prompt through one layer: per chunk
+    project_qkv (into the same few bfloat16 pages), ea_prefill_attn_q4 (the chunk causally, all earlier chunks as
+    codes), ea_quantize_pages_q4, out_proj."""
+    import numpy as np
+    dev = "cuda"
+    s = synth.CFG4
+    B, n, P, C = s.batch, s.n_ctx, args.page_tokens, args.prefill_chunk
+    H, d, r = s.n_heads, s.d_model, s.r_k
+    group = args.q4_key_group
+    if C % P or n % C or P % group:
+        raise SystemExit("cfg4-q4: the chunk must be whole pages, the prompt whole chunks, a page whole key groups")
+    desc = ea.LayerDesc(d, H, H, s.d_head, r, r, ea.EA_BF16, P, group)
+    n_qkv = 3 * H * r
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED + 4)
+    cpp = C // P                                         # pages per chunk and sequence
+    k_pool, v_pool = ea.alloc_pools(desc, B * cpp)       # the only bfloat16 cache there is: one chunk per sequence
+    stage = torch.randperm(B * cpp, generator=gen, device=dev).to(torch.int32).reshape(B, cpp).contiguous()
+    q4_pages = B * (n // P)
+    kq, vq = ea.alloc_q4_pools(desc, q4_pages)
+    q4_table = torch.randperm(q4_pages, generator=gen, device=dev).to(torch.int32).reshape(B, n // P).contiguous()
+    x = torch.randn((B, n, d), generator=gen, device=dev).to(torch.bfloat16)
+    wqkv_raw = (torch.randn((n_qkv, d), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)
+    wo_raw = (torch.randn((d, H * r), generator=gen, device=dev) * d ** -0.5).to(torch.bfloat16)
+    wqkv, wo = ea.pack_weight(wqkv_raw), ea.pack_weight(wo_raw)
+    q_r = torch.empty((B, n, H, r), dtype=torch.bfloat16, device=dev)         # kept whole for the parity check
+    o = torch.empty((B, n, H, r), dtype=torch.bfloat16, device=dev)
+    y = torch.empty((B, n, d), dtype=torch.bfloat16, device=dev)
+    xc = [x[:, c0:c0 + C].contiguous().view(B * C, d) for c0 in range(0, n, C)]
+    qc = torch.empty((B * C, H, r), dtype=torch.bfloat16, device=dev)
+    oc = torch.empty((B, C, H, r), dtype=torch.bfloat16, device=dev)
+    yc = torch.empty((B * C, d), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty(ea.prefill_q4_workspace_bytes(desc, B, C) // 4, dtype=torch.float32, device=dev)
+    zero = torch.zeros((B,), dtype=torch.int32, device=dev)
+    full = torch.full((B,), C, dtype=torch.int32, device=dev)
+    q4_lens = [torch.full((B,), c0, dtype=torch.int32, device=dev) for c0 in range(0, n, C)]
+    src_pages = stage.reshape(-1).contiguous()
+    dst_pages = [q4_table[:, c0 // P:(c0 + C) // P].reshape(-1).contiguous() for c0 in range(0, n, C)]
+    n_chunks = n // C
+
+    def step(events=None, keep=False):
+        for c in range(n_chunks):
+            e = events[c] if events is not None else None
+            if e: e[0].record()
+            ea.project_qkv(desc, xc[c], wqkv, qc, k_pool, v_pool, stage, zero, C)
+            if e: e[1].record()
+            ea.prefill_attn_q4(desc, qc.view(B, C, H, r), kq, vq, q4_table, q4_lens[c], k_pool, v_pool, stage, full, oc, ws)
+            if e: e[2].record()
+            ea.quantize_pages_q4(desc, k_pool, v_pool, src_pages, kq, vq, dst_pages[c])
+            if e: e[3].record()
+            ea.out_proj(desc, oc.view(B * C, H * r), wo, yc)
+            if e: e[4].record()
+            if keep:
+                q_r[:, c * C:(c + 1) * C] = qc.view(B, C, H, r)
+                o[:, c * C:(c + 1) * C] = oc
+                y[:, c * C:(c + 1) * C] = yc.view(B, C, d)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_chunks)] for _ in range(args.steps)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for k in range(args.steps):
+        step(ev[k])
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    t = [sum(ev[k][c][i].elapsed_time(ev[k][c][i + 1]) for k in range(args.steps) for c in range(n_chunks)) / args.steps
+         for i in range(4)]
+    attn_per_chunk = [sum(ev[k][c][1].elapsed_time(ev[k][c][2]) for k in range(args.steps)) / args.steps
+                      for c in range(n_chunks)]
+    f_proj, f_attn, f_out = 2 * B * n * d * n_qkv, B * H * n * n * 2 * r, 2 * B * n * H * r * d
+    flops = f_proj + f_attn + f_out
+
+    def tf(f, ms):
+        return f / (ms * 1e-3) / 1e12
+
+    lay, lay16 = ea.q4_layout_query(desc), ea.cache_layout_query(desc)
+    result = {
+        "metric": "low-rank causal prefill over a 4-bit cache: TFLOP/s of the whole prompt, chunk by chunk (cfg4-q4)",
+        "value": round(tf(flops, ms_per_step), 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg4-q4 causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, d_h={s.d_head}, "
+                               f"r_k=r_v={r}, in chunks of {C} tokens per sequence; per chunk project_qkv (into the same "
+                               f"{B * cpp} bfloat16 pages) + prefill_attn_q4 (the chunk causally, earlier chunks as 4-bit "
+                               f"codes, key groups of {group} tokens) + quantize_pages_q4 + out_proj; pages of {P} tokens "
+                               f"in random order",
+                   "batch": B, "n_ctx": n, "r_k": r, "r_v": r, "page_tokens": P, "chunk": C},
+        "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
+        "kernels": {"project_qkv": {"ms": round(t[0], 4), "tflops": round(tf(f_proj, t[0]), 1)},
+                    "prefill_attn_q4": {"ms": round(t[1], 4), "tflops_causal_counted": round(tf(f_attn, t[1]), 1),
+                                        "ms_per_chunk": [round(v, 4) for v in attn_per_chunk]},
+                    "quantize_pages_q4": {"ms": round(t[2], 4)},
+                    "out_proj": {"ms": round(t[3], 4), "tflops": round(tf(f_out, t[3]), 1)}},
+        "cache_bytes": {"bf16_resident": int(B * cpp * (lay16.k_page_elems + lay16.v_page_elems) * 2),
+                        "q4_after_the_prompt": int(q4_pages * (lay.k_page_bytes + lay.v_page_bytes)),
+                        "bf16_if_the_prompt_were_kept_in_16_bits": int(B * (n // P) * (lay16.k_page_elems + lay16.v_page_elems) * 2)},
+        "roofline": {"bound": "mfma", "achieved": round(tf(f_attn, t[1]), 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tf(f_attn, t[1]) / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "prefill_bf16_direct_kernel (the chunk itself) + prefill_q4_kernel (earlier chunks) + "
+                               "merge_prefill_parts_kernel: all ea_prefill_attn_q4 calls of the prompt, flops counted below "
+                               "the causal diagonal only", "flops_per_launch": f_attn, "us_per_launch": round(t[1] * 1e3, 1)},
+    }
+    if not args.no_parity:
+        from oracle import eigen_attention as ora
+        from oracle import quant_cache as oq
+        step(keep=True)
+        # the keys and values as the step's projection produced them, once more into pools that hold the whole prompt
+        # (for the check only), so that the oracle can quantise the same bfloat16 values
+        kf, vf = ea.alloc_pools(desc, B * (n // P))
+        ptf = torch.arange(B * (n // P), dtype=torch.int32, device=dev).reshape(B, n // P).contiguous()
+        qtmp = torch.empty((B * C, H, r), dtype=torch.bfloat16, device=dev)
+        for c in range(n_chunks):
+            ea.project_qkv(desc, xc[c], wqkv, qtmp, kf, vf, ptf, q4_lens[c], C)
+        torch.cuda.synchronize()
+        g = synth.rng(45)
+        picks = [(0, 0, 64), (B - 1, H - 1, n), (0, 1, C + 64)] + \
+                [(int(g.integers(B)), int(g.integers(H)), int(g.integers(65, n))) for _ in range(max(args.parity_samples // 8, 2))]
+        worst, errs = 0.0, []
+        for b, h, m in picks:
+            Kb = _stream_bits(torch, kf, ptf[b], h, H, r, lay16.r_k_pad, _k_tiles_to_rows, P, m)
+            Vb = _stream_bits(torch, vf, ptf[b], h, H, r, lay16.r_v_pad, _v_tiles_to_rows, P, m)
+            K1 = synth.bf16_bits_to_f32(Kb).astype(np.float64)[None]
+            V1 = synth.bf16_bits_to_f32(Vb).astype(np.float64)[None]
+            lo = max(m - 64, (m - 1) // C * C)               # the block's rows that lie in the chunk of row m - 1
+            qrows = q_r[b, lo:m, h].float().cpu().numpy().astype(np.float64)[None, :, None, :]
+            ref = oq.prefill_attention_quantized(qrows, [K1], [V1], [(m - 1) // C * C], s.d_head, group_tokens=group)
+            got = o[b, lo:m, h].float().cpu().numpy()[None, :, None, :]
+            e = ora.rel_l2(got, ref) if np.isfinite(got).all() else float("inf")
+            errs.append(e)
+            worst = max(worst, e)
+        result["parity"] = {"samples": len(errs), "worst_rel_l2": float(f"{worst:.3e}"),
+                            "attention_mean_rel_l2": float(f"{np.mean(errs):.3e}"), "bar": 1e-2,
+                            "ok": bool(np.isfinite(worst) and worst <= 1e-2),
+                            "what": "blocks of up to 64 query rows of the step's attention output (first rows, last rows, "
+                                    "the first rows of the second chunk, seeded random positions) vs the fp64 oracle's causal "
+                                    "attention over the same keys and values with the earlier chunks quantised"}
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_oracle_prefill(512, n, r, s.d_head)
+    return result
+
+
 def main():
     if len(sys.argv) >= 6 and sys.argv[1] == "--oracle-worker":       # a child of cpu_oracle_decode: no GPU, no torch
         oracle_worker_main(sys.argv[2], int(sys.argv[3]), float(sys.argv[4]), int(sys.argv[5]))
@@ -996,8 +1144,12 @@ def main():
 
     ea.load_library()                      # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    result = bench_prefill(args, torch, ea, synth) if args.workload.startswith("cfg4") else \
-        bench_decode(args, torch, ea, synth)
+    if args.workload == "cfg4-q4":
+        result = bench_prefill_q4(args, torch, ea, synth)
+    elif args.workload.startswith("cfg4"):
+        result = bench_prefill(args, torch, ea, synth)
+    else:
+        result = bench_decode(args, torch, ea, synth)
     print(json.dumps(result))
     par = result.get("parity")
     if isinstance(par, dict) and par.get("ok") is False:

@@ -413,13 +413,35 @@ EA_API int ea_decode_attn_alibi_q4(const ea_layer_desc* desc, const float* dev_q
                     float* dev_out, int32_t B, int32_t n_splits,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* Prefill over a partly quantised cache (Eq. (2) in rank space, causal; position-free form): sequence b holds
+ * q4_len[b] tokens in the 4-bit pools (whole key groups; a remainder is ignored) followed by tail_len[b] tokens in the
+ * bfloat16 pools, and the n queries dev_q_r [B, n, H, r_k] (bfloat16) are its LAST n tokens, all of which must lie in
+ * the bfloat16 part (n <= tail_len[b]; the call cannot check this): every query sees the whole 4-bit part and, causally,
+ * the bfloat16 part.  This is what lets a long prompt be prefilled chunk by chunk -- ea_project_qkv appends a chunk to
+ * bfloat16 pages, this call attends it, ea_quantize_pages_q4 moves its pages to the 4-bit pools, the bfloat16 pages are
+ * reused for the next chunk -- so that the prompt never exists in 16 bits as a whole.
+ *   dev_out [B, n, H, r_v] bfloat16;  dev_ws: ea_prefill_q4_workspace_bytes(desc, B, n) bytes, 16-byte aligned
+ *   (the two parts of every query row's softmax before they are merged).
+ * Three launches (bfloat16 part, 4-bit part, merge).  The tiles of the 4-bit part are expanded to half precision in
+ * registers; error against attention over the dequantised values as for ea_decode_attn_q4. */
+EA_API int64_t ea_prefill_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n);
+EA_API int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    void* dev_out, int32_t B, int32_t n,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama
  * models of the paper's quantisation experiment are of this kind): the 4-bit pools
  * hold the quantised rank-r keys k_r = k U^K of the one shared basis; every key is
  * dequantised, brought back to d_head channels (U^K k_r) and rotated by its position
  * (token i of the 4-bit part sits at position i, token i of the tail at position
  * q4_len[b] + i, the query is the newest token), exactly as ea_decode_attn_rope does
- * for the bfloat16 cache.  q4_len[b] must be a multiple of 64.
+ * for the bfloat16 cache.  q4_len[b] must be a multiple of the key group (64 or 128).
  *   dev_q [B, H, d_head] float, NOT rotated; dev_u_k [d_head, r_k] bfloat16; rope_base as in
  *   ea_decode_attn_rope; n_splits = 0 picks ea_decode_rope_auto_splits; workspace
  *   ea_decode_q4_workspace_bytes(desc, B, n_splits).  d_head 64 or 128, r_k <= d_head. */

@@ -21,7 +21,7 @@ __all__ = [
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
-    "decode_attn_rope_pos", "decode_attn_mass_rope_pos",
+    "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -35,7 +35,7 @@ EXPORTED_SYMBOLS = (
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
-    "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos",
+    "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
 )
 
 STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
@@ -141,6 +141,9 @@ def load_library():
     lib.ea_decode_q4_workspace_bytes.restype = I64
     lib.ea_decode_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_decode_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
+    lib.ea_prefill_q4_workspace_bytes.restype = I64
+    lib.ea_prefill_q4_workspace_bytes.argtypes = [D, I32, I32]
+    lib.ea_prefill_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
     lib.ea_attn_mass_workspace_bytes.restype = I64
     lib.ea_attn_mass_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_attn_mass.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, VP, I64, VP]
@@ -655,6 +658,31 @@ def decode_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v
     else:
         _check(load_library().ea_decode_attn_alibi_q4(ctypes.byref(desc), _ptr(q_r), _ptr(alibi_slopes), *rest),
                "ea_decode_attn_alibi_q4")
+
+
+def prefill_q4_workspace_bytes(desc, B: int, n: int) -> int:
+    return int(load_library().ea_prefill_q4_workspace_bytes(ctypes.byref(desc), B, n))
+
+
+def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
+                    ws, stream=None) -> None:
+    """Causal prefill attention of the last n tokens of every sequence: q_r [B, n, H, r_k] -> out [B, n, H, r_v]
+    (bfloat16) over q4_len[b] tokens of the 4-bit pools followed by tail_len[b] >= n tokens of the bfloat16 pools."""
+    B, n = q_r.shape[0], q_r.shape[1]
+    _expect(q_r, desc.dtype, "q_r"); _expect(out, desc.dtype, "out")
+    if q_r.numel() != B * n * desc.n_heads * desc.r_k or out.numel() != B * n * desc.n_heads * desc.r_v:
+        raise ValueError("q_r / out have the wrong size")
+    _u8(kq_pool, "kq_pool"); _u8(vq_pool, "vq_pool")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    for t, name in ((q4_page_table, "q4_page_table"), (q4_len, "q4_len"), (tail_page_table, "tail_page_table"),
+                    (tail_len, "tail_len")):
+        _i32(t, name)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_prefill_attn_q4(
+        ctypes.byref(desc), _ptr(q_r), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
+        q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table), _ptr(tail_len),
+        tail_page_table.shape[1], k_pool.shape[0], _ptr(out), B, n, _ptr(ws), ws_bytes, _stream(stream))
+    _check(rc, "ea_prefill_attn_q4")
 
 
 def decode_attn_alibi_q4(desc, q_r, slopes, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table,

@@ -172,6 +172,36 @@ int ea_decode_attn_alibi_q4(const ea_layer_desc* desc, const float* dev_q_r, con
                              max_tail_pages, pool_pages, dev_out, B, n_splits, dev_ws, ws_bytes, stream);
 }
 
+int64_t ea_prefill_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n) {
+  if (validate_q4(desc) != EA_OK || B <= 0 || n <= 0) return -1;
+  return 2 * (int64_t)B * n * desc->n_heads * (desc->r_v + 2) * (int64_t)sizeof(float);
+}
+
+int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_kq_pool, const void* dev_vq_pool,
+                       const int32_t* dev_q4_page_table, const int32_t* dev_q4_len, int32_t max_q4_pages,
+                       int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
+                       const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
+                       int32_t pool_pages, void* dev_out, int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes,
+                       void* stream) {
+  int rc = validate_q4(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_kq_pool || !dev_vq_pool || !dev_q4_page_table || !dev_q4_len || !dev_k_pool || !dev_v_pool ||
+      !dev_tail_page_table || !dev_tail_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || n <= 0 || max_q4_pages <= 0 || q4_pool_pages <= 0 || max_tail_pages <= 0 || pool_pages <= 0)
+    return EA_ERR_ARG;
+  if (!aligned16(dev_q_r) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool) || !aligned16(dev_k_pool) ||
+      !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  if (!dev_ws || !aligned16(dev_ws) || ws_bytes < ea_prefill_q4_workspace_bytes(desc, B, n)) return EA_ERR_WORKSPACE;
+  const Geo gq = make_geo(desc, max_q4_pages, q4_pool_pages);
+  const Geo gt = make_geo(desc, max_tail_pages, pool_pages);
+  clear_stale_error();
+  return prefill_q4(desc, gq, q4_geo_of(desc), dev_q_r, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len, gt,
+                    dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len, dev_out, B, n, (float*)dev_ws,
+                    (hipStream_t)stream);
+}
+
 int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const void* dev_u_k, double rope_base,
                            const void* dev_kq_pool, const void* dev_vq_pool, const int32_t* dev_q4_page_table,
                            const int32_t* dev_q4_len, int32_t max_q4_pages, int32_t q4_pool_pages,

@@ -180,7 +180,7 @@ int mass_from_scores(const Geo& g, const float* scores, const float* ml, const i
 
 int prefill_bf16(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool, const void* v_pool,
                  const int32_t* page_table, const int32_t* seq_len, void* out, int32_t B, int32_t n, hipStream_t st,
-                 int32_t k_compact = 0);
+                 int32_t k_compact = 0, float* part_o = nullptr, float* part_ml = nullptr);   // part_*: see PrefillArgs
 // Rotary prefill (bf16): rotated full-rank keys and rotated queries are written to the workspace, then the
 // position-free prefill kernel runs at rank d_head on them.
 int64_t prefill_rope_ws_bytes(const ea_layer_desc* d, int32_t B, int32_t n, int32_t max_pages);

@@ -34,16 +34,31 @@ struct PrefillArgs {
   int32_t k_compact;
   const float* alibi; // [H] ALiBi slopes (natural-log units, >= 0), ALIBI kernels only
   float scale_log2;
+  // When set, the kernel leaves its result as a PART of a softmax that another kernel continues (a cache whose older
+  // tokens are held elsewhere): per (sequence, query, head) row the normalised output in float, its reference
+  // exponent (log2 units) and its row sum.  `out` is not written then.
+  float* part_o = nullptr;    // [B * n_q * H, r_v]
+  float* part_ml = nullptr;   // [B * n_q * H, 2]
 };
+
+// The fragment type of the two matrix-core contractions: bfloat16 for the cache as it is, half precision for tiles
+// that are expanded from 4-bit codes in registers (their format is free, and half precision keeps three more bits).
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+__device__ __forceinline__ f32x4 mfma16(f16x8 a, f16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+template <class F> struct FragElem;
+template <> struct FragElem<bf16x8> { using type = __bf16; };
+template <> struct FragElem<f16x8> { using type = _Float16; };
 
 // One 64-token tile against one block of 16 queries: scores, online softmax, P.V.
 // MASKED = the tile is cut by the causal diagonal or by the end of the sequence (lane-wise limits);
 // unmasked tiles run the lean path.  `vis` = number of kv positions this lane's query may see.
 // ALIBI: every score gets slope * (key position - query position) (log2 units) before the softmax; `dist0` is
 // the distance of this lane's query to the tile's first token of this register quad (tok0 + 4*quad - pos).
-template <int KS, int NCB, int TB, bool MASKED, bool ALIBI>
-__device__ __forceinline__ void attend_block(const bf16x8 (&kf)[TB][KS], const bf16x8 (&vf)[TB / 2][NCB],
-                                             const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
+template <int KS, int NCB, int TB, bool MASKED, bool ALIBI, class F = bf16x8>
+__device__ __forceinline__ void attend_block(const F (&kf)[TB][KS], const F (&vf)[TB / 2][NCB],
+                                             const F (&q)[KS], const F& ones, f32x4 (&acc)[NCB],
                                              f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad,
                                              float slope, int dist0) {
   // The query arrives already multiplied by log2(e)/sqrt(d_head), and the score accumulators start at minus the
@@ -87,13 +102,13 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[TB][KS], const b
     for (int tb = 0; tb < TB; ++tb) s[tb] -= delta;
     m = m_new;
   }
-  bf16x8 pf[TB / 2];
+  F pf[TB / 2];
 #pragma unroll
   for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
+      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (typename FragElem<F>::type)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
 #pragma unroll
   for (int u = 0; u < TB / 2; ++u) lacc = mfma16(ones, pf[u], lacc);
 #pragma unroll
@@ -106,9 +121,9 @@ __device__ __forceinline__ void attend_block(const bf16x8 (&kf)[TB][KS], const b
 // without looking for the tile's maximum: the exponentials are taken against the reference as it stands and the
 // caller inspects the row sums afterwards (see the tile loop).  Per score that leaves the exponential and half a
 // conversion for the vector unit.
-template <int KS, int NCB, int TB>
-__device__ __forceinline__ void attend_block_optimistic(const bf16x8 (&kf)[TB][KS], const bf16x8 (&vf)[TB / 2][NCB],
-                                                        const bf16x8 (&q)[KS], const bf16x8& ones, f32x4 (&acc)[NCB],
+template <int KS, int NCB, int TB, class F = bf16x8>
+__device__ __forceinline__ void attend_block_optimistic(const F (&kf)[TB][KS], const F (&vf)[TB / 2][NCB],
+                                                        const F (&q)[KS], const F& ones, f32x4 (&acc)[NCB],
                                                         f32x4& lacc, float m) {
   const f32x4 neg_m{-m, -m, -m, -m};
   f32x4 s[TB];
@@ -118,13 +133,13 @@ __device__ __forceinline__ void attend_block_optimistic(const bf16x8 (&kf)[TB][K
 #pragma unroll
     for (int ks = 1; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
-  bf16x8 pf[TB / 2];
+  F pf[TB / 2];
 #pragma unroll
   for (int u = 0; u < TB / 2; ++u)
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (__bf16)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
+      for (int i = 0; i < 4; ++i) pf[u][h * 4 + i] = (typename FragElem<F>::type)__builtin_amdgcn_exp2f(s[2 * u + h][i]);
 #pragma unroll
   for (int u = 0; u < TB / 2; ++u) lacc = mfma16(ones, pf[u], lacc);
 #pragma unroll
@@ -149,13 +164,31 @@ __device__ __forceinline__ void clear_tail(bf16x8 (&vf)[TB / 2][NCB], int tok0, 
 
 template <int NCB, int QT>
 __device__ __forceinline__ void write_out(const PrefillArgs& a, const f32x4 (&acc)[QT][NCB], const f32x4 (&lacc)[QT],
-                                          int b, int head, int q0, int col, int quad) {
+                                          const float (&m)[QT], int b, int head, int q0, int col, int quad) {
   const Geo& g = a.g;
 #pragma unroll
   for (int qb = 0; qb < QT; ++qb) {
     const int qi = q0 + qb * 16 + col;
     const float l = lacc[qb][0];
     const float inv = l > 0.f ? 1.0f / l : 0.f;
+    if (a.part_o) {
+      if (qi < a.n_q) {
+        const int64_t row = ((int64_t)b * a.n_q + qi) * g.n_heads + head;
+        float* prow = a.part_o + row * g.r_v;
+        if (quad == 0) {
+          a.part_ml[2 * row] = m[qb];
+          a.part_ml[2 * row + 1] = l;
+        }
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int c = cb * 16 + quad * 4 + i;
+            if (c < g.r_v) prow[c] = acc[qb][cb][i] * inv;
+          }
+      }
+      continue;
+    }
     uint16_t* orow = a.out + (((int64_t)b * a.n_q + qi) * g.n_heads + head) * g.r_v;
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
@@ -377,7 +410,7 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
       for (int cb = 0; cb < NCB; ++cb) acc[qb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
   }
-  write_out<NCB, QT>(a, acc, lacc, b, head, q0, col, quad);
+  write_out<NCB, QT>(a, acc, lacc, m, b, head, q0, col, quad);
 }
 
 template <int KS, int NCB, bool ALIBI>
@@ -418,7 +451,8 @@ static int dispatch_ncb(int ncb, const PrefillArgs& a, int32_t B, hipStream_t st
 template <bool ALIBI>
 static int prefill_bf16_launch(const ea_layer_desc* d, const Geo& g, const void* q, const void* k_pool,
                                const void* v_pool, const int32_t* page_table, const int32_t* seq_len, void* out,
-                               int32_t B, int32_t n, hipStream_t st, int32_t k_compact, const float* alibi) {
+                               int32_t B, int32_t n, hipStream_t st, int32_t k_compact, const float* alibi,
+                               float* part_o = nullptr, float* part_ml = nullptr) {
   if ((int64_t)((n + 63) / 64) * g.n_heads * B > INT32_MAX) return EA_ERR_SHAPE;
   PrefillArgs a;
   a.q = (const uint16_t*)q;
@@ -432,6 +466,8 @@ static int prefill_bf16_launch(const ea_layer_desc* d, const Geo& g, const void*
   a.k_compact = k_compact;
   a.alibi = alibi;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)d->d_head);
+  a.part_o = part_o;
+  a.part_ml = part_ml;
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   switch (ks) {
     case 1: return dispatch_ncb<1, ALIBI>(ncb, a, B, st);

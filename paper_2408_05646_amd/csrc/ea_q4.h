@@ -132,6 +132,12 @@ int decode_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float
               const Geo* tail_geo, const void* k_pool, const void* v_pool, const int32_t* tail_page_table,
               const int32_t* tail_len,      // tail_geo == nullptr: no bfloat16 tail
               const float* alibi_slopes = nullptr);
+// Causal prefill attention of the last n tokens over q4_len 4-bit tokens followed by tail_len bfloat16 tokens; ws:
+// 2 * B * n * H * (r_v + 2) floats.
+int prefill_q4(const ea_layer_desc* d, const Geo& gq, const Q4Geo& qg, const void* q, const void* kq_pool,
+               const void* vq_pool, const int32_t* q4_page_table, const int32_t* q4_len, const Geo& gt,
+               const void* k_pool, const void* v_pool, const int32_t* tail_page_table, const int32_t* tail_len,
+               void* out, int32_t B, int32_t n, float* ws, hipStream_t st);
 int decode_rope_q4(const ea_layer_desc* d, const Geo& g, const Q4Geo& qg, const float* q, const void* u_k,
                    double rope_base, const void* kq_pool, const void* vq_pool, const int32_t* q4_page_table,
                    const int32_t* q4_len, const int32_t* tail_len, int32_t max_q4_pages, int32_t q4_pool_pages,

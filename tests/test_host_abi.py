@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 44
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 46
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -480,3 +480,20 @@ def test_q4_key_groups_of_128_tokens_share_one_block_of_scales(P, r_k, r_v, Hkv)
     bad = desc()
     bad.q4_key_group = 32
     assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -1
+
+
+def test_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def call(dd=d, q=OK_PTR, kq=OK_PTR, k=OK_PTR, tail=OK_PTR, out=OK_PTR, B=2, n=100, mq=4, qpool=8, mt=2, pool=8,
+             ws=OK_PTR, ws_bytes=1 << 40):
+        return lib.ea_prefill_attn_q4(ctypes.byref(dd), q, kq, OK_PTR, OK_PTR, OK_PTR, mq, qpool, k, OK_PTR, tail, OK_PTR,
+                                      mt, pool, out, B, n, ws, ws_bytes, None)
+
+    assert call(q=None) == -1 and call(tail=None) == -1 and call(k=None) == -1 and call(n=0) == -1 and call(mt=0) == -1
+    assert call(kq=ODD_PTR) == -3 and call(out=ODD_PTR) == -3
+    need = ea.prefill_q4_workspace_bytes(d, 2, 100)
+    assert need == 2 * 2 * 100 * 8 * (48 + 2) * 4                          # two parts: output row, exponent, row sum
+    assert call(ws=None) == -4 and call(ws_bytes=need - 1) == -4
+    assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
+    assert ea.prefill_q4_workspace_bytes(d, 0, 100) == -1
