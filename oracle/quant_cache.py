@@ -18,7 +18,8 @@ One thing here IS pinned to the paper: quantized_cache_bytes, the size accountin
 all 15 KV-cache sizes of the appendix's quantisation table.
 
 The reading:
-  * 4 bits, asymmetric: a group with minimum lo and maximum hi gets  zero = fp16(lo),
+  * 4 bits (or 3: `bits`, the two precisions of the paper's Eigen Attention rows; 15 and 7 below are 2^bits - 1),
+    asymmetric: a group with minimum lo and maximum hi gets  zero = fp16(lo),
     scale = fp16((hi - lo) / 15), both first clamped to the finite fp16 range; the quotient is taken in
     float32.  A group whose scale rounds to 0 (all values equal, or a spread below fp16's smallest step)
     gets code 0 everywhere.
@@ -42,41 +43,46 @@ LEVELS = 15          # 4 bits: codes 0 .. 15
 F16_MAX = 65504.0
 
 
-def _scale_zero(lo, hi):
+def _levels(bits: int) -> int:
+    assert bits in (3, 4)
+    return LEVELS if bits == 4 else 7
+
+
+def _scale_zero(lo, hi, levels: int = LEVELS):
     """fp16 scale and zero of groups with minima lo and maxima hi (float32 arrays)."""
     lo = np.clip(lo.astype(np.float32), -F16_MAX, F16_MAX)
     hi = np.clip(hi.astype(np.float32), -F16_MAX, F16_MAX)
-    step = np.minimum((hi - lo) / np.float32(LEVELS), np.float32(F16_MAX))
+    step = np.minimum((hi - lo) / np.float32(levels), np.float32(F16_MAX))
     return step.astype(np.float16), lo.astype(np.float16)
 
 
-def _codes(x, scale, zero):
-    """clip(rint((x - zero) / scale), 0, 15) in float32; scale == 0 gives code 0."""
+def _codes(x, scale, zero, levels: int = LEVELS):
+    """clip(rint((x - zero) / scale), 0, levels) in float32; scale == 0 gives code 0."""
     x32 = x.astype(np.float32)
     s32 = scale.astype(np.float32)
     z32 = zero.astype(np.float32)
     safe = np.where(s32 > 0, s32, np.float32(1.0))
     q = np.rint((x32 - z32) / safe)
     q = np.where(s32 > 0, q, np.float32(0.0))
-    return np.clip(q, 0, LEVELS).astype(np.uint8)
+    return np.clip(q, 0, levels).astype(np.uint8)
 
 
-def quantize_keys(K, group_tokens: int = GROUP_TOKENS):
+def quantize_keys(K, group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """K [n, r] (n a multiple of the group) -> codes uint8 [n, r], scale fp16 [n/group, r], zero fp16 [n/group, r]:
-    one scale per channel and group of `group_tokens` consecutive tokens."""
+    one scale per channel and group of `group_tokens` consecutive tokens; codes 0 .. 2^bits - 1."""
     n, r = K.shape
     assert n % group_tokens == 0
     Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)
-    scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1))
-    codes = _codes(Kg, scale[:, None, :], zero[:, None, :]).reshape(n, r)
+    scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1), _levels(bits))
+    codes = _codes(Kg, scale[:, None, :], zero[:, None, :], _levels(bits)).reshape(n, r)
     return codes, scale, zero
 
 
-def quantize_values(V):
+def quantize_values(V, bits: int = 4):
     """V [n, r] -> codes uint8 [n, r], scale fp16 [n], zero fp16 [n]: one scale per token."""
     V32 = V.astype(np.float32)
-    scale, zero = _scale_zero(V32.min(axis=1), V32.max(axis=1))
-    return _codes(V32, scale[:, None], zero[:, None]), scale, zero
+    scale, zero = _scale_zero(V32.min(axis=1), V32.max(axis=1), _levels(bits))
+    return _codes(V32, scale[:, None], zero[:, None], _levels(bits)), scale, zero
 
 
 def dequantize_keys(codes, scale, zero):
@@ -90,7 +96,7 @@ def dequantize_values(codes, scale, zero):
     return scale.astype(np.float64)[:, None] * codes.astype(np.float64) + zero.astype(np.float64)[:, None]
 
 
-def quantized_view(K, V, n_quant: int, group_tokens: int = GROUP_TOKENS):
+def quantized_view(K, V, n_quant: int, group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """The cache as attention sees it when its first n_quant tokens (a multiple of the key group) are held in 4
     bits: K [H_kv, n, r_k], V [H_kv, n, r_v] -> arrays of the same shapes, the prefix replaced by its
     quantise-dequantise round trip, the rest untouched."""
@@ -98,8 +104,8 @@ def quantized_view(K, V, n_quant: int, group_tokens: int = GROUP_TOKENS):
     Kq, Vq = np.array(K, dtype=np.float64), np.array(V, dtype=np.float64)
     for h in range(K.shape[0]):
         if n_quant:
-            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens))
-            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant]))
+            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens, bits))
+            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant], bits))
     return Kq, Vq
 
 
@@ -114,19 +120,19 @@ def quantized_cache_bytes(n_elements, bits: int, group: int, meta_bits_per_group
     return n_elements * (bits + meta_bits_per_group / group) / 8.0
 
 
-def bits_per_element_q4(r_k: int, r_v: int, group_tokens: int = GROUP_TOKENS):
-    """Bits per cached scalar of this build's 4-bit format, without layout padding: keys in groups of 64 (or 128)
-    tokens, values in groups of r_v channels, 32 bits of metadata (fp16 scale, fp16 zero) per group."""
-    return 4 + 32 / group_tokens, 4 + 32 / r_v
+def bits_per_element_q4(r_k: int, r_v: int, group_tokens: int = GROUP_TOKENS, bits: int = 4):
+    """Bits per cached scalar of this build's 4-bit (3-bit) format, without layout padding: keys in groups of 64 (or
+    128) tokens, values in groups of r_v channels, 32 bits of metadata (fp16 scale, fp16 zero) per group."""
+    return bits + 32 / group_tokens, bits + 32 / r_v
 
 
 def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_slopes=None,
-                               group_tokens: int = GROUP_TOKENS):
+                               group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """Generation-phase attention (Eq. 3 in the rank-r space) of one new token per sequence over a cache whose
     first n_quant[b] tokens are quantised: plain attention over the dequantised values (with the ALiBi bias of the
     MPT models when slopes are given: it involves positions only, so quantisation does not touch it).
     q_r [B, H, r_k]; K_list[b] [H_kv, n_b, r_k]; V_list[b] [H_kv, n_b, r_v]."""
-    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
+    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits) for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
     return ea_oracle.decode_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)
 

@@ -125,22 +125,28 @@ QUANT = [
      "    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)",
      "    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)", "test_key_groups_of_128_tokens"),
     ("the view of a partly quantised cache ignores the group length",
-     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens))",
-     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant]))", "test_key_groups_of_128_tokens"),
+     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], group_tokens, bits))",
+     "            Kq[h, :n_quant] = dequantize_keys(*quantize_keys(K[h, :n_quant], GROUP_TOKENS, bits))",
+     "test_key_groups_of_128_tokens"),
+    ("three-bit codes take sixteen levels",
+     "    return LEVELS if bits == 4 else 7", "    return LEVELS", "test_three_bit_codes"),
+    ("the values of a partly quantised cache stay at four bits when three are asked for",
+     "            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant], bits))",
+     "            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant]))", "test_three_bit_codes"),
     ("zero point at the group's maximum",
      "    return step.astype(np.float16), lo.astype(np.float16)", "    return step.astype(np.float16), hi.astype(np.float16)",
      "test_values_on_the_grid_round_trip_exactly"),
     ("values quantised per channel",
-     "    scale, zero = _scale_zero(V32.min(axis=1), V32.max(axis=1))\n"
-     "    return _codes(V32, scale[:, None], zero[:, None]), scale, zero",
-     "    scale, zero = _scale_zero(V32.min(axis=0), V32.max(axis=0))\n"
-     "    return _codes(V32, scale[None, :], zero[None, :]), scale, zero",
+     "    scale, zero = _scale_zero(V32.min(axis=1), V32.max(axis=1), _levels(bits))\n"
+     "    return _codes(V32, scale[:, None], zero[:, None], _levels(bits)), scale, zero",
+     "    scale, zero = _scale_zero(V32.min(axis=0), V32.max(axis=0), _levels(bits))\n"
+     "    return _codes(V32, scale[None, :], zero[None, :], _levels(bits)), scale, zero",
      "test_values_on_the_grid_round_trip_exactly"),
     ("keys quantised per token",
-     "    scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1))\n"
-     "    codes = _codes(Kg, scale[:, None, :], zero[:, None, :]).reshape(n, r)",
-     "    scale, zero = _scale_zero(Kg.min(axis=2), Kg.max(axis=2))\n"
-     "    codes = _codes(Kg, scale[:, :, None], zero[:, :, None]).reshape(n, r)",
+     "    scale, zero = _scale_zero(Kg.min(axis=1), Kg.max(axis=1), _levels(bits))\n"
+     "    codes = _codes(Kg, scale[:, None, :], zero[:, None, :], _levels(bits)).reshape(n, r)",
+     "    scale, zero = _scale_zero(Kg.min(axis=2), Kg.max(axis=2), _levels(bits))\n"
+     "    codes = _codes(Kg, scale[:, :, None], zero[:, :, None], _levels(bits)).reshape(n, r)",
      "test_key_groups_are_64_tokens_long"),
     ("value dequantisation with the zero inside the scale",
      "    return scale.astype(np.float64)[:, None] * codes.astype(np.float64) + zero.astype(np.float64)[:, None]",

@@ -370,3 +370,52 @@ def test_prefill_attention_over_a_partly_quantised_cache():
     # with 128-token key groups the third chunk sees one group, not two
     ch128 = oq.chunked_prefill_quantized(qa[:256], Ka, Va, 128, d_h, group_tokens=128)
     assert np.allclose(ch128[128:], oq.prefill_attention_quantized(qa[None, 128:], [Ka], [Va], [128], d_h, 128)[0], atol=1e-13)
+
+
+def test_three_bit_codes():
+    """bits = 3 (the other precision of the paper's Eigen Attention rows): eight levels per group.  Codes 0..7 with
+    both ends taken, error within half a step of the group's own scale (seven steps between minimum and maximum),
+    values on an eight-level grid reproduced exactly, coarser than four bits by the ratio of the steps, and attention
+    over the view is attention over the dequantised values."""
+    g = synth.rng(122)
+    K = np.float32(synth.gaussian(g, (128, 12))).astype(np.float64)
+    c, s, z = oq.quantize_keys(K, 64, bits=3)
+    assert c.max() == 7 and c.min() == 0 and s.shape == (2, 12)
+    Kg = K.reshape(2, 64, 12)
+    span = (Kg.max(axis=1) - Kg.min(axis=1))
+    assert np.allclose(s.astype(np.float64), span / 7, rtol=2 ** -10)
+    for grp in range(2):
+        sel = slice(64 * grp, 64 * grp + 64)
+        assert np.all(c[sel][Kg[grp].argmax(axis=0), np.arange(12)] == 7) and np.all(c[sel][Kg[grp].argmin(axis=0), np.arange(12)] == 0)
+    err = np.abs(oq.dequantize_keys(c, s, z) - K).reshape(2, 64, 12)
+    assert np.all(err <= 0.5 * s.astype(np.float64)[:, None, :] * (1 + 2e-3) + np.abs(z.astype(np.float64) - Kg.min(axis=1))[:, None, :])
+    e4 = np.abs(oq.dequantize_keys(*oq.quantize_keys(K, 64)) - K)
+    assert 1.7 < err.mean() / e4.mean() < 2.6                     # steps 15/7 times as long
+    V = np.float32(synth.gaussian(g, (40, 24))).astype(np.float64)
+    cv, sv, zv = oq.quantize_values(V, bits=3)
+    assert cv.max() == 7 and np.all(cv.max(axis=1) == 7) and np.all(cv.min(axis=1) == 0)
+    assert np.all(np.abs(oq.dequantize_values(cv, sv, zv) - V) <= 0.5 * sv.astype(np.float64)[:, None] * (1 + 2e-3) + 2e-3)
+    # an eight-level grid round-trips; a sixteen-level one does not fit
+    lo, step = np.float16(g.standard_normal(12)).astype(np.float64), 2.0 ** g.integers(-5, 1, size=12)
+    grid = lo + step * g.integers(0, 8, size=(64, 12))
+    grid[0], grid[1] = lo, lo + 7 * step
+    assert np.array_equal(oq.dequantize_keys(*oq.quantize_keys(grid, 64, bits=3)), grid)
+    grid16 = lo + step * g.integers(0, 16, size=(64, 12))
+    grid16[0], grid16[1] = lo, lo + 15 * step
+    assert not np.array_equal(oq.dequantize_keys(*oq.quantize_keys(grid16, 64, bits=3)), grid16)
+    # attention: brute force over hand-dequantised 3-bit values
+    H, r_k, r_v, d_h, n = 2, 12, 6, 16, 150
+    Kc, Vc = [synth.gaussian(g, (1, n, r_k))], [synth.gaussian(g, (1, n, r_v))]
+    q = synth.gaussian(g, (1, H, r_k))
+    got = oq.decode_attention_quantized(q, Kc, Vc, [128], d_h, bits=3)
+    ck, sk, zk = oq.quantize_keys(Kc[0][0, :128], 64, bits=3)
+    cv, sv, zv = oq.quantize_values(Vc[0][0, :128], bits=3)
+    keys = np.concatenate([sk.astype(np.float64)[np.arange(128) // 64] * ck + zk.astype(np.float64)[np.arange(128) // 64], Kc[0][0, 128:]])
+    vals = np.concatenate([sv.astype(np.float64)[:, None] * cv + zv.astype(np.float64)[:, None], Vc[0][0, 128:]])
+    for h in range(H):
+        sc = keys @ q[0, h] / np.sqrt(d_h)
+        w = np.exp(sc - sc.max())
+        assert np.allclose(got[0, h], (w / w.sum()) @ vals, rtol=0, atol=1e-12)
+    assert not np.allclose(got, oq.decode_attention_quantized(q, Kc, Vc, [128], d_h), atol=1e-3)
+    # the table's 3-bit rows in its own accounting; this build's format at 3 bits
+    assert oq.bits_per_element_q4(80, 80, 128, bits=3) == (3.25, 3.4)
