@@ -52,6 +52,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--q4-key-group", type=int, default=64, choices=[64, 128],
                     help="-q4 workloads: tokens that share a key scale (128 needs --page-tokens 128 or more)")
+    ap.add_argument("--q4-bits", type=int, default=4, choices=[4, 3], help="-q4 workloads: width of a code")
     ap.add_argument("--workload", default="cfg3", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg3-rope", "cfg5-rope", "cfg4-rope", "cfg2-q4", "cfg3-q4",
                              "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o", "cfg2-rope-h2o", "cfg3-rope-h2o", "cfg4-q4"])
     ap.add_argument("--prefill-chunk", type=int, default=2048,
@@ -304,7 +305,7 @@ def cpu_oracle_decode(streams, d_head, rope_u=None, h2o=False, positions=None):
 
 
 def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_tokens: int, rope: bool = False,
-                         key_group: int = 64):
+                         key_group: int = 64, bits: int = 4):
     """The oracle of the quantised-cache step on `n_streams` (sequence, head) streams: codes and scales are
     prepared outside the timed region (they are the cache's content); timed is what a generation step does with
     them, dequantisation of the 4-bit part and fp64 attention over it and the 16-bit newest page."""
@@ -318,8 +319,8 @@ def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_t
     nq = n_ctx - page_tokens
     K1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
     V1 = synth.round_to_bf16(g.standard_normal((heads, n_ctx, r), dtype=np.float32)).astype(np.float64)
-    kq = [oq.quantize_keys(K1[h, :nq], key_group) for h in range(heads)]
-    vq = [oq.quantize_values(V1[h, :nq]) for h in range(heads)]
+    kq = [oq.quantize_keys(K1[h, :nq], key_group, bits) for h in range(heads)]
+    vq = [oq.quantize_values(V1[h, :nq], bits) for h in range(heads)]
     q = g.standard_normal((n_seq, heads, d_head if rope else r))
     U = synth.orthonormal_basis(g, d_head, r) if rope else None
 
@@ -334,7 +335,7 @@ def cpu_oracle_decode_q4(n_streams: int, n_ctx: int, r: int, d_head: int, page_t
 
     dt = _timed_single_thread(work)
     tiles = nq // 64
-    cache_bytes = n_seq * heads * (tiles * (2 * 32 * ((r + 15) // 16 * 16) + 128 * ((r + 31) // 32) * 64 // key_group + 256)
+    cache_bytes = n_seq * heads * (tiles * (2 * 8 * bits * ((r + 15) // 16 * 16) + 128 * ((r + 31) // 32) * 64 // key_group + 256)
                                    + page_tokens * 2 * r * 2)      # what the GPU kernels would stream
     return {"value": round(cache_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"dequantisation and {'rotary ' if rope else ''}decode attention of {n_seq * heads} of one layer's 512 (sequence, head) "
@@ -477,7 +478,8 @@ def bench_decode(args, torch, ea, synth):
     L, B, n, P = args.layers, s.batch, s.n_ctx, args.page_tokens
     H, Hkv, d = s.n_heads, s.n_kv_heads, s.d_model
     ranks = synth.cfg5_layer_ranks(L) if base_name == "cfg5" else tuple((s.r_k, s.r_v) for _ in range(L))
-    descs = [ea.LayerDesc(d, H, Hkv, s.d_head, rk, rv, ea.EA_BF16, P, args.q4_key_group if q4 else 0) for rk, rv in ranks]
+    descs = [ea.LayerDesc(d, H, Hkv, s.d_head, rk, rv, ea.EA_BF16, P, args.q4_key_group if q4 else 0,
+                          args.q4_bits if q4 else 0) for rk, rv in ranks]
     max_pages = n // P
     pool_pages = B * max_pages
 
@@ -513,10 +515,11 @@ def bench_decode(args, torch, ea, synth):
             # a unit = what repeats inside a kv head's part of a page: a tile block, or (key groups of 128 tokens) a
             # pair of K tile blocks, [codes][the pair's scales][codes]
             tpg = 2 if dc.q4_key_group == 128 else 1
-            k_codes, k_scales = 32 * lay.r_k_pad, lay.k_tile_bytes - 32 * lay.r_k_pad
+            k_scales = 128 * ((lay.r_k_pad + 31) // 32)
+            k_codes = lay.k_tile_bytes - k_scales
             for pool, unit_bytes, units, sc_off, sc_bytes in (
                     (kq_pool, tpg * k_codes + k_scales, Hkv * tpp // tpg, k_codes, k_scales),
-                    (vq_pool, lay.v_tile_bytes, Hkv * tpp, 32 * lay.r_v_pad, lay.v_tile_bytes - 32 * lay.r_v_pad)):
+                    (vq_pool, lay.v_tile_bytes, Hkv * tpp, lay.v_tile_bytes - 256, 256)):
                 pool.random_(0, 256, generator=gen)
                 blocks = pool.view(pool_pages, units, unit_bytes)
                 sz = torch.empty((pool_pages, units, sc_bytes // 2), dtype=torch.float16, device=dev)
@@ -724,7 +727,7 @@ def bench_decode(args, torch, ea, synth):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload} decode: Llama-2-7B-shaped, {L} layers resident, B={B}, n={n}, "
                                f"H={H}, H_kv={Hkv}, d_h={s.d_head}, {rank_note}, "
-                               + (f"cache in 4-bit groups (keys per channel over {args.q4_key_group} tokens, values per token; fp16 "
+                               + (f"cache in {args.q4_bits}-bit groups (keys per channel over {args.q4_key_group} tokens, values per token; fp16 "
                                   "scales and zeros) except the newest page of each sequence, which is bf16; "
                                   if q4 else "bf16 ") +
                                f"paged cache (page {P} tokens, pages in random order), "
@@ -814,7 +817,7 @@ def bench_decode(args, torch, ea, synth):
 
     if not args.no_cpu and q4:
         result["cpu_baseline"] = cpu_oracle_decode_q4(512 // (32 if rope else 8), n, ranks[0][0], s.d_head,
-                                                      P, rope=rope, key_group=args.q4_key_group)
+                                                      P, rope=rope, key_group=args.q4_key_group, bits=args.q4_bits)
     elif not args.no_cpu:
         # streams of the first resident layer, copied back from the device (those the parity check already holds first)
         l = layers[0]

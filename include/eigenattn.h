@@ -63,6 +63,7 @@ typedef struct ea_layer_desc {
   int32_t page_tokens;   /* tokens per cache page: multiple of 64 (EA_BF16), of 16 (EA_F32) */
   int32_t q4_key_group;  /* 4-bit cache only: tokens that share a key scale, 64 (also meant by 0) or 128;
                             with 128, page_tokens must be a multiple of 128.  Ignored by every other call. */
+  int32_t q4_bits;       /* 4-bit cache calls only: width of a code, 4 (also meant by 0) or 3                        */
 } ea_layer_desc;
 
 /* Geometry of the two page pools of a layer (K and V are separate pools, page p
@@ -309,7 +310,9 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
  * layers only: 4 bits; a key scale covers one channel over the 64 tokens of a cache
  * tile or (desc.q4_key_group = 128, the group size of the paper's 4-bit rows) over the
  * 128 tokens of two neighbouring tiles; a value scale covers one token over its r_v
- * channels.  3-bit codes are NOT implemented.  The paper gives no
+ * channels.  desc.q4_bits = 3 selects 3-bit codes (eight levels: 7 in place of 15 below) for
+ * ea_quantize_pages_q4, ea_dequantize_pages_q4, ea_decode_attn_q4 and ea_decode_attn_alibi_q4;
+ * ea_decode_attn_rope_q4 and ea_prefill_attn_q4 take 4-bit codes only (EA_ERR_SHAPE otherwise).  The paper gives no
  * rounding rule; the one used here is
  *   zero = fp16(lo), scale = fp16((hi - lo) / 15)   (lo / hi = minimum / maximum of
  *          the group, clamped to +-65504; quotient in float),
@@ -331,8 +334,8 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
 typedef struct ea_q4_layout {
   int32_t r_k_pad;         /* multiple of 8  */
   int32_t r_v_pad;         /* multiple of 16 */
-  int64_t k_tile_bytes;    /* of a K tile block WITH scales: 32 * r_k_pad + 128 * ceil(r_k_pad / 32) */
-  int64_t v_tile_bytes;    /* 32 * r_v_pad + 256                      */
+  int64_t k_tile_bytes;    /* of a K tile block WITH scales: 32 * r_k_pad + 128 * ceil(r_k_pad / 32) (3 bits: 24 * r_k_pad + ..) */
+  int64_t v_tile_bytes;    /* 32 * r_v_pad + 256 (3 bits: 768 per pair of 16-channel blocks + 512 for an odd one, + 256) */
   int64_t k_page_bytes;    /* n_kv_heads * (page_tokens / 64) * k_tile_bytes with key groups of 64 tokens; with 128,
                               every second tile block is 128 * ceil(r_k_pad / 32) bytes shorter */
   int64_t v_page_bytes;
@@ -350,6 +353,17 @@ EA_API int64_t ea_q4_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t
 EA_API int64_t ea_q4_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
 EA_API int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
 EA_API int64_t ea_q4_v_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page);
+
+/* The same for 3-bit codes (desc.q4_bits = 3; the *_code_pos functions above return -1 then, these return -1
+ * otherwise): a code is stored in two parts, its low two bits and its high bit.  Returns the BIT offset from the
+ * start of the pool of the low two bits and writes that of the high bit to *hi_bit_pos.  A lane's four groups of
+ * eight codes share a 12-byte unit: two dwords of low bits, one of high bits (8 bytes for the two groups of an odd
+ * last value channel block).  K tile block: 24 * r_k_pad bytes of codes; V tile block: 768 per pair of 16-channel
+ * blocks + 512 for an odd last one.  The scale positions are given by ea_q4_k_scale_pos / ea_q4_v_scale_pos. */
+EA_API int64_t ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                                int32_t channel, int64_t* hi_bit_pos);
+EA_API int64_t ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                                int32_t channel, int64_t* hi_bit_pos);
 
 /* Quantise n_pages full pages: page dev_src_pages[i] of the bfloat16 pools is written
  * as page dev_dst_pages[i] of the 4-bit pools (all kv heads, keys and values).  The

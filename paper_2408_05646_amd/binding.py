@@ -22,6 +22,7 @@ __all__ = [
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
+    "q3_k_code_pos", "q3_v_code_pos",
 ]
 
 EA_F32, EA_BF16 = 0, 1
@@ -36,6 +37,7 @@ EXPORTED_SYMBOLS = (
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
+    "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
 
 STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
@@ -48,9 +50,11 @@ class EigenAttnError(RuntimeError):
 
 
 class LayerDesc(ctypes.Structure):
-    # q4_key_group (last, optional): tokens that share a key scale in the 4-bit cache, 64 (also meant by 0) or 128
+    # q4_key_group (optional): tokens that share a key scale in the 4-bit cache, 64 (also meant by 0) or 128;
+    # q4_bits (optional): width of a code of that cache, 4 (also meant by 0) or 3
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("d_model", "n_heads", "n_kv_heads", "d_head", "r_k", "r_v", "dtype", "page_tokens", "q4_key_group")]
+                ("d_model", "n_heads", "n_kv_heads", "d_head", "r_k", "r_v", "dtype", "page_tokens", "q4_key_group",
+                 "q4_bits")]
 
     def __repr__(self):
         return "LayerDesc(" + ", ".join(f"{n}={getattr(self, n)}" for n, _ in self._fields_) + ")"
@@ -136,6 +140,9 @@ def load_library():
         f.argtypes = [D, I32, I32, I32, I32]
     lib.ea_q4_v_scale_pos.restype = I64
     lib.ea_q4_v_scale_pos.argtypes = [D, I32, I32, I32]
+    for f in (lib.ea_q3_k_code_pos, lib.ea_q3_v_code_pos):
+        f.restype = I64
+        f.argtypes = [D, I32, I32, I32, I32, P(I64)]
     lib.ea_quantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
     lib.ea_dequantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
     lib.ea_decode_q4_workspace_bytes.restype = I64
@@ -574,6 +581,19 @@ def q4_k_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: in
 
 def q4_v_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:
     return int(load_library().ea_q4_v_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel))
+
+
+def q3_k_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int):
+    """3-bit codes (desc.q4_bits = 3): (bit offset of the code's low two bits, bit offset of its high bit)."""
+    hi = ctypes.c_int64(-1)
+    lo = int(load_library().ea_q3_k_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, ctypes.byref(hi)))
+    return lo, int(hi.value)
+
+
+def q3_v_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int):
+    hi = ctypes.c_int64(-1)
+    lo = int(load_library().ea_q3_v_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, ctypes.byref(hi)))
+    return lo, int(hi.value)
 
 
 def q4_k_scale_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:

@@ -10,12 +10,13 @@ static int validate_q4(const ea_layer_desc* desc) {
 }
 
 static Q4Geo q4_geo_of(const ea_layer_desc* desc) {
-  return make_q4_geo(desc->r_k, desc->r_v, desc->n_kv_heads, desc->page_tokens, desc->q4_key_group);
+  return make_q4_geo(desc->r_k, desc->r_v, desc->n_kv_heads, desc->page_tokens, desc->q4_key_group, desc->q4_bits);
 }
 
 static bool q4_pos_args_ok(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
-                           int32_t channel, bool keys) {
+                           int32_t channel, bool keys, int32_t bits = 4) {
   if (validate_q4(desc) != EA_OK) return false;
+  if (bits != 0 && (desc->q4_bits == 3) != (bits == 3)) return false;      // the wrong family of position functions
   return page >= 0 && kv_head >= 0 && kv_head < desc->n_kv_heads && token_in_page >= 0 &&
          token_in_page < desc->page_tokens && channel >= 0 && channel < (keys ? desc->r_k : desc->r_v);
 }
@@ -51,9 +52,29 @@ int64_t ea_q4_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_hea
          q4_nibble_shift(channel & 7);
 }
 
+int64_t ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                         int32_t channel, int64_t* hi_bit_pos) {
+  if (!hi_bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true, 3)) return -1;
+  const Q4Geo q = q4_geo_of(desc);
+  const Q3Pos p = q3_k_pos(token_in_page % kTile, channel);
+  const int64_t t0 = k_tile0(q, page, kv_head, token_in_page);
+  *hi_bit_pos = (t0 + p.hi_byte) * 8 + p.hi_bit;
+  return (t0 + p.lo_byte) * 8 + p.lo_bit;
+}
+
+int64_t ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                         int32_t channel, int64_t* hi_bit_pos) {
+  if (!hi_bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, false, 3)) return -1;
+  const Q4Geo q = q4_geo_of(desc);
+  const Q3Pos p = q3_v_pos(q, token_in_page % kTile, channel);
+  const int64_t t0 = v_tile0(q, page, kv_head, token_in_page);
+  *hi_bit_pos = (t0 + p.hi_byte) * 8 + p.hi_bit;
+  return (t0 + p.lo_byte) * 8 + p.lo_bit;
+}
+
 int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
                           int32_t channel) {
-  if (!q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true)) return -1;
+  if (!q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true, 0)) return -1;
   const Q4Geo q = q4_geo_of(desc);
   return (int64_t)page * q.k_page + (int64_t)kv_head * q.k_slab + q4_k_group_scales_off(q, token_in_page / kTile) +
          q4_k_scale_off(channel);
@@ -69,7 +90,7 @@ int64_t ea_q4_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_hea
 }
 
 int64_t ea_q4_v_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page) {
-  if (!q4_pos_args_ok(desc, page, kv_head, token_in_page, 0, false)) return -1;
+  if (!q4_pos_args_ok(desc, page, kv_head, token_in_page, 0, false, 0)) return -1;
   const Q4Geo q = q4_geo_of(desc);
   return v_tile0(q, page, kv_head, token_in_page) + q4_v_scale_off(q, token_in_page % kTile);
 }
@@ -194,6 +215,7 @@ int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r, const voi
       !aligned16(dev_v_pool) || !aligned16(dev_out))
     return EA_ERR_ALIGN;
   if (!dev_ws || !aligned16(dev_ws) || ws_bytes < ea_prefill_q4_workspace_bytes(desc, B, n)) return EA_ERR_WORKSPACE;
+  if (desc->q4_bits == 3) return EA_ERR_SHAPE;        // the prefill kernel expands 4-bit codes only
   const Geo gq = make_geo(desc, max_q4_pages, q4_pool_pages);
   const Geo gt = make_geo(desc, max_tail_pages, pool_pages);
   clear_stale_error();
@@ -219,6 +241,7 @@ int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const 
   if (B <= 0 || max_q4_pages <= 0 || q4_pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
   if (!(rope_base > 1.0) || !(rope_base < 1e30)) return EA_ERR_ARG;
   if (desc->r_k > desc->d_head || (desc->d_head != 64 && desc->d_head != 128)) return EA_ERR_SHAPE;
+  if (desc->q4_bits == 3) return EA_ERR_SHAPE;        // the rotary kernel expands 4-bit codes only
   if (!aligned16(dev_q) || !aligned16(dev_u_k) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool) ||
       !aligned16(dev_out) || (tail && (!aligned16(dev_k_pool) || !aligned16(dev_v_pool))))
     return EA_ERR_ALIGN;

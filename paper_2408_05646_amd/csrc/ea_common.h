@@ -39,6 +39,7 @@ inline int validate_desc(const ea_layer_desc* d) {
     if (d->n_heads / d->n_kv_heads > 16) return EA_ERR_SHAPE;
     if (d->q4_key_group != 0 && d->q4_key_group != 64 && d->q4_key_group != 128) return EA_ERR_ARG;
     if (d->q4_key_group == 128 && d->page_tokens % 128 != 0) return EA_ERR_SHAPE;
+    if (d->q4_bits != 0 && d->q4_bits != 4 && d->q4_bits != 3) return EA_ERR_ARG;
   } else {
     if (d->r_k > 256 || d->r_v > 256) return EA_ERR_SHAPE;
     if (d->page_tokens % 16 != 0) return EA_ERR_SHAPE;

@@ -38,8 +38,10 @@ struct DecodeQ4Args {
   const int32_t* tail_len;
 };
 
-template <int KS, int NCB, bool ALIBI>
+// BITS = 4 or 3: the width of a code (see ea_q4.h for the two packings; everything after the unpacking is the same).
+template <int KS, int NCB, bool ALIBI, int BITS = 4>
 __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
+  constexpr bool B3 = BITS == 3;
   __shared__ union {
     MergeSmemQ4<NCB> q4;
     DecodeSmem<KS, NCB, 2, 0> tail;
@@ -104,11 +106,14 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   f16x8 negoff, ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;
+    if (B3) negoff[j] = (_Float16)(-1024.0f / (float)(1 << (2 * (j >> 1))));       // 1024, 256, 64, 16 per element pair
+    else negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;
     ones[j] = (_Float16)1.0f;
   }
   uint32_t magic1024 = 0x64006400u, magic64 = 0x54005400u;
   asm volatile("" : "+v"(magic1024), "+v"(magic64));   // keep them in vector registers
+  Q3Magic mg3 = {{0x64006400u, 0x5C005C00u, 0x54005400u, 0x4C004C00u}};
+  if constexpr (B3) asm volatile("" : "+v"(mg3.m[0]), "+v"(mg3.m[1]), "+v"(mg3.m[2]), "+v"(mg3.m[3]));
 
   f32x4 acc[NCB];
 #pragma unroll
@@ -117,11 +122,20 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   f32x4 corr = {0.f, 0.f, 0.f, 0.f};   // every row: sum_t p zero_t - sum_t offset (p scale)_t
   float m = -INFINITY;
 
-  u32x4 kc[KS];
+  u32x4 kc[KS];                        // 3-bit codes: dwords A, B, C of the unit in [0..2]
   f16x8 ksc[KS], kzr[KS];
   u32x4 vc[NVP > 0 ? NVP : 1];
-  u32x2 vcl = {0u, 0u};
+  u32x2 vcl = {0u, 0u};                // 3-bit codes: A, C of the two-group unit
   f16x8 vsc[2], vzr[2];
+  auto load_unit = [&](const uint8_t* p) -> u32x4 {      // a 16-byte unit, or the 12 bytes of a 3-bit unit
+    if constexpr (B3) {
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
+      return u32x4{__builtin_nontemporal_load(w), __builtin_nontemporal_load(w + 1), __builtin_nontemporal_load(w + 2), 0u};
+    } else {
+      return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    }
+  };
+  constexpr int kUnit = B3 ? 12 : 16, kRun = 64 * kUnit;   // bytes of a lane's unit and of a run of 64 of them
 
   struct Pos {
     int tile, lp, tin;
@@ -151,8 +165,8 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
     for (int kk = 0; kk < KS; ++kk) {
       // lanes of a quad the last k-step does not have re-read quad 0's unit; their query channels are zero
       const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
-      const int off = kk * 1024 + (past ? col : lane) * 16;
-      kc[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+      const int off = kk * kRun + (past ? col : lane) * kUnit;
+      kc[kk] = load_unit(base + off);
       const uint8_t* sp = scales + (kk * 4 + quad) * 32;
       ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
       kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
@@ -161,19 +175,29 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   auto load_v = [&](const Pos& p, int page) {
     const uint8_t* base = a.vq_pool + (int64_t)page * qg.v_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.v_tile;
 #pragma unroll
-    for (int pp = 0; pp < NVP; ++pp)
-      vc[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + pp * 1024 + lane * 16));
-    if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * 1024 + lane * 8));
-    const uint8_t* sp = base + NCB * 512;
+    for (int pp = 0; pp < NVP; ++pp) vc[pp] = load_unit(base + pp * kRun + lane * kUnit);
+    if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * kRun + lane * 8));
+    const uint8_t* sp = base + qg.v_codes;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       vsc[u] = *reinterpret_cast<const f16x8*>(sp + (u * 4 + quad) * 16);
       vzr[u] = *reinterpret_cast<const f16x8*>(sp + 128 + (u * 4 + quad) * 16);
     }
   };
-  auto v_dword = [&](int cb, int u) -> uint32_t {
-    if (VODD && cb == NCB - 1) return vcl[u];
-    return vc[cb >> 1][(cb & 1) * 2 + u];
+  // the A operands "offset + code": 16-token block tb of k-step kk; 32-token group u of channel block cb
+  auto k_frag = [&](int kk, int tb) -> f16x8 {
+    if constexpr (B3) return unpack_q3(q3_lo_of(kc[kk][0], kc[kk][1], tb), q3_hi_of(kc[kk][2], tb), mg3);
+    else return unpack_q4(kc[kk][tb], magic1024, magic64);
+  };
+  auto v_frag = [&](int cb, int u) -> f16x8 {
+    if constexpr (B3) {
+      if (VODD && cb == NCB - 1) return unpack_q3(vcl[0] >> (8 * u), q3_hi_of(vcl[1], u), mg3);
+      const int k = (cb & 1) * 2 + u;
+      return unpack_q3(q3_lo_of(vc[cb >> 1][0], vc[cb >> 1][1], k), q3_hi_of(vc[cb >> 1][2], k), mg3);
+    } else {
+      if (VODD && cb == NCB - 1) return unpack_q4(vcl[u], magic1024, magic64);
+      return unpack_q4(vc[cb >> 1][(cb & 1) * 2 + u], magic1024, magic64);
+    }
   };
 
   bool have = cur.tile < t_end;
@@ -208,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
     for (int tb = 0; tb < 4; ++tb) {
       s[tb] = sb;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(unpack_q4(kc[kk][tb], magic1024, magic64), qs[kk], s[tb]);
+      for (int kk = 0; kk < KS; ++kk) s[tb] = mfma16h(k_frag(kk, tb), qs[kk], s[tb]);
     }
     // unconditional (a wave's last tile re-reads itself): a load behind a branch would cost a second copy of the
     // registers for the path on which nothing is loaded
@@ -268,7 +292,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(unpack_q4(v_dword(cb, u), magic1024, magic64), ps[u], acc[cb]);
+      for (int u = 0; u < 2; ++u) acc[cb] = mfma16h(v_frag(cb, u), ps[u], acc[cb]);
     }
     load_v(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
     cur = nxt;
@@ -320,8 +344,14 @@ template <int KS, int NCB>
 static void launch_q4(const DecodeQ4Args& a, int32_t B, hipStream_t st) {
   const int extra = a.has_tail ? (B + a.n_splits - 1) / a.n_splits : 0;
   const dim3 grid(a.g.n_kv_heads, a.n_splits, B + extra);
-  if (a.alibi) decode_q4_kernel<KS, NCB, true><<<grid, dim3(256), 0, st>>>(a);
-  else decode_q4_kernel<KS, NCB, false><<<grid, dim3(256), 0, st>>>(a);
+  if (a.qg.bits == 3) {
+    if (a.alibi) decode_q4_kernel<KS, NCB, true, 3><<<grid, dim3(256), 0, st>>>(a);
+    else decode_q4_kernel<KS, NCB, false, 3><<<grid, dim3(256), 0, st>>>(a);
+  } else if (a.alibi) {
+    decode_q4_kernel<KS, NCB, true><<<grid, dim3(256), 0, st>>>(a);
+  } else {
+    decode_q4_kernel<KS, NCB, false><<<grid, dim3(256), 0, st>>>(a);
+  }
 }
 
 template <int KS>

@@ -21,6 +21,15 @@
 //   [codes 0][scales 0+1][codes 1] [codes 2][scales 2+3][codes 3] ...
 // Inside a dword, element e (channel / token slot e of the 8) sits in nibble e/2 if e is even, 4 + e/2 if odd:
 // the kernel's unpacking puts nibbles i and i+4 into the two halves of one register.
+//
+// 3-bit codes (bits = 3): the same order of tokens, channels and lanes, but a lane's unit holds its four groups of
+// eight codes (K: the four 16-token blocks tb; V: the fragments (cb = 2p, u = 0), (2p, 1), (2p+1, 0), (2p+1, 1)) in
+// 12 bytes instead of 16: dword A = the low two bits of groups 0 and 1, dword B = those of groups 2 and 3, dword C =
+// the high bits of all four.  Element e = 2i + h of group k has its low bits at bit 16h + 8(k & 1) + 2i of A (k < 2)
+// or B, its high bit at bit 16h + {0, 1, 8, 9}[k] + 2i of C -- so that, after one shift per group, a mask-and-or
+// per pair of elements puts the low bits, and a second one the high bit right above them, into the mantissa of a
+// half-precision number (see unpack_q3).  An odd last value channel block has units of two groups: A, then C.
+//   K codes: 48 * r_k_pad / 2 bytes;  V codes: 768 per pair of channel blocks + 512 for an odd last one.
 #pragma once
 #include "ea_common.h"
 
@@ -32,7 +41,9 @@ struct Q4Geo {
   int32_t ncb;             // 16-channel blocks of a value row: r_v_pad / 16
   int32_t tiles_per_page;
   int32_t tpg;             // tiles per key group: 1 (64 tokens) or 2 (128 tokens)
-  int32_t k_codes;         // bytes of the codes of a K tile block: nch * 256
+  int32_t bits;            // 4 or 3
+  int32_t v_codes;         // bytes of the codes of a V tile block
+  int32_t k_codes;         // bytes of the codes of a K tile block: nch * 256 (4 bits), nch * 192 (3 bits)
   int32_t k_scales;        // bytes of the scales and zeros of a key group: ks * 128
   int64_t k_tile, v_tile;  // bytes of a tile block (K: of one that carries scales)
   int64_t k_slab;          // bytes of the K tile blocks of one kv head in a page
@@ -40,17 +51,19 @@ struct Q4Geo {
 };
 
 __host__ __device__ inline Q4Geo make_q4_geo(int32_t r_k, int32_t r_v, int32_t n_kv_heads, int32_t page_tokens,
-                                             int32_t key_group) {
+                                             int32_t key_group, int32_t bits = 4) {
   Q4Geo q;
   q.nch = (r_k + 7) / 8;
   q.ks = (q.nch + 3) / 4;
   q.ncb = (r_v + 15) / 16;
   q.tiles_per_page = page_tokens / kTile;
   q.tpg = key_group == 128 ? 2 : 1;
-  q.k_codes = q.nch * 256;
+  q.bits = bits == 3 ? 3 : 4;
+  q.k_codes = q.nch * (q.bits == 3 ? 192 : 256);
+  q.v_codes = q.bits == 3 ? (q.ncb / 2) * 768 + (q.ncb & 1) * 512 : q.ncb * 512;
   q.k_scales = q.ks * 128;
   q.k_tile = (int64_t)q.k_codes + q.k_scales;
-  q.v_tile = (int64_t)q.ncb * 512 + 256;
+  q.v_tile = (int64_t)q.v_codes + 256;
   q.k_slab = (int64_t)q.tiles_per_page * q.k_codes + (int64_t)(q.tiles_per_page / q.tpg) * q.k_scales;
   q.k_page = q.k_slab * n_kv_heads;
   q.v_page = q.v_tile * q.tiles_per_page * n_kv_heads;
@@ -87,7 +100,33 @@ __host__ __device__ inline int32_t q4_v_dword_off(const Q4Geo& q, int32_t tt, in
 }
 __host__ __device__ inline int32_t q4_v_scale_off(const Q4Geo& q, int32_t tt) {
   const int32_t u = tt >> 5, t32 = tt & 31, half = t32 >> 4, quad = (t32 & 15) >> 2;
-  return q.ncb * 512 + ((u * 4 + quad) * 8 + half * 4 + (t32 & 3)) * 2;          // the zero is 128 bytes further
+  return q.v_codes + ((u * 4 + quad) * 8 + half * 4 + (t32 & 3)) * 2;            // the zero is 128 bytes further
+}
+
+// ---- 3-bit codes: where the two parts of a code sit.  Both return byte offsets of a dword inside the tile block
+// and the bit inside that dword: the low two bits of the code, and its high bit.
+struct Q3Pos {
+  int32_t lo_byte, lo_bit, hi_byte, hi_bit;
+};
+__host__ __device__ inline Q3Pos q3_in_unit(int32_t unit_off, int32_t group, int32_t e, bool two_groups) {
+  const int32_t h = e & 1, i = e >> 1;
+  Q3Pos p;
+  p.lo_byte = unit_off + (two_groups ? 0 : (group >> 1) * 4);
+  p.lo_bit = 16 * h + 8 * (group & 1) + 2 * i;
+  p.hi_byte = unit_off + (two_groups ? 4 : 8);
+  p.hi_bit = 16 * h + (group & 1) + 8 * (group >> 1) + 2 * i;
+  return p;
+}
+__host__ __device__ inline Q3Pos q3_k_pos(int32_t tt, int32_t c) {
+  const int32_t kk = c >> 5, quad = (c >> 3) & 3, tb = tt >> 4, t = tt & 15;
+  return q3_in_unit(kk * 768 + (quad * 16 + t) * 12, tb, c & 7, false);
+}
+__host__ __device__ inline Q3Pos q3_v_pos(const Q4Geo& q, int32_t tt, int32_t c) {
+  const int32_t u = tt >> 5, t32 = tt & 31, half = t32 >> 4, quad = (t32 & 15) >> 2;
+  const int32_t slot = half * 4 + (t32 & 3);
+  const int32_t cb = c >> 4, lane = quad * 16 + (c & 15), p = cb >> 1;
+  if ((q.ncb & 1) && cb == q.ncb - 1) return q3_in_unit(p * 768 + lane * 8, u, slot, true);
+  return q3_in_unit(p * 768 + lane * 12, (cb & 1) * 2 + u, slot, false);
 }
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -118,6 +157,27 @@ __device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint3
   r[2] = (w8 & 0x000f000fu) | magic1024;
   r[3] = (w8 & 0x00f000f0u) | magic64;
   return __builtin_bit_cast(f16x8, r);
+}
+
+// Group k (0..3) of a 3-bit unit -> eight fp16 numbers offset + code, the offsets 1024, 256, 64, 16 for the element
+// pairs i = 0..3: `lo` is the dword with the group's low bits, shifted so that they sit in bits 2i, 2i+1 of each half
+// (groups 1 and 3: >> 8), `hi` the dword of high bits shifted so that the group's sit in bit 2i + 2 of each half
+// (k = 0: << 2, 1: << 1, 2: >> 6, 3: >> 7).  A field at bit s of a half word under the exponent of 2^(10-s) reads
+// 2^(10-s) + its value.
+struct Q3Magic {
+  uint32_t m[4];     // 0x64006400 (1024), 0x5C005C00 (256), 0x54005400 (64), 0x4C004C00 (16): kept in vector registers
+};
+__device__ __forceinline__ f16x8 unpack_q3(uint32_t lo, uint32_t hi, const Q3Magic& mg) {
+  u32x4 r;
+  r[0] = (hi & 0x00040004u) | ((lo & 0x00030003u) | mg.m[0]);
+  r[1] = (hi & 0x00100010u) | ((lo & 0x000c000cu) | mg.m[1]);
+  r[2] = (hi & 0x00400040u) | ((lo & 0x00300030u) | mg.m[2]);
+  r[3] = (hi & 0x01000100u) | ((lo & 0x00c000c0u) | mg.m[3]);
+  return __builtin_bit_cast(f16x8, r);
+}
+__device__ __forceinline__ uint32_t q3_lo_of(uint32_t a, uint32_t b, int k) { return (k & 2 ? b : a) >> ((k & 1) * 8); }
+__device__ __forceinline__ uint32_t q3_hi_of(uint32_t c, int k) {
+  return k == 0 ? c << 2 : k == 1 ? c << 1 : k == 2 ? c >> 6 : c >> 7;
 }
 
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,

@@ -1,7 +1,7 @@
 // Quantises whole pages of the bfloat16 rank-r cache to the 4-bit group form (keys: one scale per channel and
 // 64-token tile, or per pair of tiles; values: one scale per token).  A group with minimum lo and maximum hi gets
-// zero = fp16(lo), scale = fp16((hi - lo) / 15) and codes clip(rint((x - zero) / scale), 0, 15), all in float;
-// a scale that rounds to 0 gives code 0.  Not a hot kernel: it runs once per page, when the page is full.
+// zero = fp16(lo), scale = fp16((hi - lo) / 15) and codes clip(rint((x - zero) / scale), 0, 15), all in float
+// (7 in place of 15 for 3-bit codes); a scale that rounds to 0 gives code 0.  Not a hot kernel: it runs once per page, when the page is full.
 #include "ea_q4.h"
 
 namespace ea {
@@ -21,16 +21,16 @@ struct QuantArgs {
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __builtin_bit_cast(float, (uint32_t)b << 16); }
 
 // scale and zero of a group, as the fp16 values they are stored as
-__device__ __forceinline__ void group_scale_zero(float lo, float hi, _Float16& s, _Float16& z) {
+__device__ __forceinline__ void group_scale_zero(float lo, float hi, float levels, _Float16& s, _Float16& z) {
   lo = fminf(fmaxf(lo, -65504.f), 65504.f);
   hi = fminf(fmaxf(hi, -65504.f), 65504.f);
-  s = (_Float16)fminf((hi - lo) / 15.0f, 65504.f);
+  s = (_Float16)fminf((hi - lo) / levels, 65504.f);
   z = (_Float16)lo;
 }
 
-__device__ __forceinline__ uint32_t code_of(float x, float s, float z) {
+__device__ __forceinline__ uint32_t code_of(float x, float s, float z, float levels) {
   if (!(s > 0.f)) return 0u;
-  return (uint32_t)fminf(fmaxf(rintf((x - z) / s), 0.f), 15.f);
+  return (uint32_t)fminf(fmaxf(rintf((x - z) / s), 0.f), levels);
 }
 
 __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
@@ -42,6 +42,7 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
   const int src = a.src_pages[blockIdx.z], dst = a.dst_pages[blockIdx.z];
   if (src < 0 || src >= g.pool_pages || dst < 0 || dst >= a.q4_pool_pages) return;   // the whole workgroup leaves
   const int tid = threadIdx.x;
+  const float levels = qg.bits == 3 ? 7.0f : 15.0f;
 
   // ---- keys: x[token][channel] <- the tile in its fragment order [4 blocks][nch chunks][16 tokens][8 channels]
   {
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
           lo = fminf(lo, x[t][tid]);
           hi = fmaxf(hi, x[t][tid]);
         }
-        group_scale_zero(lo, hi, s, z);
+        group_scale_zero(lo, hi, levels, s, z);
       }
       sc[tid] = (float)s;
       zr[tid] = (float)z;
@@ -98,15 +99,37 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
         p[8] = (_Float16)zr[c];
       }
     }
-    for (int e = tid; e < qg.nch * 64; e += 256) {
-      const int tb = e & 3, t = (e >> 2) & 15, chunk = e >> 6;
-      uint32_t w = 0;
+    if (qg.bits == 3) {
+      // one 12-byte unit per (token of a block, 8-channel chunk): the four blocks' codes in three dwords
+      for (int e = tid; e < qg.nch * 16; e += 256) {
+        const int t = e & 15, chunk = e >> 4;
+        uint32_t w[3] = {0u, 0u, 0u};
+        const int unit = (chunk >> 2) * 768 + ((chunk & 3) * 16 + t) * 12;
+        for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
-      for (int ce = 0; ce < 8; ++ce) {
-        const int c = chunk * 8 + ce;
-        w |= code_of(x[tb * 16 + t][c], sc[c], zr[c]) << q4_nibble_shift(ce);
+          for (int ce = 0; ce < 8; ++ce) {
+            const int c = chunk * 8 + ce;
+            const uint32_t code = code_of(x[tb * 16 + t][c], sc[c], zr[c], levels);
+            const Q3Pos p = q3_in_unit(0, tb, ce, false);
+            w[p.lo_byte >> 2] |= (code & 3u) << p.lo_bit;
+            w[2] |= (code >> 2) << p.hi_bit;
+          }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(ko + unit);
+        dst[0] = w[0];
+        dst[1] = w[1];
+        dst[2] = w[2];
       }
-      *reinterpret_cast<uint32_t*>(ko + q4_k_dword_off(tb * 16 + t, chunk * 8)) = w;
+    } else {
+      for (int e = tid; e < qg.nch * 64; e += 256) {
+        const int tb = e & 3, t = (e >> 2) & 15, chunk = e >> 6;
+        uint32_t w = 0;
+#pragma unroll
+        for (int ce = 0; ce < 8; ++ce) {
+          const int c = chunk * 8 + ce;
+          w |= code_of(x[tb * 16 + t][c], sc[c], zr[c], levels) << q4_nibble_shift(ce);
+        }
+        *reinterpret_cast<uint32_t*>(ko + q4_k_dword_off(tb * 16 + t, chunk * 8)) = w;
+      }
     }
     __syncthreads();
   }
@@ -134,7 +157,7 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
         hi = fmaxf(hi, x[tid][c]);
       }
       _Float16 s, z;
-      group_scale_zero(lo, hi, s, z);
+      group_scale_zero(lo, hi, levels, s, z);
       sc[tid] = (float)s;
       zr[tid] = (float)z;
       _Float16* p = reinterpret_cast<_Float16*>(vo + q4_v_scale_off(qg, tid));
@@ -142,18 +165,42 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
       p[64] = z;
     }
     __syncthreads();
-    for (int e = tid; e < qg.ncb * 128; e += 256) {
-      const int lane = e & 63, u = (e >> 6) & 1, cb = e >> 7;
+    auto v_code = [&](int cb, int u, int lane, int j) -> uint32_t {
       const int quad = lane >> 4, c = cb * 16 + (lane & 15);
-      uint32_t w = 0;
+      const int tt = u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
+      return c < g.r_v ? code_of(x[tt][c], sc[tt], zr[tt], levels) : 0u;
+    };
+    if (qg.bits == 3) {
+      // one unit per (pair of channel blocks, lane): four groups (cb, u) in three dwords; an odd last block: two in two
+      const int units = (qg.ncb + 1) / 2;
+      for (int e = tid; e < units * 64; e += 256) {
+        const int lane = e & 63, p = e >> 6;
+        const bool two = (qg.ncb & 1) && p == units - 1;
+        uint32_t w[3] = {0u, 0u, 0u};
+        for (int k = 0; k < (two ? 2 : 4); ++k) {
+          const int cb = two ? 2 * p : 2 * p + (k >> 1), u = two ? k : (k & 1);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int tt = u * 32 + (j >> 2) * 16 + quad * 4 + (j & 3);
-        const uint32_t code = c < g.r_v ? code_of(x[tt][c], sc[tt], zr[tt]) : 0u;
-        w |= code << q4_nibble_shift(j);
+          for (int j = 0; j < 8; ++j) {
+            const uint32_t code = v_code(cb, u, lane, j);
+            const Q3Pos pp = q3_in_unit(0, k, j, two);
+            w[pp.lo_byte >> 2] |= (code & 3u) << pp.lo_bit;
+            w[pp.hi_byte >> 2] |= (code >> 2) << pp.hi_bit;
+          }
+        }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(vo + p * 768 + lane * (two ? 8 : 12));
+        dst[0] = w[0];
+        dst[1] = w[1];
+        if (!two) dst[2] = w[2];
       }
-      int slot;
-      *reinterpret_cast<uint32_t*>(vo + q4_v_dword_off(qg, u * 32 + quad * 4, c, &slot)) = w;
+    } else {
+      for (int e = tid; e < qg.ncb * 128; e += 256) {
+        const int lane = e & 63, u = (e >> 6) & 1, cb = e >> 7;
+        uint32_t w = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w |= v_code(cb, u, lane, j) << q4_nibble_shift(j);
+        int slot;
+        *reinterpret_cast<uint32_t*>(vo + q4_v_dword_off(qg, u * 32 + (lane >> 4) * 4, cb * 16 + (lane & 15), &slot)) = w;
+      }
     }
   }
 }
@@ -184,12 +231,22 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     const int t = u & 15, rest = u >> 4;
     const int chunk = rest % qg.nch, tb = rest / qg.nch;
     const int tt = tb * 16 + t, c0 = chunk * 8;
-    const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c0));
     const _Float16* sp = reinterpret_cast<const _Float16*>(ks_grp + q4_k_scale_off(c0));
     float val[8];
+    if (qg.bits == 3) {
 #pragma unroll
-    for (int ce = 0; ce < 8; ++ce)
-      val[ce] = c0 + ce < g.r_k ? fmaf((float)sp[ce], (float)((w >> q4_nibble_shift(ce)) & 15u), (float)sp[8 + ce]) : 0.f;
+      for (int ce = 0; ce < 8; ++ce) {
+        const Q3Pos p = q3_k_pos(tt, c0 + ce);
+        const uint32_t code = ((*reinterpret_cast<const uint32_t*>(kb + p.lo_byte) >> p.lo_bit) & 3u) |
+                              (((*reinterpret_cast<const uint32_t*>(kb + p.hi_byte) >> p.hi_bit) & 1u) << 2);
+        val[ce] = c0 + ce < g.r_k ? fmaf((float)sp[ce], (float)code, (float)sp[8 + ce]) : 0.f;
+      }
+    } else {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(kb + q4_k_dword_off(tt, c0));
+#pragma unroll
+      for (int ce = 0; ce < 8; ++ce)
+        val[ce] = c0 + ce < g.r_k ? fmaf((float)sp[ce], (float)((w >> q4_nibble_shift(ce)) & 15u), (float)sp[8 + ce]) : 0.f;
+    }
     *reinterpret_cast<u32x4*>(ko + bf16_k_slab_off(tile * kTile + tt, c0, g.r_k_pad)) =
         u32x4{pack2(val[0], val[1]), pack2(val[2], val[3]), pack2(val[4], val[5]), pack2(val[6], val[7])};
   }
@@ -200,12 +257,23 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     const int c = cb * 16 + ch, tt0 = u * 32 + quad * 4;
     float val[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (c < g.r_v) {
-      int slot0;
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt0, c, &slot0));
       const _Float16* sp = reinterpret_cast<const _Float16*>(vb + q4_v_scale_off(qg, tt0));
+      if (qg.bits == 3) {
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj)
-        val[jj] = fmaf((float)sp[jj], (float)((w >> q4_nibble_shift(jj)) & 15u), (float)sp[64 + jj]);
+        for (int jj = 0; jj < 8; ++jj) {
+          // token slot jj of this unit: token tt0 + 16 * (jj / 4) + jj % 4
+          const Q3Pos p = q3_v_pos(qg, tt0 + (jj >> 2) * 16 + (jj & 3), c);
+          const uint32_t code = ((*reinterpret_cast<const uint32_t*>(vb + p.lo_byte) >> p.lo_bit) & 3u) |
+                                (((*reinterpret_cast<const uint32_t*>(vb + p.hi_byte) >> p.hi_bit) & 1u) << 2);
+          val[jj] = fmaf((float)sp[jj], (float)code, (float)sp[64 + jj]);
+        }
+      } else {
+        int slot0;
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt0, c, &slot0));
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj)
+          val[jj] = fmaf((float)sp[jj], (float)((w >> q4_nibble_shift(jj)) & 15u), (float)sp[64 + jj]);
+      }
     }
     *reinterpret_cast<u32x4*>(vo + bf16_v_slab_off(tile * kTile + tt0, c, g.r_v_pad)) =
         u32x4{pack2(val[0], val[1]), pack2(val[2], val[3]), pack2(val[4], val[5]), pack2(val[6], val[7])};

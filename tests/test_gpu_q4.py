@@ -789,3 +789,130 @@ def test_key_group_128_remainder_and_round_trip():
         Kq, Vq = oq.quantized_view(K[b], V[b], lens[b], 128)
         assert np.array_equal(kd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Kq)))
         assert np.array_equal(vd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Vq)))
+
+
+# ---------------------------------------------------------------------------
+# 3-bit codes (desc.q4_bits = 3: the other precision of the paper's Eigen Attention rows)
+# ---------------------------------------------------------------------------
+def desc3(H, Hkv, d_h, r_k, r_v, P, group=64):
+    d = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P, group, 3)
+    return d
+
+
+def read3(buf, lo, hi):
+    """3-bit codes from their two parts: bit positions lo (two bits) and hi (one bit), arrays of the same shape."""
+    low = (buf[lo >> 3] >> (lo & 7).astype(np.uint8)) & 3
+    high = (buf[hi >> 3] >> (hi & 7).astype(np.uint8)) & 1
+    return low | (high << 2)
+
+
+@pytest.mark.parametrize("Hkv,r_k,r_v,P,group,lens,n_quant", [
+    (2, 80, 80, 64, 64, [200, 64], [128, 64]),            # five value channel blocks: an odd last one
+    (1, 30, 33, 128, 128, [300], [256]),                  # ranks off the chunk sizes, key groups of 128 tokens
+    (2, 128, 16, 64, 64, [64], [64]),
+    (1, 8, 128, 192, 64, [192], [192]),
+])
+def test_quantize_pages_3_bit_codes_bit_exact(Hkv, r_k, r_v, P, group, lens, n_quant):
+    print(f"q3 quantize Hkv={Hkv} r=({r_k},{r_v}) P={P} group={group} lens={lens}", flush=True)
+    desc = desc3(Hkv, Hkv, 128, r_k, r_v, P, group)
+    g = synth.rng(161, r_k, P)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    K[0][0, :group, 0] = 0.75                    # a constant group: scale 0
+    qc = Q4Cache(desc, K, V, n_quant, g, poison_sources=False)
+    lay = ea.q4_layout_query(desc)
+    kq = qc.kq.cpu().numpy().reshape(-1)
+    vq = qc.vq.cpu().numpy().reshape(-1)
+    kpos = np.array([[ea.q3_k_code_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(P)])      # [P, r_k, 2]
+    vpos = np.array([[ea.q3_v_code_pos(desc, 0, 0, t, c) for c in range(r_v)] for t in range(P)])
+    ks = np.array([[ea.q4_k_scale_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(0, P, group)])
+    vs = np.array([ea.q4_v_scale_pos(desc, 0, 0, t) for t in range(P)])
+    k_slab, v_slab = lay.k_page_bytes // Hkv, lay.v_page_bytes // Hkv
+    for b in range(len(lens)):
+        for kvh in range(Hkv):
+            ck, sk, zk = oq.quantize_keys(K[b][kvh, :n_quant[b]], group, bits=3)
+            cv, sv, zv = oq.quantize_values(V[b][kvh, :n_quant[b]], bits=3)
+            assert ck.max() <= 7 and cv.max() <= 7
+            for p in range(n_quant[b] // P):
+                page = int(qc.q4_table_host[b, p])
+                k0, v0 = page * lay.k_page_bytes + kvh * k_slab, page * lay.v_page_bytes + kvh * v_slab
+                where = f"b={b} kvh={kvh} page {p}"
+                assert np.array_equal(read3(kq, kpos[..., 0] + 8 * k0, kpos[..., 1] + 8 * k0), ck[p * P:(p + 1) * P]), f"key codes {where}"
+                grp = slice(p * P // group, (p + 1) * P // group)
+                assert np.array_equal(read_f16(kq, ks + k0).view(np.uint16), sk[grp].view(np.uint16)), f"key scales {where}"
+                assert np.array_equal(read_f16(kq, ks + k0 + 16).view(np.uint16), zk[grp].view(np.uint16)), f"key zeros {where}"
+                assert np.array_equal(read3(vq, vpos[..., 0] + 8 * v0, vpos[..., 1] + 8 * v0), cv[p * P:(p + 1) * P]), f"value codes {where}"
+                assert np.array_equal(read_f16(vq, vs + v0).view(np.uint16), sv[p * P:(p + 1) * P].view(np.uint16))
+                assert np.array_equal(read_f16(vq, vs + v0 + 128).view(np.uint16), zv[p * P:(p + 1) * P].view(np.uint16))
+
+
+@pytest.mark.parametrize("form", ["plain", "alibi"])
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,group,lens,n_quant,n_splits", [
+    (2, 2, 80, 80, 64, 64, [200, 130, 64], [128, 128, 64], 1),      # the last sequence has no 16-bit part
+    (2, 2, 80, 80, 64, 64, [1000, 513, 129], [960, 512, 128], 3),
+    (8, 2, 48, 112, 128, 128, [777, 1500], [768, 1408], 0),          # GQA 4:1, r_k != r_v, key groups of 128
+    (8, 2, 112, 48, 64, 64, [2048, 70], [1984, 64], 5),              # three value blocks: an odd last one
+    (16, 1, 96, 64, 64, 64, [330], [320], 2),
+    (4, 4, 128, 128, 64, 64, [513, 100], [512, 64], 2),              # full rank
+    (4, 2, 72, 40, 64, 64, [150, 70], [128, 64], 2),                 # ranks that need padding channels
+    (4, 2, 30, 33, 64, 64, [150, 70], [128, 64], 1),
+    (2, 2, 16, 16, 192, 64, [5000], [4800], 7),                      # a single value block (one two-group unit)
+    (2, 2, 80, 80, 64, 64, [300, 50, 0], [0, 0, 0], 2),              # nothing quantised yet; an empty sequence
+    (2, 1, 64, 64, 64, 64, [20000], [19968], 1),
+])
+def test_decode_over_3_bit_codes_matches_oracle(form, H, Hkv, r_k, r_v, P, group, lens, n_quant, n_splits):
+    from oracle import eigen_attention as ora
+    print(f"q3 decode {form}: H={H}/{Hkv} r=({r_k},{r_v}) P={P} group={group} lens={lens} quantised={n_quant} S={n_splits}",
+          flush=True)
+    desc = desc3(H, Hkv, 128, r_k, r_v, P, group)
+    g = synth.rng(162, H, r_k, len(lens), n_splits)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    B = len(lens)
+    q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    slopes = np.float32(2.0 ** (-8.0 * (np.arange(H) + 1) / H)).astype(np.float64) if form == "alibi" else None
+    if form == "alibi":
+        out = torch.full((B, H, r_v), float("nan"), dtype=torch.float32, device="cuda")
+        S = n_splits if n_splits else ea.decode_auto_splits(desc, B, qc.max_q4_pages * P)
+        ws = torch.full((ea.decode_q4_workspace_bytes(desc, B, S) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+        ea.decode_attn_alibi_q4(desc, torch.from_numpy(q.astype(np.float32)).cuda(),
+                                torch.from_numpy(slopes.astype(np.float32)).cuda(), qc.kq, qc.vq, qc.q4_table, qc.q4_len,
+                                qc.dc.k_pool, qc.dc.v_pool, qc.tail_table, qc.tail_len, out, S, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    else:
+        got = run_q4(desc, qc, q, n_splits)
+    keep = [b for b in range(B) if lens[b] > 0]
+    sub = lambda xs: [xs[b] for b in keep]
+    ref = np.zeros((B, H, r_v))
+    ref[keep] = oq.decode_attention_quantized(q[keep], sub(K), sub(V), sub(n_quant), 128, alibi_slopes=slopes,
+                                              group_tokens=group, bits=3)
+    err = assert_close(got, ref, TOL_BF16, f"q3 decode {form}")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+    if max(n_quant) >= 128:
+        # the kernel follows the 3-bit quantiser, not the 4-bit one
+        four = oq.decode_attention_quantized(q[keep], sub(K), sub(V), sub(n_quant), 128, alibi_slopes=slopes,
+                                             group_tokens=group)
+        assert ora.rel_l2(four, ref[keep]) > 3 * err
+
+
+def test_3_bit_round_trip_through_the_library():
+    """quantise -> dequantise through the library = the oracle's 3-bit round trip, rounded once to bfloat16."""
+    desc = desc3(2, 2, 128, 72, 40, 128)
+    g = synth.rng(163)
+    lens = [256, 128]
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    qc = Q4Cache(desc, K, V, lens, g)
+    dc = qc.dc
+    src = [int(qc.q4_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    dst = [int(dc.page_table_host[b, p]) for b in range(2) for p in range(lens[b] // 128)]
+    ea.dequantize_pages_q4(desc, qc.kq, qc.vq, torch.tensor(src, dtype=torch.int32).cuda(), dc.k_pool, dc.v_pool,
+                           torch.tensor(dst, dtype=torch.int32).cuda())
+    torch.cuda.synchronize()
+    for b in range(2):
+        kd = torch.zeros((1, 2, lens[b], 72), dtype=torch.bfloat16, device="cuda")
+        vd = torch.zeros((1, 2, lens[b], 40), dtype=torch.bfloat16, device="cuda")
+        ea.cache_gather(desc, kd, vd, dc.k_pool, dc.v_pool, dc.page_table[b:b + 1].contiguous())
+        torch.cuda.synchronize()
+        Kq, Vq = oq.quantized_view(K[b], V[b], lens[b], 64, bits=3)
+        assert np.array_equal(kd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Kq)))
+        assert np.array_equal(vd.float().cpu().numpy()[0], synth.round_to_bf16(np.float32(Vq)))

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 46
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 48
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -497,3 +497,73 @@ def test_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching():
     assert call(ws=None) == -4 and call(ws_bytes=need - 1) == -4
     assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
     assert ea.prefill_q4_workspace_bytes(d, 0, 100) == -1
+
+
+@pytest.mark.parametrize("P,r_k,r_v,Hkv,group", [(64, 80, 80, 2, 64), (128, 30, 33, 1, 128), (192, 128, 16, 2, 64), (64, 8, 112, 1, 64)])
+def test_q3_positions_tile_the_page_exactly(P, r_k, r_v, Hkv, group):
+    """3-bit codes: every code has its own two low bits and its own high bit, every scale its own two bytes, nothing
+    overlaps, everything lies inside the page, and the sizes are the documented ones."""
+    d = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
+    d.q4_key_group, d.q4_bits = group, 3
+    lay = ea.q4_layout_query(d)
+    ncb = lay.r_v_pad // 16
+    scales = 128 * (-(-lay.r_k_pad // 32))
+    assert lay.k_tile_bytes == 24 * lay.r_k_pad + scales
+    assert lay.v_tile_bytes == (ncb // 2) * 768 + (ncb % 2) * 512 + 256
+    tpg = group // 64
+    assert lay.k_page_bytes == Hkv * ((P // 64) * 24 * lay.r_k_pad + (P // 64 // tpg) * scales)
+    assert lay.v_page_bytes == Hkv * (P // 64) * lay.v_tile_bytes
+    assert ea.q4_k_code_pos(d, 0, 0, 0, 0) == -1 and ea.q4_v_code_pos(d, 0, 0, 0, 0) == -1     # the 4-bit functions decline
+    d4 = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
+    assert ea.q3_k_code_pos(d4, 0, 0, 0, 0)[0] == -1
+    page = 1
+    used_k = np.zeros(lay.k_page_bytes * 8, np.int32)          # per bit
+    used_v = np.zeros(lay.v_page_bytes * 8, np.int32)
+    for h in range(Hkv):
+        for t in range(P):
+            for c in range(r_k):
+                lo, hi = ea.q3_k_code_pos(d, page, h, t, c)
+                lo -= page * lay.k_page_bytes * 8
+                hi -= page * lay.k_page_bytes * 8
+                assert lo % 2 == 0
+                used_k[lo:lo + 2] += 1
+                used_k[hi] += 1
+            for c in range(r_v):
+                lo, hi = ea.q3_v_code_pos(d, page, h, t, c)
+                lo -= page * lay.v_page_bytes * 8
+                hi -= page * lay.v_page_bytes * 8
+                used_v[lo:lo + 2] += 1
+                used_v[hi] += 1
+            sp = ea.q4_v_scale_pos(d, page, h, t) - page * lay.v_page_bytes
+            for off in (sp, sp + 128):
+                used_v[8 * off:8 * off + 16] += 1
+        for grp in range(P // group):
+            for c in range(r_k):
+                sp = ea.q4_k_scale_pos(d, page, h, grp * group, c) - page * lay.k_page_bytes
+                assert sp == ea.q4_k_scale_pos(d, page, h, grp * group + group - 1, c) - page * lay.k_page_bytes
+                for off in (sp, sp + 16):
+                    used_k[8 * off:8 * off + 16] += 1
+    assert used_k.max() == 1 and used_v.max() == 1
+    assert used_k.sum() == Hkv * P * r_k * 3 + Hkv * (P // group) * r_k * 32
+    assert used_v.sum() == Hkv * P * r_v * 3 + Hkv * P * 32
+    # the order inside a unit: token 16*tb + t, channel 32*kk + 8*quad + e -> unit (quad*16 + t) of run kk, group tb
+    for (t, c) in [(0, 0), (17, min(9, r_k - 1)), (63, r_k - 1), (35, min(44, r_k - 1))]:
+        tb, tt, kk, quad, e = t // 16, t % 16, c // 32, (c // 8) % 4, c % 8
+        unit = kk * 768 + (quad * 16 + tt) * 12
+        lo, hi = ea.q3_k_code_pos(d, 0, 0, t, c)
+        assert lo == (unit + 4 * (tb // 2)) * 8 + 16 * (e % 2) + 8 * (tb % 2) + 2 * (e // 2)
+        assert hi == (unit + 8) * 8 + 16 * (e % 2) + [0, 1, 8, 9][tb] + 2 * (e // 2)
+    bad = desc()
+    bad.q4_bits = 2
+    assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -1
+
+
+def test_three_bit_codes_are_declined_where_they_are_not_built():
+    lib, d = raw(), desc()
+    d.q4_bits = 3
+    rc = lib.ea_decode_attn_rope_q4(ctypes.byref(d), OK_PTR, OK_PTR, 10000.0, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, None,
+                                    None, None, None, 0, 0, OK_PTR, 2, 1, OK_PTR, 1 << 30, None)
+    assert rc == -2
+    rc = lib.ea_prefill_attn_q4(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, OK_PTR, OK_PTR, OK_PTR, OK_PTR,
+                                2, 8, OK_PTR, 2, 100, OK_PTR, 1 << 40, None)
+    assert rc == -2
