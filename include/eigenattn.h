@@ -354,16 +354,18 @@ EA_API int64_t ea_q4_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t
 EA_API int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel);
 EA_API int64_t ea_q4_v_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page);
 
-/* The same for 3-bit codes (desc.q4_bits = 3; the *_code_pos functions above return -1 then, these return -1
- * otherwise): a code is stored in two parts, its low two bits and its high bit.  Returns the BIT offset from the
- * start of the pool of the low two bits and writes that of the high bit to *hi_bit_pos.  A lane's four groups of
- * eight codes share a 12-byte unit: two dwords of low bits, one of high bits (8 bytes for the two groups of an odd
- * last value channel block).  K tile block: 24 * r_k_pad bytes of codes; V tile block: 768 per pair of 16-channel
- * blocks + 512 for an odd last one.  The scale positions are given by ea_q4_k_scale_pos / ea_q4_v_scale_pos. */
-EA_API int64_t ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
-                                int32_t channel, int64_t* hi_bit_pos);
-EA_API int64_t ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
-                                int32_t channel, int64_t* hi_bit_pos);
+/* The same for 3-bit codes (desc.q4_bits = 3; the *_code_pos functions above return -1 then, these fail
+ * otherwise): bit_pos[b] receives the BIT offset from the start of the pool of bit b (b = 0, 1, 2) of the code.
+ * A lane's four groups of eight codes share a 12-byte unit: dword k holds group k (k = 0, 1, 2), element 2i + h in
+ * bits 3i .. 3i+2 of half word h; group 3 is laid out the same way in a fourth word whose half words are cut into
+ * three nibbles each, nibble j kept in bits 12 .. 15 of half word h of dword j -- so the bits of one of its codes
+ * can lie in two dwords.  The two groups of an odd last value channel block have a unit of two dwords.  K tile
+ * block: 24 * r_k_pad bytes of codes; V tile block: 768 per pair of 16-channel blocks + 512 for an odd last one.
+ * The scale positions are given by ea_q4_k_scale_pos / ea_q4_v_scale_pos.  Returns EA_OK or EA_ERR_ARG. */
+EA_API int ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                            int32_t channel, int64_t* bit_pos);
+EA_API int ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
+                            int32_t channel, int64_t* bit_pos);
 
 /* Quantise n_pages full pages: page dev_src_pages[i] of the bfloat16 pools is written
  * as page dev_dst_pages[i] of the 4-bit pools (all kv heads, keys and values).  The

@@ -141,7 +141,6 @@ def load_library():
     lib.ea_q4_v_scale_pos.restype = I64
     lib.ea_q4_v_scale_pos.argtypes = [D, I32, I32, I32]
     for f in (lib.ea_q3_k_code_pos, lib.ea_q3_v_code_pos):
-        f.restype = I64
         f.argtypes = [D, I32, I32, I32, I32, P(I64)]
     lib.ea_quantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
     lib.ea_dequantize_pages_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, VP]
@@ -584,16 +583,16 @@ def q4_v_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: in
 
 
 def q3_k_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int):
-    """3-bit codes (desc.q4_bits = 3): (bit offset of the code's low two bits, bit offset of its high bit)."""
-    hi = ctypes.c_int64(-1)
-    lo = int(load_library().ea_q3_k_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, ctypes.byref(hi)))
-    return lo, int(hi.value)
+    """3-bit codes (desc.q4_bits = 3): the bit offsets of the code's three bits, lowest first; None on bad arguments."""
+    pos = (ctypes.c_int64 * 3)()
+    rc = load_library().ea_q3_k_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, pos)
+    return tuple(int(v) for v in pos) if rc == 0 else None
 
 
 def q3_v_code_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int):
-    hi = ctypes.c_int64(-1)
-    lo = int(load_library().ea_q3_v_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, ctypes.byref(hi)))
-    return lo, int(hi.value)
+    pos = (ctypes.c_int64 * 3)()
+    rc = load_library().ea_q3_v_code_pos(ctypes.byref(desc), page, kv_head, token_in_page, channel, pos)
+    return tuple(int(v) for v in pos) if rc == 0 else None
 
 
 def q4_k_scale_pos(desc, page: int, kv_head: int, token_in_page: int, channel: int) -> int:

@@ -52,24 +52,24 @@ int64_t ea_q4_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_hea
          q4_nibble_shift(channel & 7);
 }
 
-int64_t ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
-                         int32_t channel, int64_t* hi_bit_pos) {
-  if (!hi_bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true, 3)) return -1;
+int ea_q3_k_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel,
+                     int64_t* bit_pos) {
+  if (!bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, true, 3)) return EA_ERR_ARG;
   const Q4Geo q = q4_geo_of(desc);
   const Q3Pos p = q3_k_pos(token_in_page % kTile, channel);
   const int64_t t0 = k_tile0(q, page, kv_head, token_in_page);
-  *hi_bit_pos = (t0 + p.hi_byte) * 8 + p.hi_bit;
-  return (t0 + p.lo_byte) * 8 + p.lo_bit;
+  for (int b = 0; b < 3; ++b) bit_pos[b] = (t0 + p.byte[b]) * 8 + p.bit[b];
+  return EA_OK;
 }
 
-int64_t ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,
-                         int32_t channel, int64_t* hi_bit_pos) {
-  if (!hi_bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, false, 3)) return -1;
+int ea_q3_v_code_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page, int32_t channel,
+                     int64_t* bit_pos) {
+  if (!bit_pos || !q4_pos_args_ok(desc, page, kv_head, token_in_page, channel, false, 3)) return EA_ERR_ARG;
   const Q4Geo q = q4_geo_of(desc);
   const Q3Pos p = q3_v_pos(q, token_in_page % kTile, channel);
   const int64_t t0 = v_tile0(q, page, kv_head, token_in_page);
-  *hi_bit_pos = (t0 + p.hi_byte) * 8 + p.hi_bit;
-  return (t0 + p.lo_byte) * 8 + p.lo_bit;
+  for (int b = 0; b < 3; ++b) bit_pos[b] = (t0 + p.byte[b]) * 8 + p.bit[b];
+  return EA_OK;
 }
 
 int64_t ea_q4_k_scale_pos(const ea_layer_desc* desc, int32_t page, int32_t kv_head, int32_t token_in_page,

@@ -106,14 +106,11 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   f16x8 negoff, ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    if (B3) negoff[j] = (_Float16)(-1024.0f / (float)(1 << (2 * (j >> 1))));       // 1024, 256, 64, 16 per element pair
-    else negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;
+    negoff[j] = (j & 2) ? (_Float16)(B3 ? -128.0f : -64.0f) : (_Float16)-1024.0f;   // what the unpacking adds
     ones[j] = (_Float16)1.0f;
   }
-  uint32_t magic1024 = 0x64006400u, magic64 = 0x54005400u;
+  uint32_t magic1024 = 0x64006400u, magic64 = B3 ? 0x58005800u : 0x54005400u;    // (3-bit codes: 128.0)
   asm volatile("" : "+v"(magic1024), "+v"(magic64));   // keep them in vector registers
-  Q3Magic mg3 = {{0x64006400u, 0x5C005C00u, 0x54005400u, 0x4C004C00u}};
-  if constexpr (B3) asm volatile("" : "+v"(mg3.m[0]), "+v"(mg3.m[1]), "+v"(mg3.m[2]), "+v"(mg3.m[3]));
 
   f32x4 acc[NCB];
 #pragma unroll
@@ -122,15 +119,17 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   f32x4 corr = {0.f, 0.f, 0.f, 0.f};   // every row: sum_t p zero_t - sum_t offset (p scale)_t
   float m = -INFINITY;
 
-  u32x4 kc[KS];                        // 3-bit codes: dwords A, B, C of the unit in [0..2]
+  u32x4 kc[KS];                        // 3-bit codes: the unit's three dwords in [0..2], group 3's word in [3]
   f16x8 ksc[KS], kzr[KS];
   u32x4 vc[NVP > 0 ? NVP : 1];
-  u32x2 vcl = {0u, 0u};                // 3-bit codes: A, C of the two-group unit
+  u32x2 vcl = {0u, 0u};
   f16x8 vsc[2], vzr[2];
   auto load_unit = [&](const uint8_t* p) -> u32x4 {      // a 16-byte unit, or the 12 bytes of a 3-bit unit
     if constexpr (B3) {
       const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
-      return u32x4{__builtin_nontemporal_load(w), __builtin_nontemporal_load(w + 1), __builtin_nontemporal_load(w + 2), 0u};
+      const uint32_t d0 = __builtin_nontemporal_load(w), d1 = __builtin_nontemporal_load(w + 1),
+                     d2 = __builtin_nontemporal_load(w + 2);
+      return u32x4{d0, d1, d2, 0u};
     } else {
       return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     }
@@ -186,14 +185,15 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   };
   // the A operands "offset + code": 16-token block tb of k-step kk; 32-token group u of channel block cb
   auto k_frag = [&](int kk, int tb) -> f16x8 {
-    if constexpr (B3) return unpack_q3(q3_lo_of(kc[kk][0], kc[kk][1], tb), q3_hi_of(kc[kk][2], tb), mg3);
+    if constexpr (B3) return unpack_q3(tb < 3 ? kc[kk][tb] : q3_group3(kc[kk][0], kc[kk][1], kc[kk][2]), magic1024, magic64);
     else return unpack_q4(kc[kk][tb], magic1024, magic64);
   };
   auto v_frag = [&](int cb, int u) -> f16x8 {
     if constexpr (B3) {
-      if (VODD && cb == NCB - 1) return unpack_q3(vcl[0] >> (8 * u), q3_hi_of(vcl[1], u), mg3);
+      if (VODD && cb == NCB - 1) return unpack_q3(vcl[u], magic1024, magic64);
       const int k = (cb & 1) * 2 + u;
-      return unpack_q3(q3_lo_of(vc[cb >> 1][0], vc[cb >> 1][1], k), q3_hi_of(vc[cb >> 1][2], k), mg3);
+      const u32x4& un = vc[cb >> 1];
+      return unpack_q3(k < 3 ? un[k] : q3_group3(un[0], un[1], un[2]), magic1024, magic64);
     } else {
       if (VODD && cb == NCB - 1) return unpack_q4(vcl[u], magic1024, magic64);
       return unpack_q4(vc[cb >> 1][(cb & 1) * 2 + u], magic1024, magic64);

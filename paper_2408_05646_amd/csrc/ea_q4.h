@@ -24,11 +24,12 @@
 //
 // 3-bit codes (bits = 3): the same order of tokens, channels and lanes, but a lane's unit holds its four groups of
 // eight codes (K: the four 16-token blocks tb; V: the fragments (cb = 2p, u = 0), (2p, 1), (2p+1, 0), (2p+1, 1)) in
-// 12 bytes instead of 16: dword A = the low two bits of groups 0 and 1, dword B = those of groups 2 and 3, dword C =
-// the high bits of all four.  Element e = 2i + h of group k has its low bits at bit 16h + 8(k & 1) + 2i of A (k < 2)
-// or B, its high bit at bit 16h + {0, 1, 8, 9}[k] + 2i of C -- so that, after one shift per group, a mask-and-or
-// per pair of elements puts the low bits, and a second one the high bit right above them, into the mantissa of a
-// half-precision number (see unpack_q3).  An odd last value channel block has units of two groups: A, then C.
+// 12 bytes instead of 16.  Dword k (k = 0, 1, 2) holds group k: element e = 2i + h in bits 3i .. 3i+2 of half word h
+// (twelve bits per half word).  The four bits that are left in every half word hold group 3: its half word h (again
+// twelve bits, element 2i + h at bits 3i .. 3i+2) is cut into three nibbles, nibble j stored in bits 12 .. 15 of half
+// word h of dword j.  So three of the four groups unpack exactly like 4-bit codes (one shift, four mask-and-or
+// operations: a field at bit s of a half word under the exponent of 2^(10-s) reads 2^(10-s) + its value), and the
+// fourth takes six operations more to collect.  An odd last value channel block has units of two groups: two dwords.
 //   K codes: 48 * r_k_pad / 2 bytes;  V codes: 768 per pair of channel blocks + 512 for an odd last one.
 #pragma once
 #include "ea_common.h"
@@ -103,18 +104,23 @@ __host__ __device__ inline int32_t q4_v_scale_off(const Q4Geo& q, int32_t tt) {
   return q.v_codes + ((u * 4 + quad) * 8 + half * 4 + (t32 & 3)) * 2;            // the zero is 128 bytes further
 }
 
-// ---- 3-bit codes: where the two parts of a code sit.  Both return byte offsets of a dword inside the tile block
-// and the bit inside that dword: the low two bits of the code, and its high bit.
+// ---- 3-bit codes: where the three bits of a code sit (byte offset of a dword inside the tile block, bit in it).
 struct Q3Pos {
-  int32_t lo_byte, lo_bit, hi_byte, hi_bit;
+  int32_t byte[3], bit[3];
 };
 __host__ __device__ inline Q3Pos q3_in_unit(int32_t unit_off, int32_t group, int32_t e, bool two_groups) {
   const int32_t h = e & 1, i = e >> 1;
   Q3Pos p;
-  p.lo_byte = unit_off + (two_groups ? 0 : (group >> 1) * 4);
-  p.lo_bit = 16 * h + 8 * (group & 1) + 2 * i;
-  p.hi_byte = unit_off + (two_groups ? 4 : 8);
-  p.hi_bit = 16 * h + (group & 1) + 8 * (group >> 1) + 2 * i;
+  for (int32_t b = 0; b < 3; ++b) {
+    const int32_t s = 3 * i + b;                        // bit of the group's twelve-bit half word
+    if (group < 3 || two_groups) {
+      p.byte[b] = unit_off + 4 * group;
+      p.bit[b] = 16 * h + s;
+    } else {
+      p.byte[b] = unit_off + 4 * (s >> 2);
+      p.bit[b] = 16 * h + 12 + (s & 3);
+    }
+  }
   return p;
 }
 __host__ __device__ inline Q3Pos q3_k_pos(int32_t tt, int32_t c) {
@@ -127,6 +133,12 @@ __host__ __device__ inline Q3Pos q3_v_pos(const Q4Geo& q, int32_t tt, int32_t c)
   const int32_t cb = c >> 4, lane = quad * 16 + (c & 15), p = cb >> 1;
   if ((q.ncb & 1) && cb == q.ncb - 1) return q3_in_unit(p * 768 + lane * 8, u, slot, true);
   return q3_in_unit(p * 768 + lane * 12, (cb & 1) * 2 + u, slot, false);
+}
+// the code at a position (host and device: the reference readers), and its bits spread to their places
+__host__ __device__ inline uint32_t q3_read(const uint8_t* block, const Q3Pos& p) {
+  uint32_t code = 0;
+  for (int32_t b = 0; b < 3; ++b) code |= ((*reinterpret_cast<const uint32_t*>(block + p.byte[b]) >> p.bit[b]) & 1u) << b;
+  return code;
 }
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -159,25 +171,21 @@ __device__ __forceinline__ f16x8 unpack_q4(uint32_t w, uint32_t magic1024, uint3
   return __builtin_bit_cast(f16x8, r);
 }
 
-// Group k (0..3) of a 3-bit unit -> eight fp16 numbers offset + code, the offsets 1024, 256, 64, 16 for the element
-// pairs i = 0..3: `lo` is the dword with the group's low bits, shifted so that they sit in bits 2i, 2i+1 of each half
-// (groups 1 and 3: >> 8), `hi` the dword of high bits shifted so that the group's sit in bit 2i + 2 of each half
-// (k = 0: << 2, 1: << 1, 2: >> 6, 3: >> 7).  A field at bit s of a half word under the exponent of 2^(10-s) reads
-// 2^(10-s) + its value.
-struct Q3Magic {
-  uint32_t m[4];     // 0x64006400 (1024), 0x5C005C00 (256), 0x54005400 (64), 0x4C004C00 (16): kept in vector registers
-};
-__device__ __forceinline__ f16x8 unpack_q3(uint32_t lo, uint32_t hi, const Q3Magic& mg) {
+// 3-bit codes: a word with element 2i + h in bits 3i .. 3i+2 of half word h -> eight fp16 numbers offset + code, the
+// offsets 1024 (element pairs 0 and 2) and 128 (pairs 1 and 3): bits 0-2 under the exponent of 1024.0 (0x6400), bits
+// 3-5 under that of 128.0 (0x5800, eight mantissa steps per unit).  Bits 12-15 of the half words are ignored.
+__device__ __forceinline__ f16x8 unpack_q3(uint32_t w, uint32_t magic1024, uint32_t magic128) {
+  const uint32_t w6 = w >> 6;
   u32x4 r;
-  r[0] = (hi & 0x00040004u) | ((lo & 0x00030003u) | mg.m[0]);
-  r[1] = (hi & 0x00100010u) | ((lo & 0x000c000cu) | mg.m[1]);
-  r[2] = (hi & 0x00400040u) | ((lo & 0x00300030u) | mg.m[2]);
-  r[3] = (hi & 0x01000100u) | ((lo & 0x00c000c0u) | mg.m[3]);
+  r[0] = (w & 0x00070007u) | magic1024;
+  r[1] = (w & 0x00380038u) | magic128;
+  r[2] = (w6 & 0x00070007u) | magic1024;
+  r[3] = (w6 & 0x00380038u) | magic128;
   return __builtin_bit_cast(f16x8, r);
 }
-__device__ __forceinline__ uint32_t q3_lo_of(uint32_t a, uint32_t b, int k) { return (k & 2 ? b : a) >> ((k & 1) * 8); }
-__device__ __forceinline__ uint32_t q3_hi_of(uint32_t c, int k) {
-  return k == 0 ? c << 2 : k == 1 ? c << 1 : k == 2 ? c >> 6 : c >> 7;
+// the word of group 3, collected from the upper nibbles of the unit's three dwords
+__device__ __forceinline__ uint32_t q3_group3(uint32_t d0, uint32_t d1, uint32_t d2) {
+  return ((d0 >> 12) & 0x000f000fu) | ((d1 >> 8) & 0x00f000f0u) | ((d2 >> 4) & 0x0f000f00u);
 }
 
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,

@@ -111,8 +111,8 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
             const int c = chunk * 8 + ce;
             const uint32_t code = code_of(x[tb * 16 + t][c], sc[c], zr[c], levels);
             const Q3Pos p = q3_in_unit(0, tb, ce, false);
-            w[p.lo_byte >> 2] |= (code & 3u) << p.lo_bit;
-            w[2] |= (code >> 2) << p.hi_bit;
+#pragma unroll
+            for (int b = 0; b < 3; ++b) w[p.byte[b] >> 2] |= ((code >> b) & 1u) << p.bit[b];
           }
         uint32_t* dst = reinterpret_cast<uint32_t*>(ko + unit);
         dst[0] = w[0];
@@ -183,8 +183,8 @@ __global__ __launch_bounds__(256) void quantize_q4_kernel(QuantArgs a) {
           for (int j = 0; j < 8; ++j) {
             const uint32_t code = v_code(cb, u, lane, j);
             const Q3Pos pp = q3_in_unit(0, k, j, two);
-            w[pp.lo_byte >> 2] |= (code & 3u) << pp.lo_bit;
-            w[pp.hi_byte >> 2] |= (code >> 2) << pp.hi_bit;
+#pragma unroll
+            for (int b = 0; b < 3; ++b) w[pp.byte[b] >> 2] |= ((code >> b) & 1u) << pp.bit[b];
           }
         }
         uint32_t* dst = reinterpret_cast<uint32_t*>(vo + p * 768 + lane * (two ? 8 : 12));
@@ -236,9 +236,7 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     if (qg.bits == 3) {
 #pragma unroll
       for (int ce = 0; ce < 8; ++ce) {
-        const Q3Pos p = q3_k_pos(tt, c0 + ce);
-        const uint32_t code = ((*reinterpret_cast<const uint32_t*>(kb + p.lo_byte) >> p.lo_bit) & 3u) |
-                              (((*reinterpret_cast<const uint32_t*>(kb + p.hi_byte) >> p.hi_bit) & 1u) << 2);
+        const uint32_t code = q3_read(kb, q3_k_pos(tt, c0 + ce));
         val[ce] = c0 + ce < g.r_k ? fmaf((float)sp[ce], (float)code, (float)sp[8 + ce]) : 0.f;
       }
     } else {
@@ -262,9 +260,7 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
           // token slot jj of this unit: token tt0 + 16 * (jj / 4) + jj % 4
-          const Q3Pos p = q3_v_pos(qg, tt0 + (jj >> 2) * 16 + (jj & 3), c);
-          const uint32_t code = ((*reinterpret_cast<const uint32_t*>(vb + p.lo_byte) >> p.lo_bit) & 3u) |
-                                (((*reinterpret_cast<const uint32_t*>(vb + p.hi_byte) >> p.hi_bit) & 1u) << 2);
+          const uint32_t code = q3_read(vb, q3_v_pos(qg, tt0 + (jj >> 2) * 16 + (jj & 3), c));
           val[jj] = fmaf((float)sp[jj], (float)code, (float)sp[64 + jj]);
         }
       } else {

@@ -799,11 +799,10 @@ def desc3(H, Hkv, d_h, r_k, r_v, P, group=64):
     return d
 
 
-def read3(buf, lo, hi):
-    """3-bit codes from their two parts: bit positions lo (two bits) and hi (one bit), arrays of the same shape."""
-    low = (buf[lo >> 3] >> (lo & 7).astype(np.uint8)) & 3
-    high = (buf[hi >> 3] >> (hi & 7).astype(np.uint8)) & 1
-    return low | (high << 2)
+def read3(buf, pos):
+    """3-bit codes from the bit positions of their three bits: pos [..., 3]."""
+    bits = (buf[pos >> 3] >> (pos & 7).astype(np.uint8)) & 1
+    return bits[..., 0] | (bits[..., 1] << 1) | (bits[..., 2] << 2)
 
 
 @pytest.mark.parametrize("Hkv,r_k,r_v,P,group,lens,n_quant", [
@@ -822,7 +821,7 @@ def test_quantize_pages_3_bit_codes_bit_exact(Hkv, r_k, r_v, P, group, lens, n_q
     lay = ea.q4_layout_query(desc)
     kq = qc.kq.cpu().numpy().reshape(-1)
     vq = qc.vq.cpu().numpy().reshape(-1)
-    kpos = np.array([[ea.q3_k_code_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(P)])      # [P, r_k, 2]
+    kpos = np.array([[ea.q3_k_code_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(P)])      # [P, r_k, 3]
     vpos = np.array([[ea.q3_v_code_pos(desc, 0, 0, t, c) for c in range(r_v)] for t in range(P)])
     ks = np.array([[ea.q4_k_scale_pos(desc, 0, 0, t, c) for c in range(r_k)] for t in range(0, P, group)])
     vs = np.array([ea.q4_v_scale_pos(desc, 0, 0, t) for t in range(P)])
@@ -836,11 +835,11 @@ def test_quantize_pages_3_bit_codes_bit_exact(Hkv, r_k, r_v, P, group, lens, n_q
                 page = int(qc.q4_table_host[b, p])
                 k0, v0 = page * lay.k_page_bytes + kvh * k_slab, page * lay.v_page_bytes + kvh * v_slab
                 where = f"b={b} kvh={kvh} page {p}"
-                assert np.array_equal(read3(kq, kpos[..., 0] + 8 * k0, kpos[..., 1] + 8 * k0), ck[p * P:(p + 1) * P]), f"key codes {where}"
+                assert np.array_equal(read3(kq, kpos + 8 * k0), ck[p * P:(p + 1) * P]), f"key codes {where}"
                 grp = slice(p * P // group, (p + 1) * P // group)
                 assert np.array_equal(read_f16(kq, ks + k0).view(np.uint16), sk[grp].view(np.uint16)), f"key scales {where}"
                 assert np.array_equal(read_f16(kq, ks + k0 + 16).view(np.uint16), zk[grp].view(np.uint16)), f"key zeros {where}"
-                assert np.array_equal(read3(vq, vpos[..., 0] + 8 * v0, vpos[..., 1] + 8 * v0), cv[p * P:(p + 1) * P]), f"value codes {where}"
+                assert np.array_equal(read3(vq, vpos + 8 * v0), cv[p * P:(p + 1) * P]), f"value codes {where}"
                 assert np.array_equal(read_f16(vq, vs + v0).view(np.uint16), sv[p * P:(p + 1) * P].view(np.uint16))
                 assert np.array_equal(read_f16(vq, vs + v0 + 128).view(np.uint16), zv[p * P:(p + 1) * P].view(np.uint16))
 

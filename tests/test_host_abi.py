@@ -515,25 +515,18 @@ def test_q3_positions_tile_the_page_exactly(P, r_k, r_v, Hkv, group):
     assert lay.v_page_bytes == Hkv * (P // 64) * lay.v_tile_bytes
     assert ea.q4_k_code_pos(d, 0, 0, 0, 0) == -1 and ea.q4_v_code_pos(d, 0, 0, 0, 0) == -1     # the 4-bit functions decline
     d4 = desc(Hkv=Hkv, H=Hkv, r_k=r_k, r_v=r_v, P=P)
-    assert ea.q3_k_code_pos(d4, 0, 0, 0, 0)[0] == -1
+    assert ea.q3_k_code_pos(d4, 0, 0, 0, 0) is None
     page = 1
     used_k = np.zeros(lay.k_page_bytes * 8, np.int32)          # per bit
     used_v = np.zeros(lay.v_page_bytes * 8, np.int32)
     for h in range(Hkv):
         for t in range(P):
             for c in range(r_k):
-                lo, hi = ea.q3_k_code_pos(d, page, h, t, c)
-                lo -= page * lay.k_page_bytes * 8
-                hi -= page * lay.k_page_bytes * 8
-                assert lo % 2 == 0
-                used_k[lo:lo + 2] += 1
-                used_k[hi] += 1
+                for pos in ea.q3_k_code_pos(d, page, h, t, c):
+                    used_k[pos - page * lay.k_page_bytes * 8] += 1
             for c in range(r_v):
-                lo, hi = ea.q3_v_code_pos(d, page, h, t, c)
-                lo -= page * lay.v_page_bytes * 8
-                hi -= page * lay.v_page_bytes * 8
-                used_v[lo:lo + 2] += 1
-                used_v[hi] += 1
+                for pos in ea.q3_v_code_pos(d, page, h, t, c):
+                    used_v[pos - page * lay.v_page_bytes * 8] += 1
             sp = ea.q4_v_scale_pos(d, page, h, t) - page * lay.v_page_bytes
             for off in (sp, sp + 128):
                 used_v[8 * off:8 * off + 16] += 1
@@ -546,13 +539,19 @@ def test_q3_positions_tile_the_page_exactly(P, r_k, r_v, Hkv, group):
     assert used_k.max() == 1 and used_v.max() == 1
     assert used_k.sum() == Hkv * P * r_k * 3 + Hkv * (P // group) * r_k * 32
     assert used_v.sum() == Hkv * P * r_v * 3 + Hkv * P * 32
-    # the order inside a unit: token 16*tb + t, channel 32*kk + 8*quad + e -> unit (quad*16 + t) of run kk, group tb
-    for (t, c) in [(0, 0), (17, min(9, r_k - 1)), (63, r_k - 1), (35, min(44, r_k - 1))]:
+    # the order inside a unit: token 16*tb + t, channel 32*kk + 8*quad + e -> unit (quad*16 + t) of run kk, group tb;
+    # groups 0-2: dword tb, bits 3i + b of half word h (e = 2i + h); group 3: bit 3i + b of its half word lives in
+    # nibble (3i + b) / 4, i.e. in bits 12-15 of half word h of that dword
+    for (t, c) in [(0, 0), (17, min(9, r_k - 1)), (63, r_k - 1), (35, min(44, r_k - 1)), (50, min(13, r_k - 1))]:
         tb, tt, kk, quad, e = t // 16, t % 16, c // 32, (c // 8) % 4, c % 8
         unit = kk * 768 + (quad * 16 + tt) * 12
-        lo, hi = ea.q3_k_code_pos(d, 0, 0, t, c)
-        assert lo == (unit + 4 * (tb // 2)) * 8 + 16 * (e % 2) + 8 * (tb % 2) + 2 * (e // 2)
-        assert hi == (unit + 8) * 8 + 16 * (e % 2) + [0, 1, 8, 9][tb] + 2 * (e // 2)
+        i, hh = e // 2, e % 2
+        want = []
+        for b in range(3):
+            sbit = 3 * i + b
+            want.append((unit + 4 * tb) * 8 + 16 * hh + sbit if tb < 3 else
+                        (unit + 4 * (sbit // 4)) * 8 + 16 * hh + 12 + sbit % 4)
+        assert ea.q3_k_code_pos(d, 0, 0, t, c) == tuple(want)
     bad = desc()
     bad.q4_bits = 2
     assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -1
