@@ -138,17 +138,18 @@ def decode_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, alibi_
 
 
 def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0,
-                                    group_tokens: int = GROUP_TOKENS):
+                                    group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """The same for models with rotary position embedding (Sec. 4.3, Eq. 9-10): the cached rank-r keys (of the one
     shared basis Uk) are quantised BEFORE they are brought back to d_head channels and rotated, so this is the
     rotary generation-phase attention over the dequantised rank-r keys and values.
     q [B, H, d_head] (not rotated); the rest as decode_attention_quantized."""
-    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
-    cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
+    rope_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits) for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in rope_views], [v[1] for v in rope_views])
     return ea_oracle.decode_attention_rope(q, cache, Uk, d_head, base)
 
 
-def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group_tokens: int = GROUP_TOKENS):
+def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group_tokens: int = GROUP_TOKENS,
+                                bits: int = 4):
     """Prefill-phase attention (Eq. 2 in the rank-r space, causal) of the LAST n tokens of every sequence over a
     cache whose first n_quant[b] tokens are quantised: plain causal attention over the dequantised values.
     q_r [B, n, H, r_k]; K_list[b] [H_kv, len_b, r_k]; V_list[b] [H_kv, len_b, r_v]; n <= len_b - n_quant[b] (the
@@ -156,12 +157,13 @@ def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group
     n = np.asarray(q_r).shape[1]
     for b in range(len(K_list)):
         assert n <= K_list[b].shape[1] - int(n_quant[b])
-    views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]
-    cache = ea_oracle.RankCache.from_arrays([v[0] for v in views], [v[1] for v in views])
+    prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits)
+                     for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in prefill_views], [v[1] for v in prefill_views])
     return ea_oracle.prefill_attention(q_r, cache, d_head)
 
 
-def chunked_prefill_quantized(q_r, K, V, chunk: int, d_head: int, group_tokens: int = GROUP_TOKENS):
+def chunked_prefill_quantized(q_r, K, V, chunk: int, d_head: int, group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """A prompt of n tokens prefilled chunk by chunk, every chunk's keys and values quantised as soon as the chunk
     has been attended -- so that at no time more than one chunk exists in 16 bits (what the quantisation paragraph
     of the results amounts to for a long prompt): the queries of chunk c see the tokens of chunks < c as their
@@ -175,5 +177,5 @@ def chunked_prefill_quantized(q_r, K, V, chunk: int, d_head: int, group_tokens: 
     for c0 in range(0, n, chunk):
         c1 = min(n, c0 + chunk)
         out[c0:c1] = prefill_attention_quantized(q_r[None, c0:c1], [K[:, :c1]], [V[:, :c1]], [c0], d_head,
-                                                 group_tokens)[0]
+                                                 group_tokens, bits)[0]
     return out

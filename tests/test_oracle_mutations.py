@@ -133,6 +133,18 @@ QUANT = [
     ("the values of a partly quantised cache stay at four bits when three are asked for",
      "            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant], bits))",
      "            Vq[h, :n_quant] = dequantize_values(*quantize_values(V[h, :n_quant]))", "test_three_bit_codes"),
+    ("the rotary form over a quantised cache stays at four bits when three are asked for",
+     "    rope_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits) for b in range(len(K_list))]",
+     "    rope_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens) for b in range(len(K_list))]",
+     "test_three_bit_codes_in_the_rotary_and_the_prefill_form"),
+    ("the prefill over a quantised cache stays at four bits when three are asked for",
+     "    prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits)",
+     "    prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens)",
+     "test_three_bit_codes_in_the_rotary_and_the_prefill_form"),
+    ("a prompt prefilled in chunks quantises its finished chunks at four bits when three are asked for",
+     "                                                 group_tokens, bits)[0]",
+     "                                                 group_tokens)[0]",
+     "test_three_bit_codes_in_the_rotary_and_the_prefill_form"),
     ("zero point at the group's maximum",
      "    return step.astype(np.float16), lo.astype(np.float16)", "    return step.astype(np.float16), hi.astype(np.float16)",
      "test_values_on_the_grid_round_trip_exactly"),

@@ -419,3 +419,36 @@ def test_three_bit_codes():
     assert not np.allclose(got, oq.decode_attention_quantized(q, Kc, Vc, [128], d_h), atol=1e-3)
     # the table's 3-bit rows in its own accounting; this build's format at 3 bits
     assert oq.bits_per_element_q4(80, 80, 128, bits=3) == (3.25, 3.4)
+
+
+def test_three_bit_codes_in_the_rotary_and_the_prefill_form():
+    """bits = 3 reaches the other two attention functions: each equals its plain form over the 3-bit view built by
+    hand from the quantiser (which test_three_bit_codes pins), differs from the 4-bit result, and the last row of
+    the prefill is the generation-phase function; a prompt prefilled in chunks sees its earlier chunks at 3 bits."""
+    g = synth.rng(123)
+    H, Hkv, r_k, r_v, d_h, L, n = 2, 1, 8, 6, 16, 200, 70
+
+    def view3(X, quantize, dequantize, *a):
+        out = np.array(X, np.float64)
+        out[:128] = dequantize(*quantize(X[:128], *a, bits=3))
+        return out
+    K, V = [synth.gaussian(g, (Hkv, L, r_k))], [synth.gaussian(g, (Hkv, L, r_v))]
+    K3 = [np.stack([view3(K[0][0], oq.quantize_keys, oq.dequantize_keys, 64)])]
+    V3 = [np.stack([view3(V[0][0], oq.quantize_values, oq.dequantize_values)])]
+    Uk = synth.orthonormal_basis(g, d_h, r_k)
+    qd = synth.gaussian(g, (1, H, d_h))
+    rope3 = oq.decode_attention_rope_quantized(qd, K, V, [128], Uk, d_h, 100.0, bits=3)
+    assert np.allclose(rope3, ora.decode_attention_rope(qd, ora.RankCache.from_arrays(K3, V3), Uk, d_h, 100.0), rtol=0, atol=1e-13)
+    assert not np.allclose(rope3, oq.decode_attention_rope_quantized(qd, K, V, [128], Uk, d_h, 100.0), atol=1e-3)
+    q = synth.gaussian(g, (1, n, H, r_k))
+    pre3 = oq.prefill_attention_quantized(q, K, V, [128], d_h, bits=3)
+    assert np.allclose(pre3, ora.prefill_attention(q, ora.RankCache.from_arrays(K3, V3), d_h), rtol=0, atol=1e-13)
+    assert not np.allclose(pre3, oq.prefill_attention_quantized(q, K, V, [128], d_h), atol=1e-3)
+    assert np.allclose(pre3[:, -1], oq.decode_attention_quantized(q[:, -1], K, V, [128], d_h, bits=3), rtol=0, atol=1e-13)
+    qa = synth.gaussian(g, (192, H, r_k))
+    Ka, Va = K[0][:, :192], V[0][:, :192]
+    ch3 = oq.chunked_prefill_quantized(qa, Ka, Va, 64, d_h, bits=3)
+    assert np.allclose(ch3[128:], oq.prefill_attention_quantized(qa[None, 128:], [Ka], [Va], [128], d_h, bits=3)[0], rtol=0, atol=1e-13)
+    assert np.array_equal(ch3[:64], oq.chunked_prefill_quantized(qa, Ka, Va, 64, d_h)[:64])
+    assert not np.allclose(ch3[64:], oq.chunked_prefill_quantized(qa, Ka, Va, 64, d_h)[64:], atol=1e-3)
+
