@@ -998,7 +998,7 @@ def bench_prefill_q4(args, torch, ea, synth):
     group = args.q4_key_group
     if C % P or n % C or P % group:
         raise SystemExit("cfg4-q4: the chunk must be whole pages, the prompt whole chunks, a page whole key groups")
-    desc = ea.LayerDesc(d, H, H, s.d_head, r, r, ea.EA_BF16, P, group)
+    desc = ea.LayerDesc(d, H, H, s.d_head, r, r, ea.EA_BF16, P, group, args.q4_bits)
     n_qkv = 3 * H * r
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.BASE_SEED + 4)
@@ -1067,13 +1067,13 @@ def bench_prefill_q4(args, torch, ea, synth):
 
     lay, lay16 = ea.q4_layout_query(desc), ea.cache_layout_query(desc)
     result = {
-        "metric": "low-rank causal prefill over a 4-bit cache: TFLOP/s of the whole prompt, chunk by chunk (cfg4-q4)",
+        "metric": f"low-rank causal prefill over a {args.q4_bits}-bit cache: TFLOP/s of the whole prompt, chunk by chunk (cfg4-q4)",
         "value": round(tf(flops, ms_per_step), 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg4-q4 causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, d_h={s.d_head}, "
                                f"r_k=r_v={r}, in chunks of {C} tokens per sequence; per chunk project_qkv (into the same "
-                               f"{B * cpp} bfloat16 pages) + prefill_attn_q4 (the chunk causally, earlier chunks as 4-bit "
+                               f"{B * cpp} bfloat16 pages) + prefill_attn_q4 (the chunk causally, earlier chunks as {args.q4_bits}-bit "
                                f"codes, key groups of {group} tokens) + quantize_pages_q4 + out_proj; pages of {P} tokens "
                                f"in random order",
                    "batch": B, "n_ctx": n, "r_k": r, "r_v": r, "page_tokens": P, "chunk": C},
@@ -1115,7 +1115,8 @@ def bench_prefill_q4(args, torch, ea, synth):
             V1 = synth.bf16_bits_to_f32(Vb).astype(np.float64)[None]
             lo = max(m - 64, (m - 1) // C * C)               # the block's rows that lie in the chunk of row m - 1
             qrows = q_r[b, lo:m, h].float().cpu().numpy().astype(np.float64)[None, :, None, :]
-            ref = oq.prefill_attention_quantized(qrows, [K1], [V1], [(m - 1) // C * C], s.d_head, group_tokens=group)
+            ref = oq.prefill_attention_quantized(qrows, [K1], [V1], [(m - 1) // C * C], s.d_head, group_tokens=group,
+                                                 bits=args.q4_bits)
             got = o[b, lo:m, h].float().cpu().numpy()[None, :, None, :]
             e = ora.rel_l2(got, ref) if np.isfinite(got).all() else float("inf")
             errs.append(e)

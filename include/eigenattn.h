@@ -310,10 +310,8 @@ EA_API int ea_prefill_attn_alibi(const ea_layer_desc* desc, const void* dev_q_r,
  * layers only: 4 bits; a key scale covers one channel over the 64 tokens of a cache
  * tile or (desc.q4_key_group = 128, the group size of the paper's 4-bit rows) over the
  * 128 tokens of two neighbouring tiles; a value scale covers one token over its r_v
- * channels.  desc.q4_bits = 3 selects 3-bit codes (eight levels: 7 in place of 15 below) for
- * ea_quantize_pages_q4, ea_dequantize_pages_q4, ea_decode_attn_q4 and ea_decode_attn_alibi_q4;
- * ea_decode_attn_rope_q4 and ea_prefill_attn_q4 take 4-bit codes only (EA_ERR_SHAPE otherwise).  The paper gives no
- * rounding rule; the one used here is
+ * channels.  desc.q4_bits = 3 selects 3-bit codes (eight levels: 7 in place of 15 below) in
+ * every call of this section.  The paper gives no rounding rule; the one used here is
  *   zero = fp16(lo), scale = fp16((hi - lo) / 15)   (lo / hi = minimum / maximum of
  *          the group, clamped to +-65504; quotient in float),
  *   code = clip(rint((x - zero) / scale), 0, 15) in float (round half to even), code 0

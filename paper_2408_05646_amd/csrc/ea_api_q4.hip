@@ -215,7 +215,6 @@ int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r, const voi
       !aligned16(dev_v_pool) || !aligned16(dev_out))
     return EA_ERR_ALIGN;
   if (!dev_ws || !aligned16(dev_ws) || ws_bytes < ea_prefill_q4_workspace_bytes(desc, B, n)) return EA_ERR_WORKSPACE;
-  if (desc->q4_bits == 3) return EA_ERR_SHAPE;        // the prefill kernel expands 4-bit codes only
   const Geo gq = make_geo(desc, max_q4_pages, q4_pool_pages);
   const Geo gt = make_geo(desc, max_tail_pages, pool_pages);
   clear_stale_error();
@@ -241,7 +240,6 @@ int ea_decode_attn_rope_q4(const ea_layer_desc* desc, const float* dev_q, const 
   if (B <= 0 || max_q4_pages <= 0 || q4_pool_pages <= 0 || n_splits < 0 || n_splits > 1024) return EA_ERR_ARG;
   if (!(rope_base > 1.0) || !(rope_base < 1e30)) return EA_ERR_ARG;
   if (desc->r_k > desc->d_head || (desc->d_head != 64 && desc->d_head != 128)) return EA_ERR_SHAPE;
-  if (desc->q4_bits == 3) return EA_ERR_SHAPE;        // the rotary kernel expands 4-bit codes only
   if (!aligned16(dev_q) || !aligned16(dev_u_k) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool) ||
       !aligned16(dev_out) || (tail && (!aligned16(dev_k_pool) || !aligned16(dev_v_pool))))
     return EA_ERR_ALIGN;

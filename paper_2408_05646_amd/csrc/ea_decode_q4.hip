@@ -41,7 +41,7 @@ struct DecodeQ4Args {
 // BITS = 4 or 3: the width of a code (see ea_q4.h for the two packings; everything after the unpacking is the same).
 template <int KS, int NCB, bool ALIBI, int BITS = 4>
 __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
-  constexpr bool B3 = BITS == 3;
+  typedef Codes<BITS> CD;
   __shared__ union {
     MergeSmemQ4<NCB> q4;
     DecodeSmem<KS, NCB, 2, 0> tail;
@@ -106,10 +106,10 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   f16x8 negoff, ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    negoff[j] = (j & 2) ? (_Float16)(B3 ? -128.0f : -64.0f) : (_Float16)-1024.0f;   // what the unpacking adds
+    negoff[j] = (j & 2) ? (_Float16)-CD::kOffLo : (_Float16)-1024.0f;   // what the unpacking adds
     ones[j] = (_Float16)1.0f;
   }
-  uint32_t magic1024 = 0x64006400u, magic64 = B3 ? 0x58005800u : 0x54005400u;    // (3-bit codes: 128.0)
+  uint32_t magic1024 = 0x64006400u, magic64 = CD::kMagicLo;    // (3-bit codes: 128.0)
   asm volatile("" : "+v"(magic1024), "+v"(magic64));   // keep them in vector registers
 
   f32x4 acc[NCB];
@@ -124,17 +124,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   u32x4 vc[NVP > 0 ? NVP : 1];
   u32x2 vcl = {0u, 0u};
   f16x8 vsc[2], vzr[2];
-  auto load_unit = [&](const uint8_t* p) -> u32x4 {      // a 16-byte unit, or the 12 bytes of a 3-bit unit
-    if constexpr (B3) {
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
-      const uint32_t d0 = __builtin_nontemporal_load(w), d1 = __builtin_nontemporal_load(w + 1),
-                     d2 = __builtin_nontemporal_load(w + 2);
-      return u32x4{d0, d1, d2, 0u};
-    } else {
-      return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-    }
-  };
-  constexpr int kUnit = B3 ? 12 : 16, kRun = 64 * kUnit;   // bytes of a lane's unit and of a run of 64 of them
+  constexpr int kUnit = CD::kUnit, kRun = CD::kRun;   // bytes of a lane's unit and of a run of 64 of them
 
   struct Pos {
     int tile, lp, tin;
@@ -165,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
       // lanes of a quad the last k-step does not have re-read quad 0's unit; their query channels are zero
       const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
       const int off = kk * kRun + (past ? col : lane) * kUnit;
-      kc[kk] = load_unit(base + off);
+      kc[kk] = CD::template load<true>(base + off);
       const uint8_t* sp = scales + (kk * 4 + quad) * 32;
       ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
       kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
@@ -174,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
   auto load_v = [&](const Pos& p, int page) {
     const uint8_t* base = a.vq_pool + (int64_t)page * qg.v_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.v_tile;
 #pragma unroll
-    for (int pp = 0; pp < NVP; ++pp) vc[pp] = load_unit(base + pp * kRun + lane * kUnit);
+    for (int pp = 0; pp < NVP; ++pp) vc[pp] = CD::template load<true>(base + pp * kRun + lane * kUnit);
     if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * kRun + lane * 8));
     const uint8_t* sp = base + qg.v_codes;
 #pragma unroll
@@ -184,20 +174,10 @@ __global__ __launch_bounds__(256, 2) void decode_q4_kernel(DecodeQ4Args a) {
     }
   };
   // the A operands "offset + code": 16-token block tb of k-step kk; 32-token group u of channel block cb
-  auto k_frag = [&](int kk, int tb) -> f16x8 {
-    if constexpr (B3) return unpack_q3(tb < 3 ? kc[kk][tb] : q3_group3(kc[kk][0], kc[kk][1], kc[kk][2]), magic1024, magic64);
-    else return unpack_q4(kc[kk][tb], magic1024, magic64);
-  };
+  auto k_frag = [&](int kk, int tb) -> f16x8 { return CD::frag(kc[kk], tb, magic1024, magic64); };
   auto v_frag = [&](int cb, int u) -> f16x8 {
-    if constexpr (B3) {
-      if (VODD && cb == NCB - 1) return unpack_q3(vcl[u], magic1024, magic64);
-      const int k = (cb & 1) * 2 + u;
-      const u32x4& un = vc[cb >> 1];
-      return unpack_q3(k < 3 ? un[k] : q3_group3(un[0], un[1], un[2]), magic1024, magic64);
-    } else {
-      if (VODD && cb == NCB - 1) return unpack_q4(vcl[u], magic1024, magic64);
-      return unpack_q4(vc[cb >> 1][(cb & 1) * 2 + u], magic1024, magic64);
-    }
+    if (VODD && cb == NCB - 1) return CD::frag2(vcl, u, magic1024, magic64);
+    return CD::frag(vc[cb >> 1], (cb & 1) * 2 + u, magic1024, magic64);
   };
 
   bool have = cur.tile < t_end;

@@ -44,8 +44,10 @@ struct RopeQ4Smem {
 
 constexpr int kReseedQ4 = 32;   // tiles between exact re-computations of the rotated query
 
-template <int KS, int NCB, int NKK>
+// BITS = 4 or 3: the width of a code (everything after the unpacking is the same).
+template <int KS, int NCB, int NKK, int BITS>
 __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args a) {
+  typedef Codes<BITS> CD;
   __shared__ union {
     MergeSmemQ4<NCB> mg;
     RopeQ4Smem<NKK, KS> rp;
@@ -80,10 +82,10 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
   f16x8 negoff, ones;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;
+    negoff[j] = (j & 2) ? (_Float16)-CD::kOffLo : (_Float16)-1024.0f;
     ones[j] = (_Float16)1.0f;
   }
-  uint32_t magic1024 = 0x64006400u, magic64 = 0x54005400u;
+  uint32_t magic1024 = 0x64006400u, magic64 = CD::kMagicLo;
   asm volatile("" : "+v"(magic1024), "+v"(magic64));
 
   f32x4 acc[NCB];
@@ -170,8 +172,8 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
     for (int kk = 0; kk < KS; ++kk) {
       // lanes of a quad the last k-step does not have re-read quad 0's unit; the basis is zero in their channels
       const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
-      const int off = kk * 1024 + (past ? col : lane) * 16;
-      kc[kk] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+      const int off = kk * CD::kRun + (past ? col : lane) * CD::kUnit;
+      kc[kk] = CD::template load<true>(base + off);
       const uint8_t* sp = scales + (kk * 4 + quad) * 32;
       ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
       kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
@@ -180,19 +182,18 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
   auto load_v = [&](const Pos& p, int page) {
     const uint8_t* base = a.vq_pool + (int64_t)page * qg.v_page + ((int64_t)kvh * tiles_per_page + p.tin) * qg.v_tile;
 #pragma unroll
-    for (int pp = 0; pp < NVP; ++pp)
-      vc[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + pp * 1024 + lane * 16));
-    if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * 1024 + lane * 8));
-    const uint8_t* sp = base + NCB * 512;
+    for (int pp = 0; pp < NVP; ++pp) vc[pp] = CD::template load<true>(base + pp * CD::kRun + lane * CD::kUnit);
+    if constexpr (VODD) vcl = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + NVP * CD::kRun + lane * 8));
+    const uint8_t* sp = base + (NVP * CD::kRun + (VODD ? 512 : 0));      // behind the codes
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       vsc[u] = *reinterpret_cast<const f16x8*>(sp + (u * 4 + quad) * 16);
       vzr[u] = *reinterpret_cast<const f16x8*>(sp + 128 + (u * 4 + quad) * 16);
     }
   };
-  auto v_dword = [&](int cb, int u) -> uint32_t {
-    if (VODD && cb == NCB - 1) return vcl[u];
-    return vc[cb >> 1][(cb & 1) * 2 + u];
+  auto v_frag = [&](int cb, int u) -> f16x8 {
+    if (VODD && cb == NCB - 1) return CD::frag2(vcl, u, magic1024, magic64);
+    return CD::frag(vc[cb >> 1], (cb & 1) * 2 + u, magic1024, magic64);
   };
 
   bool have = cur.tile < t_end;
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
       for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-          kf[tb][ks] = (unpack_q4(kc[ks][2 * sub + tb], magic1024, magic64) + negoff) * ksc[ks] + kzr[ks];
+          kf[tb][ks] = (CD::frag(kc[ks], 2 * sub + tb, magic1024, magic64) + negoff) * ksc[ks] + kzr[ks];
       // the key registers are free again; the load is unconditional (a wave's last tile re-reads itself), so that
       // the registers need no second copy for the path on which nothing is loaded
       if (sub == 1) load_k(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
       corr = mfma16h(negoff, ps, corr);
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb)
-        acc[cb] = mfma16h(unpack_q4(v_dword(cb, sub), magic1024, magic64), ps, acc[cb]);
+        acc[cb] = mfma16h(v_frag(cb, sub), ps, acc[cb]);
     }
     load_v(have_n ? nxt : cur, max(have_n ? page_n : page, 0));
     if (have_n) {
@@ -407,7 +408,9 @@ __global__ __launch_bounds__(256, 2) void decode_rope_q4_kernel(DecodeRopeQ4Args
 
 template <int KS, int NCB, int NKK>
 static void launch_rope_q4(const DecodeRopeQ4Args& a, int32_t B, hipStream_t st) {
-  decode_rope_q4_kernel<KS, NCB, NKK><<<dim3(a.g.n_kv_heads, a.n_splits, B), dim3(256), 0, st>>>(a);
+  const dim3 grid(a.g.n_kv_heads, a.n_splits, B);
+  if (a.qg.bits == 3) decode_rope_q4_kernel<KS, NCB, NKK, 3><<<grid, dim3(256), 0, st>>>(a);
+  else decode_rope_q4_kernel<KS, NCB, NKK, 4><<<grid, dim3(256), 0, st>>>(a);
 }
 
 template <int KS, int NKK>

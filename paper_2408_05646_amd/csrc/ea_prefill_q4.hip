@@ -33,8 +33,10 @@ struct PrefillQ4Args {
 // the 4-bit part, half a tile (32 tokens) per step, and keeps QT blocks of 16 queries as matrix-core columns.
 // HALF: only half a tile is held expanded at a time (larger ranks: half the fragment registers; the next tile's codes
 // are then requested after the second half has been expanded instead of before the first step).
-template <int KS, int NCB, int QT, bool HALF>
+// BITS = 4 or 3: the width of a code.
+template <int KS, int NCB, int QT, bool HALF, int BITS>
 __global__ __launch_bounds__(256, 2) void prefill_q4_kernel(PrefillQ4Args a) {
+  typedef Codes<BITS> CD;
   constexpr int NVP = NCB / 2;          // 16-byte units of value codes per lane
   constexpr bool VODD = (NCB & 1) != 0; // ... plus one 8-byte unit
   const Geo& g = a.g;
@@ -77,9 +79,9 @@ __global__ __launch_bounds__(256, 2) void prefill_q4_kernel(PrefillQ4Args a) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     ones[j] = (_Float16)1.0f;
-    negoff[j] = (j & 2) ? (_Float16)-64.0f : (_Float16)-1024.0f;     // what unpack_q4 adds to the codes
+    negoff[j] = (j & 2) ? (_Float16)-CD::kOffLo : (_Float16)-1024.0f;     // what the unpacking adds to the codes
   }
-  uint32_t magic1024 = 0x64006400u, magic64 = 0x54005400u;
+  uint32_t magic1024 = 0x64006400u, magic64 = CD::kMagicLo;
   asm volatile("" : "+v"(magic1024), "+v"(magic64));
 
   f32x4 acc[QT][NCB], lacc[QT];
@@ -111,25 +113,25 @@ __global__ __launch_bounds__(256, 2) void prefill_q4_kernel(PrefillQ4Args a) {
     for (int kk = 0; kk < KS; ++kk) {
       // lanes of a quad the last k-step does not have re-read quad 0's unit; their query channels are zero
       const bool past = kk == KS - 1 && kk * 4 + quad >= qg.nch;
-      kc[kk] = *reinterpret_cast<const u32x4*>(kbase + kk * 1024 + (past ? col : lane) * 16);
+      kc[kk] = CD::template load<false>(kbase + kk * CD::kRun + (past ? col : lane) * CD::kUnit);
       const uint8_t* sp = scales + (kk * 4 + (past ? 0 : quad)) * 32;
       ksc[kk] = *reinterpret_cast<const f16x8*>(sp);
       kzr[kk] = *reinterpret_cast<const f16x8*>(sp + 16);
     }
     const uint8_t* vbase = a.vq_pool + (int64_t)page * qg.v_page + ((int64_t)kvh * tiles_per_page + tin) * qg.v_tile;
 #pragma unroll
-    for (int pp = 0; pp < NVP; ++pp) vc[pp] = *reinterpret_cast<const u32x4*>(vbase + pp * 1024 + lane * 16);
-    if constexpr (VODD) vcl = *reinterpret_cast<const u32x2*>(vbase + NVP * 1024 + lane * 8);
-    const uint8_t* sp = vbase + NCB * 512;
+    for (int pp = 0; pp < NVP; ++pp) vc[pp] = CD::template load<false>(vbase + pp * CD::kRun + lane * CD::kUnit);
+    if constexpr (VODD) vcl = *reinterpret_cast<const u32x2*>(vbase + NVP * CD::kRun + lane * 8);
+    const uint8_t* sp = vbase + (NVP * CD::kRun + (VODD ? 512 : 0));      // behind the codes
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       vsc[u] = *reinterpret_cast<const f16x8*>(sp + (u * 4 + quad) * 16);
       vzr[u] = *reinterpret_cast<const f16x8*>(sp + 128 + (u * 4 + quad) * 16);
     }
   };
-  auto v_dword = [&](int cb, int u) -> uint32_t {
-    if (VODD && cb == NCB - 1) return vcl[u];
-    return vc[cb >> 1][(cb & 1) * 2 + u];
+  auto v_frag = [&](int cb, int u) -> f16x8 {
+    if (VODD && cb == NCB - 1) return CD::frag2(vcl, u, magic1024, magic64);
+    return CD::frag(vc[cb >> 1], (cb & 1) * 2 + u, magic1024, magic64);
   };
 
   // Tiles after the first run without a search for the tile's maximum, as in the bfloat16 kernel: the exponentials
@@ -156,10 +158,10 @@ __global__ __launch_bounds__(256, 2) void prefill_q4_kernel(PrefillQ4Args a) {
         for (int kk = 0; kk < KS; ++kk)
 #pragma unroll
           for (int tb = 0; tb < 2; ++tb)
-            kf[slot][tb][kk] = (unpack_q4(kc[kk][2 * half + tb], magic1024, magic64) + negoff) * ksc[kk] + kzr[kk];
+            kf[slot][tb][kk] = (CD::frag(kc[kk], 2 * half + tb, magic1024, magic64) + negoff) * ksc[kk] + kzr[kk];
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
-          vf[slot][0][cb] = (unpack_q4(v_dword(cb, half), magic1024, magic64) + negoff) * vsc[half] + vzr[half];
+          vf[slot][0][cb] = (v_frag(cb, half) + negoff) * vsc[half] + vzr[half];
       };
       const bool valid = page >= 0;
       const bool lean = optimistic && !first;         // wave-uniform
@@ -292,7 +294,9 @@ static void launch_prefill_q4(PrefillQ4Args a, hipStream_t st) {
   constexpr int QT = (fits(2, false) || fits(2, true)) ? 2 : 1;
   constexpr bool HALF = !fits(QT, false);
   a.n_qtiles = (a.n_q + 64 * QT - 1) / (64 * QT);
-  prefill_q4_kernel<KS, NCB, QT, HALF><<<dim3((uint32_t)(a.n_qtiles * a.g.n_heads * a.batch)), 256, 0, st>>>(a);
+  const dim3 grid((uint32_t)(a.n_qtiles * a.g.n_heads * a.batch));
+  if (a.qg.bits == 3) prefill_q4_kernel<KS, NCB, QT, HALF, 3><<<grid, 256, 0, st>>>(a);
+  else prefill_q4_kernel<KS, NCB, QT, HALF, 4><<<grid, 256, 0, st>>>(a);
 }
 
 template <int KS>

@@ -188,6 +188,39 @@ __device__ __forceinline__ uint32_t q3_group3(uint32_t d0, uint32_t d1, uint32_t
   return ((d0 >> 12) & 0x000f000fu) | ((d1 >> 8) & 0x00f000f0u) | ((d2 >> 4) & 0x0f000f00u);
 }
 
+// What the kernels that read codes share, for BITS = 4 or 3: a lane's unit of four groups of eight codes as it comes
+// from memory (16 bytes, or 12 in the first three dwords), the A operand "offset + code" of one group, and what the
+// unpacking added: elements 0,1,4,5 carry 1024, elements 2,3,6,7 carry kOffLo.
+template <int BITS>
+struct Codes {
+  static constexpr int kUnit = BITS == 3 ? 12 : 16;       // bytes of a lane's unit
+  static constexpr int kRun = 64 * kUnit;                 // ... of a wave's run of units
+  static constexpr float kOffLo = BITS == 3 ? 128.0f : 64.0f;
+  static constexpr uint32_t kMagicLo = BITS == 3 ? 0x58005800u : 0x54005400u;
+  template <bool NT>
+  __device__ static __forceinline__ u32x4 load(const uint8_t* p) {
+    if constexpr (BITS == 3) {
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(p);
+      if constexpr (NT)
+        return u32x4{__builtin_nontemporal_load(w), __builtin_nontemporal_load(w + 1), __builtin_nontemporal_load(w + 2), 0u};
+      else
+        return u32x4{w[0], w[1], w[2], 0u};
+    } else {
+      if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+      else return *reinterpret_cast<const u32x4*>(p);
+    }
+  }
+  // group k (0..3) of a unit; group u (0..1) of the 8-byte unit of an odd last channel block
+  __device__ static __forceinline__ f16x8 frag(const u32x4& un, int k, uint32_t magic1024, uint32_t magic_lo) {
+    if constexpr (BITS == 3) return unpack_q3(k < 3 ? un[k] : q3_group3(un[0], un[1], un[2]), magic1024, magic_lo);
+    else return unpack_q4(un[k], magic1024, magic_lo);
+  }
+  __device__ static __forceinline__ f16x8 frag2(const u32x2& un, int u, uint32_t magic1024, uint32_t magic_lo) {
+    if constexpr (BITS == 3) return unpack_q3(un[u], magic1024, magic_lo);
+    else return unpack_q4(un[u], magic1024, magic_lo);
+  }
+};
+
 int quantize_pages_q4(const Geo& g, const Q4Geo& qg, const void* k_pool, const void* v_pool, const int32_t* src_pages,
                       void* kq_pool, void* vq_pool, const int32_t* dst_pages, int32_t n_pages, int32_t q4_pool_pages,
                       hipStream_t st);

@@ -894,6 +894,33 @@ def test_decode_over_3_bit_codes_matches_oracle(form, H, Hkv, r_k, r_v, P, group
         assert ora.rel_l2(four, ref[keep]) > 3 * err
 
 
+@pytest.mark.parametrize("H,Hkv,d_h,r_k,r_v,P,group,lens,n_quant,n_splits", [
+    (2, 2, 128, 80, 80, 64, 64, [200, 130, 64], [128, 128, 64], 1),     # the last sequence has no 16-bit part
+    (8, 2, 128, 48, 112, 128, 128, [777, 1500], [768, 1408], 0),        # GQA 4:1, r_k != r_v, key groups of 128
+    (4, 4, 128, 128, 128, 64, 64, [513, 100], [512, 64], 2),            # r_k = d_h
+    (4, 2, 128, 30, 33, 64, 64, [150, 70], [128, 64], 1),               # ranks off the chunk sizes
+    (4, 2, 64, 40, 48, 64, 64, [900, 64], [896, 64], 2),                # d_h = 64; three value blocks
+    (2, 2, 128, 16, 16, 64, 64, [700], [640], 3),                       # a single value block (one two-group unit)
+    (2, 1, 128, 80, 80, 64, 64, [20000], [19968], 1),                   # one workgroup walks 312 tiles
+])
+def test_decode_rope_over_3_bit_codes_matches_oracle(H, Hkv, d_h, r_k, r_v, P, group, lens, n_quant, n_splits):
+    from oracle import eigen_attention as ora
+    print(f"q3 rope decode H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) P={P} group={group} lens={lens} quantised={n_quant} "
+          f"S={n_splits}", flush=True)
+    desc = desc3(H, Hkv, d_h, r_k, r_v, P, group)
+    g = synth.rng(164, H, r_k, len(lens), n_splits)
+    U = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    q = np.float32(synth.gaussian(g, (len(lens), H, d_h), 1.5)).astype(np.float64)
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    got = run_rope_q4(desc, qc, q, U, 10000.0, n_splits)
+    ref = oq.decode_attention_rope_quantized(q, K, V, n_quant, U, d_h, 10000.0, group_tokens=group, bits=3)
+    err = assert_close(got, ref, TOL_BF16, "q3 rope decode")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+    four = oq.decode_attention_rope_quantized(q, K, V, n_quant, U, d_h, 10000.0, group_tokens=group)
+    assert ora.rel_l2(four, ref) > 3 * err          # the kernel follows the 3-bit quantiser, not the 4-bit one
+
+
 def test_3_bit_round_trip_through_the_library():
     """quantise -> dequantise through the library = the oracle's 3-bit round trip, rounded once to bfloat16."""
     desc = desc3(2, 2, 128, 72, 40, 128)

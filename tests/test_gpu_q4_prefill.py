@@ -56,6 +56,31 @@ def test_prefill_attn_q4_matches_oracle(H, Hkv, r_k, r_v, P, group, lens, n_quan
         assert ora.rel_l2(plain, ref) > 3 * err
 
 
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,group,lens,n_quant,n", [
+    (2, 2, 80, 80, 64, 64, [200, 130], [128, 64], 60),            # five value channel blocks: an odd last one
+    (8, 2, 48, 112, 128, 128, [777, 1500], [512, 1280], 200),     # GQA 4:1, r_k != r_v, key groups of 128
+    (4, 4, 128, 128, 64, 64, [513, 400], [256, 192], 129),        # full rank: half tiles, one block of queries per wave
+    (4, 2, 30, 33, 64, 64, [150, 270], [64, 192], 70),            # ranks off the chunk sizes
+    (2, 2, 16, 16, 64, 64, [700], [512], 188),                    # a single value block (one two-group unit)
+    (2, 1, 64, 64, 64, 64, [20300], [19968], 300),                # 312 tiles of codes under 300 queries
+])
+def test_prefill_attn_over_3_bit_codes_matches_oracle(H, Hkv, r_k, r_v, P, group, lens, n_quant, n):
+    print(f"q3 prefill H={H}/{Hkv} r=({r_k},{r_v}) P={P} group={group} lens={lens} quantised={n_quant} n={n}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P, group, 3)
+    g = synth.rng(154, H, r_k, len(lens), n)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    q = quantize(desc, synth.gaussian(g, (len(lens), n, H, r_k), 1.0))
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    got = run_prefill_q4(desc, qc, q)
+    ref = oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group, bits=3)
+    err = assert_close(got, ref, TOL_BF16, "q3 prefill")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+    if max(n_quant) >= 256:
+        # the kernel follows the 3-bit quantiser, not the 4-bit one
+        four = oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group)
+        assert ora.rel_l2(four, ref) > 3 * err
+
+
 def test_prefill_q4_skips_pages_that_are_not_there():
     """A 4-bit page-table entry outside the pool makes that page's tokens vanish instead of being read."""
     desc = ea.LayerDesc(512, 4, 2, 128, 80, 48, ea.EA_BF16, 64)
@@ -74,18 +99,18 @@ def test_prefill_q4_skips_pages_that_are_not_there():
     assert_close(got, ref, TOL_BF16, "q4 prefill with a missing page")
 
 
-@pytest.mark.parametrize("group,P,chunk", [(64, 64, 256), (128, 128, 384)])
-def test_a_prompt_prefilled_in_chunks_never_exists_in_16_bits(group, P, chunk):
+@pytest.mark.parametrize("group,P,chunk,bits", [(64, 64, 256, 4), (128, 128, 384, 4), (64, 64, 256, 3)])
+def test_a_prompt_prefilled_in_chunks_never_exists_in_16_bits(group, P, chunk, bits):
     """A prompt of 4 chunks through one layer: every chunk is projected into the SAME few bfloat16 pages, attended
     (its own tokens causally, all earlier chunks as 4-bit codes), then its pages are quantised into the 4-bit pools
     and the bfloat16 pages are reused.  The bfloat16 pools never hold more than one chunk.  Every chunk's attention
     output follows the oracle that does the same, and a generation step over the fully quantised prompt follows it, too."""
     from test_gpu_layer import make_weights, device_weights
     H, Hkv, d_h, r_k, r_v, d = 8, 2, 128, 80, 48, 512
-    desc = ea.LayerDesc(d, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P, group)
+    desc = ea.LayerDesc(d, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P, group, bits)
     n_chunks = 4
     n_all = n_chunks * chunk
-    g = synth.rng(153, group)
+    g = synth.rng(153, group, bits)
     Wq, Wk, Wv, Wo, Uk, Uv = make_weights(desc, g)
     wqkv_t, wo_t, (Wq_q, Wk_q, Wv_q, Wo_q) = device_weights(desc, ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv))
     x = quantize(desc, synth.gaussian(g, (n_all + 1, d)))
@@ -117,7 +142,8 @@ def test_a_prompt_prefilled_in_chunks_never_exists_in_16_bits(group, P, chunk):
                              torch.from_numpy(ids[c0 // P:(c0 + chunk) // P]).cuda())
         torch.cuda.synchronize()
         got[c0:c0 + chunk] = out.float().cpu().numpy()[0]
-    ref = oq.chunked_prefill_quantized(q_all[:n_all], K[:, :n_all], V[:, :n_all], chunk, d_h, group_tokens=group)
+    ref = oq.chunked_prefill_quantized(q_all[:n_all], K[:, :n_all], V[:, :n_all], chunk, d_h, group_tokens=group,
+                                       bits=bits)
     worst = 0.0
     for c in range(n_chunks):
         worst = max(worst, assert_close(got[c * chunk:(c + 1) * chunk], ref[c * chunk:(c + 1) * chunk], TOL_BF16,
@@ -136,5 +162,5 @@ def test_a_prompt_prefilled_in_chunks_never_exists_in_16_bits(group, P, chunk):
                       stage_table, torch.ones(1, dtype=torch.int32).cuda(), o, 2, ws_d)
     torch.cuda.synchronize()
     q_new, _, _ = ora.project_qkv(x[n_all:], Wq_q, Wk_q, Wv_q)
-    ref_o = oq.decode_attention_quantized(q_new, [K], [V], [n_all], d_h, group_tokens=group)
+    ref_o = oq.decode_attention_quantized(q_new, [K], [V], [n_all], d_h, group_tokens=group, bits=bits)
     assert_close(o.cpu().numpy(), ref_o, TOL_BF16, "generation step over the quantised prompt")

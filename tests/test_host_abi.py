@@ -557,12 +557,13 @@ def test_q3_positions_tile_the_page_exactly(P, r_k, r_v, Hkv, group):
     assert ea.load_library().ea_q4_layout_query(ctypes.byref(bad), ctypes.byref(ea.Q4Layout())) == -1
 
 
-def test_three_bit_codes_are_declined_where_they_are_not_built():
+def test_a_code_width_other_than_3_or_4_is_declined_by_every_call_that_reads_codes():
     lib, d = raw(), desc()
-    d.q4_bits = 3
+    d.q4_bits = 5
     rc = lib.ea_decode_attn_rope_q4(ctypes.byref(d), OK_PTR, OK_PTR, 10000.0, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, None,
                                     None, None, None, 0, 0, OK_PTR, 2, 1, OK_PTR, 1 << 30, None)
-    assert rc == -2
+    assert rc == -1
     rc = lib.ea_prefill_attn_q4(ctypes.byref(d), OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, OK_PTR, OK_PTR, OK_PTR, OK_PTR,
                                 2, 8, OK_PTR, 2, 100, OK_PTR, 1 << 40, None)
-    assert rc == -2
+    assert rc == -1
+
