@@ -1,7 +1,8 @@
 """Seeded random shapes through the C ABI against the fp64 oracle: group sizes, head counts, ranks 8..128 (mostly off
 every chunk size), page sizes, ragged / empty / tile-edge lengths and split counts drawn at random, for the
 generation-phase attention in its five forms (plain, with the attention mass, over the 4-bit cache, ALiBi, rotary)
-and the causal prefill attention, the projection GEMMs, and the fp32 form of every call."""
+and the causal prefill attention, the quantised cache in its four formats (4 or 3 bits, key groups of 64 or 128 tokens:
+position-free and rotary decode, prefill over codes), the projection GEMMs, and the fp32 form of every call."""
 import numpy as np
 import pytest
 import torch
@@ -111,6 +112,39 @@ def test_q4_prefill_alibi_and_rotary_random_shapes(seed):
                             dc.v_pool, dc.page_table, dc.seq_len, orr, n_splits=S_r, ws=ws)
         torch.cuda.synchronize()
         assert_close(orr.cpu().numpy(), ora.decode_attention_rope(qr, cache, U, 128), TOL_BF16, "rotary decode")
+
+
+@pytest.mark.parametrize("seed", [251, 252])
+def test_quantised_cache_random_formats(seed):
+    """Code width (4 or 3 bits) and key group (64 or 128 tokens) drawn with the shape: the position-free and the rotary
+    generation-phase attention and the prefill over codes, each against the oracle that quantises the same way."""
+    from oracle import quant_cache as oq
+    import test_gpu_q4_prefill as q4p
+    rs = np.random.default_rng(seed)
+    for case in range(24):
+        H, Hkv, r_k, r_v, P, lens, S = draw(rs, 1800, with_empty=False)
+        bits, group = int(rs.choice([3, 4])), int(rs.choice([64, 128]))
+        if group == 128 and P % 128:
+            P = 128
+        print(f"seed {seed} case {case}: H={H}/{Hkv} r=({r_k},{r_v}) P={P} bits={bits} group={group} lens={lens} S={S}",
+              flush=True)
+        desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P, group, bits)
+        g = synth.rng(seed, case)
+        B = len(lens)
+        K, V = q4.offset_cache(desc, lens, g, k_std=1.5)
+        n_quant = [int(rs.integers(0, (n - 1) // P + 1)) * P for n in lens]        # at least one token stays in 16 bits
+        qc = q4.Q4Cache(desc, K, V, n_quant, g)
+        q = np.float32(synth.gaussian(g, (B, H, r_k), 1.5)).astype(np.float64)
+        ref = oq.decode_attention_quantized(q, K, V, n_quant, 128, group_tokens=group, bits=bits)
+        assert_close(q4.run_q4(desc, qc, q, S), ref, TOL_BF16, "quantised decode")
+        U = quantize(desc, synth.orthonormal_basis(g, 128, r_k))
+        qr = np.float32(synth.gaussian(g, (B, H, 128), 1.5)).astype(np.float64)
+        ref = oq.decode_attention_rope_quantized(qr, K, V, n_quant, U, 128, 10000.0, group_tokens=group, bits=bits)
+        assert_close(q4.run_rope_q4(desc, qc, qr, U, 10000.0, S), ref, TOL_BF16, "quantised rotary decode")
+        n = min(min(lens[b] - n_quant[b] for b in range(B)), 200)
+        qp = quantize(desc, synth.gaussian(g, (B, n, H, r_k)))
+        ref = oq.prefill_attention_quantized(qp, K, V, n_quant, 128, group_tokens=group, bits=bits)
+        assert_close(q4p.run_prefill_q4(desc, qc, qp), ref, TOL_BF16, "prefill over codes")
 
 
 @pytest.mark.parametrize("seed", [301])
