@@ -100,7 +100,8 @@ def traffic_from_profiles(workload: str):
     names the kernel sources it was measured on and carries their stamp, and `stale` says whether they have
     changed since."""
     name = {"cfg3": "decode_attn_cfg3_hbm_traffic.txt", "cfg3-rope": "decode_attn_rope_cfg3_hbm_traffic.txt",
-            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt",
+            "cfg3-q4": "decode_attn_q4_cfg3_hbm_traffic.txt", "cfg3-q4-3bit": "decode_attn_q3_cfg3_hbm_traffic.txt",
+            "cfg3-h2o": "decode_attn_mass_cfg3_hbm_traffic.txt",
             "cfg2": "decode_attn_cfg2_hbm_traffic.txt", "cfg5": "decode_attn_cfg5_hbm_traffic.txt",
             "cfg3-rope-h2o": "decode_attn_mass_rope_pos_cfg3_hbm_traffic.txt"}.get(workload)
     if name is None:
@@ -702,7 +703,8 @@ def bench_decode(args, torch, ea, synth):
         ("" if splits == [1] else " + merge_splits_kernel") + \
         (" (one ea_decode_attn_rope call)" if rope else " (one ea_decode_attn call)")
     if q4:
-        kern = "decode_q4_kernel (4-bit part and, in its last grid slices, the bf16 newest page) + merge_splits_kernel (one ea_decode_attn_q4 call)"
+        kern = (f"decode_q4_kernel ({args.q4_bits}-bit part and, in its last grid slices, the bf16 newest page) + merge_splits_kernel "
+                "(one ea_decode_attn_q4 call)")
     if h2o:
         kern = ("decode_bf16_kernel (score-storing form) + merge_splits_kernel + mass_from_scores_kernel "
                 "(one ea_decode_attn_mass call)")
@@ -713,7 +715,11 @@ def bench_decode(args, torch, ea, synth):
         kern = ("decode_bf16_kernel (rotary variant with explicit positions, score-storing form) + merge_splits_kernel + "
                 "mass_from_scores_kernel (one ea_decode_attn_mass_rope_pos call)")
 
-    traffic, traffic_src = traffic_from_profiles(args.workload)
+    # (a figure belongs to one cache format: 64-token key groups, and one summary per code width)
+    key = args.workload
+    if q4:
+        key = None if args.q4_key_group != 64 else (key + "-3bit" if args.q4_bits == 3 else key)
+    traffic, traffic_src = traffic_from_profiles(key)
     if traffic_src is not None and traffic_src["stale"]:
         print(f"bench.py: {traffic_src['file']} was measured on other kernel sources "
               f"({traffic_src['measured_on_sources']} != {traffic_src['sources_now']}): roofline.traffic may be out of date",
