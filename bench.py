@@ -676,6 +676,63 @@ def bench_decode(args, torch, ea, synth):
         step()                              # leaves q_r / o / y of the separate calls in place for the parity check
         torch.cuda.synchronize()
 
+    # ---- the same step in TWO launches per layer (ea_decode_layer_fused: projection + append, then attention, split
+    # merge and output projection in one launch), eager and as a HIP-graph replay; its y against the separate calls'
+    fused = None
+    if not q4 and not h2o and B <= 16:
+        y_sep = [l["y"].clone() for l in layers]
+        fws = torch.empty(max(ea.decode_layer_fused_workspace_bytes(l["desc"], B, l["S"], rope) for l in layers) // 4,
+                          dtype=torch.float32, device=dev)
+        fstatus = torch.zeros(1, dtype=torch.int32, device=dev)
+
+        def fused_step():
+            for l in layers:
+                ea.decode_layer(l["desc"], l["x"], l["wqkv"], l["wo"], l["k_pool"], l["v_pool"], l["page_table"],
+                                seq_before, l["y"], l["S"], fws, u_k=l["u_k"], rope_base=ROPE_BASE, status=fstatus,
+                                fused=True)
+
+        for _ in range(max(args.warmup, 1)):
+            fused_step()
+        torch.cuda.synchronize()
+        f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        f0.record()
+        for _ in range(args.steps):
+            fused_step()
+        f1.record()
+        torch.cuda.synchronize()
+        ms_fused = f0.elapsed_time(f1) / args.steps
+        worst = max(float((l["y"].float() - ys.float()).norm() / ys.float().norm()) for l, ys in zip(layers, y_sep))
+        ms_fused_graph = None
+        if not args.no_graph:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                fused_step()
+            torch.cuda.current_stream().wait_stream(side)
+            fgraph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(fgraph):
+                fused_step()
+            fgraph.replay()
+            torch.cuda.synchronize()
+            f0.record()
+            for _ in range(args.steps):
+                fgraph.replay()
+            f1.record()
+            torch.cuda.synchronize()
+            ms_fused_graph = f0.elapsed_time(f1) / args.steps
+        fused = {
+            "ms_per_step": round(ms_fused, 4),             "hip_graph_replay_ms_per_step": None if ms_fused_graph is None else round(ms_fused_graph, 4),
+            "y_rel_l2_vs_separate_calls": round(worst, 6), "status_word": int(fstatus.item()),
+            "what": "the same step through ea_decode_layer_fused" + ("_rope" if rope else "") +
+                    ": two launches per layer (o rounded to bfloat16 once before the output projection)"}
+        if fused["status_word"] != 0 or not worst < 6e-3:
+            print(f"bench.py: two-launch step disagrees with the separate calls ({fused})", file=sys.stderr)
+            fused["ok"] = False
+        else:
+            fused["ok"] = True
+        step()
+        torch.cuda.synchronize()
+
     # ---- algorithmic bytes (what the method itself must move)
     attn_bytes_sum, step_bytes = 0, 0
     for dc in descs:
@@ -762,6 +819,8 @@ def bench_decode(args, torch, ea, synth):
             "ms_per_step": round(ms_per_step_layer, 4),
             "GBps": round(step_bytes / (ms_per_step_layer * 1e-3) / 1e9, 1),
             "what": "the same step through ea_decode_layer" + ("_rope" if rope else "") + " (one call per layer)"},
+        "two_launches_per_layer": None if fused is None else dict(
+            fused, GBps=round(step_bytes / (fused["ms_per_step"] * 1e-3) / 1e9, 1)),
         "step_algorithmic_bytes": step_bytes,
         "fill_seconds": round(t_fill, 1), "timed_wall_seconds": round(wall, 3),
         "paper_context": PAPER_CONTEXT,
@@ -1164,6 +1223,9 @@ def main():
     par = result.get("parity")
     if isinstance(par, dict) and par.get("ok") is False:
         print(f"bench.py: the timed step does not match the oracle: {par}", file=sys.stderr)
+        sys.exit(4)
+    two = result.get("two_launches_per_layer")
+    if isinstance(two, dict) and two.get("ok") is False:
         sys.exit(4)
 
 

@@ -236,6 +236,41 @@ EA_API int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, co
                    int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
                    int32_t* dev_status, void* stream);
 
+/* ea_decode_layer in TWO launches (the same step, Sec. 2 "LLM inference" with the folded weights of Eq. 8; B <= 16):
+ *   launch 1: [q_r | k_r | v_r] = x [W^Q' | W^K' | W^V'] and the append, as ea_project_qkv;
+ *   launch 2: the attention of ea_decode_attn over seq_len[b] + 1 tokens, the merge of the split partials (by the
+ *             workgroup that finishes a (sequence, kv head) last) and y = [o_1 .. o_H] W^O': the last
+ *             min(d / 16, compute units, grid size) workgroups of the grid request their share of W^O', wait until
+ *             every workgroup of the grid has delivered its part of o, and multiply.  o is rounded to bfloat16 once
+ *             before the projection (ea_decode_layer keeps it in float).
+ * Arguments, workspace rules and result as ea_decode_layer, with these differences:
+ *   n_splits: at most 64 (EA_ERR_SHAPE above; 0 = choose, which never exceeds it)
+ *   dev_ws: ea_decode_layer_fused_workspace_bytes(...) bytes (the counters the second launch uses live there; the
+ *           first launch clears them, so the workspace still needs no preparation)
+ *   dev_status: NULL, or a word the caller has set to zero: appends that could not be stored are counted in its low
+ *           bits as in ea_project_qkv, and bit 30 (EA_STATUS_WAIT_EXPIRED) is set if a workgroup of the second
+ *           launch gave up waiting for the rest of its grid -- then dev_y is incomplete.  The wait is bounded
+ *           (ea_set_wait_limit polls of the counter, a few seconds by default) so that the launch always ends.
+ *   Only workgroups that hold at most half of the chip's resident workgroup slots ever wait, and only for
+ *   workgroups dispatched before or with them, so a call that has the GPU to itself, or shares it with kernels
+ *   that do not wait for anything, cannot run into the limit.  Two-launch calls that overlap in time with each
+ *   other on one GPU (different streams) can: serialise them, or use ea_decode_layer.
+ * ea_set_wait_limit(polls >= 1) sets the bound for the calls that follow (process-wide; 1 makes every waiting
+ * workgroup give up at once unless the grid has already finished, which is how the expiry path is tested). */
+#define EA_STATUS_WAIT_EXPIRED (1 << 30)
+EA_API int64_t ea_decode_layer_fused_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits,
+                   int32_t rotary);
+EA_API int ea_decode_layer_fused(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
+                   const void* dev_wo, void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
+                   const int32_t* dev_seq_len, void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages,
+                   int32_t n_splits, void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream);
+EA_API int ea_decode_layer_fused_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
+                   const void* dev_wo, const void* dev_u_k, double rope_base, void* dev_k_pool, void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                   int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                   int32_t* dev_status, void* stream);
+EA_API int ea_set_wait_limit(uint32_t polls);
+
 /* Generation-phase attention for models with rotary position embedding
  * (Sec. 4.3, Eq. 9-10): the query keeps all d_head channels, the cache holds the
  * rank-r_k keys k_r = k U^K of ONE basis U^K shared by all heads, and each cached

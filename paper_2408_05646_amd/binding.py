@@ -21,6 +21,7 @@ __all__ = [
     "quantize_pages_q4", "dequantize_pages_q4", "decode_q4_workspace_bytes", "decode_attn_q4", "decode_attn_rope_q4", "decode_attn_alibi_q4",
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
+    "decode_layer_fused_workspace_bytes", "decode_layer_fused", "decode_layer_fused_rope", "set_wait_limit", "STATUS_WAIT_EXPIRED",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
     "q3_k_code_pos", "q3_v_code_pos",
 ]
@@ -36,11 +37,13 @@ EXPORTED_SYMBOLS = (
     "ea_quantize_pages_q4", "ea_dequantize_pages_q4", "ea_decode_q4_workspace_bytes", "ea_decode_attn_q4", "ea_decode_attn_rope_q4", "ea_decode_attn_alibi_q4",
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
+    "ea_decode_layer_fused_workspace_bytes", "ea_decode_layer_fused", "ea_decode_layer_fused_rope", "ea_set_wait_limit",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
 
 STATIC_SCRATCH_BYTES = 8 * 1024 * 1024      # EA_STATIC_SCRATCH_BYTES of the header
+STATUS_WAIT_EXPIRED = 1 << 30               # EA_STATUS_WAIT_EXPIRED of the header
 
 
 class EigenAttnError(RuntimeError):
@@ -119,8 +122,13 @@ def load_library():
     lib.ea_decode_layer_workspace_bytes.restype = I64
     lib.ea_decode_layer_workspace_bytes.argtypes = [D, I32, I32, I32]
     lib.ea_decode_layer.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP, VP]
+    lib.ea_decode_layer_fused.argtypes = lib.ea_decode_layer.argtypes
+    lib.ea_decode_layer_fused_workspace_bytes.restype = I64
+    lib.ea_decode_layer_fused_workspace_bytes.argtypes = [D, I32, I32, I32]
+    lib.ea_set_wait_limit.argtypes = [ctypes.c_uint32]
     lib.ea_decode_layer_rope.argtypes = [D, VP, VP, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP,
                                          I64, VP, VP]
+    lib.ea_decode_layer_fused_rope.argtypes = lib.ea_decode_layer_rope.argtypes
     lib.ea_decode_attn_static.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP]
     lib.ea_decode_attn_rope.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP]
     lib.ea_decode_attn_rope_pos.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, VP, VP, I32, I32, I32, I32,
@@ -373,11 +381,20 @@ def decode_layer_workspace_bytes(desc, B: int, n_splits: int, rotary: bool = Fal
     return int(load_library().ea_decode_layer_workspace_bytes(ctypes.byref(desc), B, n_splits, int(rotary)))
 
 
+def decode_layer_fused_workspace_bytes(desc, B: int, n_splits: int, rotary: bool = False) -> int:
+    return int(load_library().ea_decode_layer_fused_workspace_bytes(ctypes.byref(desc), B, n_splits, int(rotary)))
+
+
+def set_wait_limit(polls: int) -> None:
+    _check(load_library().ea_set_wait_limit(int(polls)), "ea_set_wait_limit")
+
+
 def decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws, u_k=None,
-                 rope_base: float = 10000.0, status=None, stream=None) -> None:
+                 rope_base: float = 10000.0, status=None, stream=None, fused: bool = False) -> None:
     """One generation step of a layer (projection + append, attention over seq_len + 1 tokens, output projection) in
     one call: x [B, d] -> y [B, d], both bfloat16.  With u_k ([d_head, r_k] bfloat16) the rotary form
-    (ea_decode_layer_rope).  ws: decode_layer_workspace_bytes bytes."""
+    (ea_decode_layer_rope).  ws: decode_layer_workspace_bytes bytes.  fused: the two-launch form
+    (ea_decode_layer_fused / ea_decode_layer_fused_rope; ws: decode_layer_fused_workspace_bytes bytes)."""
     B = seq_len.shape[0]
     _expect(x, desc.dtype, "x"); _expect(y, desc.dtype, "y"); _expect(wqkv, desc.dtype, "wqkv"); _expect(wo, desc.dtype, "wo")
     _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
@@ -393,19 +410,33 @@ def decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_sp
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     lib = load_library()
     if u_k is None:
-        rc = lib.ea_decode_layer(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(k_pool), _ptr(v_pool),
-                                 _ptr(page_table), _ptr(seq_len), _ptr(y), B, page_table.shape[1], k_pool.shape[0],
-                                 n_splits, _ptr(ws), ws_bytes, _ptr(status), _stream(stream))
-        _check(rc, "ea_decode_layer")
+        fn = lib.ea_decode_layer_fused if fused else lib.ea_decode_layer
+        rc = fn(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(k_pool), _ptr(v_pool),
+                _ptr(page_table), _ptr(seq_len), _ptr(y), B, page_table.shape[1], k_pool.shape[0],
+                n_splits, _ptr(ws), ws_bytes, _ptr(status), _stream(stream))
+        _check(rc, "ea_decode_layer_fused" if fused else "ea_decode_layer")
     else:
         _expect(u_k, desc.dtype, "u_k")
         if u_k.numel() != desc.d_head * desc.r_k or not u_k.is_contiguous():
             raise ValueError("u_k must be a contiguous [d_head, r_k] tensor")
-        rc = lib.ea_decode_layer_rope(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(u_k), float(rope_base),
-                                      _ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(y), B,
-                                      page_table.shape[1], k_pool.shape[0], n_splits, _ptr(ws), ws_bytes,
-                                      _ptr(status), _stream(stream))
-        _check(rc, "ea_decode_layer_rope")
+        fn = lib.ea_decode_layer_fused_rope if fused else lib.ea_decode_layer_rope
+        rc = fn(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(u_k), float(rope_base),
+                _ptr(k_pool), _ptr(v_pool), _ptr(page_table), _ptr(seq_len), _ptr(y), B,
+                page_table.shape[1], k_pool.shape[0], n_splits, _ptr(ws), ws_bytes,
+                _ptr(status), _stream(stream))
+        _check(rc, "ea_decode_layer_fused_rope" if fused else "ea_decode_layer_rope")
+
+
+def decode_layer_fused(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws, status=None,
+                       stream=None) -> None:
+    decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits, ws, status=status, stream=stream,
+                 fused=True)
+
+
+def decode_layer_fused_rope(desc, x, wqkv, wo, u_k, rope_base, k_pool, v_pool, page_table, seq_len, y, n_splits: int,
+                            ws, status=None, stream=None) -> None:
+    decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits, ws, u_k=u_k, rope_base=rope_base,
+                 status=status, stream=stream, fused=True)
 
 
 def decode_layer_rope(desc, x, wqkv, wo, u_k, rope_base, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws,

@@ -108,7 +108,8 @@ int ea_pack_weight(const void* dev_w_t, void* dev_packed, int32_t N, int32_t K, 
 static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void* dev_x, const void* dev_wqkv_t,
                             void* dev_q, int32_t q_dtype, void* dev_k_pool, void* dev_v_pool,
                             const int32_t* dev_page_table, const int32_t* dev_seq_len, int32_t B, int32_t T,
-                            int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream) {
+                            int32_t max_pages, int32_t pool_pages, int32_t* dev_status, void* stream,
+                            uint32_t* dev_clear = nullptr, int32_t clear_words = 0) {
   if (!dev_x || !dev_wqkv_t || !dev_q || !dev_k_pool || !dev_v_pool || !dev_page_table || !dev_seq_len)
     return EA_ERR_ARG;
   if (B <= 0 || T <= 0 || max_pages <= 0 || pool_pages <= 0) return EA_ERR_ARG;
@@ -130,6 +131,8 @@ static int project_qkv_impl(const ea_layer_desc* desc, int32_t q_dim, const void
   dst.seq_len = dev_seq_len;
   dst.T = T;
   dst.status = dev_status;
+  dst.clear = dev_clear;
+  dst.clear_words = clear_words;
   dst.g = make_geo(desc, max_pages, pool_pages);
   dst.g.q_dim = q_dim;
   const int32_t N = desc->n_heads * q_dim + desc->n_kv_heads * (desc->r_k + desc->r_v);
@@ -419,7 +422,25 @@ int64_t ea_decode_layer_workspace_bytes(const ea_layer_desc* desc, int32_t B, in
   return layer_ws_bytes(desc, B, n_splits, rotary ? desc->d_head : desc->r_k);
 }
 
-static int decode_layer_impl(const ea_layer_desc* desc, bool rope, const void* dev_x, const void* dev_wqkv,
+// Polls of the arrival counter after which a waiting workgroup of the two-launch step gives up.
+static uint32_t g_wait_limit = 1u << 20;
+
+int ea_set_wait_limit(uint32_t polls) {
+  if (polls == 0) return EA_ERR_ARG;
+  g_wait_limit = polls;
+  return EA_OK;
+}
+
+static int64_t fused_sync_bytes(const ea_layer_desc* desc, int32_t B) {
+  return align256(4 * (1 + (int64_t)B * desc->n_kv_heads));
+}
+
+int64_t ea_decode_layer_fused_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t rotary) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || B > 16 || n_splits < 1 || n_splits > 1024) return -1;
+  return layer_ws_bytes(desc, B, n_splits, rotary ? desc->d_head : desc->r_k) + fused_sync_bytes(desc, B);
+}
+
+static int decode_layer_impl(const ea_layer_desc* desc, bool rope, bool fused, const void* dev_x, const void* dev_wqkv,
                              const void* dev_wo, const void* dev_u_k, double rope_base, void* dev_k_pool,
                              void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y,
                              int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
@@ -444,20 +465,52 @@ static int decode_layer_impl(const ea_layer_desc* desc, bool rope, const void* d
   }
   const int32_t q_dim = rope ? desc->d_head : desc->r_k;
   if (!dev_ws || (reinterpret_cast<uintptr_t>(dev_ws) & 255u)) return EA_ERR_WORKSPACE;
-  if (ws_bytes < layer_ws_bytes(desc, B, n_splits, q_dim)) return EA_ERR_WORKSPACE;
+  if (ws_bytes < layer_ws_bytes(desc, B, n_splits, q_dim) + (fused ? fused_sync_bytes(desc, B) : 0))
+    return EA_ERR_WORKSPACE;
+  if (fused) {
+    if (B > 16 || desc->d_model % 16 != 0 || n_splits > kTailMaxSplits) return EA_ERR_SHAPE;
+    if (ea_decode_workspace_bytes(desc, B, n_splits) >= (int64_t)1 << 31) return EA_ERR_SHAPE;   // 32-bit offsets into the partials
+    if (dev_status && (reinterpret_cast<uintptr_t>(dev_status) & 3u)) return EA_ERR_ALIGN;
+  }
   char* w = (char*)dev_ws;
   float* part = (float*)w;                                   // split partials (nothing when n_splits == 1)
   w += align256(ea_decode_workspace_bytes(desc, B, n_splits));
   float* q = (float*)w;
   w += align256((int64_t)B * desc->n_heads * q_dim * 4);
   float* o = (float*)w;
+  w += align256((int64_t)B * desc->n_heads * desc->r_v * 4);
+  uint32_t* sync = (uint32_t*)w;                             // two-launch form only
   hipStream_t st = (hipStream_t)stream;
-  // a1 + a2: projection and append
+  const int32_t sync_words = 1 + B * desc->n_kv_heads;
+  // a1 + a2: projection and append (two-launch form: its first workgroup also clears the counters of the launch
+  // that follows)
   rc = project_qkv_impl(desc, q_dim, dev_x, dev_wqkv, q, EA_F32, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, B,
-                        1, max_pages, pool_pages, dev_status, stream);
+                        1, max_pages, pool_pages, dev_status, stream, fused ? sync : nullptr, fused ? sync_words : 0);
   if (rc != EA_OK) return rc;
   // a3 over the sequences including the token just appended (the kernels add one to the lengths they read)
   Geo g = make_geo(desc, max_pages, pool_pages);
+  if (fused) {
+    // a3 + merge + a5 in one launch
+    TailArgs t;
+    t.o = (uint16_t*)o;
+    t.w_o = (const uint16_t*)dev_wo;
+    t.y = (uint16_t*)dev_y;
+    t.N = desc->d_model;
+    t.K = desc->n_heads * desc->r_v;
+    t.sync = sync;
+    t.status = dev_status;
+    t.spin_limit = g_wait_limit;
+    t.ws_bytes = (uint32_t)ea_decode_workspace_bytes(desc, B, n_splits);
+    // the workgroups that go on to the projection wait for the rest of the grid: they may hold at most half of
+    // the chip's resident workgroup slots (2 per compute unit), so that everything they wait for can run
+    const int64_t n_wgs = (int64_t)desc->n_kv_heads * n_splits * B;
+    int64_t n_work = desc->d_model / 16;
+    if (n_work > n_wgs) n_work = n_wgs;
+    if (n_work > resident_compute_units()) n_work = resident_compute_units();
+    t.n_work = (int32_t)n_work;
+    return decode_tail_bf16(desc, g, q, rope ? dev_u_k : nullptr, rope_base, dev_k_pool, dev_v_pool, dev_page_table,
+                            dev_seq_len, B, n_splits, part, 1, t, st);
+  }
   if (rope)
     rc = decode_rope_bf16(desc, g, q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B,
                           n_splits, part, st, 0, 0, 1);
@@ -476,8 +529,28 @@ int ea_decode_layer(const ea_layer_desc* desc, const void* dev_x, const void* de
                     void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
                     void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
                     int64_t ws_bytes, int32_t* dev_status, void* stream) {
-  return decode_layer_impl(desc, false, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool, dev_page_table,
-                           dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes, dev_status, stream);
+  return decode_layer_impl(desc, false, false, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream);
+}
+
+int ea_decode_layer_fused(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                          void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
+                          const int32_t* dev_seq_len, void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages,
+                          int32_t n_splits, void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream) {
+  return decode_layer_impl(desc, false, true, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream);
+}
+
+int ea_decode_layer_fused_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                               const void* dev_u_k, double rope_base, void* dev_k_pool, void* dev_v_pool,
+                               const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                               int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                               int32_t* dev_status, void* stream) {
+  return decode_layer_impl(desc, true, true, dev_x, dev_wqkv, dev_wo, dev_u_k, rope_base, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream);
 }
 
 int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
@@ -485,7 +558,7 @@ int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, const voi
                          const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
                          int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
                          int32_t* dev_status, void* stream) {
-  return decode_layer_impl(desc, true, dev_x, dev_wqkv, dev_wo, dev_u_k, rope_base, dev_k_pool, dev_v_pool,
+  return decode_layer_impl(desc, true, false, dev_x, dev_wqkv, dev_wo, dev_u_k, rope_base, dev_k_pool, dev_v_pool,
                            dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
                            dev_status, stream);
 }

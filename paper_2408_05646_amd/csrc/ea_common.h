@@ -169,6 +169,24 @@ int prefill_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, cons
 int decode_scores_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
                        const int32_t* page_table, const int32_t* seq_len, int32_t B, int32_t n_splits, float* ws,
                        float* scores, int32_t s_row, hipStream_t st);
+// The back half of a generation step in one launch (attention over seq_len + seq_add tokens, split merge, output
+// projection); u_k = null: position-free form.
+constexpr int32_t kStatusWaitExpired = 1 << 30;   // bit of the status word: a bounded wait ran out
+constexpr int kTailMaxSplits = 64;                 // splits per sequence the one-launch back half merges
+struct TailArgs {
+  uint16_t* o;            // [B, H * r_v] bf16: merged attention output (workspace)
+  const uint16_t* w_o;    // packed W^O': [N/16][K/32] fragments of 1 KiB
+  uint16_t* y;            // [B, N] bf16
+  int32_t N, K;           // d_model, H * r_v
+  uint32_t* sync;         // [0]: arrivals; [1 + b * H_kv + kv head]: tickets
+  int32_t* status;        // or null
+  uint32_t spin_limit;
+  int32_t n_work;         // workgroups that run the projection: <= N / 16, <= grid size
+  uint32_t ws_bytes;      // of the split partials
+};
+int decode_tail_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
+                     const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
+                     int32_t B, int32_t n_splits, float* ws, int32_t seq_add, const TailArgs& t, hipStream_t st);
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st,
                  float* ml_out = nullptr);   // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
 // Row length (floats) of the per-head scratch rows e / scores for a cache of n_cap tokens: whole tiles, plus a pad
@@ -205,6 +223,10 @@ struct QkvDest {
   int32_t T;
   Geo g;
   int32_t* status = nullptr;   // device word that counts the (sequence, token) appends that could not be stored, or null
+  // Generation-phase kernels only (M <= 64): words the first workgroup sets to zero -- the counters of the launch that
+  // follows in the same call (a kernel boundary lies between the two, so it finds them cleared).
+  uint32_t* clear = nullptr;
+  int32_t clear_words = 0;
 };
 int pack_weight(const void* w_t, void* packed, int32_t N, int32_t K, bool bf16, hipStream_t st);
 int gemm_qkv_bf16(const void* x, const void* w_t, int32_t M, int32_t N, int32_t K, const QkvDest& dst, hipStream_t st);

@@ -115,9 +115,34 @@ union DecodeSmem {
   StreamSmem<KS, NCB, TBN, NKK, SCORES, POS> st;
 };
 
-template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false, bool POS = false>
+// What becomes of one (head, channel) of a workgroup's merged result -- reference exponent mm, row sum lsum,
+// weighted value sum val: the output element when the sequence is not split, else the split partials.  The
+// default uses plain stores (visible to the kernel that comes next); a kernel that goes on to consume the
+// values itself passes an emitter of its own.
+struct PlainEmit {
+  __device__ __forceinline__ void operator()(const DecodeArgs& a, int b, int n_batch, int split, int head, int c,
+                                             int r_v_pad, float mm, float lsum, float val) const {
+    const Geo& g = a.g;
+    if (a.n_splits == 1 && a.ws_slots == 0) {
+      if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
+    } else {
+      const int slots = a.ws_slots > 0 ? a.ws_slots : a.n_splits;
+      const int64_t BHS = (int64_t)n_batch * g.n_heads * slots;
+      const int64_t row = ((int64_t)b * g.n_heads + head) * slots + a.ws_slot0 + split;
+      if (c == 0) {
+        a.ws[row] = mm;
+        a.ws[BHS + row] = lsum;
+      }
+      a.ws[2 * BHS + row * r_v_pad + c] = val;
+    }
+  }
+};
+
+template <int KS, int NCB, int TBN, int WPE, int NKK, bool ALIBI = false, bool SCORES = false, bool POS = false,
+          typename Emit = PlainEmit>
 __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int kvh, const int split, const int b,
-                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK, SCORES, POS>& sm) {
+                                                 const int n_batch, DecodeSmem<KS, NCB, TBN, NKK, SCORES, POS>& sm,
+                                                 const Emit& emit = Emit{}) {
   constexpr bool ROPE = NKK > 0;
   static_assert(!(ROPE && ALIBI), "a model has one position scheme");
   static_assert(!POS || ROPE, "explicit positions matter to the rotary form only");
@@ -653,19 +678,7 @@ __device__ __forceinline__ void decode_bf16_body(const DecodeArgs& a, const int 
         val += wt * sm_acc[w][hd][c];
       }
     }
-    const int head = kvh * G + hd;
-    if (a.n_splits == 1 && a.ws_slots == 0) {
-      if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
-    } else {
-      const int slots = a.ws_slots > 0 ? a.ws_slots : a.n_splits;
-      const int64_t BHS = (int64_t)n_batch * g.n_heads * slots;
-      const int64_t row = ((int64_t)b * g.n_heads + head) * slots + a.ws_slot0 + split;
-      if (c == 0) {
-        a.ws[row] = mm;
-        a.ws[BHS + row] = lsum;
-      }
-      a.ws[2 * BHS + row * r_v_pad + c] = val;
-    }
+    emit(a, b, n_batch, split, kvh * G + hd, c, r_v_pad, mm, lsum, val);
   }
 }
 

@@ -404,6 +404,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_skinny_kernel(const void* __res
   // compiler wait for it on the spot.)
   typename Epilogue::RowLookup look = ep.lookup_begin(tid < M ? tid : 0);
   bool looked = false;
+  if (blockIdx.x == 0) ep.clear(tid, 512);
 
   // the waves interleave the k steps (neighbouring waves stream neighbouring kilobytes of the weights)
   for (int s0 = wave; s0 < steps; s0 += WAVES * UN) {     // this wave: steps s0, s0 + WAVES, ...
@@ -521,6 +522,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_skinny_pipe_kernel(const uint16
   __shared__ f32x4 stage[kPipeMaxUnits][64];
 
   typename Epilogue::RowLookup look = ep.lookup_begin(tid < M ? tid : 0);
+  if (blockIdx.x == 0) ep.clear(tid, 512);
   // this lane's part of the weight / activation fragment of its wave's u-th k step, or beyond every descriptor
   uint32_t w_off[UN], a_off[UN];
 #pragma unroll
@@ -657,6 +659,9 @@ struct QkvEpBf16 {
     return rw;
   }
   __device__ __forceinline__ Col column(int c) const { return qkv_col(d, c); }
+  __device__ __forceinline__ void clear(int tid, int nthreads) const {
+    for (int i = tid; i < d.clear_words; i += nthreads) d.clear[i] = 0u;
+  }
   __device__ __forceinline__ void put(const Col& cl, const Row& rw, int r, float v) const { qkv_put<true>(d, cl, rw, r, v); }
   __device__ __forceinline__ bool swap_for(int c0) const {
     const Geo& g = d.g;
@@ -769,6 +774,7 @@ struct PlainEpBf16 {
   __device__ __forceinline__ void lookup_next(RowLookup&) const {}
   __device__ __forceinline__ Row lookup_end(const RowLookup&, bool) const { return Row{}; }
   __device__ __forceinline__ Col column(int c) const { return c; }
+  __device__ __forceinline__ void clear(int, int) const {}
   __device__ __forceinline__ void put(const Col& c, const Row&, int r, float v) const { y[(int64_t)r * N + c] = f32_to_bf16_rne(v); }
   __device__ __forceinline__ bool swap_for(int) const { return true; }
   template <int MI>

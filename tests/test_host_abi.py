@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 48
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 52
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -567,3 +567,30 @@ def test_a_code_width_other_than_3_or_4_is_declined_by_every_call_that_reads_cod
                                 2, 8, OK_PTR, 2, 100, OK_PTR, 1 << 40, None)
     assert rc == -1
 
+
+
+def test_layer_step_entry_points_reject_bad_arguments_before_launching():
+    lib = raw()
+    d = desc(H=8, Hkv=2, r_k=80, r_v=48, P=64, d=512)
+
+    def call(fn, dd=d, x=OK_PTR, wo=OK_PTR, y=OK_PTR, B=4, n_splits=2, ws=OK_PTR, ws_bytes=1 << 30, status=None):
+        return fn(ctypes.byref(dd), x, OK_PTR, wo, OK_PTR, OK_PTR, OK_PTR, OK_PTR, y, B, 4, 16, n_splits, ws, ws_bytes,
+                  status, None)
+
+    for fn, need in ((lib.ea_decode_layer, ea.decode_layer_workspace_bytes(d, 4, 2)),
+                     (lib.ea_decode_layer_fused, ea.decode_layer_fused_workspace_bytes(d, 4, 2))):
+        assert call(fn, x=None) == -1 and call(fn, y=None) == -1 and call(fn, B=0) == -1 and call(fn, n_splits=1025) == -1
+        assert call(fn, wo=ODD_PTR) == -3
+        assert call(fn, ws=None) == -4 and call(fn, ws_bytes=need - 1) == -4
+        assert call(fn, ws=OK_PTR + 16) == -4                              # the workspace must be 256-byte aligned
+        assert call(fn, dd=desc(dtype=ea.EA_F32, P=64)) == -2              # bf16 layers only
+        assert call(fn, dd=desc(H=8, Hkv=2, r_k=80, r_v=47, P=64, d=512)) == -2   # H * r_v must be a multiple of 32
+    # the two-launch form: at most 16 sequences and 64 splits, and it brings its counters in the workspace
+    assert call(lib.ea_decode_layer_fused, B=17, n_splits=1) == -2
+    assert call(lib.ea_decode_layer_fused, n_splits=65) == -2
+    assert ea.decode_layer_fused_workspace_bytes(d, 4, 2) == ea.decode_layer_workspace_bytes(d, 4, 2) + 256
+    assert ea.decode_layer_fused_workspace_bytes(d, 17, 1) == -1
+    assert call(lib.ea_decode_layer_fused, status=OK_PTR + 2) == -3
+    assert lib.ea_set_wait_limit(0) == -1 and lib.ea_set_wait_limit(1 << 20) == 0
+    header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
+    assert re.search(r"#define\s+EA_STATUS_WAIT_EXPIRED\s+\(1 << 30\)", header) and ea.STATUS_WAIT_EXPIRED == 1 << 30
