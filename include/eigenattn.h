@@ -213,9 +213,8 @@ EA_API int ea_decode_attn_static(const ea_layer_desc* desc, const void* dev_q_r,
  *   [q_r | k_r | v_r] = x [W^Q' | W^K' | W^V'],  K_r <- Concat(K_r, k_r), V_r <- Concat(V_r, v_r)   (ea_project_qkv, T = 1)
  *   o = Softmax(q_r K_r^T / sqrt(d_h)) V_r over the seq_len[b] + 1 cached tokens                       (ea_decode_attn)
  *   y = [o_1 .. o_H] W^O'                                                                                (ea_out_proj)
- * enqueued back to back on the stream: three launches, four when the sequence is split (the merge of the split
- * partials is a launch of its own: merging inside the attention launch, by the workgroup that finishes last, was
- * built and measured no faster on MI355X).  q_r and o never leave the workspace.  EA_BF16 layers only.
+ * enqueued back to back on the stream: three launches, four when the sequence is split (ea_decode_layer_fused
+ * below does the same step in two).  q_r and o never leave the workspace.  EA_BF16 layers only.
  *   dev_x [B, d] bfloat16; dev_wqkv / dev_wo packed as for ea_project_qkv / ea_out_proj; dev_y [B, d] bfloat16
  *   dev_seq_len [B]: lengths BEFORE this step (the token is appended at that position); not modified
  *   n_splits: as ea_decode_attn (0 = choose)
