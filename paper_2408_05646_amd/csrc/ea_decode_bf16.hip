@@ -5,6 +5,8 @@ namespace ea {
 
 // out[b, h, :] = sum_s w_s acc_s / sum_s w_s l_s with w_s = 2^(m_s - max_s m_s).  With ml_out, the row's
 // reference exponent max_s m_s and normaliser sum_s w_s l_s are stored too, as ml_out[2 (b H + h)], [.. + 1].
+// The loads of up to eight splits are requested together (a split past the last reads the last one again and is
+// ignored), so a row with at most eight splits costs one round trip to memory, not one per split.
 __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, int32_t BH, int32_t S,
                                     int32_t r_v, int32_t r_v_pad, float* __restrict__ ml_out) {
   const int64_t bh = blockIdx.x;
@@ -12,25 +14,61 @@ __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restr
   const float* pm = ws + bh * S;
   const float* pl = ws + BHS + bh * S;
   const float* pa = ws + 2 * BHS + bh * S * r_v_pad;
-  float mm = -INFINITY;
-  for (int s = 0; s < S; ++s) mm = fmaxf(mm, pm[s]);
-  if (ml_out && threadIdx.x == 0) {
-    float lsum = 0.f;
-    if (mm != -INFINITY)
-      for (int s = 0; s < S; ++s) lsum += __builtin_amdgcn_exp2f(pm[s] - mm) * pl[s];
-    ml_out[2 * bh] = mm;
-    ml_out[2 * bh + 1] = lsum;
-  }
-  for (int c = threadIdx.x; c < r_v; c += blockDim.x) {
-    float lsum = 0.f, val = 0.f;
-    if (mm != -INFINITY) {
-      for (int s = 0; s < S; ++s) {
-        const float wt = __builtin_amdgcn_exp2f(pm[s] - mm);
-        lsum += wt * pl[s];
-        val += wt * pa[(int64_t)s * r_v_pad + c];
+  for (int c0 = 0; c0 < r_v; c0 += blockDim.x) {
+    const int c = min(c0 + (int)threadIdx.x, r_v - 1);      // surplus threads repeat the last channel and store nothing
+    float mm = -INFINITY, lsum = 0.f, val = 0.f;
+    if (S <= 8) {
+      float m8[8], l8[8], a8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int s = min(u, S - 1);
+        m8[u] = pm[s];
+        l8[u] = pl[s];
+        a8[u] = pa[(int64_t)s * r_v_pad + c];
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (u < S) mm = fmaxf(mm, m8[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        if (u < S && mm != -INFINITY) {
+          const float wt = __builtin_amdgcn_exp2f(m8[u] - mm);
+          lsum += wt * l8[u];
+          val += wt * a8[u];
+        }
+      }
+    } else {
+      for (int s0 = 0; s0 < S; s0 += 8) {
+        float m8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m8[u] = pm[min(s0 + u, S - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mm = fmaxf(mm, m8[u]);
+      }
+      for (int s0 = 0; s0 < S && mm != -INFINITY; s0 += 8) {
+        float m8[8], l8[8], a8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int s = min(s0 + u, S - 1);
+          m8[u] = pm[s];
+          l8[u] = pl[s];
+          a8[u] = pa[(int64_t)s * r_v_pad + c];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          if (s0 + u < S) {
+            const float wt = __builtin_amdgcn_exp2f(m8[u] - mm);
+            lsum += wt * l8[u];
+            val += wt * a8[u];
+          }
+        }
       }
     }
-    out[bh * r_v + c] = lsum > 0.f ? val / lsum : 0.f;
+    if (ml_out && c0 == 0 && threadIdx.x == 0) {
+      ml_out[2 * bh] = mm;
+      ml_out[2 * bh + 1] = lsum;
+    }
+    if (c0 + (int)threadIdx.x < r_v) out[bh * r_v + c] = lsum > 0.f ? val / lsum : 0.f;
   }
 }
 
