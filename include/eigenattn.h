@@ -257,6 +257,9 @@ EA_API int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, co
  * ea_set_wait_limit(polls >= 1) sets the bound for the calls that follow (process-wide; 1 makes every waiting
  * workgroup give up at once unless the grid has already finished, which is how the expiry path is tested). */
 #define EA_STATUS_WAIT_EXPIRED (1 << 30)
+/* How many workgroups of the second launch project (and therefore wait): min(d / 16, compute units, grid size),
+ * -1 on a bad description.  Host arithmetic only. */
+EA_API int32_t ea_decode_layer_fused_workers(const ea_layer_desc* desc, int32_t B, int32_t n_splits);
 EA_API int64_t ea_decode_layer_fused_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits,
                    int32_t rotary);
 EA_API int ea_decode_layer_fused(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,

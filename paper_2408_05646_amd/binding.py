@@ -22,6 +22,7 @@ __all__ = [
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
     "decode_layer_fused_workspace_bytes", "decode_layer_fused", "decode_layer_fused_rope", "set_wait_limit", "STATUS_WAIT_EXPIRED",
+    "decode_layer_fused_workers",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
     "q3_k_code_pos", "q3_v_code_pos",
 ]
@@ -38,6 +39,7 @@ EXPORTED_SYMBOLS = (
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
     "ea_decode_layer_fused_workspace_bytes", "ea_decode_layer_fused", "ea_decode_layer_fused_rope", "ea_set_wait_limit",
+    "ea_decode_layer_fused_workers",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
@@ -126,6 +128,8 @@ def load_library():
     lib.ea_decode_layer_fused_workspace_bytes.restype = I64
     lib.ea_decode_layer_fused_workspace_bytes.argtypes = [D, I32, I32, I32]
     lib.ea_set_wait_limit.argtypes = [ctypes.c_uint32]
+    lib.ea_decode_layer_fused_workers.restype = I32
+    lib.ea_decode_layer_fused_workers.argtypes = [D, I32, I32]
     lib.ea_decode_layer_rope.argtypes = [D, VP, VP, VP, VP, ctypes.c_double, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP,
                                          I64, VP, VP]
     lib.ea_decode_layer_fused_rope.argtypes = lib.ea_decode_layer_rope.argtypes
@@ -383,6 +387,10 @@ def decode_layer_workspace_bytes(desc, B: int, n_splits: int, rotary: bool = Fal
 
 def decode_layer_fused_workspace_bytes(desc, B: int, n_splits: int, rotary: bool = False) -> int:
     return int(load_library().ea_decode_layer_fused_workspace_bytes(ctypes.byref(desc), B, n_splits, int(rotary)))
+
+
+def decode_layer_fused_workers(desc, B: int, n_splits: int) -> int:
+    return int(load_library().ea_decode_layer_fused_workers(ctypes.byref(desc), B, n_splits))
 
 
 def set_wait_limit(polls: int) -> None:

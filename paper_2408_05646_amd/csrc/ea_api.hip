@@ -435,6 +435,19 @@ static int64_t fused_sync_bytes(const ea_layer_desc* desc, int32_t B) {
   return align256(4 * (1 + (int64_t)B * desc->n_kv_heads));
 }
 
+// Workgroups of the second launch that go on to the output projection.  They wait for the rest of the grid, so
+// they may hold at most half of the chip's resident workgroup slots (2 per compute unit): then every workgroup
+// they wait for finds a slot.  (Workgroups go to the chip's eight dies in turn and each die dispatches its share in
+// order, so the bound holds per die as well: the waiting workgroups are the last of every die's share.)
+int32_t ea_decode_layer_fused_workers(const ea_layer_desc* desc, int32_t B, int32_t n_splits) {
+  if (validate_desc(desc) != EA_OK || B <= 0 || n_splits < 1) return -1;
+  const int64_t n_wgs = (int64_t)desc->n_kv_heads * n_splits * B;
+  int64_t n_work = desc->d_model / 16;
+  if (n_work > n_wgs) n_work = n_wgs;
+  if (n_work > resident_compute_units()) n_work = resident_compute_units();
+  return (int32_t)(n_work < 1 ? 1 : n_work);
+}
+
 int64_t ea_decode_layer_fused_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t rotary) {
   if (validate_desc(desc) != EA_OK || B <= 0 || B > 16 || n_splits < 1 || n_splits > 1024) return -1;
   return layer_ws_bytes(desc, B, n_splits, rotary ? desc->d_head : desc->r_k) + fused_sync_bytes(desc, B);
@@ -503,11 +516,7 @@ static int decode_layer_impl(const ea_layer_desc* desc, bool rope, bool fused, c
     t.ws_bytes = (uint32_t)ea_decode_workspace_bytes(desc, B, n_splits);
     // the workgroups that go on to the projection wait for the rest of the grid: they may hold at most half of
     // the chip's resident workgroup slots (2 per compute unit), so that everything they wait for can run
-    const int64_t n_wgs = (int64_t)desc->n_kv_heads * n_splits * B;
-    int64_t n_work = desc->d_model / 16;
-    if (n_work > n_wgs) n_work = n_wgs;
-    if (n_work > resident_compute_units()) n_work = resident_compute_units();
-    t.n_work = (int32_t)n_work;
+    t.n_work = ea_decode_layer_fused_workers(desc, B, n_splits);
     return decode_tail_bf16(desc, g, q, rope ? dev_u_k : nullptr, rope_base, dev_k_pool, dev_v_pool, dev_page_table,
                             dev_seq_len, B, n_splits, part, 1, t, st);
   }

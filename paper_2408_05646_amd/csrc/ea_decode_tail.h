@@ -9,8 +9,9 @@
 //   * one arrival count for the whole grid, raised by every workgroup when it has nothing more to write to o.
 // Only the LAST n_work workgroups of the grid (in dispatch order) go on to the projection: each requests the
 // weights of its first block of 16 output channels, THEN waits for the arrival count to reach the grid size, and
-// multiplies.  No other workgroup ever waits, workgroups are dispatched in order, and the waiting ones fill at
-// most half of the chip's resident slots, so every workgroup they wait for can run: the wait ends.  It is bounded
+// multiplies.  No other workgroup ever waits, workgroups are dispatched in order (to the chip's dies in turn, in
+// order on each die), and the waiting ones fill at most half of the resident slots of the chip and of every die,
+// so every workgroup they wait for can run: the wait ends.  It is bounded
 // all the same (spin_limit polls); a workgroup whose wait runs out sets bit 30 of the status word, writes no y
 // and leaves.
 // Values that cross workgroups are read with loads that bypass the caches of the reading compute unit and its L2.

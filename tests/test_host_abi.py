@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 52
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 53
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -594,3 +594,48 @@ def test_layer_step_entry_points_reject_bad_arguments_before_launching():
     assert lib.ea_set_wait_limit(0) == -1 and lib.ea_set_wait_limit(1 << 20) == 0
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     assert re.search(r"#define\s+EA_STATUS_WAIT_EXPIRED\s+\(1 << 30\)", header) and ea.STATUS_WAIT_EXPIRED == 1 << 30
+
+
+def _dispatch_model_finishes(n_wgs, n_work, slots_per_die, dies=8):
+    """The second launch of the two-launch layer step as the chip runs it: workgroup i belongs to die i % dies, a die
+    starts its workgroups in order as slots come free, the last n_work workgroups of the grid wait (holding their
+    slot) until every workgroup has arrived, all others arrive and leave.  True if every workgroup gets to leave."""
+    queue = [[i for i in range(n_wgs) if i % dies == x] for x in range(dies)]
+    nxt = [0] * dies                       # next workgroup of each die's share to start
+    held = [0] * dies                      # slots held by waiting workgroups
+    arrived = 0
+    while True:
+        progress = False
+        for x in range(dies):
+            while nxt[x] < len(queue[x]) and held[x] < slots_per_die:
+                wg = queue[x][nxt[x]]
+                nxt[x] += 1
+                arrived += 1
+                progress = True
+                if wg >= n_wgs - n_work:
+                    held[x] += 1           # waits for the whole grid in its slot
+        if arrived == n_wgs:
+            return True                    # the waiting ones see the count and leave
+        if not progress:
+            return False                   # every free slot is held by a workgroup that waits for one not started
+
+
+def test_workgroups_that_wait_never_block_the_ones_they_wait_for():
+    # the rule the library applies (ea_decode_layer_fused_workers) keeps the waiting workgroups within half of the
+    # resident slots: 2 per compute unit, 256 compute units in 8 dies on MI355X (also what the library assumes when it
+    # cannot ask a device)
+    slots_per_die = 2 * 256 // 8
+    for d_model in (256, 4096, 8192, 16384):
+        for Hkv in (2, 8, 32):
+            for B in (1, 8, 16):
+                for S in (1, 4, 8, 64):
+                    dd = ea.LayerDesc(d_model, 32, Hkv, 128, 80, 80, ea.EA_BF16, 64)
+                    n_work = ea.decode_layer_fused_workers(dd, B, S)
+                    n_wgs = Hkv * S * B
+                    assert 1 <= n_work <= min(d_model // 16, n_wgs, 256)
+                    assert _dispatch_model_finishes(n_wgs, n_work, slots_per_die)
+    # and the model does tell the difference: more waiting workgroups than a die has slots never finish ...
+    assert not _dispatch_model_finishes(n_wgs=4096, n_work=1024, slots_per_die=slots_per_die)
+    # ... while half the slots are safe however long the grid
+    assert _dispatch_model_finishes(n_wgs=1 << 16, n_work=256, slots_per_die=slots_per_die)
+    assert ea.decode_layer_fused_workers(desc(H=8, Hkv=3), 4, 1) == -1
