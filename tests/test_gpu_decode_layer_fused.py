@@ -40,6 +40,7 @@ def layer_weights(desc, g, rope):
     (256, 2, 1, 32, 16, 1, 70, 1),           # a single workgroup does everything
     (512, 8, 2, 80, 48, 2, 1700, 12),        # more than eight splits: the merge goes through LDS
     (4096, 32, 32, 128, 128, 2, 300, 2),     # full rank: 4096 channels, two rounds of weights per wave
+    (8192, 8, 2, 80, 48, 2, 200, 2),         # d = 8192: the projection launch takes its general form; 512 channel blocks
 ])
 def test_fused_decode_layer_matches_oracle_decode_step(rope, d, H, Hkv, r_k, r_v, B, n0, S):
     print(f"fused decode layer rope={rope} d={d} H={H}/{Hkv} r=({r_k},{r_v}) B={B} n0={n0} S={S}", flush=True)
