@@ -207,3 +207,38 @@ def test_fused_decode_layers_are_graph_capturable():
         for y, e in zip(ys, eager):
             assert torch.equal(y, e), f"replay {rep} differs from the eager result"
     assert int(status.item()) == 0
+
+
+def test_fused_decode_layer_beside_other_work_on_the_gpu():
+    """The two-launch step while another stream keeps the compute units busy with kernels that wait for nothing
+    (large matrix products): the projecting workgroups may have to wait longer for the rest of their grid, which is
+    dispatched as slots come free, but the wait ends, nothing expires and the result is the one of a quiet GPU."""
+    d, H, Hkv, r_k, r_v, B, S = 1024, 32, 8, 64, 64, 8, 8              # 512 workgroups: every resident slot
+    desc = ea.LayerDesc(d, H, Hkv, 128, r_k, r_v, ea.EA_BF16, 64)
+    g = synth.rng(101)
+    K0, V0 = random_cache(desc, [2100 - 7 * b for b in range(B)], g)
+    dc = DeviceCache(desc, K0, V0, g, extra_len=1)
+    wqkv, wo, _, _, _ = layer_weights(desc, g, False)
+    xd = to_dev(desc, quantize(desc, synth.gaussian(g, (B, d))))
+    ws = torch.empty(ea.decode_layer_fused_workspace_bytes(desc, B, S) // 4, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    y_quiet = torch.empty((B, d), dtype=torch.bfloat16, device="cuda")
+    k_before, v_before = dc.k_pool.clone(), dc.v_pool.clone()
+    ea.decode_layer(desc, xd, wqkv, wo, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y_quiet, S, ws, status=status,
+                    fused=True)
+    torch.cuda.synchronize()
+    a = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    y = torch.empty_like(y_quiet)
+    for rep in range(3):
+        dc.k_pool.copy_(k_before); dc.v_pool.copy_(v_before)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            for _ in range(40):
+                a @ a                                            # a few milliseconds of other kernels
+        for _ in range(10):
+            ea.decode_layer(desc, xd, wqkv, wo, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y, S, ws,
+                            status=status, fused=True)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        assert torch.equal(y, y_quiet), f"round {rep}"
