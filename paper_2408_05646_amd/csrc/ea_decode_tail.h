@@ -11,9 +11,8 @@
 // weights of its first block of 16 output channels, THEN waits for the arrival count to reach the grid size, and
 // multiplies.  No other workgroup ever waits, workgroups are dispatched in order (to the chip's dies in turn, in
 // order on each die), and the waiting ones fill at most half of the resident slots of the chip and of every die,
-// so every workgroup they wait for can run: the wait ends.  It is bounded
-// all the same (spin_limit polls); a workgroup whose wait runs out sets bit 30 of the status word, writes no y
-// and leaves.
+// so every workgroup they wait for can run: the wait ends.  It is bounded all the same (spin_limit polls); a
+// workgroup whose wait runs out sets bit 30 of the status word, writes no y and leaves.
 // Values that cross workgroups are read with loads that bypass the caches of the reading compute unit and its L2.
 #pragma once
 #include "ea_decode_kernel.h"
@@ -24,7 +23,6 @@ namespace ea {
 constexpr int kCoherent = 17;              // cache policy sc0 sc1: write through to / read from memory
 constexpr int kTailRound = 24;             // k steps of 32 per wave and round of the projection (3072 channels)
 constexpr uint32_t kOobTail = 0x7ffffff0u; // an offset beyond every buffer descriptor: reads as zero
-
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tail_rsrc(const void* p, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
