@@ -781,6 +781,12 @@ def bench_decode(args, torch, ea, synth):
         print(f"bench.py: {traffic_src['file']} was measured on other kernel sources "
               f"({traffic_src['measured_on_sources']} != {traffic_src['sources_now']}): roofline.traffic may be out of date",
               file=sys.stderr)
+    if traffic is not None and not 0.95 <= traffic / attn_bytes <= 1.5:
+        # (a summary whose counters were scaled wrongly, not a property of the kernel: say so rather than report it)
+        print(f"bench.py: {traffic_src['file']} holds {traffic:.0f} bytes per launch against {attn_bytes:.0f} algorithmic: "
+              "not a plausible HBM traffic for this kernel, left out", file=sys.stderr)
+        traffic_src["implausible_bytes"] = traffic
+        traffic = None
     rank_note = f"r_k=r_v={s.r_k}" if base_name != "cfg5" else "per-layer (r_k, r_v) drawn from {48,64,80,96,112}"
     result = {
         "metric": "low-rank decode attn: achieved HBM GB/s over the whole decode step"
