@@ -469,6 +469,109 @@ def check_step_parity(torch, ea, synth, layers, s, B, n, P, rope, n_samples, see
     return res, streams0
 
 
+def check_step_parity_q4(torch, ea, synth, layers, s, B, n, P, rope, n_samples, seed, bits, key_group):
+    """The timed step over the group-quantised cache against the fp64 oracle: for sampled (layer, sequence, kv head)
+    triples the codes, scales and zeros of the stream are gathered from raw pool memory at the positions the
+    library's host reference functions give (ea_q4_*_pos / ea_q3_*_pos), dequantised by the oracle, joined with the
+    bfloat16 newest page, and attended by the oracle with the step's own queries."""
+    import numpy as np
+    from oracle import eigen_attention as ora
+    from oracle import quant_cache as oq
+    L, H, Hkv, d_h = len(layers), s.n_heads, s.n_kv_heads, s.d_head
+    G = H // Hkv
+    g = synth.rng(34, seed)
+    triples = [(0, 0, 0), (L - 1, B - 1, Hkv - 1)]
+    while len(triples) < n_samples:
+        triples.append(((len(triples) - 2) % L, int(g.integers(B)), int(g.integers(Hkv))))
+    n_q = n - P                                   # tokens held as codes; the newest page is bfloat16
+    pages_q = n_q // P
+    pos_cache = {}
+
+    def positions(dc, kvh):
+        """Bit offsets of the codes and byte offsets of the scales of one (page 0, kv head) tile run: [P, r] each."""
+        key = (dc.r_k, dc.r_v, kvh)
+        if key not in pos_cache:
+            out = {}
+            for name, r, code_pos3, code_pos4, scale_pos in (
+                    ("k", dc.r_k, ea.q3_k_code_pos, ea.q4_k_code_pos, lambda t, c: ea.q4_k_scale_pos(dc, 0, kvh, t, c)),
+                    ("v", dc.r_v, ea.q3_v_code_pos, ea.q4_v_code_pos, lambda t, c: ea.q4_v_scale_pos(dc, 0, kvh, t))):
+                cp = np.zeros((bits if bits == 3 else 1, P, r), np.int64)
+                sp = np.zeros((P, r), np.int64)
+                for t in range(P):
+                    for c in range(r):
+                        if bits == 3:
+                            cp[:, t, c] = code_pos3(dc, 0, kvh, t, c)
+                        else:
+                            cp[0, t, c] = code_pos4(dc, 0, kvh, t, c)
+                        sp[t, c] = scale_pos(t, c)
+                assert (cp >= 0).all() and (sp >= 0).all()
+                out[name] = (cp, sp)
+            pos_cache[key] = out
+        return pos_cache[key]
+
+    def gather(pool, page_ids, cp, sp, zero_off):
+        """codes uint8 [pages * P, r], scale and zero fp16 [pages * P, r] of the pages, from raw pool bytes."""
+        flat = pool.reshape(-1)
+        base = (page_ids.long() * pool.shape[1])[:, None, None]                       # byte offset of each page
+        codes = torch.zeros((page_ids.numel(),) + cp.shape[1:], dtype=torch.uint8, device=pool.device)
+        for bit in range(cp.shape[0]):
+            cpt = torch.from_numpy(cp[bit]).to(pool.device)
+            byte = flat[(base + cpt[None] // 8).reshape(-1)].reshape(codes.shape)
+            sh = (cpt % 8).to(torch.uint8)[None]
+            if cp.shape[0] == 1:
+                codes = (byte >> sh) & 15
+            else:
+                codes |= ((byte >> sh) & 1) << bit
+        spt = torch.from_numpy(sp).to(pool.device)
+        half = flat.view(torch.float16)
+
+        def halves(off):
+            return half[((base + spt[None] + off) // 2).reshape(-1)].reshape(codes.shape).cpu().numpy()
+
+        r = cp.shape[2]
+        return codes.reshape(-1, r).cpu().numpy(), halves(0).reshape(-1, r), halves(zero_off).reshape(-1, r)
+
+    worst, where, errs = 0.0, None, []
+    for li, b, kvh in triples:
+        l = layers[li]
+        dc = l["desc"]
+        lay = ea.cache_layout_query(dc)
+        pos = positions(dc, kvh)
+        pids = l["page_table"][b, :pages_q]
+        kc, ks, kz = gather(l["kq_pool"], pids, *pos["k"], 16)
+        vc, vs, vz = gather(l["vq_pool"], pids, *pos["v"], 128)
+        # one key scale per channel and group of `key_group` tokens (every token of a group names the same one), one
+        # value scale per token (every channel names the same one)
+        assert (ks.reshape(-1, key_group, dc.r_k) == ks.reshape(-1, key_group, dc.r_k)[:, :1]).all()
+        Kq = oq.dequantize_keys(kc, ks[::key_group], kz[::key_group])
+        Vq = oq.dequantize_values(vc, vs[:, 0], vz[:, 0])
+        Kt = _stream_bits(torch, l["k_pool"], l["tail_table"][b], kvh, Hkv, dc.r_k, lay.r_k_pad, _k_tiles_to_rows, P, P)
+        Vt = _stream_bits(torch, l["v_pool"], l["tail_table"][b], kvh, Hkv, dc.r_v, lay.r_v_pad, _v_tiles_to_rows, P, P)
+        K = np.concatenate([Kq, synth.bf16_bits_to_f32(Kt).astype(np.float64)])
+        V = np.concatenate([Vq, synth.bf16_bits_to_f32(Vt).astype(np.float64)])
+        cache = ora.RankCache.from_arrays([K[None]], [V[None]])
+        heads = list(range(kvh * G, (kvh + 1) * G))
+        q = l["q_r"][b, heads].cpu().numpy()[None].astype(np.float64)
+        if rope:
+            ref = ora.decode_attention_rope(q, cache, l["u_k"].float().cpu().numpy(), d_h, ROPE_BASE)
+        else:
+            ref = ora.decode_attention(q, cache, d_h)
+        got = l["o"][b, heads].cpu().numpy()[None]
+        if not np.isfinite(got).all():
+            return {"samples": len(errs), "worst_rel_l2": float("inf"), "ok": False,
+                    "where": f"non-finite output, layer {li}"}
+        e = ora.rel_l2(got, ref)
+        errs.append(e)
+        if e > worst:
+            worst, where = e, f"layer {li}, sequence {b}, kv head {kvh}"
+    return {"samples": len(errs), "worst_rel_l2": float(f"{worst:.3e}"), "mean_rel_l2": float(f"{np.mean(errs):.3e}"),
+            "where_worst": where, "bar": 1e-2, "ok": bool(np.isfinite(worst) and worst <= 1e-2),
+            "what": f"decode attention outputs of the timed resident step over the {bits}-bit cache vs the fp64 oracle: "
+                    "codes, scales and zeros gathered from raw pool memory at the positions the host reference "
+                    "functions give, dequantised by the oracle, joined with the bfloat16 newest page; the step's own "
+                    "queries; sampled over all resident layers"}
+
+
 def bench_decode(args, torch, ea, synth):
     dev = "cuda"
     base_name, rope = args.workload.split("-")[0], "-rope" in args.workload
@@ -882,9 +985,10 @@ def bench_decode(args, torch, ea, synth):
         result["parity"], streams0 = check_step_parity(torch, ea, synth, layers, s, B, n, P, rope,
                                                        max(args.parity_samples, 2), int(base_name[-1]),
                                                        slot_pos=slot_pos, q_pos=q_pos)
-    elif q4:
-        result["parity"] = {"samples": 0, "note": "not checked in this run: the 4-bit workloads are compared with the "
-                                                  "oracle by the GPU tests (tests/test_gpu_q4.py)"}
+    elif q4 and not args.no_parity:
+        result["parity"] = check_step_parity_q4(torch, ea, synth, layers, s, B, n, P, rope,
+                                                max(min(args.parity_samples, 16), 2), int(base_name[-1]),
+                                                args.q4_bits, args.q4_key_group)
 
     if not args.no_cpu and q4:
         result["cpu_baseline"] = cpu_oracle_decode_q4(512 // (32 if rope else 8), n, ranks[0][0], s.d_head,
