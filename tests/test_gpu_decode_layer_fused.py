@@ -242,3 +242,53 @@ def test_fused_decode_layer_beside_other_work_on_the_gpu():
         torch.cuda.synchronize()
         assert int(status.item()) == 0
         assert torch.equal(y, y_quiet), f"round {rep}"
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_fused_decode_layer_random_shapes(seed):
+    """Drawn shapes through the two-launch step (group sizes, head counts, ranks off every chunk size, page sizes,
+    ragged lengths down to an empty cache, split counts 1..16, model widths from fewer channel blocks than
+    workgroups to many more) against the oracle's generation step; the appended token against the three-launch call."""
+    rs = np.random.default_rng(seed)
+    for case in range(16):
+        G = int(rs.choice([1, 1, 2, 4, 8, 16]))
+        Hkv = int(rs.choice([1, 2, 3, 4, 8]))
+        H = G * Hkv
+        r_k = int(rs.integers(1, 17)) * 8
+        r_v = 0
+        while r_v == 0 or (H * r_v) % 32 != 0:                   # the output projection contracts H * r_v in steps of 32
+            r_v = int(rs.integers(1, 17)) * 8
+        P = int(rs.choice([64, 128, 256]))
+        B = int(rs.integers(1, 17))
+        d = int(rs.choice([128, 256, 512, 1024, 2048]))
+        rope = bool(rs.integers(2))
+        lens = [int(rs.choice([0, 1, 63, 64, 65, 128, int(rs.integers(1, 1500))])) for _ in range(B)]
+        S = int(rs.choice([0, 1, 2, 3, 5, 8, 9, 16]))
+        print(f"seed {seed} case {case}: d={d} H={H}/{Hkv} r=({r_k},{r_v}) P={P} B={B} lens={lens} S={S} rope={rope}", flush=True)
+        desc = ea.LayerDesc(d, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+        g = synth.rng(seed, case)
+        x = quantize(desc, synth.gaussian(g, (B, d)))
+        K0, V0 = random_cache(desc, lens, g)
+        dc = DeviceCache(desc, K0, V0, g, extra_len=1)
+        wqkv, wo, u_dev, Uk1, folded = layer_weights(desc, g, rope)
+        S_eff = S or (ea.decode_rope_auto_splits if rope else ea.decode_auto_splits)(desc, B, dc.max_pages * P)
+        ws = torch.full((ea.decode_layer_fused_workspace_bytes(desc, B, S_eff, rope) // 4,), float("nan"), device="cuda")
+        y = torch.full((B, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        xd = to_dev(desc, x)
+        k_before, v_before = dc.k_pool.clone(), dc.v_pool.clone()
+        ea.decode_layer(desc, xd, wqkv, wo, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y, S, ws, u_k=u_dev,
+                        status=status, fused=True)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        cache = ora.RankCache.from_arrays(K0, V0)
+        y_ref = (ora.decode_step_rope(x, folded, Uk1, cache, 128, 10000.0) if rope
+                 else ora.decode_step(x, folded, cache, 128))
+        assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"seed {seed} case {case}")
+        k_after, v_after = dc.k_pool.clone(), dc.v_pool.clone()
+        dc.k_pool.copy_(k_before); dc.v_pool.copy_(v_before)
+        y3 = torch.empty_like(y)
+        ws3 = torch.empty(max(ea.decode_layer_workspace_bytes(desc, B, S_eff, rope) // 4, 4), device="cuda")
+        ea.decode_layer(desc, xd, wqkv, wo, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y3, S, ws3, u_k=u_dev)
+        torch.cuda.synchronize()
+        assert same_bits(k_after, dc.k_pool) and same_bits(v_after, dc.v_pool)
