@@ -214,7 +214,8 @@ EA_API int ea_decode_attn_static(const ea_layer_desc* desc, const void* dev_q_r,
  *   o = Softmax(q_r K_r^T / sqrt(d_h)) V_r over the seq_len[b] + 1 cached tokens                       (ea_decode_attn)
  *   y = [o_1 .. o_H] W^O'                                                                                (ea_out_proj)
  * enqueued back to back on the stream: three launches, four when the sequence is split (ea_decode_layer_fused
- * below does the same step in two).  q_r and o never leave the workspace.  EA_BF16 layers only.
+ * below does the same step in two).  q_r (float) and o (rounded to bfloat16 once, as after a prefill) never leave
+ * the workspace.  EA_BF16 layers only.
  *   dev_x [B, d] bfloat16; dev_wqkv / dev_wo packed as for ea_project_qkv / ea_out_proj; dev_y [B, d] bfloat16
  *   dev_seq_len [B]: lengths BEFORE this step (the token is appended at that position); not modified
  *   n_splits: as ea_decode_attn (0 = choose)
@@ -240,8 +241,7 @@ EA_API int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, co
  *   launch 2: the attention of ea_decode_attn over seq_len[b] + 1 tokens, the merge of the split partials (by the
  *             workgroup that finishes a (sequence, kv head) last) and y = [o_1 .. o_H] W^O': the last
  *             min(d / 16, compute units, grid size) workgroups of the grid request their share of W^O', wait until
- *             every workgroup of the grid has delivered its part of o, and multiply.  o is rounded to bfloat16 once
- *             before the projection (ea_decode_layer keeps it in float).
+ *             every workgroup of the grid has delivered its part of o, and multiply.
  * Arguments, workspace rules and result as ea_decode_layer, with these differences:
  *   n_splits: at most 64 (EA_ERR_SHAPE above; 0 = choose, which never exceeds it)
  *   dev_ws: ea_decode_layer_fused_workspace_bytes(...) bytes (the counters the second launch uses live there; the

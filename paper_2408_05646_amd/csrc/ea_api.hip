@@ -520,18 +520,21 @@ static int decode_layer_impl(const ea_layer_desc* desc, bool rope, bool fused, c
     return decode_tail_bf16(desc, g, q, rope ? dev_u_k : nullptr, rope_base, dev_k_pool, dev_v_pool, dev_page_table,
                             dev_seq_len, B, n_splits, part, 1, t, st);
   }
+  // (o is this call's own intermediate: it is kept in bfloat16, rounded once, which the output projection reads
+  // faster than float rows)
   if (rope)
     rc = decode_rope_bf16(desc, g, q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B,
-                          n_splits, part, st, 0, 0, 1);
+                          n_splits, part, st, 0, 0, 1, 1);
   else
-    rc = decode_bf16(desc, g, q, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B, n_splits, part, st, 0, 0, 1);
+    rc = decode_bf16(desc, g, q, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B, n_splits, part, st, 0, 0, 1,
+                     1);
   if (rc != EA_OK) return rc;
   if (n_splits > 1) {
-    rc = merge_splits(g, part, o, B, n_splits, st);
+    rc = merge_splits(g, part, o, B, n_splits, st, nullptr, 1);
     if (rc != EA_OK) return rc;
   }
   // a5
-  return gemm_out_bf16(o, 1, dev_wo, dev_y, B, desc->d_model, desc->n_heads * desc->r_v, st);
+  return gemm_out_bf16(o, 0, dev_wo, dev_y, B, desc->d_model, desc->n_heads * desc->r_v, st);
 }
 
 int ea_decode_layer(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,

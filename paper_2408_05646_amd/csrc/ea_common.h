@@ -141,14 +141,14 @@ int cache_copy(const ea_layer_desc* d, const Geo& g, bool scatter, void* k_dense
 // ws_slots > 0: write split partials only, into slots ws_slot0 .. of a workspace laid out for ws_slots splits.
 int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
-                hipStream_t st, int32_t ws_slots = 0, int32_t ws_slot0 = 0, int32_t seq_add = 0);
+                hipStream_t st, int32_t ws_slots = 0, int32_t ws_slot0 = 0, int32_t seq_add = 0, int32_t out_bf16 = 0);
 int decode_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* k_pool, const float* v_pool,
                const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
                hipStream_t st);
 int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
                      float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st, int32_t ws_slots = 0,
-                     int32_t ws_slot0 = 0, int32_t seq_add = 0);
+                     int32_t ws_slot0 = 0, int32_t seq_add = 0, int32_t out_bf16 = 0);
 int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* u_k, double rope_base,
                     const float* k_pool, const float* v_pool, const int32_t* page_table, const int32_t* seq_len,
                     float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);
@@ -188,7 +188,8 @@ int decode_tail_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const
                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
                      int32_t B, int32_t n_splits, float* ws, int32_t seq_add, const TailArgs& t, hipStream_t st);
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st,
-                 float* ml_out = nullptr);   // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
+                 float* ml_out = nullptr,    // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
+                 int32_t out_bf16 = 0);      // out holds bfloat16 instead of float
 // Row length (floats) of the per-head scratch rows e / scores for a cache of n_cap tokens: whole tiles, plus a pad
 // of 17 * 256 bytes.  Without it the rows of long sequences start a power of two apart, and all the workgroups,
 // which advance through their rows in step, would write to the same memory channel at the same time.

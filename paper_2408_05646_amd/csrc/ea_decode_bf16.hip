@@ -8,7 +8,7 @@ namespace ea {
 // The loads of up to eight splits are requested together (a split past the last reads the last one again and is
 // ignored), so a row with at most eight splits costs one round trip to memory, not one per split.
 __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restrict__ out, int32_t BH, int32_t S,
-                                    int32_t r_v, int32_t r_v_pad, float* __restrict__ ml_out) {
+                                    int32_t r_v, int32_t r_v_pad, float* __restrict__ ml_out, int32_t out_bf16) {
   const int64_t bh = blockIdx.x;
   const int64_t BHS = (int64_t)BH * S;
   const float* pm = ws + bh * S;
@@ -68,13 +68,18 @@ __global__ void merge_splits_kernel(const float* __restrict__ ws, float* __restr
       ml_out[2 * bh] = mm;
       ml_out[2 * bh + 1] = lsum;
     }
-    if (c0 + (int)threadIdx.x < r_v) out[bh * r_v + c] = lsum > 0.f ? val / lsum : 0.f;
+    if (c0 + (int)threadIdx.x < r_v) {
+      const float o = lsum > 0.f ? val / lsum : 0.f;
+      if (out_bf16) reinterpret_cast<__bf16*>(out)[bh * r_v + c] = (__bf16)o;
+      else out[bh * r_v + c] = o;
+    }
   }
 }
 
-int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st, float* ml_out) {
+int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st, float* ml_out,
+                 int32_t out_bf16) {
   merge_splits_kernel<<<dim3(B * g.n_heads), dim3(64), 0, st>>>(ws, out, B * g.n_heads, n_splits, g.r_v, g.r_v_pad,
-                                                               ml_out);
+                                                               ml_out, out_bf16);
   return launch_status();
 }
 
@@ -103,9 +108,10 @@ static int dispatch_ncb(int ncb, const DecodeArgs& a, int32_t B, hipStream_t st)
 
 int decode_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* k_pool, const void* v_pool,
                 const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B, int32_t n_splits, float* ws,
-                hipStream_t st, int32_t ws_slots, int32_t ws_slot0, int32_t seq_add) {
+                hipStream_t st, int32_t ws_slots, int32_t ws_slot0, int32_t seq_add, int32_t out_bf16) {
   if (B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   DecodeArgs a;
+  a.out_bf16 = out_bf16;
   a.q = q;
   a.k_pool = (const uint16_t*)k_pool;
   a.v_pool = (const uint16_t*)v_pool;

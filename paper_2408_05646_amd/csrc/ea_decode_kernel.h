@@ -62,6 +62,7 @@ struct DecodeArgs {
   const int32_t* slot_pos = nullptr;   // [B, pos_stride]: of the token in logical cache slot t (0 <= value < 2^24)
   const int32_t* q_pos = nullptr;      // [B]: of the query
   int32_t pos_stride = 0;              // >= max_pages * page_tokens
+  int32_t out_bf16 = 0;                // `out` holds bfloat16 instead of float (the layer step's own intermediate)
 };
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
@@ -124,7 +125,12 @@ struct PlainEmit {
                                              int r_v_pad, float mm, float lsum, float val) const {
     const Geo& g = a.g;
     if (a.n_splits == 1 && a.ws_slots == 0) {
-      if (c < g.r_v) a.out[((int64_t)b * g.n_heads + head) * g.r_v + c] = lsum > 0.f ? val / lsum : 0.f;
+      if (c < g.r_v) {
+        const int64_t idx = ((int64_t)b * g.n_heads + head) * g.r_v + c;
+        const float o = lsum > 0.f ? val / lsum : 0.f;
+        if (a.out_bf16) reinterpret_cast<__bf16*>(a.out)[idx] = (__bf16)o;
+        else a.out[idx] = o;
+      }
     } else {
       const int slots = a.ws_slots > 0 ? a.ws_slots : a.n_splits;
       const int64_t BHS = (int64_t)n_batch * g.n_heads * slots;

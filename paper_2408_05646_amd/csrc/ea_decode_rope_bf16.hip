@@ -9,7 +9,7 @@ int decode_rope_bf16_d128(int ks, int ncb, const DecodeArgs& a, int32_t B, hipSt
 int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
                      float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st, int32_t ws_slots,
-                     int32_t ws_slot0, int32_t seq_add) {
+                     int32_t ws_slot0, int32_t seq_add, int32_t out_bf16) {
   if (B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   if (d->d_head != 64 && d->d_head != 128) return EA_ERR_SHAPE;
   DecodeArgs a;
@@ -30,6 +30,7 @@ int decode_rope_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const
   a.ws_slots = ws_slots;
   a.ws_slot0 = ws_slot0;
   a.seq_add = seq_add;
+  a.out_bf16 = out_bf16;
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   if (d->d_head == 128) return decode_rope_bf16_d128(ks, ncb, a, B, st);
   return dispatch_ks_rope<2>(ks, ncb, a, B, st);

@@ -52,7 +52,8 @@ def test_decode_layer_matches_oracle_decode_step(rope, H, Hkv, r_k, r_v, B, n0, 
         y_ref = ora.decode_step(x, folded_q, cache, d_h)
     assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, "decode layer y")
     assert int(status.item()) == 0
-    # the same step through the separate calls gives the same bits (same kernels, same order of additions)
+    # the same step through the separate calls (same kernels; the layer call keeps its intermediate o in bfloat16,
+    # the separate calls here pass it in float: one rounding of o apart)
     dc.k_pool.copy_(k_before); dc.v_pool.copy_(v_before)
     q_dim = d_h if rope else r_k
     q_r = torch.empty((B, H, q_dim), dtype=torch.float32, device="cuda")
@@ -68,7 +69,7 @@ def test_decode_layer_matches_oracle_decode_step(rope, H, Hkv, r_k, r_v, B, n0, 
         ea.decode_attn(desc, q_r, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len + 1, o, n_splits=S_eff, ws=ws2)
     ea.out_proj(desc, o.view(B, -1), wo, y2)
     torch.cuda.synchronize()
-    assert torch.allclose(y.float(), y2.float(), rtol=2e-2, atol=1e-3)
+    assert ora.rel_l2(y.float().cpu().numpy(), y2.float().cpu().numpy()) < 6e-3
     assert_close(y2.float().cpu().numpy(), y_ref, TOL_BF16, "separate calls y")
 
 
