@@ -243,13 +243,14 @@ def out_proj(o, Wo_f, counter: Optional[OpCounter] = None):
 # --------------------------------------------------------------------------
 # One generation step of the low-rank attention block (all rows of the path)
 # --------------------------------------------------------------------------
-def decode_step(x, folded, cache: RankCache, d_head: int, counter: Optional[OpCounter] = None):
-    """x [B, d]: project, append one token per sequence, attend, project out -> y [B, d]."""
+def decode_step(x, folded, cache: RankCache, d_head: int, counter: Optional[OpCounter] = None, alibi_slopes=None):
+    """x [B, d]: project, append one token per sequence, attend, project out -> y [B, d].  With alibi_slopes [H]
+    (the MPT family of Sec. 5.1) the attention adds each head's distance bias to its scores."""
     Wq_f, Wk_f, Wv_f, Wo_f = folded
     q, k, v = project_qkv(x, Wq_f, Wk_f, Wv_f, counter)
     for b in range(x.shape[0]):
         cache.append(b, k[b:b + 1], v[b:b + 1])
-    o = decode_attention(q, cache, d_head, counter)
+    o = decode_attention(q, cache, d_head, counter, alibi_slopes=alibi_slopes)
     return out_proj(o, Wo_f, counter)
 
 

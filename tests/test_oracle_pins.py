@@ -475,6 +475,39 @@ def test_alibi_bias_definition_limits_and_shift_invariance():
         assert np.allclose(op[0, j], ora.decode_attention(qp[:, j], prefix, d_h, alibi_slopes=slopes)[0], rtol=1e-12)
 
 
+def test_alibi_step_full_rank_equals_the_textbook_block_with_the_bias_written_out():
+    """One generation step with per-head slopes, at r = d_h, against standard attention computed here with loops:
+    score of the newest token against key t minus slope * (n - 1 - t), softmax, values, original W^O."""
+    d, H, Hkv, d_h, n = 24, 4, 2, 8, 9
+    Wq, Wk, Wv, Wo, Uk, Uv, x = make_layer(7, d, H, Hkv, d_h, d_h, d_h, n)
+    slopes = np.array([0.5, 0.25, 0.125, 0.0625])
+    folded = ora.fold_weights(Wq, Wk, Wv, Wo, Uk, Uv, H, Hkv)
+    cache = ora.RankCache.empty(1, Hkv, d_h, d_h)
+    _, k, v = ora.project_qkv(x[:-1], *folded[:3])
+    cache.append(0, k, v)
+    y = ora.decode_step(x[-1:], folded, cache, d_h, alibi_slopes=slopes)
+    assert cache.seq_len(0) == n
+    heads = np.zeros(H * d_h)
+    for i in range(H):
+        g = i // (H // Hkv)
+        qi = x[n - 1] @ Wq[:, i * d_h:(i + 1) * d_h]
+        Kg = x @ Wk[:, g * d_h:(g + 1) * d_h]
+        Vg = x @ Wv[:, g * d_h:(g + 1) * d_h]
+        s = [float(Kg[t] @ qi) / math.sqrt(d_h) - slopes[i] * (n - 1 - t) for t in range(n)]
+        e = [math.exp(a - max(s)) for a in s]
+        for c in range(d_h):
+            heads[i * d_h + c] = sum(e[t] / sum(e) * Vg[t, c] for t in range(n))
+    assert ora.rel_l2(y[0], heads @ Wo) < 1e-12
+    # the slopes matter (a dropped pass-through would leave the plain step) and zero slopes are the plain step
+    cache2 = ora.RankCache.from_arrays([np.stack([a[:n - 1] for a in cache.K[0]])],
+                                       [np.stack([a[:n - 1] for a in cache.V[0]])])
+    cache3 = ora.RankCache.from_arrays([np.stack([a[:n - 1] for a in cache.K[0]])],
+                                       [np.stack([a[:n - 1] for a in cache.V[0]])])
+    y_plain = ora.decode_step(x[-1:], folded, cache2, d_h)
+    assert ora.rel_l2(y, y_plain) > 1e-3
+    assert np.array_equal(ora.decode_step(x[-1:], folded, cache3, d_h, alibi_slopes=np.zeros(H)), y_plain)
+
+
 def test_bf16_rounding_helpers():
     x = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, 1.0 + 3 * 2 ** -8, -0.0, 3.4028e38, np.inf], np.float32)
     r = synth.round_to_bf16(x)
