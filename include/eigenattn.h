@@ -224,7 +224,10 @@ EA_API int ea_decode_attn_static(const ea_layer_desc* desc, const void* dev_q_r,
  *           needs no preparation
  *   dev_status: as ea_project_qkv (NULL, or the word that counts appends that could not be stored)
  * ea_decode_layer_rope is the same step for models with rotary position embedding (Sec. 4.3): dev_wqkv as for
- * ea_project_qkv_rope, dev_u_k [d_head, r_k] bfloat16 and rope_base as for ea_decode_attn_rope. */
+ * ea_project_qkv_rope, dev_u_k [d_head, r_k] bfloat16 and rope_base as for ea_decode_attn_rope.
+ * ea_decode_layer_alibi is the same step for models with the ALiBi position bias (the MPT family of Sec. 5.1):
+ * dev_slopes [H] float as for ea_decode_attn_alibi (NULL: EA_ERR_ARG), workspace as the position-free form
+ * (rotary = 0). */
 EA_API int64_t ea_decode_layer_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n_splits, int32_t rotary);
 EA_API int ea_decode_layer(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
                    void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len,
@@ -235,6 +238,10 @@ EA_API int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, co
                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
                    int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
                    int32_t* dev_status, void* stream);
+EA_API int ea_decode_layer_alibi(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                   const float* dev_slopes, void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
+                   const int32_t* dev_seq_len, void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages,
+                   int32_t n_splits, void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream);
 
 /* ea_decode_layer in TWO launches (the same step, Sec. 2 "LLM inference" with the folded weights of Eq. 8; B <= 16):
  *   launch 1: [q_r | k_r | v_r] = x [W^Q' | W^K' | W^V'] and the append, as ea_project_qkv;
@@ -268,6 +275,12 @@ EA_API int ea_decode_layer_fused(const ea_layer_desc* desc, const void* dev_x, c
                    int32_t n_splits, void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream);
 EA_API int ea_decode_layer_fused_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
                    const void* dev_wo, const void* dev_u_k, double rope_base, void* dev_k_pool, void* dev_v_pool,
+                   const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                   int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                   int32_t* dev_status, void* stream);
+/* (ALiBi form: dev_slopes as ea_decode_layer_alibi, workspace of the position-free form) */
+EA_API int ea_decode_layer_fused_alibi(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv,
+                   const void* dev_wo, const float* dev_slopes, void* dev_k_pool, void* dev_v_pool,
                    const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
                    int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
                    int32_t* dev_status, void* stream);

@@ -22,7 +22,7 @@ __all__ = [
     "attn_mass", "attn_mass_workspace_bytes", "decode_attn_mass", "decode_attn_mass_workspace_bytes",
     "decode_attn_static", "STATIC_SCRATCH_BYTES", "decode_layer_workspace_bytes", "decode_layer", "decode_layer_rope",
     "decode_layer_fused_workspace_bytes", "decode_layer_fused", "decode_layer_fused_rope", "set_wait_limit", "STATUS_WAIT_EXPIRED",
-    "decode_layer_fused_workers",
+    "decode_layer_fused_workers", "decode_layer_alibi", "decode_layer_fused_alibi",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
     "q3_k_code_pos", "q3_v_code_pos",
 ]
@@ -39,7 +39,7 @@ EXPORTED_SYMBOLS = (
     "ea_attn_mass_workspace_bytes", "ea_attn_mass", "ea_decode_attn_mass_workspace_bytes", "ea_decode_attn_mass",
     "ea_decode_attn_static", "ea_decode_layer_workspace_bytes", "ea_decode_layer", "ea_decode_layer_rope",
     "ea_decode_layer_fused_workspace_bytes", "ea_decode_layer_fused", "ea_decode_layer_fused_rope", "ea_set_wait_limit",
-    "ea_decode_layer_fused_workers",
+    "ea_decode_layer_fused_workers", "ea_decode_layer_alibi", "ea_decode_layer_fused_alibi",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
@@ -125,6 +125,8 @@ def load_library():
     lib.ea_decode_layer_workspace_bytes.argtypes = [D, I32, I32, I32]
     lib.ea_decode_layer.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP, VP]
     lib.ea_decode_layer_fused.argtypes = lib.ea_decode_layer.argtypes
+    lib.ea_decode_layer_alibi.argtypes = [D, VP, VP, VP, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, VP, I64, VP, VP]
+    lib.ea_decode_layer_fused_alibi.argtypes = lib.ea_decode_layer_alibi.argtypes
     lib.ea_decode_layer_fused_workspace_bytes.restype = I64
     lib.ea_decode_layer_fused_workspace_bytes.argtypes = [D, I32, I32, I32]
     lib.ea_set_wait_limit.argtypes = [ctypes.c_uint32]
@@ -398,11 +400,14 @@ def set_wait_limit(polls: int) -> None:
 
 
 def decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws, u_k=None,
-                 rope_base: float = 10000.0, status=None, stream=None, fused: bool = False) -> None:
+                 rope_base: float = 10000.0, status=None, stream=None, fused: bool = False, alibi_slopes=None) -> None:
     """One generation step of a layer (projection + append, attention over seq_len + 1 tokens, output projection) in
     one call: x [B, d] -> y [B, d], both bfloat16.  With u_k ([d_head, r_k] bfloat16) the rotary form
     (ea_decode_layer_rope).  ws: decode_layer_workspace_bytes bytes.  fused: the two-launch form
-    (ea_decode_layer_fused / ea_decode_layer_fused_rope; ws: decode_layer_fused_workspace_bytes bytes)."""
+    (ea_decode_layer_fused / ea_decode_layer_fused_rope; ws: decode_layer_fused_workspace_bytes bytes).
+    With alibi_slopes ([H] float32, not together with u_k) the ALiBi form (ea_decode_layer_alibi /
+    ea_decode_layer_fused_alibi)."""
+    import torch
     B = seq_len.shape[0]
     _expect(x, desc.dtype, "x"); _expect(y, desc.dtype, "y"); _expect(wqkv, desc.dtype, "wqkv"); _expect(wo, desc.dtype, "wo")
     _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
@@ -417,7 +422,17 @@ def decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_sp
         _i32(status, "status")
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     lib = load_library()
-    if u_k is None:
+    if alibi_slopes is not None:
+        if u_k is not None:
+            raise ValueError("alibi_slopes and u_k exclude each other")
+        if alibi_slopes.dtype != torch.float32 or alibi_slopes.numel() != desc.n_heads or not alibi_slopes.is_contiguous():
+            raise ValueError("alibi_slopes must be a contiguous float32 [H] tensor")
+        fn = lib.ea_decode_layer_fused_alibi if fused else lib.ea_decode_layer_alibi
+        rc = fn(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(alibi_slopes), _ptr(k_pool), _ptr(v_pool),
+                _ptr(page_table), _ptr(seq_len), _ptr(y), B, page_table.shape[1], k_pool.shape[0],
+                n_splits, _ptr(ws), ws_bytes, _ptr(status), _stream(stream))
+        _check(rc, "ea_decode_layer_fused_alibi" if fused else "ea_decode_layer_alibi")
+    elif u_k is None:
         fn = lib.ea_decode_layer_fused if fused else lib.ea_decode_layer
         rc = fn(ctypes.byref(desc), _ptr(x), _ptr(wqkv), _ptr(wo), _ptr(k_pool), _ptr(v_pool),
                 _ptr(page_table), _ptr(seq_len), _ptr(y), B, page_table.shape[1], k_pool.shape[0],
@@ -445,6 +460,18 @@ def decode_layer_fused_rope(desc, x, wqkv, wo, u_k, rope_base, k_pool, v_pool, p
                             ws, status=None, stream=None) -> None:
     decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits, ws, u_k=u_k, rope_base=rope_base,
                  status=status, stream=stream, fused=True)
+
+
+def decode_layer_alibi(desc, x, wqkv, wo, alibi_slopes, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws,
+                       status=None, stream=None, fused: bool = False) -> None:
+    decode_layer(desc, x, wqkv, wo, k_pool, v_pool, page_table, seq_len, y, n_splits, ws, status=status, stream=stream,
+                 fused=fused, alibi_slopes=alibi_slopes)
+
+
+def decode_layer_fused_alibi(desc, x, wqkv, wo, alibi_slopes, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws,
+                             status=None, stream=None) -> None:
+    decode_layer_alibi(desc, x, wqkv, wo, alibi_slopes, k_pool, v_pool, page_table, seq_len, y, n_splits, ws,
+                       status=status, stream=stream, fused=True)
 
 
 def decode_layer_rope(desc, x, wqkv, wo, u_k, rope_base, k_pool, v_pool, page_table, seq_len, y, n_splits: int, ws,

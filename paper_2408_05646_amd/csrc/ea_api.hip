@@ -457,7 +457,8 @@ static int decode_layer_impl(const ea_layer_desc* desc, bool rope, bool fused, c
                              const void* dev_wo, const void* dev_u_k, double rope_base, void* dev_k_pool,
                              void* dev_v_pool, const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y,
                              int32_t B, int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws,
-                             int64_t ws_bytes, int32_t* dev_status, void* stream) {
+                             int64_t ws_bytes, int32_t* dev_status, void* stream,
+                             const float* dev_slopes = nullptr) {
   int rc = validate_desc(desc);
   if (rc != EA_OK) return rc;
   if (desc->dtype != EA_BF16) return EA_ERR_SHAPE;
@@ -518,13 +519,16 @@ static int decode_layer_impl(const ea_layer_desc* desc, bool rope, bool fused, c
     // the chip's resident workgroup slots (2 per compute unit), so that everything they wait for can run
     t.n_work = ea_decode_layer_fused_workers(desc, B, n_splits);
     return decode_tail_bf16(desc, g, q, rope ? dev_u_k : nullptr, rope_base, dev_k_pool, dev_v_pool, dev_page_table,
-                            dev_seq_len, B, n_splits, part, 1, t, st);
+                            dev_seq_len, B, n_splits, part, 1, t, st, dev_slopes);
   }
   // (o is this call's own intermediate: it is kept in bfloat16, rounded once, which the output projection reads
   // faster than float rows)
   if (rope)
     rc = decode_rope_bf16(desc, g, q, dev_u_k, rope_base, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B,
                           n_splits, part, st, 0, 0, 1, 1);
+  else if (dev_slopes)
+    rc = decode_alibi_bf16(desc, g, q, dev_slopes, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B, n_splits,
+                           part, st, 1, 1);
   else
     rc = decode_bf16(desc, g, q, dev_k_pool, dev_v_pool, dev_page_table, dev_seq_len, o, B, n_splits, part, st, 0, 0, 1,
                      1);
@@ -563,6 +567,27 @@ int ea_decode_layer_fused_rope(const ea_layer_desc* desc, const void* dev_x, con
   return decode_layer_impl(desc, true, true, dev_x, dev_wqkv, dev_wo, dev_u_k, rope_base, dev_k_pool, dev_v_pool,
                            dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
                            dev_status, stream);
+}
+
+int ea_decode_layer_alibi(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                          const float* dev_slopes, void* dev_k_pool, void* dev_v_pool, const int32_t* dev_page_table,
+                          const int32_t* dev_seq_len, void* dev_y, int32_t B, int32_t max_pages, int32_t pool_pages,
+                          int32_t n_splits, void* dev_ws, int64_t ws_bytes, int32_t* dev_status, void* stream) {
+  if (!dev_slopes) return EA_ERR_ARG;
+  return decode_layer_impl(desc, false, false, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream, dev_slopes);
+}
+
+int ea_decode_layer_fused_alibi(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,
+                                const float* dev_slopes, void* dev_k_pool, void* dev_v_pool,
+                                const int32_t* dev_page_table, const int32_t* dev_seq_len, void* dev_y, int32_t B,
+                                int32_t max_pages, int32_t pool_pages, int32_t n_splits, void* dev_ws, int64_t ws_bytes,
+                                int32_t* dev_status, void* stream) {
+  if (!dev_slopes) return EA_ERR_ARG;
+  return decode_layer_impl(desc, false, true, dev_x, dev_wqkv, dev_wo, nullptr, 0.0, dev_k_pool, dev_v_pool,
+                           dev_page_table, dev_seq_len, dev_y, B, max_pages, pool_pages, n_splits, dev_ws, ws_bytes,
+                           dev_status, stream, dev_slopes);
 }
 
 int ea_decode_layer_rope(const ea_layer_desc* desc, const void* dev_x, const void* dev_wqkv, const void* dev_wo,

@@ -154,7 +154,7 @@ int decode_rope_f32(const ea_layer_desc* d, const Geo& g, const float* q, const 
                     float* out, int32_t B, int32_t n_splits, float* ws, hipStream_t st);
 int decode_alibi_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const void* k_pool,
                       const void* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
-                      int32_t n_splits, float* ws, hipStream_t st);
+                      int32_t n_splits, float* ws, hipStream_t st, int32_t seq_add = 0, int32_t out_bf16 = 0);
 int decode_alibi_f32(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const float* k_pool,
                      const float* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
                      int32_t n_splits, float* ws, hipStream_t st);
@@ -186,7 +186,8 @@ struct TailArgs {
 };
 int decode_tail_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const void* u_k, double rope_base,
                      const void* k_pool, const void* v_pool, const int32_t* page_table, const int32_t* seq_len,
-                     int32_t B, int32_t n_splits, float* ws, int32_t seq_add, const TailArgs& t, hipStream_t st);
+                     int32_t B, int32_t n_splits, float* ws, int32_t seq_add, const TailArgs& t, hipStream_t st,
+                     const float* slopes = nullptr);   // slopes [H]: the ALiBi form (not with u_k)
 int merge_splits(const Geo& g, const float* ws, float* out, int32_t B, int32_t n_splits, hipStream_t st,
                  float* ml_out = nullptr,    // ml_out [B, H, 2]: each row's reference exponent and normaliser, or null
                  int32_t out_bf16 = 0);      // out holds bfloat16 instead of float

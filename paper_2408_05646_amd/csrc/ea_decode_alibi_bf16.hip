@@ -29,7 +29,7 @@ static int dispatch_ncb_alibi(int ncb, const DecodeArgs& a, int32_t B, hipStream
 
 int decode_alibi_bf16(const ea_layer_desc* d, const Geo& g, const float* q, const float* slopes, const void* k_pool,
                       const void* v_pool, const int32_t* page_table, const int32_t* seq_len, float* out, int32_t B,
-                      int32_t n_splits, float* ws, hipStream_t st) {
+                      int32_t n_splits, float* ws, hipStream_t st, int32_t seq_add, int32_t out_bf16) {
   if (B > 65535 || g.n_kv_heads > 65535) return EA_ERR_SHAPE;
   DecodeArgs a;
   a.q = q;
@@ -46,6 +46,8 @@ int decode_alibi_bf16(const ea_layer_desc* d, const Geo& g, const float* q, cons
   a.d_head = d->d_head;
   a.log2_base = 0.0;
   a.alibi = slopes;
+  a.seq_add = seq_add;
+  a.out_bf16 = out_bf16;
   const int ks = (g.r_k_pad + 31) / 32, ncb = g.r_v_pad / 16;
   switch (ks) {
     case 1: return dispatch_ncb_alibi<1>(ncb, a, B, st);

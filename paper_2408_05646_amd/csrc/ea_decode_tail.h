@@ -58,7 +58,7 @@ struct TailEmit {
   }
 };
 
-template <int KS, int NCB, int TBN, int NKK>
+template <int KS, int NCB, int TBN, int NKK, bool ALIBI = false>
 __global__ __launch_bounds__(256, 2) void decode_layer_back_kernel(DecodeArgs a, TailArgs t) {
   __shared__ DecodeSmem<KS, NCB, TBN, NKK> sm;
   __shared__ f32x4 red[4][64];
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void decode_layer_back_kernel(DecodeArgs a,
   const __amdgpu_buffer_rsrc_t ws_rsrc = tail_rsrc(a.ws, a.n_splits > 1 ? t.ws_bytes : 0u);
 
   // ---- attention of this (kv head, split, sequence)
-  decode_bf16_body<KS, NCB, TBN, 2, NKK, false, false, false, TailEmit>(a, kvh, split, b, n_batch, sm,
+  decode_bf16_body<KS, NCB, TBN, 2, NKK, ALIBI, false, false, TailEmit>(a, kvh, split, b, n_batch, sm,
                                                                         TailEmit{o_rsrc, ws_rsrc});
   // every store of the workgroup has been acknowledged before the workgroup is counted anywhere
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

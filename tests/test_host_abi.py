@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 53
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 55
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -592,6 +592,18 @@ def test_layer_step_entry_points_reject_bad_arguments_before_launching():
     assert ea.decode_layer_fused_workspace_bytes(d, 17, 1) == -1
     assert call(lib.ea_decode_layer_fused, status=OK_PTR + 2) == -3
     assert lib.ea_set_wait_limit(0) == -1 and lib.ea_set_wait_limit(1 << 20) == 0
+    # the ALiBi forms: the same checks behind one more pointer, which must be there
+
+    def call_alibi(fn, slopes=OK_PTR, x=OK_PTR, B=4, n_splits=2, ws=OK_PTR, ws_bytes=1 << 30):
+        return fn(ctypes.byref(d), x, OK_PTR, OK_PTR, slopes, OK_PTR, OK_PTR, OK_PTR, OK_PTR, OK_PTR, B, 4, 16, n_splits,
+                  ws, ws_bytes, None, None)
+
+    for fn, need in ((lib.ea_decode_layer_alibi, ea.decode_layer_workspace_bytes(d, 4, 2)),
+                     (lib.ea_decode_layer_fused_alibi, ea.decode_layer_fused_workspace_bytes(d, 4, 2))):
+        assert call_alibi(fn, slopes=None) == -1 and call_alibi(fn, x=None) == -1 and call_alibi(fn, B=0) == -1
+        assert call_alibi(fn, ws=None) == -4 and call_alibi(fn, ws_bytes=need - 1) == -4
+    assert call_alibi(lib.ea_decode_layer_fused_alibi, B=17, n_splits=1) == -2
+    assert call_alibi(lib.ea_decode_layer_fused_alibi, n_splits=65) == -2
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     assert re.search(r"#define\s+EA_STATUS_WAIT_EXPIRED\s+\(1 << 30\)", header) and ea.STATUS_WAIT_EXPIRED == 1 << 30
 

@@ -75,10 +75,14 @@ ATTENTION = [
      "test_full_rank_equals_standard_attention_decode"),
     ("the generation step attends before it appends (the new token does not see itself)",
      "    for b in range(x.shape[0]):\n        cache.append(b, k[b:b + 1], v[b:b + 1])\n"
-     "    o = decode_attention(q, cache, d_head, counter)",
-     "    o = decode_attention(q, cache, d_head, counter)\n"
+     "    o = decode_attention(q, cache, d_head, counter, alibi_slopes=alibi_slopes)",
+     "    o = decode_attention(q, cache, d_head, counter, alibi_slopes=alibi_slopes)\n"
      "    for b in range(x.shape[0]):\n        cache.append(b, k[b:b + 1], v[b:b + 1])",
      "test_full_rank_equals_standard_attention_decode"),
+    ("the generation step drops the ALiBi slopes it was given",
+     "    o = decode_attention(q, cache, d_head, counter, alibi_slopes=alibi_slopes)",
+     "    o = decode_attention(q, cache, d_head, counter)",
+     "test_alibi_step_full_rank_equals_the_textbook_block_with_the_bias_written_out"),
     ("every head goes through W^O'_0",
      "        y += o[:, i, :] @ Wo_f[i]", "        y += o[:, i, :] @ Wo_f[0]", "test_brute_force_projection_and_out_proj"),
     ("values taken in reversed token order",
