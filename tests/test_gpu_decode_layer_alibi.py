@@ -134,3 +134,50 @@ def test_alibi_layer_calls_reject_missing_slopes_and_slopes_with_a_rotary_basis(
     ea.decode_layer(desc, x, wqkv, wo, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y, 1, ws)
     torch.cuda.synchronize()
     assert ora.rel_l2(y0.float().cpu().numpy(), y.float().cpu().numpy()) < 1e-3
+
+
+@pytest.mark.parametrize("seed", [4101, 4102])
+def test_alibi_decode_layer_random_shapes(seed):
+    """Drawn shapes (group sizes, head counts that are no power of two, ranks off every chunk size, page sizes, ragged
+    lengths down to an empty cache, split counts, model widths, slopes from zero to steep) through both forms against
+    the oracle's generation step with slopes."""
+    rs = np.random.default_rng(seed)
+    for case in range(12):
+        G = int(rs.choice([1, 1, 2, 4, 8, 16]))
+        Hkv = int(rs.choice([1, 2, 3, 4, 8]))
+        H = G * Hkv
+        r_k = int(rs.integers(1, 17)) * 8
+        r_v = 0
+        while r_v == 0 or (H * r_v) % 32 != 0:
+            r_v = int(rs.integers(1, 17)) * 8
+        P = int(rs.choice([64, 128, 256]))
+        B = int(rs.integers(1, 17))
+        d = int(rs.choice([128, 256, 512, 1024, 2048]))
+        lens = [int(rs.choice([0, 1, 63, 64, 65, 128, int(rs.integers(1, 1500))])) for _ in range(B)]
+        S = int(rs.choice([0, 1, 2, 3, 5, 8, 9, 16]))
+        slopes = (rs.choice([0.0, 1.0, 4.0], size=H) * rs.random(H) * 0.1 + 2.0 ** -rs.integers(1, 10, size=H) *
+                  rs.integers(0, 2, size=H)).astype(np.float32)
+        print(f"seed {seed} case {case}: d={d} H={H}/{Hkv} r=({r_k},{r_v}) P={P} B={B} lens={lens} S={S}", flush=True)
+        desc = ea.LayerDesc(d, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+        g = synth.rng(seed, case)
+        x = quantize(desc, synth.gaussian(g, (B, d)))
+        K0, V0 = random_cache(desc, lens, g)
+        wqkv, wo, _, _, folded = layer_weights(desc, g, False)
+        sl = torch.tensor(slopes, device="cuda")
+        xd = to_dev(desc, x)
+        y_ref = ora.decode_step(x, folded, ora.RankCache.from_arrays(K0, V0), 128, alibi_slopes=slopes.astype(np.float64))
+        pools = []
+        for fused in (False, True):
+            dc = DeviceCache(desc, K0, V0, synth.rng(seed, case, 1), extra_len=1)
+            S_eff = S or ea.decode_auto_splits(desc, B, dc.max_pages * P)
+            nbytes = (ea.decode_layer_fused_workspace_bytes if fused else ea.decode_layer_workspace_bytes)(desc, B, S_eff)
+            ws = torch.full((max(nbytes // 4, 4),), float("nan"), device="cuda")
+            y = torch.full((B, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+            status = torch.zeros(1, dtype=torch.int32, device="cuda")
+            ea.decode_layer_alibi(desc, xd, wqkv, wo, sl, dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, y, S, ws,
+                                  status=status, fused=fused)
+            torch.cuda.synchronize()
+            assert int(status.item()) == 0
+            assert_close(y.float().cpu().numpy(), y_ref, TOL_BF16, f"seed {seed} case {case} fused={fused}")
+            pools.append((dc.k_pool, dc.v_pool))
+        assert same_bits(pools[0][0], pools[1][0]) and same_bits(pools[0][1], pools[1][1])
