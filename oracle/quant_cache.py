@@ -163,6 +163,21 @@ def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group
     return ea_oracle.prefill_attention(q_r, cache, d_head)
 
 
+def prefill_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0,
+                                     group_tokens: int = GROUP_TOKENS, bits: int = 4):
+    """prefill_attention_quantized for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama models of
+    the quantisation experiment): causal rotary attention of the LAST n tokens over the dequantised rank-r keys and
+    values, token t of a sequence at position t whether it is held in codes or in 16 bits.
+    q [B, n, H, d_head] (not rotated); the rest as prefill_attention_quantized."""
+    n = np.asarray(q).shape[1]
+    for b in range(len(K_list)):
+        assert n <= K_list[b].shape[1] - int(n_quant[b])
+    rope_prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits)
+                          for b in range(len(K_list))]
+    cache = ea_oracle.RankCache.from_arrays([v[0] for v in rope_prefill_views], [v[1] for v in rope_prefill_views])
+    return ea_oracle.prefill_attention_rope(q, cache, Uk, d_head, base)
+
+
 def chunked_prefill_quantized(q_r, K, V, chunk: int, d_head: int, group_tokens: int = GROUP_TOKENS, bits: int = 4):
     """A prompt of n tokens prefilled chunk by chunk, every chunk's keys and values quantised as soon as the chunk
     has been attended -- so that at no time more than one chunk exists in 16 bits (what the quantisation paragraph

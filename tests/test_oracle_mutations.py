@@ -125,6 +125,14 @@ QUANT = [
      "    return ea_oracle.prefill_attention(q_r, cache, d_head)",
      "    return np.stack([ea_oracle.decode_attention(np.asarray(q_r)[:, j], cache, d_head) for j in range(n)], axis=1)",
      "test_prefill_attention_over_a_partly_quantised_cache"),
+    ("the rotary prefill over a partly quantised cache attends the unquantised cache",
+     "    rope_prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits)\n",
+     "    rope_prefill_views = [(np.asarray(K_list[b], np.float64), np.asarray(V_list[b], np.float64))\n",
+     "test_rotary_prefill_over_a_partly_quantised_cache"),
+    ("the rotary prefill over a partly quantised cache ignores the base it is given",
+     "    return ea_oracle.prefill_attention_rope(q, cache, Uk, d_head, base)",
+     "    return ea_oracle.prefill_attention_rope(q, cache, Uk, d_head)",
+     "test_rotary_prefill_over_a_partly_quantised_cache"),
     ("the key quantiser ignores the group length it is given",
      "    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)",
      "    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)", "test_key_groups_of_128_tokens"),

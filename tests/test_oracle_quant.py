@@ -372,6 +372,50 @@ def test_prefill_attention_over_a_partly_quantised_cache():
     assert np.allclose(ch128[128:], oq.prefill_attention_quantized(qa[None, 128:], [Ka], [Va], [128], d_h, 128)[0], atol=1e-13)
 
 
+def test_rotary_prefill_over_a_partly_quantised_cache():
+    """(a) nothing quantised = the rotary prefill oracle; (b) every query row = the rotary generation-phase function
+    (pinned by brute force above) on the prefix that ends with it, the quantised part unchanged; (c) brute force
+    for one (query, head) with the rotation written in complex numbers; (d) 3-bit
+    codes give something else than 4-bit ones."""
+    g = synth.rng(131)
+    H, Hkv, r_k, r_v, d_h, L, n = 4, 2, 8, 6, 16, 200, 40
+    Uk = synth.orthonormal_basis(g, d_h, r_k)
+    K = [synth.gaussian(g, (Hkv, L, r_k))]
+    V = [synth.gaussian(g, (Hkv, L, r_v))]
+    q = synth.gaussian(g, (1, n, H, d_h))
+    plain = ora.prefill_attention_rope(q, ora.RankCache.from_arrays(K, V), Uk, d_h, 100.0)
+    assert np.array_equal(oq.prefill_attention_rope_quantized(q, K, V, [0], Uk, d_h, 100.0), plain)
+    got = oq.prefill_attention_rope_quantized(q, K, V, [128], Uk, d_h, 100.0)
+    assert not np.allclose(got, plain, atol=1e-3)
+    for j in (0, 17, n - 1):
+        pos = L - n + j
+        row = oq.decode_attention_rope_quantized(q[:, j], [K[0][:, :pos + 1]], [V[0][:, :pos + 1]], [128], Uk, d_h, 100.0)
+        assert np.allclose(got[:, j], row, rtol=0, atol=1e-12)
+    # (c) brute force for one (query, head): keys dequantised by hand, brought back to d_head channels, pairs turned
+    # as complex numbers; the score depends on the two positions only through their difference
+    j, h, kv = 23, 2, 1
+    pos = L - n + j
+    ck, sk, zk = oq.quantize_keys(K[0][kv, :128])
+    cv, sv, zv = oq.quantize_values(V[0][kv, :128])
+    theta = 100.0 ** (-np.arange(0, d_h, 2) / d_h)
+    qc = q[0, j, h, 0::2] + 1j * q[0, j, h, 1::2]
+    sc, vals = [], []
+    for t in range(pos + 1):
+        if t < 128:
+            key = np.array([float(sk[t // 64, c]) * int(ck[t, c]) + float(zk[t // 64, c]) for c in range(r_k)])
+            val = np.array([float(sv[t]) * int(cv[t, c]) + float(zv[t]) for c in range(r_v)])
+        else:
+            key, val = K[0][kv, t], V[0][kv, t]
+        full = Uk @ key
+        kc = full[0::2] + 1j * full[1::2]
+        sc.append(float(np.real(np.sum(qc * np.conj(kc) * np.exp(1j * theta * (pos - t))))) / np.sqrt(d_h))
+        vals.append(val)
+    w = np.exp(np.array(sc) - max(sc))
+    assert np.allclose(got[0, j, h], (w[:, None] * np.array(vals)).sum(axis=0) / w.sum(), rtol=0, atol=1e-12)
+    three = oq.prefill_attention_rope_quantized(q, K, V, [128], Uk, d_h, 100.0, bits=3)
+    assert not np.allclose(three, got, atol=1e-3)
+
+
 def test_three_bit_codes():
     """bits = 3 (the other precision of the paper's Eigen Attention rows): eight levels per group.  Codes 0..7 with
     both ends taken, error within half a step of the group's own scale (seven steps between minimum and maximum),
