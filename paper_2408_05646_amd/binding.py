@@ -24,6 +24,7 @@ __all__ = [
     "decode_layer_fused_workspace_bytes", "decode_layer_fused", "decode_layer_fused_rope", "set_wait_limit", "STATUS_WAIT_EXPIRED",
     "decode_layer_fused_workers", "decode_layer_alibi", "decode_layer_fused_alibi",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
+    "prefill_attn_rope_q4", "prefill_rope_q4_workspace_bytes",
     "q3_k_code_pos", "q3_v_code_pos",
 ]
 
@@ -41,6 +42,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_layer_fused_workspace_bytes", "ea_decode_layer_fused", "ea_decode_layer_fused_rope", "ea_set_wait_limit",
     "ea_decode_layer_fused_workers", "ea_decode_layer_alibi", "ea_decode_layer_fused_alibi",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
+    "ea_prefill_rope_q4_workspace_bytes", "ea_prefill_attn_rope_q4",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
 
@@ -164,6 +166,10 @@ def load_library():
     lib.ea_prefill_q4_workspace_bytes.restype = I64
     lib.ea_prefill_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_prefill_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
+    lib.ea_prefill_rope_q4_workspace_bytes.restype = I64
+    lib.ea_prefill_rope_q4_workspace_bytes.argtypes = [D, I32, I32, I32, I32]
+    lib.ea_prefill_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
+                                            VP, I32, I32, VP, I64, VP]
     lib.ea_attn_mass_workspace_bytes.restype = I64
     lib.ea_attn_mass_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_attn_mass.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, I32, VP, I64, VP]
@@ -768,6 +774,35 @@ def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, 
         q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table), _ptr(tail_len),
         tail_page_table.shape[1], k_pool.shape[0], _ptr(out), B, n, _ptr(ws), ws_bytes, _stream(stream))
     _check(rc, "ea_prefill_attn_q4")
+
+
+def prefill_rope_q4_workspace_bytes(desc, B: int, n: int, max_q4_pages: int, max_tail_pages: int) -> int:
+    return int(load_library().ea_prefill_rope_q4_workspace_bytes(ctypes.byref(desc), B, n, max_q4_pages,
+                                                                 max_tail_pages))
+
+
+def prefill_attn_rope_q4(desc, q, u_k, rope_base: float, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool,
+                         tail_page_table, tail_len, out, ws, stream=None) -> None:
+    """Rotary variant of prefill_attn_q4: q [B, n, H, d_head] bfloat16 (not rotated), u_k [d_head, r_k] bfloat16;
+    q4_len in whole pages; ws: prefill_rope_q4_workspace_bytes bytes."""
+    B, n = q.shape[0], q.shape[1]
+    _expect(q, desc.dtype, "q"); _expect(out, desc.dtype, "out"); _expect(u_k, desc.dtype, "u_k")
+    if q.numel() != B * n * desc.n_heads * desc.d_head or out.numel() != B * n * desc.n_heads * desc.r_v:
+        raise ValueError("q / out have the wrong size")
+    if u_k.numel() != desc.d_head * desc.r_k or not u_k.is_contiguous():
+        raise ValueError("u_k must be a contiguous [d_head, r_k] tensor")
+    _u8(kq_pool, "kq_pool"); _u8(vq_pool, "vq_pool")
+    _expect(k_pool, desc.dtype, "k_pool"); _expect(v_pool, desc.dtype, "v_pool")
+    for t, name in ((q4_page_table, "q4_page_table"), (q4_len, "q4_len"), (tail_page_table, "tail_page_table"),
+                    (tail_len, "tail_len")):
+        _i32(t, name)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    rc = load_library().ea_prefill_attn_rope_q4(
+        ctypes.byref(desc), _ptr(q), _ptr(u_k), float(rope_base), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table),
+        _ptr(q4_len), q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table),
+        _ptr(tail_len), tail_page_table.shape[1], k_pool.shape[0], _ptr(out), B, n, _ptr(ws), ws_bytes,
+        _stream(stream))
+    _check(rc, "ea_prefill_attn_rope_q4")
 
 
 def decode_attn_alibi_q4(desc, q_r, slopes, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table,

@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 55
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 57
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -497,6 +497,32 @@ def test_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching():
     assert call(ws=None) == -4 and call(ws_bytes=need - 1) == -4
     assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
     assert ea.prefill_q4_workspace_bytes(d, 0, 100) == -1
+
+
+def test_rotary_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching():
+    lib, d = raw(), desc()
+
+    def call(dd=d, q=OK_PTR, u=OK_PTR, base=10000.0, kq=OK_PTR, k=OK_PTR, tail=OK_PTR, out=OK_PTR, B=2, n=100, mq=4,
+             qpool=8, mt=2, pool=8, ws=OK_PTR, ws_bytes=1 << 40):
+        return lib.ea_prefill_attn_rope_q4(ctypes.byref(dd), q, u, base, kq, OK_PTR, OK_PTR, OK_PTR, mq, qpool, k, OK_PTR,
+                                           tail, OK_PTR, mt, pool, out, B, n, ws, ws_bytes, None)
+
+    assert call(q=None) == -1 and call(u=None) == -1 and call(tail=None) == -1 and call(k=None) == -1
+    assert call(n=0) == -1 and call(mt=0) == -1 and call(mq=0) == -1 and call(base=1.0) == -1
+    assert call(kq=ODD_PTR) == -3 and call(out=ODD_PTR) == -3 and call(u=ODD_PTR) == -3
+    need = ea.prefill_rope_q4_workspace_bytes(d, 2, 100, 4, 2)
+    lay = ea.cache_layout_query(d)
+    align = lambda x: -(-x // 256) * 256
+    pages = 2 * (4 + 2)
+    # the page lists and the staged table, two stage pools of bfloat16 pages, the rotary prefill's own workspace
+    assert need == (align(4 * 2 * (3 * 6 + 1)) + align(pages * lay.k_page_elems * 2) + align(pages * lay.v_page_elems * 2)
+                    + ea.prefill_rope_workspace_bytes(d, 2, 100, 6))
+    assert call(ws=None) == -4 and call(ws_bytes=need - 1) == -4 and call(ws=OK_PTR + 16) == -4
+    assert call(dd=desc(dtype=ea.EA_F32, P=64)) == -2                      # bf16 layers only
+    assert call(dd=desc(d_h=96)) == -2                                     # d_head 64 or 128
+    assert call(dd=desc(d_h=64, r_k=80)) == -2                             # r_k <= d_head
+    assert ea.prefill_rope_q4_workspace_bytes(d, 0, 100, 4, 2) == -1
+    assert ea.prefill_rope_q4_workspace_bytes(d, 1 << 20, 100, 1 << 10, 1 << 10) == -1      # 2^31 stage pages
 
 
 @pytest.mark.parametrize("P,r_k,r_v,Hkv,group", [(64, 80, 80, 2, 64), (128, 30, 33, 1, 128), (192, 128, 16, 2, 64), (64, 8, 112, 1, 64)])
