@@ -139,3 +139,35 @@ def test_a_rotary_prompt_prefilled_in_chunks_with_every_chunk_quantised_at_once(
                                                   [c0], U, d_h, 10000.0)
         err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16, f"chunk {c}")
         print(f"  chunk {c}: rel-L2 {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("seed", [5201])
+def test_prefill_attn_rope_q4_random_shapes(seed):
+    """Drawn shapes: group sizes, ranks off every chunk size, both head sizes, page sizes, key groups and code widths,
+    ragged lengths, sequences with nothing quantised and with nothing but one page in 16 bits."""
+    rs = np.random.default_rng(seed)
+    for case in range(10):
+        G = int(rs.choice([1, 2, 4, 8]))
+        Hkv = int(rs.choice([1, 2, 3]))
+        H = G * Hkv
+        d_h = int(rs.choice([64, 128]))
+        r_k = int(rs.integers(1, d_h // 8 + 1)) * 8
+        r_v = int(rs.integers(1, 17)) * 8
+        group = int(rs.choice([64, 128]))
+        P = int(rs.choice([64, 128, 256] if group == 64 else [128, 256]))
+        bits = int(rs.choice([4, 3]))
+        B = int(rs.integers(1, 4))
+        n = int(rs.integers(1, 150))
+        n_quant = [int(rs.integers(0, 6)) * P for _ in range(B)]
+        lens = [nq + n + int(rs.integers(0, 200)) for nq in n_quant]
+        print(f"seed {seed} case {case}: H={H}/{Hkv} d_h={d_h} r=({r_k},{r_v}) P={P} group={group} bits={bits} "
+              f"lens={lens} quantised={n_quant} n={n}", flush=True)
+        desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P, group, bits)
+        g = synth.rng(seed, case)
+        U = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+        K, V = offset_cache(desc, lens, g)
+        q = quantize(desc, synth.gaussian(g, (B, n, H, d_h)))
+        qc = Q4Cache(desc, K, V, n_quant, g)
+        got = run_prefill_rope_q4(desc, qc, q, U, 10000.0)
+        ref = oq.prefill_attention_rope_quantized(q, K, V, n_quant, U, d_h, 10000.0, group_tokens=group, bits=bits)
+        assert_close(got, ref, TOL_BF16, f"seed {seed} case {case}")
