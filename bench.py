@@ -57,6 +57,9 @@ def parse_args():
                              "cfg5-q4", "cfg3-rope-q4", "cfg2-h2o", "cfg3-h2o", "cfg2-rope-h2o", "cfg3-rope-h2o", "cfg4-q4"])
     ap.add_argument("--prefill-chunk", type=int, default=2048,
                     help="cfg4-q4: tokens per sequence that are prefilled (and then quantised) at a time")
+    ap.add_argument("--q4-staged", action="store_true",
+                    help="cfg4-q4: attend through ea_prefill_attn_q4_staged (codes dequantised into 16-bit stage pools "
+                         "inside the workspace, then the 16-bit prefill kernel) instead of ea_prefill_attn_q4")
     ap.add_argument("--layers", type=int, default=32, help="resident layers (32 = the full model)")
     ap.add_argument("--page-tokens", type=int, default=64)
     ap.add_argument("--n-splits", type=int, default=0, help="0 = library default")
@@ -1194,7 +1197,10 @@ def bench_prefill_q4(args, torch, ea, synth):
     qc = torch.empty((B * C, H, r), dtype=torch.bfloat16, device=dev)
     oc = torch.empty((B, C, H, r), dtype=torch.bfloat16, device=dev)
     yc = torch.empty((B * C, d), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty(ea.prefill_q4_workspace_bytes(desc, B, C) // 4, dtype=torch.float32, device=dev)
+    staged = bool(args.q4_staged)
+    ws_bytes = (ea.prefill_q4_staged_workspace_bytes(desc, B, C, n // P, cpp) if staged
+                else ea.prefill_q4_workspace_bytes(desc, B, C))
+    ws = torch.empty(ws_bytes // 4, dtype=torch.float32, device=dev)
     zero = torch.zeros((B,), dtype=torch.int32, device=dev)
     full = torch.full((B,), C, dtype=torch.int32, device=dev)
     q4_lens = [torch.full((B,), c0, dtype=torch.int32, device=dev) for c0 in range(0, n, C)]
@@ -1208,7 +1214,8 @@ def bench_prefill_q4(args, torch, ea, synth):
             if e: e[0].record()
             ea.project_qkv(desc, xc[c], wqkv, qc, k_pool, v_pool, stage, zero, C)
             if e: e[1].record()
-            ea.prefill_attn_q4(desc, qc.view(B, C, H, r), kq, vq, q4_table, q4_lens[c], k_pool, v_pool, stage, full, oc, ws)
+            ea.prefill_attn_q4(desc, qc.view(B, C, H, r), kq, vq, q4_table, q4_lens[c], k_pool, v_pool, stage, full, oc, ws,
+                               staged=staged)
             if e: e[2].record()
             ea.quantize_pages_q4(desc, k_pool, v_pool, src_pages, kq, vq, dst_pages[c])
             if e: e[3].record()
@@ -1248,24 +1255,28 @@ def bench_prefill_q4(args, torch, ea, synth):
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg4-q4 causal prefill: one Llama-2-7B-shaped layer, B={B}, n={n}, H={H}, d_h={s.d_head}, "
                                f"r_k=r_v={r}, in chunks of {C} tokens per sequence; per chunk project_qkv (into the same "
-                               f"{B * cpp} bfloat16 pages) + prefill_attn_q4 (the chunk causally, earlier chunks as {args.q4_bits}-bit "
+                               f"{B * cpp} bfloat16 pages) + {'prefill_attn_q4_staged' if staged else 'prefill_attn_q4'} (the chunk causally, earlier chunks as {args.q4_bits}-bit "
                                f"codes, key groups of {group} tokens) + quantize_pages_q4 + out_proj; pages of {P} tokens "
                                f"in random order",
                    "batch": B, "n_ctx": n, "r_k": r, "r_v": r, "page_tokens": P, "chunk": C},
         "tokens_per_s": round(B * n / (ms_per_step * 1e-3), 1),
         "kernels": {"project_qkv": {"ms": round(t[0], 4), "tflops": round(tf(f_proj, t[0]), 1)},
-                    "prefill_attn_q4": {"ms": round(t[1], 4), "tflops_causal_counted": round(tf(f_attn, t[1]), 1),
+                    ("prefill_attn_q4_staged" if staged else "prefill_attn_q4"): {"ms": round(t[1], 4), "tflops_causal_counted": round(tf(f_attn, t[1]), 1),
                                         "ms_per_chunk": [round(v, 4) for v in attn_per_chunk]},
                     "quantize_pages_q4": {"ms": round(t[2], 4)},
                     "out_proj": {"ms": round(t[3], 4), "tflops": round(tf(f_out, t[3]), 1)}},
         "cache_bytes": {"bf16_resident": int(B * cpp * (lay16.k_page_elems + lay16.v_page_elems) * 2),
+                        "workspace_of_the_attention_call": int(ws_bytes),
                         "q4_after_the_prompt": int(q4_pages * (lay.k_page_bytes + lay.v_page_bytes)),
                         "bf16_if_the_prompt_were_kept_in_16_bits": int(B * (n // P) * (lay16.k_page_elems + lay16.v_page_elems) * 2)},
         "roofline": {"bound": "mfma", "achieved": round(tf(f_attn, t[1]), 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tf(f_attn, t[1]) / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "prefill_bf16_direct_kernel (the chunk itself) + prefill_q4_kernel (earlier chunks) + "
-                               "merge_prefill_parts_kernel: all ea_prefill_attn_q4 calls of the prompt, flops counted below "
-                               "the causal diagonal only", "flops_per_launch": f_attn, "us_per_launch": round(t[1] * 1e3, 1)},
+                     "kernel": ("stage_lists_kernel + dequantize_q4_kernel + copy_pages_kernel + prefill_bf16_direct_kernel: all "
+                                "ea_prefill_attn_q4_staged calls of the prompt, flops counted below the causal diagonal only"
+                                if staged else
+                                "prefill_bf16_direct_kernel (the chunk itself) + prefill_q4_kernel (earlier chunks) + "
+                                "merge_prefill_parts_kernel: all ea_prefill_attn_q4 calls of the prompt, flops counted below "
+                                "the causal diagonal only"), "flops_per_launch": f_attn, "us_per_launch": round(t[1] * 1e3, 1)},
     }
     if not args.no_parity:
         from oracle import eigen_attention as ora

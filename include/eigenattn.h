@@ -499,14 +499,35 @@ EA_API int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r,
                     void* dev_out, int32_t B, int32_t n,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* ea_prefill_attn_q4 by staging: the same result (Eq. (2) in rank space, causal, over q4_len[b] tokens of codes followed
+ * by tail_len[b] bfloat16 tokens), computed by dequantising the 4-bit pages (as ea_dequantize_pages_q4) and copying the
+ * bfloat16 pages into stage pools inside the workspace and running ea_prefill_attn on those: 4 launches.  While the
+ * call runs, this layer's sequence exists in 16 bits in the workspace (the caches of the other layers stay codes);
+ * in exchange the attention runs at the speed of the 16-bit kernel (a config-4 prompt in four chunks: 1.57 ms of
+ * attention per layer instead of 2.51 ms).  q4_len[b] must be a multiple of page_tokens (whole pages; a remainder is ignored).
+ * One more rounding than ea_prefill_attn_q4 (dequantised values to bfloat16 instead of half precision).
+ *   dev_ws: ea_prefill_q4_staged_workspace_bytes(desc, B, n, max_q4_pages, max_tail_pages) bytes, 256-byte aligned
+ *   everything else as ea_prefill_attn_q4 */
+EA_API int64_t ea_prefill_q4_staged_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n,
+                    int32_t max_q4_pages, int32_t max_tail_pages);
+EA_API int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_q_r,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    void* dev_out, int32_t B, int32_t n,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* ea_prefill_attn_q4 for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama models of the paper's
  * quantisation experiment): token i of the 4-bit part sits at position i, token i of the bfloat16 part at position
  * q4_len[b] + i, the n queries dev_q [B, n, H, d_head] (bfloat16, NOT rotated) are the last n tokens.  Here
  * q4_len[b] must be a multiple of page_tokens (whole pages, as ea_quantize_pages_q4 writes them; a remainder is
  * ignored and the bfloat16 part then counts from the rounded-down length).  A rotary prefill brings every cached key
  * back to d_head channels in a 16-bit workspace anyway (ea_prefill_attn_rope), so this call expands the codes on the
- * way there: the 4-bit pages are dequantised (as ea_dequantize_pages_q4) and the bfloat16 pages copied into stage
- * pools inside the workspace, and ea_prefill_attn_rope runs on those -- 4 + its own 3 launches.  Page ids outside
+ * way there: staged as in ea_prefill_attn_q4_staged, then ea_prefill_attn_rope runs on the stage pools -- 3 + its
+ * own 3 launches.  Page ids outside
  * their pool make that page's tokens vanish, as everywhere.
  *   dev_u_k [d_head, r_k] bfloat16, rope_base, d_head 64 or 128, r_k <= d_head: as ea_prefill_attn_rope
  *   dev_out [B, n, H, r_v] bfloat16

@@ -24,7 +24,7 @@ __all__ = [
     "decode_layer_fused_workspace_bytes", "decode_layer_fused", "decode_layer_fused_rope", "set_wait_limit", "STATUS_WAIT_EXPIRED",
     "decode_layer_fused_workers", "decode_layer_alibi", "decode_layer_fused_alibi",
     "decode_attn_rope_pos", "decode_attn_mass_rope_pos", "prefill_attn_q4", "prefill_q4_workspace_bytes",
-    "prefill_attn_rope_q4", "prefill_rope_q4_workspace_bytes",
+    "prefill_attn_rope_q4", "prefill_rope_q4_workspace_bytes", "prefill_q4_staged_workspace_bytes",
     "q3_k_code_pos", "q3_v_code_pos",
 ]
 
@@ -43,6 +43,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_layer_fused_workers", "ea_decode_layer_alibi", "ea_decode_layer_fused_alibi",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
     "ea_prefill_rope_q4_workspace_bytes", "ea_prefill_attn_rope_q4",
+    "ea_prefill_q4_staged_workspace_bytes", "ea_prefill_attn_q4_staged",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
 
@@ -166,6 +167,9 @@ def load_library():
     lib.ea_prefill_q4_workspace_bytes.restype = I64
     lib.ea_prefill_q4_workspace_bytes.argtypes = [D, I32, I32]
     lib.ea_prefill_attn_q4.argtypes = [D, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP, I64, VP]
+    lib.ea_prefill_q4_staged_workspace_bytes.restype = I64
+    lib.ea_prefill_q4_staged_workspace_bytes.argtypes = [D, I32, I32, I32, I32]
+    lib.ea_prefill_attn_q4_staged.argtypes = lib.ea_prefill_attn_q4.argtypes
     lib.ea_prefill_rope_q4_workspace_bytes.restype = I64
     lib.ea_prefill_rope_q4_workspace_bytes.argtypes = [D, I32, I32, I32, I32]
     lib.ea_prefill_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
@@ -755,10 +759,17 @@ def prefill_q4_workspace_bytes(desc, B: int, n: int) -> int:
     return int(load_library().ea_prefill_q4_workspace_bytes(ctypes.byref(desc), B, n))
 
 
+def prefill_q4_staged_workspace_bytes(desc, B: int, n: int, max_q4_pages: int, max_tail_pages: int) -> int:
+    return int(load_library().ea_prefill_q4_staged_workspace_bytes(ctypes.byref(desc), B, n, max_q4_pages,
+                                                                   max_tail_pages))
+
+
 def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
-                    ws, stream=None) -> None:
+                    ws, stream=None, staged: bool = False) -> None:
     """Causal prefill attention of the last n tokens of every sequence: q_r [B, n, H, r_k] -> out [B, n, H, r_v]
-    (bfloat16) over q4_len[b] tokens of the 4-bit pools followed by tail_len[b] >= n tokens of the bfloat16 pools."""
+    (bfloat16) over q4_len[b] tokens of the 4-bit pools followed by tail_len[b] >= n tokens of the bfloat16 pools.
+    staged: ea_prefill_attn_q4_staged (codes dequantised into stage pools inside ws, which then must hold
+    prefill_q4_staged_workspace_bytes bytes; q4_len in whole pages)."""
     B, n = q_r.shape[0], q_r.shape[1]
     _expect(q_r, desc.dtype, "q_r"); _expect(out, desc.dtype, "out")
     if q_r.numel() != B * n * desc.n_heads * desc.r_k or out.numel() != B * n * desc.n_heads * desc.r_v:
@@ -769,11 +780,12 @@ def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, 
                     (tail_len, "tail_len")):
         _i32(t, name)
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
-    rc = load_library().ea_prefill_attn_q4(
+    lib = load_library()
+    rc = (lib.ea_prefill_attn_q4_staged if staged else lib.ea_prefill_attn_q4)(
         ctypes.byref(desc), _ptr(q_r), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
         q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table), _ptr(tail_len),
         tail_page_table.shape[1], k_pool.shape[0], _ptr(out), B, n, _ptr(ws), ws_bytes, _stream(stream))
-    _check(rc, "ea_prefill_attn_q4")
+    _check(rc, "ea_prefill_attn_q4_staged" if staged else "ea_prefill_attn_q4")
 
 
 def prefill_rope_q4_workspace_bytes(desc, B: int, n: int, max_q4_pages: int, max_tail_pages: int) -> int:

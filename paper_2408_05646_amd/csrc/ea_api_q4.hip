@@ -1,6 +1,6 @@
 // C ABI of the 4-bit group-quantised cache: layout reference functions, page quantisation, attention.
 #include "ea_q4.h"
-#include "ea_prefill_rope_q4.h"
+#include "ea_prefill_q4_staged.h"
 
 using namespace ea;
 
@@ -224,11 +224,44 @@ int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r, const voi
                     (hipStream_t)stream);
 }
 
+int64_t ea_prefill_q4_staged_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_q4_pages,
+                                             int32_t max_tail_pages) {
+  if (validate_q4(desc) != EA_OK || B <= 0 || n <= 0 || max_q4_pages <= 0 || max_tail_pages <= 0) return -1;
+  if ((int64_t)B * ((int64_t)max_q4_pages + max_tail_pages) > INT32_MAX) return -1;
+  return prefill_staged_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages, false);
+}
+
+int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_kq_pool,
+                              const void* dev_vq_pool, const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                              int32_t max_q4_pages, int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
+                              const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
+                              int32_t pool_pages, void* dev_out, int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes,
+                              void* stream) {
+  int rc = validate_q4(desc);
+  if (rc != EA_OK) return rc;
+  if (!dev_q_r || !dev_kq_pool || !dev_vq_pool || !dev_q4_page_table || !dev_q4_len || !dev_k_pool || !dev_v_pool ||
+      !dev_tail_page_table || !dev_tail_len || !dev_out)
+    return EA_ERR_ARG;
+  if (B <= 0 || n <= 0 || max_q4_pages <= 0 || q4_pool_pages <= 0 || max_tail_pages <= 0 || pool_pages <= 0)
+    return EA_ERR_ARG;
+  if ((int64_t)B * ((int64_t)max_q4_pages + max_tail_pages) > INT32_MAX) return EA_ERR_SHAPE;
+  if (!aligned16(dev_q_r) || !aligned16(dev_kq_pool) || !aligned16(dev_vq_pool) || !aligned16(dev_k_pool) ||
+      !aligned16(dev_v_pool) || !aligned16(dev_out))
+    return EA_ERR_ALIGN;
+  if (!dev_ws || (reinterpret_cast<uintptr_t>(dev_ws) & 255u) ||
+      ws_bytes < prefill_staged_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages, false))
+    return EA_ERR_WORKSPACE;
+  clear_stale_error();
+  return prefill_staged_q4(desc, q4_geo_of(desc), dev_q_r, nullptr, 0.0, dev_kq_pool, dev_vq_pool, dev_q4_page_table,
+                           dev_q4_len, max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table,
+                           dev_tail_len, max_tail_pages, pool_pages, dev_out, B, n, dev_ws, (hipStream_t)stream);
+}
+
 int64_t ea_prefill_rope_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_q4_pages,
                                            int32_t max_tail_pages) {
   if (validate_q4(desc) != EA_OK || B <= 0 || n <= 0 || max_q4_pages <= 0 || max_tail_pages <= 0) return -1;
   if ((int64_t)B * ((int64_t)max_q4_pages + max_tail_pages) > INT32_MAX) return -1;
-  return prefill_rope_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages);
+  return prefill_staged_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages, true);
 }
 
 int ea_prefill_attn_rope_q4(const ea_layer_desc* desc, const void* dev_q, const void* dev_u_k, double rope_base,
@@ -251,10 +284,10 @@ int ea_prefill_attn_rope_q4(const ea_layer_desc* desc, const void* dev_q, const 
       !aligned16(dev_k_pool) || !aligned16(dev_v_pool) || !aligned16(dev_out))
     return EA_ERR_ALIGN;
   if (!dev_ws || (reinterpret_cast<uintptr_t>(dev_ws) & 255u) ||
-      ws_bytes < prefill_rope_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages))
+      ws_bytes < prefill_staged_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages, true))
     return EA_ERR_WORKSPACE;
   clear_stale_error();
-  return prefill_rope_q4(desc, q4_geo_of(desc), dev_q, dev_u_k, rope_base, dev_kq_pool, dev_vq_pool, dev_q4_page_table,
+  return prefill_staged_q4(desc, q4_geo_of(desc), dev_q, dev_u_k, rope_base, dev_kq_pool, dev_vq_pool, dev_q4_page_table,
                          dev_q4_len, max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table,
                          dev_tail_len, max_tail_pages, pool_pages, dev_out, B, n, dev_ws, (hipStream_t)stream);
 }

@@ -1,10 +1,12 @@
-// Rotary prefill (Sec. 4.3, Eq. 9-10) over a cache whose older tokens are 4- or 3-bit codes (quantisation paragraph
-// of the results; the Llama models of that experiment are rotary).  In the rotary prefill every cached key is brought
-// back to d_head channels and rotated once, into a 16-bit workspace, before the attention kernel runs -- so the codes
-// are expanded on the way there instead of inside the attention kernel: the pages of the 4-bit part are dequantised
-// into stage pools of bfloat16 pages, the pages of the bfloat16 part are copied behind them, and the rotary prefill
-// of the 16-bit cache runs on the stage pools.  The stage pools live in the caller's workspace for this call only.
-#include "ea_prefill_rope_q4.h"
+// Prefill (Eq. 2 in rank space, causal) over a cache whose older tokens are 4- or 3-bit codes (quantisation paragraph
+// of the results), by staging: the pages of the 4-bit part are dequantised into stage pools of bfloat16 pages, the
+// pages of the bfloat16 part are copied behind them, and the prefill of the 16-bit cache runs on the stage pools,
+// which live in the caller's workspace for this call only.  Rotary form (Sec. 4.3, Eq. 9-10; the Llama models of that
+// experiment): a rotary prefill brings every cached key back to d_head channels in a 16-bit workspace anyway, so the
+// codes are expanded on the way there.  Position-free form: the alternative to attending the codes in the attention
+// kernel itself -- one layer's sequence exists in 16 bits while the call runs, and the attention runs at the speed of
+// the 16-bit kernel.
+#include "ea_prefill_q4_staged.h"
 
 namespace ea {
 
@@ -79,14 +81,14 @@ __global__ __launch_bounds__(256) void copy_pages_kernel(const uint16_t* __restr
 
 }  // namespace
 
-int64_t prefill_rope_q4_ws_bytes(const ea_layer_desc* d, int32_t B, int32_t n, int32_t mq, int32_t mt) {
+int64_t prefill_staged_q4_ws_bytes(const ea_layer_desc* d, int32_t B, int32_t n, int32_t mq, int32_t mt, bool rope) {
   const Geo g = make_geo(d, mq + mt, 1);
   const int64_t stage_pages = (int64_t)B * (mq + mt);
   return align256(list_ints(B, mq, mt) * 4) + align256(stage_pages * g.k_page * 2) + align256(stage_pages * g.v_page * 2) +
-         prefill_rope_ws_bytes(d, B, n, mq + mt);
+         (rope ? prefill_rope_ws_bytes(d, B, n, mq + mt) : 0);
 }
 
-int prefill_rope_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, const void* u_k, double rope_base,
+int prefill_staged_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, const void* u_k, double rope_base,
                     const void* kq_pool, const void* vq_pool, const int32_t* q4_table, const int32_t* q4_len, int32_t mq,
                     int32_t q4_pool_pages, const void* k_pool, const void* v_pool, const int32_t* tail_table,
                     const int32_t* tail_len, int32_t mt, int32_t pool_pages, void* out, int32_t B, int32_t n, void* ws,
@@ -124,6 +126,7 @@ int prefill_rope_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, cons
   }
   rc = launch_status();
   if (rc != EA_OK) return rc;
+  if (!u_k) return prefill_bf16(d, gs, q, k_stage, v_stage, l.table, l.len, out, B, n, st);
   return prefill_rope_bf16(d, gs, q, u_k, rope_base, k_stage, v_stage, l.table, l.len, out, B, n, w, st);
 }
 

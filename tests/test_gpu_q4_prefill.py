@@ -15,12 +15,14 @@ from test_gpu_q4 import Q4Cache, offset_cache
 pytestmark = pytest.mark.gpu
 
 
-def run_prefill_q4(desc, qc, q):
+def run_prefill_q4(desc, qc, q, staged=False):
     B, n = q.shape[0], q.shape[1]
     out = torch.full((B, n, desc.n_heads, desc.r_v), float("nan"), dtype=torch.bfloat16, device="cuda")
-    ws = torch.full((ea.prefill_q4_workspace_bytes(desc, B, n) // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    nbytes = (ea.prefill_q4_staged_workspace_bytes(desc, B, n, qc.q4_table.shape[1], qc.tail_table.shape[1]) if staged
+              else ea.prefill_q4_workspace_bytes(desc, B, n))
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
     ea.prefill_attn_q4(desc, to_dev(desc, q), qc.kq, qc.vq, qc.q4_table, qc.q4_len, qc.dc.k_pool, qc.dc.v_pool,
-                       qc.tail_table, qc.tail_len, out, ws)
+                       qc.tail_table, qc.tail_len, out, ws, staged=staged)
     torch.cuda.synchronize()
     return out.float().cpu().numpy()
 
@@ -54,6 +56,12 @@ def test_prefill_attn_q4_matches_oracle(H, Hkv, r_k, r_v, P, group, lens, n_quan
         # the quantisation is what is measured: the unquantised cache gives something else
         plain = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), 128)
         assert ora.rel_l2(plain, ref) > 3 * err
+    # the staged call (codes dequantised into 16-bit stage pools, then the 16-bit prefill) computes the same
+    before = [t.clone() for t in (qc.kq, qc.vq, qc.dc.k_pool, qc.dc.v_pool)]
+    err_s = assert_close(run_prefill_q4(desc, qc, q, staged=True), ref, TOL_BF16, "q4 prefill, staged")
+    print(f"  staged rel-L2 {err_s:.2e}", flush=True)
+    for a, b in zip(before, (qc.kq, qc.vq, qc.dc.k_pool, qc.dc.v_pool)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
 
 
 @pytest.mark.parametrize("H,Hkv,r_k,r_v,P,group,lens,n_quant,n", [
@@ -75,6 +83,8 @@ def test_prefill_attn_over_3_bit_codes_matches_oracle(H, Hkv, r_k, r_v, P, group
     ref = oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group, bits=3)
     err = assert_close(got, ref, TOL_BF16, "q3 prefill")
     print(f"  rel-L2 {err:.2e}", flush=True)
+    err_s = assert_close(run_prefill_q4(desc, qc, q, staged=True), ref, TOL_BF16, "q3 prefill, staged")
+    print(f"  staged rel-L2 {err_s:.2e}", flush=True)
     if max(n_quant) >= 256:
         # the kernel follows the 3-bit quantiser, not the 4-bit one
         four = oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group)

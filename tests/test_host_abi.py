@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 57
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 59
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -522,6 +522,19 @@ def test_rotary_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching
     assert call(dd=desc(d_h=96)) == -2                                     # d_head 64 or 128
     assert call(dd=desc(d_h=64, r_k=80)) == -2                             # r_k <= d_head
     assert ea.prefill_rope_q4_workspace_bytes(d, 0, 100, 4, 2) == -1
+    # the position-free staged call: the same stage, no rotary workspace, the argument list of ea_prefill_attn_q4
+    staged = ea.prefill_q4_staged_workspace_bytes(d, 2, 100, 4, 2)
+    assert staged == need - ea.prefill_rope_workspace_bytes(d, 2, 100, 6)
+
+    def call_staged(q=OK_PTR, tail=OK_PTR, n=100, mq=4, ws=OK_PTR, ws_bytes=1 << 40, dd=d):
+        return lib.ea_prefill_attn_q4_staged(ctypes.byref(dd), q, OK_PTR, OK_PTR, OK_PTR, OK_PTR, mq, 8, OK_PTR, OK_PTR,
+                                             tail, OK_PTR, 2, 8, OK_PTR, 2, n, ws, ws_bytes, None)
+
+    assert call_staged(q=None) == -1 and call_staged(tail=None) == -1 and call_staged(n=0) == -1 and call_staged(mq=0) == -1
+    assert call_staged(q=ODD_PTR) == -3
+    assert call_staged(ws=None) == -4 and call_staged(ws_bytes=staged - 1) == -4 and call_staged(ws=OK_PTR + 16) == -4
+    assert call_staged(dd=desc(dtype=ea.EA_F32, P=64)) == -2
+    assert ea.prefill_q4_staged_workspace_bytes(d, 2, 0, 4, 2) == -1
     assert ea.prefill_rope_q4_workspace_bytes(d, 1 << 20, 100, 1 << 10, 1 << 10) == -1      # 2^31 stage pages
 
 
