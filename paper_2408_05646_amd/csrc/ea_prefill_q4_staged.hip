@@ -23,6 +23,8 @@ struct StageLists {
   int32_t* len;     // [B] tokens of the staged sequence
 };
 
+constexpr int kCopySlices = 8;   // workgroups per page and pool in the page copy
+
 int64_t list_ints(int32_t B, int32_t mq, int32_t mt) { return (int64_t)B * (3 * (int64_t)(mq + mt) + 1); }
 
 // One thread per (sequence, logical page of the staged sequence).  The 4-bit part counts in whole pages (what
@@ -63,7 +65,7 @@ __global__ void stage_lists_kernel(StageLists l, const int32_t* __restrict__ q4_
   if (p == 0) l.len[b] = nqp * page_tokens + nt;
 }
 
-// Whole bfloat16 pages, keys and values, 16 bytes per thread and step: grid (pages in the list, 2).
+// Whole bfloat16 pages, keys and values, 16 bytes per thread and step: grid (pages in the list, 2, slices of a page).
 __global__ __launch_bounds__(256) void copy_pages_kernel(const uint16_t* __restrict__ k_pool,
                                                          const uint16_t* __restrict__ v_pool,
                                                          uint16_t* __restrict__ k_stage, uint16_t* __restrict__ v_stage,
@@ -76,7 +78,7 @@ __global__ __launch_bounds__(256) void copy_pages_kernel(const uint16_t* __restr
   const int64_t units = (keys ? k_page : v_page) / 8;                       // pages are whole 16-byte units
   const u32x4* from = reinterpret_cast<const u32x4*>((keys ? k_pool : v_pool) + (int64_t)src * (keys ? k_page : v_page));
   u32x4* to = reinterpret_cast<u32x4*>((keys ? k_stage : v_stage) + (int64_t)dst * (keys ? k_page : v_page));
-  for (int64_t u = threadIdx.x; u < units; u += 256) to[u] = from[u];
+  for (int64_t u = (int64_t)blockIdx.z * 256 + threadIdx.x; u < units; u += (int64_t)gridDim.z * 256) to[u] = from[u];
 }
 
 }  // namespace
@@ -120,7 +122,7 @@ int prefill_staged_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, co
   if (rc != EA_OK) return rc;
   for (int32_t done = 0; done < B * mt; done += 65535) {
     const int32_t now = B * mt - done < 65535 ? B * mt - done : 65535;
-    copy_pages_kernel<<<dim3((uint32_t)now, 2), 256, 0, st>>>((const uint16_t*)k_pool, (const uint16_t*)v_pool, k_stage,
+    copy_pages_kernel<<<dim3((uint32_t)now, 2, kCopySlices), 256, 0, st>>>((const uint16_t*)k_pool, (const uint16_t*)v_pool, k_stage,
                                                               v_stage, l.src_t + done, l.dst_t + done, gs.k_page,
                                                               gs.v_page, pool_pages, stage_pages);
   }
