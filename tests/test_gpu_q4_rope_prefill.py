@@ -171,3 +171,49 @@ def test_prefill_attn_rope_q4_random_shapes(seed):
         got = run_prefill_rope_q4(desc, qc, q, U, 10000.0)
         ref = oq.prefill_attention_rope_quantized(q, K, V, n_quant, U, d_h, 10000.0, group_tokens=group, bits=bits)
         assert_close(got, ref, TOL_BF16, f"seed {seed} case {case}")
+
+
+@pytest.mark.parametrize("rope", [False, True])
+def test_staged_quantised_prefill_is_graph_capturable(rope):
+    """The staged calls only enqueue kernels on the caller's stream (the stage lives in the caller's workspace; no
+    allocation, no memset), so they can be captured in a HIP graph; every replay, with the workspace and the output
+    overwritten in between, reproduces the eager result."""
+    H, Hkv, d_h, r_k, r_v, P = 4, 2, 128, 80, 48, 64
+    desc = ea.LayerDesc(H * d_h, H, Hkv, d_h, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(174, int(rope))
+    lens, n_quant, n = [700, 400], [512, 192], 150
+    U = quantize(desc, synth.orthonormal_basis(g, d_h, r_k))
+    K, V = offset_cache(desc, lens, g)
+    q = to_dev(desc, quantize(desc, synth.gaussian(g, (2, n, H, d_h if rope else r_k))))
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    Ud = to_dev(desc, U)
+    out = torch.empty((2, n, H, r_v), dtype=torch.bfloat16, device="cuda")
+    mq, mt = qc.q4_table.shape[1], qc.tail_table.shape[1]
+    nbytes = (ea.prefill_rope_q4_workspace_bytes if rope else ea.prefill_q4_staged_workspace_bytes)(desc, 2, n, mq, mt)
+    ws = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda")
+
+    def call():
+        if rope:
+            ea.prefill_attn_rope_q4(desc, q, Ud, 10000.0, qc.kq, qc.vq, qc.q4_table, qc.q4_len, qc.dc.k_pool,
+                                    qc.dc.v_pool, qc.tail_table, qc.tail_len, out, ws)
+        else:
+            ea.prefill_attn_q4(desc, q, qc.kq, qc.vq, qc.q4_table, qc.q4_len, qc.dc.k_pool, qc.dc.v_pool,
+                               qc.tail_table, qc.tail_len, out, ws, staged=True)
+
+    call()
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        out.zero_(); ws.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
