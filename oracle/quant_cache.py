@@ -149,18 +149,19 @@ def decode_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int,
 
 
 def prefill_attention_quantized(q_r, K_list, V_list, n_quant, d_head: int, group_tokens: int = GROUP_TOKENS,
-                                bits: int = 4):
+                                bits: int = 4, alibi_slopes=None):
     """Prefill-phase attention (Eq. 2 in the rank-r space, causal) of the LAST n tokens of every sequence over a
     cache whose first n_quant[b] tokens are quantised: plain causal attention over the dequantised values.
     q_r [B, n, H, r_k]; K_list[b] [H_kv, len_b, r_k]; V_list[b] [H_kv, len_b, r_v]; n <= len_b - n_quant[b] (the
-    queries belong to tokens that are still held in 16 bits)."""
+    queries belong to tokens that are still held in 16 bits).  With alibi_slopes [H] the ALiBi bias of the MPT models
+    is added to the scores (positions only: quantisation does not touch it)."""
     n = np.asarray(q_r).shape[1]
     for b in range(len(K_list)):
         assert n <= K_list[b].shape[1] - int(n_quant[b])
     prefill_views = [quantized_view(K_list[b], V_list[b], int(n_quant[b]), group_tokens, bits)
                      for b in range(len(K_list))]
     cache = ea_oracle.RankCache.from_arrays([v[0] for v in prefill_views], [v[1] for v in prefill_views])
-    return ea_oracle.prefill_attention(q_r, cache, d_head)
+    return ea_oracle.prefill_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)
 
 
 def prefill_attention_rope_quantized(q, K_list, V_list, n_quant, Uk, d_head: int, base: float = 10000.0,

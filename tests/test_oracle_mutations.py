@@ -122,7 +122,7 @@ QUANT = [
     ("a chunked prefill never quantises the chunks it has finished",
      "[V[:, :c1]], [c0], d_head,", "[V[:, :c1]], [0], d_head,", "test_prefill_attention_over_a_partly_quantised_cache"),
     ("the prefill over a partly quantised cache drops the causal mask (every query sees the whole cache)",
-     "    return ea_oracle.prefill_attention(q_r, cache, d_head)",
+     "    return ea_oracle.prefill_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)",
      "    return np.stack([ea_oracle.decode_attention(np.asarray(q_r)[:, j], cache, d_head) for j in range(n)], axis=1)",
      "test_prefill_attention_over_a_partly_quantised_cache"),
     ("the rotary prefill over a partly quantised cache attends the unquantised cache",
@@ -133,6 +133,10 @@ QUANT = [
      "    return ea_oracle.prefill_attention_rope(q, cache, Uk, d_head, base)",
      "    return ea_oracle.prefill_attention_rope(q, cache, Uk, d_head)",
      "test_rotary_prefill_over_a_partly_quantised_cache"),
+    ("the prefill over a partly quantised cache drops the ALiBi slopes it was given",
+     "    return ea_oracle.prefill_attention(q_r, cache, d_head, alibi_slopes=alibi_slopes)",
+     "    return ea_oracle.prefill_attention(q_r, cache, d_head)",
+     "test_prefill_attention_over_a_partly_quantised_cache"),
     ("the key quantiser ignores the group length it is given",
      "    Kg = K.astype(np.float32).reshape(n // group_tokens, group_tokens, r)",
      "    Kg = K.astype(np.float32).reshape(n // GROUP_TOKENS, GROUP_TOKENS, r)", "test_key_groups_of_128_tokens"),

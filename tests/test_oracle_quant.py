@@ -343,6 +343,16 @@ def test_prefill_attention_over_a_partly_quantised_cache():
     got = oq.prefill_attention_quantized(q, K, V, [128], d_h)
     assert not np.allclose(got, plain, atol=1e-3)
     assert np.allclose(got[:, -1], oq.decode_attention_quantized(q[:, -1], K, V, [128], d_h), rtol=0, atol=1e-13)
+    # with ALiBi slopes: zero slopes change nothing, and every row is the generation-phase function (whose bias is
+    # pinned by brute force elsewhere) on the prefix that ends with it
+    slopes = np.array([0.5, 0.25, 0.125, 0.0625])
+    assert np.array_equal(oq.prefill_attention_quantized(q, K, V, [128], d_h, alibi_slopes=np.zeros(H)), got)
+    biased = oq.prefill_attention_quantized(q, K, V, [128], d_h, alibi_slopes=slopes)
+    assert not np.allclose(biased, got, atol=1e-3)
+    for jj in (0, 33, n - 1):
+        pp = L - n + jj
+        row = oq.decode_attention_quantized(q[:, jj], [K[0][:, :pp + 1]], [V[0][:, :pp + 1]], [128], d_h, alibi_slopes=slopes)
+        assert np.allclose(biased[:, jj], row, rtol=0, atol=1e-12)
     # (c) query j = 10 (position 140), head 3 (kv head 1): keys 0..127 dequantised, 128..140 as they are
     j, h, kv = 10, 3, 1
     pos = L - n + j
