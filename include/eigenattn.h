@@ -520,6 +520,19 @@ EA_API int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_
                     void* dev_out, int32_t B, int32_t n,
                     void* dev_ws, int64_t ws_bytes, void* stream);
 
+/* The staged call with the ALiBi position bias (the MPT family of Sec. 5.1): dev_slopes [H] float as for
+ * ea_prefill_attn_alibi (NULL: EA_ERR_ARG); token i of the 4-bit part sits at position i, token i of the bfloat16 part
+ * at position q4_len[b] + i (q4_len[b] in whole pages).  Workspace as ea_prefill_attn_q4_staged. */
+EA_API int ea_prefill_attn_alibi_q4(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                    const void* dev_kq_pool, const void* dev_vq_pool,
+                    const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                    int32_t max_q4_pages, int32_t q4_pool_pages,
+                    const void* dev_k_pool, const void* dev_v_pool,
+                    const int32_t* dev_tail_page_table, const int32_t* dev_tail_len,
+                    int32_t max_tail_pages, int32_t pool_pages,
+                    void* dev_out, int32_t B, int32_t n,
+                    void* dev_ws, int64_t ws_bytes, void* stream);
+
 /* ea_prefill_attn_q4 for models with rotary position embedding (Sec. 4.3, Eq. 9-10; the Llama models of the paper's
  * quantisation experiment): token i of the 4-bit part sits at position i, token i of the bfloat16 part at position
  * q4_len[b] + i, the n queries dev_q [B, n, H, d_head] (bfloat16, NOT rotated) are the last n tokens.  Here

@@ -43,7 +43,7 @@ EXPORTED_SYMBOLS = (
     "ea_decode_layer_fused_workers", "ea_decode_layer_alibi", "ea_decode_layer_fused_alibi",
     "ea_decode_attn_rope_pos", "ea_decode_attn_mass_rope_pos", "ea_prefill_q4_workspace_bytes", "ea_prefill_attn_q4",
     "ea_prefill_rope_q4_workspace_bytes", "ea_prefill_attn_rope_q4",
-    "ea_prefill_q4_staged_workspace_bytes", "ea_prefill_attn_q4_staged",
+    "ea_prefill_q4_staged_workspace_bytes", "ea_prefill_attn_q4_staged", "ea_prefill_attn_alibi_q4",
     "ea_q3_k_code_pos", "ea_q3_v_code_pos",
 )
 
@@ -170,6 +170,8 @@ def load_library():
     lib.ea_prefill_q4_staged_workspace_bytes.restype = I64
     lib.ea_prefill_q4_staged_workspace_bytes.argtypes = [D, I32, I32, I32, I32]
     lib.ea_prefill_attn_q4_staged.argtypes = lib.ea_prefill_attn_q4.argtypes
+    lib.ea_prefill_attn_alibi_q4.argtypes = [D, VP, VP, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32, VP, I32, I32, VP,
+                                             I64, VP]
     lib.ea_prefill_rope_q4_workspace_bytes.restype = I64
     lib.ea_prefill_rope_q4_workspace_bytes.argtypes = [D, I32, I32, I32, I32]
     lib.ea_prefill_attn_rope_q4.argtypes = [D, VP, VP, ctypes.c_double, VP, VP, VP, VP, I32, I32, VP, VP, VP, VP, I32, I32,
@@ -765,11 +767,13 @@ def prefill_q4_staged_workspace_bytes(desc, B: int, n: int, max_q4_pages: int, m
 
 
 def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, v_pool, tail_page_table, tail_len, out,
-                    ws, stream=None, staged: bool = False) -> None:
+                    ws, stream=None, staged: bool = False, alibi_slopes=None) -> None:
     """Causal prefill attention of the last n tokens of every sequence: q_r [B, n, H, r_k] -> out [B, n, H, r_v]
     (bfloat16) over q4_len[b] tokens of the 4-bit pools followed by tail_len[b] >= n tokens of the bfloat16 pools.
     staged: ea_prefill_attn_q4_staged (codes dequantised into stage pools inside ws, which then must hold
-    prefill_q4_staged_workspace_bytes bytes; q4_len in whole pages)."""
+    prefill_q4_staged_workspace_bytes bytes; q4_len in whole pages).  With alibi_slopes ([H] float32) the staged call
+    with the ALiBi bias (ea_prefill_attn_alibi_q4; same workspace)."""
+    import torch
     B, n = q_r.shape[0], q_r.shape[1]
     _expect(q_r, desc.dtype, "q_r"); _expect(out, desc.dtype, "out")
     if q_r.numel() != B * n * desc.n_heads * desc.r_k or out.numel() != B * n * desc.n_heads * desc.r_v:
@@ -781,6 +785,16 @@ def prefill_attn_q4(desc, q_r, kq_pool, vq_pool, q4_page_table, q4_len, k_pool, 
         _i32(t, name)
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     lib = load_library()
+    if alibi_slopes is not None:
+        if alibi_slopes.dtype != torch.float32 or alibi_slopes.numel() != desc.n_heads or not alibi_slopes.is_contiguous():
+            raise ValueError("alibi_slopes must be a contiguous float32 [H] tensor")
+        rc = lib.ea_prefill_attn_alibi_q4(
+            ctypes.byref(desc), _ptr(q_r), _ptr(alibi_slopes), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table),
+            _ptr(q4_len), q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table),
+            _ptr(tail_len), tail_page_table.shape[1], k_pool.shape[0], _ptr(out), B, n, _ptr(ws), ws_bytes,
+            _stream(stream))
+        _check(rc, "ea_prefill_attn_alibi_q4")
+        return
     rc = (lib.ea_prefill_attn_q4_staged if staged else lib.ea_prefill_attn_q4)(
         ctypes.byref(desc), _ptr(q_r), _ptr(kq_pool), _ptr(vq_pool), _ptr(q4_page_table), _ptr(q4_len),
         q4_page_table.shape[1], kq_pool.shape[0], _ptr(k_pool), _ptr(v_pool), _ptr(tail_page_table), _ptr(tail_len),

@@ -231,12 +231,12 @@ int64_t ea_prefill_q4_staged_workspace_bytes(const ea_layer_desc* desc, int32_t 
   return prefill_staged_q4_ws_bytes(desc, B, n, max_q4_pages, max_tail_pages, false);
 }
 
-int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_kq_pool,
-                              const void* dev_vq_pool, const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
-                              int32_t max_q4_pages, int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
-                              const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
-                              int32_t pool_pages, void* dev_out, int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes,
-                              void* stream) {
+static int prefill_q4_staged_impl(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                                  const void* dev_kq_pool, const void* dev_vq_pool, const int32_t* dev_q4_page_table,
+                                  const int32_t* dev_q4_len, int32_t max_q4_pages, int32_t q4_pool_pages,
+                                  const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_tail_page_table,
+                                  const int32_t* dev_tail_len, int32_t max_tail_pages, int32_t pool_pages,
+                                  void* dev_out, int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes, void* stream) {
   int rc = validate_q4(desc);
   if (rc != EA_OK) return rc;
   if (!dev_q_r || !dev_kq_pool || !dev_vq_pool || !dev_q4_page_table || !dev_q4_len || !dev_k_pool || !dev_v_pool ||
@@ -254,7 +254,31 @@ int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_q_r, co
   clear_stale_error();
   return prefill_staged_q4(desc, q4_geo_of(desc), dev_q_r, nullptr, 0.0, dev_kq_pool, dev_vq_pool, dev_q4_page_table,
                            dev_q4_len, max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table,
-                           dev_tail_len, max_tail_pages, pool_pages, dev_out, B, n, dev_ws, (hipStream_t)stream);
+                           dev_tail_len, max_tail_pages, pool_pages, dev_out, B, n, dev_ws, (hipStream_t)stream,
+                           dev_slopes);
+}
+
+int ea_prefill_attn_q4_staged(const ea_layer_desc* desc, const void* dev_q_r, const void* dev_kq_pool,
+                              const void* dev_vq_pool, const int32_t* dev_q4_page_table, const int32_t* dev_q4_len,
+                              int32_t max_q4_pages, int32_t q4_pool_pages, const void* dev_k_pool, const void* dev_v_pool,
+                              const int32_t* dev_tail_page_table, const int32_t* dev_tail_len, int32_t max_tail_pages,
+                              int32_t pool_pages, void* dev_out, int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes,
+                              void* stream) {
+  return prefill_q4_staged_impl(desc, dev_q_r, nullptr, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
+                                max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len,
+                                max_tail_pages, pool_pages, dev_out, B, n, dev_ws, ws_bytes, stream);
+}
+
+int ea_prefill_attn_alibi_q4(const ea_layer_desc* desc, const void* dev_q_r, const float* dev_slopes,
+                             const void* dev_kq_pool, const void* dev_vq_pool, const int32_t* dev_q4_page_table,
+                             const int32_t* dev_q4_len, int32_t max_q4_pages, int32_t q4_pool_pages,
+                             const void* dev_k_pool, const void* dev_v_pool, const int32_t* dev_tail_page_table,
+                             const int32_t* dev_tail_len, int32_t max_tail_pages, int32_t pool_pages, void* dev_out,
+                             int32_t B, int32_t n, void* dev_ws, int64_t ws_bytes, void* stream) {
+  if (!dev_slopes) return EA_ERR_ARG;
+  return prefill_q4_staged_impl(desc, dev_q_r, dev_slopes, dev_kq_pool, dev_vq_pool, dev_q4_page_table, dev_q4_len,
+                                max_q4_pages, q4_pool_pages, dev_k_pool, dev_v_pool, dev_tail_page_table, dev_tail_len,
+                                max_tail_pages, pool_pages, dev_out, B, n, dev_ws, ws_bytes, stream);
 }
 
 int64_t ea_prefill_rope_q4_workspace_bytes(const ea_layer_desc* desc, int32_t B, int32_t n, int32_t max_q4_pages,

@@ -3,7 +3,7 @@
 // pages of the bfloat16 part are copied behind them, and the prefill of the 16-bit cache runs on the stage pools,
 // which live in the caller's workspace for this call only.  Rotary form (Sec. 4.3, Eq. 9-10; the Llama models of that
 // experiment): a rotary prefill brings every cached key back to d_head channels in a 16-bit workspace anyway, so the
-// codes are expanded on the way there.  Position-free form: the alternative to attending the codes in the attention
+// codes are expanded on the way there.  Position-free form (and with the ALiBi bias): the alternative to attending the codes in the attention
 // kernel itself -- one layer's sequence exists in 16 bits while the call runs, and the attention runs at the speed of
 // the 16-bit kernel.
 #include "ea_prefill_q4_staged.h"
@@ -94,7 +94,7 @@ int prefill_staged_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, co
                     const void* kq_pool, const void* vq_pool, const int32_t* q4_table, const int32_t* q4_len, int32_t mq,
                     int32_t q4_pool_pages, const void* k_pool, const void* v_pool, const int32_t* tail_table,
                     const int32_t* tail_len, int32_t mt, int32_t pool_pages, void* out, int32_t B, int32_t n, void* ws,
-                    hipStream_t st) {
+                    hipStream_t st, const float* slopes) {
   const int64_t stage_pages64 = (int64_t)B * (mq + mt);
   if (stage_pages64 > INT32_MAX || (int64_t)B * mq > INT32_MAX) return EA_ERR_SHAPE;
   const int32_t mp = mq + mt, stage_pages = (int32_t)stage_pages64;
@@ -128,6 +128,8 @@ int prefill_staged_q4(const ea_layer_desc* d, const Q4Geo& qg, const void* q, co
   }
   rc = launch_status();
   if (rc != EA_OK) return rc;
+  if (u_k && slopes) return EA_ERR_ARG;
+  if (slopes) return prefill_alibi_bf16(d, gs, q, slopes, k_stage, v_stage, l.table, l.len, out, B, n, st);
   if (!u_k) return prefill_bf16(d, gs, q, k_stage, v_stage, l.table, l.len, out, B, n, st);
   return prefill_rope_bf16(d, gs, q, u_k, rope_base, k_stage, v_stage, l.table, l.len, out, B, n, w, st);
 }

@@ -174,3 +174,33 @@ def test_a_prompt_prefilled_in_chunks_never_exists_in_16_bits(group, P, chunk, b
     q_new, _, _ = ora.project_qkv(x[n_all:], Wq_q, Wk_q, Wv_q)
     ref_o = oq.decode_attention_quantized(q_new, [K], [V], [n_all], d_h, group_tokens=group, bits=bits)
     assert_close(o.cpu().numpy(), ref_o, TOL_BF16, "generation step over the quantised prompt")
+
+
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,P,group,bits,lens,n_quant,n", [
+    (2, 2, 80, 80, 64, 64, 4, [200, 130], [128, 64], 60),
+    (8, 2, 48, 112, 128, 64, 4, [777, 1500], [512, 1280], 200),      # GQA 4:1, r_k != r_v
+    (4, 4, 128, 128, 64, 64, 3, [513, 400], [256, 192], 129),        # full rank, 3-bit codes
+    (4, 2, 30, 33, 128, 128, 4, [150, 470], [0, 384], 70),           # ranks off the chunk sizes, key groups of 128
+])
+def test_prefill_attn_alibi_q4_matches_oracle(H, Hkv, r_k, r_v, P, group, bits, lens, n_quant, n):
+    """The staged call with the ALiBi bias against the oracle's causal attention with slopes over the dequantised cache."""
+    print(f"q{bits} alibi prefill H={H}/{Hkv} r=({r_k},{r_v}) P={P} group={group} lens={lens} quantised={n_quant} n={n}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P, group, bits)
+    g = synth.rng(156, H, r_k, len(lens), n)
+    K, V = offset_cache(desc, lens, g, k_std=1.5)
+    B = len(lens)
+    q = quantize(desc, synth.gaussian(g, (B, n, H, r_k), 1.0))
+    qc = Q4Cache(desc, K, V, n_quant, g)
+    slopes = np.array([2.0 ** (-8.0 * (h + 1) / H) for h in range(H)], np.float32)
+    out = torch.full((B, n, H, r_v), float("nan"), dtype=torch.bfloat16, device="cuda")
+    nbytes = ea.prefill_q4_staged_workspace_bytes(desc, B, n, qc.q4_table.shape[1], qc.tail_table.shape[1])
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device="cuda")
+    ea.prefill_attn_q4(desc, to_dev(desc, q), qc.kq, qc.vq, qc.q4_table, qc.q4_len, qc.dc.k_pool, qc.dc.v_pool,
+                       qc.tail_table, qc.tail_len, out, ws, alibi_slopes=torch.tensor(slopes, device="cuda"))
+    torch.cuda.synchronize()
+    ref = oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group, bits=bits,
+                                         alibi_slopes=slopes.astype(np.float64))
+    err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "q4 alibi prefill")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+    # the bias is in there
+    assert ora.rel_l2(oq.prefill_attention_quantized(q, K, V, n_quant, 128, group_tokens=group, bits=bits), ref) > 10 * err

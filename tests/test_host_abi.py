@@ -19,7 +19,7 @@ def desc(dtype=ea.EA_BF16, H=8, Hkv=2, r_k=80, r_v=48, P=128, d=1024, d_h=128):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "eigenattn.h")).read()
     declared = set(re.findall(r"EA_API\s+[\w\s\*]+?\b(ea_\w+)\s*\(", header))
-    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 59
+    assert declared == set(ea.EXPORTED_SYMBOLS) and len(declared) == 60
     lib = ctypes.CDLL(ea.library_path())
     for name in declared:
         assert getattr(lib, name) is not None
@@ -535,6 +535,13 @@ def test_rotary_prefill_over_the_q4_cache_rejects_bad_arguments_before_launching
     assert call_staged(ws=None) == -4 and call_staged(ws_bytes=staged - 1) == -4 and call_staged(ws=OK_PTR + 16) == -4
     assert call_staged(dd=desc(dtype=ea.EA_F32, P=64)) == -2
     assert ea.prefill_q4_staged_workspace_bytes(d, 2, 0, 4, 2) == -1
+
+    def call_alibi(q=OK_PTR, slopes=OK_PTR, ws=OK_PTR, ws_bytes=1 << 40):
+        return lib.ea_prefill_attn_alibi_q4(ctypes.byref(d), q, slopes, OK_PTR, OK_PTR, OK_PTR, OK_PTR, 4, 8, OK_PTR,
+                                            OK_PTR, OK_PTR, OK_PTR, 2, 8, OK_PTR, 2, 100, ws, ws_bytes, None)
+
+    assert call_alibi(slopes=None) == -1 and call_alibi(q=None) == -1 and call_alibi(q=ODD_PTR) == -3
+    assert call_alibi(ws_bytes=staged - 1) == -4 and call_alibi(ws=None) == -4
     assert ea.prefill_rope_q4_workspace_bytes(d, 1 << 20, 100, 1 << 10, 1 << 10) == -1      # 2^31 stage pages
 
 
