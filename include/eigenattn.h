@@ -503,8 +503,8 @@ EA_API int ea_prefill_attn_q4(const ea_layer_desc* desc, const void* dev_q_r,
  * by tail_len[b] bfloat16 tokens), computed by dequantising the 4-bit pages (as ea_dequantize_pages_q4) and copying the
  * bfloat16 pages into stage pools inside the workspace and running ea_prefill_attn on those: 4 launches.  While the
  * call runs, this layer's sequence exists in 16 bits in the workspace (the caches of the other layers stay codes);
- * in exchange the attention runs at the speed of the 16-bit kernel (a config-4 prompt in four chunks: 1.46 ms of
- * attention per layer instead of 2.51 ms).  q4_len[b] must be a multiple of page_tokens (whole pages; a remainder is ignored).
+ * in exchange the attention runs at the speed of the 16-bit kernel (a config-4 prompt in four chunks: about 1.5 ms of
+ * attention per layer instead of 2.4-2.5 ms).  q4_len[b] must be a multiple of page_tokens (whole pages; a remainder is ignored).
  * One more rounding than ea_prefill_attn_q4 (dequantised values to bfloat16 instead of half precision).
  *   dev_ws: ea_prefill_q4_staged_workspace_bytes(desc, B, n, max_q4_pages, max_tail_pages) bytes, 256-byte aligned
  *   everything else as ea_prefill_attn_q4 */
