@@ -231,7 +231,16 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     const int t = u & 15, rest = u >> 4;
     const int chunk = rest % qg.nch, tb = rest / qg.nch;
     const int tt = tb * 16 + t, c0 = chunk * 8;
-    const _Float16* sp = reinterpret_cast<const _Float16*>(ks_grp + q4_k_scale_off(c0));
+    // the 8 scales and the 8 zeros of these channels: two 16-byte units, 16 bytes apart
+    typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+    const half8 sc8 = *reinterpret_cast<const half8*>(ks_grp + q4_k_scale_off(c0));
+    const half8 zr8 = *reinterpret_cast<const half8*>(ks_grp + q4_k_scale_off(c0) + 16);
+    _Float16 sp[16];
+#pragma unroll
+    for (int ce = 0; ce < 8; ++ce) {
+      sp[ce] = sc8[ce];
+      sp[8 + ce] = zr8[ce];
+    }
     float val[8];
     if (qg.bits == 3) {
 #pragma unroll
@@ -255,20 +264,23 @@ __global__ __launch_bounds__(256) void dequantize_q4_kernel(QuantArgs a) {
     const int c = cb * 16 + ch, tt0 = u * 32 + quad * 4;
     float val[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (c < g.r_v) {
-      const _Float16* sp = reinterpret_cast<const _Float16*>(vb + q4_v_scale_off(qg, tt0));
+      // the scales of the unit's 8 token slots and, 128 bytes further, their zeros: one 16-byte unit each
+      typedef __attribute__((ext_vector_type(8))) _Float16 half8;
+      const half8 sc8 = *reinterpret_cast<const half8*>(vb + q4_v_scale_off(qg, tt0));
+      const half8 zr8 = *reinterpret_cast<const half8*>(vb + q4_v_scale_off(qg, tt0) + 128);
       if (qg.bits == 3) {
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj) {
           // token slot jj of this unit: token tt0 + 16 * (jj / 4) + jj % 4
           const uint32_t code = q3_read(vb, q3_v_pos(qg, tt0 + (jj >> 2) * 16 + (jj & 3), c));
-          val[jj] = fmaf((float)sp[jj], (float)code, (float)sp[64 + jj]);
+          val[jj] = fmaf((float)sc8[jj], (float)code, (float)zr8[jj]);
         }
       } else {
         int slot0;
         const uint32_t w = *reinterpret_cast<const uint32_t*>(vb + q4_v_dword_off(qg, tt0, c, &slot0));
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj)
-          val[jj] = fmaf((float)sp[jj], (float)((w >> q4_nibble_shift(jj)) & 15u), (float)sp[64 + jj]);
+          val[jj] = fmaf((float)sc8[jj], (float)((w >> q4_nibble_shift(jj)) & 15u), (float)zr8[jj]);
       }
     }
     *reinterpret_cast<u32x4*>(vo + bf16_v_slab_off(tile * kTile + tt0, c, g.r_v_pad)) =
