@@ -56,7 +56,10 @@ template <> struct FragElem<f16x8> { using type = _Float16; };
 // unmasked tiles run the lean path.  `vis` = number of kv positions this lane's query may see.
 // ALIBI: every score gets slope * (key position - query position) (log2 units) before the softmax; `dist0` is
 // the distance of this lane's query to the tile's first token of this register quad (tok0 + 4*quad - pos).
-template <int KS, int NCB, int TB, bool MASKED, bool ALIBI, class F = bf16x8>
+// RAWREF (ALiBi only): the tile's maximum is taken over the scores WITHOUT the bias.  The bias of a visible key is
+// never positive, so a reference exponent that bounds the scores alone bounds the biased ones too, and the tiles
+// that run without a maximum search can keep it although the bias of their keys grows from tile to tile.
+template <int KS, int NCB, int TB, bool MASKED, bool ALIBI, class F = bf16x8, bool RAWREF = false>
 __device__ __forceinline__ void attend_block(const F (&kf)[TB][KS], const F (&vf)[TB / 2][NCB],
                                              const F (&q)[KS], const F& ones, f32x4 (&acc)[NCB],
                                              f32x4& lacc, float& m, float scale_log2, int tok0, int vis, int quad,
@@ -71,21 +74,33 @@ __device__ __forceinline__ void attend_block(const F (&kf)[TB][KS], const F (&vf
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
-  if (ALIBI) {
+  float mx = -INFINITY;
+  if constexpr (ALIBI && RAWREF) {
     const float base = slope * (float)dist0;
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(slope, (float)(tb * 16 + i), base);
-  }
-  float mx = -INFINITY;
+      for (int i = 0; i < 4; ++i) {
+        const bool hidden = MASKED && tok0 + tb * 16 + quad * 4 + i >= vis;
+        mx = fmaxf(mx, hidden ? -INFINITY : s[tb][i]);
+        s[tb][i] = hidden ? -INFINITY : s[tb][i] + fmaf(slope, (float)(tb * 16 + i), base);
+      }
+  } else {
+    if (ALIBI) {
+      const float base = slope * (float)dist0;
 #pragma unroll
-  for (int tb = 0; tb < TB; ++tb)
+      for (int tb = 0; tb < TB; ++tb)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
-      mx = fmaxf(mx, s[tb][i]);
+        for (int i = 0; i < 4; ++i) s[tb][i] += fmaf(slope, (float)(tb * 16 + i), base);
     }
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (MASKED && tok0 + tb * 16 + quad * 4 + i >= vis) s[tb][i] = -INFINITY;
+        mx = fmaxf(mx, s[tb][i]);
+      }
+  }
   mx = quad_column_max(mx);                                  // relative to m_base
   // m is a reference exponent, not the exact running max: it only moves when the max has grown by more
   // than kLazy (log2 units), so P stays <= 2^kLazy -- harmless in bf16 / fp32 -- and the accumulators are
@@ -121,12 +136,21 @@ __device__ __forceinline__ void attend_block(const F (&kf)[TB][KS], const F (&vf
 // without looking for the tile's maximum: the exponentials are taken against the reference as it stands and the
 // caller inspects the row sums afterwards (see the tile loop).  Per score that leaves the exponential and half a
 // conversion for the vector unit.
-template <int KS, int NCB, int TB, class F = bf16x8>
+// ALIBI: the accumulators start at bias - m instead (one multiply-add per score, as the exact form pays for the bias
+// alone); m must then bound the scores without the bias (RAWREF above).
+template <int KS, int NCB, int TB, class F = bf16x8, bool ALIBI = false>
 __device__ __forceinline__ void attend_block_optimistic(const F (&kf)[TB][KS], const F (&vf)[TB / 2][NCB],
                                                         const F (&q)[KS], const F& ones, f32x4 (&acc)[NCB],
-                                                        f32x4& lacc, float m) {
+                                                        f32x4& lacc, float m, float slope = 0.f, int dist0 = 0) {
   const f32x4 neg_m{-m, -m, -m, -m};
   f32x4 s[TB];
+  if constexpr (ALIBI) {
+    const float base = fmaf(slope, (float)dist0, -m);
+#pragma unroll
+    for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) s[tb][i] = fmaf(slope, (float)(tb * 16 + i), base);
+  }
   // Two waves share a SIMD, and of two that are ready the older one issues.  Its run of exponentials would keep
   // the issue port for itself while the other wave's matrix instructions -- which need the port only half of
   // their time -- wait; with the matrix phases at the higher priority the wave that is multiplying goes first and
@@ -134,7 +158,8 @@ __device__ __forceinline__ void attend_block_optimistic(const F (&kf)[TB][KS], c
   __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int tb = 0; tb < TB; ++tb) {
-    s[tb] = mfma16(kf[tb][0], q[0], neg_m);
+    if constexpr (ALIBI) s[tb] = mfma16(kf[tb][0], q[0], s[tb]);
+    else s[tb] = mfma16(kf[tb][0], q[0], neg_m);
 #pragma unroll
     for (int ks = 1; ks < KS; ++ks) s[tb] = mfma16(kf[tb][ks], q[ks], s[tb]);
   }
@@ -337,9 +362,12 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
   // (accumulators scaled down, a handful of times per query at most); one that passed 2^kAbort, or is not a
   // number, means the scores rose by more than the headroom since the last look -- then the wave starts over and
   // takes every tile with the exact maximum (P <= row sum < 2^kAbort otherwise, so the output accumulators are as
-  // far from overflow as the values allow).  ALiBi tiles always take the exact form.
-  constexpr float kGrow = 32.0f, kAbort = 64.0f;
-  bool optimistic = !ALIBI;
+  // far from overflow as the values allow).  With the ALiBi bias the reference bounds the scores without the bias
+  // (which is never positive for a key a query may see), so the same holds; what the bias can do instead is push
+  // every term of a row far below its reference, so a row sum that ends below 2^-kTiny also sends the wave into
+  // the exact walk, whose reference follows the biased maximum.
+  constexpr float kGrow = 32.0f, kAbort = 64.0f, kTiny = 64.0f;
+  bool optimistic = true;
   for (;;) {                                                     // one walk; a second, exact one if the first was lost
     bool lost_walk = false;
     int page = -1;
@@ -359,19 +387,42 @@ __global__ __launch_bounds__(256, WPE) void prefill_bf16_direct_kernel(PrefillAr
       if (full && optimistic && t > 0) {
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb)
-          attend_block_optimistic<KS, NCB, TB>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb]);
+          attend_block_optimistic<KS, NCB, TB, bf16x8, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], slope,
+                                                              tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
       } else if (full) {
 #pragma unroll
-        for (int qb = 0; qb < QT; ++qb)
-          attend_block<KS, NCB, TB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0,
-                                              quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
+        for (int qb = 0; qb < QT; ++qb) {
+          const int dist0 = tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col);
+          if (ALIBI && optimistic)
+            attend_block<KS, NCB, TB, false, ALIBI, bf16x8, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb],
+                                                                   a.scale_log2, tok0, 0, quad, slope, dist0);
+          else
+            attend_block<KS, NCB, TB, false, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, 0,
+                                                    quad, slope, dist0);
+        }
       } else {
         if (tok0 + kStep > limit) clear_tail<NCB, TB>(vf, tok0, limit, quad);
 #pragma unroll
         for (int qb = 0; qb < QT; ++qb) {
           const int vis = min(pos0 + q0 + qb * 16 + col + 1, limit);
-          attend_block<KS, NCB, TB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis,
-                                             quad, slope, tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col));
+          const int dist0 = tok0 + quad * 4 - (pos0 + q0 + qb * 16 + col);
+          if (ALIBI && optimistic)
+            attend_block<KS, NCB, TB, true, ALIBI, bf16x8, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb],
+                                                                  a.scale_log2, tok0, vis, quad, slope, dist0);
+          else
+            attend_block<KS, NCB, TB, true, ALIBI>(kf, vf, qf[qb], ones, acc[qb], lacc[qb], m[qb], a.scale_log2, tok0, vis,
+                                                   quad, slope, dist0);
+        }
+      }
+      if (ALIBI && optimistic && t + 1 == t_end) {
+        bool tiny = false;
+#pragma unroll
+        for (int qb = 0; qb < QT; ++qb)
+          tiny |= q0 + qb * 16 + col < a.n_q && min(pos0 + q0 + qb * 16 + col + 1, len) > 0 &&
+                  !(lacc[qb][0] > __builtin_exp2f(-kTiny));
+        if (__any(tiny)) {                                           // wave-uniform
+          lost_walk = true;
+          break;
         }
       }
       if (optimistic && ((t & 7) == 7 || t + 1 == t_end)) {

@@ -77,3 +77,56 @@ def test_prefill_alibi(dtype, H, Hkv, r_k, r_v, lens, n, P):
     ref = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), d_h, alibi_slopes=slopes)
     err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16 if dtype == ea.EA_BF16 else TOL_F32, "alibi prefill")
     print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("H,Hkv,r_k,r_v,lens,n,P,slope_kind", [
+    (4, 2, 64, 64, [2100, 1500], 1400, 64, "mpt"),        # many unmasked tiles under every query block: the lean tiles
+    (8, 8, 80, 48, [3000], 3000, 128, "mpt"),             # a whole prompt, padded ranks
+    (2, 2, 64, 64, [2500], 900, 64, "steep"),             # slopes of 1 and 4 per token: only the nearest keys count
+    (2, 1, 128, 128, [1800], 1000, 64, "flat"),           # slopes 0 and 1e-4: nearly the plain call
+])
+def test_prefill_alibi_long_rows(H, Hkv, r_k, r_v, lens, n, P, slope_kind):
+    """Rows long enough that most tiles lie wholly below the diagonal (they run without a maximum search, against a
+    reference that bounds the scores without the bias)."""
+    print(f"alibi prefill, long rows H={H}/{Hkv} r=({r_k},{r_v}) lens={lens} n={n} slopes={slope_kind}", flush=True)
+    desc = ea.LayerDesc(H * 128, H, Hkv, 128, r_k, r_v, ea.EA_BF16, P)
+    g = synth.rng(33, H, r_k, n)
+    K, V = random_cache(desc, lens, g, k_std=1.5)
+    q = quantize(desc, synth.gaussian(g, (len(lens), n, H, r_k), 1.5))
+    slopes = {"mpt": mpt_slopes(H), "steep": np.array([1.0, 4.0] * (H // 2)),
+              "flat": np.array([0.0, 1e-4] * (H // 2))}[slope_kind]
+    dc = DeviceCache(desc, K, V, g)
+    out = torch.full((len(lens), n, H, r_v), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ea.prefill_attn_alibi(desc, to_dev(desc, q), torch.from_numpy(slopes.astype(np.float32)).cuda(), dc.k_pool,
+                          dc.v_pool, dc.page_table, dc.seq_len, out)
+    torch.cuda.synchronize()
+    ref = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), 128, alibi_slopes=np.float32(slopes).astype(np.float64))
+    err = assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "alibi prefill, long rows")
+    print(f"  rel-L2 {err:.2e}", flush=True)
+
+
+def test_prefill_alibi_scores_far_above_what_the_bias_leaves():
+    """Early keys whose scores WITHOUT the bias are about 2^150 times above everything a steep slope lets the queries
+    see: against a reference that bounds those scores every visible term underflows, the row sums end near zero, and
+    the wave must repeat its walk with the exact (biased) maximum."""
+    H, r, P, L, n = 2, 64, 64, 1536, 512
+    desc = ea.LayerDesc(H * 128, H, H, 128, r, r, ea.EA_BF16, P)
+    g = synth.rng(34)
+    K, V = random_cache(desc, [L], g, k_std=0.5)
+    u = synth.gaussian(g, (r,))
+    u /= np.linalg.norm(u)
+    # every query has the component 2 u; keys 100..107 are c u with 2 c / sqrt(d_h) = 150 ln 2
+    q = quantize(desc, 0.1 * synth.gaussian(g, (1, n, H, r)) + 2.0 * u)
+    c = 150 * np.log(2) * np.sqrt(128) / 2
+    for h in range(H):
+        K[0][h, 100:108] = quantize(desc, c * u)
+    raw = np.einsum("nhc,hc->nh", q[0], K[0][:, 100]) / np.sqrt(128) / np.log(2)
+    assert raw.min() > 120 and raw.max() < 180                      # log2 units, before the bias
+    slopes = np.array([2.0, 0.5])
+    dc = DeviceCache(desc, K, V, g)
+    out = torch.full((1, n, H, r), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ea.prefill_attn_alibi(desc, to_dev(desc, q), torch.from_numpy(slopes.astype(np.float32)).cuda(), dc.k_pool,
+                          dc.v_pool, dc.page_table, dc.seq_len, out)
+    torch.cuda.synchronize()
+    ref = ora.prefill_attention(q, ora.RankCache.from_arrays(K, V), 128, alibi_slopes=slopes)
+    assert_close(out.float().cpu().numpy(), ref, TOL_BF16, "alibi prefill, underflow against the unbiased reference")
