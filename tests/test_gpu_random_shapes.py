@@ -91,6 +91,15 @@ def test_q4_prefill_alibi_and_rotary_random_shapes(seed):
         ea.prefill_attn(desc, to_dev(desc, qp), dc.k_pool, dc.v_pool, dc.page_table, dc.seq_len, out)
         torch.cuda.synchronize()
         assert_close(out.float().cpu().numpy(), ora.prefill_attention(qp, cache, 128), TOL_BF16, "prefill")
+        # ---- the same prefill with the ALiBi bias: the MPT slopes, steep ones (1 or 3 per token) or none, per case
+        slopes = [2.0 ** (-8.0 * (np.arange(H) + 1) / H), np.where(np.arange(H) % 2 == 0, 1.0, 3.0),
+                  np.zeros(H)][case % 3].astype(np.float32).astype(np.float64)
+        out.fill_(float("nan"))
+        ea.prefill_attn_alibi(desc, to_dev(desc, qp), torch.from_numpy(slopes.astype(np.float32)).cuda(), dc.k_pool,
+                              dc.v_pool, dc.page_table, dc.seq_len, out)
+        torch.cuda.synchronize()
+        assert_close(out.float().cpu().numpy(), ora.prefill_attention(qp, cache, 128, alibi_slopes=slopes), TOL_BF16,
+                     "alibi prefill")
         # ---- ALiBi decode
         slopes = 2.0 ** (-8.0 * (np.arange(H) + 1) / H)
         qa = np.float32(synth.gaussian(g, (B, H, r_k))).astype(np.float64)
