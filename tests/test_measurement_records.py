@@ -34,3 +34,20 @@ def test_traffic_summaries_are_plausible_and_stamped():
             assert os.path.exists(os.path.join(ROOT, "paper_2408_05646_amd", "csrc", name)) or \
                 os.path.exists(os.path.join(ROOT, "include", name)), (path, name)
         assert "rocprofv3 --pmc FETCH_SIZE" in text and "rocprofv3 --pmc WRITE_SIZE" in text, path
+
+
+def test_every_profile_summary_names_its_command_and_its_kernel_sources():
+    """Every summary under profiles/ is text, gives the rocprofv3 command that made it (which runs committed files
+    only), names the kernel sources it was measured on -- files that exist -- and carries their hash."""
+    files = sorted(glob.glob(os.path.join(ROOT, "profiles", "*")))
+    assert len(files) >= 20
+    for path in files:
+        assert path.endswith((".txt", ".md")), path
+        text = open(path).read()
+        assert len(text) < 40000, path                                  # a summary, not raw profiler output
+        assert "rocprofv3" in text and "bench.py" in text and "_work" not in text, path
+        srcs = _field(text, "kernel_sources").split()
+        assert srcs and re.fullmatch(r"[0-9a-f]{16}", _field(text, "kernel_sources_sha16")), path
+        for name in srcs:
+            assert os.path.exists(os.path.join(ROOT, "paper_2408_05646_amd", "csrc", name)) or \
+                os.path.exists(os.path.join(ROOT, "include", name)), (path, name)
